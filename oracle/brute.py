@@ -1,0 +1,96 @@
+"""Brute-force definitions the oracle is pinned against (numpy / pure Python).
+
+TEST INFRASTRUCTURE ONLY.  Nothing here calls the C++ oracle or the HIP path;
+each function restates a definition so a mistake in the oracle's queue logic
+shows up as a disagreement.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def delivered_currents(spikes: np.ndarray, row_ptr, col, amp, D) -> np.ndarray:
+    """I_j(n) = sum_i a_ij * s_i(n - D_ij)  (delivery at t_post = t_pre + d,
+    Section 3.2 eqs. 10-11; weighted events add linearly, Section 4.3 "Ring").
+
+    spikes [T, N] (0/1), amp [S] float64, D [S] int  ->  I [T, N] float64.
+    """
+    T, N = spikes.shape
+    I = np.zeros((T, N), np.float64)
+    src = np.repeat(np.arange(N), np.diff(row_ptr))
+    s = spikes.astype(np.float64)
+    for p in range(len(col)):
+        d = int(D[p])
+        if d < T:
+            I[d:, col[p]] += amp[p] * s[:T - d, src[p]]
+    return I
+
+
+def replay_bounded(spikes: np.ndarray, row_ptr, col, D, capacity: int):
+    """Replay of the bounded-bag rule on a given raster [T, N].
+
+    At each step: events due now leave their target's bag; then the spikes of
+    the step are taken in ascending source order, each row in storage order,
+    and an event is admitted iff its target currently holds fewer than
+    `capacity` undelivered events (an incoming event is dropped when the queue
+    is full, Section 4.3 "FIFORing").  Returns (admitted, dropped) as lists of
+    (syn, n_emit, k) tuples in canonical order.
+    """
+    T, N = spikes.shape
+    occ = [0] * N
+    due = {}           # arrival step -> list of targets
+    admitted, dropped = [], []
+    for n in range(T):
+        for j in due.pop(n, []):
+            occ[j] -= 1
+        for i in np.nonzero(spikes[n])[0]:
+            for p in range(int(row_ptr[i]), int(row_ptr[i + 1])):
+                j = int(col[p])
+                k = n + int(D[p])
+                if occ[j] >= capacity:
+                    dropped.append((p, n, k))
+                else:
+                    occ[j] += 1
+                    admitted.append((p, n, k))
+                    due.setdefault(k, []).append(j)
+    return admitted, dropped
+
+
+def hold_one_spike(spikes: np.ndarray, row_ptr, col, D):
+    """A queue that stores one spike time and refuses newcomers while occupied
+    (Section 4.3 "SingleSpike(Hold)", stated there to behave like a FIFO of
+    capacity one).  One such queue per target.  Returns the set of delivered
+    (syn, n_emit, k)."""
+    T, N = spikes.shape
+    EMPTY = None
+    held = [EMPTY] * N
+    out = set()
+    for n in range(T):
+        for j in range(N):
+            if held[j] is not EMPTY and held[j][2] <= n:
+                out.add(held[j])
+                held[j] = EMPTY
+        for i in np.nonzero(spikes[n])[0]:
+            for p in range(int(row_ptr[i]), int(row_ptr[i + 1])):
+                j = int(col[p])
+                if held[j] is EMPTY:
+                    held[j] = (p, n, n + int(D[p]))
+    return out
+
+
+def currents_from_events(events, col, amp, T: int, N: int) -> np.ndarray:
+    """Sum the amplitudes of a list of (syn, n_emit, k) at their arrival step."""
+    I = np.zeros((T, N), np.float64)
+    for p, _, k in events:
+        if k < T:
+            I[k, col[p]] += amp[p]
+    return I
+
+
+def erlang_b(c: int, a: float) -> float:
+    """Blocking probability of an M/G/c/c loss system with offered load a
+    (recurrence B(0)=1, B(k) = a B(k-1) / (k + a B(k-1)))."""
+    b = 1.0
+    for k in range(1, c + 1):
+        b = a * b / (k + a * b)
+    return b
