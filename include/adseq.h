@@ -1,0 +1,190 @@
+/* adseq.h -- C ABI of the MI355X (gfx950) delayed spike-event delivery library.
+ *
+ * The library runs, per time step, the hot path of autodifferentiable
+ * spike-event queues: pop the events due now, add the external drive, update
+ * the LIF state, compact the neurons that spiked, fan each spike out over its
+ * CSR row and enqueue the events at (step + delay); and, afterwards, the
+ * reverse-time sweep that yields weight and delay gradients.
+ *
+ * Conventions for every entry point
+ *   - returns ADSEQ_OK (0) or a negative ADSEQ_E_* code; never throws or aborts;
+ *     on error the outputs are left untouched and the handle stays usable;
+ *   - every array argument is a DEVICE pointer owned by the caller unless the
+ *     comment says "host"; the library never allocates device memory and never
+ *     creates streams: all state lives in the caller's workspace and all work
+ *     is launched on the `stream` argument (a hipStream_t passed as void*,
+ *     NULL = the default stream) without synchronising, except where stated;
+ *   - one handle = one network x `batch` independent trials; a handle is not
+ *     thread safe; neuron (b, i) has flat index b * n_neurons + i;
+ *   - steps are numbered 0, 1, 2, ... and must be issued in that order.
+ *
+ * Semantics of one step n (Section 3.2 eqs. 10-11: an event emitted at t_pre with
+ * delay d is delivered at t_post = t_pre + d; Section 4.1 listing "Synapse
+ * implementation": detect, enqueue, pop, integrate):
+ *   1. pop     Iq_j = sum of the amplitudes of the stored events with arrival
+ *              step n and target j (summed as 32-bit fixed point Q8.24, so the
+ *              result does not depend on the order of arrival);
+ *   2. drive   I_j = Iq_j * 2^-24 + (xi_j ? ext_weight : 0) (+ i_ext_j), xi_j a
+ *              Bernoulli(ext_rate_hz * dt) draw from a counter-based hash of
+ *              (seed, b * N + j, n);
+ *   3. LIF     U_j = fma(alpha, V_j, I_j), alpha = (float)exp(-dt/tau_m);
+ *              s_j = U_j >= v_thresh (Heaviside, eq. 6); V_j = s_j ? v_reset : U_j;
+ *   4. enqueue for every spiking i and every synapse p of row i: an event with
+ *              target col[p], arrival n + D_p and amplitude a_p.
+ *   Integer delays: D_p = delay_steps[p], a_p = weight[p].  Continuous delays:
+ *   D_p = max(1, ceil(delay_ms[p] / dt)), a_p = weight[p] * exp(-(D_p dt - delay_ms[p]) / tau_m).
+ *
+ * Queue kinds (Section 4.3)
+ *   ADSEQ_RING    dense delay line [d_max_steps + 1][batch * n_neurons]; events
+ *                 are summed into slot (n + D) mod depth; lossless ("Ring").
+ *   ADSEQ_FIFO    per target, `capacity` unordered slots; an incoming event is
+ *                 dropped (and counted) when the target already holds `capacity`
+ *                 undelivered events ("FIFORing": drops the incoming spikes when
+ *                 the queue is full); every stored event is delivered exactly at
+ *                 its arrival step.
+ *   ADSEQ_SORTED  per target, `capacity` slots kept ordered by arrival step; pop
+ *                 takes from the front ("SortedArray"); same admission rule.
+ *   Admission order within a step is canonical: ascending global synapse index
+ *   (= ascending source neuron, then position in the row), independently per trial.
+ */
+#ifndef ADSEQ_H
+#define ADSEQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct adseq adseq_t; /* opaque; host memory owned by the library, freed by adseq_destroy */
+
+enum { ADSEQ_RING = 0, ADSEQ_FIFO = 1, ADSEQ_SORTED = 2 };
+enum { ADSEQ_SURR_SUPERSPIKE = 0, ADSEQ_SURR_OFF = 1 };
+
+enum {
+  ADSEQ_OK = 0,
+  ADSEQ_E_INVALID_ARG = -1, /* null pointer, non-positive size, unknown enum, dt > tau_m ...    */
+  ADSEQ_E_DELAY_RANGE = -2, /* a delay below one step (or <= 0 ms) or above d_max_steps         */
+  ADSEQ_E_WORKSPACE = -3,   /* workspace missing, misaligned (256 B) or smaller than required   */
+  ADSEQ_E_ORDER = -4,       /* step issued out of order                                         */
+  ADSEQ_E_NO_TAPE = -5,     /* backward without a complete recorded forward run                 */
+  ADSEQ_E_HIP = -6,         /* a HIP call failed; adseq_last_error has the text                 */
+  ADSEQ_E_CAPACITY = -7,    /* tape (steps, spikes, events) or per-step contender pool overflow */
+  ADSEQ_E_GRAPH = -8        /* CSR malformed: row_ptr not monotone from 0 to n_synapses, or a
+                               column index outside [0, n_neurons)                             */
+};
+
+typedef struct {
+  int32_t n_neurons;    /* N >= 1                                                             */
+  int32_t batch;        /* B >= 1 independent trials sharing the network                      */
+  int32_t d_max_steps;  /* largest arrival offset in steps, 1..1023                           */
+  int32_t capacity;     /* slots per target for FIFO / SORTED (1..32767); ignored for RING    */
+  int32_t kind;         /* ADSEQ_RING / ADSEQ_FIFO / ADSEQ_SORTED                             */
+  int32_t surrogate;    /* ADSEQ_SURR_SUPERSPIKE: 1/(|U-theta|+1)^2 (eq. 7); ADSEQ_SURR_OFF: 0 */
+  int32_t record_tape;  /* 1 = adseq_step keeps what adseq_backward needs                     */
+  int32_t max_steps;    /* tape length in steps (needed when record_tape = 1)                 */
+  float dt_ms, tau_m_ms, v_thresh, v_reset; /* LIF; requires 0 < dt_ms <= tau_m_ms            */
+  float ext_rate_hz, ext_weight;            /* Poisson drive, 0 rate = none                   */
+  uint64_t seed;                            /* of the drive's counter-based generator         */
+  int64_t n_synapses;                       /* S = row_ptr[N]                                 */
+  const int64_t *row_ptr;     /* [N+1] CSR by source neuron                                   */
+  const int32_t *col;         /* [S] target neuron                                            */
+  const float *weight;        /* [S] finite fp32; |amplitude| saturates at 128                */
+  const uint8_t *delay_steps; /* [S] integer delays in steps, or NULL                         */
+  const float *delay_ms;      /* [S] continuous delays in ms, or NULL (exactly one is given)  */
+  /* The four arrays above must stay valid and unchanged for the life of the handle. */
+  int64_t tape_spike_capacity; /* spikes the tape can hold in total; 0 = default
+                                  (max_steps * B * N / 16 + B * N)                            */
+  int64_t tape_event_capacity; /* FIFO/SORTED with tape: emitted events it can hold (one
+                                  admission flag each); 0 = default
+                                  (tape_spike_capacity * ceil(S / N))                         */
+  int64_t step_event_capacity; /* FIFO/SORTED: events per step that may contend for free
+                                  slots; 0 = default min(B * S, 2^24)                         */
+  void *workspace;             /* device memory, 256-byte aligned                             */
+  size_t workspace_bytes;      /* >= adseq_workspace_bytes(cfg)                               */
+  void *stream;                /* stream for the preparation kernels of adseq_create          */
+} adseq_config;
+
+/* Bytes of device workspace `cfg` needs (pointer fields are not read). 0 if cfg is invalid. */
+size_t adseq_workspace_bytes(const adseq_config *cfg);
+
+/* Builds a handle: validates cfg (host), then on cfg->stream converts the synapses into the
+ * packed internal form, validates delays and the CSR on the device, clears all state, and
+ * synchronises that stream once.  *out is written only on success. */
+int adseq_create(const adseq_config *cfg, adseq_t **out);
+
+/* Frees the host-side handle.  The workspace stays the caller's. */
+int adseq_destroy(adseq_t *h);
+
+/* Back to step 0: V = 0, queues empty, counters zero, tape empty.  Stream ordered. */
+int adseq_reset(adseq_t *h, void *stream);
+
+/* Open-loop delivery (the queue's pop, Section 4.2): writes the current delivered at `step`,
+ * I_out[b*N + j] = (float)Iq * 2^-24, fp32 [B*N], and removes those events.  `step` must be
+ * the next step not yet delivered.  LIF state and tape are not touched. */
+int adseq_deliver(adseq_t *h, int64_t step, float *I_out, void *stream);
+
+/* Open-loop enqueue (the queue's enqueue, Section 4.2): fans out the spikes listed in
+ * spike_ids[0 .. *n_spikes) (flat ids b*N + i, each id at most once per step; both DEVICE
+ * pointers) with emission step `step`, which must be the step last delivered.  May be called
+ * several times for one step; for the bounded kinds admission is then canonical within each
+ * call and calls are served in order. */
+int adseq_enqueue(adseq_t *h, int64_t step, const int32_t *spike_ids, const int32_t *n_spikes,
+                  void *stream);
+
+/* One closed-loop step (pop, drive, LIF, compaction, fan-out, enqueue; see the header comment).
+ * i_ext: optional extra input current fp32 [B*N] or NULL.  spikes_out: optional 0/1 bytes
+ * [B*N] or NULL. */
+int adseq_step(adseq_t *h, int64_t step, const float *i_ext, uint8_t *spikes_out, void *stream);
+
+/* n_steps closed-loop steps starting at `step0` (same as calling adseq_step in a loop with
+ * i_ext = spikes_out = NULL). */
+int adseq_run(adseq_t *h, int64_t step0, int64_t n_steps, void *stream);
+
+/* Reverse-time sweep over the T steps recorded since the last reset (Section 3.2: the event
+ * carries d t_post / d d = 1, eq. 13; on delivery the receiving state gets (jump / tau_m) times
+ * that, eq. 17; the spike function's derivative is the surrogate of eq. 7, applied only where a
+ * spike was emitted for the queue term).  With gU[T] = 0, for n = T-1 .. 0:
+ *   G_i   = sum over admitted events p of row i emitted at n with n + D_p < T of a_p * gU[col_p][n + D_p]
+ *   gU_i[n] = (1 - s_i[n]) * alpha * gU_i[n+1] + sigma'(U_i[n] - theta) * (dL_dcount_i + s_i[n] * G_i) + dL_dU_i[n]
+ *   grad_w[p] += f_p * gU[col_p][n + D_p],   grad_d[p] += (a_p / tau_m) * unit * gU[col_p][n + D_p]
+ * (f_p = a_p / weight_p; unit = 1 per ms for delay_ms, dt per step for delay_steps), summed over
+ * trials.  dL_dcount: fp32 [B*N] or NULL; dL_dU: fp32 [T][B*N] or NULL; grad_w, grad_d: fp32 [S],
+ * overwritten.  Synchronises the stream once at the start to read the device error word. */
+int adseq_backward(adseq_t *h, const float *dL_dcount, const float *dL_dU, float *grad_w,
+                   float *grad_d, void *stream);
+
+/* Event counters since the last reset (host pointers, any may be NULL): events refused by a
+ * full queue, events offered to the queues, events delivered.  Synchronises `stream`.
+ * Returns ADSEQ_E_CAPACITY if a tape or pool overflow happened since the last reset. */
+int adseq_drop_count(adseq_t *h, uint64_t *dropped, uint64_t *enqueued, uint64_t *delivered,
+                     void *stream);
+
+/* Further counters (host pointer to 8 int64): [0] offered, [1] dropped, [2] delivered events;
+ * [3..5] the same as sums of Q8.24 amplitudes; [6] spikes recorded on the tape; [7] device error
+ * bits.  Synchronises `stream`. */
+int adseq_counters(adseq_t *h, int64_t *out8, void *stream);
+
+/* Where the tape lives inside the workspace (device pointers; valid for the handle's life).
+ * membrane: fp32 [max_steps][B*N] pre-reset membrane values U; step_offset: int64 [max_steps+1]
+ * spikes of step n are spike_id[step_offset[n] .. step_offset[n+1]) (flat ids, unordered within
+ * a step); event_base: int64 per recorded spike, index of its row's first admission flag;
+ * admitted: one byte per emitted event (bounded kinds only, else NULL). */
+typedef struct {
+  const float *membrane;
+  const int64_t *step_offset;
+  const int32_t *spike_id;
+  const int64_t *event_base;
+  const uint8_t *admitted;
+  int64_t steps_recorded;
+} adseq_tape_view;
+int adseq_tape(const adseq_t *h, adseq_tape_view *out);
+
+/* Text of the last error on this handle (host string owned by the handle). */
+const char *adseq_last_error(const adseq_t *h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADSEQ_H */

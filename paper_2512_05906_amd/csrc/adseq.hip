@@ -1,0 +1,957 @@
+// MI355X (gfx950) kernels and C ABI for delayed spike-event delivery through
+// autodifferentiable queues.  See include/adseq.h for the contract of every
+// entry point; this file holds the device code and the host-side bookkeeping.
+//
+// Layout of the state in the caller's workspace (all arrays 256-byte aligned):
+//   V            fp32  [BN]                 membrane state
+//   ring         i32   [R][BN]              RING: Q8.24 sums per arrival slot, R = d_max + 1
+//   cnt_ring     u32   [R][kFanoutBlocks]   RING: events per arrival slot, one private column per
+//                                           fan-out block (no atomics; summed at pop)
+//   slot_k/a     u32/i32 [C][BN]            FIFO/SORTED: arrival step and Q8.24 amplitude, slot-major
+//                                           so that one slot of 64 consecutive targets is one line
+//   occ, head    i32   [BN]                 FIFO/SORTED: stored events; SORTED: index of the front
+//   c_head, pool_*                          per-step contender lists (one linked list per target)
+//   packed, a_q  u32/i32 [S]                synapses: (col << dbits | D) and Q8.24 amplitude
+//   amp, fdec    fp32  [S]                  continuous delays only: a = w f and f
+//   tape_*                                  membrane tape, spike list, admission flags
+//   bwd_*                                   adjoint delay line [R][BN], carry, queue term
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "adseq.h"
+
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kFanoutBlocks = 1024;
+constexpr int kAdmitBlocks = 1024;
+
+enum : unsigned {
+  ERR_DELAY = 1u, ERR_GRAPH = 2u, ERR_TAPE_SPIKES = 4u, ERR_TAPE_EVENTS = 8u, ERR_POOL = 16u
+};
+
+struct Counters {
+  unsigned long long offered, dropped, delivered;
+  long long sum_offered, sum_dropped, sum_delivered;
+  long long tape_spikes, tape_events;
+  unsigned err;
+  int n_spk[2];
+  int pool_n[2];
+};
+
+struct ExpCoef { double c[21]; };
+
+struct Dev {
+  int N, B, BN, R, C, kind, dbits, d_max;
+  unsigned dmask;
+  int continuous, record, surrogate, max_steps, pool_cap;
+  float alpha, theta, v_reset, ext_w, dt, tau;
+  unsigned long long p_thresh, seed;
+  long long S, spike_cap, event_cap;
+  const long long* row_ptr;
+  const int* col;
+  const float* weight;
+  const unsigned char* delay_steps;
+  const float* delay_ms;
+  unsigned* packed;
+  int* a_q;
+  float* amp;
+  float* fdec;
+  float* V;
+  int* ring;
+  unsigned* cnt_ring;
+  unsigned* slot_k;
+  int* slot_a;
+  int* occ;
+  int* head;
+  int* c_head;
+  long long* pool_p;
+  long long* pool_t;
+  int* pool_g;
+  int* pool_next;
+  unsigned* pool_k;
+  int* pool_a;
+  int* cur_spk;
+  float* tapeU;
+  long long* step_off;
+  int* tape_spk;
+  long long* tape_evb;
+  unsigned char* tape_adm;
+  float* bwd_ring;
+  float* bwd_carry;
+  float* bwd_G;
+  Counters* ctr;
+};
+
+// ---------------------------------------------------------------- device helpers
+
+// splitmix64 output function (Steele, Lea, Flood 2014)
+__device__ __forceinline__ unsigned long long mix64(unsigned long long z) {
+  z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ull;
+  z ^= z >> 27; z *= 0x94D049BB133111EBull;
+  z ^= z >> 31; return z;
+}
+// 32 uniform bits for (seed, unit g, step n): the drive's counter-based generator
+__device__ __forceinline__ unsigned drive_bits(unsigned long long seed, unsigned long long g,
+                                               unsigned long long n) {
+  const unsigned long long G = 0x9E3779B97F4A7C15ull;
+  unsigned long long z = mix64(seed + G * (g + 1));
+  z = mix64(z + G * (n + 1));
+  return (unsigned)(z >> 32);
+}
+
+__device__ __forceinline__ int wrap_add(int a, int b) { return (int)((unsigned)a + (unsigned)b); }
+
+__device__ __forceinline__ long long wave_sum(long long v) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_sum_f(float v) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+  return v;
+}
+
+// Adds the block's totals of two per-thread values to two global 64-bit counters
+// (one atomic each per block).  Every thread of the block must call it.
+__device__ __forceinline__ void block_add2(unsigned long long* c0, long long v0, long long* c1,
+                                           long long v1) {
+  __shared__ long long red[2][kBlock / 64];
+  v0 = wave_sum(v0); v1 = wave_sum(v1);
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  if (lane == 0) { red[0][w] = v0; red[1][w] = v1; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    long long a = 0, b = 0;
+    for (int i = 0; i < kBlock / 64; ++i) { a += red[0][i]; b += red[1][i]; }
+    if (a) atomicAdd(c0, (unsigned long long)a);
+    if (b) atomicAdd((unsigned long long*)c1, (unsigned long long)b);
+  }
+  __syncthreads();
+}
+
+__global__ void k_fill_u32(unsigned* p, unsigned v, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+       i += (size_t)gridDim.x * blockDim.x)
+    p[i] = v;
+}
+
+// ---------------------------------------------------------------- preparation
+
+// Synapse p -> arrival offset D_p, Q8.24 amplitude, packed (col, D); validates delays and columns.
+// Continuous delays: D = max(1, ceil(d/dt)), a = w exp(-(D dt - d)/tau); exp as the degree-20
+// Taylor polynomial (Horner, fused multiply-add) so that the value is reproducible bit for bit.
+__global__ __launch_bounds__(kBlock) void k_prepare(Dev d, ExpCoef ec) {
+  const double dt = (double)d.dt, tau = (double)d.tau;
+  for (long long p = (long long)blockIdx.x * kBlock + threadIdx.x; p < d.S;
+       p += (long long)gridDim.x * kBlock) {
+    unsigned err = 0;
+    const double w = (double)d.weight[p];
+    double f = 1.0;
+    long long D;
+    if (!d.continuous) {
+      D = d.delay_steps[p];
+      if (D < 1) { err |= ERR_DELAY; D = 1; }
+    } else {
+      const double dl = (double)d.delay_ms[p];
+      if (!(dl > 0.0)) err |= ERR_DELAY;
+      const double q = ceil(dl / dt);
+      D = (q >= 1.0 && q < 1e9) ? (long long)q : 1;
+      const double x = ((double)D * dt - dl) / tau;
+      if (!(x >= 0.0 && x <= 1.0)) err |= ERR_DELAY;
+      const double y = -x;
+      double r = ec.c[20];
+      for (int k = 19; k >= 0; --k) r = __fma_rn(r, y, ec.c[k]);
+      f = r;
+    }
+    if (D > d.d_max) { err |= ERR_DELAY; D = d.d_max; }
+    const int c = d.col[p];
+    if (c < 0 || c >= d.N) err |= ERR_GRAPH;
+    const double a = w * f;
+    long long q = __double2ll_rn(a * 16777216.0);
+    q = q > 2147483647LL ? 2147483647LL : (q < -2147483648LL ? -2147483648LL : q);
+    d.a_q[p] = (int)q;
+    d.packed[p] = ((unsigned)c << d.dbits) | (unsigned)D;
+    if (d.continuous) { d.amp[p] = (float)a; d.fdec[p] = (float)f; }
+    if (err) atomicOr(&d.ctr->err, err);
+  }
+  // row_ptr: starts at 0, ends at S, never decreases, rows shorter than 2^31
+  for (long long i = (long long)blockIdx.x * kBlock + threadIdx.x; i < d.N;
+       i += (long long)gridDim.x * kBlock) {
+    const long long a = d.row_ptr[i], b = d.row_ptr[i + 1];
+    bool bad = a > b || a < 0 || b > d.S || b - a > 0x7fffffffLL;
+    if (i == 0 && a != 0) bad = true;
+    if (i == d.N - 1 && b != d.S) bad = true;
+    if (bad) atomicOr(&d.ctr->err, ERR_GRAPH);
+  }
+}
+
+// ---------------------------------------------------------------- pop + drive + LIF + compaction
+
+// One thread per (trial, neuron).  KIND selects how the due events are popped.
+// LIF = true: closed-loop step (drive, membrane update, spike compaction, tape);
+// LIF = false: open-loop delivery, writes the popped current to I_out.
+template <int KIND, bool LIF>
+__global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int parity,
+                                                    const float* __restrict__ i_ext,
+                                                    unsigned char* __restrict__ spikes_out,
+                                                    float* __restrict__ I_out) {
+  const int g = blockIdx.x * kBlock + threadIdx.x;
+  const bool act = g < d.BN;
+  int acc = 0;
+  long long popped = 0;
+  const unsigned kn = (unsigned)n;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    d.ctr->n_spk[parity ^ 1] = 0;  // next step's spike counter; nobody reads it now
+  }
+  if (act) {
+    if (KIND == ADSEQ_RING) {
+      const size_t idx = (size_t)(n % d.R) * d.BN + g;
+      acc = d.ring[idx];
+      if (acc != 0) d.ring[idx] = 0;
+    } else if (KIND == ADSEQ_FIFO) {
+      // bounded bag: every stored event due now leaves; survivors are packed to the front
+      const int occ = d.occ[g];
+      int keep = 0;
+      for (int s = 0; s < occ; ++s) {
+        const size_t si = (size_t)s * d.BN + g;
+        const unsigned k = d.slot_k[si];
+        if (k == kn) {
+          acc = wrap_add(acc, d.slot_a[si]);
+          ++popped;
+        } else {
+          if (keep != s) {
+            const size_t di = (size_t)keep * d.BN + g;
+            d.slot_k[di] = k;
+            d.slot_a[di] = d.slot_a[si];
+          }
+          ++keep;
+        }
+      }
+      if (keep != occ) d.occ[g] = keep;
+    } else {
+      // ordered by arrival: everything due now sits at the front of the circular array
+      int occ = d.occ[g];
+      if (occ > 0) {
+        int hd = d.head[g];
+        while (occ > 0 && d.slot_k[(size_t)hd * d.BN + g] == kn) {
+          acc = wrap_add(acc, d.slot_a[(size_t)hd * d.BN + g]);
+          hd = hd + 1 == d.C ? 0 : hd + 1;
+          --occ;
+          ++popped;
+        }
+        if (popped) { d.occ[g] = occ; d.head[g] = hd; }
+      }
+    }
+  }
+  if (KIND == ADSEQ_RING && blockIdx.x == 0) {
+    // event count of this arrival slot: sum the fan-out blocks' private columns
+    unsigned* row = d.cnt_ring + (size_t)(n % d.R) * kFanoutBlocks;
+    for (int x = threadIdx.x; x < kFanoutBlocks; x += kBlock) {
+      const unsigned c = row[x];
+      if (c) { popped += c; row[x] = 0; }
+    }
+  }
+  bool s = false;
+  if (act) {
+    float I = (float)acc * 0x1p-24f;
+    if (LIF) {
+      if (d.p_thresh) {
+        const bool xi = (unsigned long long)drive_bits(d.seed, (unsigned long long)g,
+                                                       (unsigned long long)n) < d.p_thresh;
+        I = I + (xi ? d.ext_w : 0.0f);
+      }
+      if (i_ext) I = I + i_ext[g];
+      const float U = __fmaf_rn(d.alpha, d.V[g], I);
+      s = U >= d.theta;
+      d.V[g] = s ? d.v_reset : U;
+      if (d.record && n < d.max_steps) d.tapeU[(size_t)n * d.BN + g] = U;
+      if (spikes_out) spikes_out[g] = s ? 1 : 0;
+    } else {
+      I_out[g] = I;
+    }
+  }
+  if (LIF) {
+    // wavefront ballot + prefix popcount; one atomic per wavefront that has spikes
+    const unsigned long long m = __ballot(s);
+    const int lane = threadIdx.x & 63;
+    int base = 0;
+    if (lane == 0 && m) base = atomicAdd(&d.ctr->n_spk[parity], __popcll(m));
+    base = __shfl(base, 0, 64);
+    if (s) d.cur_spk[base + __popcll(m & ((1ull << lane) - 1ull))] = g;
+  }
+  block_add2(&d.ctr->delivered, popped, &d.ctr->sum_delivered, (long long)acc);
+}
+
+// ---------------------------------------------------------------- fan-out + enqueue
+
+// One block per spike (grid-stride over the spike list); the block walks the CSR row with
+// coalesced reads of (packed, a_q).  RING: integer atomic add into the arrival slot.
+// FIFO/SORTED: events whose target is already full are dropped here; the others become
+// contenders, pushed on their target's linked list for k_admit.
+template <int KIND>
+__global__ __launch_bounds__(kBlock) void k_fanout(Dev d, long long n, const int* __restrict__ spk,
+                                                   const int* __restrict__ n_spk_ptr, int parity,
+                                                   int record) {
+  __shared__ unsigned hist[1024];
+  __shared__ long long s_evb;
+  int nspk = *n_spk_ptr;
+  nspk = nspk < 0 ? 0 : (nspk > d.BN ? d.BN : nspk);
+  if (KIND == ADSEQ_RING) {
+    for (int x = threadIdx.x; x <= d.d_max; x += kBlock) hist[x] = 0;
+    __syncthreads();
+  }
+  if (KIND != ADSEQ_RING && blockIdx.x == 0 && threadIdx.x == 0) d.ctr->pool_n[parity ^ 1] = 0;
+  const long long off = record ? d.step_off[n] : 0;
+  const int m = (int)(n % d.R);
+  const int lane = threadIdx.x & 63;
+  long long c_off = 0, s_off = 0, c_drop = 0, s_drop = 0;
+  for (int e = blockIdx.x; e < nspk; e += gridDim.x) {
+    const int g = spk[e];
+    if ((unsigned)g >= (unsigned)d.BN) continue;  // uniform over the block
+    const int b = g / d.N, i = g - b * d.N;
+    const long long r0 = d.row_ptr[i], r1 = d.row_ptr[i + 1];
+    long long tbase = -1;
+    if (record) {
+      const bool fits = off + e < d.spike_cap;
+      if (threadIdx.x == 0) {
+        if (fits) d.tape_spk[off + e] = g; else atomicOr(&d.ctr->err, ERR_TAPE_SPIKES);
+      }
+      if (KIND != ADSEQ_RING) {
+        if (threadIdx.x == 0) {
+          long long evb = (long long)atomicAdd((unsigned long long*)&d.ctr->tape_events,
+                                               (unsigned long long)(r1 - r0));
+          if (evb + (r1 - r0) > d.event_cap) { atomicOr(&d.ctr->err, ERR_TAPE_EVENTS); evb = -1; }
+          if (fits) d.tape_evb[off + e] = evb;
+          s_evb = evb;
+        }
+        __syncthreads();
+        tbase = s_evb;
+        __syncthreads();
+      }
+    }
+    for (long long p0 = r0; p0 < r1; p0 += kBlock) {
+      const long long p = p0 + threadIdx.x;
+      const bool valid = p < r1;
+      unsigned pk = 0; int a = 0;
+      if (valid) { pk = d.packed[p]; a = d.a_q[p]; c_off += 1; s_off += a; }
+      const int D = (int)(pk & d.dmask);
+      const int col = (int)(pk >> d.dbits);
+      if (KIND == ADSEQ_RING) {
+        if (valid) {
+          int slot = m + D; if (slot >= d.R) slot -= d.R;
+          atomicAdd(&d.ring[(size_t)slot * d.BN + (size_t)b * d.N + col], a);
+          atomicAdd(&hist[D], 1u);
+        }
+      } else {
+        const int gt = b * d.N + col;
+        const long long tidx = (valid && tbase >= 0) ? tbase + (p - r0) : -1;
+        bool contend = false;
+        if (valid) {
+          contend = d.occ[gt] < d.C;
+          if (!contend) { c_drop += 1; s_drop += a; if (tidx >= 0) d.tape_adm[tidx] = 0; }
+        }
+        // wavefront-aggregated claim of pool entries
+        const unsigned long long cm = __ballot(contend);
+        if (cm) {
+          int base = 0;
+          if (lane == __ffsll((long long)cm) - 1) base = atomicAdd(&d.ctr->pool_n[parity], __popcll(cm));
+          base = __shfl(base, __ffsll((long long)cm) - 1, 64);
+          if (contend) {
+            const int x = base + __popcll(cm & ((1ull << lane) - 1ull));
+            if (x >= d.pool_cap) {
+              atomicOr(&d.ctr->err, ERR_POOL);
+              c_drop += 1; s_drop += a; if (tidx >= 0) d.tape_adm[tidx] = 0;
+            } else {
+              d.pool_p[x] = p; d.pool_t[x] = tidx; d.pool_g[x] = gt;
+              d.pool_k[x] = (unsigned)(n + D); d.pool_a[x] = a;
+              d.pool_next[x] = atomicExch(&d.c_head[gt], x);
+            }
+          }
+        }
+      }
+    }
+  }
+  if (KIND == ADSEQ_RING) {
+    __syncthreads();
+    for (int D = threadIdx.x; D <= d.d_max; D += kBlock) {
+      const unsigned c = hist[D];
+      if (c) {
+        int slot = m + D; if (slot >= d.R) slot -= d.R;
+        d.cnt_ring[(size_t)slot * kFanoutBlocks + blockIdx.x] += c;
+      }
+    }
+  }
+  if (record && blockIdx.x == 0 && threadIdx.x == 0) {
+    if (n + 1 <= d.max_steps) d.step_off[n + 1] = off + nspk;
+    d.ctr->tape_spikes = off + nspk;
+  }
+  block_add2(&d.ctr->offered, c_off, &d.ctr->sum_offered, s_off);
+  if (KIND != ADSEQ_RING) block_add2(&d.ctr->dropped, c_drop, &d.ctr->sum_dropped, s_drop);
+}
+
+// Admission for the bounded kinds.  One thread per contender; the thread whose entry is the head
+// of its target's list serves the whole list: the min(K, free) contenders with the smallest
+// synapse index are stored (canonical order), the rest are dropped.
+template <int KIND>
+__global__ __launch_bounds__(kBlock) void k_admit(Dev d, int parity) {
+  int np = d.ctr->pool_n[parity];
+  np = np > d.pool_cap ? d.pool_cap : np;
+  long long c_drop = 0, s_drop = 0;
+  for (int x0 = blockIdx.x * kBlock; x0 < np; x0 += gridDim.x * kBlock) {
+    const int x = x0 + threadIdx.x;
+    if (x >= np) continue;
+    const int gt = d.pool_g[x];
+    if (d.c_head[gt] != x) continue;
+    const int occ = d.occ[gt];
+    const int F = d.C - occ;
+    int K = 0;
+    for (int y = x; y >= 0; y = d.pool_next[y]) ++K;
+    const int take = K < F ? K : F;
+    int hd = KIND == ADSEQ_SORTED ? d.head[gt] : 0;
+    long long last = -1;
+    for (int r = 0; r < take; ++r) {
+      int best = -1; long long bp = 0x7fffffffffffffffLL;
+      for (int y = x; y >= 0; y = d.pool_next[y]) {
+        const long long pp = d.pool_p[y];
+        if (pp > last && pp < bp) { bp = pp; best = y; }
+      }
+      last = bp;
+      const unsigned k = d.pool_k[best];
+      const int a = d.pool_a[best];
+      if (KIND == ADSEQ_FIFO) {
+        const size_t si = (size_t)(occ + r) * d.BN + gt;
+        d.slot_k[si] = k; d.slot_a[si] = a;
+      } else {
+        // insertion from the back of the circular ordered array (stable for equal arrival steps)
+        int pos = occ + r;
+        while (pos > 0) {
+          int ph = hd + pos - 1; if (ph >= d.C) ph -= d.C;
+          const size_t si = (size_t)ph * d.BN + gt;
+          const unsigned kk = d.slot_k[si];
+          if (kk <= k) break;
+          int pd = ph + 1; if (pd >= d.C) pd -= d.C;
+          const size_t di = (size_t)pd * d.BN + gt;
+          d.slot_k[di] = kk; d.slot_a[di] = d.slot_a[si];
+          --pos;
+        }
+        int pw = hd + pos; if (pw >= d.C) pw -= d.C;
+        const size_t wi = (size_t)pw * d.BN + gt;
+        d.slot_k[wi] = k; d.slot_a[wi] = a;
+      }
+      const long long t = d.pool_t[best];
+      if (t >= 0) d.tape_adm[t] = 1;
+    }
+    if (take < K) {
+      for (int y = x; y >= 0; y = d.pool_next[y]) {
+        if (d.pool_p[y] > last) {
+          c_drop += 1; s_drop += d.pool_a[y];
+          const long long t = d.pool_t[y];
+          if (t >= 0) d.tape_adm[t] = 0;
+        }
+      }
+    }
+    d.occ[gt] = occ + take;
+    d.c_head[gt] = -1;
+  }
+  block_add2(&d.ctr->dropped, c_drop, &d.ctr->sum_dropped, s_drop);
+}
+
+// ---------------------------------------------------------------- backward
+
+// Queue term of the reverse sweep at step n: one block per recorded spike (b, i, n).  Gathers the
+// adjoint at each admitted event's arrival slot, reduces G_i, and accumulates the weight and
+// delay gradients of the row.
+template <bool BOUNDED, bool ATOMIC>
+__global__ __launch_bounds__(kBlock) void k_bwd_gather(Dev d, long long n, long long T, float dscale,
+                                                       float* __restrict__ grad_w,
+                                                       float* __restrict__ grad_d) {
+  __shared__ float red[kBlock / 64];
+  const long long off = d.step_off[n];
+  const int cnt = (int)(d.step_off[n + 1] - off);
+  const int m = (int)(n % d.R);
+  for (int e = blockIdx.x; e < cnt; e += gridDim.x) {
+    const int g = d.tape_spk[off + e];
+    const int b = g / d.N, i = g - b * d.N;
+    const long long r0 = d.row_ptr[i], r1 = d.row_ptr[i + 1];
+    const long long evb = BOUNDED ? d.tape_evb[off + e] : 0;
+    float G = 0.0f;
+    for (long long p = r0 + threadIdx.x; p < r1; p += kBlock) {
+      const unsigned pk = d.packed[p];
+      const int D = (int)(pk & d.dmask);
+      const int col = (int)(pk >> d.dbits);
+      if (n + D >= T) continue;                               // not delivered inside the run
+      if (BOUNDED && !d.tape_adm[evb + (p - r0)]) continue;   // refused by a full queue
+      int slot = m + D; if (slot >= d.R) slot -= d.R;
+      const float gv = d.bwd_ring[(size_t)slot * d.BN + (size_t)b * d.N + col];
+      const float a = d.continuous ? d.amp[p] : d.weight[p];
+      const float f = d.continuous ? d.fdec[p] : 1.0f;
+      G += a * gv;
+      const float gw = f * gv, gd = a * dscale * gv;
+      if (ATOMIC) { unsafeAtomicAdd(&grad_w[p], gw); unsafeAtomicAdd(&grad_d[p], gd); }
+      else { grad_w[p] += gw; grad_d[p] += gd; }
+    }
+    G = wave_sum_f(G);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = G;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      float t = 0.0f;
+      for (int w = 0; w < kBlock / 64; ++w) t += red[w];
+      d.bwd_G[g] = t;
+    }
+    __syncthreads();
+  }
+}
+
+// Neuron part of the reverse sweep at step n:
+//   gU[n] = (1 - s) alpha gU[n+1] + sigma'(U - theta) (dL/dcount + s G) + dL/dU[n]
+__global__ __launch_bounds__(kBlock) void k_bwd_neurons(Dev d, long long n,
+                                                        const float* __restrict__ dL_dcount,
+                                                        const float* __restrict__ dL_dU) {
+  const int g = blockIdx.x * kBlock + threadIdx.x;
+  if (g >= d.BN) return;
+  const float U = d.tapeU[(size_t)n * d.BN + g];
+  const bool s = U >= d.theta;
+  float sg = 0.0f;
+  if (d.surrogate == ADSEQ_SURR_SUPERSPIKE) {
+    const float x = fabsf(U - d.theta) + 1.0f;
+    sg = 1.0f / (x * x);
+  }
+  float inner = dL_dcount ? dL_dcount[g] : 0.0f;
+  if (s) inner += d.bwd_G[g];
+  float gu = sg * inner;
+  if (!s) gu = __fmaf_rn(d.alpha, d.bwd_carry[g], gu);
+  if (dL_dU) gu += dL_dU[(size_t)n * d.BN + g];
+  d.bwd_carry[g] = gu;
+  d.bwd_ring[(size_t)(n % d.R) * d.BN + g] = gu;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------- host side
+
+struct adseq {
+  adseq_config cfg;
+  Dev dev;
+  size_t ws_bytes;
+  long long next_step;   // next step to deliver
+  long long enq_calls;   // parity source for the pool / spike counters
+  bool tape_ok;          // every step since reset went through adseq_step with recording
+  char err[256];
+};
+
+namespace {
+
+struct Layout {
+  size_t V, ring, cnt_ring, slot_k, slot_a, occ, head, c_head, pool_p, pool_t, pool_g, pool_next,
+      pool_k, pool_a, cur_spk, packed, a_q, amp, fdec, tapeU, step_off, tape_spk, tape_evb, tape_adm,
+      bwd_ring, bwd_carry, bwd_G, ctr, total;
+  long long spike_cap, event_cap, pool_cap;
+  int R, dbits;
+};
+
+int bit_width(unsigned v) { int b = 0; while (v) { ++b; v >>= 1; } return b; }
+
+bool host_validate(const adseq_config* c) {
+  if (!c) return false;
+  if (c->n_neurons < 1 || c->batch < 1 || c->d_max_steps < 1 || c->d_max_steps > 1023) return false;
+  if ((long long)c->n_neurons * c->batch > 0x7fffffffLL) return false;
+  if (c->kind != ADSEQ_RING && c->kind != ADSEQ_FIFO && c->kind != ADSEQ_SORTED) return false;
+  if (c->kind != ADSEQ_RING && (c->capacity < 1 || c->capacity > 32767)) return false;
+  if (c->surrogate != ADSEQ_SURR_SUPERSPIKE && c->surrogate != ADSEQ_SURR_OFF) return false;
+  if (!(c->dt_ms > 0.0f) || !(c->tau_m_ms > 0.0f) || c->dt_ms > c->tau_m_ms) return false;
+  if (!(c->ext_rate_hz >= 0.0f)) return false;
+  if (c->n_synapses < 0) return false;
+  if (c->record_tape && c->max_steps < 1) return false;
+  if (c->tape_spike_capacity < 0 || c->tape_event_capacity < 0 || c->step_event_capacity < 0)
+    return false;
+  if (bit_width((unsigned)(c->n_neurons - 1)) + bit_width((unsigned)c->d_max_steps) > 32) return false;
+  return true;
+}
+
+bool make_layout(const adseq_config* c, Layout* L) {
+  if (!host_validate(c)) return false;
+  const size_t BN = (size_t)c->n_neurons * c->batch;
+  const size_t S = (size_t)c->n_synapses;
+  const bool bounded = c->kind != ADSEQ_RING;
+  const bool cont = c->delay_ms != nullptr;
+  L->R = c->d_max_steps + 1;
+  L->dbits = bit_width((unsigned)c->d_max_steps);
+  L->spike_cap = 0; L->event_cap = 0; L->pool_cap = 0;
+  if (c->record_tape) {
+    L->spike_cap = c->tape_spike_capacity ? c->tape_spike_capacity
+                                          : (long long)((size_t)c->max_steps * BN / 16 + BN);
+    if (bounded) {
+      const long long fan = (long long)((S + c->n_neurons - 1) / c->n_neurons);
+      L->event_cap = c->tape_event_capacity ? c->tape_event_capacity : L->spike_cap * (fan ? fan : 1);
+    }
+  }
+  if (bounded) {
+    long long cap = c->step_event_capacity;
+    if (!cap) {
+      const double bs = (double)c->batch * (double)S;
+      cap = bs < 16777216.0 ? (long long)bs : 16777216LL;
+      if (cap < 1) cap = 1;
+    }
+    if (cap > 0x7fffffffLL) cap = 0x7fffffffLL;
+    L->pool_cap = cap;
+  }
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o += (bytes + 255) & ~(size_t)255; return at; };
+  L->ctr = take(sizeof(Counters));
+  L->V = take(BN * 4);
+  L->ring = take(bounded ? 0 : (size_t)L->R * BN * 4);
+  L->cnt_ring = take(bounded ? 0 : (size_t)L->R * kFanoutBlocks * 4);
+  L->slot_k = take(bounded ? (size_t)c->capacity * BN * 4 : 0);
+  L->slot_a = take(bounded ? (size_t)c->capacity * BN * 4 : 0);
+  L->occ = take(bounded ? BN * 4 : 0);
+  L->head = take(bounded ? BN * 4 : 0);
+  L->c_head = take(bounded ? BN * 4 : 0);
+  L->pool_p = take((size_t)L->pool_cap * 8);
+  L->pool_t = take((size_t)L->pool_cap * 8);
+  L->pool_g = take((size_t)L->pool_cap * 4);
+  L->pool_next = take((size_t)L->pool_cap * 4);
+  L->pool_k = take((size_t)L->pool_cap * 4);
+  L->pool_a = take((size_t)L->pool_cap * 4);
+  L->cur_spk = take(BN * 4);
+  L->packed = take(S * 4);
+  L->a_q = take(S * 4);
+  L->amp = take(cont ? S * 4 : 0);
+  L->fdec = take(cont ? S * 4 : 0);
+  const size_t T = c->record_tape ? (size_t)c->max_steps : 0;
+  L->tapeU = take(T * BN * 4);
+  L->step_off = take(c->record_tape ? (T + 1) * 8 : 0);
+  L->tape_spk = take((size_t)L->spike_cap * 4);
+  L->tape_evb = take(bounded ? (size_t)L->spike_cap * 8 : 0);
+  L->tape_adm = take((size_t)L->event_cap);
+  L->bwd_ring = take(c->record_tape ? (size_t)L->R * BN * 4 : 0);
+  L->bwd_carry = take(c->record_tape ? BN * 4 : 0);
+  L->bwd_G = take(c->record_tape ? BN * 4 : 0);
+  L->total = o;
+  return true;
+}
+
+int fail(adseq* h, int code, const char* fmt, ...) {
+  if (h) {
+    va_list ap; va_start(ap, fmt);
+    vsnprintf(h->err, sizeof(h->err), fmt, ap);
+    va_end(ap);
+  }
+  return code;
+}
+
+#define HIP_TRY(h, call)                                                              \
+  do {                                                                                \
+    hipError_t e_ = (call);                                                           \
+    if (e_ != hipSuccess)                                                             \
+      return fail((h), ADSEQ_E_HIP, "%s failed: %s", #call, hipGetErrorString(e_));   \
+  } while (0)
+
+int grid_for(size_t n) {
+  size_t g = (n + kBlock - 1) / kBlock;
+  return (int)(g < 1 ? 1 : (g > 65535 * 16 ? 65535 * 16 : g));
+}
+
+void fill_u32(hipStream_t st, void* p, unsigned v, size_t count) {
+  if (!count) return;
+  size_t g = (count + kBlock - 1) / kBlock;
+  if (g > 4096) g = 4096;
+  hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)g), dim3(kBlock), 0, st, (unsigned*)p, v, count);
+}
+
+// Clears the dynamic state (not the prepared synapses).
+void launch_reset(adseq* h, hipStream_t st) {
+  const Dev& d = h->dev;
+  const size_t BN = (size_t)d.BN;
+  fill_u32(st, d.ctr, 0u, sizeof(Counters) / 4);
+  fill_u32(st, d.V, 0u, BN);
+  if (d.kind == ADSEQ_RING) {
+    fill_u32(st, d.ring, 0u, (size_t)d.R * BN);
+    fill_u32(st, d.cnt_ring, 0u, (size_t)d.R * kFanoutBlocks);
+  } else {
+    fill_u32(st, d.occ, 0u, BN);
+    fill_u32(st, d.head, 0u, BN);
+    fill_u32(st, d.c_head, 0xffffffffu, BN);
+  }
+  if (d.record) fill_u32(st, d.step_off, 0u, 2);  // step_off[0] = 0 (int64)
+  h->next_step = 0;
+  h->enq_calls = 0;
+  h->tape_ok = d.record != 0;
+}
+
+template <bool LIF>
+void launch_neurons(adseq* h, hipStream_t st, long long n, int parity, const float* i_ext,
+                    unsigned char* spikes_out, float* I_out) {
+  const Dev& d = h->dev;
+  const dim3 grid(grid_for((size_t)d.BN)), block(kBlock);
+  switch (d.kind) {
+    case ADSEQ_RING:
+      hipLaunchKernelGGL((k_neurons<ADSEQ_RING, LIF>), grid, block, 0, st, d, n, parity, i_ext, spikes_out, I_out);
+      break;
+    case ADSEQ_FIFO:
+      hipLaunchKernelGGL((k_neurons<ADSEQ_FIFO, LIF>), grid, block, 0, st, d, n, parity, i_ext, spikes_out, I_out);
+      break;
+    default:
+      hipLaunchKernelGGL((k_neurons<ADSEQ_SORTED, LIF>), grid, block, 0, st, d, n, parity, i_ext, spikes_out, I_out);
+      break;
+  }
+}
+
+void launch_fanout(adseq* h, hipStream_t st, long long n, const int* spk, const int* n_spk,
+                   int parity, int record) {
+  const Dev& d = h->dev;
+  const dim3 grid(kFanoutBlocks), block(kBlock);
+  switch (d.kind) {
+    case ADSEQ_RING:
+      hipLaunchKernelGGL((k_fanout<ADSEQ_RING>), grid, block, 0, st, d, n, spk, n_spk, parity, record);
+      break;
+    case ADSEQ_FIFO:
+      hipLaunchKernelGGL((k_fanout<ADSEQ_FIFO>), grid, block, 0, st, d, n, spk, n_spk, parity, record);
+      hipLaunchKernelGGL((k_admit<ADSEQ_FIFO>), dim3(kAdmitBlocks), block, 0, st, d, parity);
+      break;
+    default:
+      hipLaunchKernelGGL((k_fanout<ADSEQ_SORTED>), grid, block, 0, st, d, n, spk, n_spk, parity, record);
+      hipLaunchKernelGGL((k_admit<ADSEQ_SORTED>), dim3(kAdmitBlocks), block, 0, st, d, parity);
+      break;
+  }
+}
+
+int step_impl(adseq* h, long long step, const float* i_ext, unsigned char* spikes_out, hipStream_t st) {
+  if (step != h->next_step)
+    return fail(h, ADSEQ_E_ORDER, "adseq_step: got step %lld, expected %lld", step, h->next_step);
+  const Dev& d = h->dev;
+  const int parity = (int)(h->enq_calls & 1);
+  const int record = (d.record && h->tape_ok && step < d.max_steps) ? 1 : 0;
+  if (d.record && step >= d.max_steps) h->tape_ok = false;
+  launch_neurons<true>(h, st, step, parity, i_ext, spikes_out, nullptr);
+  launch_fanout(h, st, step, d.cur_spk, &d.ctr->n_spk[parity], parity, record);
+  h->enq_calls += 1;
+  h->next_step = step + 1;
+  HIP_TRY(h, hipGetLastError());
+  return ADSEQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t adseq_workspace_bytes(const adseq_config* cfg) {
+  Layout L;
+  if (!make_layout(cfg, &L)) return 0;
+  return L.total;
+}
+
+int adseq_create(const adseq_config* cfg, adseq_t** out) {
+  if (!cfg || !out) return ADSEQ_E_INVALID_ARG;
+  Layout L;
+  if (!make_layout(cfg, &L)) return ADSEQ_E_INVALID_ARG;
+  if (!cfg->row_ptr || !cfg->weight || (!cfg->col && cfg->n_synapses > 0)) return ADSEQ_E_INVALID_ARG;
+  if ((cfg->delay_steps == nullptr) == (cfg->delay_ms == nullptr)) return ADSEQ_E_INVALID_ARG;
+  if (!cfg->workspace || ((uintptr_t)cfg->workspace & 255) || cfg->workspace_bytes < L.total)
+    return ADSEQ_E_WORKSPACE;
+  adseq* h = new (std::nothrow) adseq();
+  if (!h) return ADSEQ_E_INVALID_ARG;
+  h->cfg = *cfg;
+  h->ws_bytes = L.total;
+  h->err[0] = 0;
+  Dev& d = h->dev;
+  memset(&d, 0, sizeof(d));
+  char* ws = (char*)cfg->workspace;
+  d.N = cfg->n_neurons; d.B = cfg->batch; d.BN = cfg->n_neurons * cfg->batch;
+  d.R = L.R; d.C = cfg->capacity; d.kind = cfg->kind; d.dbits = L.dbits; d.d_max = cfg->d_max_steps;
+  d.dmask = (1u << L.dbits) - 1u;
+  d.continuous = cfg->delay_ms ? 1 : 0;
+  d.record = cfg->record_tape ? 1 : 0;
+  d.surrogate = cfg->surrogate;
+  d.max_steps = cfg->record_tape ? cfg->max_steps : 0;
+  d.pool_cap = (int)L.pool_cap;
+  d.alpha = (float)std::exp(-(double)cfg->dt_ms / (double)cfg->tau_m_ms);
+  d.theta = cfg->v_thresh; d.v_reset = cfg->v_reset; d.ext_w = cfg->ext_weight;
+  d.dt = cfg->dt_ms; d.tau = cfg->tau_m_ms;
+  {
+    double p = (double)cfg->ext_rate_hz * (double)cfg->dt_ms * 1e-3;
+    if (p < 0.0) p = 0.0;
+    if (p > 1.0) p = 1.0;
+    d.p_thresh = (unsigned long long)std::floor(p * 4294967296.0);
+  }
+  d.seed = cfg->seed;
+  d.S = cfg->n_synapses; d.spike_cap = L.spike_cap; d.event_cap = L.event_cap;
+  d.row_ptr = (const long long*)cfg->row_ptr; d.col = cfg->col; d.weight = cfg->weight;
+  d.delay_steps = cfg->delay_steps; d.delay_ms = cfg->delay_ms;
+  d.ctr = (Counters*)(ws + L.ctr);
+  d.V = (float*)(ws + L.V); d.ring = (int*)(ws + L.ring); d.cnt_ring = (unsigned*)(ws + L.cnt_ring);
+  d.slot_k = (unsigned*)(ws + L.slot_k); d.slot_a = (int*)(ws + L.slot_a);
+  d.occ = (int*)(ws + L.occ); d.head = (int*)(ws + L.head); d.c_head = (int*)(ws + L.c_head);
+  d.pool_p = (long long*)(ws + L.pool_p); d.pool_t = (long long*)(ws + L.pool_t);
+  d.pool_g = (int*)(ws + L.pool_g); d.pool_next = (int*)(ws + L.pool_next);
+  d.pool_k = (unsigned*)(ws + L.pool_k); d.pool_a = (int*)(ws + L.pool_a);
+  d.cur_spk = (int*)(ws + L.cur_spk);
+  d.packed = (unsigned*)(ws + L.packed); d.a_q = (int*)(ws + L.a_q);
+  d.amp = d.continuous ? (float*)(ws + L.amp) : nullptr;
+  d.fdec = d.continuous ? (float*)(ws + L.fdec) : nullptr;
+  d.tapeU = (float*)(ws + L.tapeU); d.step_off = (long long*)(ws + L.step_off);
+  d.tape_spk = (int*)(ws + L.tape_spk); d.tape_evb = (long long*)(ws + L.tape_evb);
+  d.tape_adm = (unsigned char*)(ws + L.tape_adm);
+  d.bwd_ring = (float*)(ws + L.bwd_ring); d.bwd_carry = (float*)(ws + L.bwd_carry);
+  d.bwd_G = (float*)(ws + L.bwd_G);
+
+  hipStream_t st = (hipStream_t)cfg->stream;
+  launch_reset(h, st);
+  ExpCoef ec;
+  ec.c[0] = 1.0;
+  for (int k = 1; k <= 20; ++k) ec.c[k] = ec.c[k - 1] / (double)k;
+  {
+    size_t work = (size_t)(d.S > d.N ? d.S : d.N);
+    size_t g = (work + kBlock - 1) / kBlock;
+    if (g > 8192) g = 8192;
+    if (g < 1) g = 1;
+    hipLaunchKernelGGL(k_prepare, dim3((unsigned)g), dim3(kBlock), 0, st, d, ec);
+  }
+  unsigned err = 0;
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess) e = hipMemcpyAsync(&err, &d.ctr->err, sizeof(err), hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  if (e != hipSuccess) { delete h; return ADSEQ_E_HIP; }
+  if (err & ERR_GRAPH) { delete h; return ADSEQ_E_GRAPH; }
+  if (err & ERR_DELAY) { delete h; return ADSEQ_E_DELAY_RANGE; }
+  *out = h;
+  return ADSEQ_OK;
+}
+
+int adseq_destroy(adseq_t* h) {
+  if (!h) return ADSEQ_E_INVALID_ARG;
+  delete h;
+  return ADSEQ_OK;
+}
+
+int adseq_reset(adseq_t* h, void* stream) {
+  if (!h) return ADSEQ_E_INVALID_ARG;
+  launch_reset(h, (hipStream_t)stream);
+  HIP_TRY(h, hipGetLastError());
+  return ADSEQ_OK;
+}
+
+int adseq_deliver(adseq_t* h, int64_t step, float* I_out, void* stream) {
+  if (!h || !I_out) return h ? fail(h, ADSEQ_E_INVALID_ARG, "adseq_deliver: null argument") : ADSEQ_E_INVALID_ARG;
+  if (step != h->next_step)
+    return fail(h, ADSEQ_E_ORDER, "adseq_deliver: got step %lld, expected %lld", (long long)step, h->next_step);
+  const int parity = (int)(h->enq_calls & 1);
+  launch_neurons<false>(h, (hipStream_t)stream, step, parity, nullptr, nullptr, I_out);
+  h->next_step = step + 1;
+  h->tape_ok = false;
+  HIP_TRY(h, hipGetLastError());
+  return ADSEQ_OK;
+}
+
+int adseq_enqueue(adseq_t* h, int64_t step, const int32_t* spike_ids, const int32_t* n_spikes,
+                  void* stream) {
+  if (!h || !spike_ids || !n_spikes)
+    return h ? fail(h, ADSEQ_E_INVALID_ARG, "adseq_enqueue: null argument") : ADSEQ_E_INVALID_ARG;
+  if (step != h->next_step - 1)
+    return fail(h, ADSEQ_E_ORDER, "adseq_enqueue: got step %lld, expected %lld (the step last delivered)",
+                (long long)step, h->next_step - 1);
+  const int parity = (int)(h->enq_calls & 1);
+  launch_fanout(h, (hipStream_t)stream, step, spike_ids, n_spikes, parity, 0);
+  h->enq_calls += 1;
+  h->tape_ok = false;
+  HIP_TRY(h, hipGetLastError());
+  return ADSEQ_OK;
+}
+
+int adseq_step(adseq_t* h, int64_t step, const float* i_ext, uint8_t* spikes_out, void* stream) {
+  if (!h) return ADSEQ_E_INVALID_ARG;
+  return step_impl(h, step, i_ext, spikes_out, (hipStream_t)stream);
+}
+
+int adseq_run(adseq_t* h, int64_t step0, int64_t n_steps, void* stream) {
+  if (!h) return ADSEQ_E_INVALID_ARG;
+  if (n_steps < 0) return fail(h, ADSEQ_E_INVALID_ARG, "adseq_run: negative step count");
+  for (int64_t n = 0; n < n_steps; ++n) {
+    const int rc = step_impl(h, step0 + n, nullptr, nullptr, (hipStream_t)stream);
+    if (rc != ADSEQ_OK) return rc;
+  }
+  return ADSEQ_OK;
+}
+
+int adseq_backward(adseq_t* h, const float* dL_dcount, const float* dL_dU, float* grad_w,
+                   float* grad_d, void* stream) {
+  if (!h || !grad_w || !grad_d)
+    return h ? fail(h, ADSEQ_E_INVALID_ARG, "adseq_backward: null gradient buffer") : ADSEQ_E_INVALID_ARG;
+  const Dev& d = h->dev;
+  if (!d.record || !h->tape_ok)
+    return fail(h, ADSEQ_E_NO_TAPE, "adseq_backward: no complete recorded forward run");
+  hipStream_t st = (hipStream_t)stream;
+  unsigned err = 0;
+  HIP_TRY(h, hipMemcpyAsync(&err, &d.ctr->err, sizeof(err), hipMemcpyDeviceToHost, st));
+  HIP_TRY(h, hipStreamSynchronize(st));
+  if (err & (ERR_TAPE_SPIKES | ERR_TAPE_EVENTS | ERR_POOL))
+    return fail(h, ADSEQ_E_CAPACITY, "adseq_backward: tape or contender pool overflowed (bits %u)", err);
+  const long long T = h->next_step;
+  fill_u32(st, grad_w, 0u, (size_t)d.S);
+  fill_u32(st, grad_d, 0u, (size_t)d.S);
+  fill_u32(st, d.bwd_ring, 0u, (size_t)d.R * d.BN);
+  fill_u32(st, d.bwd_carry, 0u, (size_t)d.BN);
+  // gradient per unit the delay was given in: 1/tau per ms, dt/tau per step
+  const float dscale = d.continuous ? (float)(1.0 / (double)d.tau) : (float)((double)d.dt / (double)d.tau);
+  const dim3 block(kBlock), gn(grid_for((size_t)d.BN)), gg(kFanoutBlocks);
+  const bool bounded = d.kind != ADSEQ_RING, atomic = d.B > 1;
+  for (long long n = T - 1; n >= 0; --n) {
+    if (bounded) {
+      if (atomic) hipLaunchKernelGGL((k_bwd_gather<true, true>), gg, block, 0, st, d, n, T, dscale, grad_w, grad_d);
+      else hipLaunchKernelGGL((k_bwd_gather<true, false>), gg, block, 0, st, d, n, T, dscale, grad_w, grad_d);
+    } else {
+      if (atomic) hipLaunchKernelGGL((k_bwd_gather<false, true>), gg, block, 0, st, d, n, T, dscale, grad_w, grad_d);
+      else hipLaunchKernelGGL((k_bwd_gather<false, false>), gg, block, 0, st, d, n, T, dscale, grad_w, grad_d);
+    }
+    hipLaunchKernelGGL(k_bwd_neurons, gn, block, 0, st, d, n, dL_dcount, dL_dU);
+  }
+  HIP_TRY(h, hipGetLastError());
+  return ADSEQ_OK;
+}
+
+int adseq_counters(adseq_t* h, int64_t* out8, void* stream) {
+  if (!h || !out8) return ADSEQ_E_INVALID_ARG;
+  Counters c;
+  hipStream_t st = (hipStream_t)stream;
+  HIP_TRY(h, hipMemcpyAsync(&c, h->dev.ctr, sizeof(c), hipMemcpyDeviceToHost, st));
+  HIP_TRY(h, hipStreamSynchronize(st));
+  out8[0] = (int64_t)c.offered; out8[1] = (int64_t)c.dropped; out8[2] = (int64_t)c.delivered;
+  out8[3] = c.sum_offered; out8[4] = c.sum_dropped; out8[5] = c.sum_delivered;
+  out8[6] = c.tape_spikes; out8[7] = (int64_t)c.err;
+  return ADSEQ_OK;
+}
+
+int adseq_drop_count(adseq_t* h, uint64_t* dropped, uint64_t* enqueued, uint64_t* delivered,
+                     void* stream) {
+  if (!h) return ADSEQ_E_INVALID_ARG;
+  int64_t c[8];
+  const int rc = adseq_counters(h, c, stream);
+  if (rc != ADSEQ_OK) return rc;
+  if (dropped) *dropped = (uint64_t)c[1];
+  if (enqueued) *enqueued = (uint64_t)c[0];
+  if (delivered) *delivered = (uint64_t)c[2];
+  if (c[7] & (ERR_TAPE_SPIKES | ERR_TAPE_EVENTS | ERR_POOL))
+    return fail(h, ADSEQ_E_CAPACITY, "tape or contender pool overflowed (bits %lld)", (long long)c[7]);
+  return ADSEQ_OK;
+}
+
+int adseq_tape(const adseq_t* h, adseq_tape_view* out) {
+  if (!h || !out) return ADSEQ_E_INVALID_ARG;
+  const Dev& d = h->dev;
+  if (!d.record) return ADSEQ_E_NO_TAPE;
+  out->membrane = d.tapeU;
+  out->step_offset = (const int64_t*)d.step_off;
+  out->spike_id = d.tape_spk;
+  out->event_base = d.kind != ADSEQ_RING ? (const int64_t*)d.tape_evb : nullptr;
+  out->admitted = d.kind != ADSEQ_RING ? d.tape_adm : nullptr;
+  out->steps_recorded = h->tape_ok ? (h->next_step < d.max_steps ? h->next_step : d.max_steps) : 0;
+  return ADSEQ_OK;
+}
+
+const char* adseq_last_error(const adseq_t* h) { return h ? h->err : "null handle"; }
+
+}  // extern "C"

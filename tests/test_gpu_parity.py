@@ -1,0 +1,223 @@
+"""HIP path vs CPU oracle, element by element, through the C ABI (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2512_05906_amd import adseq, synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+KINDS = {"ring": oracle.RING, "fifo": oracle.FIFO, "sorted": oracle.SORTED}
+
+
+def _compare_forward(wl, kind, cap, T=None, B=None, i_ext=None, check_sets=True):
+    T = wl.n_steps if T is None else T
+    B = wl.batch if B is None else B
+    ref = oracle.Run(wl, kind, cap, n_steps=T, batch=B, i_ext=i_ext, log_events=True, n_threads=8)
+    sim, out = H.run_gpu(wl, kind, cap, n_steps=T, batch=B, i_ext=i_ext)
+    np.testing.assert_array_equal(out["S"], ref.spikes)                 # raster, bit exact
+    np.testing.assert_array_equal(out["U"].view(np.uint32), ref.U.view(np.uint32))  # membrane, bit exact
+    np.testing.assert_array_equal(H.spikes_from_tape(out, wl, B), ref.spikes)
+    c, rc = out["counters"], ref.counters()
+    for key in ("enqueued", "dropped", "delivered", "sum_enqueued", "sum_dropped", "sum_delivered"):
+        assert c[key] == rc[key], key
+    assert c["error_bits"] == 0
+    assert sim.drop_count() == dict(dropped=rc["dropped"], enqueued=rc["enqueued"], delivered=rc["delivered"])
+    if kind != oracle.RING and check_sets:
+        adm, drp = H.gpu_dropped_set(sim, out, wl)
+        o_del, o_drp = H.oracle_sets(ref)
+        assert drp == o_drp                                              # dropped-event set
+        in_run = {(p, n, b) for (p, n, b) in adm if n + int(ref.D[p]) < T}
+        assert in_run == o_del                                           # delivered-event set
+    sim.close()
+    return ref, out
+
+
+@pytest.mark.parametrize("kind", ["ring", "sorted", "fifo"])
+def test_cfg0_forward_lossless(kind):
+    """Config 0 with the ring and with the exact ordered queue (capacity = the
+    largest occupancy the oracle sees, so nothing is dropped)."""
+    wl = synth.cfg0()
+    cap = oracle.Run(wl, oracle.FIFO, 10**6).counters()["max_occupancy"] if kind != "ring" else 0
+    ref, out = _compare_forward(wl, KINDS[kind], cap)
+    assert ref.counters()["dropped"] == 0 and ref.spikes.sum() > 100
+
+
+@pytest.mark.parametrize("kind,cap", [("fifo", 1), ("fifo", 3), ("sorted", 2), ("sorted", 5)])
+def test_cfg0_forward_lossy(kind, cap):
+    wl = synth.cfg0(seed=11)
+    wl.ext_rate_hz = 120.0
+    ref, _ = _compare_forward(wl, KINDS[kind], cap)
+    assert ref.counters()["dropped"] > 0
+
+
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 4), ("sorted", 4)])
+@pytest.mark.parametrize("continuous", [False, True])
+def test_ragged_rows_batched(kind, cap, continuous):
+    """Rows of 0..700 synapses (several 256-wide tiles plus a ragged tail, empty rows,
+    duplicate targets), 3 trials, heavy drive so that the bounded kinds overflow."""
+    wl = synth.ragged_network(300, 700, 37, seed=5, rate_hz=300.0, t=120, b=3, continuous=continuous,
+                              w_mean=0.004, w_std=0.003)
+    ref, _ = _compare_forward(wl, KINDS[kind], cap, check_sets=(kind != "ring"))
+    assert ref.spikes.sum() > 300
+    if kind != "ring":
+        assert ref.counters()["dropped"] > 1000
+
+
+def test_external_current_and_no_drive():
+    wl = synth.cfg0(seed=3)
+    wl.ext_rate_hz = 0.0
+    rng = np.random.default_rng(0)
+    i_ext = (rng.random((200, 2, 100)) * 0.02).astype(np.float32)
+    ref, _ = _compare_forward(wl, oracle.RING, 0, T=200, B=2, i_ext=i_ext)
+    assert ref.spikes.sum() > 10
+
+
+def test_no_spikes_and_zero_steps():
+    wl = synth.cfg0(seed=3)
+    wl.ext_rate_hz = 0.0
+    ref, out = _compare_forward(wl, oracle.FIFO, 2, T=50)
+    assert ref.spikes.sum() == 0 and out["counters"]["enqueued"] == 0
+    sim, out = H.run_gpu(wl, oracle.RING, 0, n_steps=0, record=False)
+    assert out["counters"]["delivered"] == 0
+
+
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 2), ("sorted", 3)])
+def test_open_loop_enqueue_deliver(kind, cap):
+    """adseq_enqueue / adseq_deliver with externally generated spike lists (the
+    shape of the paper's Poisson benchmark, Section 5.1)."""
+    wl = synth.ragged_network(200, 40, 25, seed=9, rate_hz=0.0, t=150, b=2)
+    T, B, N = 150, 2, 200
+    lists = synth.poisson_spike_lists(N, B, T, 400.0, wl.dt_ms, seed=4)
+    forced = np.zeros((T, B * N), np.uint8)
+    for n, ids in enumerate(lists):
+        forced[n, ids] = 1
+    forced = forced.reshape(T, B, N)
+    ref = oracle.Run(wl, KINDS[kind], cap, n_steps=T, batch=B, forced_spikes=forced, keep_currents=True)
+    sim = adseq.Adseq(wl, KINDS[kind], cap, batch=B)
+    I = torch.zeros((T, B, N), dtype=torch.float32, device=sim.dev)
+    for n in range(T):
+        sim.deliver(n, I[n])
+        ids = torch.from_numpy(lists[n]).to(sim.dev)
+        cnt = torch.tensor([len(lists[n])], dtype=torch.int32, device=sim.dev)
+        sim.enqueue(n, ids, cnt)
+    torch.cuda.synchronize()
+    want = ref.Iq.astype(np.float32) * np.float32(2.0 ** -24)
+    np.testing.assert_array_equal(I.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    c, rc = sim.counters(), ref.counters()
+    for key in ("enqueued", "dropped", "delivered", "sum_delivered"):
+        assert c[key] == rc[key], key
+    if kind != "ring":
+        assert rc["dropped"] > 0
+    # out-of-order calls are refused and leave the handle usable
+    with pytest.raises(adseq.AdseqError) as ei:
+        sim.deliver(T + 5, I[0])
+    assert ei.value.code == -4
+    sim.deliver(T, I[0])
+    sim.close()
+
+
+def test_run_twice_is_bit_identical_and_reset_works():
+    wl = synth.ragged_network(300, 200, 30, seed=6, rate_hz=200.0, t=100, b=2, w_mean=0.01, w_std=0.01)
+    sim, a = H.run_gpu(wl, oracle.FIFO, 3, per_step=False)
+    sim.reset()
+    sim.run(0, 100)
+    torch.cuda.synchronize()
+    b = sim.tape()["U"].cpu().numpy()
+    np.testing.assert_array_equal(a["U"].view(np.uint32), b.view(np.uint32))
+    assert sim.counters() == a["counters"]
+    sim.close()
+
+
+def test_create_rejects_bad_delays_and_graph():
+    wl = synth.cfg0()
+    wl.delay_steps[7] = 0
+    with pytest.raises(adseq.AdseqError) as ei:
+        adseq.Adseq(wl, adseq.RING)
+    assert ei.value.code == -2
+    wl = synth.cfg0()
+    wl.delay_steps[7] = 21
+    with pytest.raises(adseq.AdseqError) as ei:
+        adseq.Adseq(wl, adseq.RING)
+    assert ei.value.code == -2
+    wl = synth.cfg0()
+    wl.col[5] = 100
+    with pytest.raises(adseq.AdseqError) as ei:
+        adseq.Adseq(wl, adseq.RING)
+    assert ei.value.code == -8
+    wl = synth.cfg0()
+    wl.row_ptr[10] = wl.row_ptr[11] + 1
+    with pytest.raises(adseq.AdseqError) as ei:
+        adseq.Adseq(wl, adseq.RING)
+    assert ei.value.code == -8
+
+
+# ---------------------------------------------------------------- backward
+
+def _compare_backward(wl, kind, cap, T, B, use_dU=True, surrogate=0, **kw):
+    ref = oracle.Run(wl, kind, cap, n_steps=T, batch=B, surrogate=surrogate, n_threads=8)
+    wl_t = synth.Workload(**{**wl.__dict__, "n_steps": T, "batch": B})
+    y = synth.spike_count_targets(wl_t)
+    counts = ref.spikes.sum(axis=0).astype(np.float32)
+    dL_dc = (2.0 * (counts - y) / np.float32(B * wl.n_neurons)).astype(np.float32)
+    dL_dU = synth.random_cotangent(wl_t, scale=1e-3) if use_dU else None
+    gw, gd = ref.backward(dL_dc, dL_dU)
+    sim, out = H.run_gpu(wl, kind, cap, n_steps=T, batch=B, per_step=False, surrogate=surrogate, **kw)
+    np.testing.assert_array_equal(out["U"].view(np.uint32), ref.U.view(np.uint32))
+    dev = sim.dev
+    g_w = torch.full((wl.n_synapses,), 7.0, dtype=torch.float32, device=dev)  # must be overwritten
+    g_d = torch.full((wl.n_synapses,), 7.0, dtype=torch.float32, device=dev)
+    sim.backward(torch.from_numpy(dL_dc).to(dev),
+                 None if dL_dU is None else torch.from_numpy(dL_dU).to(dev), g_w, g_d)
+    torch.cuda.synchronize()
+    H.grad_close(g_w.cpu().numpy(), gw)
+    H.grad_close(g_d.cpu().numpy(), gd)
+    assert np.abs(gw).max() > 0 and np.abs(gd).max() > 0
+    sim.close()
+    return ref
+
+
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 4), ("sorted", 6)])
+@pytest.mark.parametrize("continuous", [False, True])
+def test_backward_small_ragged(kind, cap, continuous):
+    wl = synth.ragged_network(120, 300, 30, seed=12, rate_hz=300.0, t=150, b=1, continuous=continuous,
+                              w_mean=0.01, w_std=0.01)
+    ref = _compare_backward(wl, KINDS[kind], cap, 150, 1, tape_spike_capacity=150 * 120)
+    assert ref.spikes.sum() > 100
+    if kind != "ring":
+        assert ref.counters()["dropped"] > 0
+
+
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 32), ("fifo", 2), ("sorted", 128)])
+def test_cfg1_forward_backward(kind, cap):
+    """Config 1 (1,000 neurons, fan-out 100, batch 16, 2,000 steps), MSE spike-count loss."""
+    wl = synth.cfg1()
+    ref = _compare_backward(wl, KINDS[kind], cap, wl.n_steps, wl.batch, use_dU=False)
+    if cap == 2:
+        assert ref.counters()["dropped"] > 10000
+    else:
+        assert ref.counters()["dropped"] == 0
+
+
+def test_backward_without_tape_is_refused():
+    wl = synth.cfg0()
+    sim = adseq.Adseq(wl, adseq.RING, record_tape=False)
+    sim.run(0, 10)
+    g = torch.zeros(wl.n_synapses, device=sim.dev)
+    with pytest.raises(adseq.AdseqError) as ei:
+        sim.backward(None, None, g, g.clone())
+    assert ei.value.code == -5
+    sim.close()
+
+
+def test_tape_overflow_is_reported():
+    wl = synth.cfg0(seed=11)
+    wl.ext_rate_hz = 400.0
+    sim = adseq.Adseq(wl, adseq.RING, record_tape=True, max_steps=200, tape_spike_capacity=5)
+    sim.run(0, 200)
+    with pytest.raises(adseq.AdseqError) as ei:
+        sim.drop_count()
+    assert ei.value.code == -7
+    sim.close()
