@@ -1,0 +1,159 @@
+#!/usr/bin/env python3
+"""Benchmark of the delayed spike-event delivery hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over the workload: reset, T time
+steps forward (pop, drive, LIF, compaction, fan-out, enqueue) and the reverse
+sweep with weight and delay gradients.  Default workload: the 100,000-neuron x
+1,000-fan-out network (1e8 synapses, delays 1..250 steps, 1,000 time steps,
+ring queue), synthetic and seeded.
+
+Prints ONE JSON line: metric "synaptic events delivered/s (fwd)" plus the
+forward+backward time per time step, the HBM roofline of the dominant kernel,
+the FIFO drop rate when a bounded queue is selected, and the CPU oracle timed
+on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+# algorithmic bytes: per event and per neuron-step
+FWD_B_EVENT = {"ring": 17, "fifo": 25, "sorted": 25}
+FWD_B_NEURON = 20          # queue row read + clear, V read + write, U tape write
+BWD_B_EVENT = 29
+BWD_B_NEURON = 16
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg3", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4"])
+    ap.add_argument("--queue", default="ring", choices=["ring", "fifo", "sorted"])
+    ap.add_argument("--capacity", type=int, default=32)
+    ap.add_argument("--time-steps", type=int, default=0, help="override the workload's T")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-events", type=float, default=4e7)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2512_05906_amd import adseq, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    dev = torch.device("cuda:0")
+    wl = getattr(synth, args.workload)()
+    T = args.time_steps or wl.n_steps
+    B, N = wl.batch, wl.n_neurons
+    BN = B * N
+    kind = {"ring": adseq.RING, "fifo": adseq.FIFO, "sorted": adseq.SORTED}[args.queue]
+    cap = 0 if kind == adseq.RING else args.capacity
+    fan = wl.n_synapses // N
+    spike_cap = max(BN * T // 4, 4 * BN)
+    sim = adseq.Adseq(wl, kind, cap, record_tape=True, max_steps=T, tape_spike_capacity=spike_cap,
+                      tape_event_capacity=(spike_cap * fan if kind != adseq.RING else 0))
+    y = torch.from_numpy(synth.spike_count_targets(wl)).to(dev).reshape(-1)
+    g_w = torch.empty(wl.n_synapses, dtype=torch.float32, device=dev)
+    g_d = torch.empty(wl.n_synapses, dtype=torch.float32, device=dev)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+
+    def one_step(evs=None):
+        sim.reset()
+        if evs:
+            evs[0].record()
+        sim.run(0, T)
+        if evs:
+            evs[1].record()
+        # loss glue (plumbing, not the path): dL/dcount of the MSE spike-count loss
+        counts = (sim.membrane_tape(T) >= wl.v_thresh).sum(dim=0).reshape(-1).to(torch.float32)
+        dc = (2.0 / BN) * (counts - y)
+        sim.backward(dc, None, g_w, g_d)
+        if evs:
+            evs[2].record()
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        one_step(ev[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    fwd_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    bwd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+    c = sim.counters()
+    assert c["error_bits"] == 0, c
+    delivered, offered, dropped = c["delivered"], c["enqueued"], c["dropped"]
+    spikes = c["tape_spikes"]
+    mean_rate_hz = spikes / BN / (T * wl.dt_ms * 1e-3)
+    value = delivered / (fwd_ms * 1e-3)
+    admitted = offered - dropped
+    fwd_bytes = FWD_B_EVENT[args.queue] * offered + FWD_B_NEURON * BN * T
+    bwd_bytes = BWD_B_EVENT * admitted + BWD_B_NEURON * BN * T
+    achieved = (fwd_bytes + bwd_bytes) / ((fwd_ms + bwd_ms) * 1e-3) / 1e9
+
+    out = {
+        "metric": "synaptic events delivered/s (fwd)",
+        "value": value,
+        "unit": "events/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: N={N} fan_out={fan} synapses={wl.n_synapses} "
+                               f"d_max={wl.d_max_steps} T={T} B={B} queue={args.queue}"
+                               + (f"[{cap}]" if cap else "") + f" drive={wl.ext_rate_hz}Hz",
+                   "mean_rate_hz": mean_rate_hz, "events_per_run": offered,
+                   "delivered_per_run": delivered},
+        "fwd_ms_per_run": fwd_ms,
+        "bwd_ms_per_run": bwd_ms,
+        "fwd_us_per_timestep": fwd_ms * 1e3 / T,
+        "fwdbwd_us_per_timestep": (fwd_ms + bwd_ms) * 1e3 / T,
+        "drop_rate": dropped / max(1, offered),
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "forward + backward launch sequence (all kernels of one run)",
+                     "algorithmic_bytes_per_run": fwd_bytes + bwd_bytes},
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import oracle
+        off = sim.tape()["step_offset"].cpu().numpy()
+        ev_cum = off * fan
+        Ts = int(np.searchsorted(ev_cum, args.cpu_sample_events))
+        Ts = max(10, min(T, Ts))
+        t1 = time.perf_counter()
+        ref = oracle.Run(wl, kind, cap, n_steps=Ts, n_threads=min(B, os.cpu_count() or 1))
+        t_or = time.perf_counter() - t1
+        rc = ref.counters()
+        U = sim.tape()["U"][:Ts].cpu().numpy()
+        parity = bool(np.array_equal(U.view(np.uint32), ref.U.view(np.uint32)))
+        out["cpu_baseline"] = {"value": rc["delivered"] / t_or, "unit": "events/s",
+                               "cores": min(B, os.cpu_count() or 1), "kind": "oracle",
+                               "sample": f"first {Ts} of {T} time steps of the same network "
+                                         f"({rc['enqueued']} events offered, {rc['delivered']} delivered), "
+                                         f"forward only, {t_or:.1f} s",
+                               "membrane_bit_exact_vs_gpu_on_sample": parity}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -204,6 +204,14 @@ class Adseq:
             out["_view"] = view
         return out
 
+    def membrane_tape(self, n_steps: int) -> torch.Tensor:
+        """Zero-copy view [n_steps, B, N] of the recorded membrane values (no synchronisation)."""
+        tv = TapeView()
+        self._check(self.lib.adseq_tape(self.h, C.byref(tv)))
+        off = tv.membrane - self.workspace.data_ptr()
+        nb = n_steps * self.B * self.N * 4
+        return self.workspace[off:off + nb].view(torch.float32).view(n_steps, self.B, self.N)
+
     def admitted_flags(self, event_base: int, count: int) -> torch.Tensor:
         tv = TapeView()
         self._check(self.lib.adseq_tape(self.h, C.byref(tv)))

@@ -83,18 +83,21 @@ def cfg1(seed: int = 1001, n_steps: int = 2000, batch: int = 16) -> Workload:
                           w_std=0.01, rate_hz=20.0, seed=seed)
 
 
-# Drive rates for cfg2 / cfg3 come from a bisection on the run-average firing
-# rate with the ring queue ("Input recipe"); frozen here.
-CFG2_DRIVE_HZ = {5: 0.0, 20: 0.0, 80: 0.0}
-CFG3_DRIVE_HZ = 0.0
+# Drive rates for cfg2 / cfg3: bisection on the run-average firing rate with the
+# ring queue, frozen here.  The purely excitatory networks have loop gain > 1
+# (each spike hands out fan_out * mean weight = 2 thresholds of charge), so the
+# activity ramps up during the run and the rate is a run average, not a steady
+# state; 80 Hz sits on the runaway edge of cfg2 and is only reachable open loop.
+CFG2_DRIVE_HZ = {5: 25.158, 20: 30.808}
+CFG3_DRIVE_HZ = 42.87
 
 
-def cfg2(seed: int = 1002, rate_hz: float = 20.0, n_steps: int = 10000) -> Workload:
+def cfg2(seed: int = 1002, rate_hz: float = CFG2_DRIVE_HZ[20], n_steps: int = 10000) -> Workload:
     return random_network("cfg2", 10000, 1000, n_steps, 1, 200, w_mean=0.002,
                           w_std=0.001, rate_hz=rate_hz, seed=seed)
 
 
-def cfg3(seed: int = 1003, rate_hz: float = 20.0, n_steps: int = 1000,
+def cfg3(seed: int = 1003, rate_hz: float = CFG3_DRIVE_HZ, n_steps: int = 1000,
          n_neurons: int = 100000, fan_out: int = 1000) -> Workload:
     return random_network("cfg3", n_neurons, fan_out, n_steps, 1, 250,
                           w_mean=0.002, w_std=0.001, rate_hz=rate_hz, seed=seed)
