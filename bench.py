@@ -136,8 +136,8 @@ def main():
 
     if not args.no_cpu_baseline:
         from oracle import oracle
-        off = sim.tape()["step_offset"].cpu().numpy()
-        ev_cum = off * fan
+        per_step = (sim.membrane_tape(T) >= wl.v_thresh).sum(dim=(1, 2)).cpu().numpy()
+        ev_cum = np.concatenate([[0], np.cumsum(per_step)]) * fan
         Ts = int(np.searchsorted(ev_cum, args.cpu_sample_events))
         Ts = max(10, min(T, Ts))
         t1 = time.perf_counter()

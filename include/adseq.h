@@ -94,8 +94,8 @@ typedef struct {
   const uint8_t *delay_steps; /* [S] integer delays in steps, or NULL                         */
   const float *delay_ms;      /* [S] continuous delays in ms, or NULL (exactly one is given)  */
   /* The four arrays above must stay valid and unchanged for the life of the handle. */
-  int64_t tape_spike_capacity; /* spikes the tape can hold in total; 0 = default
-                                  (max_steps * B * N / 16 + B * N)                            */
+  int64_t tape_spike_capacity; /* FIFO/SORTED with tape: spikes the tape's spike list can hold
+                                  in total; 0 = default (max_steps * B * N / 16 + B * N)      */
   int64_t tape_event_capacity; /* FIFO/SORTED with tape: emitted events it can hold (one
                                   admission flag each); 0 = default
                                   (tape_spike_capacity * ceil(S / N))                         */
@@ -167,7 +167,8 @@ int adseq_drop_count(adseq_t *h, uint64_t *dropped, uint64_t *enqueued, uint64_t
 int adseq_counters(adseq_t *h, int64_t *out8, void *stream);
 
 /* Where the tape lives inside the workspace (device pointers; valid for the handle's life).
- * membrane: fp32 [max_steps][B*N] pre-reset membrane values U; step_offset: int64 [max_steps+1]
+ * membrane: fp32 [max_steps][B*N] pre-reset membrane values U (a spike is exactly U >= v_thresh);
+ * step_offset (NULL for ADSEQ_RING, whose fused step keeps no spike list): int64 [max_steps+1],
  * spikes of step n are spike_id[step_offset[n] .. step_offset[n+1]) (flat ids, unordered within
  * a step); event_base: int64 per recorded spike, index of its row's first admission flag;
  * admitted: one byte per emitted event (bounded kinds only, else NULL). */

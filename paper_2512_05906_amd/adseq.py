@@ -194,6 +194,8 @@ class Adseq:
         T = int(tv.steps_recorded)
         out = dict(steps=T)
         out["U"] = view(tv.membrane, T * BN * 4, torch.float32).view(T, self.B, self.N)
+        if not tv.step_offset:      # ring: the spikes are U >= v_thresh, no list is kept
+            return out
         off = view(tv.step_offset, (T + 1) * 8, torch.int64)
         out["step_offset"] = off
         n_spk = int(off[T].item()) if T > 0 else 0

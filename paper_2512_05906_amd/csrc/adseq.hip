@@ -5,8 +5,8 @@
 // Layout of the state in the caller's workspace (all arrays 256-byte aligned):
 //   V            fp32  [BN]                 membrane state
 //   ring         i32   [R][BN]              RING: Q8.24 sums per arrival slot, R = d_max + 1
-//   cnt_ring     u32   [R][kFanoutBlocks]   RING: events per arrival slot, one private column per
-//                                           fan-out block (no atomics; summed at pop)
+//   spike_bits   u64   [R][4 nblk]          RING: spike bit masks of the last R steps (one word per
+//                                           wavefront), from which in-flight events are counted on demand
 //   slot_k/a     u32/i32 [C][BN]            FIFO/SORTED: arrival step and Q8.24 amplitude, slot-major
 //                                           so that one slot of 64 consecutive targets is one line
 //   occ, head    i32   [BN]                 FIFO/SORTED: stored events; SORTED: index of the front
@@ -42,6 +42,14 @@ struct Counters {
   unsigned err;
   int n_spk[2];
   int pool_n[2];
+  unsigned long long in_flight[2];  // scratch of k_ring_in_flight: events, Q8.24 sum
+};
+
+// Private counters of one block of the fused step kernel (no atomics; summed on demand).
+struct BlkCtr {
+  unsigned long long offered, delivered, spikes;
+  long long sum_offered, sum_delivered;
+  long long pad[3];
 };
 
 struct ExpCoef { double c[21]; };
@@ -64,7 +72,7 @@ struct Dev {
   float* fdec;
   float* V;
   int* ring;
-  unsigned* cnt_ring;
+  unsigned long long* spike_bits;  // RING: [R][words] spikes of the last R steps
   unsigned* slot_k;
   int* slot_a;
   int* occ;
@@ -86,6 +94,9 @@ struct Dev {
   float* bwd_carry;
   float* bwd_G;
   Counters* ctr;
+  BlkCtr* blk;   // [nblk]
+  int nblk;      // blocks of the fused step kernel = ceil(BN / 256)
+  int words;     // 64-neuron words per step in spike_bits = 4 * nblk
 };
 
 // ---------------------------------------------------------------- device helpers
@@ -248,13 +259,9 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
       }
     }
   }
-  if (KIND == ADSEQ_RING && blockIdx.x == 0) {
-    // event count of this arrival slot: sum the fan-out blocks' private columns
-    unsigned* row = d.cnt_ring + (size_t)(n % d.R) * kFanoutBlocks;
-    for (int x = threadIdx.x; x < kFanoutBlocks; x += kBlock) {
-      const unsigned c = row[x];
-      if (c) { popped += c; row[x] = 0; }
-    }
+  if (KIND == ADSEQ_RING && (threadIdx.x & 63) == 0) {
+    // open-loop use: this step's spike bits start empty; adseq_enqueue sets them
+    d.spike_bits[(size_t)(n % d.R) * d.words + (size_t)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6)] = 0ull;
   }
   bool s = false;
   if (act) {
@@ -297,14 +304,9 @@ template <int KIND>
 __global__ __launch_bounds__(kBlock) void k_fanout(Dev d, long long n, const int* __restrict__ spk,
                                                    const int* __restrict__ n_spk_ptr, int parity,
                                                    int record) {
-  __shared__ unsigned hist[1024];
   __shared__ long long s_evb;
   int nspk = *n_spk_ptr;
   nspk = nspk < 0 ? 0 : (nspk > d.BN ? d.BN : nspk);
-  if (KIND == ADSEQ_RING) {
-    for (int x = threadIdx.x; x <= d.d_max; x += kBlock) hist[x] = 0;
-    __syncthreads();
-  }
   if (KIND != ADSEQ_RING && blockIdx.x == 0 && threadIdx.x == 0) d.ctr->pool_n[parity ^ 1] = 0;
   const long long off = record ? d.step_off[n] : 0;
   const int m = (int)(n % d.R);
@@ -316,6 +318,8 @@ __global__ __launch_bounds__(kBlock) void k_fanout(Dev d, long long n, const int
     const int b = g / d.N, i = g - b * d.N;
     const long long r0 = d.row_ptr[i], r1 = d.row_ptr[i + 1];
     long long tbase = -1;
+    if (KIND == ADSEQ_RING && threadIdx.x == 0)
+      atomicOr(&d.spike_bits[(size_t)m * d.words + (g >> 6)], 1ull << (g & 63));
     if (record) {
       const bool fits = off + e < d.spike_cap;
       if (threadIdx.x == 0) {
@@ -345,7 +349,6 @@ __global__ __launch_bounds__(kBlock) void k_fanout(Dev d, long long n, const int
         if (valid) {
           int slot = m + D; if (slot >= d.R) slot -= d.R;
           atomicAdd(&d.ring[(size_t)slot * d.BN + (size_t)b * d.N + col], a);
-          atomicAdd(&hist[D], 1u);
         }
       } else {
         const int gt = b * d.N + col;
@@ -373,16 +376,6 @@ __global__ __launch_bounds__(kBlock) void k_fanout(Dev d, long long n, const int
             }
           }
         }
-      }
-    }
-  }
-  if (KIND == ADSEQ_RING) {
-    __syncthreads();
-    for (int D = threadIdx.x; D <= d.d_max; D += kBlock) {
-      const unsigned c = hist[D];
-      if (c) {
-        int slot = m + D; if (slot >= d.R) slot -= d.R;
-        d.cnt_ring[(size_t)slot * kFanoutBlocks + blockIdx.x] += c;
       }
     }
   }
@@ -459,6 +452,281 @@ __global__ __launch_bounds__(kBlock) void k_admit(Dev d, int parity) {
     d.c_head[gt] = -1;
   }
   block_add2(&d.ctr->dropped, c_drop, &d.ctr->sum_dropped, s_drop);
+}
+
+// ---------------------------------------------------------------- fused closed-loop step (RING)
+
+constexpr int kBatch = 8;  // row entries each thread keeps in flight before it issues the scatter
+
+// Ascending in-block list of the flagged threads: ballot + popcount prefix per wavefront,
+// wavefront totals through LDS.  Returns the number of entries and this thread's position.
+__device__ __forceinline__ int block_compact(bool flag, int* s_list, int* s_wcnt, int* pos_out) {
+  const unsigned long long m = __ballot(flag);
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  if (lane == 0) s_wcnt[w] = __popcll(m);
+  __syncthreads();
+  int base = 0, total = 0;
+  for (int x = 0; x < kBlock / 64; ++x) { const int c = s_wcnt[x]; if (x < w) base += c; total += c; }
+  const int pos = base + __popcll(m & ((1ull << lane) - 1ull));
+  if (flag) s_list[pos] = threadIdx.x;
+  *pos_out = pos;
+  return total;
+}
+
+// Exclusive prefix of s_len[0..cnt) into s_pref[0..cnt] (cnt <= 256).  All threads call it.
+__device__ __forceinline__ void block_prefix(const int* s_len, int* s_pref, int cnt) {
+  if (cnt <= 32) {
+    if (threadIdx.x == 0) {
+      int run = 0;
+      for (int e = 0; e < cnt; ++e) { s_pref[e] = run; run += s_len[e]; }
+      s_pref[cnt] = run;
+    }
+    __syncthreads();
+    return;
+  }
+  // Hillis-Steele inclusive scan over 256 entries, shifted by one on output
+  __shared__ int s_tmp[2][kBlock];
+  int cur = 0;
+  s_tmp[0][threadIdx.x] = (int)threadIdx.x < cnt ? s_len[threadIdx.x] : 0;
+  __syncthreads();
+  for (int o = 1; o < kBlock; o <<= 1) {
+    int v = s_tmp[cur][threadIdx.x];
+    if ((int)threadIdx.x >= o) v += s_tmp[cur][threadIdx.x - o];
+    s_tmp[cur ^ 1][threadIdx.x] = v;
+    cur ^= 1;
+    __syncthreads();
+  }
+  if ((int)threadIdx.x < cnt) s_pref[threadIdx.x + 1] = s_tmp[cur][threadIdx.x];
+  if (threadIdx.x == 0) s_pref[0] = 0;
+  __syncthreads();
+}
+
+// One launch per time step; block b owns neurons [256 b, 256 b + 256): it pops their ring slots,
+// integrates, compacts its own spikes in LDS and fans them out itself, so a step needs no global
+// spike list, no second launch and no atomic on a shared counter.  The rows of the block's spikes
+// are walked as one concatenated index space, kBatch entries per thread in flight, so that the
+// row reads of all its spikes overlap instead of queueing behind each other.  The ring is
+// d_max + 1 deep, hence the row popped at step n is never a target of the events emitted at step n
+// (arrival offsets are 1..d_max).
+template <bool RECORD>
+__global__ __launch_bounds__(kBlock) void k_step_ring(Dev d, long long n,
+                                                      const float* __restrict__ i_ext,
+                                                      unsigned char* __restrict__ spikes_out) {
+  __shared__ int s_spk[kBlock];
+  __shared__ int s_wcnt[kBlock / 64];
+  __shared__ long long s_r0[kBlock];
+  __shared__ int s_len[kBlock];
+  __shared__ int s_base[kBlock];
+  __shared__ int s_pref[kBlock + 1];
+  __shared__ long long s_red[2][kBlock / 64];
+  const int g = blockIdx.x * kBlock + threadIdx.x;
+  const bool act = g < d.BN;
+  const int m = (int)(n % d.R);
+  int acc = 0;
+  bool s = false;
+  long long r0 = 0, r1 = 0;
+  int bbase = 0;
+  if (act) {
+    const int b = g / d.N, i = g - b * d.N;
+    bbase = b * d.N;
+    // own row bounds, fetched with the state so that a spike does not wait for them
+    r0 = d.row_ptr[i]; r1 = d.row_ptr[i + 1];
+    const size_t idx = (size_t)m * d.BN + g;
+    acc = d.ring[idx];
+    if (acc != 0) d.ring[idx] = 0;
+    float I = (float)acc * 0x1p-24f;
+    if (d.p_thresh) {
+      const bool xi = (unsigned long long)drive_bits(d.seed, (unsigned long long)g,
+                                                     (unsigned long long)n) < d.p_thresh;
+      I = I + (xi ? d.ext_w : 0.0f);
+    }
+    if (i_ext) I = I + i_ext[g];
+    const float U = __fmaf_rn(d.alpha, d.V[g], I);
+    s = U >= d.theta;
+    d.V[g] = s ? d.v_reset : U;
+    if (RECORD) d.tapeU[(size_t)n * d.BN + g] = U;
+    if (spikes_out) spikes_out[g] = s ? 1 : 0;
+  }
+  int pos;
+  const int nspk = block_compact(s, s_spk, s_wcnt, &pos);
+  // spike bits of this step, kept for d_max + 1 steps: the events still in flight are counted
+  // from them on demand (adseq_counters), not on the hot path
+  const unsigned long long wave_bits = __ballot(s);
+  if ((threadIdx.x & 63) == 0)
+    d.spike_bits[(size_t)m * d.words + (size_t)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6)] = wave_bits;
+  const long long sum_pop = wave_sum((long long)acc);
+  if ((threadIdx.x & 63) == 0) s_red[0][threadIdx.x >> 6] = sum_pop;
+  long long s_off = 0;
+  int total = 0;
+  if (nspk) {
+    if (s) { s_r0[pos] = r0; s_len[pos] = (int)(r1 - r0); s_base[pos] = bbase; }
+    __syncthreads();
+    block_prefix(s_len, s_pref, nspk);
+    total = s_pref[nspk];
+    int e = 0;
+    for (int v0 = threadIdx.x; v0 < total; v0 += kBlock * kBatch) {
+      unsigned pk[kBatch]; int aq[kBatch]; int bs[kBatch];
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) {
+        const int v = v0 + j * kBlock;
+        pk[j] = 0; aq[j] = 0; bs[j] = -1;
+        if (v < total) {
+          while (v >= s_pref[e + 1]) ++e;
+          const long long p = s_r0[e] + (v - s_pref[e]);
+          pk[j] = d.packed[p]; aq[j] = d.a_q[p]; bs[j] = s_base[e];
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) {
+        if (bs[j] >= 0) {
+          int slot = m + (int)(pk[j] & d.dmask); if (slot >= d.R) slot -= d.R;
+          atomicAdd(&d.ring[(size_t)slot * d.BN + (size_t)bs[j] + (pk[j] >> d.dbits)], aq[j]);
+          s_off += aq[j];
+        }
+      }
+    }
+    s_off = wave_sum(s_off);
+    if ((threadIdx.x & 63) == 0) s_red[1][threadIdx.x >> 6] = s_off;
+  }
+  __syncthreads();
+  // block totals -> this block's private counters (plain read-modify-write by one thread)
+  if (threadIdx.x == 0) {
+    long long sp = 0, so = 0;
+    for (int w = 0; w < kBlock / 64; ++w) { sp += s_red[0][w]; if (nspk) so += s_red[1][w]; }
+    if (nspk | (sp != 0)) {
+      BlkCtr& bc = d.blk[blockIdx.x];
+      if (nspk) { bc.offered += (unsigned long long)total; bc.sum_offered += so; bc.spikes += (unsigned long long)nspk; }
+      if (sp) bc.sum_delivered += sp;
+    }
+  }
+}
+
+// Events of the ring that are still in flight at step n_end (arrival >= n_end): counted from the
+// spike bits of the last d_max + 1 steps.  One block per (slot, 64-neuron word); on demand only.
+__global__ __launch_bounds__(kBlock) void k_ring_in_flight(Dev d, long long n_end,
+                                                           unsigned long long* out /*[2]*/) {
+  const long long item = blockIdx.x;
+  const int slot = (int)(item / d.words);
+  const long long word = item % d.words;
+  // the step this slot last held: the largest n' < n_end with n' % R == slot
+  long long np = n_end - 1 - ((n_end - 1 - slot) % d.R + d.R) % d.R;
+  if (n_end <= 0 || np < 0) return;
+  unsigned long long bits = d.spike_bits[(size_t)slot * d.words + word];
+  long long cnt = 0, sum = 0;
+  while (bits) {
+    const int bit = __ffsll((long long)bits) - 1;
+    bits &= bits - 1;
+    const long long g = word * 64 + bit;
+    if (g >= d.BN) break;
+    const int i = (int)(g % d.N);
+    const long long r0 = d.row_ptr[i], r1 = d.row_ptr[i + 1];
+    for (long long p = r0 + threadIdx.x; p < r1; p += kBlock) {
+      const int D = (int)(d.packed[p] & d.dmask);
+      if (np + D >= n_end) { cnt += 1; sum += d.a_q[p]; }
+    }
+  }
+  block_add2(&out[0], cnt, (long long*)&out[1], sum);
+}
+
+// One launch per reverse step for the ring: the block re-derives its spikes from the membrane
+// tape (s = U >= theta), gathers the queue term of each of them over the CSR row, accumulates the
+// row's weight and delay gradients, and then updates the adjoint of its 256 neurons.
+template <bool ATOMIC>
+__global__ __launch_bounds__(kBlock) void k_bwd_step_ring(Dev d, long long n, long long T, float dscale,
+                                                          const float* __restrict__ dL_dcount,
+                                                          const float* __restrict__ dL_dU,
+                                                          float* __restrict__ grad_w,
+                                                          float* __restrict__ grad_d) {
+  __shared__ int s_spk[kBlock];
+  __shared__ int s_wcnt[kBlock / 64];
+  __shared__ long long s_r0[kBlock];
+  __shared__ int s_len[kBlock];
+  __shared__ int s_base[kBlock];
+  __shared__ int s_pref[kBlock + 1];
+  __shared__ float s_G[kBlock];
+  const int g = blockIdx.x * kBlock + threadIdx.x;
+  const bool act = g < d.BN;
+  const int m = (int)(n % d.R);
+  float U = 0.0f;
+  bool s = false;
+  long long r0 = 0, r1 = 0;
+  int bbase = 0;
+  if (act) {
+    const int b = g / d.N, i = g - b * d.N;
+    bbase = b * d.N;
+    r0 = d.row_ptr[i]; r1 = d.row_ptr[i + 1];
+    U = d.tapeU[(size_t)n * d.BN + g];
+    s = U >= d.theta;
+  }
+  int pos;
+  const int nspk = block_compact(s, s_spk, s_wcnt, &pos);
+  if (nspk) {
+    if (s) { s_r0[pos] = r0; s_len[pos] = (int)(r1 - r0); s_base[pos] = bbase; s_G[pos] = 0.0f; }
+    __syncthreads();
+    block_prefix(s_len, s_pref, nspk);
+    const int total = s_pref[nspk];
+    int e = 0;
+    for (int v0 = threadIdx.x; v0 < total; v0 += kBlock * kBatch) {
+      unsigned pk[kBatch]; float am[kBatch]; float fd[kBatch]; int bs[kBatch]; int ee[kBatch];
+      long long pp[kBatch];
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) {
+        const int v = v0 + j * kBlock;
+        pk[j] = 0; am[j] = 0.0f; fd[j] = 1.0f; bs[j] = -1; ee[j] = 0; pp[j] = 0;
+        if (v < total) {
+          while (v >= s_pref[e + 1]) ++e;
+          const long long p = s_r0[e] + (v - s_pref[e]);
+          pk[j] = d.packed[p];
+          if (d.continuous) { am[j] = d.amp[p]; fd[j] = d.fdec[p]; } else { am[j] = d.weight[p]; }
+          bs[j] = s_base[e]; ee[j] = e; pp[j] = p;
+        }
+      }
+      float gv[kBatch];
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) {
+        gv[j] = 0.0f;
+        const int D = (int)(pk[j] & d.dmask);
+        if (bs[j] >= 0 && n + D < T) {  // else: not delivered inside the run
+          int slot = m + D; if (slot >= d.R) slot -= d.R;
+          gv[j] = d.bwd_ring[(size_t)slot * d.BN + (size_t)bs[j] + (pk[j] >> d.dbits)];
+        } else {
+          bs[j] = -1;
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) {
+        // queue term: one LDS add per wavefront when the whole wavefront serves the same spike
+        const float contrib = bs[j] >= 0 ? am[j] * gv[j] : 0.0f;
+        const int e0 = __shfl(ee[j], 0, 64);
+        if (__all(ee[j] == e0)) {
+          const float t = wave_sum_f(contrib);
+          if ((threadIdx.x & 63) == 0 && t != 0.0f) atomicAdd(&s_G[e0], t);
+        } else if (contrib != 0.0f) {
+          atomicAdd(&s_G[ee[j]], contrib);
+        }
+        if (bs[j] >= 0) {
+          const float gw = fd[j] * gv[j], gd = am[j] * dscale * gv[j];
+          if (ATOMIC) { unsafeAtomicAdd(&grad_w[pp[j]], gw); unsafeAtomicAdd(&grad_d[pp[j]], gd); }
+          else { grad_w[pp[j]] += gw; grad_d[pp[j]] += gd; }
+        }
+      }
+    }
+    __syncthreads();
+  }
+  if (act) {
+    float sg = 0.0f;
+    if (d.surrogate == ADSEQ_SURR_SUPERSPIKE) {
+      const float x = fabsf(U - d.theta) + 1.0f;
+      sg = 1.0f / (x * x);
+    }
+    float inner = dL_dcount ? dL_dcount[g] : 0.0f;
+    if (s) inner += s_G[pos];
+    float gu = sg * inner;
+    if (!s) gu = __fmaf_rn(d.alpha, d.bwd_carry[g], gu);
+    if (dL_dU) gu += dL_dU[(size_t)n * d.BN + g];
+    d.bwd_carry[g] = gu;
+    d.bwd_ring[(size_t)m * d.BN + g] = gu;
+  }
 }
 
 // ---------------------------------------------------------------- backward
@@ -547,11 +815,11 @@ struct adseq {
 namespace {
 
 struct Layout {
-  size_t V, ring, cnt_ring, slot_k, slot_a, occ, head, c_head, pool_p, pool_t, pool_g, pool_next,
+  size_t V, ring, spike_bits, slot_k, slot_a, occ, head, c_head, pool_p, pool_t, pool_g, pool_next,
       pool_k, pool_a, cur_spk, packed, a_q, amp, fdec, tapeU, step_off, tape_spk, tape_evb, tape_adm,
-      bwd_ring, bwd_carry, bwd_G, ctr, total;
+      bwd_ring, bwd_carry, bwd_G, ctr, blk, total;
   long long spike_cap, event_cap, pool_cap;
-  int R, dbits;
+  int R, dbits, nblk, words;
 };
 
 int bit_width(unsigned v) { int b = 0; while (v) { ++b; v >>= 1; } return b; }
@@ -602,10 +870,13 @@ bool make_layout(const adseq_config* c, Layout* L) {
   }
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o += (bytes + 255) & ~(size_t)255; return at; };
+  L->nblk = (int)((BN + kBlock - 1) / kBlock);
+  L->words = L->nblk * (kBlock / 64);
   L->ctr = take(sizeof(Counters));
+  L->blk = take((size_t)L->nblk * sizeof(BlkCtr));
   L->V = take(BN * 4);
   L->ring = take(bounded ? 0 : (size_t)L->R * BN * 4);
-  L->cnt_ring = take(bounded ? 0 : (size_t)L->R * kFanoutBlocks * 4);
+  L->spike_bits = take(bounded ? 0 : (size_t)L->R * L->words * 8);
   L->slot_k = take(bounded ? (size_t)c->capacity * BN * 4 : 0);
   L->slot_a = take(bounded ? (size_t)c->capacity * BN * 4 : 0);
   L->occ = take(bounded ? BN * 4 : 0);
@@ -625,7 +896,7 @@ bool make_layout(const adseq_config* c, Layout* L) {
   const size_t T = c->record_tape ? (size_t)c->max_steps : 0;
   L->tapeU = take(T * BN * 4);
   L->step_off = take(c->record_tape ? (T + 1) * 8 : 0);
-  L->tape_spk = take((size_t)L->spike_cap * 4);
+  L->tape_spk = take(bounded ? (size_t)L->spike_cap * 4 : 0);
   L->tape_evb = take(bounded ? (size_t)L->spike_cap * 8 : 0);
   L->tape_adm = take((size_t)L->event_cap);
   L->bwd_ring = take(c->record_tape ? (size_t)L->R * BN * 4 : 0);
@@ -668,10 +939,11 @@ void launch_reset(adseq* h, hipStream_t st) {
   const Dev& d = h->dev;
   const size_t BN = (size_t)d.BN;
   fill_u32(st, d.ctr, 0u, sizeof(Counters) / 4);
+  fill_u32(st, d.blk, 0u, (size_t)d.nblk * sizeof(BlkCtr) / 4);
   fill_u32(st, d.V, 0u, BN);
   if (d.kind == ADSEQ_RING) {
     fill_u32(st, d.ring, 0u, (size_t)d.R * BN);
-    fill_u32(st, d.cnt_ring, 0u, (size_t)d.R * kFanoutBlocks);
+    fill_u32(st, d.spike_bits, 0u, (size_t)d.R * d.words * 2);
   } else {
     fill_u32(st, d.occ, 0u, BN);
     fill_u32(st, d.head, 0u, BN);
@@ -727,8 +999,13 @@ int step_impl(adseq* h, long long step, const float* i_ext, unsigned char* spike
   const int parity = (int)(h->enq_calls & 1);
   const int record = (d.record && h->tape_ok && step < d.max_steps) ? 1 : 0;
   if (d.record && step >= d.max_steps) h->tape_ok = false;
-  launch_neurons<true>(h, st, step, parity, i_ext, spikes_out, nullptr);
-  launch_fanout(h, st, step, d.cur_spk, &d.ctr->n_spk[parity], parity, record);
+  if (d.kind == ADSEQ_RING) {
+    if (record) hipLaunchKernelGGL((k_step_ring<true>), dim3(d.nblk), dim3(kBlock), 0, st, d, step, i_ext, spikes_out);
+    else hipLaunchKernelGGL((k_step_ring<false>), dim3(d.nblk), dim3(kBlock), 0, st, d, step, i_ext, spikes_out);
+  } else {
+    launch_neurons<true>(h, st, step, parity, i_ext, spikes_out, nullptr);
+    launch_fanout(h, st, step, d.cur_spk, &d.ctr->n_spk[parity], parity, record);
+  }
   h->enq_calls += 1;
   h->next_step = step + 1;
   HIP_TRY(h, hipGetLastError());
@@ -783,7 +1060,8 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   d.row_ptr = (const long long*)cfg->row_ptr; d.col = cfg->col; d.weight = cfg->weight;
   d.delay_steps = cfg->delay_steps; d.delay_ms = cfg->delay_ms;
   d.ctr = (Counters*)(ws + L.ctr);
-  d.V = (float*)(ws + L.V); d.ring = (int*)(ws + L.ring); d.cnt_ring = (unsigned*)(ws + L.cnt_ring);
+  d.blk = (BlkCtr*)(ws + L.blk); d.nblk = L.nblk; d.words = L.words;
+  d.V = (float*)(ws + L.V); d.ring = (int*)(ws + L.ring); d.spike_bits = (unsigned long long*)(ws + L.spike_bits);
   d.slot_k = (unsigned*)(ws + L.slot_k); d.slot_a = (int*)(ws + L.slot_a);
   d.occ = (int*)(ws + L.occ); d.head = (int*)(ws + L.head); d.c_head = (int*)(ws + L.c_head);
   d.pool_p = (long long*)(ws + L.pool_p); d.pool_t = (long long*)(ws + L.pool_t);
@@ -900,6 +1178,11 @@ int adseq_backward(adseq_t* h, const float* dL_dcount, const float* dL_dU, float
   const dim3 block(kBlock), gn(grid_for((size_t)d.BN)), gg(kFanoutBlocks);
   const bool bounded = d.kind != ADSEQ_RING, atomic = d.B > 1;
   for (long long n = T - 1; n >= 0; --n) {
+    if (!bounded) {
+      if (atomic) hipLaunchKernelGGL((k_bwd_step_ring<true>), dim3(d.nblk), block, 0, st, d, n, T, dscale, dL_dcount, dL_dU, grad_w, grad_d);
+      else hipLaunchKernelGGL((k_bwd_step_ring<false>), dim3(d.nblk), block, 0, st, d, n, T, dscale, dL_dcount, dL_dU, grad_w, grad_d);
+      continue;
+    }
     if (bounded) {
       if (atomic) hipLaunchKernelGGL((k_bwd_gather<true, true>), gg, block, 0, st, d, n, T, dscale, grad_w, grad_d);
       else hipLaunchKernelGGL((k_bwd_gather<true, false>), gg, block, 0, st, d, n, T, dscale, grad_w, grad_d);
@@ -917,11 +1200,35 @@ int adseq_counters(adseq_t* h, int64_t* out8, void* stream) {
   if (!h || !out8) return ADSEQ_E_INVALID_ARG;
   Counters c;
   hipStream_t st = (hipStream_t)stream;
-  HIP_TRY(h, hipMemcpyAsync(&c, h->dev.ctr, sizeof(c), hipMemcpyDeviceToHost, st));
+  const Dev& d = h->dev;
+  if (d.kind == ADSEQ_RING) {
+    // the ring sums amplitudes, so delivered = offered - still in flight; the latter is counted
+    // here, on demand, from the spike bits of the last d_max + 1 steps
+    fill_u32(st, d.ctr->in_flight, 0u, 4);
+    const long long items = (long long)d.R * d.words;
+    hipLaunchKernelGGL(k_ring_in_flight, dim3((unsigned)items), dim3(kBlock), 0, st, d, h->next_step,
+                       d.ctr->in_flight);
+  }
+  HIP_TRY(h, hipMemcpyAsync(&c, d.ctr, sizeof(c), hipMemcpyDeviceToHost, st));
   HIP_TRY(h, hipStreamSynchronize(st));
   out8[0] = (int64_t)c.offered; out8[1] = (int64_t)c.dropped; out8[2] = (int64_t)c.delivered;
   out8[3] = c.sum_offered; out8[4] = c.sum_dropped; out8[5] = c.sum_delivered;
   out8[6] = c.tape_spikes; out8[7] = (int64_t)c.err;
+  if (d.kind == ADSEQ_RING) {
+    // the fused step kernel keeps private counters per block: add them up here
+    const int nb = d.nblk;
+    BlkCtr* hb = new (std::nothrow) BlkCtr[nb];
+    if (!hb) return fail(h, ADSEQ_E_INVALID_ARG, "adseq_counters: out of host memory");
+    hipError_t e = hipMemcpyAsync(hb, d.blk, sizeof(BlkCtr) * nb, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) { delete[] hb; return fail(h, ADSEQ_E_HIP, "copy of block counters failed: %s", hipGetErrorString(e)); }
+    for (int i = 0; i < nb; ++i) {
+      out8[0] += (int64_t)hb[i].offered; out8[3] += hb[i].sum_offered;
+      out8[5] += hb[i].sum_delivered; out8[6] += (int64_t)hb[i].spikes;
+    }
+    delete[] hb;
+    out8[2] = out8[0] - (int64_t)c.in_flight[0];
+  }
   return ADSEQ_OK;
 }
 
@@ -944,8 +1251,9 @@ int adseq_tape(const adseq_t* h, adseq_tape_view* out) {
   const Dev& d = h->dev;
   if (!d.record) return ADSEQ_E_NO_TAPE;
   out->membrane = d.tapeU;
-  out->step_offset = (const int64_t*)d.step_off;
-  out->spike_id = d.tape_spk;
+  // the ring's fused step keeps no spike list: its spikes are exactly U >= v_thresh on the tape
+  out->step_offset = d.kind != ADSEQ_RING ? (const int64_t*)d.step_off : nullptr;
+  out->spike_id = d.kind != ADSEQ_RING ? d.tape_spk : nullptr;
   out->event_base = d.kind != ADSEQ_RING ? (const int64_t*)d.tape_evb : nullptr;
   out->admitted = d.kind != ADSEQ_RING ? d.tape_adm : nullptr;
   out->steps_recorded = h->tape_ok ? (h->next_step < d.max_steps ? h->next_step : d.max_steps) : 0;

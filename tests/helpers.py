@@ -27,8 +27,9 @@ def run_gpu(wl, kind, capacity=0, *, n_steps=None, batch=None, record=True, i_ex
     if record:
         tp = sim.tape()
         out["U"] = tp["U"].cpu().numpy()
-        out["step_offset"] = tp["step_offset"].cpu().numpy()
-        out["spike_id"] = tp["spike_id"].cpu().numpy()
+        if "step_offset" in tp:
+            out["step_offset"] = tp["step_offset"].cpu().numpy()
+            out["spike_id"] = tp["spike_id"].cpu().numpy()
         if "event_base" in tp:
             out["event_base"] = tp["event_base"].cpu().numpy()
     return sim, out
