@@ -182,6 +182,17 @@ typedef struct {
 } adseq_tape_view;
 int adseq_tape(const adseq_t *h, adseq_tape_view *out);
 
+/* Kernel timing for benchmarks (not a call of the method; for callers that want per-kernel
+ * durations without an external profiler).  While enabled, adseq_step / adseq_run /
+ * adseq_backward record a HIP event on the caller's stream after every kernel they launch
+ * (events are created by the library on first use and destroyed with the handle).
+ * adseq_profile_read synchronises `stream` and returns, per kernel class, the summed time in ms and
+ * the number of launches since the last read: [0] fan-out + enqueue, [1] pop + drive + LIF,
+ * [2] backward queue term + gradients, [3] backward neuron update; then it forgets them.
+ * For FIFO/SORTED class [0] covers the fan-out and admission launches together. */
+int adseq_profile(adseq_t *h, int enable);
+int adseq_profile_read(adseq_t *h, double *ms4 /*host*/, int64_t *launches4 /*host*/, void *stream);
+
 /* Text of the last error on this handle (host string owned by the handle). */
 const char *adseq_last_error(const adseq_t *h);
 

@@ -14,7 +14,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libadseq.so")
+LIB_PATH = os.environ.get("ADSEQ_LIB", os.path.join(_HERE, "libadseq.so"))
 
 RING, FIFO, SORTED = 0, 1, 2
 SURR_SUPERSPIKE, SURR_OFF = 0, 1
@@ -24,7 +24,7 @@ ERRORS = {0: "OK", -1: "INVALID_ARG", -2: "DELAY_RANGE", -3: "WORKSPACE", -4: "O
 
 EXPORTS = ["adseq_workspace_bytes", "adseq_create", "adseq_destroy", "adseq_reset", "adseq_deliver",
            "adseq_enqueue", "adseq_step", "adseq_run", "adseq_backward", "adseq_drop_count",
-           "adseq_counters", "adseq_tape", "adseq_last_error"]
+           "adseq_counters", "adseq_tape", "adseq_profile", "adseq_profile_read", "adseq_last_error"]
 
 
 class AdseqError(RuntimeError):
@@ -80,6 +80,8 @@ def load():
                                        C.POINTER(C.c_uint64), vp]
         L.adseq_counters.argtypes = [vp, C.POINTER(i64), vp]
         L.adseq_tape.argtypes = [vp, C.POINTER(TapeView)]
+        L.adseq_profile.argtypes = [vp, C.c_int]
+        L.adseq_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64), vp]
         L.adseq_last_error.restype = C.c_char_p
         L.adseq_last_error.argtypes = [vp]
         for name in EXPORTS:
@@ -179,6 +181,16 @@ class Adseq:
         names = ["enqueued", "dropped", "delivered", "sum_enqueued", "sum_dropped", "sum_delivered",
                  "tape_spikes", "error_bits"]
         return dict(zip(names, [int(x) for x in out]))
+
+    def profile(self, enable: bool):
+        self._check(self.lib.adseq_profile(self.h, int(enable)))
+
+    def profile_read(self):
+        ms = (C.c_double * 4)()
+        cnt = (C.c_int64 * 4)()
+        self._check(self.lib.adseq_profile_read(self.h, ms, cnt, _stream()))
+        names = ["fan_out", "lif", "bwd_gather", "bwd_neurons"]
+        return {k: dict(ms=ms[i], launches=int(cnt[i])) for i, k in enumerate(names)}
 
     def tape(self):
         """Zero-copy torch views of the tape inside the workspace."""

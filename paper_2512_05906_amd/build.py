@@ -27,5 +27,15 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+def build_copy_reference() -> str:
+    """The plain copy program that the HBM traffic counters are calibrated with."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    out = os.path.join(HERE, "copy_ref")
+    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang",
+                           "-packed-fp32-ops", "-o", out, os.path.join(HERE, "csrc", "copy_ref.hip")])
+    return out
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_copy_reference())

@@ -22,6 +22,7 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "adseq.h"
 
@@ -454,10 +455,6 @@ __global__ __launch_bounds__(kBlock) void k_admit(Dev d, int parity) {
   block_add2(&d.ctr->dropped, c_drop, &d.ctr->sum_dropped, s_drop);
 }
 
-// ---------------------------------------------------------------- fused closed-loop step (RING)
-
-constexpr int kBatch = 8;  // row entries each thread keeps in flight before it issues the scatter
-
 // Ascending in-block list of the flagged threads: ballot + popcount prefix per wavefront,
 // wavefront totals through LDS.  Returns the number of entries and this thread's position.
 __device__ __forceinline__ int block_compact(bool flag, int* s_list, int* s_wcnt, int* pos_out) {
@@ -473,64 +470,35 @@ __device__ __forceinline__ int block_compact(bool flag, int* s_list, int* s_wcnt
   return total;
 }
 
-// Exclusive prefix of s_len[0..cnt) into s_pref[0..cnt] (cnt <= 256).  All threads call it.
-__device__ __forceinline__ void block_prefix(const int* s_len, int* s_pref, int cnt) {
-  if (cnt <= 32) {
-    if (threadIdx.x == 0) {
-      int run = 0;
-      for (int e = 0; e < cnt; ++e) { s_pref[e] = run; run += s_len[e]; }
-      s_pref[cnt] = run;
-    }
-    __syncthreads();
-    return;
-  }
-  // Hillis-Steele inclusive scan over 256 entries, shifted by one on output
-  __shared__ int s_tmp[2][kBlock];
-  int cur = 0;
-  s_tmp[0][threadIdx.x] = (int)threadIdx.x < cnt ? s_len[threadIdx.x] : 0;
-  __syncthreads();
-  for (int o = 1; o < kBlock; o <<= 1) {
-    int v = s_tmp[cur][threadIdx.x];
-    if ((int)threadIdx.x >= o) v += s_tmp[cur][threadIdx.x - o];
-    s_tmp[cur ^ 1][threadIdx.x] = v;
-    cur ^= 1;
-    __syncthreads();
-  }
-  if ((int)threadIdx.x < cnt) s_pref[threadIdx.x + 1] = s_tmp[cur][threadIdx.x];
-  if (threadIdx.x == 0) s_pref[0] = 0;
-  __syncthreads();
-}
+// ---------------------------------------------------------------- closed-loop step (RING)
+//
+// Two launches per time step, neither with an atomic on a shared counter:
+//   k_lif_ring   block b owns neurons [256 b, 256 b + 256): pops their ring slots, integrates,
+//                records the membrane value, publishes the spike bits of its four wavefronts;
+//   k_fan_ring   kSplit blocks per neuron block: block (b, c) re-derives b's spikes from the spike
+//                bits and scatters chunk c (256 entries out of every kSplit * 256) of each spike's CSR
+//                row, so that one neuron block's spikes are spread over kSplit compute units and the
+//                row reads of all its spikes are in flight together.
+// The ring is d_max + 1 deep, hence the row popped at step n is never a target of the events
+// emitted at step n (arrival offsets are 1..d_max).
 
-// One launch per time step; block b owns neurons [256 b, 256 b + 256): it pops their ring slots,
-// integrates, compacts its own spikes in LDS and fans them out itself, so a step needs no global
-// spike list, no second launch and no atomic on a shared counter.  The rows of the block's spikes
-// are walked as one concatenated index space, kBatch entries per thread in flight, so that the
-// row reads of all its spikes overlap instead of queueing behind each other.  The ring is
-// d_max + 1 deep, hence the row popped at step n is never a target of the events emitted at step n
-// (arrival offsets are 1..d_max).
+#ifndef ADSEQ_KSPLIT
+#define ADSEQ_KSPLIT 4
+#endif
+constexpr int kSplit = ADSEQ_KSPLIT;  // fan-out blocks per neuron block
+constexpr int kBatch = 8;  // spikes whose row entries a thread keeps in flight together
+
 template <bool RECORD>
-__global__ __launch_bounds__(kBlock) void k_step_ring(Dev d, long long n,
-                                                      const float* __restrict__ i_ext,
-                                                      unsigned char* __restrict__ spikes_out) {
-  __shared__ int s_spk[kBlock];
-  __shared__ int s_wcnt[kBlock / 64];
-  __shared__ long long s_r0[kBlock];
-  __shared__ int s_len[kBlock];
-  __shared__ int s_base[kBlock];
-  __shared__ int s_pref[kBlock + 1];
-  __shared__ long long s_red[2][kBlock / 64];
+__global__ __launch_bounds__(kBlock) void k_lif_ring(Dev d, long long n,
+                                                     const float* __restrict__ i_ext,
+                                                     unsigned char* __restrict__ spikes_out) {
+  __shared__ long long s_red[kBlock / 64];
   const int g = blockIdx.x * kBlock + threadIdx.x;
   const bool act = g < d.BN;
   const int m = (int)(n % d.R);
   int acc = 0;
   bool s = false;
-  long long r0 = 0, r1 = 0;
-  int bbase = 0;
   if (act) {
-    const int b = g / d.N, i = g - b * d.N;
-    bbase = b * d.N;
-    // own row bounds, fetched with the state so that a spike does not wait for them
-    r0 = d.row_ptr[i]; r1 = d.row_ptr[i + 1];
     const size_t idx = (size_t)m * d.BN + g;
     acc = d.ring[idx];
     if (acc != 0) d.ring[idx] = 0;
@@ -547,33 +515,73 @@ __global__ __launch_bounds__(kBlock) void k_step_ring(Dev d, long long n,
     if (RECORD) d.tapeU[(size_t)n * d.BN + g] = U;
     if (spikes_out) spikes_out[g] = s ? 1 : 0;
   }
-  int pos;
-  const int nspk = block_compact(s, s_spk, s_wcnt, &pos);
-  // spike bits of this step, kept for d_max + 1 steps: the events still in flight are counted
-  // from them on demand (adseq_counters), not on the hot path
-  const unsigned long long wave_bits = __ballot(s);
+  // spike bits of this step: read by k_fan_ring, and kept for d_max + 1 steps so that the events
+  // still in flight can be counted on demand (adseq_counters) instead of on the hot path
+  const unsigned long long bits = __ballot(s);
   if ((threadIdx.x & 63) == 0)
-    d.spike_bits[(size_t)m * d.words + (size_t)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6)] = wave_bits;
-  const long long sum_pop = wave_sum((long long)acc);
-  if ((threadIdx.x & 63) == 0) s_red[0][threadIdx.x >> 6] = sum_pop;
-  long long s_off = 0;
-  int total = 0;
-  if (nspk) {
-    if (s) { s_r0[pos] = r0; s_len[pos] = (int)(r1 - r0); s_base[pos] = bbase; }
-    __syncthreads();
-    block_prefix(s_len, s_pref, nspk);
-    total = s_pref[nspk];
-    int e = 0;
-    for (int v0 = threadIdx.x; v0 < total; v0 += kBlock * kBatch) {
+    d.spike_bits[(size_t)m * d.words + (size_t)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6)] = bits;
+  const long long sp = wave_sum((long long)acc);
+  const long long ns = wave_sum((long long)(s ? 1 : 0));
+  if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = sp;
+  __shared__ long long s_ns[kBlock / 64];
+  if ((threadIdx.x & 63) == 0) s_ns[threadIdx.x >> 6] = ns;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    long long a = 0, c = 0;
+    for (int w = 0; w < kBlock / 64; ++w) { a += s_red[w]; c += s_ns[w]; }
+    if (a | c) {
+      BlkCtr& bc = d.blk[blockIdx.x];
+      bc.sum_delivered += a; bc.spikes += (unsigned long long)c;
+    }
+  }
+}
+
+// Spikes of neuron block `nb` at ring slot m, from the spike bits: fills s_r0 / s_len / s_base in
+// ascending neuron order and returns their number (0: nothing to do; uniform over the block).
+__device__ __forceinline__ int block_spikes_from_bits(const Dev& d, int m, int nb, long long* s_r0,
+                                                      int* s_len, int* s_base) {
+  const unsigned long long* w = d.spike_bits + (size_t)m * d.words + (size_t)nb * (kBlock / 64);
+  const unsigned long long w0 = w[0], w1 = w[1], w2 = w[2], w3 = w[3];
+  if ((w0 | w1 | w2 | w3) == 0ull) return 0;
+  const int wi = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const unsigned long long mine = wi == 0 ? w0 : (wi == 1 ? w1 : (wi == 2 ? w2 : w3));
+  if ((mine >> lane) & 1ull) {
+    int pos = __popcll(mine & ((1ull << lane) - 1ull));
+    if (wi > 0) pos += __popcll(w0);
+    if (wi > 1) pos += __popcll(w1);
+    if (wi > 2) pos += __popcll(w2);
+    const int g = nb * kBlock + threadIdx.x;
+    const int b = g / d.N, i = g - b * d.N;
+    const long long r0 = d.row_ptr[i];
+    s_r0[pos] = r0; s_len[pos] = (int)(d.row_ptr[i + 1] - r0); s_base[pos] = b * d.N;
+  }
+  __syncthreads();
+  return __popcll(w0) + __popcll(w1) + __popcll(w2) + __popcll(w3);
+}
+
+__global__ __launch_bounds__(kBlock) void k_fan_ring(Dev d, long long n) {
+  __shared__ long long s_r0[kBlock];
+  __shared__ int s_len[kBlock];
+  __shared__ int s_base[kBlock];
+  __shared__ long long s_red[2][kBlock / 64];
+  const int nb = blockIdx.x / kSplit, c = blockIdx.x % kSplit;
+  const int m = (int)(n % d.R);
+  const int nspk = block_spikes_from_bits(d, m, nb, s_r0, s_len, s_base);
+  if (nspk == 0) return;
+  long long c_off = 0, s_off = 0;
+  for (int e0 = 0; e0 < nspk; e0 += kBatch) {
+    int maxlen = 0;
+#pragma unroll
+    for (int j = 0; j < kBatch; ++j)
+      if (e0 + j < nspk) { const int l = s_len[e0 + j]; maxlen = l > maxlen ? l : maxlen; }
+    for (int q = c * kBlock + threadIdx.x; q < maxlen; q += kSplit * kBlock) {
       unsigned pk[kBatch]; int aq[kBatch]; int bs[kBatch];
 #pragma unroll
       for (int j = 0; j < kBatch; ++j) {
-        const int v = v0 + j * kBlock;
-        pk[j] = 0; aq[j] = 0; bs[j] = -1;
-        if (v < total) {
-          while (v >= s_pref[e + 1]) ++e;
-          const long long p = s_r0[e] + (v - s_pref[e]);
-          pk[j] = d.packed[p]; aq[j] = d.a_q[p]; bs[j] = s_base[e];
+        bs[j] = -1; pk[j] = 0; aq[j] = 0;
+        if (e0 + j < nspk && q < s_len[e0 + j]) {
+          const long long p = s_r0[e0 + j] + q;
+          pk[j] = d.packed[p]; aq[j] = d.a_q[p]; bs[j] = s_base[e0 + j];
         }
       }
 #pragma unroll
@@ -581,23 +589,19 @@ __global__ __launch_bounds__(kBlock) void k_step_ring(Dev d, long long n,
         if (bs[j] >= 0) {
           int slot = m + (int)(pk[j] & d.dmask); if (slot >= d.R) slot -= d.R;
           atomicAdd(&d.ring[(size_t)slot * d.BN + (size_t)bs[j] + (pk[j] >> d.dbits)], aq[j]);
-          s_off += aq[j];
+          c_off += 1; s_off += aq[j];
         }
       }
     }
-    s_off = wave_sum(s_off);
-    if ((threadIdx.x & 63) == 0) s_red[1][threadIdx.x >> 6] = s_off;
   }
+  c_off = wave_sum(c_off); s_off = wave_sum(s_off);
+  if ((threadIdx.x & 63) == 0) { s_red[0][threadIdx.x >> 6] = c_off; s_red[1][threadIdx.x >> 6] = s_off; }
   __syncthreads();
-  // block totals -> this block's private counters (plain read-modify-write by one thread)
   if (threadIdx.x == 0) {
-    long long sp = 0, so = 0;
-    for (int w = 0; w < kBlock / 64; ++w) { sp += s_red[0][w]; if (nspk) so += s_red[1][w]; }
-    if (nspk | (sp != 0)) {
-      BlkCtr& bc = d.blk[blockIdx.x];
-      if (nspk) { bc.offered += (unsigned long long)total; bc.sum_offered += so; bc.spikes += (unsigned long long)nspk; }
-      if (sp) bc.sum_delivered += sp;
-    }
+    long long a = 0, b = 0;
+    for (int w = 0; w < kBlock / 64; ++w) { a += s_red[0][w]; b += s_red[1][w]; }
+    BlkCtr& bc = d.blk[d.nblk + blockIdx.x];
+    bc.offered += (unsigned long long)a; bc.sum_offered += b;
   }
 }
 
@@ -628,57 +632,52 @@ __global__ __launch_bounds__(kBlock) void k_ring_in_flight(Dev d, long long n_en
   block_add2(&out[0], cnt, (long long*)&out[1], sum);
 }
 
-// One launch per reverse step for the ring: the block re-derives its spikes from the membrane
-// tape (s = U >= theta), gathers the queue term of each of them over the CSR row, accumulates the
-// row's weight and delay gradients, and then updates the adjoint of its 256 neurons.
+// Queue term of the reverse sweep for the ring, kSplit blocks per neuron block: block (b, c)
+// re-derives b's spikes at step n from the membrane tape (s = U >= theta), gathers the adjoint at
+// the arrival slot of chunk c of each spike's row, accumulates the row's weight and delay
+// gradients, and leaves its partial queue term in g_part[c][neuron].
 template <bool ATOMIC>
-__global__ __launch_bounds__(kBlock) void k_bwd_step_ring(Dev d, long long n, long long T, float dscale,
-                                                          const float* __restrict__ dL_dcount,
-                                                          const float* __restrict__ dL_dU,
-                                                          float* __restrict__ grad_w,
-                                                          float* __restrict__ grad_d) {
+__global__ __launch_bounds__(kBlock) void k_bwd_gather_ring(Dev d, long long n, long long T, float dscale,
+                                                            float* __restrict__ grad_w,
+                                                            float* __restrict__ grad_d) {
   __shared__ int s_spk[kBlock];
   __shared__ int s_wcnt[kBlock / 64];
   __shared__ long long s_r0[kBlock];
   __shared__ int s_len[kBlock];
   __shared__ int s_base[kBlock];
-  __shared__ int s_pref[kBlock + 1];
   __shared__ float s_G[kBlock];
-  const int g = blockIdx.x * kBlock + threadIdx.x;
-  const bool act = g < d.BN;
+  const int nb = blockIdx.x / kSplit, c = blockIdx.x % kSplit;
+  const int g = nb * kBlock + threadIdx.x;
   const int m = (int)(n % d.R);
-  float U = 0.0f;
   bool s = false;
-  long long r0 = 0, r1 = 0;
-  int bbase = 0;
-  if (act) {
-    const int b = g / d.N, i = g - b * d.N;
-    bbase = b * d.N;
-    r0 = d.row_ptr[i]; r1 = d.row_ptr[i + 1];
-    U = d.tapeU[(size_t)n * d.BN + g];
-    s = U >= d.theta;
-  }
+  if (g < d.BN) s = d.tapeU[(size_t)n * d.BN + g] >= d.theta;
+  if (!__syncthreads_or(s ? 1 : 0)) return;
   int pos;
   const int nspk = block_compact(s, s_spk, s_wcnt, &pos);
-  if (nspk) {
-    if (s) { s_r0[pos] = r0; s_len[pos] = (int)(r1 - r0); s_base[pos] = bbase; s_G[pos] = 0.0f; }
-    __syncthreads();
-    block_prefix(s_len, s_pref, nspk);
-    const int total = s_pref[nspk];
-    int e = 0;
-    for (int v0 = threadIdx.x; v0 < total; v0 += kBlock * kBatch) {
-      unsigned pk[kBatch]; float am[kBatch]; float fd[kBatch]; int bs[kBatch]; int ee[kBatch];
-      long long pp[kBatch];
+  if (s) {
+    const int b = g / d.N, i = g - b * d.N;
+    const long long r0 = d.row_ptr[i];
+    s_r0[pos] = r0; s_len[pos] = (int)(d.row_ptr[i + 1] - r0); s_base[pos] = b * d.N; s_G[pos] = 0.0f;
+  }
+  __syncthreads();
+  for (int e0 = 0; e0 < nspk; e0 += kBatch) {
+    int maxlen = 0;
+#pragma unroll
+    for (int j = 0; j < kBatch; ++j)
+      if (e0 + j < nspk) { const int l = s_len[e0 + j]; maxlen = l > maxlen ? l : maxlen; }
+    float Gacc[kBatch];
+#pragma unroll
+    for (int j = 0; j < kBatch; ++j) Gacc[j] = 0.0f;
+    for (int q = c * kBlock + threadIdx.x; q < maxlen; q += kSplit * kBlock) {
+      unsigned pk[kBatch]; float am[kBatch]; float fd[kBatch]; int bs[kBatch]; long long pp[kBatch];
 #pragma unroll
       for (int j = 0; j < kBatch; ++j) {
-        const int v = v0 + j * kBlock;
-        pk[j] = 0; am[j] = 0.0f; fd[j] = 1.0f; bs[j] = -1; ee[j] = 0; pp[j] = 0;
-        if (v < total) {
-          while (v >= s_pref[e + 1]) ++e;
-          const long long p = s_r0[e] + (v - s_pref[e]);
+        bs[j] = -1; pk[j] = 0; am[j] = 0.0f; fd[j] = 1.0f; pp[j] = 0;
+        if (e0 + j < nspk && q < s_len[e0 + j]) {
+          const long long p = s_r0[e0 + j] + q;
           pk[j] = d.packed[p];
           if (d.continuous) { am[j] = d.amp[p]; fd[j] = d.fdec[p]; } else { am[j] = d.weight[p]; }
-          bs[j] = s_base[e]; ee[j] = e; pp[j] = p;
+          bs[j] = s_base[e0 + j]; pp[j] = p;
         }
       }
       float gv[kBatch];
@@ -695,38 +694,25 @@ __global__ __launch_bounds__(kBlock) void k_bwd_step_ring(Dev d, long long n, lo
       }
 #pragma unroll
       for (int j = 0; j < kBatch; ++j) {
-        // queue term: one LDS add per wavefront when the whole wavefront serves the same spike
-        const float contrib = bs[j] >= 0 ? am[j] * gv[j] : 0.0f;
-        const int e0 = __shfl(ee[j], 0, 64);
-        if (__all(ee[j] == e0)) {
-          const float t = wave_sum_f(contrib);
-          if ((threadIdx.x & 63) == 0 && t != 0.0f) atomicAdd(&s_G[e0], t);
-        } else if (contrib != 0.0f) {
-          atomicAdd(&s_G[ee[j]], contrib);
-        }
         if (bs[j] >= 0) {
+          Gacc[j] += am[j] * gv[j];
           const float gw = fd[j] * gv[j], gd = am[j] * dscale * gv[j];
           if (ATOMIC) { unsafeAtomicAdd(&grad_w[pp[j]], gw); unsafeAtomicAdd(&grad_d[pp[j]], gd); }
           else { grad_w[pp[j]] += gw; grad_d[pp[j]] += gd; }
         }
       }
     }
-    __syncthreads();
-  }
-  if (act) {
-    float sg = 0.0f;
-    if (d.surrogate == ADSEQ_SURR_SUPERSPIKE) {
-      const float x = fabsf(U - d.theta) + 1.0f;
-      sg = 1.0f / (x * x);
+#pragma unroll
+    for (int j = 0; j < kBatch; ++j) {
+      if (e0 + j < nspk) {  // uniform over the block
+        const float t = wave_sum_f(Gacc[j]);
+        if ((threadIdx.x & 63) == 0 && t != 0.0f) atomicAdd(&s_G[e0 + j], t);
+      }
     }
-    float inner = dL_dcount ? dL_dcount[g] : 0.0f;
-    if (s) inner += s_G[pos];
-    float gu = sg * inner;
-    if (!s) gu = __fmaf_rn(d.alpha, d.bwd_carry[g], gu);
-    if (dL_dU) gu += dL_dU[(size_t)n * d.BN + g];
-    d.bwd_carry[g] = gu;
-    d.bwd_ring[(size_t)m * d.BN + g] = gu;
   }
+  __syncthreads();
+  if ((int)threadIdx.x < nspk)
+    d.bwd_G[(size_t)c * d.BN + (size_t)nb * kBlock + s_spk[threadIdx.x]] = s_G[threadIdx.x];
 }
 
 // ---------------------------------------------------------------- backward
@@ -790,7 +776,13 @@ __global__ __launch_bounds__(kBlock) void k_bwd_neurons(Dev d, long long n,
     sg = 1.0f / (x * x);
   }
   float inner = dL_dcount ? dL_dcount[g] : 0.0f;
-  if (s) inner += d.bwd_G[g];
+  if (s) {
+    if (d.kind == ADSEQ_RING) {
+      for (int c = 0; c < kSplit; ++c) inner += d.bwd_G[(size_t)c * d.BN + g];
+    } else {
+      inner += d.bwd_G[g];
+    }
+  }
   float gu = sg * inner;
   if (!s) gu = __fmaf_rn(d.alpha, d.bwd_carry[g], gu);
   if (dL_dU) gu += dL_dU[(size_t)n * d.BN + g];
@@ -810,6 +802,11 @@ struct adseq {
   long long enq_calls;   // parity source for the pool / spike counters
   bool tape_ok;          // every step since reset went through adseq_step with recording
   char err[256];
+  // optional kernel timing (adseq_profile): one event after each bracketed launch
+  bool prof = false;
+  std::vector<hipEvent_t> evs;
+  std::vector<int> ev_kind;   // kernel class the event closes, -1 = start marker
+  size_t ev_used = 0;
 };
 
 namespace {
@@ -873,7 +870,7 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->nblk = (int)((BN + kBlock - 1) / kBlock);
   L->words = L->nblk * (kBlock / 64);
   L->ctr = take(sizeof(Counters));
-  L->blk = take((size_t)L->nblk * sizeof(BlkCtr));
+  L->blk = take((size_t)L->nblk * (kSplit + 1) * sizeof(BlkCtr));  // neuron blocks + kSplit fan-out blocks each
   L->V = take(BN * 4);
   L->ring = take(bounded ? 0 : (size_t)L->R * BN * 4);
   L->spike_bits = take(bounded ? 0 : (size_t)L->R * L->words * 8);
@@ -901,7 +898,7 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->tape_adm = take((size_t)L->event_cap);
   L->bwd_ring = take(c->record_tape ? (size_t)L->R * BN * 4 : 0);
   L->bwd_carry = take(c->record_tape ? BN * 4 : 0);
-  L->bwd_G = take(c->record_tape ? BN * 4 : 0);
+  L->bwd_G = take(c->record_tape ? BN * 4 * kSplit : 0);  // kSplit partial queue terms per neuron
   L->total = o;
   return true;
 }
@@ -939,7 +936,7 @@ void launch_reset(adseq* h, hipStream_t st) {
   const Dev& d = h->dev;
   const size_t BN = (size_t)d.BN;
   fill_u32(st, d.ctr, 0u, sizeof(Counters) / 4);
-  fill_u32(st, d.blk, 0u, (size_t)d.nblk * sizeof(BlkCtr) / 4);
+  fill_u32(st, d.blk, 0u, (size_t)d.nblk * (kSplit + 1) * sizeof(BlkCtr) / 4);
   fill_u32(st, d.V, 0u, BN);
   if (d.kind == ADSEQ_RING) {
     fill_u32(st, d.ring, 0u, (size_t)d.R * BN);
@@ -992,6 +989,19 @@ void launch_fanout(adseq* h, hipStream_t st, long long n, const int* spk, const 
   }
 }
 
+// Records an event that closes a launch of class `kind` (and opens the next one).
+void mark(adseq* h, hipStream_t st, int kind) {
+  if (!h->prof) return;
+  if (h->ev_used == h->evs.size()) {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return;
+    h->evs.push_back(e); h->ev_kind.push_back(kind);
+  }
+  h->ev_kind[h->ev_used] = kind;
+  (void)hipEventRecord(h->evs[h->ev_used], st);
+  h->ev_used += 1;
+}
+
 int step_impl(adseq* h, long long step, const float* i_ext, unsigned char* spikes_out, hipStream_t st) {
   if (step != h->next_step)
     return fail(h, ADSEQ_E_ORDER, "adseq_step: got step %lld, expected %lld", step, h->next_step);
@@ -1000,11 +1010,18 @@ int step_impl(adseq* h, long long step, const float* i_ext, unsigned char* spike
   const int record = (d.record && h->tape_ok && step < d.max_steps) ? 1 : 0;
   if (d.record && step >= d.max_steps) h->tape_ok = false;
   if (d.kind == ADSEQ_RING) {
-    if (record) hipLaunchKernelGGL((k_step_ring<true>), dim3(d.nblk), dim3(kBlock), 0, st, d, step, i_ext, spikes_out);
-    else hipLaunchKernelGGL((k_step_ring<false>), dim3(d.nblk), dim3(kBlock), 0, st, d, step, i_ext, spikes_out);
+    mark(h, st, -1);
+    if (record) hipLaunchKernelGGL((k_lif_ring<true>), dim3(d.nblk), dim3(kBlock), 0, st, d, step, i_ext, spikes_out);
+    else hipLaunchKernelGGL((k_lif_ring<false>), dim3(d.nblk), dim3(kBlock), 0, st, d, step, i_ext, spikes_out);
+    mark(h, st, 1);
+    hipLaunchKernelGGL(k_fan_ring, dim3(d.nblk * kSplit), dim3(kBlock), 0, st, d, step);
+    mark(h, st, 0);
   } else {
+    mark(h, st, -1);
     launch_neurons<true>(h, st, step, parity, i_ext, spikes_out, nullptr);
+    mark(h, st, 1);
     launch_fanout(h, st, step, d.cur_spk, &d.ctr->n_spk[parity], parity, record);
+    mark(h, st, 0);
   }
   h->enq_calls += 1;
   h->next_step = step + 1;
@@ -1102,6 +1119,7 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
 
 int adseq_destroy(adseq_t* h) {
   if (!h) return ADSEQ_E_INVALID_ARG;
+  for (hipEvent_t e : h->evs) (void)hipEventDestroy(e);
   delete h;
   return ADSEQ_OK;
 }
@@ -1177,10 +1195,14 @@ int adseq_backward(adseq_t* h, const float* dL_dcount, const float* dL_dU, float
   const float dscale = d.continuous ? (float)(1.0 / (double)d.tau) : (float)((double)d.dt / (double)d.tau);
   const dim3 block(kBlock), gn(grid_for((size_t)d.BN)), gg(kFanoutBlocks);
   const bool bounded = d.kind != ADSEQ_RING, atomic = d.B > 1;
+  mark(h, st, -1);
   for (long long n = T - 1; n >= 0; --n) {
     if (!bounded) {
-      if (atomic) hipLaunchKernelGGL((k_bwd_step_ring<true>), dim3(d.nblk), block, 0, st, d, n, T, dscale, dL_dcount, dL_dU, grad_w, grad_d);
-      else hipLaunchKernelGGL((k_bwd_step_ring<false>), dim3(d.nblk), block, 0, st, d, n, T, dscale, dL_dcount, dL_dU, grad_w, grad_d);
+      if (atomic) hipLaunchKernelGGL((k_bwd_gather_ring<true>), dim3(d.nblk * kSplit), block, 0, st, d, n, T, dscale, grad_w, grad_d);
+      else hipLaunchKernelGGL((k_bwd_gather_ring<false>), dim3(d.nblk * kSplit), block, 0, st, d, n, T, dscale, grad_w, grad_d);
+      mark(h, st, 2);
+      hipLaunchKernelGGL(k_bwd_neurons, gn, block, 0, st, d, n, dL_dcount, dL_dU);
+      mark(h, st, 3);
       continue;
     }
     if (bounded) {
@@ -1190,7 +1212,9 @@ int adseq_backward(adseq_t* h, const float* dL_dcount, const float* dL_dU, float
       if (atomic) hipLaunchKernelGGL((k_bwd_gather<false, true>), gg, block, 0, st, d, n, T, dscale, grad_w, grad_d);
       else hipLaunchKernelGGL((k_bwd_gather<false, false>), gg, block, 0, st, d, n, T, dscale, grad_w, grad_d);
     }
+    mark(h, st, 2);
     hipLaunchKernelGGL(k_bwd_neurons, gn, block, 0, st, d, n, dL_dcount, dL_dU);
+    mark(h, st, 3);
   }
   HIP_TRY(h, hipGetLastError());
   return ADSEQ_OK;
@@ -1216,7 +1240,7 @@ int adseq_counters(adseq_t* h, int64_t* out8, void* stream) {
   out8[6] = c.tape_spikes; out8[7] = (int64_t)c.err;
   if (d.kind == ADSEQ_RING) {
     // the fused step kernel keeps private counters per block: add them up here
-    const int nb = d.nblk;
+    const int nb = d.nblk * (kSplit + 1);
     BlkCtr* hb = new (std::nothrow) BlkCtr[nb];
     if (!hb) return fail(h, ADSEQ_E_INVALID_ARG, "adseq_counters: out of host memory");
     hipError_t e = hipMemcpyAsync(hb, d.blk, sizeof(BlkCtr) * nb, hipMemcpyDeviceToHost, st);
@@ -1257,6 +1281,28 @@ int adseq_tape(const adseq_t* h, adseq_tape_view* out) {
   out->event_base = d.kind != ADSEQ_RING ? (const int64_t*)d.tape_evb : nullptr;
   out->admitted = d.kind != ADSEQ_RING ? d.tape_adm : nullptr;
   out->steps_recorded = h->tape_ok ? (h->next_step < d.max_steps ? h->next_step : d.max_steps) : 0;
+  return ADSEQ_OK;
+}
+
+int adseq_profile(adseq_t* h, int enable) {
+  if (!h) return ADSEQ_E_INVALID_ARG;
+  h->prof = enable != 0;
+  h->ev_used = 0;
+  return ADSEQ_OK;
+}
+
+int adseq_profile_read(adseq_t* h, double* ms4, int64_t* launches4, void* stream) {
+  if (!h || !ms4 || !launches4) return ADSEQ_E_INVALID_ARG;
+  HIP_TRY(h, hipStreamSynchronize((hipStream_t)stream));
+  for (int k = 0; k < 4; ++k) { ms4[k] = 0.0; launches4[k] = 0; }
+  for (size_t i = 1; i < h->ev_used; ++i) {
+    const int k = h->ev_kind[i];
+    if (k < 0 || k > 3) continue;
+    float ms = 0.0f;
+    if (hipEventElapsedTime(&ms, h->evs[i - 1], h->evs[i]) != hipSuccess) continue;
+    ms4[k] += (double)ms; launches4[k] += 1;
+  }
+  h->ev_used = 0;
   return ADSEQ_OK;
 }
 
