@@ -118,10 +118,19 @@ def main():
         "bwd_gather": BWD_B_EVENT * in_run,
         "bwd_neurons": BWD_B_NEURON * BN * T,
     }
+    if args.queue == "ring":
+        # the ring runs ONE kernel per time step in each direction: neuron update and
+        # fan-out (or gather) are two block roles of the same launch
+        alg = {"fan_out": alg["fan_out"] + alg["lif"], "bwd_gather": alg["bwd_gather"] + alg["bwd_neurons"]}
+        label = {"fan_out": "k_step_ring (pop + LIF | fan-out + enqueue)",
+                 "bwd_gather": "k_bwd_step_ring (adjoint update | gather + gradients)"}
+    else:
+        label = {"fan_out": "k_fanout + k_admit", "lif": "k_neurons (pop + LIF + compaction)",
+                 "bwd_gather": "k_bwd_gather", "bwd_neurons": "k_bwd_neurons"}
     kernels = {}
     for k, v in prof.items():
         if v["launches"]:
-            kernels[k] = {"ms_per_run": v["ms"], "launches": v["launches"],
+            kernels[k] = {"kernel": label[k], "ms_per_run": v["ms"], "launches": v["launches"],
                           "avg_us": v["ms"] * 1e3 / v["launches"],
                           "algorithmic_bytes_per_launch": alg[k] / v["launches"],
                           "achieved_GBs": alg[k] / (v["ms"] * 1e-3) / 1e9}
@@ -157,7 +166,7 @@ def main():
         "drop_rate": dropped / max(1, offered),
         "roofline": {"bound": "hbm", "achieved": kernels[dom]["achieved_GBs"], "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": kernels[dom]["achieved_GBs"] / HBM_PEAK_GBS,
-                     "traffic": traffic, "kernel": dom,
+                     "traffic": traffic, "kernel": label[dom],
                      "avg_launch_us": kernels[dom]["avg_us"],
                      "algorithmic_bytes_per_launch": kernels[dom]["algorithmic_bytes_per_launch"],
                      "whole_run_achieved_GBs": achieved_run,

@@ -69,6 +69,8 @@ struct Dev {
   const float* delay_ms;
   unsigned* packed;
   int* a_q;
+  long long* d1_ptr;   // RING: [N+1] per-row ranges into d1_off
+  unsigned* d1_off;    // RING: positions (within the row) of the entries with arrival offset 1
   float* amp;
   float* fdec;
   float* V;
@@ -199,6 +201,50 @@ __global__ __launch_bounds__(kBlock) void k_prepare(Dev d, ExpCoef ec) {
     if (i == 0 && a != 0) bad = true;
     if (i == d.N - 1 && b != d.S) bad = true;
     if (bad) atomicOr(&d.ctr->err, ERR_GRAPH);
+  }
+}
+
+// Per-row lists of the entries with arrival offset 1 (RING).  One wavefront per row.
+// pass 0: d1_ptr[i + 1] = count; (then k_scan_rows turns counts into offsets;) pass 1: fill d1_off.
+__global__ __launch_bounds__(kBlock) void k_d1_lists(Dev d, int pass) {
+  const int lane = threadIdx.x & 63;
+  const long long wave = ((long long)blockIdx.x * kBlock + threadIdx.x) >> 6;
+  const long long nwaves = ((long long)gridDim.x * kBlock) >> 6;
+  for (long long i = wave; i < d.N; i += nwaves) {
+    const long long r0 = d.row_ptr[i], r1 = d.row_ptr[i + 1];
+    long long base = pass ? d.d1_ptr[i] : 0;
+    int total = 0;
+    for (long long q0 = r0; q0 < r1; q0 += 64) {
+      const long long p = q0 + lane;
+      const bool hit = p < r1 && (d.packed[p] & d.dmask) == 1u;
+      const unsigned long long mk = __ballot(hit);
+      if (pass && hit) d.d1_off[base + total + __popcll(mk & ((1ull << lane) - 1ull))] = (unsigned)(p - r0);
+      total += __popcll(mk);
+    }
+    if (!pass && lane == 0) d.d1_ptr[i + 1] = total;
+  }
+  if (!pass && blockIdx.x == 0 && threadIdx.x == 0) d.d1_ptr[0] = 0;
+}
+
+// In-place inclusive scan of ptr[1..n] (single block; create-time only).
+__global__ __launch_bounds__(1024) void k_scan_rows(long long* ptr, long long n) {
+  __shared__ long long s_w[16];
+  __shared__ long long s_carry;
+  if (threadIdx.x == 0) s_carry = 0;
+  __syncthreads();
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  for (long long base = 1; base <= n; base += 1024) {
+    const long long idx = base + threadIdx.x;
+    long long v = idx <= n ? ptr[idx] : 0;
+    for (int o = 1; o < 64; o <<= 1) { const long long t = __shfl_up(v, o, 64); if (lane >= o) v += t; }
+    if (lane == 63) s_w[w] = v;
+    __syncthreads();
+    long long add = s_carry;
+    for (int x = 0; x < w; ++x) add += s_w[x];
+    if (idx <= n) ptr[idx] = v + add;
+    __syncthreads();
+    if (threadIdx.x == 1023) s_carry = v + add;
+    __syncthreads();
   }
 }
 
@@ -472,13 +518,13 @@ __device__ __forceinline__ int block_compact(bool flag, int* s_list, int* s_wcnt
 
 // ---------------------------------------------------------------- closed-loop step (RING)
 //
-// Two launches per time step, neither with an atomic on a shared counter:
-//   k_lif_ring   block b owns neurons [256 b, 256 b + 256): pops their ring slots, integrates,
-//                records the membrane value, publishes the spike bits of its four wavefronts;
-//   k_fan_ring   kSplit blocks per neuron block: block (b, c) re-derives b's spikes from the spike
-//                bits and scatters chunk c (256 entries out of every kSplit * 256) of each spike's CSR
-//                row, so that one neuron block's spikes are spread over kSplit compute units and the
-//                row reads of all its spikes are in flight together.
+// One launch per time step, without an atomic on any shared counter, made of two kinds of blocks:
+//   ring_lif   block b owns neurons [256 b, 256 b + 256): pops their ring slots, integrates,
+//              records the membrane value, publishes the spike bits of its four wavefronts;
+//   ring_fan   kSplit blocks per neuron block: block (b, c) re-derives b's spikes from the spike
+//              bits and scatters chunk c (256 entries out of every kSplit * 256) of each spike's CSR
+//              row, so that one neuron block's spikes are spread over kSplit compute units and the
+//              row reads of all its spikes are in flight together.
 // The ring is d_max + 1 deep, hence the row popped at step n is never a target of the events
 // emitted at step n (arrival offsets are 1..d_max).
 
@@ -488,12 +534,15 @@ __device__ __forceinline__ int block_compact(bool flag, int* s_list, int* s_wcnt
 constexpr int kSplit = ADSEQ_KSPLIT;  // fan-out blocks per neuron block
 constexpr int kBatch = 8;  // spikes whose row entries a thread keeps in flight together
 
+// Neuron part of a ring step for neuron block `nb`: pop, drive, LIF, tape, spike words; plus the
+// scatter of the block's own events with arrival offset 1 (taken from the per-row lists built at
+// create), which are the only ones the next step's pop depends on.
 template <bool RECORD>
-__global__ __launch_bounds__(kBlock) void k_lif_ring(Dev d, long long n,
-                                                     const float* __restrict__ i_ext,
-                                                     unsigned char* __restrict__ spikes_out) {
-  __shared__ long long s_red[kBlock / 64];
-  const int g = blockIdx.x * kBlock + threadIdx.x;
+__device__ __forceinline__ void ring_lif(const Dev& d, long long n, int nb,
+                                         const float* __restrict__ i_ext,
+                                         unsigned char* __restrict__ spikes_out) {
+  __shared__ long long s_red[3][kBlock / 64];
+  const int g = nb * kBlock + threadIdx.x;
   const bool act = g < d.BN;
   const int m = (int)(n % d.R);
   int acc = 0;
@@ -515,24 +564,44 @@ __global__ __launch_bounds__(kBlock) void k_lif_ring(Dev d, long long n,
     if (RECORD) d.tapeU[(size_t)n * d.BN + g] = U;
     if (spikes_out) spikes_out[g] = s ? 1 : 0;
   }
-  // spike bits of this step: read by k_fan_ring, and kept for d_max + 1 steps so that the events
-  // still in flight can be counted on demand (adseq_counters) instead of on the hot path
+  // spike bits of this step: read by the fan-out blocks of the next launch, and kept for
+  // d_max + 1 steps so that the events still in flight can be counted on demand
   const unsigned long long bits = __ballot(s);
   if ((threadIdx.x & 63) == 0)
-    d.spike_bits[(size_t)m * d.words + (size_t)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6)] = bits;
+    d.spike_bits[(size_t)m * d.words + (size_t)nb * (kBlock / 64) + (threadIdx.x >> 6)] = bits;
+  long long c1 = 0, s1 = 0;
+  if (s) {
+    const int b = g / d.N, i = g - b * d.N;
+    const long long q0 = d.d1_ptr[i], q1 = d.d1_ptr[i + 1];
+    if (q1 > q0) {
+      const long long r0 = d.row_ptr[i];
+      int slot = m + 1; if (slot >= d.R) slot -= d.R;
+      int* __restrict__ dst = d.ring + (size_t)slot * d.BN + (size_t)b * d.N;
+      for (long long q = q0; q < q1; ++q) {
+        const long long p = r0 + d.d1_off[q];
+        const int a = d.a_q[p];
+        atomicAdd(&dst[d.packed[p] >> d.dbits], a);
+        c1 += 1; s1 += a;
+      }
+    }
+  }
   const long long sp = wave_sum((long long)acc);
   const long long ns = wave_sum((long long)(s ? 1 : 0));
-  if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = sp;
-  __shared__ long long s_ns[kBlock / 64];
-  if ((threadIdx.x & 63) == 0) s_ns[threadIdx.x >> 6] = ns;
+  c1 = wave_sum(c1); s1 = wave_sum(s1);
+  __shared__ long long s_c1[kBlock / 64];
+  if ((threadIdx.x & 63) == 0) {
+    const int w = threadIdx.x >> 6;
+    s_red[0][w] = sp; s_red[1][w] = ns; s_red[2][w] = s1; s_c1[w] = c1;
+  }
   __syncthreads();
   if (threadIdx.x == 0) {
-    long long a = 0, c = 0;
-    for (int w = 0; w < kBlock / 64; ++w) { a += s_red[w]; c += s_ns[w]; }
-    if (a | c) {
-      BlkCtr& bc = d.blk[blockIdx.x];
-      bc.sum_delivered += a; bc.spikes += (unsigned long long)c;
-    }
+    long long a = 0, c = 0, so = 0, co = 0;
+    for (int w = 0; w < kBlock / 64; ++w) { a += s_red[0][w]; c += s_red[1][w]; so += s_red[2][w]; co += s_c1[w]; }
+    // private counters of this block; atomics only so that nothing waits for a read
+    BlkCtr& bc = d.blk[nb];
+    if (a) atomicAdd((unsigned long long*)&bc.sum_delivered, (unsigned long long)a);
+    if (c) atomicAdd(&bc.spikes, (unsigned long long)c);
+    if (co) { atomicAdd(&bc.offered, (unsigned long long)co); atomicAdd((unsigned long long*)&bc.sum_offered, (unsigned long long)so); }
   }
 }
 
@@ -559,12 +628,15 @@ __device__ __forceinline__ int block_spikes_from_bits(const Dev& d, int m, int n
   return __popcll(w0) + __popcll(w1) + __popcll(w2) + __popcll(w3);
 }
 
-__global__ __launch_bounds__(kBlock) void k_fan_ring(Dev d, long long n) {
+// Fan-out part of a ring step: fan block `fb` = (neuron block fb / kSplit, chunk fb % kSplit)
+// scatters its chunk of the rows of that neuron block's spikes at step n, except the entries with
+// arrival offset 1 (already scattered by ring_lif in the launch that detected the spikes).
+__device__ __forceinline__ void ring_fan(const Dev& d, long long n, int fb) {
   __shared__ long long s_r0[kBlock];
   __shared__ int s_len[kBlock];
   __shared__ int s_base[kBlock];
   __shared__ long long s_red[2][kBlock / 64];
-  const int nb = blockIdx.x / kSplit, c = blockIdx.x % kSplit;
+  const int nb = fb / kSplit, c = fb % kSplit;
   const int m = (int)(n % d.R);
   const int nspk = block_spikes_from_bits(d, m, nb, s_r0, s_len, s_base);
   if (nspk == 0) return;
@@ -586,8 +658,9 @@ __global__ __launch_bounds__(kBlock) void k_fan_ring(Dev d, long long n) {
       }
 #pragma unroll
       for (int j = 0; j < kBatch; ++j) {
-        if (bs[j] >= 0) {
-          int slot = m + (int)(pk[j] & d.dmask); if (slot >= d.R) slot -= d.R;
+        const int D = (int)(pk[j] & d.dmask);
+        if (bs[j] >= 0 && D != 1) {
+          int slot = m + D; if (slot >= d.R) slot -= d.R;
           atomicAdd(&d.ring[(size_t)slot * d.BN + (size_t)bs[j] + (pk[j] >> d.dbits)], aq[j]);
           c_off += 1; s_off += aq[j];
         }
@@ -600,9 +673,24 @@ __global__ __launch_bounds__(kBlock) void k_fan_ring(Dev d, long long n) {
   if (threadIdx.x == 0) {
     long long a = 0, b = 0;
     for (int w = 0; w < kBlock / 64; ++w) { a += s_red[0][w]; b += s_red[1][w]; }
-    BlkCtr& bc = d.blk[d.nblk + blockIdx.x];
-    bc.offered += (unsigned long long)a; bc.sum_offered += b;
+    BlkCtr& bc = d.blk[d.nblk + fb];
+    if (a) { atomicAdd(&bc.offered, (unsigned long long)a); atomicAdd((unsigned long long*)&bc.sum_offered, (unsigned long long)b); }
   }
+}
+
+// One launch per time step for the ring.  The first nblk blocks (when n_lif >= 0) integrate step
+// n_lif; the other nblk * kSplit blocks (when n_fan >= 0) fan out the spikes of step n_fan =
+// n_lif - 1 with arrival offsets >= 2.  The two halves are independent: the pop of step n only
+// needs offset-1 events of step n - 1 (scattered by ring_lif itself, one launch earlier) and
+// events of older steps (complete), and with a ring d_max + 1 deep no fan-out event of step n - 1
+// with offset >= 2 lands in the row being popped.  So the neuron update hides behind the scatter.
+template <bool RECORD>
+__global__ __launch_bounds__(kBlock) void k_step_ring(Dev d, long long n_lif, long long n_fan,
+                                                      const float* __restrict__ i_ext,
+                                                      unsigned char* __restrict__ spikes_out) {
+  const int lif_blocks = n_lif >= 0 ? d.nblk : 0;
+  if ((int)blockIdx.x < lif_blocks) ring_lif<RECORD>(d, n_lif, (int)blockIdx.x, i_ext, spikes_out);
+  else ring_fan(d, n_fan, (int)blockIdx.x - lif_blocks);
 }
 
 // Events of the ring that are still in flight at step n_end (arrival >= n_end): counted from the
@@ -632,21 +720,20 @@ __global__ __launch_bounds__(kBlock) void k_ring_in_flight(Dev d, long long n_en
   block_add2(&out[0], cnt, (long long*)&out[1], sum);
 }
 
-// Queue term of the reverse sweep for the ring, kSplit blocks per neuron block: block (b, c)
-// re-derives b's spikes at step n from the membrane tape (s = U >= theta), gathers the adjoint at
-// the arrival slot of chunk c of each spike's row, accumulates the row's weight and delay
-// gradients, and leaves its partial queue term in g_part[c][neuron].
+// Queue term of the reverse sweep for the ring, kSplit blocks per neuron block: gather block
+// (b, c) re-derives b's spikes at step n from the membrane tape (s = U >= theta), gathers the
+// adjoint at the arrival slot of chunk c of each spike's row (arrival offsets >= 2), accumulates the
+// row's weight and delay gradients, and leaves its partial queue term in g_part[n & 1][c][neuron].
 template <bool ATOMIC>
-__global__ __launch_bounds__(kBlock) void k_bwd_gather_ring(Dev d, long long n, long long T, float dscale,
-                                                            float* __restrict__ grad_w,
-                                                            float* __restrict__ grad_d) {
+__device__ __forceinline__ void ring_bwd_gather(const Dev& d, long long n, long long T, float dscale, int fb,
+                                                float* __restrict__ grad_w, float* __restrict__ grad_d) {
   __shared__ int s_spk[kBlock];
   __shared__ int s_wcnt[kBlock / 64];
   __shared__ long long s_r0[kBlock];
   __shared__ int s_len[kBlock];
   __shared__ int s_base[kBlock];
   __shared__ float s_G[kBlock];
-  const int nb = blockIdx.x / kSplit, c = blockIdx.x % kSplit;
+  const int nb = fb / kSplit, c = fb % kSplit;
   const int g = nb * kBlock + threadIdx.x;
   const int m = (int)(n % d.R);
   bool s = false;
@@ -685,7 +772,7 @@ __global__ __launch_bounds__(kBlock) void k_bwd_gather_ring(Dev d, long long n, 
       for (int j = 0; j < kBatch; ++j) {
         gv[j] = 0.0f;
         const int D = (int)(pk[j] & d.dmask);
-        if (bs[j] >= 0 && n + D < T) {  // else: not delivered inside the run
+        if (bs[j] >= 0 && D != 1 && n + D < T) {  // offset 1: ring_bwd_neurons; n + D >= T: never delivered
           int slot = m + D; if (slot >= d.R) slot -= d.R;
           gv[j] = d.bwd_ring[(size_t)slot * d.BN + (size_t)bs[j] + (pk[j] >> d.dbits)];
         } else {
@@ -712,7 +799,74 @@ __global__ __launch_bounds__(kBlock) void k_bwd_gather_ring(Dev d, long long n, 
   }
   __syncthreads();
   if ((int)threadIdx.x < nspk)
-    d.bwd_G[(size_t)c * d.BN + (size_t)nb * kBlock + s_spk[threadIdx.x]] = s_G[threadIdx.x];
+    d.bwd_G[((size_t)(n & 1) * kSplit + c) * d.BN + (size_t)nb * kBlock + s_spk[threadIdx.x]] = s_G[threadIdx.x];
+}
+
+// Neuron part of the reverse sweep for the ring at step n: adds the offset-1 events of its own
+// spikes (they need gU[n + 1], written one launch earlier) to the kSplit partial queue terms, then
+//   gU[n] = (1 - s) alpha gU[n+1] + sigma'(U - theta) (dL/dcount + s G) + dL/dU[n]
+template <bool ATOMIC>
+__device__ __forceinline__ void ring_bwd_neurons(const Dev& d, long long n, long long T, float dscale, int nb,
+                                                 const float* __restrict__ dL_dcount,
+                                                 const float* __restrict__ dL_dU,
+                                                 float* __restrict__ grad_w, float* __restrict__ grad_d) {
+  const int g = nb * kBlock + threadIdx.x;
+  if (g >= d.BN) return;
+  const int m = (int)(n % d.R);
+  const float U = d.tapeU[(size_t)n * d.BN + g];
+  const bool s = U >= d.theta;
+  float sg = 0.0f;
+  if (d.surrogate == ADSEQ_SURR_SUPERSPIKE) {
+    const float x = fabsf(U - d.theta) + 1.0f;
+    sg = 1.0f / (x * x);
+  }
+  float inner = dL_dcount ? dL_dcount[g] : 0.0f;
+  if (s) {
+    float G = 0.0f;
+    for (int c = 0; c < kSplit; ++c) G += d.bwd_G[((size_t)(n & 1) * kSplit + c) * d.BN + g];
+    if (n + 1 < T) {
+      const int b = g / d.N, i = g - b * d.N;
+      const long long q0 = d.d1_ptr[i], q1 = d.d1_ptr[i + 1];
+      if (q1 > q0) {
+        const long long r0 = d.row_ptr[i];
+        int slot = m + 1; if (slot >= d.R) slot -= d.R;
+        const float* __restrict__ src = d.bwd_ring + (size_t)slot * d.BN + (size_t)b * d.N;
+        for (long long q = q0; q < q1; ++q) {
+          const long long p = r0 + d.d1_off[q];
+          const float gv = src[d.packed[p] >> d.dbits];
+          const float a = d.continuous ? d.amp[p] : d.weight[p];
+          const float f = d.continuous ? d.fdec[p] : 1.0f;
+          G += a * gv;
+          const float gw = f * gv, gd = a * dscale * gv;
+          if (ATOMIC) { unsafeAtomicAdd(&grad_w[p], gw); unsafeAtomicAdd(&grad_d[p], gd); }
+          else { grad_w[p] += gw; grad_d[p] += gd; }
+        }
+      }
+    }
+    inner += G;
+  }
+  float gu = sg * inner;
+  if (!s) gu = __fmaf_rn(d.alpha, d.bwd_carry[g], gu);
+  if (dL_dU) gu += dL_dU[(size_t)n * d.BN + g];
+  d.bwd_carry[g] = gu;
+  d.bwd_ring[(size_t)m * d.BN + g] = gu;
+}
+
+// One launch per reverse step for the ring: the first nblk blocks (when n_neu >= 0) update the
+// adjoint of step n_neu; the other nblk * kSplit blocks (when n_gat >= 0) gather the queue terms
+// of step n_gat = n_neu - 1 (offsets >= 2, which only read adjoint rows written by earlier launches).
+template <bool ATOMIC>
+__global__ __launch_bounds__(kBlock) void k_bwd_step_ring(Dev d, long long n_neu, long long n_gat,
+                                                          long long T, float dscale,
+                                                          const float* __restrict__ dL_dcount,
+                                                          const float* __restrict__ dL_dU,
+                                                          float* __restrict__ grad_w,
+                                                          float* __restrict__ grad_d) {
+  const int neu_blocks = n_neu >= 0 ? d.nblk : 0;
+  if ((int)blockIdx.x < neu_blocks)
+    ring_bwd_neurons<ATOMIC>(d, n_neu, T, dscale, (int)blockIdx.x, dL_dcount, dL_dU, grad_w, grad_d);
+  else
+    ring_bwd_gather<ATOMIC>(d, n_gat, T, dscale, (int)blockIdx.x - neu_blocks, grad_w, grad_d);
 }
 
 // ---------------------------------------------------------------- backward
@@ -776,13 +930,7 @@ __global__ __launch_bounds__(kBlock) void k_bwd_neurons(Dev d, long long n,
     sg = 1.0f / (x * x);
   }
   float inner = dL_dcount ? dL_dcount[g] : 0.0f;
-  if (s) {
-    if (d.kind == ADSEQ_RING) {
-      for (int c = 0; c < kSplit; ++c) inner += d.bwd_G[(size_t)c * d.BN + g];
-    } else {
-      inner += d.bwd_G[g];
-    }
-  }
+  if (s) inner += d.bwd_G[g];
   float gu = sg * inner;
   if (!s) gu = __fmaf_rn(d.alpha, d.bwd_carry[g], gu);
   if (dL_dU) gu += dL_dU[(size_t)n * d.BN + g];
@@ -801,6 +949,7 @@ struct adseq {
   long long next_step;   // next step to deliver
   long long enq_calls;   // parity source for the pool / spike counters
   bool tape_ok;          // every step since reset went through adseq_step with recording
+  long long pending_fan; // RING: step whose fan-out (offsets >= 2) rides with the next launch, or -1
   char err[256];
   // optional kernel timing (adseq_profile): one event after each bracketed launch
   bool prof = false;
@@ -813,7 +962,7 @@ namespace {
 
 struct Layout {
   size_t V, ring, spike_bits, slot_k, slot_a, occ, head, c_head, pool_p, pool_t, pool_g, pool_next,
-      pool_k, pool_a, cur_spk, packed, a_q, amp, fdec, tapeU, step_off, tape_spk, tape_evb, tape_adm,
+      pool_k, pool_a, cur_spk, packed, a_q, d1_ptr, d1_off, amp, fdec, tapeU, step_off, tape_spk, tape_evb, tape_adm,
       bwd_ring, bwd_carry, bwd_G, ctr, blk, total;
   long long spike_cap, event_cap, pool_cap;
   int R, dbits, nblk, words;
@@ -888,6 +1037,8 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->cur_spk = take(BN * 4);
   L->packed = take(S * 4);
   L->a_q = take(S * 4);
+  L->d1_ptr = take(bounded ? 0 : ((size_t)c->n_neurons + 1) * 8);
+  L->d1_off = take(bounded ? 0 : S * 4);  // worst case: every entry has offset 1
   L->amp = take(cont ? S * 4 : 0);
   L->fdec = take(cont ? S * 4 : 0);
   const size_t T = c->record_tape ? (size_t)c->max_steps : 0;
@@ -898,7 +1049,7 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->tape_adm = take((size_t)L->event_cap);
   L->bwd_ring = take(c->record_tape ? (size_t)L->R * BN * 4 : 0);
   L->bwd_carry = take(c->record_tape ? BN * 4 : 0);
-  L->bwd_G = take(c->record_tape ? BN * 4 * kSplit : 0);  // kSplit partial queue terms per neuron
+  L->bwd_G = take(c->record_tape ? BN * 4 * kSplit * 2 : 0);  // kSplit partial queue terms per neuron, two step parities
   L->total = o;
   return true;
 }
@@ -949,6 +1100,7 @@ void launch_reset(adseq* h, hipStream_t st) {
   if (d.record) fill_u32(st, d.step_off, 0u, 2);  // step_off[0] = 0 (int64)
   h->next_step = 0;
   h->enq_calls = 0;
+  h->pending_fan = -1;
   h->tape_ok = d.record != 0;
 }
 
@@ -989,6 +1141,28 @@ void launch_fanout(adseq* h, hipStream_t st, long long n, const int* spk, const 
   }
 }
 
+void mark(adseq* h, hipStream_t st, int kind);
+
+// RING: one launch = neuron update of step n_lif (if >= 0) + fan-out of step n_fan (if >= 0).
+void launch_ring_step(adseq* h, hipStream_t st, long long n_lif, long long n_fan, int record,
+                      const float* i_ext, unsigned char* spikes_out) {
+  const Dev& d = h->dev;
+  const unsigned grid = (unsigned)((n_lif >= 0 ? d.nblk : 0) + (n_fan >= 0 ? d.nblk * kSplit : 0));
+  if (!grid) return;
+  mark(h, st, -1);
+  if (record) hipLaunchKernelGGL((k_step_ring<true>), dim3(grid), dim3(kBlock), 0, st, d, n_lif, n_fan, i_ext, spikes_out);
+  else hipLaunchKernelGGL((k_step_ring<false>), dim3(grid), dim3(kBlock), 0, st, d, n_lif, n_fan, i_ext, spikes_out);
+  mark(h, st, 0);
+}
+
+// RING: launches the fan-out that is still riding, so that the queue state is complete.
+void flush_ring(adseq* h, hipStream_t st) {
+  if (h->dev.kind == ADSEQ_RING && h->pending_fan >= 0) {
+    launch_ring_step(h, st, -1, h->pending_fan, 0, nullptr, nullptr);
+    h->pending_fan = -1;
+  }
+}
+
 // Records an event that closes a launch of class `kind` (and opens the next one).
 void mark(adseq* h, hipStream_t st, int kind) {
   if (!h->prof) return;
@@ -1010,12 +1184,8 @@ int step_impl(adseq* h, long long step, const float* i_ext, unsigned char* spike
   const int record = (d.record && h->tape_ok && step < d.max_steps) ? 1 : 0;
   if (d.record && step >= d.max_steps) h->tape_ok = false;
   if (d.kind == ADSEQ_RING) {
-    mark(h, st, -1);
-    if (record) hipLaunchKernelGGL((k_lif_ring<true>), dim3(d.nblk), dim3(kBlock), 0, st, d, step, i_ext, spikes_out);
-    else hipLaunchKernelGGL((k_lif_ring<false>), dim3(d.nblk), dim3(kBlock), 0, st, d, step, i_ext, spikes_out);
-    mark(h, st, 1);
-    hipLaunchKernelGGL(k_fan_ring, dim3(d.nblk * kSplit), dim3(kBlock), 0, st, d, step);
-    mark(h, st, 0);
+    launch_ring_step(h, st, step, h->pending_fan, record, i_ext, spikes_out);
+    h->pending_fan = step;
   } else {
     mark(h, st, -1);
     launch_neurons<true>(h, st, step, parity, i_ext, spikes_out, nullptr);
@@ -1086,6 +1256,7 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   d.pool_k = (unsigned*)(ws + L.pool_k); d.pool_a = (int*)(ws + L.pool_a);
   d.cur_spk = (int*)(ws + L.cur_spk);
   d.packed = (unsigned*)(ws + L.packed); d.a_q = (int*)(ws + L.a_q);
+  d.d1_ptr = (long long*)(ws + L.d1_ptr); d.d1_off = (unsigned*)(ws + L.d1_off);
   d.amp = d.continuous ? (float*)(ws + L.amp) : nullptr;
   d.fdec = d.continuous ? (float*)(ws + L.fdec) : nullptr;
   d.tapeU = (float*)(ws + L.tapeU); d.step_off = (long long*)(ws + L.step_off);
@@ -1105,6 +1276,13 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
     if (g > 8192) g = 8192;
     if (g < 1) g = 1;
     hipLaunchKernelGGL(k_prepare, dim3((unsigned)g), dim3(kBlock), 0, st, d, ec);
+    if (d.kind == ADSEQ_RING) {
+      size_t gw = ((size_t)d.N * 64 + kBlock - 1) / kBlock;
+      if (gw > 16384) gw = 16384;
+      hipLaunchKernelGGL(k_d1_lists, dim3((unsigned)gw), dim3(kBlock), 0, st, d, 0);
+      hipLaunchKernelGGL(k_scan_rows, dim3(1), dim3(1024), 0, st, d.d1_ptr, (long long)d.N);
+      hipLaunchKernelGGL(k_d1_lists, dim3((unsigned)gw), dim3(kBlock), 0, st, d, 1);
+    }
   }
   unsigned err = 0;
   hipError_t e = hipGetLastError();
@@ -1136,6 +1314,7 @@ int adseq_deliver(adseq_t* h, int64_t step, float* I_out, void* stream) {
   if (step != h->next_step)
     return fail(h, ADSEQ_E_ORDER, "adseq_deliver: got step %lld, expected %lld", (long long)step, h->next_step);
   const int parity = (int)(h->enq_calls & 1);
+  flush_ring(h, (hipStream_t)stream);
   launch_neurons<false>(h, (hipStream_t)stream, step, parity, nullptr, nullptr, I_out);
   h->next_step = step + 1;
   h->tape_ok = false;
@@ -1151,6 +1330,7 @@ int adseq_enqueue(adseq_t* h, int64_t step, const int32_t* spike_ids, const int3
     return fail(h, ADSEQ_E_ORDER, "adseq_enqueue: got step %lld, expected %lld (the step last delivered)",
                 (long long)step, h->next_step - 1);
   const int parity = (int)(h->enq_calls & 1);
+  flush_ring(h, (hipStream_t)stream);
   launch_fanout(h, (hipStream_t)stream, step, spike_ids, n_spikes, parity, 0);
   h->enq_calls += 1;
   h->tape_ok = false;
@@ -1170,6 +1350,8 @@ int adseq_run(adseq_t* h, int64_t step0, int64_t n_steps, void* stream) {
     const int rc = step_impl(h, step0 + n, nullptr, nullptr, (hipStream_t)stream);
     if (rc != ADSEQ_OK) return rc;
   }
+  flush_ring(h, (hipStream_t)stream);
+  HIP_TRY(h, hipGetLastError());
   return ADSEQ_OK;
 }
 
@@ -1181,6 +1363,7 @@ int adseq_backward(adseq_t* h, const float* dL_dcount, const float* dL_dU, float
   if (!d.record || !h->tape_ok)
     return fail(h, ADSEQ_E_NO_TAPE, "adseq_backward: no complete recorded forward run");
   hipStream_t st = (hipStream_t)stream;
+  flush_ring(h, st);
   unsigned err = 0;
   HIP_TRY(h, hipMemcpyAsync(&err, &d.ctr->err, sizeof(err), hipMemcpyDeviceToHost, st));
   HIP_TRY(h, hipStreamSynchronize(st));
@@ -1195,16 +1378,22 @@ int adseq_backward(adseq_t* h, const float* dL_dcount, const float* dL_dU, float
   const float dscale = d.continuous ? (float)(1.0 / (double)d.tau) : (float)((double)d.dt / (double)d.tau);
   const dim3 block(kBlock), gn(grid_for((size_t)d.BN)), gg(kFanoutBlocks);
   const bool bounded = d.kind != ADSEQ_RING, atomic = d.B > 1;
+  if (!bounded) {
+    // launch k: neuron update of step n (if any) + gather of step n - 1 (if any); T + 1 launches
+    for (long long n = T; n >= 0; --n) {
+      const long long n_neu = n < T ? n : -1, n_gat = n - 1;
+      const unsigned grid = (unsigned)((n_neu >= 0 ? d.nblk : 0) + (n_gat >= 0 ? d.nblk * kSplit : 0));
+      if (!grid) continue;
+      mark(h, st, -1);
+      if (atomic) hipLaunchKernelGGL((k_bwd_step_ring<true>), dim3(grid), block, 0, st, d, n_neu, n_gat, T, dscale, dL_dcount, dL_dU, grad_w, grad_d);
+      else hipLaunchKernelGGL((k_bwd_step_ring<false>), dim3(grid), block, 0, st, d, n_neu, n_gat, T, dscale, dL_dcount, dL_dU, grad_w, grad_d);
+      mark(h, st, 2);
+    }
+    HIP_TRY(h, hipGetLastError());
+    return ADSEQ_OK;
+  }
   mark(h, st, -1);
   for (long long n = T - 1; n >= 0; --n) {
-    if (!bounded) {
-      if (atomic) hipLaunchKernelGGL((k_bwd_gather_ring<true>), dim3(d.nblk * kSplit), block, 0, st, d, n, T, dscale, grad_w, grad_d);
-      else hipLaunchKernelGGL((k_bwd_gather_ring<false>), dim3(d.nblk * kSplit), block, 0, st, d, n, T, dscale, grad_w, grad_d);
-      mark(h, st, 2);
-      hipLaunchKernelGGL(k_bwd_neurons, gn, block, 0, st, d, n, dL_dcount, dL_dU);
-      mark(h, st, 3);
-      continue;
-    }
     if (bounded) {
       if (atomic) hipLaunchKernelGGL((k_bwd_gather<true, true>), gg, block, 0, st, d, n, T, dscale, grad_w, grad_d);
       else hipLaunchKernelGGL((k_bwd_gather<true, false>), gg, block, 0, st, d, n, T, dscale, grad_w, grad_d);
@@ -1225,6 +1414,7 @@ int adseq_counters(adseq_t* h, int64_t* out8, void* stream) {
   Counters c;
   hipStream_t st = (hipStream_t)stream;
   const Dev& d = h->dev;
+  flush_ring(h, st);
   if (d.kind == ADSEQ_RING) {
     // the ring sums amplitudes, so delivered = offered - still in flight; the latter is counted
     // here, on demand, from the spike bits of the last d_max + 1 steps
