@@ -224,3 +224,27 @@ def test_tape_overflow_is_reported():
         sim.drop_count()
     assert ei.value.code == -7
     sim.close()
+
+
+# ---------------------------------------------------------------- the larger configs, shortened
+
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 8), ("fifo", 32)])
+def test_cfg2_shape_forward(kind, cap):
+    """Config 2's network (10,000 neurons, fan-out 1,000, delays 1..200) for 240 steps with a
+    drive strong enough to make it fire within them; bounded kinds overflow heavily."""
+    wl = synth.cfg2(rate_hz=100.0)
+    ref, _ = _compare_forward(wl, KINDS[kind], cap, T=240, check_sets=False)
+    assert ref.spikes.sum() > 2000
+    if kind != "ring":
+        assert ref.counters()["dropped"] > 1000000
+
+
+@pytest.mark.parametrize("kind,cap", [("sorted", 128), ("fifo", 32), ("ring", 0)])
+def test_cfg4_shape_forward_backward(kind, cap):
+    """Config 4's network (4,096 neurons, fan-out 256, lognormal weights with 20 % inhibitory
+    sources, continuous delays 0.1..20 ms), 6 trials, 300 steps, delay and weight gradients."""
+    wl = synth.cfg4(n_steps=300, batch=6)
+    wl.ext_rate_hz = 250.0
+    ref = _compare_backward(wl, KINDS[kind], cap, 300, 6, use_dU=False,
+                            tape_spike_capacity=300 * 6 * 4096 // 4)
+    assert ref.spikes.sum() > 3000
