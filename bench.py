@@ -119,14 +119,24 @@ def main():
         "bwd_neurons": BWD_B_NEURON * BN * T,
     }
     if args.queue == "ring":
-        # the ring runs ONE kernel per time step in each direction: neuron update and
-        # fan-out (or gather) are two block roles of the same launch
-        alg = {"fan_out": alg["fan_out"] + alg["lif"], "bwd_gather": alg["bwd_gather"] + alg["bwd_neurons"]}
-        label = {"fan_out": "k_step_ring (pop + LIF | fan-out + enqueue)",
-                 "bwd_gather": "k_bwd_step_ring (adjoint update | gather + gradients)"}
-    else:
-        label = {"fan_out": "k_fanout + k_admit", "lif": "k_neurons (pop + LIF + compaction)",
-                 "bwd_gather": "k_bwd_gather", "bwd_neurons": "k_bwd_neurons"}
+        # events that arrive inside the window they were emitted in are scattered by the step
+        # kernel itself; the others by the window expansion.  Share of the former for a spike at
+        # a uniformly distributed window phase: sum_D P(D) max(0, W - D) / W.
+        W = int(os.environ.get("ADSEQ_RING_WINDOW", "16"))
+        if wl.delay_steps is not None:
+            D = np.bincount(wl.delay_steps, minlength=W + 1).astype(np.float64)
+        else:
+            D = np.bincount(np.maximum(1, np.ceil(wl.delay_ms.astype(np.float64) / wl.dt_ms)).astype(np.int64),
+                            minlength=W + 1).astype(np.float64)
+        near = float((D[:W] * (W - np.arange(W))).sum() / (W * D.sum()))
+        alg["lif"] += FWD_B_EVENT["ring"] * offered * near
+        alg["fan_out"] = FWD_B_EVENT["ring"] * offered * (1.0 - near)
+        alg["bwd_neurons"] += BWD_B_EVENT * in_run * near
+        alg["bwd_gather"] = BWD_B_EVENT * in_run * (1.0 - near)
+        label = {"fan_out": "k_win_bin + k_win_acc (expansion of one window: stage by target part, sum in LDS)",
+                 "lif": "k_step_win (pop + drive + LIF + spike bits + in-window scatter)",
+                 "bwd_gather": "k_bwd_win (far queue terms and gradient sums of one window)",
+                 "bwd_neurons": "k_bwd_step_win (adjoint update + in-window gather)"}
     kernels = {}
     for k, v in prof.items():
         if v["launches"]:

@@ -14,7 +14,7 @@ HIPCC_FLAGS = [
     "-ffp-contract=off",          # the LIF update spells its one fma out; nothing else may fuse
     "-munsafe-fp-atomics",        # hardware fp32 atomic add for the batched gradient accumulation
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-I", os.path.join(ROOT, "include"),
+    "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"),
 ]
 
 

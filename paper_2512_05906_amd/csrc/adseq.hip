@@ -4,22 +4,27 @@
 //
 // Layout of the state in the caller's workspace (all arrays 256-byte aligned):
 //   V            fp32  [BN]                 membrane state
-//   ring         i32   [R][BN]              RING: Q8.24 sums per arrival slot, R = d_max + 1
-//   spike_bits   u64   [R][4 nblk]          RING: spike bit masks of the last R steps (one word per
-//                                           wavefront), from which in-flight events are counted on demand
+//   win          i32   [W][BN]              RING: Q8.24 sums per arrival step of the current window
+//   spike_bits   u64   [R][4 nblk]          RING: spike bit masks of the last R = d_max + 1 steps (one
+//                                           word per wavefront): the events not yet in `win`
+//   dstart, nearcnt, perm, rowsum           RING: index of the rows sorted by arrival offset
+//   ebuf, ecnt                              RING: staging regions of the window expansion
 //   slot_k/a     u32/i32 [C][BN]            FIFO/SORTED: arrival step and Q8.24 amplitude, slot-major
 //                                           so that one slot of 64 consecutive targets is one line
 //   occ, head    i32   [BN]                 FIFO/SORTED: stored events; SORTED: index of the front
 //   c_head, pool_*                          per-step contender lists (one linked list per target)
 //   packed, a_q  u32/i32 [S]                synapses: (col << dbits | D) and Q8.24 amplitude
-//   amp, fdec    fp32  [S]                  continuous delays only: a = w f and f
+//                                           (RING: every row sorted by D; else the caller's order)
+//   amp, fdec    fp32  [S]                  a = w f (RING or continuous delays) and f (continuous)
 //   tape_*                                  membrane tape, spike list, admission flags
-//   bwd_*                                   adjoint delay line [R][BN], carry, queue term
+//   bwd_*                                   FIFO/SORTED: adjoint delay line [R][BN], carry, queue term
+//   gwin, Gacc, gsum                        RING: adjoint rows of the window, far queue terms, per-synapse sums
 #include <hip/hip_runtime.h>
 
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -69,12 +74,25 @@ struct Dev {
   const float* delay_ms;
   unsigned* packed;
   int* a_q;
-  long long* d1_ptr;   // RING: [N+1] per-row ranges into d1_off
-  unsigned* d1_off;    // RING: positions (within the row) of the entries with arrival offset 1
+  // RING (windowed delay line, see ring_window.h)
+  int W, wshift;        // window length in steps (power of two) and its log2
+  int tp_shift;         // log2 of the targets per part (W << tp_shift = cells of one LDS tile)
+  int P, NB, cap;       // target parts, blocks of the staging pass, events per (part, block) region
+  int wgroups;          // 64-word groups per step in spike_bits
+  int* win;             // [W][BN]
+  unsigned* dstart;     // [N][d_max + 2]
+  unsigned* nearcnt;    // [W + 1][N]
+  unsigned* perm;       // [S]
+  long long* rowsum;    // [N]
+  uint2* ebuf;          // [min(P, kMaxParts)][NB][cap]
+  int* ecnt;            // [min(P, kMaxParts)][NB]
+  unsigned long long* tape_bits;  // [T][words]
+  float* gwin;          // [W][BN]
+  float* Gacc;          // [R][BN]
+  float* gsum;          // [S]
   float* amp;
   float* fdec;
   float* V;
-  int* ring;
   unsigned long long* spike_bits;  // RING: [R][words] spikes of the last R steps
   unsigned* slot_k;
   int* slot_a;
@@ -204,53 +222,9 @@ __global__ __launch_bounds__(kBlock) void k_prepare(Dev d, ExpCoef ec) {
   }
 }
 
-// Per-row lists of the entries with arrival offset 1 (RING).  One wavefront per row.
-// pass 0: d1_ptr[i + 1] = count; (then k_scan_rows turns counts into offsets;) pass 1: fill d1_off.
-__global__ __launch_bounds__(kBlock) void k_d1_lists(Dev d, int pass) {
-  const int lane = threadIdx.x & 63;
-  const long long wave = ((long long)blockIdx.x * kBlock + threadIdx.x) >> 6;
-  const long long nwaves = ((long long)gridDim.x * kBlock) >> 6;
-  for (long long i = wave; i < d.N; i += nwaves) {
-    const long long r0 = d.row_ptr[i], r1 = d.row_ptr[i + 1];
-    long long base = pass ? d.d1_ptr[i] : 0;
-    int total = 0;
-    for (long long q0 = r0; q0 < r1; q0 += 64) {
-      const long long p = q0 + lane;
-      const bool hit = p < r1 && (d.packed[p] & d.dmask) == 1u;
-      const unsigned long long mk = __ballot(hit);
-      if (pass && hit) d.d1_off[base + total + __popcll(mk & ((1ull << lane) - 1ull))] = (unsigned)(p - r0);
-      total += __popcll(mk);
-    }
-    if (!pass && lane == 0) d.d1_ptr[i + 1] = total;
-  }
-  if (!pass && blockIdx.x == 0 && threadIdx.x == 0) d.d1_ptr[0] = 0;
-}
-
-// In-place inclusive scan of ptr[1..n] (single block; create-time only).
-__global__ __launch_bounds__(1024) void k_scan_rows(long long* ptr, long long n) {
-  __shared__ long long s_w[16];
-  __shared__ long long s_carry;
-  if (threadIdx.x == 0) s_carry = 0;
-  __syncthreads();
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  for (long long base = 1; base <= n; base += 1024) {
-    const long long idx = base + threadIdx.x;
-    long long v = idx <= n ? ptr[idx] : 0;
-    for (int o = 1; o < 64; o <<= 1) { const long long t = __shfl_up(v, o, 64); if (lane >= o) v += t; }
-    if (lane == 63) s_w[w] = v;
-    __syncthreads();
-    long long add = s_carry;
-    for (int x = 0; x < w; ++x) add += s_w[x];
-    if (idx <= n) ptr[idx] = v + add;
-    __syncthreads();
-    if (threadIdx.x == 1023) s_carry = v + add;
-    __syncthreads();
-  }
-}
-
 // ---------------------------------------------------------------- pop + drive + LIF + compaction
 
-// One thread per (trial, neuron).  KIND selects how the due events are popped.
+// FIFO / SORTED.  One thread per (trial, neuron).  KIND selects how the due events are popped.
 // LIF = true: closed-loop step (drive, membrane update, spike compaction, tape);
 // LIF = false: open-loop delivery, writes the popped current to I_out.
 template <int KIND, bool LIF>
@@ -267,11 +241,7 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
     d.ctr->n_spk[parity ^ 1] = 0;  // next step's spike counter; nobody reads it now
   }
   if (act) {
-    if (KIND == ADSEQ_RING) {
-      const size_t idx = (size_t)(n % d.R) * d.BN + g;
-      acc = d.ring[idx];
-      if (acc != 0) d.ring[idx] = 0;
-    } else if (KIND == ADSEQ_FIFO) {
+    if (KIND == ADSEQ_FIFO) {
       // bounded bag: every stored event due now leaves; survivors are packed to the front
       const int occ = d.occ[g];
       int keep = 0;
@@ -306,10 +276,6 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
       }
     }
   }
-  if (KIND == ADSEQ_RING && (threadIdx.x & 63) == 0) {
-    // open-loop use: this step's spike bits start empty; adseq_enqueue sets them
-    d.spike_bits[(size_t)(n % d.R) * d.words + (size_t)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6)] = 0ull;
-  }
   bool s = false;
   if (act) {
     float I = (float)acc * 0x1p-24f;
@@ -343,10 +309,9 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
 
 // ---------------------------------------------------------------- fan-out + enqueue
 
-// One block per spike (grid-stride over the spike list); the block walks the CSR row with
-// coalesced reads of (packed, a_q).  RING: integer atomic add into the arrival slot.
-// FIFO/SORTED: events whose target is already full are dropped here; the others become
-// contenders, pushed on their target's linked list for k_admit.
+// FIFO / SORTED.  One block per spike (grid-stride over the spike list); the block walks the
+// CSR row with coalesced reads of (packed, a_q).  Events whose target is already full are
+// dropped here; the others become contenders, pushed on their target's linked list for k_admit.
 template <int KIND>
 __global__ __launch_bounds__(kBlock) void k_fanout(Dev d, long long n, const int* __restrict__ spk,
                                                    const int* __restrict__ n_spk_ptr, int parity,
@@ -354,9 +319,8 @@ __global__ __launch_bounds__(kBlock) void k_fanout(Dev d, long long n, const int
   __shared__ long long s_evb;
   int nspk = *n_spk_ptr;
   nspk = nspk < 0 ? 0 : (nspk > d.BN ? d.BN : nspk);
-  if (KIND != ADSEQ_RING && blockIdx.x == 0 && threadIdx.x == 0) d.ctr->pool_n[parity ^ 1] = 0;
+  if (blockIdx.x == 0 && threadIdx.x == 0) d.ctr->pool_n[parity ^ 1] = 0;
   const long long off = record ? d.step_off[n] : 0;
-  const int m = (int)(n % d.R);
   const int lane = threadIdx.x & 63;
   long long c_off = 0, s_off = 0, c_drop = 0, s_drop = 0;
   for (int e = blockIdx.x; e < nspk; e += gridDim.x) {
@@ -365,25 +329,21 @@ __global__ __launch_bounds__(kBlock) void k_fanout(Dev d, long long n, const int
     const int b = g / d.N, i = g - b * d.N;
     const long long r0 = d.row_ptr[i], r1 = d.row_ptr[i + 1];
     long long tbase = -1;
-    if (KIND == ADSEQ_RING && threadIdx.x == 0)
-      atomicOr(&d.spike_bits[(size_t)m * d.words + (g >> 6)], 1ull << (g & 63));
     if (record) {
       const bool fits = off + e < d.spike_cap;
       if (threadIdx.x == 0) {
         if (fits) d.tape_spk[off + e] = g; else atomicOr(&d.ctr->err, ERR_TAPE_SPIKES);
       }
-      if (KIND != ADSEQ_RING) {
-        if (threadIdx.x == 0) {
-          long long evb = (long long)atomicAdd((unsigned long long*)&d.ctr->tape_events,
-                                               (unsigned long long)(r1 - r0));
-          if (evb + (r1 - r0) > d.event_cap) { atomicOr(&d.ctr->err, ERR_TAPE_EVENTS); evb = -1; }
-          if (fits) d.tape_evb[off + e] = evb;
-          s_evb = evb;
-        }
-        __syncthreads();
-        tbase = s_evb;
-        __syncthreads();
+      if (threadIdx.x == 0) {
+        long long evb = (long long)atomicAdd((unsigned long long*)&d.ctr->tape_events,
+                                             (unsigned long long)(r1 - r0));
+        if (evb + (r1 - r0) > d.event_cap) { atomicOr(&d.ctr->err, ERR_TAPE_EVENTS); evb = -1; }
+        if (fits) d.tape_evb[off + e] = evb;
+        s_evb = evb;
       }
+      __syncthreads();
+      tbase = s_evb;
+      __syncthreads();
     }
     for (long long p0 = r0; p0 < r1; p0 += kBlock) {
       const long long p = p0 + threadIdx.x;
@@ -392,12 +352,7 @@ __global__ __launch_bounds__(kBlock) void k_fanout(Dev d, long long n, const int
       if (valid) { pk = d.packed[p]; a = d.a_q[p]; c_off += 1; s_off += a; }
       const int D = (int)(pk & d.dmask);
       const int col = (int)(pk >> d.dbits);
-      if (KIND == ADSEQ_RING) {
-        if (valid) {
-          int slot = m + D; if (slot >= d.R) slot -= d.R;
-          atomicAdd(&d.ring[(size_t)slot * d.BN + (size_t)b * d.N + col], a);
-        }
-      } else {
+      {
         const int gt = b * d.N + col;
         const long long tidx = (valid && tbase >= 0) ? tbase + (p - r0) : -1;
         bool contend = false;
@@ -431,7 +386,7 @@ __global__ __launch_bounds__(kBlock) void k_fanout(Dev d, long long n, const int
     d.ctr->tape_spikes = off + nspk;
   }
   block_add2(&d.ctr->offered, c_off, &d.ctr->sum_offered, s_off);
-  if (KIND != ADSEQ_RING) block_add2(&d.ctr->dropped, c_drop, &d.ctr->sum_dropped, s_drop);
+  block_add2(&d.ctr->dropped, c_drop, &d.ctr->sum_dropped, s_drop);
 }
 
 // Admission for the bounded kinds.  One thread per contender; the thread whose entry is the head
@@ -516,365 +471,16 @@ __device__ __forceinline__ int block_compact(bool flag, int* s_list, int* s_wcnt
   return total;
 }
 
-// ---------------------------------------------------------------- closed-loop step (RING)
-//
-// One launch per time step, without an atomic on any shared counter, made of two kinds of blocks:
-//   ring_lif   block b owns neurons [256 b, 256 b + 256): pops their ring slots, integrates,
-//              records the membrane value, publishes the spike bits of its four wavefronts;
-//   ring_fan   kSplit blocks per neuron block: block (b, c) re-derives b's spikes from the spike
-//              bits and scatters chunk c (256 entries out of every kSplit * 256) of each spike's CSR
-//              row, so that one neuron block's spikes are spread over kSplit compute units and the
-//              row reads of all its spikes are in flight together.
-// The ring is d_max + 1 deep, hence the row popped at step n is never a target of the events
-// emitted at step n (arrival offsets are 1..d_max).
+// ---------------------------------------------------------------- ring queue (windowed delay line)
 
-#ifndef ADSEQ_KSPLIT
-#define ADSEQ_KSPLIT 4
-#endif
-constexpr int kSplit = ADSEQ_KSPLIT;  // fan-out blocks per neuron block
-constexpr int kBatch = 8;  // spikes whose row entries a thread keeps in flight together
+#include "ring_window.h"
 
-// Neuron part of a ring step for neuron block `nb`: pop, drive, LIF, tape, spike words; plus the
-// scatter of the block's own events with arrival offset 1 (taken from the per-row lists built at
-// create), which are the only ones the next step's pop depends on.
-template <bool RECORD>
-__device__ __forceinline__ void ring_lif(const Dev& d, long long n, int nb,
-                                         const float* __restrict__ i_ext,
-                                         unsigned char* __restrict__ spikes_out) {
-  __shared__ long long s_red[3][kBlock / 64];
-  const int g = nb * kBlock + threadIdx.x;
-  const bool act = g < d.BN;
-  const int m = (int)(n % d.R);
-  int acc = 0;
-  bool s = false;
-  if (act) {
-    const size_t idx = (size_t)m * d.BN + g;
-    acc = d.ring[idx];
-    if (acc != 0) d.ring[idx] = 0;
-    float I = (float)acc * 0x1p-24f;
-    if (d.p_thresh) {
-      const bool xi = (unsigned long long)drive_bits(d.seed, (unsigned long long)g,
-                                                     (unsigned long long)n) < d.p_thresh;
-      I = I + (xi ? d.ext_w : 0.0f);
-    }
-    if (i_ext) I = I + i_ext[g];
-    const float U = __fmaf_rn(d.alpha, d.V[g], I);
-    s = U >= d.theta;
-    d.V[g] = s ? d.v_reset : U;
-    if (RECORD) d.tapeU[(size_t)n * d.BN + g] = U;
-    if (spikes_out) spikes_out[g] = s ? 1 : 0;
-  }
-  // spike bits of this step: read by the fan-out blocks of the next launch, and kept for
-  // d_max + 1 steps so that the events still in flight can be counted on demand
-  const unsigned long long bits = __ballot(s);
-  if ((threadIdx.x & 63) == 0)
-    d.spike_bits[(size_t)m * d.words + (size_t)nb * (kBlock / 64) + (threadIdx.x >> 6)] = bits;
-  long long c1 = 0, s1 = 0;
-  if (s) {
-    const int b = g / d.N, i = g - b * d.N;
-    const long long q0 = d.d1_ptr[i], q1 = d.d1_ptr[i + 1];
-    if (q1 > q0) {
-      const long long r0 = d.row_ptr[i];
-      int slot = m + 1; if (slot >= d.R) slot -= d.R;
-      int* __restrict__ dst = d.ring + (size_t)slot * d.BN + (size_t)b * d.N;
-      for (long long q = q0; q < q1; ++q) {
-        const long long p = r0 + d.d1_off[q];
-        const int a = d.a_q[p];
-        atomicAdd(&dst[d.packed[p] >> d.dbits], a);
-        c1 += 1; s1 += a;
-      }
-    }
-  }
-  const long long sp = wave_sum((long long)acc);
-  const long long ns = wave_sum((long long)(s ? 1 : 0));
-  c1 = wave_sum(c1); s1 = wave_sum(s1);
-  __shared__ long long s_c1[kBlock / 64];
-  if ((threadIdx.x & 63) == 0) {
-    const int w = threadIdx.x >> 6;
-    s_red[0][w] = sp; s_red[1][w] = ns; s_red[2][w] = s1; s_c1[w] = c1;
-  }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    long long a = 0, c = 0, so = 0, co = 0;
-    for (int w = 0; w < kBlock / 64; ++w) { a += s_red[0][w]; c += s_red[1][w]; so += s_red[2][w]; co += s_c1[w]; }
-    // private counters of this block; atomics only so that nothing waits for a read
-    BlkCtr& bc = d.blk[nb];
-    if (a) atomicAdd((unsigned long long*)&bc.sum_delivered, (unsigned long long)a);
-    if (c) atomicAdd(&bc.spikes, (unsigned long long)c);
-    if (co) { atomicAdd(&bc.offered, (unsigned long long)co); atomicAdd((unsigned long long*)&bc.sum_offered, (unsigned long long)so); }
-  }
-}
-
-// Spikes of neuron block `nb` at ring slot m, from the spike bits: fills s_r0 / s_len / s_base in
-// ascending neuron order and returns their number (0: nothing to do; uniform over the block).
-__device__ __forceinline__ int block_spikes_from_bits(const Dev& d, int m, int nb, long long* s_r0,
-                                                      int* s_len, int* s_base) {
-  const unsigned long long* w = d.spike_bits + (size_t)m * d.words + (size_t)nb * (kBlock / 64);
-  const unsigned long long w0 = w[0], w1 = w[1], w2 = w[2], w3 = w[3];
-  if ((w0 | w1 | w2 | w3) == 0ull) return 0;
-  const int wi = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const unsigned long long mine = wi == 0 ? w0 : (wi == 1 ? w1 : (wi == 2 ? w2 : w3));
-  if ((mine >> lane) & 1ull) {
-    int pos = __popcll(mine & ((1ull << lane) - 1ull));
-    if (wi > 0) pos += __popcll(w0);
-    if (wi > 1) pos += __popcll(w1);
-    if (wi > 2) pos += __popcll(w2);
-    const int g = nb * kBlock + threadIdx.x;
-    const int b = g / d.N, i = g - b * d.N;
-    const long long r0 = d.row_ptr[i];
-    s_r0[pos] = r0; s_len[pos] = (int)(d.row_ptr[i + 1] - r0); s_base[pos] = b * d.N;
-  }
-  __syncthreads();
-  return __popcll(w0) + __popcll(w1) + __popcll(w2) + __popcll(w3);
-}
-
-// Fan-out part of a ring step: fan block `fb` = (neuron block fb / kSplit, chunk fb % kSplit)
-// scatters its chunk of the rows of that neuron block's spikes at step n, except the entries with
-// arrival offset 1 (already scattered by ring_lif in the launch that detected the spikes).
-__device__ __forceinline__ void ring_fan(const Dev& d, long long n, int fb) {
-  __shared__ long long s_r0[kBlock];
-  __shared__ int s_len[kBlock];
-  __shared__ int s_base[kBlock];
-  __shared__ long long s_red[2][kBlock / 64];
-  const int nb = fb / kSplit, c = fb % kSplit;
-  const int m = (int)(n % d.R);
-  const int nspk = block_spikes_from_bits(d, m, nb, s_r0, s_len, s_base);
-  if (nspk == 0) return;
-  long long c_off = 0, s_off = 0;
-  for (int e0 = 0; e0 < nspk; e0 += kBatch) {
-    int maxlen = 0;
-#pragma unroll
-    for (int j = 0; j < kBatch; ++j)
-      if (e0 + j < nspk) { const int l = s_len[e0 + j]; maxlen = l > maxlen ? l : maxlen; }
-    for (int q = c * kBlock + threadIdx.x; q < maxlen; q += kSplit * kBlock) {
-      unsigned pk[kBatch]; int aq[kBatch]; int bs[kBatch];
-#pragma unroll
-      for (int j = 0; j < kBatch; ++j) {
-        bs[j] = -1; pk[j] = 0; aq[j] = 0;
-        if (e0 + j < nspk && q < s_len[e0 + j]) {
-          const long long p = s_r0[e0 + j] + q;
-          pk[j] = d.packed[p]; aq[j] = d.a_q[p]; bs[j] = s_base[e0 + j];
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < kBatch; ++j) {
-        const int D = (int)(pk[j] & d.dmask);
-        if (bs[j] >= 0 && D != 1) {
-          int slot = m + D; if (slot >= d.R) slot -= d.R;
-          atomicAdd(&d.ring[(size_t)slot * d.BN + (size_t)bs[j] + (pk[j] >> d.dbits)], aq[j]);
-          c_off += 1; s_off += aq[j];
-        }
-      }
-    }
-  }
-  c_off = wave_sum(c_off); s_off = wave_sum(s_off);
-  if ((threadIdx.x & 63) == 0) { s_red[0][threadIdx.x >> 6] = c_off; s_red[1][threadIdx.x >> 6] = s_off; }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    long long a = 0, b = 0;
-    for (int w = 0; w < kBlock / 64; ++w) { a += s_red[0][w]; b += s_red[1][w]; }
-    BlkCtr& bc = d.blk[d.nblk + fb];
-    if (a) { atomicAdd(&bc.offered, (unsigned long long)a); atomicAdd((unsigned long long*)&bc.sum_offered, (unsigned long long)b); }
-  }
-}
-
-// One launch per time step for the ring.  The first nblk blocks (when n_lif >= 0) integrate step
-// n_lif; the other nblk * kSplit blocks (when n_fan >= 0) fan out the spikes of step n_fan =
-// n_lif - 1 with arrival offsets >= 2.  The two halves are independent: the pop of step n only
-// needs offset-1 events of step n - 1 (scattered by ring_lif itself, one launch earlier) and
-// events of older steps (complete), and with a ring d_max + 1 deep no fan-out event of step n - 1
-// with offset >= 2 lands in the row being popped.  So the neuron update hides behind the scatter.
-template <bool RECORD>
-__global__ __launch_bounds__(kBlock) void k_step_ring(Dev d, long long n_lif, long long n_fan,
-                                                      const float* __restrict__ i_ext,
-                                                      unsigned char* __restrict__ spikes_out) {
-  const int lif_blocks = n_lif >= 0 ? d.nblk : 0;
-  if ((int)blockIdx.x < lif_blocks) ring_lif<RECORD>(d, n_lif, (int)blockIdx.x, i_ext, spikes_out);
-  else ring_fan(d, n_fan, (int)blockIdx.x - lif_blocks);
-}
-
-// Events of the ring that are still in flight at step n_end (arrival >= n_end): counted from the
-// spike bits of the last d_max + 1 steps.  One block per (slot, 64-neuron word); on demand only.
-__global__ __launch_bounds__(kBlock) void k_ring_in_flight(Dev d, long long n_end,
-                                                           unsigned long long* out /*[2]*/) {
-  const long long item = blockIdx.x;
-  const int slot = (int)(item / d.words);
-  const long long word = item % d.words;
-  // the step this slot last held: the largest n' < n_end with n' % R == slot
-  long long np = n_end - 1 - ((n_end - 1 - slot) % d.R + d.R) % d.R;
-  if (n_end <= 0 || np < 0) return;
-  unsigned long long bits = d.spike_bits[(size_t)slot * d.words + word];
-  long long cnt = 0, sum = 0;
-  while (bits) {
-    const int bit = __ffsll((long long)bits) - 1;
-    bits &= bits - 1;
-    const long long g = word * 64 + bit;
-    if (g >= d.BN) break;
-    const int i = (int)(g % d.N);
-    const long long r0 = d.row_ptr[i], r1 = d.row_ptr[i + 1];
-    for (long long p = r0 + threadIdx.x; p < r1; p += kBlock) {
-      const int D = (int)(d.packed[p] & d.dmask);
-      if (np + D >= n_end) { cnt += 1; sum += d.a_q[p]; }
-    }
-  }
-  block_add2(&out[0], cnt, (long long*)&out[1], sum);
-}
-
-// Queue term of the reverse sweep for the ring, kSplit blocks per neuron block: gather block
-// (b, c) re-derives b's spikes at step n from the membrane tape (s = U >= theta), gathers the
-// adjoint at the arrival slot of chunk c of each spike's row (arrival offsets >= 2), accumulates the
-// row's weight and delay gradients, and leaves its partial queue term in g_part[n & 1][c][neuron].
-template <bool ATOMIC>
-__device__ __forceinline__ void ring_bwd_gather(const Dev& d, long long n, long long T, float dscale, int fb,
-                                                float* __restrict__ grad_w, float* __restrict__ grad_d) {
-  __shared__ int s_spk[kBlock];
-  __shared__ int s_wcnt[kBlock / 64];
-  __shared__ long long s_r0[kBlock];
-  __shared__ int s_len[kBlock];
-  __shared__ int s_base[kBlock];
-  __shared__ float s_G[kBlock];
-  const int nb = fb / kSplit, c = fb % kSplit;
-  const int g = nb * kBlock + threadIdx.x;
-  const int m = (int)(n % d.R);
-  bool s = false;
-  if (g < d.BN) s = d.tapeU[(size_t)n * d.BN + g] >= d.theta;
-  if (!__syncthreads_or(s ? 1 : 0)) return;
-  int pos;
-  const int nspk = block_compact(s, s_spk, s_wcnt, &pos);
-  if (s) {
-    const int b = g / d.N, i = g - b * d.N;
-    const long long r0 = d.row_ptr[i];
-    s_r0[pos] = r0; s_len[pos] = (int)(d.row_ptr[i + 1] - r0); s_base[pos] = b * d.N; s_G[pos] = 0.0f;
-  }
-  __syncthreads();
-  for (int e0 = 0; e0 < nspk; e0 += kBatch) {
-    int maxlen = 0;
-#pragma unroll
-    for (int j = 0; j < kBatch; ++j)
-      if (e0 + j < nspk) { const int l = s_len[e0 + j]; maxlen = l > maxlen ? l : maxlen; }
-    float Gacc[kBatch];
-#pragma unroll
-    for (int j = 0; j < kBatch; ++j) Gacc[j] = 0.0f;
-    for (int q = c * kBlock + threadIdx.x; q < maxlen; q += kSplit * kBlock) {
-      unsigned pk[kBatch]; float am[kBatch]; float fd[kBatch]; int bs[kBatch]; long long pp[kBatch];
-#pragma unroll
-      for (int j = 0; j < kBatch; ++j) {
-        bs[j] = -1; pk[j] = 0; am[j] = 0.0f; fd[j] = 1.0f; pp[j] = 0;
-        if (e0 + j < nspk && q < s_len[e0 + j]) {
-          const long long p = s_r0[e0 + j] + q;
-          pk[j] = d.packed[p];
-          if (d.continuous) { am[j] = d.amp[p]; fd[j] = d.fdec[p]; } else { am[j] = d.weight[p]; }
-          bs[j] = s_base[e0 + j]; pp[j] = p;
-        }
-      }
-      float gv[kBatch];
-#pragma unroll
-      for (int j = 0; j < kBatch; ++j) {
-        gv[j] = 0.0f;
-        const int D = (int)(pk[j] & d.dmask);
-        if (bs[j] >= 0 && D != 1 && n + D < T) {  // offset 1: ring_bwd_neurons; n + D >= T: never delivered
-          int slot = m + D; if (slot >= d.R) slot -= d.R;
-          gv[j] = d.bwd_ring[(size_t)slot * d.BN + (size_t)bs[j] + (pk[j] >> d.dbits)];
-        } else {
-          bs[j] = -1;
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < kBatch; ++j) {
-        if (bs[j] >= 0) {
-          Gacc[j] += am[j] * gv[j];
-          const float gw = fd[j] * gv[j], gd = am[j] * dscale * gv[j];
-          if (ATOMIC) { unsafeAtomicAdd(&grad_w[pp[j]], gw); unsafeAtomicAdd(&grad_d[pp[j]], gd); }
-          else { grad_w[pp[j]] += gw; grad_d[pp[j]] += gd; }
-        }
-      }
-    }
-#pragma unroll
-    for (int j = 0; j < kBatch; ++j) {
-      if (e0 + j < nspk) {  // uniform over the block
-        const float t = wave_sum_f(Gacc[j]);
-        if ((threadIdx.x & 63) == 0 && t != 0.0f) atomicAdd(&s_G[e0 + j], t);
-      }
-    }
-  }
-  __syncthreads();
-  if ((int)threadIdx.x < nspk)
-    d.bwd_G[((size_t)(n & 1) * kSplit + c) * d.BN + (size_t)nb * kBlock + s_spk[threadIdx.x]] = s_G[threadIdx.x];
-}
-
-// Neuron part of the reverse sweep for the ring at step n: adds the offset-1 events of its own
-// spikes (they need gU[n + 1], written one launch earlier) to the kSplit partial queue terms, then
-//   gU[n] = (1 - s) alpha gU[n+1] + sigma'(U - theta) (dL/dcount + s G) + dL/dU[n]
-template <bool ATOMIC>
-__device__ __forceinline__ void ring_bwd_neurons(const Dev& d, long long n, long long T, float dscale, int nb,
-                                                 const float* __restrict__ dL_dcount,
-                                                 const float* __restrict__ dL_dU,
-                                                 float* __restrict__ grad_w, float* __restrict__ grad_d) {
-  const int g = nb * kBlock + threadIdx.x;
-  if (g >= d.BN) return;
-  const int m = (int)(n % d.R);
-  const float U = d.tapeU[(size_t)n * d.BN + g];
-  const bool s = U >= d.theta;
-  float sg = 0.0f;
-  if (d.surrogate == ADSEQ_SURR_SUPERSPIKE) {
-    const float x = fabsf(U - d.theta) + 1.0f;
-    sg = 1.0f / (x * x);
-  }
-  float inner = dL_dcount ? dL_dcount[g] : 0.0f;
-  if (s) {
-    float G = 0.0f;
-    for (int c = 0; c < kSplit; ++c) G += d.bwd_G[((size_t)(n & 1) * kSplit + c) * d.BN + g];
-    if (n + 1 < T) {
-      const int b = g / d.N, i = g - b * d.N;
-      const long long q0 = d.d1_ptr[i], q1 = d.d1_ptr[i + 1];
-      if (q1 > q0) {
-        const long long r0 = d.row_ptr[i];
-        int slot = m + 1; if (slot >= d.R) slot -= d.R;
-        const float* __restrict__ src = d.bwd_ring + (size_t)slot * d.BN + (size_t)b * d.N;
-        for (long long q = q0; q < q1; ++q) {
-          const long long p = r0 + d.d1_off[q];
-          const float gv = src[d.packed[p] >> d.dbits];
-          const float a = d.continuous ? d.amp[p] : d.weight[p];
-          const float f = d.continuous ? d.fdec[p] : 1.0f;
-          G += a * gv;
-          const float gw = f * gv, gd = a * dscale * gv;
-          if (ATOMIC) { unsafeAtomicAdd(&grad_w[p], gw); unsafeAtomicAdd(&grad_d[p], gd); }
-          else { grad_w[p] += gw; grad_d[p] += gd; }
-        }
-      }
-    }
-    inner += G;
-  }
-  float gu = sg * inner;
-  if (!s) gu = __fmaf_rn(d.alpha, d.bwd_carry[g], gu);
-  if (dL_dU) gu += dL_dU[(size_t)n * d.BN + g];
-  d.bwd_carry[g] = gu;
-  d.bwd_ring[(size_t)m * d.BN + g] = gu;
-}
-
-// One launch per reverse step for the ring: the first nblk blocks (when n_neu >= 0) update the
-// adjoint of step n_neu; the other nblk * kSplit blocks (when n_gat >= 0) gather the queue terms
-// of step n_gat = n_neu - 1 (offsets >= 2, which only read adjoint rows written by earlier launches).
-template <bool ATOMIC>
-__global__ __launch_bounds__(kBlock) void k_bwd_step_ring(Dev d, long long n_neu, long long n_gat,
-                                                          long long T, float dscale,
-                                                          const float* __restrict__ dL_dcount,
-                                                          const float* __restrict__ dL_dU,
-                                                          float* __restrict__ grad_w,
-                                                          float* __restrict__ grad_d) {
-  const int neu_blocks = n_neu >= 0 ? d.nblk : 0;
-  if ((int)blockIdx.x < neu_blocks)
-    ring_bwd_neurons<ATOMIC>(d, n_neu, T, dscale, (int)blockIdx.x, dL_dcount, dL_dU, grad_w, grad_d);
-  else
-    ring_bwd_gather<ATOMIC>(d, n_gat, T, dscale, (int)blockIdx.x - neu_blocks, grad_w, grad_d);
-}
-
-// ---------------------------------------------------------------- backward
+// ---------------------------------------------------------------- backward (FIFO / SORTED)
 
 // Queue term of the reverse sweep at step n: one block per recorded spike (b, i, n).  Gathers the
 // adjoint at each admitted event's arrival slot, reduces G_i, and accumulates the weight and
 // delay gradients of the row.
-template <bool BOUNDED, bool ATOMIC>
+template <bool ATOMIC>
 __global__ __launch_bounds__(kBlock) void k_bwd_gather(Dev d, long long n, long long T, float dscale,
                                                        float* __restrict__ grad_w,
                                                        float* __restrict__ grad_d) {
@@ -886,14 +492,14 @@ __global__ __launch_bounds__(kBlock) void k_bwd_gather(Dev d, long long n, long 
     const int g = d.tape_spk[off + e];
     const int b = g / d.N, i = g - b * d.N;
     const long long r0 = d.row_ptr[i], r1 = d.row_ptr[i + 1];
-    const long long evb = BOUNDED ? d.tape_evb[off + e] : 0;
+    const long long evb = d.tape_evb[off + e];
     float G = 0.0f;
     for (long long p = r0 + threadIdx.x; p < r1; p += kBlock) {
       const unsigned pk = d.packed[p];
       const int D = (int)(pk & d.dmask);
       const int col = (int)(pk >> d.dbits);
       if (n + D >= T) continue;                               // not delivered inside the run
-      if (BOUNDED && !d.tape_adm[evb + (p - r0)]) continue;   // refused by a full queue
+      if (!d.tape_adm[evb + (p - r0)]) continue;              // refused by a full queue
       int slot = m + D; if (slot >= d.R) slot -= d.R;
       const float gv = d.bwd_ring[(size_t)slot * d.BN + (size_t)b * d.N + col];
       const float a = d.continuous ? d.amp[p] : d.weight[p];
@@ -949,7 +555,6 @@ struct adseq {
   long long next_step;   // next step to deliver
   long long enq_calls;   // parity source for the pool / spike counters
   bool tape_ok;          // every step since reset went through adseq_step with recording
-  long long pending_fan; // RING: step whose fan-out (offsets >= 2) rides with the next launch, or -1
   char err[256];
   // optional kernel timing (adseq_profile): one event after each bracketed launch
   bool prof = false;
@@ -961,12 +566,25 @@ struct adseq {
 namespace {
 
 struct Layout {
-  size_t V, ring, spike_bits, slot_k, slot_a, occ, head, c_head, pool_p, pool_t, pool_g, pool_next,
-      pool_k, pool_a, cur_spk, packed, a_q, d1_ptr, d1_off, amp, fdec, tapeU, step_off, tape_spk, tape_evb, tape_adm,
-      bwd_ring, bwd_carry, bwd_G, ctr, blk, total;
+  size_t V, win, spike_bits, slot_k, slot_a, occ, head, c_head, pool_p, pool_t, pool_g, pool_next,
+      pool_k, pool_a, cur_spk, packed, a_q, dstart, nearcnt, perm, rowsum, ebuf, ecnt, amp, fdec, tapeU,
+      tape_bits, step_off, tape_spk, tape_evb, tape_adm, bwd_ring, bwd_carry, bwd_G, gwin, Gacc, gsum, ctr,
+      blk, total;
   long long spike_cap, event_cap, pool_cap;
   int R, dbits, nblk, words;
+  int W, wshift, tp_shift, P, NB, cap, wgroups;  // RING
 };
+
+// Window length of the ring in steps: 16 unless ADSEQ_RING_WINDOW names another power of two
+// in 2..64 (a tuning knob: results do not depend on it).
+int ring_window_steps() {
+  int w = 16;
+  if (const char* e = getenv("ADSEQ_RING_WINDOW")) {
+    const int v = atoi(e);
+    if (v >= 2 && v <= 64 && (v & (v - 1)) == 0) w = v;
+  }
+  return w;
+}
 
 int bit_width(unsigned v) { int b = 0; while (v) { ++b; v >>= 1; } return b; }
 
@@ -1018,10 +636,31 @@ bool make_layout(const adseq_config* c, Layout* L) {
   auto take = [&](size_t bytes) { size_t at = o; o += (bytes + 255) & ~(size_t)255; return at; };
   L->nblk = (int)((BN + kBlock - 1) / kBlock);
   L->words = L->nblk * (kBlock / 64);
+  L->W = L->wshift = L->tp_shift = L->P = L->NB = L->cap = L->wgroups = 0;
+  size_t stage_parts = 0;
+  if (!bounded) {
+    L->W = ring_window_steps();
+    L->wshift = bit_width((unsigned)L->W) - 1;
+    L->tp_shift = bit_width((unsigned)kTileCells) - 1 - L->wshift;
+    L->P = (int)((BN + ((size_t)1 << L->tp_shift) - 1) >> L->tp_shift);
+    L->wgroups = (L->words + 63) / 64;
+    // blocks of the staging pass: one 64-word chunk per wavefront when the history is full
+    const long long chunks = (long long)c->d_max_steps * L->wgroups;
+    long long nb = (chunks + kBinWaves - 1) / kBinWaves;
+    L->NB = (int)(nb < 1 ? 1 : (nb > kMaxBinBlocks ? kMaxBinBlocks : nb));
+    stage_parts = (size_t)(L->P < kMaxParts ? L->P : kMaxParts);
+    // staging capacity in events: by default what a window holds when every neuron fires at
+    // 1/32 per step, between 2^16 and 2^26 events
+    double ev = c->step_event_capacity ? (double)c->step_event_capacity
+                                       : (double)c->batch * (double)S * (double)L->W / 32.0;
+    if (!c->step_event_capacity) ev = ev < 65536.0 ? 65536.0 : (ev > 67108864.0 ? 67108864.0 : ev);
+    const double per = ev / ((double)stage_parts * (double)L->NB);
+    L->cap = (int)(per > 65536.0 ? 65536.0 : per);
+  }
   L->ctr = take(sizeof(Counters));
-  L->blk = take((size_t)L->nblk * (kSplit + 1) * sizeof(BlkCtr));  // neuron blocks + kSplit fan-out blocks each
+  L->blk = take((size_t)L->nblk * sizeof(BlkCtr));  // RING: private counters of the step kernel's blocks
   L->V = take(BN * 4);
-  L->ring = take(bounded ? 0 : (size_t)L->R * BN * 4);
+  L->win = take(bounded ? 0 : (size_t)L->W * BN * 4);
   L->spike_bits = take(bounded ? 0 : (size_t)L->R * L->words * 8);
   L->slot_k = take(bounded ? (size_t)c->capacity * BN * 4 : 0);
   L->slot_a = take(bounded ? (size_t)c->capacity * BN * 4 : 0);
@@ -1037,19 +676,28 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->cur_spk = take(BN * 4);
   L->packed = take(S * 4);
   L->a_q = take(S * 4);
-  L->d1_ptr = take(bounded ? 0 : ((size_t)c->n_neurons + 1) * 8);
-  L->d1_off = take(bounded ? 0 : S * 4);  // worst case: every entry has offset 1
-  L->amp = take(cont ? S * 4 : 0);
+  L->dstart = take(bounded ? 0 : (size_t)c->n_neurons * (c->d_max_steps + 2) * 4);
+  L->nearcnt = take(bounded ? 0 : (size_t)(L->W + 1) * c->n_neurons * 4);
+  L->perm = take(bounded ? 0 : S * 4);
+  L->rowsum = take(bounded ? 0 : (size_t)c->n_neurons * 8);
+  L->ebuf = take(bounded ? 0 : stage_parts * L->NB * (size_t)L->cap * 8);
+  L->ecnt = take(bounded ? 0 : stage_parts * L->NB * 4);
+  L->amp = take((cont || !bounded) ? S * 4 : 0);
   L->fdec = take(cont ? S * 4 : 0);
   const size_t T = c->record_tape ? (size_t)c->max_steps : 0;
   L->tapeU = take(T * BN * 4);
+  L->tape_bits = take(bounded ? 0 : T * L->words * 8);
   L->step_off = take(c->record_tape ? (T + 1) * 8 : 0);
   L->tape_spk = take(bounded ? (size_t)L->spike_cap * 4 : 0);
   L->tape_evb = take(bounded ? (size_t)L->spike_cap * 8 : 0);
   L->tape_adm = take((size_t)L->event_cap);
-  L->bwd_ring = take(c->record_tape ? (size_t)L->R * BN * 4 : 0);
-  L->bwd_carry = take(c->record_tape ? BN * 4 : 0);
-  L->bwd_G = take(c->record_tape ? BN * 4 * kSplit * 2 : 0);  // kSplit partial queue terms per neuron, two step parities
+  const bool tape = c->record_tape != 0;
+  L->bwd_ring = take(tape && bounded ? (size_t)L->R * BN * 4 : 0);
+  L->bwd_carry = take(tape ? BN * 4 : 0);
+  L->bwd_G = take(tape && bounded ? BN * 4 : 0);
+  L->gwin = take(tape && !bounded ? (size_t)L->W * BN * 4 : 0);
+  L->Gacc = take(tape && !bounded ? (size_t)L->R * BN * 4 : 0);
+  L->gsum = take(tape && !bounded ? S * 4 : 0);
   L->total = o;
   return true;
 }
@@ -1087,10 +735,10 @@ void launch_reset(adseq* h, hipStream_t st) {
   const Dev& d = h->dev;
   const size_t BN = (size_t)d.BN;
   fill_u32(st, d.ctr, 0u, sizeof(Counters) / 4);
-  fill_u32(st, d.blk, 0u, (size_t)d.nblk * (kSplit + 1) * sizeof(BlkCtr) / 4);
+  fill_u32(st, d.blk, 0u, (size_t)d.nblk * sizeof(BlkCtr) / 4);
   fill_u32(st, d.V, 0u, BN);
   if (d.kind == ADSEQ_RING) {
-    fill_u32(st, d.ring, 0u, (size_t)d.R * BN);
+    fill_u32(st, d.win, 0u, (size_t)d.W * BN);
     fill_u32(st, d.spike_bits, 0u, (size_t)d.R * d.words * 2);
   } else {
     fill_u32(st, d.occ, 0u, BN);
@@ -1100,7 +748,6 @@ void launch_reset(adseq* h, hipStream_t st) {
   if (d.record) fill_u32(st, d.step_off, 0u, 2);  // step_off[0] = 0 (int64)
   h->next_step = 0;
   h->enq_calls = 0;
-  h->pending_fan = -1;
   h->tape_ok = d.record != 0;
 }
 
@@ -1110,9 +757,6 @@ void launch_neurons(adseq* h, hipStream_t st, long long n, int parity, const flo
   const Dev& d = h->dev;
   const dim3 grid(grid_for((size_t)d.BN)), block(kBlock);
   switch (d.kind) {
-    case ADSEQ_RING:
-      hipLaunchKernelGGL((k_neurons<ADSEQ_RING, LIF>), grid, block, 0, st, d, n, parity, i_ext, spikes_out, I_out);
-      break;
     case ADSEQ_FIFO:
       hipLaunchKernelGGL((k_neurons<ADSEQ_FIFO, LIF>), grid, block, 0, st, d, n, parity, i_ext, spikes_out, I_out);
       break;
@@ -1127,9 +771,6 @@ void launch_fanout(adseq* h, hipStream_t st, long long n, const int* spk, const 
   const Dev& d = h->dev;
   const dim3 grid(kFanoutBlocks), block(kBlock);
   switch (d.kind) {
-    case ADSEQ_RING:
-      hipLaunchKernelGGL((k_fanout<ADSEQ_RING>), grid, block, 0, st, d, n, spk, n_spk, parity, record);
-      break;
     case ADSEQ_FIFO:
       hipLaunchKernelGGL((k_fanout<ADSEQ_FIFO>), grid, block, 0, st, d, n, spk, n_spk, parity, record);
       hipLaunchKernelGGL((k_admit<ADSEQ_FIFO>), dim3(kAdmitBlocks), block, 0, st, d, parity);
@@ -1143,24 +784,18 @@ void launch_fanout(adseq* h, hipStream_t st, long long n, const int* spk, const 
 
 void mark(adseq* h, hipStream_t st, int kind);
 
-// RING: one launch = neuron update of step n_lif (if >= 0) + fan-out of step n_fan (if >= 0).
-void launch_ring_step(adseq* h, hipStream_t st, long long n_lif, long long n_fan, int record,
-                      const float* i_ext, unsigned char* spikes_out) {
+// RING: when step n opens a window, expands the events of the earlier spikes that arrive in it
+// (staging pass + per-part accumulation; the accumulation is skipped when nothing can be staged).
+void ring_open_window(adseq* h, hipStream_t st, long long n) {
   const Dev& d = h->dev;
-  const unsigned grid = (unsigned)((n_lif >= 0 ? d.nblk : 0) + (n_fan >= 0 ? d.nblk * kSplit : 0));
-  if (!grid) return;
+  if ((n & (long long)(d.W - 1)) != 0 || n <= 0) return;
   mark(h, st, -1);
-  if (record) hipLaunchKernelGGL((k_step_ring<true>), dim3(grid), dim3(kBlock), 0, st, d, n_lif, n_fan, i_ext, spikes_out);
-  else hipLaunchKernelGGL((k_step_ring<false>), dim3(grid), dim3(kBlock), 0, st, d, n_lif, n_fan, i_ext, spikes_out);
-  mark(h, st, 0);
-}
-
-// RING: launches the fan-out that is still riding, so that the queue state is complete.
-void flush_ring(adseq* h, hipStream_t st) {
-  if (h->dev.kind == ADSEQ_RING && h->pending_fan >= 0) {
-    launch_ring_step(h, st, -1, h->pending_fan, 0, nullptr, nullptr);
-    h->pending_fan = -1;
+  hipLaunchKernelGGL(k_win_bin, dim3((unsigned)d.NB), dim3(kBinThreads), 0, st, d, n);
+  if (d.cap > 0) {
+    const int parts = d.P < kMaxParts ? d.P : kMaxParts;
+    hipLaunchKernelGGL(k_win_acc, dim3((unsigned)parts), dim3(kBinThreads), 0, st, d, d.NB);
   }
+  mark(h, st, 0);
 }
 
 // Records an event that closes a launch of class `kind` (and opens the next one).
@@ -1184,8 +819,11 @@ int step_impl(adseq* h, long long step, const float* i_ext, unsigned char* spike
   const int record = (d.record && h->tape_ok && step < d.max_steps) ? 1 : 0;
   if (d.record && step >= d.max_steps) h->tape_ok = false;
   if (d.kind == ADSEQ_RING) {
-    launch_ring_step(h, st, step, h->pending_fan, record, i_ext, spikes_out);
-    h->pending_fan = step;
+    ring_open_window(h, st, step);
+    mark(h, st, -1);
+    if (record) hipLaunchKernelGGL((k_step_win<true>), dim3((unsigned)d.nblk), dim3(kBlock), 0, st, d, step, i_ext, spikes_out);
+    else hipLaunchKernelGGL((k_step_win<false>), dim3((unsigned)d.nblk), dim3(kBlock), 0, st, d, step, i_ext, spikes_out);
+    mark(h, st, 1);
   } else {
     mark(h, st, -1);
     launch_neurons<true>(h, st, step, parity, i_ext, spikes_out, nullptr);
@@ -1248,7 +886,15 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   d.delay_steps = cfg->delay_steps; d.delay_ms = cfg->delay_ms;
   d.ctr = (Counters*)(ws + L.ctr);
   d.blk = (BlkCtr*)(ws + L.blk); d.nblk = L.nblk; d.words = L.words;
-  d.V = (float*)(ws + L.V); d.ring = (int*)(ws + L.ring); d.spike_bits = (unsigned long long*)(ws + L.spike_bits);
+  d.V = (float*)(ws + L.V); d.spike_bits = (unsigned long long*)(ws + L.spike_bits);
+  d.W = L.W; d.wshift = L.wshift; d.tp_shift = L.tp_shift; d.P = L.P; d.NB = L.NB; d.cap = L.cap;
+  d.wgroups = L.wgroups;
+  d.win = (int*)(ws + L.win);
+  d.dstart = (unsigned*)(ws + L.dstart); d.nearcnt = (unsigned*)(ws + L.nearcnt);
+  d.perm = (unsigned*)(ws + L.perm); d.rowsum = (long long*)(ws + L.rowsum);
+  d.ebuf = (uint2*)(ws + L.ebuf); d.ecnt = (int*)(ws + L.ecnt);
+  d.tape_bits = (unsigned long long*)(ws + L.tape_bits);
+  d.gwin = (float*)(ws + L.gwin); d.Gacc = (float*)(ws + L.Gacc); d.gsum = (float*)(ws + L.gsum);
   d.slot_k = (unsigned*)(ws + L.slot_k); d.slot_a = (int*)(ws + L.slot_a);
   d.occ = (int*)(ws + L.occ); d.head = (int*)(ws + L.head); d.c_head = (int*)(ws + L.c_head);
   d.pool_p = (long long*)(ws + L.pool_p); d.pool_t = (long long*)(ws + L.pool_t);
@@ -1256,8 +902,7 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   d.pool_k = (unsigned*)(ws + L.pool_k); d.pool_a = (int*)(ws + L.pool_a);
   d.cur_spk = (int*)(ws + L.cur_spk);
   d.packed = (unsigned*)(ws + L.packed); d.a_q = (int*)(ws + L.a_q);
-  d.d1_ptr = (long long*)(ws + L.d1_ptr); d.d1_off = (unsigned*)(ws + L.d1_off);
-  d.amp = d.continuous ? (float*)(ws + L.amp) : nullptr;
+  d.amp = (d.continuous || d.kind == ADSEQ_RING) ? (float*)(ws + L.amp) : nullptr;
   d.fdec = d.continuous ? (float*)(ws + L.fdec) : nullptr;
   d.tapeU = (float*)(ws + L.tapeU); d.step_off = (long long*)(ws + L.step_off);
   d.tape_spk = (int*)(ws + L.tape_spk); d.tape_evb = (long long*)(ws + L.tape_evb);
@@ -1270,24 +915,31 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   ExpCoef ec;
   ec.c[0] = 1.0;
   for (int k = 1; k <= 20; ++k) ec.c[k] = ec.c[k - 1] / (double)k;
-  {
+  unsigned err = 0;
+  auto read_err = [&]() -> hipError_t {
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipMemcpyAsync(&err, &d.ctr->err, sizeof(err), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    return e;
+  };
+  hipError_t e = hipSuccess;
+  if (d.kind == ADSEQ_RING) {
+    // the rows are walked by the sort, so row_ptr is checked (and the result read) first
+    hipLaunchKernelGGL(k_check_rows, dim3((unsigned)grid_for((size_t)d.N)), dim3(kBlock), 0, st, d);
+    e = read_err();
+    if (e == hipSuccess && !err) {
+      const unsigned g = (unsigned)(d.N < 262144 ? d.N : 262144);
+      hipLaunchKernelGGL(k_sort_rows, dim3(g), dim3(kBlock), 0, st, d, ec);
+      e = read_err();
+    }
+  } else {
     size_t work = (size_t)(d.S > d.N ? d.S : d.N);
     size_t g = (work + kBlock - 1) / kBlock;
     if (g > 8192) g = 8192;
     if (g < 1) g = 1;
     hipLaunchKernelGGL(k_prepare, dim3((unsigned)g), dim3(kBlock), 0, st, d, ec);
-    if (d.kind == ADSEQ_RING) {
-      size_t gw = ((size_t)d.N * 64 + kBlock - 1) / kBlock;
-      if (gw > 16384) gw = 16384;
-      hipLaunchKernelGGL(k_d1_lists, dim3((unsigned)gw), dim3(kBlock), 0, st, d, 0);
-      hipLaunchKernelGGL(k_scan_rows, dim3(1), dim3(1024), 0, st, d.d1_ptr, (long long)d.N);
-      hipLaunchKernelGGL(k_d1_lists, dim3((unsigned)gw), dim3(kBlock), 0, st, d, 1);
-    }
+    e = read_err();
   }
-  unsigned err = 0;
-  hipError_t e = hipGetLastError();
-  if (e == hipSuccess) e = hipMemcpyAsync(&err, &d.ctr->err, sizeof(err), hipMemcpyDeviceToHost, st);
-  if (e == hipSuccess) e = hipStreamSynchronize(st);
   if (e != hipSuccess) { delete h; return ADSEQ_E_HIP; }
   if (err & ERR_GRAPH) { delete h; return ADSEQ_E_GRAPH; }
   if (err & ERR_DELAY) { delete h; return ADSEQ_E_DELAY_RANGE; }
@@ -1314,8 +966,13 @@ int adseq_deliver(adseq_t* h, int64_t step, float* I_out, void* stream) {
   if (step != h->next_step)
     return fail(h, ADSEQ_E_ORDER, "adseq_deliver: got step %lld, expected %lld", (long long)step, h->next_step);
   const int parity = (int)(h->enq_calls & 1);
-  flush_ring(h, (hipStream_t)stream);
-  launch_neurons<false>(h, (hipStream_t)stream, step, parity, nullptr, nullptr, I_out);
+  if (h->dev.kind == ADSEQ_RING) {
+    ring_open_window(h, (hipStream_t)stream, step);
+    hipLaunchKernelGGL(k_deliver_win, dim3((unsigned)h->dev.nblk), dim3(kBlock), 0, (hipStream_t)stream,
+                       h->dev, (long long)step, I_out);
+  } else {
+    launch_neurons<false>(h, (hipStream_t)stream, step, parity, nullptr, nullptr, I_out);
+  }
   h->next_step = step + 1;
   h->tape_ok = false;
   HIP_TRY(h, hipGetLastError());
@@ -1330,8 +987,11 @@ int adseq_enqueue(adseq_t* h, int64_t step, const int32_t* spike_ids, const int3
     return fail(h, ADSEQ_E_ORDER, "adseq_enqueue: got step %lld, expected %lld (the step last delivered)",
                 (long long)step, h->next_step - 1);
   const int parity = (int)(h->enq_calls & 1);
-  flush_ring(h, (hipStream_t)stream);
-  launch_fanout(h, (hipStream_t)stream, step, spike_ids, n_spikes, parity, 0);
+  if (h->dev.kind == ADSEQ_RING)
+    hipLaunchKernelGGL(k_enqueue_win, dim3(kFanoutBlocks), dim3(kBlock), 0, (hipStream_t)stream, h->dev,
+                       (long long)step, spike_ids, n_spikes);
+  else
+    launch_fanout(h, (hipStream_t)stream, step, spike_ids, n_spikes, parity, 0);
   h->enq_calls += 1;
   h->tape_ok = false;
   HIP_TRY(h, hipGetLastError());
@@ -1350,7 +1010,6 @@ int adseq_run(adseq_t* h, int64_t step0, int64_t n_steps, void* stream) {
     const int rc = step_impl(h, step0 + n, nullptr, nullptr, (hipStream_t)stream);
     if (rc != ADSEQ_OK) return rc;
   }
-  flush_ring(h, (hipStream_t)stream);
   HIP_TRY(h, hipGetLastError());
   return ADSEQ_OK;
 }
@@ -1363,44 +1022,47 @@ int adseq_backward(adseq_t* h, const float* dL_dcount, const float* dL_dU, float
   if (!d.record || !h->tape_ok)
     return fail(h, ADSEQ_E_NO_TAPE, "adseq_backward: no complete recorded forward run");
   hipStream_t st = (hipStream_t)stream;
-  flush_ring(h, st);
   unsigned err = 0;
   HIP_TRY(h, hipMemcpyAsync(&err, &d.ctr->err, sizeof(err), hipMemcpyDeviceToHost, st));
   HIP_TRY(h, hipStreamSynchronize(st));
   if (err & (ERR_TAPE_SPIKES | ERR_TAPE_EVENTS | ERR_POOL))
     return fail(h, ADSEQ_E_CAPACITY, "adseq_backward: tape or contender pool overflowed (bits %u)", err);
   const long long T = h->next_step;
-  fill_u32(st, grad_w, 0u, (size_t)d.S);
-  fill_u32(st, grad_d, 0u, (size_t)d.S);
-  fill_u32(st, d.bwd_ring, 0u, (size_t)d.R * d.BN);
-  fill_u32(st, d.bwd_carry, 0u, (size_t)d.BN);
   // gradient per unit the delay was given in: 1/tau per ms, dt/tau per step
   const float dscale = d.continuous ? (float)(1.0 / (double)d.tau) : (float)((double)d.dt / (double)d.tau);
   const dim3 block(kBlock), gn(grid_for((size_t)d.BN)), gg(kFanoutBlocks);
   const bool bounded = d.kind != ADSEQ_RING, atomic = d.B > 1;
+  fill_u32(st, d.bwd_carry, 0u, (size_t)d.BN);
   if (!bounded) {
-    // launch k: neuron update of step n (if any) + gather of step n - 1 (if any); T + 1 launches
-    for (long long n = T; n >= 0; --n) {
-      const long long n_neu = n < T ? n : -1, n_gat = n - 1;
-      const unsigned grid = (unsigned)((n_neu >= 0 ? d.nblk : 0) + (n_gat >= 0 ? d.nblk * kSplit : 0));
-      if (!grid) continue;
+    fill_u32(st, d.gsum, 0u, (size_t)d.S);
+    fill_u32(st, d.gwin, 0u, (size_t)d.W * d.BN);
+    fill_u32(st, d.Gacc, 0u, (size_t)d.R * d.BN);
+    // one launch per reverse step; when a step closes a window (n mod W = 0) the far queue terms
+    // of all earlier spikes that arrive in that window are gathered in one pass
+    const long long chunks_max = (long long)d.d_max * d.wgroups;
+    const unsigned gwin_grid = (unsigned)((chunks_max + kBlock / 64 - 1) / (kBlock / 64) < 4096
+                                              ? (chunks_max + kBlock / 64 - 1) / (kBlock / 64) : 4096);
+    for (long long n = T - 1; n >= 0; --n) {
       mark(h, st, -1);
-      if (atomic) hipLaunchKernelGGL((k_bwd_step_ring<true>), dim3(grid), block, 0, st, d, n_neu, n_gat, T, dscale, dL_dcount, dL_dU, grad_w, grad_d);
-      else hipLaunchKernelGGL((k_bwd_step_ring<false>), dim3(grid), block, 0, st, d, n_neu, n_gat, T, dscale, dL_dcount, dL_dU, grad_w, grad_d);
-      mark(h, st, 2);
+      hipLaunchKernelGGL(k_bwd_step_win, gn, block, 0, st, d, n, T, dL_dcount, dL_dU);
+      mark(h, st, 3);
+      if ((n & (long long)(d.W - 1)) == 0 && n > 0) {
+        hipLaunchKernelGGL(k_bwd_win, dim3(gwin_grid ? gwin_grid : 1u), block, 0, st, d, n, T);
+        mark(h, st, 2);
+      }
     }
+    const unsigned gf = (unsigned)(d.N < 65536 ? d.N : 65536);
+    hipLaunchKernelGGL(k_grad_finish, dim3(gf), block, 0, st, d, dscale, grad_w, grad_d);
     HIP_TRY(h, hipGetLastError());
     return ADSEQ_OK;
   }
+  fill_u32(st, grad_w, 0u, (size_t)d.S);
+  fill_u32(st, grad_d, 0u, (size_t)d.S);
+  fill_u32(st, d.bwd_ring, 0u, (size_t)d.R * d.BN);
   mark(h, st, -1);
   for (long long n = T - 1; n >= 0; --n) {
-    if (bounded) {
-      if (atomic) hipLaunchKernelGGL((k_bwd_gather<true, true>), gg, block, 0, st, d, n, T, dscale, grad_w, grad_d);
-      else hipLaunchKernelGGL((k_bwd_gather<true, false>), gg, block, 0, st, d, n, T, dscale, grad_w, grad_d);
-    } else {
-      if (atomic) hipLaunchKernelGGL((k_bwd_gather<false, true>), gg, block, 0, st, d, n, T, dscale, grad_w, grad_d);
-      else hipLaunchKernelGGL((k_bwd_gather<false, false>), gg, block, 0, st, d, n, T, dscale, grad_w, grad_d);
-    }
+    if (atomic) hipLaunchKernelGGL((k_bwd_gather<true>), gg, block, 0, st, d, n, T, dscale, grad_w, grad_d);
+    else hipLaunchKernelGGL((k_bwd_gather<false>), gg, block, 0, st, d, n, T, dscale, grad_w, grad_d);
     mark(h, st, 2);
     hipLaunchKernelGGL(k_bwd_neurons, gn, block, 0, st, d, n, dL_dcount, dL_dU);
     mark(h, st, 3);
@@ -1414,7 +1076,6 @@ int adseq_counters(adseq_t* h, int64_t* out8, void* stream) {
   Counters c;
   hipStream_t st = (hipStream_t)stream;
   const Dev& d = h->dev;
-  flush_ring(h, st);
   if (d.kind == ADSEQ_RING) {
     // the ring sums amplitudes, so delivered = offered - still in flight; the latter is counted
     // here, on demand, from the spike bits of the last d_max + 1 steps
@@ -1429,8 +1090,8 @@ int adseq_counters(adseq_t* h, int64_t* out8, void* stream) {
   out8[3] = c.sum_offered; out8[4] = c.sum_dropped; out8[5] = c.sum_delivered;
   out8[6] = c.tape_spikes; out8[7] = (int64_t)c.err;
   if (d.kind == ADSEQ_RING) {
-    // the fused step kernel keeps private counters per block: add them up here
-    const int nb = d.nblk * (kSplit + 1);
+    // the step kernel keeps private counters per block: add them up here
+    const int nb = d.nblk;
     BlkCtr* hb = new (std::nothrow) BlkCtr[nb];
     if (!hb) return fail(h, ADSEQ_E_INVALID_ARG, "adseq_counters: out of host memory");
     hipError_t e = hipMemcpyAsync(hb, d.blk, sizeof(BlkCtr) * nb, hipMemcpyDeviceToHost, st);

@@ -12,11 +12,11 @@ pytestmark = pytest.mark.gpu
 KINDS = {"ring": oracle.RING, "fifo": oracle.FIFO, "sorted": oracle.SORTED}
 
 
-def _compare_forward(wl, kind, cap, T=None, B=None, i_ext=None, check_sets=True):
+def _compare_forward(wl, kind, cap, T=None, B=None, i_ext=None, check_sets=True, **kw):
     T = wl.n_steps if T is None else T
     B = wl.batch if B is None else B
     ref = oracle.Run(wl, kind, cap, n_steps=T, batch=B, i_ext=i_ext, log_events=True, n_threads=8)
-    sim, out = H.run_gpu(wl, kind, cap, n_steps=T, batch=B, i_ext=i_ext)
+    sim, out = H.run_gpu(wl, kind, cap, n_steps=T, batch=B, i_ext=i_ext, **kw)
     np.testing.assert_array_equal(out["S"], ref.spikes)                 # raster, bit exact
     np.testing.assert_array_equal(out["U"].view(np.uint32), ref.U.view(np.uint32))  # membrane, bit exact
     if kind != oracle.RING:
@@ -67,6 +67,27 @@ def test_ragged_rows_batched(kind, cap, continuous):
     assert ref.spikes.sum() > 300
     if kind != "ring":
         assert ref.counters()["dropped"] > 1000
+
+
+@pytest.mark.parametrize("window", [2, 8, 16, 64])
+@pytest.mark.parametrize("stage", [0, 1, 700])
+def test_ring_window_length_and_staging_capacity(window, stage, monkeypatch):
+    """The ring's results depend neither on the window length nor on the capacity of the
+    staging buffer of the window expansion: default (everything staged), 1 event (every far
+    event takes the atomic fallback), 700 events (regions overflow: both routes mixed)."""
+    monkeypatch.setenv("ADSEQ_RING_WINDOW", str(window))
+    wl = synth.ragged_network(300, 700, 37, seed=5, rate_hz=300.0, t=150, b=3,
+                              w_mean=0.004, w_std=0.003)
+    ref, _ = _compare_forward(wl, oracle.RING, 0, step_event_capacity=stage)
+    assert ref.spikes.sum() > 300
+
+
+@pytest.mark.parametrize("window", [4, 32])
+def test_ring_backward_other_window_lengths(window, monkeypatch):
+    monkeypatch.setenv("ADSEQ_RING_WINDOW", str(window))
+    wl = synth.ragged_network(120, 300, 30, seed=12, rate_hz=300.0, t=150, b=2, continuous=True,
+                              w_mean=0.01, w_std=0.01)
+    _compare_backward(wl, oracle.RING, 0, 150, 2)
 
 
 def test_external_current_and_no_drive():
