@@ -13,9 +13,10 @@
 //                                           so that one slot of 64 consecutive targets is one line
 //   occ, head    i32   [BN]                 FIFO/SORTED: stored events; SORTED: index of the front
 //   c_head, pool_*                          per-step contender lists (one linked list per target)
-//   packed, a_q  u32/i32 [S]                synapses: (col << dbits | D) and Q8.24 amplitude
-//                                           (RING: every row sorted by D; else the caller's order)
-//   amp, fdec    fp32  [S]                  a = w f (RING or continuous delays) and f (continuous)
+//   packed, a_q  u32/i32 [S]                FIFO/SORTED synapses: (col << dbits | D) and Q8.24 amplitude
+//   synf, synb   2 x u32 [S]                RING synapses, every row sorted by D: {packed, Q8.24 amplitude}
+//                                           for the forward pass, {packed, fp32 amplitude} for the reverse
+//   amp, fdec    fp32  [S]                  continuous delays: a = w f (FIFO/SORTED) and f
 //   tape_*                                  membrane tape, spike list, admission flags
 //   bwd_*                                   FIFO/SORTED: adjoint delay line [R][BN], carry, queue term
 //   gwin, Gacc, gsum                        RING: adjoint rows of the window, far queue terms, per-synapse sums
@@ -78,8 +79,10 @@ struct Dev {
   int W, wshift;        // window length in steps (power of two) and its log2
   int tp_shift;         // log2 of the targets per part (W << tp_shift = cells of one LDS tile)
   int P, NB, cap;       // target parts, blocks of the staging pass, events per (part, block) region
-  int wgroups;          // 64-word groups per step in spike_bits
+  int wgroups;          // 8-word lines (64 bytes) per step in spike_bits
   int* win;             // [W][BN]
+  uint2* synf;          // [S] sorted rows: {col << dbits | D, Q8.24 amplitude}
+  uint2* synb;          // [S] sorted rows: {col << dbits | D, fp32 amplitude bits}
   unsigned* dstart;     // [N][d_max + 2]
   unsigned* nearcnt;    // [W + 1][N]
   unsigned* perm;       // [S]
@@ -556,6 +559,25 @@ struct adseq {
   long long enq_calls;   // parity source for the pool / spike counters
   bool tape_ok;          // every step since reset went through adseq_step with recording
   char err[256];
+  // RING: second stream for the old part of the window expansion / gather, and what the caller's
+  // stream still has to wait for
+  hipStream_t side = nullptr;
+  hipStream_t cap = nullptr;       // origin stream of graph captures
+  hipEvent_t ev_main = nullptr, ev_side = nullptr;
+  bool overlap = false;            // side stream in use
+  bool graphs = false;             // adseq_run / adseq_backward replay captured graphs
+  bool side_pending = false;       // ev_side marks side-stream work nobody has waited for yet
+  long long old_window = -1;       // window start whose old part has been launched (forward)
+  bool dry = false;                // host-state transitions only: nothing is launched
+  struct Graph {
+    int kind;                      // 0 forward run, 1 backward
+    long long a, b;                // forward: first step, steps; backward: steps
+    int flags;                     // forward: recording, old_window state
+    const void* ptr[4];            // backward: the caller's four arrays
+    hipGraph_t graph;
+    hipGraphExec_t exec;
+  };
+  std::vector<Graph> cache;
   // optional kernel timing (adseq_profile): one event after each bracketed launch
   bool prof = false;
   std::vector<hipEvent_t> evs;
@@ -567,7 +589,7 @@ namespace {
 
 struct Layout {
   size_t V, win, spike_bits, slot_k, slot_a, occ, head, c_head, pool_p, pool_t, pool_g, pool_next,
-      pool_k, pool_a, cur_spk, packed, a_q, dstart, nearcnt, perm, rowsum, ebuf, ecnt, amp, fdec, tapeU,
+      pool_k, pool_a, cur_spk, packed, a_q, synf, synb, dstart, nearcnt, perm, rowsum, ebuf, ecnt, amp, fdec, tapeU,
       tape_bits, step_off, tape_spk, tape_evb, tape_adm, bwd_ring, bwd_carry, bwd_G, gwin, Gacc, gsum, ctr,
       blk, total;
   long long spike_cap, event_cap, pool_cap;
@@ -575,16 +597,19 @@ struct Layout {
   int W, wshift, tp_shift, P, NB, cap, wgroups;  // RING
 };
 
-// Window length of the ring in steps: 16 unless ADSEQ_RING_WINDOW names another power of two
-// in 2..64 (a tuning knob: results do not depend on it).
-int ring_window_steps() {
-  int w = 16;
-  if (const char* e = getenv("ADSEQ_RING_WINDOW")) {
+// A power of two in [lo, hi] from the environment, else the default (tuning knobs of the ring:
+// results do not depend on them).
+int env_pow2(const char* name, int dflt, int lo, int hi) {
+  if (const char* e = getenv(name)) {
     const int v = atoi(e);
-    if (v >= 2 && v <= 64 && (v & (v - 1)) == 0) w = v;
+    if (v >= lo && v <= hi && (v & (v - 1)) == 0) return v;
   }
-  return w;
+  return dflt;
 }
+// Window length of the ring in steps.
+int ring_window_steps() { return env_pow2("ADSEQ_RING_WINDOW", 16, 2, 64); }
+// Cells (target, step) of the LDS tile of one target part.
+int ring_tile_cells() { return env_pow2("ADSEQ_RING_TILE", 4096, 1024, kMaxTileCells); }
 
 int bit_width(unsigned v) { int b = 0; while (v) { ++b; v >>= 1; } return b; }
 
@@ -641,13 +666,14 @@ bool make_layout(const adseq_config* c, Layout* L) {
   if (!bounded) {
     L->W = ring_window_steps();
     L->wshift = bit_width((unsigned)L->W) - 1;
-    L->tp_shift = bit_width((unsigned)kTileCells) - 1 - L->wshift;
+    L->tp_shift = bit_width((unsigned)ring_tile_cells()) - 1 - L->wshift;
     L->P = (int)((BN + ((size_t)1 << L->tp_shift) - 1) >> L->tp_shift);
-    L->wgroups = (L->words + 63) / 64;
-    // blocks of the staging pass: one 64-word chunk per wavefront when the history is full
-    const long long chunks = (long long)c->d_max_steps * L->wgroups;
-    long long nb = (chunks + kBinWaves - 1) / kBinWaves;
-    L->NB = (int)(nb < 1 ? 1 : (nb > kMaxBinBlocks ? kMaxBinBlocks : nb));
+    L->wgroups = (L->words + 7) / 8;
+    // blocks of the staging pass: about four 8-word lines per wavefront when the history is full
+    const long long lines = (long long)c->d_max_steps * L->wgroups;
+    long long nb = (lines + 4 * kBinWaves - 1) / (4 * kBinWaves);
+    nb = env_pow2("ADSEQ_RING_BINBLOCKS", (int)(nb < 1 ? 1 : (nb > kMaxBinBlocks ? kMaxBinBlocks : nb)), 1, kMaxBinBlocks);
+    L->NB = (int)nb;
     stage_parts = (size_t)(L->P < kMaxParts ? L->P : kMaxParts);
     // staging capacity in events: by default what a window holds when every neuron fires at
     // 1/32 per step, between 2^16 and 2^26 events
@@ -660,7 +686,7 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->ctr = take(sizeof(Counters));
   L->blk = take((size_t)L->nblk * sizeof(BlkCtr));  // RING: private counters of the step kernel's blocks
   L->V = take(BN * 4);
-  L->win = take(bounded ? 0 : (size_t)L->W * BN * 4);
+  L->win = take(bounded ? 0 : 2 * (size_t)L->W * BN * 4);
   L->spike_bits = take(bounded ? 0 : (size_t)L->R * L->words * 8);
   L->slot_k = take(bounded ? (size_t)c->capacity * BN * 4 : 0);
   L->slot_a = take(bounded ? (size_t)c->capacity * BN * 4 : 0);
@@ -674,15 +700,17 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->pool_k = take((size_t)L->pool_cap * 4);
   L->pool_a = take((size_t)L->pool_cap * 4);
   L->cur_spk = take(BN * 4);
-  L->packed = take(S * 4);
-  L->a_q = take(S * 4);
+  L->packed = take(bounded ? S * 4 : 0);
+  L->a_q = take(bounded ? S * 4 : 0);
+  L->synf = take(bounded ? 0 : S * 8);
+  L->synb = take(bounded ? 0 : S * 8);
   L->dstart = take(bounded ? 0 : (size_t)c->n_neurons * (c->d_max_steps + 2) * 4);
   L->nearcnt = take(bounded ? 0 : (size_t)(L->W + 1) * c->n_neurons * 4);
   L->perm = take(bounded ? 0 : S * 4);
   L->rowsum = take(bounded ? 0 : (size_t)c->n_neurons * 8);
   L->ebuf = take(bounded ? 0 : stage_parts * L->NB * (size_t)L->cap * 8);
   L->ecnt = take(bounded ? 0 : stage_parts * L->NB * 4);
-  L->amp = take((cont || !bounded) ? S * 4 : 0);
+  L->amp = take(cont && bounded ? S * 4 : 0);
   L->fdec = take(cont ? S * 4 : 0);
   const size_t T = c->record_tape ? (size_t)c->max_steps : 0;
   L->tapeU = take(T * BN * 4);
@@ -695,7 +723,7 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->bwd_ring = take(tape && bounded ? (size_t)L->R * BN * 4 : 0);
   L->bwd_carry = take(tape ? BN * 4 : 0);
   L->bwd_G = take(tape && bounded ? BN * 4 : 0);
-  L->gwin = take(tape && !bounded ? (size_t)L->W * BN * 4 : 0);
+  L->gwin = take(tape && !bounded ? 2 * (size_t)L->W * BN * 4 : 0);
   L->Gacc = take(tape && !bounded ? (size_t)L->R * BN * 4 : 0);
   L->gsum = take(tape && !bounded ? S * 4 : 0);
   L->total = o;
@@ -730,15 +758,19 @@ void fill_u32(hipStream_t st, void* p, unsigned v, size_t count) {
   hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)g), dim3(kBlock), 0, st, (unsigned*)p, v, count);
 }
 
+void join_side(adseq* h, hipStream_t st);
+
 // Clears the dynamic state (not the prepared synapses).
 void launch_reset(adseq* h, hipStream_t st) {
   const Dev& d = h->dev;
+  join_side(h, st);
+  h->old_window = -1;
   const size_t BN = (size_t)d.BN;
   fill_u32(st, d.ctr, 0u, sizeof(Counters) / 4);
   fill_u32(st, d.blk, 0u, (size_t)d.nblk * sizeof(BlkCtr) / 4);
   fill_u32(st, d.V, 0u, BN);
   if (d.kind == ADSEQ_RING) {
-    fill_u32(st, d.win, 0u, (size_t)d.W * BN);
+    fill_u32(st, d.win, 0u, 2 * (size_t)d.W * BN);
     fill_u32(st, d.spike_bits, 0u, (size_t)d.R * d.words * 2);
   } else {
     fill_u32(st, d.occ, 0u, BN);
@@ -784,16 +816,57 @@ void launch_fanout(adseq* h, hipStream_t st, long long n, const int* spk, const 
 
 void mark(adseq* h, hipStream_t st, int kind);
 
-// RING: when step n opens a window, expands the events of the earlier spikes that arrive in it
-// (staging pass + per-part accumulation; the accumulation is skipped when nothing can be staged).
-void ring_open_window(adseq* h, hipStream_t st, long long n) {
+// RING: makes `st` wait for whatever the side stream was last given.
+void join_side(adseq* h, hipStream_t st) {
+  if (h->side_pending && !h->dry) (void)hipStreamWaitEvent(st, h->ev_side, 0);
+  h->side_pending = false;
+}
+
+// RING: expansion of window [kw, kw + W) for the spikes of steps [n_lo, n_hi) on stream `st`.
+// staged: staging pass + per-part accumulation (the accumulation is skipped when nothing can be
+// staged); else one pass with plain atomics.
+void launch_expand(adseq* h, hipStream_t st, long long kw, long long n_lo, long long n_hi, bool staged) {
   const Dev& d = h->dev;
-  if ((n & (long long)(d.W - 1)) != 0 || n <= 0) return;
-  mark(h, st, -1);
-  hipLaunchKernelGGL(k_win_bin, dim3((unsigned)d.NB), dim3(kBinThreads), 0, st, d, n);
-  if (d.cap > 0) {
+  if (n_lo < 0) n_lo = 0;
+  if (n_lo < kw - d.d_max) n_lo = kw - d.d_max;
+  if (n_lo >= n_hi || h->dry) return;
+  if (staged && d.cap > 0) {
+    hipLaunchKernelGGL(k_win_bin, dim3((unsigned)d.NB), dim3(kBinThreads), 0, st, d, kw, n_lo, n_hi, 1);
     const int parts = d.P < kMaxParts ? d.P : kMaxParts;
-    hipLaunchKernelGGL(k_win_acc, dim3((unsigned)parts), dim3(kBinThreads), 0, st, d, d.NB);
+    hipLaunchKernelGGL(k_win_acc, dim3((unsigned)parts), dim3(kBinThreads), 0, st, d, kw, d.NB);
+  } else {
+    // one 8-word line per wavefront if the grid allows
+    const long long lines = (n_hi - n_lo) * d.wgroups;
+    long long nb = (lines + kBinWaves - 1) / kBinWaves;
+    nb = nb < 1 ? 1 : (nb > kMaxBinBlocks ? kMaxBinBlocks : nb);
+    hipLaunchKernelGGL(k_win_bin, dim3((unsigned)nb), dim3(kBinThreads), 0, st, d, kw, n_lo, n_hi, 0);
+  }
+}
+
+// RING: called before step k0 is popped when k0 opens a window (k0 mod W = 0).  The window's
+// events from spikes older than the previous window were expanded on the side stream while that
+// window ran (or are expanded here if they were not); those of the previous window's own spikes
+// are added now; then the old part of the next window is handed to the side stream.
+void ring_open_window(adseq* h, hipStream_t st, long long k0) {
+  const Dev& d = h->dev;
+  if ((k0 & (long long)(d.W - 1)) != 0 || k0 <= 0) return;
+  mark(h, st, -1);
+  if (h->old_window == k0) {
+    join_side(h, st);
+    launch_expand(h, st, k0, k0 - d.W, k0, false);
+  } else {
+    join_side(h, st);
+    launch_expand(h, st, k0, k0 - d.d_max, k0, true);
+  }
+  if (h->overlap && !h->prof && k0 + d.W - d.d_max < k0) {
+    if (!h->dry) {
+      (void)hipEventRecord(h->ev_main, st);
+      (void)hipStreamWaitEvent(h->side, h->ev_main, 0);
+    }
+    launch_expand(h, h->side, k0 + d.W, k0 + d.W - d.d_max, k0, true);
+    if (!h->dry) (void)hipEventRecord(h->ev_side, h->side);
+    h->side_pending = true;
+    h->old_window = k0 + d.W;
   }
   mark(h, st, 0);
 }
@@ -821,7 +894,8 @@ int step_impl(adseq* h, long long step, const float* i_ext, unsigned char* spike
   if (d.kind == ADSEQ_RING) {
     ring_open_window(h, st, step);
     mark(h, st, -1);
-    if (record) hipLaunchKernelGGL((k_step_win<true>), dim3((unsigned)d.nblk), dim3(kBlock), 0, st, d, step, i_ext, spikes_out);
+    if (h->dry) {}
+    else if (record) hipLaunchKernelGGL((k_step_win<true>), dim3((unsigned)d.nblk), dim3(kBlock), 0, st, d, step, i_ext, spikes_out);
     else hipLaunchKernelGGL((k_step_win<false>), dim3((unsigned)d.nblk), dim3(kBlock), 0, st, d, step, i_ext, spikes_out);
     mark(h, st, 1);
   } else {
@@ -833,7 +907,146 @@ int step_impl(adseq* h, long long step, const float* i_ext, unsigned char* spike
   }
   h->enq_calls += 1;
   h->next_step = step + 1;
-  HIP_TRY(h, hipGetLastError());
+  if (!h->dry) HIP_TRY(h, hipGetLastError());
+  return ADSEQ_OK;
+}
+
+// RING: n_steps closed-loop steps as one captured graph (kernel nodes of the caller-stream chain
+// and of the side-stream branch, joined at the end), replayed from a small cache when the same
+// run is asked for again.  Returns ADSEQ_OK, or a negative code with nothing launched and the
+// host state untouched, in which case the caller falls back to plain launches.
+int ring_run_graph(adseq* h, long long step0, long long n_steps, hipStream_t st) {
+  const Dev& d = h->dev;
+  const int record = (d.record && h->tape_ok) ? 1 : 0;
+  join_side(h, st);   // nothing from before the graph is left in flight beside it
+  const int flags = record | (h->old_window == ((step0 + d.W - 1) & ~(long long)(d.W - 1)) ? 2 : 0);
+  adseq::Graph* hit = nullptr;
+  for (auto& g : h->cache)
+    if (g.kind == 0 && g.a == step0 && g.b == n_steps && g.flags == flags) hit = &g;
+  // host-state snapshot, to roll back if the capture fails
+  const long long s_next = h->next_step, s_enq = h->enq_calls, s_old = h->old_window;
+  const bool s_tape = h->tape_ok;
+  int rc = ADSEQ_OK;
+  if (!hit) {
+    if (hipStreamBeginCapture(h->cap, hipStreamCaptureModeThreadLocal) != hipSuccess) return ADSEQ_E_HIP;
+    for (long long n = 0; n < n_steps && rc == ADSEQ_OK; ++n) rc = step_impl(h, step0 + n, nullptr, nullptr, h->cap);
+    join_side(h, h->cap);
+    hipGraph_t graph = nullptr;
+    hipError_t e = hipStreamEndCapture(h->cap, &graph);
+    hipGraphExec_t exec = nullptr;
+    if (e == hipSuccess && rc == ADSEQ_OK) e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    if (e != hipSuccess || rc != ADSEQ_OK) {
+      if (graph) (void)hipGraphDestroy(graph);
+      (void)hipGetLastError();
+      h->next_step = s_next; h->enq_calls = s_enq; h->old_window = s_old; h->tape_ok = s_tape;
+      h->side_pending = false;
+      return rc != ADSEQ_OK ? rc : ADSEQ_E_HIP;
+    }
+    if (h->cache.size() >= 8) {
+      (void)hipGraphExecDestroy(h->cache.front().exec);
+      (void)hipGraphDestroy(h->cache.front().graph);
+      h->cache.erase(h->cache.begin());
+    }
+    adseq::Graph g{};
+    g.kind = 0; g.a = step0; g.b = n_steps; g.flags = flags; g.graph = graph; g.exec = exec;
+    h->cache.push_back(g);
+    hit = &h->cache.back();
+  } else {
+    h->dry = true;
+    for (long long n = 0; n < n_steps && rc == ADSEQ_OK; ++n) rc = step_impl(h, step0 + n, nullptr, nullptr, st);
+    join_side(h, st);
+    h->dry = false;
+    if (rc != ADSEQ_OK) return rc;
+  }
+  if (hipGraphLaunch(hit->exec, st) != hipSuccess) return fail(h, ADSEQ_E_HIP, "hipGraphLaunch failed");
+  return ADSEQ_OK;
+}
+
+// RING: far gather of window [kw, kw + W) for the recorded spikes of steps [n_lo, n_hi).
+void launch_bwd_win(adseq* h, hipStream_t st, long long kw, long long n_lo, long long n_hi, long long T) {
+  const Dev& d = h->dev;
+  if (n_lo < 0) n_lo = 0;
+  if (n_lo < kw - d.d_max) n_lo = kw - d.d_max;
+  if (n_lo >= n_hi) return;
+  // about four 8-word lines per wavefront
+  const long long lines = (n_hi - n_lo) * d.wgroups;
+  long long g = (lines + 15) / 16;
+  g = g < 1 ? 1 : (g > 8192 ? 8192 : g);
+  hipLaunchKernelGGL(k_bwd_win, dim3((unsigned)g), dim3(kBlock), 0, st, d, kw, n_lo, n_hi, T);
+}
+
+// RING: the whole reverse sweep on `st` (and, for the old part of every window's far gather, on
+// the side stream, joined before the gradients are finished).  One launch per reverse step; when
+// a step closes a window (n mod W = 0) the far queue terms of the earlier spikes that arrive in
+// that window are gathered: those of the W steps swept next at once, the older ones beside them.
+void ring_backward_launch(adseq* h, hipStream_t st, long long T, float dscale, const float* dL_dcount,
+                          const float* dL_dU, float* grad_w, float* grad_d) {
+  const Dev& d = h->dev;
+  const dim3 block(kBlock), gn(grid_for((size_t)d.BN));
+  const bool split = h->overlap && !h->prof && d.d_max > d.W;
+  fill_u32(st, d.bwd_carry, 0u, (size_t)d.BN);
+  fill_u32(st, d.gsum, 0u, (size_t)d.S);
+  fill_u32(st, d.gwin, 0u, 2 * (size_t)d.W * d.BN);
+  fill_u32(st, d.Gacc, 0u, (size_t)d.R * d.BN);
+  for (long long n = T - 1; n >= 0; --n) {
+    mark(h, st, -1);
+    hipLaunchKernelGGL(k_bwd_step_win, gn, block, 0, st, d, n, T, dL_dcount, dL_dU);
+    mark(h, st, 3);
+    if ((n & (long long)(d.W - 1)) == 0 && n > 0) {
+      if (!split) {
+        launch_bwd_win(h, st, n, n - d.d_max, n, T);
+      } else {
+        join_side(h, st);                      // old part of the window swept before this one
+        (void)hipEventRecord(h->ev_main, st);  // rows of this window are complete
+        launch_bwd_win(h, st, n, n - d.W, n, T);
+        (void)hipStreamWaitEvent(h->side, h->ev_main, 0);
+        launch_bwd_win(h, h->side, n, n - d.d_max, n - d.W, T);
+        (void)hipEventRecord(h->ev_side, h->side);
+        h->side_pending = true;
+      }
+      mark(h, st, 2);
+    }
+  }
+  join_side(h, st);
+  const unsigned gf = (unsigned)(d.N < 65536 ? d.N : 65536);
+  hipLaunchKernelGGL(k_grad_finish, dim3(gf), block, 0, st, d, dscale, grad_w, grad_d);
+}
+
+int ring_backward_graph(adseq* h, hipStream_t st, long long T, float dscale, const float* dL_dcount,
+                        const float* dL_dU, float* grad_w, float* grad_d) {
+  adseq::Graph* hit = nullptr;
+  for (auto& g : h->cache)
+    if (g.kind == 1 && g.a == T && g.ptr[0] == dL_dcount && g.ptr[1] == dL_dU && g.ptr[2] == grad_w &&
+        g.ptr[3] == grad_d)
+      hit = &g;
+  if (!hit) {
+    if (hipStreamBeginCapture(h->cap, hipStreamCaptureModeThreadLocal) != hipSuccess) {
+      (void)hipGetLastError();
+      return ADSEQ_E_HIP;
+    }
+    ring_backward_launch(h, h->cap, T, dscale, dL_dcount, dL_dU, grad_w, grad_d);
+    hipGraph_t graph = nullptr;
+    hipError_t e = hipStreamEndCapture(h->cap, &graph);
+    hipGraphExec_t exec = nullptr;
+    if (e == hipSuccess) e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    h->side_pending = false;
+    if (e != hipSuccess) {
+      if (graph) (void)hipGraphDestroy(graph);
+      (void)hipGetLastError();
+      return ADSEQ_E_HIP;
+    }
+    if (h->cache.size() >= 8) {
+      (void)hipGraphExecDestroy(h->cache.front().exec);
+      (void)hipGraphDestroy(h->cache.front().graph);
+      h->cache.erase(h->cache.begin());
+    }
+    adseq::Graph g{};
+    g.kind = 1; g.a = T; g.ptr[0] = dL_dcount; g.ptr[1] = dL_dU; g.ptr[2] = grad_w; g.ptr[3] = grad_d;
+    g.graph = graph; g.exec = exec;
+    h->cache.push_back(g);
+    hit = &h->cache.back();
+  }
+  if (hipGraphLaunch(hit->exec, st) != hipSuccess) { (void)hipGetLastError(); return ADSEQ_E_HIP; }
   return ADSEQ_OK;
 }
 
@@ -902,7 +1115,8 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   d.pool_k = (unsigned*)(ws + L.pool_k); d.pool_a = (int*)(ws + L.pool_a);
   d.cur_spk = (int*)(ws + L.cur_spk);
   d.packed = (unsigned*)(ws + L.packed); d.a_q = (int*)(ws + L.a_q);
-  d.amp = (d.continuous || d.kind == ADSEQ_RING) ? (float*)(ws + L.amp) : nullptr;
+  d.amp = (d.continuous && d.kind != ADSEQ_RING) ? (float*)(ws + L.amp) : nullptr;
+  d.synf = (uint2*)(ws + L.synf); d.synb = (uint2*)(ws + L.synb);
   d.fdec = d.continuous ? (float*)(ws + L.fdec) : nullptr;
   d.tapeU = (float*)(ws + L.tapeU); d.step_off = (long long*)(ws + L.step_off);
   d.tape_spk = (int*)(ws + L.tape_spk); d.tape_evb = (long long*)(ws + L.tape_evb);
@@ -943,13 +1157,36 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   if (e != hipSuccess) { delete h; return ADSEQ_E_HIP; }
   if (err & ERR_GRAPH) { delete h; return ADSEQ_E_GRAPH; }
   if (err & ERR_DELAY) { delete h; return ADSEQ_E_DELAY_RANGE; }
+  if (d.kind == ADSEQ_RING) {
+    // the ring overlaps the old part of each window's expansion with the steps of the window
+    // before it on a stream of its own (default priority), and replays whole runs as graphs;
+    // ADSEQ_RING_OVERLAP=0 / ADSEQ_RING_GRAPH=0 switch either off (results are the same)
+    const char* ov = getenv("ADSEQ_RING_OVERLAP");
+    const char* gr = getenv("ADSEQ_RING_GRAPH");
+    h->overlap = !(ov && ov[0] == '0');
+    h->graphs = !(gr && gr[0] == '0');
+    hipError_t es = hipSuccess;
+    if (h->overlap || h->graphs) {
+      es = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking);
+      if (es == hipSuccess) es = hipStreamCreateWithFlags(&h->cap, hipStreamNonBlocking);
+      if (es == hipSuccess) es = hipEventCreateWithFlags(&h->ev_main, hipEventDisableTiming);
+      if (es == hipSuccess) es = hipEventCreateWithFlags(&h->ev_side, hipEventDisableTiming);
+    }
+    if (es != hipSuccess) { adseq_destroy(h); return ADSEQ_E_HIP; }
+  }
   *out = h;
   return ADSEQ_OK;
 }
 
 int adseq_destroy(adseq_t* h) {
   if (!h) return ADSEQ_E_INVALID_ARG;
+  if (h->side) (void)hipStreamSynchronize(h->side);
+  for (auto& g : h->cache) { (void)hipGraphExecDestroy(g.exec); (void)hipGraphDestroy(g.graph); }
   for (hipEvent_t e : h->evs) (void)hipEventDestroy(e);
+  if (h->ev_main) (void)hipEventDestroy(h->ev_main);
+  if (h->ev_side) (void)hipEventDestroy(h->ev_side);
+  if (h->side) (void)hipStreamDestroy(h->side);
+  if (h->cap) (void)hipStreamDestroy(h->cap);
   delete h;
   return ADSEQ_OK;
 }
@@ -1006,6 +1243,14 @@ int adseq_step(adseq_t* h, int64_t step, const float* i_ext, uint8_t* spikes_out
 int adseq_run(adseq_t* h, int64_t step0, int64_t n_steps, void* stream) {
   if (!h) return ADSEQ_E_INVALID_ARG;
   if (n_steps < 0) return fail(h, ADSEQ_E_INVALID_ARG, "adseq_run: negative step count");
+  if (step0 != h->next_step)
+    return fail(h, ADSEQ_E_ORDER, "adseq_run: got step %lld, expected %lld", (long long)step0, h->next_step);
+  if (h->dev.kind == ADSEQ_RING && h->graphs && !h->prof && n_steps >= 32 &&
+      (!h->dev.record || !h->tape_ok || step0 + n_steps <= h->dev.max_steps)) {
+    const int rc = ring_run_graph(h, step0, n_steps, (hipStream_t)stream);
+    if (rc == ADSEQ_OK) return rc;
+    if (h->next_step != step0) return rc;   // the graph was launched in part: not recoverable here
+  }
   for (int64_t n = 0; n < n_steps; ++n) {
     const int rc = step_impl(h, step0 + n, nullptr, nullptr, (hipStream_t)stream);
     if (rc != ADSEQ_OK) return rc;
@@ -1032,30 +1277,16 @@ int adseq_backward(adseq_t* h, const float* dL_dcount, const float* dL_dU, float
   const float dscale = d.continuous ? (float)(1.0 / (double)d.tau) : (float)((double)d.dt / (double)d.tau);
   const dim3 block(kBlock), gn(grid_for((size_t)d.BN)), gg(kFanoutBlocks);
   const bool bounded = d.kind != ADSEQ_RING, atomic = d.B > 1;
-  fill_u32(st, d.bwd_carry, 0u, (size_t)d.BN);
   if (!bounded) {
-    fill_u32(st, d.gsum, 0u, (size_t)d.S);
-    fill_u32(st, d.gwin, 0u, (size_t)d.W * d.BN);
-    fill_u32(st, d.Gacc, 0u, (size_t)d.R * d.BN);
-    // one launch per reverse step; when a step closes a window (n mod W = 0) the far queue terms
-    // of all earlier spikes that arrive in that window are gathered in one pass
-    const long long chunks_max = (long long)d.d_max * d.wgroups;
-    const unsigned gwin_grid = (unsigned)((chunks_max + kBlock / 64 - 1) / (kBlock / 64) < 4096
-                                              ? (chunks_max + kBlock / 64 - 1) / (kBlock / 64) : 4096);
-    for (long long n = T - 1; n >= 0; --n) {
-      mark(h, st, -1);
-      hipLaunchKernelGGL(k_bwd_step_win, gn, block, 0, st, d, n, T, dL_dcount, dL_dU);
-      mark(h, st, 3);
-      if ((n & (long long)(d.W - 1)) == 0 && n > 0) {
-        hipLaunchKernelGGL(k_bwd_win, dim3(gwin_grid ? gwin_grid : 1u), block, 0, st, d, n, T);
-        mark(h, st, 2);
-      }
-    }
-    const unsigned gf = (unsigned)(d.N < 65536 ? d.N : 65536);
-    hipLaunchKernelGGL(k_grad_finish, dim3(gf), block, 0, st, d, dscale, grad_w, grad_d);
+    join_side(h, st);
+    if (h->graphs && !h->prof && T >= 32 && ring_backward_graph(h, st, T, dscale, dL_dcount, dL_dU, grad_w, grad_d) == ADSEQ_OK)
+      return ADSEQ_OK;
+    ring_backward_launch(h, st, T, dscale, dL_dcount, dL_dU, grad_w, grad_d);
+    join_side(h, st);
     HIP_TRY(h, hipGetLastError());
     return ADSEQ_OK;
   }
+  fill_u32(st, d.bwd_carry, 0u, (size_t)d.BN);
   fill_u32(st, grad_w, 0u, (size_t)d.S);
   fill_u32(st, grad_d, 0u, (size_t)d.S);
   fill_u32(st, d.bwd_ring, 0u, (size_t)d.R * d.BN);
@@ -1076,6 +1307,7 @@ int adseq_counters(adseq_t* h, int64_t* out8, void* stream) {
   Counters c;
   hipStream_t st = (hipStream_t)stream;
   const Dev& d = h->dev;
+  join_side(h, st);
   if (d.kind == ADSEQ_RING) {
     // the ring sums amplitudes, so delivered = offered - still in flight; the latter is counted
     // here, on demand, from the spike bits of the last d_max + 1 steps

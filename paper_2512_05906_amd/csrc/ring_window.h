@@ -2,7 +2,8 @@
 // anonymous namespace, after Dev and the device helpers.
 //
 // Time is cut into windows of W steps (W a power of two).  The queue state is
-//   win        i32 [W][BN]   Q8.24 sums of the events that arrive inside the current window,
+//   win        i32 [2][W][BN] Q8.24 sums of the events that arrive inside the current window
+//                            (buffer (n / W) & 1) and, being prepared, inside the next one,
 //   spike_bits u64 [R][words] the spikes of the last R = d_max + 1 steps,
 // and the synapse rows, re-ordered at create so that every row is ascending in its arrival
 // offset D, with dstart[i][D] = position in row i of the first entry with offset >= D.
@@ -19,8 +20,13 @@
 // events into a 64 KB LDS tile with LDS atomics and adds the tile to win with coalesced
 // accesses.  Events that do not fit their region fall back to a global atomic on win, so the
 // result never depends on the staging capacity.
+// The expansion of window q + 1 is split in two: the spikes older than window q ("old part", 15/16
+// of the events for W = 16, d_max = 250) are expanded on a second stream while the steps of
+// window q run; the spikes of window q itself ("recent part") follow at the boundary with plain
+// atomics.  Hence the two window buffers.
 //
-// The reverse sweep mirrors it: gwin f32 [W][BN] holds the adjoint rows of the current window;
+// The reverse sweep mirrors it: gwin f32 [2][W][BN] holds the adjoint rows of the current window
+// and of the one swept before it (still being read by the old part of its gather);
 // a spike's queue term is the sum of a near part (gathered by the step kernel) and one far part
 // per later window (gathered by k_bwd_win from the 6.4 MB window, which the L2 holds, into
 // Gacc[n mod R][g]); the per-synapse sum of gathered adjoints goes to gsum in sorted order and is
@@ -28,10 +34,9 @@
 
 constexpr int kBinThreads = 1024;   // threads per block of k_win_bin / k_win_acc
 constexpr int kBinWaves = kBinThreads / 64;
-constexpr int kTileCells = 16384;   // cells (target, row) per LDS tile = 64 KB
+constexpr int kMaxTileCells = 16384; // cells (target, row) of the largest LDS tile = 64 KB
 constexpr int kMaxParts = 4096;     // LDS cursors of k_win_bin; targets beyond them use atomics
 constexpr int kMaxBinBlocks = 512;
-static_assert(kMaxBinBlocks <= 16 * kBinWaves * 4 && kMaxBinBlocks % (kBinWaves * 4) == 0, "k_win_acc keeps one run count per lane");
 
 // ---------------------------------------------------------------- create: sorted rows
 
@@ -81,7 +86,8 @@ __global__ __launch_bounds__(kBlock) void k_check_rows(Dev d) {
 }
 
 // One block per row: counting sort of the row by arrival offset.  Writes the sorted synapse
-// arrays (packed, a_q, amp, fdec), perm (sorted position -> position in the caller's row),
+// arrays (synf = {packed, Q8.24 amplitude} for the forward pass, synb = {packed, fp32 amplitude}
+// for the reverse sweep, fdec), perm (sorted position -> position in the caller's row),
 // dstart, nearcnt and the row's Q8.24 amplitude sum.
 __global__ __launch_bounds__(kBlock) void k_sort_rows(Dev d, ExpCoef ec) {
   __shared__ unsigned s_hist[1026];
@@ -136,9 +142,9 @@ __global__ __launch_bounds__(kBlock) void k_sort_rows(Dev d, ExpCoef ec) {
       int c = d.col[p];
       if (c < 0 || c >= d.N) c = 0;
       const long long q = r0 + atomicAdd(&s_hist[s.D], 1u);
-      d.packed[q] = ((unsigned)c << d.dbits) | (unsigned)s.D;
-      d.a_q[q] = s.a_q;
-      d.amp[q] = s.amp;
+      const unsigned pk = ((unsigned)c << d.dbits) | (unsigned)s.D;
+      d.synf[q] = make_uint2(pk, (unsigned)s.a_q);
+      d.synb[q] = make_uint2(pk, __float_as_uint(s.amp));
       if (d.continuous) d.fdec[q] = s.f;
       d.perm[q] = (unsigned)(p - r0);
       sum += s.a_q;
@@ -157,15 +163,23 @@ __global__ __launch_bounds__(kBlock) void k_sort_rows(Dev d, ExpCoef ec) {
 
 // ---------------------------------------------------------------- forward: one launch per step
 
+// Window buffer that holds arrival step k.
+__device__ __forceinline__ int* win_of(const Dev& d, long long k) {
+  return d.win + (size_t)((k >> d.wshift) & 1) * d.W * d.BN;
+}
+__device__ __forceinline__ float* gwin_of(const Dev& d, long long k) {
+  return d.gwin + (size_t)((k >> d.wshift) & 1) * d.W * d.BN;
+}
+
 // Adds the entries [0, cnt) of the sorted row at pr0 (arrival offsets 1 .. W - 1 - phi) of a
 // spike of trial base / N to the rows phi + D of the window.  Whole wavefront.
-__device__ __forceinline__ void near_scatter(const Dev& d, int phi, long long pr0, unsigned cnt, int base) {
+__device__ __forceinline__ void near_scatter(const Dev& d, int* __restrict__ win, int phi, long long pr0,
+                                             unsigned cnt, int base) {
   const int lane = threadIdx.x & 63;
   for (unsigned q = lane; q < cnt; q += 64) {
-    const unsigned pk = d.packed[pr0 + q];
-    const int a = d.a_q[pr0 + q];
-    const int D = (int)(pk & d.dmask);
-    atomicAdd(&d.win[(size_t)(phi + D) * d.BN + (size_t)base + (pk >> d.dbits)], a);
+    const uint2 e = d.synf[pr0 + q];
+    const int D = (int)(e.x & d.dmask);
+    atomicAdd(&win[(size_t)(phi + D) * d.BN + (size_t)base + (e.x >> d.dbits)], (int)e.y);
   }
 }
 
@@ -185,16 +199,17 @@ __global__ __launch_bounds__(kBlock) void k_step_win(Dev d, long long n, const f
   bool s = false;
   long long r0 = 0;
   unsigned ncnt = 0;
+  int* __restrict__ win = win_of(d, n);
   if (act) {
     b = g / d.N; i = g - b * d.N;
     const size_t idx = (size_t)phi * d.BN + g;
-    acc = d.win[idx];
+    acc = win[idx];
     // row start and in-window entry count of every neuron, loaded beside the pop so that a
     // spiking neuron's fan-out does not wait for them (both arrays stay in the L2)
     r0 = d.row_ptr[i];
     if (near_h >= 1) ncnt = d.nearcnt[(size_t)near_h * d.N + i];
     const float v = d.V[g];
-    if (acc != 0) d.win[idx] = 0;
+    if (acc != 0) win[idx] = 0;
     float I = (float)acc * 0x1p-24f;
     if (d.p_thresh) {
       const bool xi = (unsigned long long)drive_bits(d.seed, (unsigned long long)g,
@@ -220,7 +235,7 @@ __global__ __launch_bounds__(kBlock) void k_step_win(Dev d, long long n, const f
   while (m) {
     const int L = __ffsll((long long)m) - 1;
     m &= m - 1;
-    near_scatter(d, phi, __shfl(r0, L, 64), __shfl(ncnt, L, 64), __shfl(b, L, 64) * d.N);
+    near_scatter(d, win, phi, __shfl(r0, L, 64), __shfl(ncnt, L, 64), __shfl(b, L, 64) * d.N);
   }
   const long long sp = wave_sum((long long)acc);
   const long long ns = wave_sum((long long)(s ? 1 : 0));
@@ -248,10 +263,11 @@ __global__ __launch_bounds__(kBlock) void k_deliver_win(Dev d, long long n, floa
   const int g = blockIdx.x * kBlock + threadIdx.x;
   const int phi = (int)(n & (long long)(d.W - 1));
   int acc = 0;
+  int* __restrict__ win = win_of(d, n);
   if (g < d.BN) {
     const size_t idx = (size_t)phi * d.BN + g;
-    acc = d.win[idx];
-    if (acc != 0) d.win[idx] = 0;
+    acc = win[idx];
+    if (acc != 0) win[idx] = 0;
     I_out[g] = (float)acc * 0x1p-24f;
   }
   if ((threadIdx.x & 63) == 0)
@@ -280,7 +296,7 @@ __global__ __launch_bounds__(kBlock) void k_enqueue_win(Dev d, long long n, cons
       atomicOr(&d.spike_bits[(size_t)(n % d.R) * d.words + (g >> 6)], 1ull << (g & 63));
       c_off += d.row_ptr[i + 1] - r0; s_off += d.rowsum[i];
     }
-    if (near_h >= 1) near_scatter(d, phi, r0, d.nearcnt[(size_t)near_h * d.N + i], b * d.N);
+    if (near_h >= 1) near_scatter(d, win_of(d, n), phi, r0, d.nearcnt[(size_t)near_h * d.N + i], b * d.N);
   }
   block_add2(&d.ctr->offered, c_off, &d.ctr->sum_offered, s_off);
 }
@@ -289,8 +305,8 @@ __global__ __launch_bounds__(kBlock) void k_enqueue_win(Dev d, long long n, cons
 
 // One far event of the window: staged in region (part, block) if there is room, else added to
 // win with a global atomic.
-__device__ __forceinline__ void stage_event(const Dev& d, int* s_cur, int nparts, unsigned pk, int a,
-                                            int dlo, int base) {
+__device__ __forceinline__ void stage_event(const Dev& d, int* __restrict__ win, int* s_cur, int nparts,
+                                            unsigned pk, int a, int dlo, int base) {
   const int r = (int)(pk & d.dmask) - dlo;             // row of the window, 0 .. W - 1
   const int gt = base + (int)(pk >> d.dbits);
   const int part = gt >> d.tp_shift;
@@ -302,29 +318,52 @@ __device__ __forceinline__ void stage_event(const Dev& d, int* s_cur, int nparts
       return;
     }
   }
-  atomicAdd(&d.win[(size_t)r * d.BN + gt], a);
+  atomicAdd(&win[(size_t)r * d.BN + gt], a);
 }
 
-// Pass 1 of the expansion of window [k0, k0 + W): walks the spike bits of steps
-// [k0 - d_max, k0) in chunks of 64 words (one chunk per wavefront, chunks dealt round-robin
-// to the blocks so that every block sees every step), and for each spike reads the piece of its
-// sorted row that lands in the window (up to 8 row loads in flight per wavefront) and stages the
-// events by target part.  gridDim.x must be d.NB.
-__global__ __launch_bounds__(kBinThreads) void k_win_bin(Dev d, long long k0) {
+// A wavefront's share of a walk over the spike words of steps [n_lo, n_hi): the words of a step
+// are cut into lines of 8 (64 bytes); the line numbered c = gw + nwaves * (8 t + group) belongs
+// to the 8-lane group `group` of wavefront gw in trip t, so that lines are dealt round-robin over
+// all wavefronts and one wavefront sees up to 8 lines of different steps at once.  Sets the step
+// and the spike word of this lane (0 if it has none).
+__device__ __forceinline__ unsigned long long walk_word(const Dev& d, const unsigned long long* __restrict__ words,
+                                                        bool circular, long long n_lo, long long n_hi,
+                                                        long long c0, long long nwaves, long long* n_out,
+                                                        int* word_out) {
+  const int lane = threadIdx.x & 63;
+  const long long lps = (d.words + 7) >> 3;
+  const long long c = c0 + nwaves * (lane >> 3);
+  *n_out = n_lo; *word_out = 0;
+  if (c >= (n_hi - n_lo) * lps) return 0ull;
+  const long long si = c / lps;
+  const long long n = n_lo + si;
+  const int word = (int)(c - si * lps) * 8 + (lane & 7);
+  *n_out = n; *word_out = word;
+  if (word >= d.words) return 0ull;
+  return words[(size_t)(circular ? n % d.R : n) * d.words + word];
+}
+
+// Pass 1 of the expansion of window [k0, k0 + W) for the spikes of steps [n_lo, n_hi), with
+// k0 - d_max <= n_lo and n_hi <= k0.  Every lane that holds a spike looks up the piece of the
+// spike's sorted row that lands in the window (dstart); the wavefront then reads the pieces four
+// at a time (8 full-width loads in flight) and stages the events by target part.  stage = 0:
+// every event is added to the window with a global atomic instead.  With stage != 0, gridDim.x
+// must be d.NB (the staging regions are per block).
+__global__ __launch_bounds__(kBinThreads) void k_win_bin(Dev d, long long k0, long long n_lo, long long n_hi,
+                                                         int stage) {
   __shared__ int s_cur[kMaxParts];
-  const int nparts = d.cap > 0 ? (d.P < kMaxParts ? d.P : kMaxParts) : 0;
+  const int nparts = (stage && d.cap > 0) ? (d.P < kMaxParts ? d.P : kMaxParts) : 0;
+  int* __restrict__ win = win_of(d, k0);
   for (int x = threadIdx.x; x < nparts; x += kBinThreads) s_cur[x] = 0;
   __syncthreads();
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const long long n_lo = k0 > d.d_max ? k0 - d.d_max : 0;
-  const long long nchunks = (k0 - n_lo) * d.wgroups;
+  const long long gw = blockIdx.x + (long long)gridDim.x * wv;   // blocks interleaved: every block sees every step
+  const long long nwaves = (long long)gridDim.x * kBinWaves;
+  const long long nlines = (n_hi - n_lo) * ((d.words + 7) >> 3);
   const int nb = d.d_max + 2;
-  for (long long c = blockIdx.x + (long long)gridDim.x * wv; c < nchunks; c += (long long)gridDim.x * kBinWaves) {
-    const long long si = c / d.wgroups;
-    const int wg = (int)(c - si * d.wgroups);
-    const long long n = n_lo + si;
-    const int word = wg * 64 + lane;
-    unsigned long long bits = word < d.words ? d.spike_bits[(size_t)(n % d.R) * d.words + word] : 0ull;
+  for (long long c0 = gw; c0 < nlines; c0 += nwaves * 8) {
+    long long n; int word;
+    unsigned long long bits = walk_word(d, d.spike_bits, true, n_lo, n_hi, c0, nwaves, &n, &word);
     const int dlo = (int)(k0 - n);                      // 1 .. d_max
     const int dhi = dlo + d.W < nb - 1 ? dlo + d.W : nb - 1;
     while (__ballot(bits != 0ull)) {
@@ -346,25 +385,30 @@ __global__ __launch_bounds__(kBinThreads) void k_win_bin(Dev d, long long k0) {
         int L[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) { L[j] = -1; if (todo) { L[j] = __ffsll((long long)todo) - 1; todo &= todo - 1; } }
-        long long P0[4]; int LEN[4], BASE[4];
-        unsigned pk[4][2]; int aq[4][2];
+        long long P0[4]; int LEN[4], BASE[4], DLO[4];
+        uint2 ev[4][2];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          LEN[j] = 0; P0[j] = 0; BASE[j] = 0;
-          if (L[j] >= 0) { P0[j] = __shfl(p0, L[j], 64); LEN[j] = __shfl(len, L[j], 64); BASE[j] = __shfl(base, L[j], 64); }
+          LEN[j] = 0; P0[j] = 0; BASE[j] = 0; DLO[j] = 0;
+          if (L[j] >= 0) {
+            P0[j] = __shfl(p0, L[j], 64); LEN[j] = __shfl(len, L[j], 64);
+            BASE[j] = __shfl(base, L[j], 64); DLO[j] = __shfl(dlo, L[j], 64);
+          }
 #pragma unroll
           for (int h = 0; h < 2; ++h) {
-            pk[j][h] = 0; aq[j][h] = 0;
-            if (lane + 64 * h < LEN[j]) { pk[j][h] = d.packed[P0[j] + lane + 64 * h]; aq[j][h] = d.a_q[P0[j] + lane + 64 * h]; }
+            ev[j][h] = make_uint2(0u, 0u);
+            if (lane + 64 * h < LEN[j]) ev[j][h] = d.synf[P0[j] + lane + 64 * h];
           }
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
 #pragma unroll
           for (int h = 0; h < 2; ++h)
-            if (lane + 64 * h < LEN[j]) stage_event(d, s_cur, nparts, pk[j][h], aq[j][h], dlo, BASE[j]);
-          for (int q = 128 + lane; q < LEN[j]; q += 64)
-            stage_event(d, s_cur, nparts, d.packed[P0[j] + q], d.a_q[P0[j] + q], dlo, BASE[j]);
+            if (lane + 64 * h < LEN[j]) stage_event(d, win, s_cur, nparts, ev[j][h].x, (int)ev[j][h].y, DLO[j], BASE[j]);
+          for (int q = 128 + lane; q < LEN[j]; q += 64) {
+            const uint2 e = d.synf[P0[j] + q];
+            stage_event(d, win, s_cur, nparts, e.x, (int)e.y, DLO[j], BASE[j]);
+          }
         }
       }
     }
@@ -377,43 +421,45 @@ __global__ __launch_bounds__(kBinThreads) void k_win_bin(Dev d, long long k0) {
 }
 
 // Pass 2: block `part` sums the staged events of its target range into an LDS tile
-// [W][targets per part] and adds the tile to win.  nb_runs = grid size of pass 1.
-__global__ __launch_bounds__(kBinThreads) void k_win_acc(Dev d, int nb_runs) {
-  __shared__ int tile[kTileCells];
+// [W][targets per part] and adds the tile to the buffer of window k0.  nb_runs = grid size of
+// pass 1 (a multiple of 16 or below 16).  A run (the events one block of pass 1 staged for this
+// part) is read by a 16-lane group, 4 runs per load instruction, 4 instructions in flight.
+__global__ __launch_bounds__(kBinThreads) void k_win_acc(Dev d, long long k0, int nb_runs) {
+  __shared__ int tile[kMaxTileCells];
   const int part = blockIdx.x;
-  for (int x = threadIdx.x; x < kTileCells; x += kBinThreads) tile[x] = 0;
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  // wavefront wv takes the runs (4 per round) ((k * kBinWaves + wv) * 4 + j); lane t = 4 k + j
-  // fetches that run's event count up front (at most kMaxBinBlocks / kBinWaves = 32 per wavefront)
-  const int myrun = ((lane >> 2) * kBinWaves + wv) * 4 + (lane & 3);
-  const int mycnt = myrun < nb_runs ? d.ecnt[(size_t)part * nb_runs + myrun] : 0;
+  const int cells = d.W << d.tp_shift;
+  for (int x = threadIdx.x; x < cells; x += kBinThreads) tile[x] = 0;
   __syncthreads();
-  for (int k = 0; (k * kBinWaves + wv) * 4 < nb_runs; ++k) {
-    const int b0 = (k * kBinWaves + wv) * 4;
-    uint2 ev[4]; int cn[4];
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int sub = lane & 15, grp = lane >> 4;
+  const int* __restrict__ cnts = d.ecnt + (size_t)part * nb_runs;
+  for (int r0 = (wv * 4 + grp) * 4; r0 < nb_runs; r0 += kBinWaves * 16) {
+    int cn[4]; uint2 ev[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) cn[j] = r0 + j < nb_runs ? cnts[r0 + j] : 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      cn[j] = __shfl(mycnt, k * 4 + j, 64);
       ev[j] = make_uint2(0u, 0u);
-      if (lane < cn[j]) ev[j] = d.ebuf[((size_t)part * nb_runs + b0 + j) * d.cap + lane];
+      if (sub < cn[j]) ev[j] = d.ebuf[((size_t)part * nb_runs + r0 + j) * d.cap + sub];
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      if (lane < cn[j]) atomicAdd(&tile[ev[j].x], (int)ev[j].y);
-      for (int q = 64 + lane; q < cn[j]; q += 64) {
-        const uint2 e = d.ebuf[((size_t)part * nb_runs + b0 + j) * d.cap + q];
+      if (sub < cn[j]) atomicAdd(&tile[ev[j].x], (int)ev[j].y);
+      for (int q = 16 + sub; q < cn[j]; q += 16) {
+        const uint2 e = d.ebuf[((size_t)part * nb_runs + r0 + j) * d.cap + q];
         atomicAdd(&tile[e.x], (int)e.y);
       }
     }
   }
   __syncthreads();
   const int tp = 1 << d.tp_shift;
-  for (int x = threadIdx.x; x < kTileCells; x += kBinThreads) {
+  int* __restrict__ win = win_of(d, k0);
+  for (int x = threadIdx.x; x < cells; x += kBinThreads) {
     const int v = tile[x];
     const int r = x >> d.tp_shift;
     const long long t = (long long)part * tp + (x & (tp - 1));
     if (v != 0 && t < d.BN) {
-      int* cell = &d.win[(size_t)r * d.BN + t];
+      int* cell = &win[(size_t)r * d.BN + t];
       *cell = wrap_add(*cell, v);
     }
   }
@@ -439,8 +485,8 @@ __global__ __launch_bounds__(kBlock) void k_ring_in_flight(Dev d, long long n_en
     const int i = (int)(g % d.N);
     const long long r0 = d.row_ptr[i], r1 = d.row_ptr[i + 1];
     for (long long p = r0 + threadIdx.x; p < r1; p += kBlock) {
-      const int D = (int)(d.packed[p] & d.dmask);
-      if (np + D >= n_end) { cnt += 1; sum += d.a_q[p]; }
+      const uint2 e = d.synf[p];
+      if (np + (int)(e.x & d.dmask) >= n_end) { cnt += 1; sum += (int)e.y; }
     }
   }
   block_add2(&out[0], cnt, (long long*)&out[1], sum);
@@ -451,16 +497,17 @@ __global__ __launch_bounds__(kBlock) void k_ring_in_flight(Dev d, long long n_en
 // Gathers the adjoint at the arrival cell of the entries [0, cnt) of the sorted row at pr0
 // (a spike at step n, window phase phi; arrivals inside the same window), adds it to gsum and
 // returns the wavefront's sum of amplitude * adjoint in every lane.
-__device__ __forceinline__ float near_gather(const Dev& d, long long n, long long T, int phi, long long pr0,
-                                             unsigned cnt, int base) {
+__device__ __forceinline__ float near_gather(const Dev& d, const float* __restrict__ gwin, long long n,
+                                             long long T, int phi, long long pr0, unsigned cnt, int base) {
   const int lane = threadIdx.x & 63;
   float G = 0.0f;
   for (unsigned q = lane; q < cnt; q += 64) {
-    const unsigned pk = d.packed[pr0 + q];
+    const uint2 e = d.synb[pr0 + q];
+    const unsigned pk = e.x;
     const int D = (int)(pk & d.dmask);
     if (n + D < T) {
-      const float gv = d.gwin[(size_t)(phi + D) * d.BN + (size_t)base + (pk >> d.dbits)];
-      G += d.amp[pr0 + q] * gv;
+      const float gv = gwin[(size_t)(phi + D) * d.BN + (size_t)base + (pk >> d.dbits)];
+      G += __uint_as_float(e.y) * gv;
       unsafeAtomicAdd(&d.gsum[pr0 + q], gv);
     }
   }
@@ -485,6 +532,7 @@ __global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, lon
   int b = 0, i = 0;
   long long r0 = 0;
   unsigned ncnt = 0;
+  float* __restrict__ gwin = gwin_of(d, n);
   if (act) {
     b = g / d.N; i = g - b * d.N;
     U = d.tapeU[(size_t)n * d.BN + g];
@@ -505,7 +553,7 @@ __global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, lon
   while (m) {
     const int L = __ffsll((long long)m) - 1;
     m &= m - 1;
-    const float t = near_gather(d, n, T, phi, __shfl(r0, L, 64), __shfl(ncnt, L, 64), __shfl(b, L, 64) * d.N);
+    const float t = near_gather(d, gwin, n, T, phi, __shfl(r0, L, 64), __shfl(ncnt, L, 64), __shfl(b, L, 64) * d.N);
     if (lane == L) G += t;
   }
   if (act) {
@@ -519,31 +567,31 @@ __global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, lon
     if (!s) gu = __fmaf_rn(d.alpha, carry, gu);
     gu += dU;
     d.bwd_carry[g] = gu;
-    d.gwin[(size_t)phi * d.BN + g] = gu;
+    gwin[(size_t)phi * d.BN + g] = gu;
   }
 }
 
 // Far part of the queue terms for window [k0, k0 + W), whose adjoint rows are complete: for
-// every recorded spike of steps [k0 - d_max, k0) the piece of its sorted row that arrives in
-// the window gathers its adjoints, adds them to gsum, and the wavefront's sum of
-// amplitude * adjoint is added to Gacc[n mod R][g] (one wavefront per spike: plain update).
-__global__ __launch_bounds__(kBlock) void k_bwd_win(Dev d, long long k0, long long T) {
+// every recorded spike of steps [n_lo, n_hi) (k0 - d_max <= n_lo, n_hi <= k0) the piece of its
+// sorted row that arrives in the window gathers its adjoints, adds them to gsum, and the
+// wavefront's sum of amplitude * adjoint is added to Gacc[n mod R][g] (one wavefront per spike
+// and launch: plain update).  Same walk over the spike words as k_win_bin.
+__global__ __launch_bounds__(kBlock) void k_bwd_win(Dev d, long long k0, long long n_lo, long long n_hi,
+                                                    long long T) {
   const int lane = threadIdx.x & 63;
-  const long long wave = ((long long)blockIdx.x * kBlock + threadIdx.x) >> 6;
+  const long long gw = ((long long)blockIdx.x * kBlock + threadIdx.x) >> 6;
   const long long nwaves = ((long long)gridDim.x * kBlock) >> 6;
-  const long long n_lo = k0 > d.d_max ? k0 - d.d_max : 0;
-  const long long nchunks = (k0 - n_lo) * d.wgroups;
+  const long long nlines = (n_hi - n_lo) * ((d.words + 7) >> 3);
   const int nb = d.d_max + 2;
-  for (long long c = wave; c < nchunks; c += nwaves) {
-    const long long si = c / d.wgroups;
-    const int wg = (int)(c - si * d.wgroups);
-    const long long n = n_lo + si;
-    const int word = wg * 64 + lane;
-    unsigned long long bits = word < d.words ? d.tape_bits[(size_t)n * d.words + word] : 0ull;
+  const float* __restrict__ gwin = gwin_of(d, k0);
+  for (long long c0 = gw; c0 < nlines; c0 += nwaves * 8) {
+    long long n; int word;
+    unsigned long long bits = walk_word(d, d.tape_bits, false, n_lo, n_hi, c0, nwaves, &n, &word);
     const int dlo = (int)(k0 - n);
     int dhi = dlo + d.W < nb - 1 ? dlo + d.W : nb - 1;
     if ((long long)dhi > T - n) dhi = (int)(T - n);    // arrivals n + D >= T are never delivered
     if (dhi < dlo) dhi = dlo;
+    const int slot = (int)(n % d.R);
     while (__ballot(bits != 0ull)) {
       long long p0 = 0, g = 0; int len = 0, base = 0;
       if (bits) {
@@ -562,16 +610,19 @@ __global__ __launch_bounds__(kBlock) void k_bwd_win(Dev d, long long k0, long lo
         int L[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) { L[j] = -1; if (todo) { L[j] = __ffsll((long long)todo) - 1; todo &= todo - 1; } }
-        long long P0[4], GG[4]; int LEN[4], BASE[4];
-        unsigned pk[4][2]; float am[4][2];
+        long long P0[4]; int LEN[4], BASE[4], DLO[4];
+        uint2 ev[4][2];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          LEN[j] = 0; P0[j] = 0; BASE[j] = 0; GG[j] = 0;
-          if (L[j] >= 0) { P0[j] = __shfl(p0, L[j], 64); LEN[j] = __shfl(len, L[j], 64); BASE[j] = __shfl(base, L[j], 64); GG[j] = __shfl(g, L[j], 64); }
+          LEN[j] = 0; P0[j] = 0; BASE[j] = 0; DLO[j] = 0;
+          if (L[j] >= 0) {
+            P0[j] = __shfl(p0, L[j], 64); LEN[j] = __shfl(len, L[j], 64);
+            BASE[j] = __shfl(base, L[j], 64); DLO[j] = __shfl(dlo, L[j], 64);
+          }
 #pragma unroll
           for (int h = 0; h < 2; ++h) {
-            pk[j][h] = 0; am[j][h] = 0.0f;
-            if (lane + 64 * h < LEN[j]) { pk[j][h] = d.packed[P0[j] + lane + 64 * h]; am[j][h] = d.amp[P0[j] + lane + 64 * h]; }
+            ev[j][h] = make_uint2(0u, 0u);
+            if (lane + 64 * h < LEN[j]) ev[j][h] = d.synb[P0[j] + lane + 64 * h];
           }
         }
         float gv[4][2];
@@ -581,7 +632,7 @@ __global__ __launch_bounds__(kBlock) void k_bwd_win(Dev d, long long k0, long lo
           for (int h = 0; h < 2; ++h) {
             gv[j][h] = 0.0f;
             if (lane + 64 * h < LEN[j])
-              gv[j][h] = d.gwin[(size_t)((int)(pk[j][h] & d.dmask) - dlo) * d.BN + (size_t)BASE[j] + (pk[j][h] >> d.dbits)];
+              gv[j][h] = gwin[(size_t)((int)(ev[j][h].x & d.dmask) - DLO[j]) * d.BN + (size_t)BASE[j] + (ev[j][h].x >> d.dbits)];
           }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -589,16 +640,21 @@ __global__ __launch_bounds__(kBlock) void k_bwd_win(Dev d, long long k0, long lo
           float G = 0.0f;
 #pragma unroll
           for (int h = 0; h < 2; ++h)
-            if (lane + 64 * h < LEN[j]) { G += am[j][h] * gv[j][h]; unsafeAtomicAdd(&d.gsum[P0[j] + lane + 64 * h], gv[j][h]); }
+            if (lane + 64 * h < LEN[j]) {
+              G += __uint_as_float(ev[j][h].y) * gv[j][h];
+              unsafeAtomicAdd(&d.gsum[P0[j] + lane + 64 * h], gv[j][h]);
+            }
           for (int q = 128 + lane; q < LEN[j]; q += 64) {
-            const unsigned pq = d.packed[P0[j] + q];
-            const float x = d.gwin[(size_t)((int)(pq & d.dmask) - dlo) * d.BN + (size_t)BASE[j] + (pq >> d.dbits)];
-            G += d.amp[P0[j] + q] * x;
+            const uint2 e = d.synb[P0[j] + q];
+            const float x = gwin[(size_t)((int)(e.x & d.dmask) - DLO[j]) * d.BN + (size_t)BASE[j] + (e.x >> d.dbits)];
+            G += __uint_as_float(e.y) * x;
             unsafeAtomicAdd(&d.gsum[P0[j] + q], x);
           }
           G = wave_sum_f(G);
+          const long long GG = __shfl(g, L[j], 64);
+          const int SL = __shfl(slot, L[j], 64);
           if (lane == 0) {
-            float* ga = &d.Gacc[(size_t)((n % d.R)) * d.BN + GG[j]];
+            float* ga = &d.Gacc[(size_t)SL * d.BN + GG];
             *ga += G;
           }
         }
@@ -616,7 +672,7 @@ __global__ __launch_bounds__(kBlock) void k_grad_finish(Dev d, float dscale, flo
       const float gs = d.gsum[q];
       const long long p = r0 + d.perm[q];
       grad_w[p] = (d.continuous ? d.fdec[q] : 1.0f) * gs;
-      grad_d[p] = d.amp[q] * dscale * gs;
+      grad_d[p] = __uint_as_float(d.synb[q].y) * dscale * gs;
     }
   }
 }

@@ -155,6 +155,45 @@ def test_run_twice_is_bit_identical_and_reset_works():
     sim.close()
 
 
+@pytest.mark.parametrize("overlap,graph", [("1", "1"), ("0", "1"), ("1", "0"), ("0", "0")])
+def test_ring_graph_replays_and_overlap_switches(overlap, graph, monkeypatch):
+    """adseq_run / adseq_backward of the ring replay captured graphs and overlap the old part of
+    every window on a second stream: each of several replays (with eager per-step work and
+    synchronisations between them) must reproduce the oracle, with either switch on or off."""
+    monkeypatch.setenv("ADSEQ_RING_OVERLAP", overlap)
+    monkeypatch.setenv("ADSEQ_RING_GRAPH", graph)
+    wl = synth.ragged_network(400, 500, 60, seed=21, rate_hz=250.0, t=200, b=2, w_mean=0.006, w_std=0.004)
+    T, B = 200, 2
+    ref = oracle.Run(wl, oracle.RING, 0, n_steps=T, batch=B, n_threads=8)
+    dL_dc = np.full((B, wl.n_neurons), 2e-3, np.float32)
+    gw, gd = ref.backward(dL_dc, None)
+    sim = adseq.Adseq(wl, adseq.RING, 0, batch=B, record_tape=True, max_steps=T)
+    dev = sim.dev
+    dc = torch.from_numpy(dL_dc).to(dev)
+    g_w = torch.empty(wl.n_synapses, device=dev)
+    g_d = torch.empty(wl.n_synapses, device=dev)
+    for rep in range(4):
+        sim.reset()
+        if rep == 2:                       # eager steps first, then the rest as one run
+            for n in range(37):
+                sim.step(n)
+            sim.run(37, T - 37)
+        else:
+            sim.run(0, T)
+        torch.cuda.synchronize()
+        U = sim.tape()["U"].cpu().numpy()
+        np.testing.assert_array_equal(U.view(np.uint32), ref.U.view(np.uint32))
+        c, rc = sim.counters(), ref.counters()
+        for key in ("enqueued", "delivered", "sum_enqueued", "sum_delivered"):
+            assert c[key] == rc[key], (rep, key)
+        g_w.fill_(3.0); g_d.fill_(3.0)
+        sim.backward(dc, None, g_w, g_d)
+        torch.cuda.synchronize()
+        H.grad_close(g_w.cpu().numpy(), gw)
+        H.grad_close(g_d.cpu().numpy(), gd)
+    sim.close()
+
+
 def test_create_rejects_bad_delays_and_graph():
     wl = synth.cfg0()
     wl.delay_steps[7] = 0
