@@ -68,6 +68,7 @@ def main():
     y = torch.from_numpy(synth.spike_count_targets(wl)).to(dev).reshape(-1)
     g_w = torch.empty(wl.n_synapses, dtype=torch.float32, device=dev)
     g_d = torch.empty(wl.n_synapses, dtype=torch.float32, device=dev)
+    counts_i = torch.empty(BN, dtype=torch.int32, device=dev)
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
 
     def one_step(evs=None):
@@ -78,8 +79,8 @@ def main():
         if evs:
             evs[1].record()
         # loss glue (plumbing, not the path): dL/dcount of the MSE spike-count loss
-        counts = (sim.membrane_tape(T) >= wl.v_thresh).sum(dim=0).reshape(-1).to(torch.float32)
-        dc = (2.0 / BN) * (counts - y)
+        sim.spike_counts(counts_i)
+        dc = (2.0 / BN) * (counts_i.to(torch.float32) - y)
         sim.backward(dc, None, g_w, g_d)
         if evs:
             evs[2].record()

@@ -182,6 +182,13 @@ typedef struct {
 } adseq_tape_view;
 int adseq_tape(const adseq_t *h, adseq_tape_view *out);
 
+/* Spike count of every (trial, neuron) over the steps recorded since the last reset (the input of
+ * the spike-count loss of the paper's recurrent-network benchmark, Section 5.1): counts int32
+ * [B*N], overwritten.  Needs record_tape = 1 and a complete recorded run.  Stream ordered for
+ * ADSEQ_RING; FIFO / SORTED synchronise `stream` once (the spike list's length lives on the
+ * device). */
+int adseq_spike_counts(adseq_t *h, int32_t *counts, void *stream);
+
 /* Kernel timing for benchmarks (not a call of the method; for callers that want per-kernel
  * durations without an external profiler).  While enabled, adseq_step / adseq_run /
  * adseq_backward record a HIP event on the caller's stream after every kernel they launch

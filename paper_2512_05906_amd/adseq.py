@@ -24,7 +24,7 @@ ERRORS = {0: "OK", -1: "INVALID_ARG", -2: "DELAY_RANGE", -3: "WORKSPACE", -4: "O
 
 EXPORTS = ["adseq_workspace_bytes", "adseq_create", "adseq_destroy", "adseq_reset", "adseq_deliver",
            "adseq_enqueue", "adseq_step", "adseq_run", "adseq_backward", "adseq_drop_count",
-           "adseq_counters", "adseq_tape", "adseq_profile", "adseq_profile_read", "adseq_last_error"]
+           "adseq_counters", "adseq_tape", "adseq_spike_counts", "adseq_profile", "adseq_profile_read", "adseq_last_error"]
 
 
 class AdseqError(RuntimeError):
@@ -80,6 +80,7 @@ def load():
                                        C.POINTER(C.c_uint64), vp]
         L.adseq_counters.argtypes = [vp, C.POINTER(i64), vp]
         L.adseq_tape.argtypes = [vp, C.POINTER(TapeView)]
+        L.adseq_spike_counts.argtypes = [vp, vp, vp]
         L.adseq_profile.argtypes = [vp, C.c_int]
         L.adseq_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64), vp]
         L.adseq_last_error.restype = C.c_char_p
@@ -181,6 +182,10 @@ class Adseq:
         names = ["enqueued", "dropped", "delivered", "sum_enqueued", "sum_dropped", "sum_delivered",
                  "tape_spikes", "error_bits"]
         return dict(zip(names, [int(x) for x in out]))
+
+    def spike_counts(self, counts: torch.Tensor):
+        """Per-(trial, neuron) spike counts of the recorded run into an int32 tensor [B*N]."""
+        self._check(self.lib.adseq_spike_counts(self.h, _dptr(counts), _stream()))
 
     def profile(self, enable: bool):
         self._check(self.lib.adseq_profile(self.h, int(enable)))

@@ -50,13 +50,7 @@ struct Counters {
   int n_spk[2];
   int pool_n[2];
   unsigned long long in_flight[2];  // scratch of k_ring_in_flight: events, Q8.24 sum
-};
-
-// Private counters of one block of the fused step kernel (no atomics; summed on demand).
-struct BlkCtr {
-  unsigned long long offered, delivered, spikes;
-  long long sum_offered, sum_delivered;
-  long long pad[3];
+  unsigned long long fold[3];       // scratch of k_count_spikes: spikes, events, Q8.24 sum
 };
 
 struct ExpCoef { double c[21]; };
@@ -118,9 +112,8 @@ struct Dev {
   float* bwd_carry;
   float* bwd_G;
   Counters* ctr;
-  BlkCtr* blk;   // [nblk]
-  int nblk;      // blocks of the fused step kernel = ceil(BN / 256)
-  int words;     // 64-neuron words per step in spike_bits = 4 * nblk
+  int nblk;      // neuron blocks of a step launch: ceil(BN / 256)
+  int words;     // 64-neuron words per step in spike_bits (RING) = 4 * nblk
 };
 
 // ---------------------------------------------------------------- device helpers
@@ -474,6 +467,14 @@ __device__ __forceinline__ int block_compact(bool flag, int* s_list, int* s_wcnt
   return total;
 }
 
+// Spike counts from the recorded spike lists (FIFO / SORTED): counts must be zero on entry.
+__global__ __launch_bounds__(kBlock) void k_spike_counts_list(Dev d, long long n_spikes, int* __restrict__ counts) {
+  for (long long e = (long long)blockIdx.x * kBlock + threadIdx.x; e < n_spikes; e += (long long)gridDim.x * kBlock) {
+    const int g = d.tape_spk[e];
+    if ((unsigned)g < (unsigned)d.BN) atomicAdd(&counts[g], 1);
+  }
+}
+
 // ---------------------------------------------------------------- ring queue (windowed delay line)
 
 #include "ring_window.h"
@@ -559,25 +560,7 @@ struct adseq {
   long long enq_calls;   // parity source for the pool / spike counters
   bool tape_ok;          // every step since reset went through adseq_step with recording
   char err[256];
-  // RING: second stream for the old part of the window expansion / gather, and what the caller's
-  // stream still has to wait for
-  hipStream_t side = nullptr;
-  hipStream_t cap = nullptr;       // origin stream of graph captures
-  hipEvent_t ev_main = nullptr, ev_side = nullptr;
-  bool overlap = false;            // side stream in use
-  bool graphs = false;             // adseq_run / adseq_backward replay captured graphs
-  bool side_pending = false;       // ev_side marks side-stream work nobody has waited for yet
-  long long old_window = -1;       // window start whose old part has been launched (forward)
-  bool dry = false;                // host-state transitions only: nothing is launched
-  struct Graph {
-    int kind;                      // 0 forward run, 1 backward
-    long long a, b;                // forward: first step, steps; backward: steps
-    int flags;                     // forward: recording, old_window state
-    const void* ptr[4];            // backward: the caller's four arrays
-    hipGraph_t graph;
-    hipGraphExec_t exec;
-  };
-  std::vector<Graph> cache;
+  long long fold_upto = 0;  // RING: spikes of steps below this are in the device counters
   // optional kernel timing (adseq_profile): one event after each bracketed launch
   bool prof = false;
   std::vector<hipEvent_t> evs;
@@ -591,7 +574,7 @@ struct Layout {
   size_t V, win, spike_bits, slot_k, slot_a, occ, head, c_head, pool_p, pool_t, pool_g, pool_next,
       pool_k, pool_a, cur_spk, packed, a_q, synf, synb, dstart, nearcnt, perm, rowsum, ebuf, ecnt, amp, fdec, tapeU,
       tape_bits, step_off, tape_spk, tape_evb, tape_adm, bwd_ring, bwd_carry, bwd_G, gwin, Gacc, gsum, ctr,
-      blk, total;
+      total;
   long long spike_cap, event_cap, pool_cap;
   int R, dbits, nblk, words;
   int W, wshift, tp_shift, P, NB, cap, wgroups;  // RING
@@ -660,20 +643,26 @@ bool make_layout(const adseq_config* c, Layout* L) {
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o += (bytes + 255) & ~(size_t)255; return at; };
   L->nblk = (int)((BN + kBlock - 1) / kBlock);
-  L->words = L->nblk * (kBlock / 64);
+  L->words = 0;
   L->W = L->wshift = L->tp_shift = L->P = L->NB = L->cap = L->wgroups = 0;
   size_t stage_parts = 0;
   if (!bounded) {
+    L->words = L->nblk * (kBlock / 64);
+    // the window is no longer than the largest delay (so that a window boundary comes before
+    // any spike word is overwritten)
     L->W = ring_window_steps();
+    while (L->W > c->d_max_steps) L->W >>= 1;
     L->wshift = bit_width((unsigned)L->W) - 1;
-    L->tp_shift = bit_width((unsigned)ring_tile_cells()) - 1 - L->wshift;
+    int cells = ring_tile_cells();
+    if (cells < L->W) cells = L->W;
+    L->tp_shift = bit_width((unsigned)cells) - 1 - L->wshift;
     L->P = (int)((BN + ((size_t)1 << L->tp_shift) - 1) >> L->tp_shift);
     L->wgroups = (L->words + 7) / 8;
-    // blocks of the staging pass: about four 8-word lines per wavefront when the history is full
+    // blocks of the staging pass: about four 8-word lines per wavefront when the history is
+    // full, but no more than one block per compute unit (measured best on cfg3: 256 of 128..512)
     const long long lines = (long long)c->d_max_steps * L->wgroups;
-    long long nb = (lines + 4 * kBinWaves - 1) / (4 * kBinWaves);
-    nb = env_pow2("ADSEQ_RING_BINBLOCKS", (int)(nb < 1 ? 1 : (nb > kMaxBinBlocks ? kMaxBinBlocks : nb)), 1, kMaxBinBlocks);
-    L->NB = (int)nb;
+    long long nb = (lines + 4 * kRingWaves - 1) / (4 * kRingWaves);
+    L->NB = env_pow2("ADSEQ_RING_BINBLOCKS", (int)(nb < 1 ? 1 : (nb > 256 ? 256 : nb)), 1, kMaxBinBlocks);
     stage_parts = (size_t)(L->P < kMaxParts ? L->P : kMaxParts);
     // staging capacity in events: by default what a window holds when every neuron fires at
     // 1/32 per step, between 2^16 and 2^26 events
@@ -684,7 +673,6 @@ bool make_layout(const adseq_config* c, Layout* L) {
     L->cap = (int)(per > 65536.0 ? 65536.0 : per);
   }
   L->ctr = take(sizeof(Counters));
-  L->blk = take((size_t)L->nblk * sizeof(BlkCtr));  // RING: private counters of the step kernel's blocks
   L->V = take(BN * 4);
   L->win = take(bounded ? 0 : 2 * (size_t)L->W * BN * 4);
   L->spike_bits = take(bounded ? 0 : (size_t)L->R * L->words * 8);
@@ -758,16 +746,12 @@ void fill_u32(hipStream_t st, void* p, unsigned v, size_t count) {
   hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)g), dim3(kBlock), 0, st, (unsigned*)p, v, count);
 }
 
-void join_side(adseq* h, hipStream_t st);
-
 // Clears the dynamic state (not the prepared synapses).
 void launch_reset(adseq* h, hipStream_t st) {
   const Dev& d = h->dev;
-  join_side(h, st);
-  h->old_window = -1;
+  h->fold_upto = 0;
   const size_t BN = (size_t)d.BN;
   fill_u32(st, d.ctr, 0u, sizeof(Counters) / 4);
-  fill_u32(st, d.blk, 0u, (size_t)d.nblk * sizeof(BlkCtr) / 4);
   fill_u32(st, d.V, 0u, BN);
   if (d.kind == ADSEQ_RING) {
     fill_u32(st, d.win, 0u, 2 * (size_t)d.W * BN);
@@ -816,58 +800,23 @@ void launch_fanout(adseq* h, hipStream_t st, long long n, const int* spk, const 
 
 void mark(adseq* h, hipStream_t st, int kind);
 
-// RING: makes `st` wait for whatever the side stream was last given.
-void join_side(adseq* h, hipStream_t st) {
-  if (h->side_pending && !h->dry) (void)hipStreamWaitEvent(st, h->ev_side, 0);
-  h->side_pending = false;
-}
-
-// RING: expansion of window [kw, kw + W) for the spikes of steps [n_lo, n_hi) on stream `st`.
-// staged: staging pass + per-part accumulation (the accumulation is skipped when nothing can be
-// staged); else one pass with plain atomics.
-void launch_expand(adseq* h, hipStream_t st, long long kw, long long n_lo, long long n_hi, bool staged) {
-  const Dev& d = h->dev;
-  if (n_lo < 0) n_lo = 0;
-  if (n_lo < kw - d.d_max) n_lo = kw - d.d_max;
-  if (n_lo >= n_hi || h->dry) return;
-  if (staged && d.cap > 0) {
-    hipLaunchKernelGGL(k_win_bin, dim3((unsigned)d.NB), dim3(kBinThreads), 0, st, d, kw, n_lo, n_hi, 1);
-    const int parts = d.P < kMaxParts ? d.P : kMaxParts;
-    hipLaunchKernelGGL(k_win_acc, dim3((unsigned)parts), dim3(kBinThreads), 0, st, d, kw, d.NB);
-  } else {
-    // one 8-word line per wavefront if the grid allows
-    const long long lines = (n_hi - n_lo) * d.wgroups;
-    long long nb = (lines + kBinWaves - 1) / kBinWaves;
-    nb = nb < 1 ? 1 : (nb > kMaxBinBlocks ? kMaxBinBlocks : nb);
-    hipLaunchKernelGGL(k_win_bin, dim3((unsigned)nb), dim3(kBinThreads), 0, st, d, kw, n_lo, n_hi, 0);
-  }
-}
-
-// RING: called before step k0 is popped when k0 opens a window (k0 mod W = 0).  The window's
-// events from spikes older than the previous window were expanded on the side stream while that
-// window ran (or are expanded here if they were not); those of the previous window's own spikes
-// are added now; then the old part of the next window is handed to the side stream.
+// RING: called before step k0 is popped when k0 opens a window (k0 mod W = 0): expands the
+// events of the spikes of the last d_max steps that arrive in the window (staging pass, then
+// per-part accumulation; without staging room the first pass scatters with atomics and the
+// second is skipped).  The staging pass also counts the spikes not counted yet, and their
+// events, into the device counters.
 void ring_open_window(adseq* h, hipStream_t st, long long k0) {
   const Dev& d = h->dev;
   if ((k0 & (long long)(d.W - 1)) != 0 || k0 <= 0) return;
   mark(h, st, -1);
-  if (h->old_window == k0) {
-    join_side(h, st);
-    launch_expand(h, st, k0, k0 - d.W, k0, false);
-  } else {
-    join_side(h, st);
-    launch_expand(h, st, k0, k0 - d.d_max, k0, true);
+  const long long n_lo = k0 - d.d_max > 0 ? k0 - d.d_max : 0;
+  hipLaunchKernelGGL(k_win_bin, dim3((unsigned)d.NB), dim3(kRingThreads), 0, st, d, k0, n_lo, k0, 0, d.NB,
+                     d.cap > 0 ? 1 : 0, h->fold_upto);
+  if (d.cap > 0) {
+    const int parts = d.P < kMaxParts ? d.P : kMaxParts;
+    hipLaunchKernelGGL(k_win_acc, dim3((unsigned)parts), dim3(kRingThreads), 0, st, d, k0, 0);
   }
-  if (h->overlap && !h->prof && k0 + d.W - d.d_max < k0) {
-    if (!h->dry) {
-      (void)hipEventRecord(h->ev_main, st);
-      (void)hipStreamWaitEvent(h->side, h->ev_main, 0);
-    }
-    launch_expand(h, h->side, k0 + d.W, k0 + d.W - d.d_max, k0, true);
-    if (!h->dry) (void)hipEventRecord(h->ev_side, h->side);
-    h->side_pending = true;
-    h->old_window = k0 + d.W;
-  }
+  h->fold_upto = k0;
   mark(h, st, 0);
 }
 
@@ -894,9 +843,9 @@ int step_impl(adseq* h, long long step, const float* i_ext, unsigned char* spike
   if (d.kind == ADSEQ_RING) {
     ring_open_window(h, st, step);
     mark(h, st, -1);
-    if (h->dry) {}
-    else if (record) hipLaunchKernelGGL((k_step_win<true>), dim3((unsigned)d.nblk), dim3(kBlock), 0, st, d, step, i_ext, spikes_out);
-    else hipLaunchKernelGGL((k_step_win<false>), dim3((unsigned)d.nblk), dim3(kBlock), 0, st, d, step, i_ext, spikes_out);
+    const dim3 grid((unsigned)d.nblk), block(kBlock);
+    if (record) hipLaunchKernelGGL((k_step_win<true>), grid, block, 0, st, d, step, i_ext, spikes_out);
+    else hipLaunchKernelGGL((k_step_win<false>), grid, block, 0, st, d, step, i_ext, spikes_out);
     mark(h, st, 1);
   } else {
     mark(h, st, -1);
@@ -907,83 +856,25 @@ int step_impl(adseq* h, long long step, const float* i_ext, unsigned char* spike
   }
   h->enq_calls += 1;
   h->next_step = step + 1;
-  if (!h->dry) HIP_TRY(h, hipGetLastError());
+  HIP_TRY(h, hipGetLastError());
   return ADSEQ_OK;
 }
 
-// RING: n_steps closed-loop steps as one captured graph (kernel nodes of the caller-stream chain
-// and of the side-stream branch, joined at the end), replayed from a small cache when the same
-// run is asked for again.  Returns ADSEQ_OK, or a negative code with nothing launched and the
-// host state untouched, in which case the caller falls back to plain launches.
-int ring_run_graph(adseq* h, long long step0, long long n_steps, hipStream_t st) {
-  const Dev& d = h->dev;
-  const int record = (d.record && h->tape_ok) ? 1 : 0;
-  join_side(h, st);   // nothing from before the graph is left in flight beside it
-  const int flags = record | (h->old_window == ((step0 + d.W - 1) & ~(long long)(d.W - 1)) ? 2 : 0);
-  adseq::Graph* hit = nullptr;
-  for (auto& g : h->cache)
-    if (g.kind == 0 && g.a == step0 && g.b == n_steps && g.flags == flags) hit = &g;
-  // host-state snapshot, to roll back if the capture fails
-  const long long s_next = h->next_step, s_enq = h->enq_calls, s_old = h->old_window;
-  const bool s_tape = h->tape_ok;
-  int rc = ADSEQ_OK;
-  if (!hit) {
-    if (hipStreamBeginCapture(h->cap, hipStreamCaptureModeThreadLocal) != hipSuccess) return ADSEQ_E_HIP;
-    for (long long n = 0; n < n_steps && rc == ADSEQ_OK; ++n) rc = step_impl(h, step0 + n, nullptr, nullptr, h->cap);
-    join_side(h, h->cap);
-    hipGraph_t graph = nullptr;
-    hipError_t e = hipStreamEndCapture(h->cap, &graph);
-    hipGraphExec_t exec = nullptr;
-    if (e == hipSuccess && rc == ADSEQ_OK) e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
-    if (e != hipSuccess || rc != ADSEQ_OK) {
-      if (graph) (void)hipGraphDestroy(graph);
-      (void)hipGetLastError();
-      h->next_step = s_next; h->enq_calls = s_enq; h->old_window = s_old; h->tape_ok = s_tape;
-      h->side_pending = false;
-      return rc != ADSEQ_OK ? rc : ADSEQ_E_HIP;
-    }
-    if (h->cache.size() >= 8) {
-      (void)hipGraphExecDestroy(h->cache.front().exec);
-      (void)hipGraphDestroy(h->cache.front().graph);
-      h->cache.erase(h->cache.begin());
-    }
-    adseq::Graph g{};
-    g.kind = 0; g.a = step0; g.b = n_steps; g.flags = flags; g.graph = graph; g.exec = exec;
-    h->cache.push_back(g);
-    hit = &h->cache.back();
-  } else {
-    h->dry = true;
-    for (long long n = 0; n < n_steps && rc == ADSEQ_OK; ++n) rc = step_impl(h, step0 + n, nullptr, nullptr, st);
-    join_side(h, st);
-    h->dry = false;
-    if (rc != ADSEQ_OK) return rc;
-  }
-  if (hipGraphLaunch(hit->exec, st) != hipSuccess) return fail(h, ADSEQ_E_HIP, "hipGraphLaunch failed");
-  return ADSEQ_OK;
-}
-
-// RING: far gather of window [kw, kw + W) for the recorded spikes of steps [n_lo, n_hi).
-void launch_bwd_win(adseq* h, hipStream_t st, long long kw, long long n_lo, long long n_hi, long long T) {
-  const Dev& d = h->dev;
-  if (n_lo < 0) n_lo = 0;
-  if (n_lo < kw - d.d_max) n_lo = kw - d.d_max;
-  if (n_lo >= n_hi) return;
-  // about four 8-word lines per wavefront
+// RING: virtual blocks of one far gather over the spikes of steps [n_lo, n_hi): about four
+// 8-word lines per wavefront.
+int gather_blocks(const Dev& d, long long n_lo, long long n_hi) {
   const long long lines = (n_hi - n_lo) * d.wgroups;
-  long long g = (lines + 15) / 16;
-  g = g < 1 ? 1 : (g > 8192 ? 8192 : g);
-  hipLaunchKernelGGL(k_bwd_win, dim3((unsigned)g), dim3(kBlock), 0, st, d, kw, n_lo, n_hi, T);
+  long long g = (lines + 4 * kRingWaves - 1) / (4 * kRingWaves);
+  return env_pow2("ADSEQ_RING_GATHERBLOCKS", (int)(g < 1 ? 1 : (g > 256 ? 256 : g)), 1, 2048);
 }
 
-// RING: the whole reverse sweep on `st` (and, for the old part of every window's far gather, on
-// the side stream, joined before the gradients are finished).  One launch per reverse step; when
-// a step closes a window (n mod W = 0) the far queue terms of the earlier spikes that arrive in
-// that window are gathered: those of the W steps swept next at once, the older ones beside them.
+// RING: the whole reverse sweep on `st`.  One launch per reverse step; when a step closes a
+// window (n mod W = 0) the far queue terms of all earlier spikes that arrive in that window are
+// gathered in one pass.
 void ring_backward_launch(adseq* h, hipStream_t st, long long T, float dscale, const float* dL_dcount,
                           const float* dL_dU, float* grad_w, float* grad_d) {
   const Dev& d = h->dev;
-  const dim3 block(kBlock), gn(grid_for((size_t)d.BN));
-  const bool split = h->overlap && !h->prof && d.d_max > d.W;
+  const dim3 block(kBlock), gn((unsigned)d.nblk);
   fill_u32(st, d.bwd_carry, 0u, (size_t)d.BN);
   fill_u32(st, d.gsum, 0u, (size_t)d.S);
   fill_u32(st, d.gwin, 0u, 2 * (size_t)d.W * d.BN);
@@ -993,61 +884,14 @@ void ring_backward_launch(adseq* h, hipStream_t st, long long T, float dscale, c
     hipLaunchKernelGGL(k_bwd_step_win, gn, block, 0, st, d, n, T, dL_dcount, dL_dU);
     mark(h, st, 3);
     if ((n & (long long)(d.W - 1)) == 0 && n > 0) {
-      if (!split) {
-        launch_bwd_win(h, st, n, n - d.d_max, n, T);
-      } else {
-        join_side(h, st);                      // old part of the window swept before this one
-        (void)hipEventRecord(h->ev_main, st);  // rows of this window are complete
-        launch_bwd_win(h, st, n, n - d.W, n, T);
-        (void)hipStreamWaitEvent(h->side, h->ev_main, 0);
-        launch_bwd_win(h, h->side, n, n - d.d_max, n - d.W, T);
-        (void)hipEventRecord(h->ev_side, h->side);
-        h->side_pending = true;
-      }
+      const long long lo = n - d.d_max > 0 ? n - d.d_max : 0;
+      const int nvb = gather_blocks(d, lo, n);
+      hipLaunchKernelGGL(k_bwd_win, dim3((unsigned)nvb), dim3(kRingThreads), 0, st, d, n, lo, n, T, 0, nvb);
       mark(h, st, 2);
     }
   }
-  join_side(h, st);
   const unsigned gf = (unsigned)(d.N < 65536 ? d.N : 65536);
   hipLaunchKernelGGL(k_grad_finish, dim3(gf), block, 0, st, d, dscale, grad_w, grad_d);
-}
-
-int ring_backward_graph(adseq* h, hipStream_t st, long long T, float dscale, const float* dL_dcount,
-                        const float* dL_dU, float* grad_w, float* grad_d) {
-  adseq::Graph* hit = nullptr;
-  for (auto& g : h->cache)
-    if (g.kind == 1 && g.a == T && g.ptr[0] == dL_dcount && g.ptr[1] == dL_dU && g.ptr[2] == grad_w &&
-        g.ptr[3] == grad_d)
-      hit = &g;
-  if (!hit) {
-    if (hipStreamBeginCapture(h->cap, hipStreamCaptureModeThreadLocal) != hipSuccess) {
-      (void)hipGetLastError();
-      return ADSEQ_E_HIP;
-    }
-    ring_backward_launch(h, h->cap, T, dscale, dL_dcount, dL_dU, grad_w, grad_d);
-    hipGraph_t graph = nullptr;
-    hipError_t e = hipStreamEndCapture(h->cap, &graph);
-    hipGraphExec_t exec = nullptr;
-    if (e == hipSuccess) e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
-    h->side_pending = false;
-    if (e != hipSuccess) {
-      if (graph) (void)hipGraphDestroy(graph);
-      (void)hipGetLastError();
-      return ADSEQ_E_HIP;
-    }
-    if (h->cache.size() >= 8) {
-      (void)hipGraphExecDestroy(h->cache.front().exec);
-      (void)hipGraphDestroy(h->cache.front().graph);
-      h->cache.erase(h->cache.begin());
-    }
-    adseq::Graph g{};
-    g.kind = 1; g.a = T; g.ptr[0] = dL_dcount; g.ptr[1] = dL_dU; g.ptr[2] = grad_w; g.ptr[3] = grad_d;
-    g.graph = graph; g.exec = exec;
-    h->cache.push_back(g);
-    hit = &h->cache.back();
-  }
-  if (hipGraphLaunch(hit->exec, st) != hipSuccess) { (void)hipGetLastError(); return ADSEQ_E_HIP; }
-  return ADSEQ_OK;
 }
 
 }  // namespace
@@ -1098,7 +942,7 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   d.row_ptr = (const long long*)cfg->row_ptr; d.col = cfg->col; d.weight = cfg->weight;
   d.delay_steps = cfg->delay_steps; d.delay_ms = cfg->delay_ms;
   d.ctr = (Counters*)(ws + L.ctr);
-  d.blk = (BlkCtr*)(ws + L.blk); d.nblk = L.nblk; d.words = L.words;
+  d.nblk = L.nblk; d.words = L.words;
   d.V = (float*)(ws + L.V); d.spike_bits = (unsigned long long*)(ws + L.spike_bits);
   d.W = L.W; d.wshift = L.wshift; d.tp_shift = L.tp_shift; d.P = L.P; d.NB = L.NB; d.cap = L.cap;
   d.wgroups = L.wgroups;
@@ -1157,36 +1001,13 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   if (e != hipSuccess) { delete h; return ADSEQ_E_HIP; }
   if (err & ERR_GRAPH) { delete h; return ADSEQ_E_GRAPH; }
   if (err & ERR_DELAY) { delete h; return ADSEQ_E_DELAY_RANGE; }
-  if (d.kind == ADSEQ_RING) {
-    // the ring overlaps the old part of each window's expansion with the steps of the window
-    // before it on a stream of its own (default priority), and replays whole runs as graphs;
-    // ADSEQ_RING_OVERLAP=0 / ADSEQ_RING_GRAPH=0 switch either off (results are the same)
-    const char* ov = getenv("ADSEQ_RING_OVERLAP");
-    const char* gr = getenv("ADSEQ_RING_GRAPH");
-    h->overlap = !(ov && ov[0] == '0');
-    h->graphs = !(gr && gr[0] == '0');
-    hipError_t es = hipSuccess;
-    if (h->overlap || h->graphs) {
-      es = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking);
-      if (es == hipSuccess) es = hipStreamCreateWithFlags(&h->cap, hipStreamNonBlocking);
-      if (es == hipSuccess) es = hipEventCreateWithFlags(&h->ev_main, hipEventDisableTiming);
-      if (es == hipSuccess) es = hipEventCreateWithFlags(&h->ev_side, hipEventDisableTiming);
-    }
-    if (es != hipSuccess) { adseq_destroy(h); return ADSEQ_E_HIP; }
-  }
   *out = h;
   return ADSEQ_OK;
 }
 
 int adseq_destroy(adseq_t* h) {
   if (!h) return ADSEQ_E_INVALID_ARG;
-  if (h->side) (void)hipStreamSynchronize(h->side);
-  for (auto& g : h->cache) { (void)hipGraphExecDestroy(g.exec); (void)hipGraphDestroy(g.graph); }
   for (hipEvent_t e : h->evs) (void)hipEventDestroy(e);
-  if (h->ev_main) (void)hipEventDestroy(h->ev_main);
-  if (h->ev_side) (void)hipEventDestroy(h->ev_side);
-  if (h->side) (void)hipStreamDestroy(h->side);
-  if (h->cap) (void)hipStreamDestroy(h->cap);
   delete h;
   return ADSEQ_OK;
 }
@@ -1245,12 +1066,6 @@ int adseq_run(adseq_t* h, int64_t step0, int64_t n_steps, void* stream) {
   if (n_steps < 0) return fail(h, ADSEQ_E_INVALID_ARG, "adseq_run: negative step count");
   if (step0 != h->next_step)
     return fail(h, ADSEQ_E_ORDER, "adseq_run: got step %lld, expected %lld", (long long)step0, h->next_step);
-  if (h->dev.kind == ADSEQ_RING && h->graphs && !h->prof && n_steps >= 32 &&
-      (!h->dev.record || !h->tape_ok || step0 + n_steps <= h->dev.max_steps)) {
-    const int rc = ring_run_graph(h, step0, n_steps, (hipStream_t)stream);
-    if (rc == ADSEQ_OK) return rc;
-    if (h->next_step != step0) return rc;   // the graph was launched in part: not recoverable here
-  }
   for (int64_t n = 0; n < n_steps; ++n) {
     const int rc = step_impl(h, step0 + n, nullptr, nullptr, (hipStream_t)stream);
     if (rc != ADSEQ_OK) return rc;
@@ -1278,11 +1093,7 @@ int adseq_backward(adseq_t* h, const float* dL_dcount, const float* dL_dU, float
   const dim3 block(kBlock), gn(grid_for((size_t)d.BN)), gg(kFanoutBlocks);
   const bool bounded = d.kind != ADSEQ_RING, atomic = d.B > 1;
   if (!bounded) {
-    join_side(h, st);
-    if (h->graphs && !h->prof && T >= 32 && ring_backward_graph(h, st, T, dscale, dL_dcount, dL_dU, grad_w, grad_d) == ADSEQ_OK)
-      return ADSEQ_OK;
     ring_backward_launch(h, st, T, dscale, dL_dcount, dL_dU, grad_w, grad_d);
-    join_side(h, st);
     HIP_TRY(h, hipGetLastError());
     return ADSEQ_OK;
   }
@@ -1307,14 +1118,20 @@ int adseq_counters(adseq_t* h, int64_t* out8, void* stream) {
   Counters c;
   hipStream_t st = (hipStream_t)stream;
   const Dev& d = h->dev;
-  join_side(h, st);
   if (d.kind == ADSEQ_RING) {
-    // the ring sums amplitudes, so delivered = offered - still in flight; the latter is counted
-    // here, on demand, from the spike bits of the last d_max + 1 steps
-    fill_u32(st, d.ctr->in_flight, 0u, 4);
+    // The ring keeps no per-event counters.  Spikes and the events they emit are counted from
+    // the spike words: up to the last window boundary by the boundary pass (device counters),
+    // since then here; and delivered = offered - still in flight, the latter counted here from
+    // the spike words of the last d_max + 1 steps.
+    fill_u32(st, d.ctr->in_flight, 0u, 4 + 6);
     const long long items = (long long)d.R * d.words;
     hipLaunchKernelGGL(k_ring_in_flight, dim3((unsigned)items), dim3(kBlock), 0, st, d, h->next_step,
                        d.ctr->in_flight);
+    if (h->fold_upto < h->next_step) {
+      const long long it = (h->next_step - h->fold_upto) * d.words;
+      hipLaunchKernelGGL(k_count_spikes, dim3((unsigned)grid_for((size_t)it)), dim3(kBlock), 0, st, d,
+                         h->fold_upto, h->next_step, d.ctr->fold);
+    }
   }
   HIP_TRY(h, hipMemcpyAsync(&c, d.ctr, sizeof(c), hipMemcpyDeviceToHost, st));
   HIP_TRY(h, hipStreamSynchronize(st));
@@ -1322,19 +1139,9 @@ int adseq_counters(adseq_t* h, int64_t* out8, void* stream) {
   out8[3] = c.sum_offered; out8[4] = c.sum_dropped; out8[5] = c.sum_delivered;
   out8[6] = c.tape_spikes; out8[7] = (int64_t)c.err;
   if (d.kind == ADSEQ_RING) {
-    // the step kernel keeps private counters per block: add them up here
-    const int nb = d.nblk;
-    BlkCtr* hb = new (std::nothrow) BlkCtr[nb];
-    if (!hb) return fail(h, ADSEQ_E_INVALID_ARG, "adseq_counters: out of host memory");
-    hipError_t e = hipMemcpyAsync(hb, d.blk, sizeof(BlkCtr) * nb, hipMemcpyDeviceToHost, st);
-    if (e == hipSuccess) e = hipStreamSynchronize(st);
-    if (e != hipSuccess) { delete[] hb; return fail(h, ADSEQ_E_HIP, "copy of block counters failed: %s", hipGetErrorString(e)); }
-    for (int i = 0; i < nb; ++i) {
-      out8[0] += (int64_t)hb[i].offered; out8[3] += hb[i].sum_offered;
-      out8[5] += hb[i].sum_delivered; out8[6] += (int64_t)hb[i].spikes;
-    }
-    delete[] hb;
+    out8[6] += (int64_t)c.fold[0]; out8[0] += (int64_t)c.fold[1]; out8[3] += (int64_t)c.fold[2];
     out8[2] = out8[0] - (int64_t)c.in_flight[0];
+    out8[5] = out8[3] - (int64_t)c.in_flight[1];
   }
   return ADSEQ_OK;
 }
@@ -1364,6 +1171,30 @@ int adseq_tape(const adseq_t* h, adseq_tape_view* out) {
   out->event_base = d.kind != ADSEQ_RING ? (const int64_t*)d.tape_evb : nullptr;
   out->admitted = d.kind != ADSEQ_RING ? d.tape_adm : nullptr;
   out->steps_recorded = h->tape_ok ? (h->next_step < d.max_steps ? h->next_step : d.max_steps) : 0;
+  return ADSEQ_OK;
+}
+
+int adseq_spike_counts(adseq_t* h, int32_t* counts, void* stream) {
+  if (!h || !counts) return h ? fail(h, ADSEQ_E_INVALID_ARG, "adseq_spike_counts: null argument") : ADSEQ_E_INVALID_ARG;
+  const Dev& d = h->dev;
+  if (!d.record || !h->tape_ok)
+    return fail(h, ADSEQ_E_NO_TAPE, "adseq_spike_counts: no complete recorded forward run");
+  hipStream_t st = (hipStream_t)stream;
+  const long long T = h->next_step;
+  if (d.kind == ADSEQ_RING) {
+    hipLaunchKernelGGL(k_spike_counts_bits, dim3((unsigned)grid_for((size_t)d.BN)), dim3(kBlock), 0, st, d, T, counts);
+  } else {
+    // the number of recorded spikes lives on the device: read it (one synchronisation)
+    long long n_spikes = 0;
+    HIP_TRY(h, hipMemcpyAsync(&n_spikes, &d.ctr->tape_spikes, sizeof(n_spikes), hipMemcpyDeviceToHost, st));
+    HIP_TRY(h, hipStreamSynchronize(st));
+    if (n_spikes > d.spike_cap) n_spikes = d.spike_cap;
+    fill_u32(st, counts, 0u, (size_t)d.BN);
+    if (n_spikes > 0)
+      hipLaunchKernelGGL(k_spike_counts_list, dim3((unsigned)grid_for((size_t)n_spikes)), dim3(kBlock), 0, st, d,
+                         n_spikes, counts);
+  }
+  HIP_TRY(h, hipGetLastError());
   return ADSEQ_OK;
 }
 

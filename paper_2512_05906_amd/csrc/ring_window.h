@@ -14,26 +14,31 @@
 //     n + D begins.  Then one expansion pass walks the spikes of the last d_max steps; for a
 //     spike at step n the entries that land in window [k0, k0 + W) are the contiguous piece
 //     D in [k0 - n, k0 - n + W) of its row, read with full-width loads.
-// The expansion pass does not scatter with one memory-side atomic per event.  It bins the
-// events by target range into per-(part, block) regions of a staging buffer (LDS cursors, no
-// global atomics); a second kernel gives each part to one workgroup, which sums the part's
-// events into a 64 KB LDS tile with LDS atomics and adds the tile to win with coalesced
+// The expansion does not scatter with one memory-side atomic per event.  It stages the events
+// by target range ("part") into per-(part, block) regions of a buffer (LDS cursors, no global
+// atomics); then every part is given to one workgroup, which sums the part's events into an LDS
+// tile [W][targets of the part] with LDS atomics and adds the tile to win with coalesced
 // accesses.  Events that do not fit their region fall back to a global atomic on win, so the
 // result never depends on the staging capacity.
-// The expansion of window q + 1 is split in two: the spikes older than window q ("old part", 15/16
-// of the events for W = 16, d_max = 250) are expanded on a second stream while the steps of
-// window q run; the spikes of window q itself ("recent part") follow at the boundary with plain
-// atomics.  Hence the two window buffers.
+// Nor does the expansion wait for the window boundary.  The spikes older than the current window
+// ("old spikes": 15/16 of the next window's events for W = 16, d_max = 250) are known while the
+// current window runs, so the preparation of the next window from them is cut into W slices
+// (staging slices, then accumulation slices) and slice phi rides, as extra blocks, on the launch
+// of the current window's step phi, whose neuron blocks are latency-bound and leave most of the
+// chip idle.  Hence two window buffers.  At the boundary only the spikes of the window just
+// finished are left: one pass with plain atomics, which also counts those spikes and their
+// events into the device counters (the step kernel itself counts nothing).
 //
 // The reverse sweep mirrors it: gwin f32 [2][W][BN] holds the adjoint rows of the current window
-// and of the one swept before it (still being read by the old part of its gather);
-// a spike's queue term is the sum of a near part (gathered by the step kernel) and one far part
-// per later window (gathered by k_bwd_win from the 6.4 MB window, which the L2 holds, into
-// Gacc[n mod R][g]); the per-synapse sum of gathered adjoints goes to gsum in sorted order and is
-// scaled and un-permuted into grad_w / grad_d by k_grad_finish.
+// and of the one swept before it.  A spike's queue term is the sum of a near part (gathered by
+// the step kernel) and one far part per later window, gathered from the window (6.4 MB: the L2
+// holds it) into Gacc[n mod R][g] -- for the spikes of the W steps swept next in a pass at the
+// boundary, for the older ones in W slices riding on those W step launches.  The per-synapse sum
+// of gathered adjoints goes to gsum in sorted order and is scaled and un-permuted into
+// grad_w / grad_d by k_grad_finish.
 
-constexpr int kBinThreads = 1024;   // threads per block of k_win_bin / k_win_acc
-constexpr int kBinWaves = kBinThreads / 64;
+constexpr int kRingThreads = 1024;  // threads per block of the ring's step and expansion kernels
+constexpr int kRingWaves = kRingThreads / 64;
 constexpr int kMaxTileCells = 16384; // cells (target, row) of the largest LDS tile = 64 KB
 constexpr int kMaxParts = 4096;     // LDS cursors of k_win_bin; targets beyond them use atomics
 constexpr int kMaxBinBlocks = 512;
@@ -183,27 +188,28 @@ __device__ __forceinline__ void near_scatter(const Dev& d, int* __restrict__ win
   }
 }
 
-// Block b owns neurons [256 b, 256 b + 256): pops their cells of row phi = n mod W, adds the
-// drive, integrates, records the membrane value and the spike bits, and scatters the in-window
-// events of its own spikes.  No atomic on any shared counter.
+// One launch per time step.  Block b owns neurons [256 b, 256 b + 256): pops their cells of
+// row phi = n mod W, adds the drive, integrates, records the membrane value and the spike bits,
+// and scatters the in-window events of its own spikes.  No block-level synchronisation and no
+// counter: spikes and offered events are counted from the spike bits when a window closes.
 template <bool RECORD>
 __global__ __launch_bounds__(kBlock) void k_step_win(Dev d, long long n, const float* __restrict__ i_ext,
                                                      unsigned char* __restrict__ spikes_out) {
-  __shared__ long long s_red[4][kBlock / 64];
   const int g = blockIdx.x * kBlock + threadIdx.x;
   const bool act = g < d.BN;
   const int phi = (int)(n & (long long)(d.W - 1));
   int near_h = d.W - 1 - phi;
   if (near_h > d.d_max) near_h = d.d_max;
-  int acc = 0, b = 0, i = 0;
+  int b = 0;
   bool s = false;
   long long r0 = 0;
   unsigned ncnt = 0;
   int* __restrict__ win = win_of(d, n);
   if (act) {
-    b = g / d.N; i = g - b * d.N;
+    b = g / d.N;
+    const int i = g - b * d.N;
     const size_t idx = (size_t)phi * d.BN + g;
-    acc = win[idx];
+    const int acc = win[idx];
     // row start and in-window entry count of every neuron, loaded beside the pop so that a
     // spiking neuron's fan-out does not wait for them (both arrays stay in the L2)
     r0 = d.row_ptr[i];
@@ -229,31 +235,11 @@ __global__ __launch_bounds__(kBlock) void k_step_win(Dev d, long long n, const f
     d.spike_bits[(size_t)(n % d.R) * d.words + word] = bits;
     if (RECORD) d.tape_bits[(size_t)n * d.words + word] = bits;
   }
-  long long c_off = 0, s_off = 0;
-  if (s) { c_off = d.row_ptr[i + 1] - r0; s_off = d.rowsum[i]; }
   unsigned long long m = __ballot(s && ncnt > 0);
   while (m) {
     const int L = __ffsll((long long)m) - 1;
     m &= m - 1;
     near_scatter(d, win, phi, __shfl(r0, L, 64), __shfl(ncnt, L, 64), __shfl(b, L, 64) * d.N);
-  }
-  const long long sp = wave_sum((long long)acc);
-  const long long ns = wave_sum((long long)(s ? 1 : 0));
-  c_off = wave_sum(c_off); s_off = wave_sum(s_off);
-  if ((threadIdx.x & 63) == 0) {
-    const int w = threadIdx.x >> 6;
-    s_red[0][w] = sp; s_red[1][w] = ns; s_red[2][w] = c_off; s_red[3][w] = s_off;
-  }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    long long a = 0, c = 0, co = 0, so = 0;
-    for (int w = 0; w < kBlock / 64; ++w) { a += s_red[0][w]; c += s_red[1][w]; co += s_red[2][w]; so += s_red[3][w]; }
-    // private counters of this block; atomics only so that nothing waits for a read
-    BlkCtr& bc = d.blk[blockIdx.x];
-    if (a) atomicAdd((unsigned long long*)&bc.sum_delivered, (unsigned long long)a);
-    if (c) atomicAdd(&bc.spikes, (unsigned long long)c);
-    if (co) atomicAdd(&bc.offered, (unsigned long long)co);
-    if (so) atomicAdd((unsigned long long*)&bc.sum_offered, (unsigned long long)so);
   }
 }
 
@@ -262,17 +248,15 @@ __global__ __launch_bounds__(kBlock) void k_step_win(Dev d, long long n, const f
 __global__ __launch_bounds__(kBlock) void k_deliver_win(Dev d, long long n, float* __restrict__ I_out) {
   const int g = blockIdx.x * kBlock + threadIdx.x;
   const int phi = (int)(n & (long long)(d.W - 1));
-  int acc = 0;
   int* __restrict__ win = win_of(d, n);
   if (g < d.BN) {
     const size_t idx = (size_t)phi * d.BN + g;
-    acc = win[idx];
+    const int acc = win[idx];
     if (acc != 0) win[idx] = 0;
     I_out[g] = (float)acc * 0x1p-24f;
   }
   if ((threadIdx.x & 63) == 0)
     d.spike_bits[(size_t)(n % d.R) * d.words + (size_t)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6)] = 0ull;
-  block_add2(&d.ctr->delivered, 0, &d.ctr->sum_delivered, (long long)acc);
 }
 
 // Open-loop enqueue of the listed spikes at step n: one wavefront per spike sets its bit and
@@ -286,34 +270,42 @@ __global__ __launch_bounds__(kBlock) void k_enqueue_win(Dev d, long long n, cons
   if (near_h > d.d_max) near_h = d.d_max;
   const int lane = threadIdx.x & 63;
   const int wave = (blockIdx.x * kBlock + threadIdx.x) >> 6, nwaves = (gridDim.x * kBlock) >> 6;
-  long long c_off = 0, s_off = 0;
   for (int e = wave; e < nspk; e += nwaves) {
     const int g = spk[e];
     if ((unsigned)g >= (unsigned)d.BN) continue;  // uniform over the wavefront
     const int b = g / d.N, i = g - b * d.N;
-    const long long r0 = d.row_ptr[i];
-    if (lane == 0) {
-      atomicOr(&d.spike_bits[(size_t)(n % d.R) * d.words + (g >> 6)], 1ull << (g & 63));
-      c_off += d.row_ptr[i + 1] - r0; s_off += d.rowsum[i];
-    }
-    if (near_h >= 1) near_scatter(d, win_of(d, n), phi, r0, d.nearcnt[(size_t)near_h * d.N + i], b * d.N);
+    if (lane == 0) atomicOr(&d.spike_bits[(size_t)(n % d.R) * d.words + (g >> 6)], 1ull << (g & 63));
+    if (near_h >= 1)
+      near_scatter(d, win_of(d, n), phi, d.row_ptr[i], d.nearcnt[(size_t)near_h * d.N + i], b * d.N);
   }
-  block_add2(&d.ctr->offered, c_off, &d.ctr->sum_offered, s_off);
 }
 
 // ---------------------------------------------------------------- forward: window expansion
 
-// One far event of the window: staged in region (part, block) if there is room, else added to
+// The piece of one spike's sorted row that lands in the window being expanded.
+struct Seg { long long p0; int len; int base; int dlo; int slot; long long g; };
+constexpr int kSegQueue = 768;   // queue entries per block (32 B each)
+
+// LDS of a block of an expansion / gather role.
+struct ExpandLds {
+  int cur[kMaxParts];        // staging cursors of k_win_bin's parts
+  Seg q[kSegQueue];          // segments found by the walk, shared out among the wavefronts
+  int qn, qhead;
+  long long red[3][kRingWaves];
+};
+static_assert(sizeof(ExpandLds) <= kMaxTileCells * 4, "roles share one LDS buffer");
+
+// One far event of the window: staged in region (part, vb) if there is room, else added to
 // win with a global atomic.
 __device__ __forceinline__ void stage_event(const Dev& d, int* __restrict__ win, int* s_cur, int nparts,
-                                            unsigned pk, int a, int dlo, int base) {
+                                            int vb, unsigned pk, int a, int dlo, int base) {
   const int r = (int)(pk & d.dmask) - dlo;             // row of the window, 0 .. W - 1
   const int gt = base + (int)(pk >> d.dbits);
   const int part = gt >> d.tp_shift;
   if (part < nparts) {
     const int pos = atomicAdd(&s_cur[part], 1);
     if (pos < d.cap) {
-      d.ebuf[((size_t)part * gridDim.x + blockIdx.x) * d.cap + pos] =
+      d.ebuf[((size_t)part * d.NB + vb) * d.cap + pos] =
           make_uint2((unsigned)((r << d.tp_shift) | (gt & ((1 << d.tp_shift) - 1))), (unsigned)a);
       return;
     }
@@ -343,32 +335,34 @@ __device__ __forceinline__ unsigned long long walk_word(const Dev& d, const unsi
   return words[(size_t)(circular ? n % d.R : n) * d.words + word];
 }
 
-// Pass 1 of the expansion of window [k0, k0 + W) for the spikes of steps [n_lo, n_hi), with
-// k0 - d_max <= n_lo and n_hi <= k0.  Every lane that holds a spike looks up the piece of the
-// spike's sorted row that lands in the window (dstart); the wavefront then reads the pieces four
-// at a time (8 full-width loads in flight) and stages the events by target part.  stage = 0:
-// every event is added to the window with a global atomic instead.  With stage != 0, gridDim.x
-// must be d.NB (the staging regions are per block).
-__global__ __launch_bounds__(kBinThreads) void k_win_bin(Dev d, long long k0, long long n_lo, long long n_hi,
-                                                         int stage) {
-  __shared__ int s_cur[kMaxParts];
-  const int nparts = (stage && d.cap > 0) ? (d.P < kMaxParts ? d.P : kMaxParts) : 0;
-  int* __restrict__ win = win_of(d, k0);
-  for (int x = threadIdx.x; x < nparts; x += kBinThreads) s_cur[x] = 0;
-  __syncthreads();
+// Walks the spike words of steps [n_lo, n_hi) as virtual block vb of nvb (16 wavefronts each)
+// and, for every spike, looks up the piece of its sorted row with arrival offsets
+// [k0 - n, k0 - n + W) (cut at arrival T when T >= 0) and appends it to the block's LDS queue;
+// handle(seg) is called instead when the queue is full.  Spikes of steps >= count_from are
+// counted into cnt[3] (spikes, their events, Q8.24 sum of those).  Ends with a block barrier.
+template <class Direct>
+__device__ __forceinline__ void walk_segments(const Dev& d, ExpandLds& L, const unsigned long long* __restrict__ words,
+                                              bool circular, long long k0, long long n_lo, long long n_hi,
+                                              long long T, int vb, int nvb, long long count_from,
+                                              long long* cnt, Direct handle) {
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const long long gw = blockIdx.x + (long long)gridDim.x * wv;   // blocks interleaved: every block sees every step
-  const long long nwaves = (long long)gridDim.x * kBinWaves;
+  const long long gw = vb + (long long)nvb * wv;   // blocks interleaved: every block sees every step
+  const long long nwaves = (long long)nvb * kRingWaves;
   const long long nlines = (n_hi - n_lo) * ((d.words + 7) >> 3);
   const int nb = d.d_max + 2;
   for (long long c0 = gw; c0 < nlines; c0 += nwaves * 8) {
     long long n; int word;
-    unsigned long long bits = walk_word(d, d.spike_bits, true, n_lo, n_hi, c0, nwaves, &n, &word);
+    unsigned long long bits = walk_word(d, words, circular, n_lo, n_hi, c0, nwaves, &n, &word);
     const int dlo = (int)(k0 - n);                      // 1 .. d_max
-    const int dhi = dlo + d.W < nb - 1 ? dlo + d.W : nb - 1;
+    int dhi = dlo + d.W < nb - 1 ? dlo + d.W : nb - 1;
+    if (T >= 0) {
+      if ((long long)dhi > T - n) dhi = (int)(T - n);   // arrivals n + D >= T are never delivered
+      if (dhi < dlo) dhi = dlo;
+    }
+    const bool counted = n >= count_from;
     while (__ballot(bits != 0ull)) {
-      // every lane that still has a spike takes its lowest one: row piece [p0, p0 + len)
-      long long p0 = 0; int len = 0, base = 0;
+      // every lane that still has a spike takes its lowest one
+      Seg sg; sg.p0 = 0; sg.len = 0; sg.base = 0; sg.dlo = dlo; sg.slot = (int)(n % d.R); sg.g = 0;
       if (bits) {
         const int bit = __ffsll((long long)bits) - 1;
         bits &= bits - 1;
@@ -377,63 +371,122 @@ __global__ __launch_bounds__(kBinThreads) void k_win_bin(Dev d, long long k0, lo
           const int b = (int)(g / d.N), i = (int)(g - (long long)b * d.N);
           const unsigned* ds = d.dstart + (size_t)i * nb;
           const unsigned q0 = ds[dlo], q1 = ds[dhi];
-          p0 = d.row_ptr[i] + q0; len = (int)(q1 - q0); base = b * d.N;
+          const long long r0 = d.row_ptr[i];
+          sg.p0 = r0 + q0; sg.len = (int)(q1 - q0); sg.base = b * d.N; sg.g = g;
+          if (counted) { cnt[0] += 1; cnt[1] += d.row_ptr[i + 1] - r0; cnt[2] += d.rowsum[i]; }
         }
       }
-      unsigned long long todo = __ballot(len > 0);
-      while (todo) {
-        int L[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) { L[j] = -1; if (todo) { L[j] = __ffsll((long long)todo) - 1; todo &= todo - 1; } }
-        long long P0[4]; int LEN[4], BASE[4], DLO[4];
-        uint2 ev[4][2];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          LEN[j] = 0; P0[j] = 0; BASE[j] = 0; DLO[j] = 0;
-          if (L[j] >= 0) {
-            P0[j] = __shfl(p0, L[j], 64); LEN[j] = __shfl(len, L[j], 64);
-            BASE[j] = __shfl(base, L[j], 64); DLO[j] = __shfl(dlo, L[j], 64);
-          }
-#pragma unroll
-          for (int h = 0; h < 2; ++h) {
-            ev[j][h] = make_uint2(0u, 0u);
-            if (lane + 64 * h < LEN[j]) ev[j][h] = d.synf[P0[j] + lane + 64 * h];
-          }
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-#pragma unroll
-          for (int h = 0; h < 2; ++h)
-            if (lane + 64 * h < LEN[j]) stage_event(d, win, s_cur, nparts, ev[j][h].x, (int)ev[j][h].y, DLO[j], BASE[j]);
-          for (int q = 128 + lane; q < LEN[j]; q += 64) {
-            const uint2 e = d.synf[P0[j] + q];
-            stage_event(d, win, s_cur, nparts, e.x, (int)e.y, DLO[j], BASE[j]);
-          }
+      const bool has = sg.len > 0;
+      const unsigned long long mask = __ballot(has);
+      if (mask) {
+        int pos = 0;
+        if (lane == 0) pos = atomicAdd(&L.qn, __popcll(mask));
+        pos = __shfl(pos, 0, 64) + __popcll(mask & ((1ull << lane) - 1ull));
+        if (has && pos < kSegQueue) L.q[pos] = sg;
+        unsigned long long ovf = __ballot(has && pos >= kSegQueue);
+        while (ovf) {
+          const int src = __ffsll((long long)ovf) - 1;
+          ovf &= ovf - 1;
+          Seg o;
+          o.p0 = __shfl(sg.p0, src, 64); o.len = __shfl(sg.len, src, 64); o.base = __shfl(sg.base, src, 64);
+          o.dlo = __shfl(sg.dlo, src, 64); o.slot = __shfl(sg.slot, src, 64); o.g = __shfl(sg.g, src, 64);
+          handle(o);
         }
       }
     }
   }
   __syncthreads();
-  for (int x = threadIdx.x; x < nparts; x += kBinThreads) {
-    const int c = s_cur[x];
-    d.ecnt[(size_t)x * gridDim.x + blockIdx.x] = c < d.cap ? c : d.cap;
+}
+
+// Adds the block's totals of cnt[0..3) to ctr->tape_spikes / offered / sum_offered.
+__device__ __forceinline__ void fold_counts(const Dev& d, ExpandLds& L, long long* cnt) {
+  for (int k = 0; k < 3; ++k) {
+    const long long v = wave_sum(cnt[k]);
+    if ((threadIdx.x & 63) == 0) L.red[k][threadIdx.x >> 6] = v;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    long long t[3] = {0, 0, 0};
+    for (int k = 0; k < 3; ++k) for (int w = 0; w < kRingWaves; ++w) t[k] += L.red[k][w];
+    if (t[0]) atomicAdd((unsigned long long*)&d.ctr->tape_spikes, (unsigned long long)t[0]);
+    if (t[1]) atomicAdd(&d.ctr->offered, (unsigned long long)t[1]);
+    if (t[2]) atomicAdd((unsigned long long*)&d.ctr->sum_offered, (unsigned long long)t[2]);
   }
 }
 
-// Pass 2: block `part` sums the staged events of its target range into an LDS tile
-// [W][targets per part] and adds the tile to the buffer of window k0.  nb_runs = grid size of
-// pass 1 (a multiple of 16 or below 16).  A run (the events one block of pass 1 staged for this
-// part) is read by a 16-lane group, 4 runs per load instruction, 4 instructions in flight.
-__global__ __launch_bounds__(kBinThreads) void k_win_acc(Dev d, long long k0, int nb_runs) {
-  __shared__ int tile[kMaxTileCells];
-  const int part = blockIdx.x;
+// Staging role (pass 1 of the expansion of window [k0, k0 + W)) for the spikes of steps
+// [n_lo, n_hi), k0 - d_max <= n_lo, n_hi <= k0, as virtual block vb of nvb.  The walk fills the
+// block's queue of row pieces; then the wavefronts take pieces four at a time (8 full-width loads
+// in flight) and stage the events by target part.  stage = 0: every event is added to the window
+// with a global atomic instead.  With stage != 0, nvb must be d.NB (one staging region per part
+// and virtual block).
+__device__ __forceinline__ void role_bin(const Dev& d, ExpandLds& L, long long k0, long long n_lo, long long n_hi,
+                                         int vb, int nvb, int stage, long long count_from) {
+  const int nparts = (stage && d.cap > 0) ? (d.P < kMaxParts ? d.P : kMaxParts) : 0;
+  int* __restrict__ win = win_of(d, k0);
+  for (int x = threadIdx.x; x < nparts; x += kRingThreads) L.cur[x] = 0;
+  if (threadIdx.x == 0) { L.qn = 0; L.qhead = 0; }
+  __syncthreads();
+  const int lane = threadIdx.x & 63;
+  auto one = [&](const Seg& o) {
+    for (int q = lane; q < o.len; q += 64) {
+      const uint2 e = d.synf[o.p0 + q];
+      stage_event(d, win, L.cur, nparts, vb, e.x, (int)e.y, o.dlo, o.base);
+    }
+  };
+  long long cnt[3] = {0, 0, 0};
+  walk_segments(d, L, d.spike_bits, true, k0, n_lo, n_hi, -1, vb, nvb, count_from, cnt, one);
+  const int qn = L.qn < kSegQueue ? L.qn : kSegQueue;
+  for (;;) {
+    int t = 0;
+    if (lane == 0) t = atomicAdd(&L.qhead, 4);
+    t = __shfl(t, 0, 64);
+    if (t >= qn) break;
+    Seg o[4];
+    uint2 ev[4][2];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      o[j].len = 0;
+      if (t + j < qn) o[j] = L.q[t + j];
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        ev[j][h] = make_uint2(0u, 0u);
+        if (lane + 64 * h < o[j].len) ev[j][h] = d.synf[o[j].p0 + lane + 64 * h];
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+        if (lane + 64 * h < o[j].len)
+          stage_event(d, win, L.cur, nparts, vb, ev[j][h].x, (int)ev[j][h].y, o[j].dlo, o[j].base);
+      for (int q = 128 + lane; q < o[j].len; q += 64) {
+        const uint2 e = d.synf[o[j].p0 + q];
+        stage_event(d, win, L.cur, nparts, vb, e.x, (int)e.y, o[j].dlo, o[j].base);
+      }
+    }
+  }
+  __syncthreads();
+  for (int x = threadIdx.x; x < nparts; x += kRingThreads) {
+    const int c = L.cur[x];
+    d.ecnt[(size_t)x * d.NB + vb] = c < d.cap ? c : d.cap;
+  }
+  if (count_from < n_hi) fold_counts(d, L, cnt);
+}
+
+// Accumulation role (pass 2): sums the staged events of target part `part` into an LDS tile
+// [W][targets per part] and adds the tile to the buffer of window k0.  A run (the events one
+// virtual block of pass 1 staged for this part) is read by a 16-lane group, 4 runs per load
+// instruction, 4 instructions in flight.
+__device__ __forceinline__ void role_acc(const Dev& d, int* tile, long long k0, int part) {
   const int cells = d.W << d.tp_shift;
-  for (int x = threadIdx.x; x < cells; x += kBinThreads) tile[x] = 0;
+  const int nb_runs = d.NB;
+  for (int x = threadIdx.x; x < cells; x += kRingThreads) tile[x] = 0;
   __syncthreads();
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int sub = lane & 15, grp = lane >> 4;
   const int* __restrict__ cnts = d.ecnt + (size_t)part * nb_runs;
-  for (int r0 = (wv * 4 + grp) * 4; r0 < nb_runs; r0 += kBinWaves * 16) {
+  for (int r0 = (wv * 4 + grp) * 4; r0 < nb_runs; r0 += kRingWaves * 16) {
     int cn[4]; uint2 ev[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) cn[j] = r0 + j < nb_runs ? cnts[r0 + j] : 0;
@@ -454,7 +507,7 @@ __global__ __launch_bounds__(kBinThreads) void k_win_acc(Dev d, long long k0, in
   __syncthreads();
   const int tp = 1 << d.tp_shift;
   int* __restrict__ win = win_of(d, k0);
-  for (int x = threadIdx.x; x < cells; x += kBinThreads) {
+  for (int x = threadIdx.x; x < cells; x += kRingThreads) {
     const int v = tile[x];
     const int r = x >> d.tp_shift;
     const long long t = (long long)part * tp + (x & (tp - 1));
@@ -462,6 +515,46 @@ __global__ __launch_bounds__(kBinThreads) void k_win_acc(Dev d, long long k0, in
       int* cell = &win[(size_t)r * d.BN + t];
       *cell = wrap_add(*cell, v);
     }
+  }
+}
+
+// The two passes of the expansion as kernels.
+// The same roles as launches of their own (window boundaries, catching up, open loop).
+__global__ __launch_bounds__(kRingThreads) void k_win_bin(Dev d, long long k0, long long n_lo, long long n_hi,
+                                                          int vb0, int nvb, int stage, long long count_from) {
+  __shared__ ExpandLds L;
+  role_bin(d, L, k0, n_lo, n_hi, vb0 + (int)blockIdx.x, nvb, stage, count_from);
+}
+__global__ __launch_bounds__(kRingThreads) void k_win_acc(Dev d, long long k0, int p0) {
+  __shared__ int tile[kMaxTileCells];
+  role_acc(d, tile, k0, p0 + (int)blockIdx.x);
+}
+
+// Spikes of steps [n_lo, n_hi) (still in the circular spike words), their events and the Q8.24
+// sum of those, added to out[0..3).  On demand only (counters of the steps since the last window
+// boundary).
+__global__ __launch_bounds__(kBlock) void k_count_spikes(Dev d, long long n_lo, long long n_hi,
+                                                         unsigned long long* out /*[3]*/) {
+  const long long items = (n_hi - n_lo) * d.words;
+  long long c0 = 0, c1 = 0, c2 = 0;
+  for (long long it = (long long)blockIdx.x * kBlock + threadIdx.x; it < items; it += (long long)gridDim.x * kBlock) {
+    const long long n = n_lo + it / d.words;
+    const long long word = it % d.words;
+    unsigned long long bits = d.spike_bits[(size_t)(n % d.R) * d.words + word];
+    while (bits) {
+      const int bit = __ffsll((long long)bits) - 1;
+      bits &= bits - 1;
+      const long long g = word * 64 + bit;
+      if (g >= d.BN) break;
+      const int i = (int)(g % d.N);
+      c0 += 1; c1 += d.row_ptr[i + 1] - d.row_ptr[i]; c2 += d.rowsum[i];
+    }
+  }
+  c0 = wave_sum(c0); c1 = wave_sum(c1); c2 = wave_sum(c2);
+  if ((threadIdx.x & 63) == 0) {
+    if (c0) atomicAdd(&out[0], (unsigned long long)c0);
+    if (c1) atomicAdd(&out[1], (unsigned long long)c1);
+    if (c2) atomicAdd(&out[2], (unsigned long long)c2);
   }
 }
 
@@ -492,6 +585,18 @@ __global__ __launch_bounds__(kBlock) void k_ring_in_flight(Dev d, long long n_en
   block_add2(&out[0], cnt, (long long*)&out[1], sum);
 }
 
+// Spike count of every (trial, neuron) over the recorded steps [0, T), from the recorded spike
+// words.  One thread per neuron; the 64 threads of a wavefront share each word.
+__global__ __launch_bounds__(kBlock) void k_spike_counts_bits(Dev d, long long T, int* __restrict__ counts) {
+  const int g = blockIdx.x * kBlock + threadIdx.x;
+  if (g >= d.BN) return;
+  const unsigned long long* __restrict__ w = d.tape_bits + (g >> 6);
+  const int sh = g & 63;
+  int c = 0;
+  for (long long n = 0; n < T; ++n) c += (int)((w[(size_t)n * d.words] >> sh) & 1ull);
+  counts[g] = c;
+}
+
 // ---------------------------------------------------------------- reverse sweep
 
 // Gathers the adjoint at the arrival cell of the entries [0, cnt) of the sorted row at pr0
@@ -503,10 +608,9 @@ __device__ __forceinline__ float near_gather(const Dev& d, const float* __restri
   float G = 0.0f;
   for (unsigned q = lane; q < cnt; q += 64) {
     const uint2 e = d.synb[pr0 + q];
-    const unsigned pk = e.x;
-    const int D = (int)(pk & d.dmask);
+    const int D = (int)(e.x & d.dmask);
     if (n + D < T) {
-      const float gv = gwin[(size_t)(phi + D) * d.BN + (size_t)base + (pk >> d.dbits)];
+      const float gv = gwin[(size_t)(phi + D) * d.BN + (size_t)base + (e.x >> d.dbits)];
       G += __uint_as_float(e.y) * gv;
       unsafeAtomicAdd(&d.gsum[pr0 + q], gv);
     }
@@ -516,8 +620,8 @@ __device__ __forceinline__ float near_gather(const Dev& d, const float* __restri
 }
 
 // Reverse step n: queue term of the block's spikes = far part (left in Gacc by the windows
-// already swept) + near part (gathered here from the rows of this window written by the
-// earlier launches), then
+// already swept) + near part (gathered here from the rows of this window written by the earlier
+// launches), then
 //   gU[n] = (1 - s) alpha gU[n+1] + sigma'(U - theta) (dL/dcount + s G) + dL/dU[n]
 __global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, long long T,
                                                          const float* __restrict__ dL_dcount,
@@ -529,24 +633,25 @@ __global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, lon
   if (near_h > d.d_max) near_h = d.d_max;
   float U = 0.0f, carry = 0.0f, inner = 0.0f, G = 0.0f, dU = 0.0f;
   bool s = false;
-  int b = 0, i = 0;
+  int b = 0;
   long long r0 = 0;
   unsigned ncnt = 0;
   float* __restrict__ gwin = gwin_of(d, n);
   if (act) {
-    b = g / d.N; i = g - b * d.N;
+    b = g / d.N;
+    const int i = g - b * d.N;
     U = d.tapeU[(size_t)n * d.BN + g];
     carry = d.bwd_carry[g];
     r0 = d.row_ptr[i];
     if (near_h >= 1) ncnt = d.nearcnt[(size_t)near_h * d.N + i];
     if (dL_dcount) inner = dL_dcount[g];
     if (dL_dU) dU = dL_dU[(size_t)n * d.BN + g];
+    // far queue term: only spiking neurons have one, but it is loaded for all so that it does
+    // not wait for the membrane value
+    float* ga = &d.Gacc[(size_t)(n % d.R) * d.BN + g];
+    G = *ga;
     s = U >= d.theta;
-    if (s) {
-      float* ga = &d.Gacc[(size_t)(n % d.R) * d.BN + g];
-      G = *ga;
-      if (G != 0.0f) *ga = 0.0f;
-    }
+    if (G != 0.0f) *ga = 0.0f;
   }
   unsigned long long m = __ballot(s && ncnt > 0);
   const int lane = threadIdx.x & 63;
@@ -571,108 +676,115 @@ __global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, lon
   }
 }
 
-// Far part of the queue terms for window [k0, k0 + W), whose adjoint rows are complete: for
-// every recorded spike of steps [n_lo, n_hi) (k0 - d_max <= n_lo, n_hi <= k0) the piece of its
-// sorted row that arrives in the window gathers its adjoints, adds them to gsum, and the
-// wavefront's sum of amplitude * adjoint is added to Gacc[n mod R][g] (one wavefront per spike
-// and launch: plain update).  Same walk over the spike words as k_win_bin.
-__global__ __launch_bounds__(kBlock) void k_bwd_win(Dev d, long long k0, long long n_lo, long long n_hi,
-                                                    long long T) {
+// Gather role: far part of the queue terms for window [k0, k0 + W), whose adjoint rows are
+// complete, for the recorded spikes of steps [n_lo, n_hi) (k0 - d_max <= n_lo, n_hi <= k0), as
+// virtual block vb of nvb.  The piece of each spike's sorted row that arrives in the window
+// gathers its adjoints from the window (6.4 MB: the L2 holds it), adds them to gsum, and the
+// wavefront's sum of amplitude * adjoint is added to Gacc[n mod R][g] (one wavefront per piece,
+// one piece per spike and window: plain update).
+__device__ __forceinline__ void role_gather(const Dev& d, ExpandLds& L, long long k0, long long n_lo, long long n_hi,
+                                            long long T, int vb, int nvb) {
+  if (threadIdx.x == 0) { L.qn = 0; L.qhead = 0; }
+  __syncthreads();
   const int lane = threadIdx.x & 63;
-  const long long gw = ((long long)blockIdx.x * kBlock + threadIdx.x) >> 6;
-  const long long nwaves = ((long long)gridDim.x * kBlock) >> 6;
-  const long long nlines = (n_hi - n_lo) * ((d.words + 7) >> 3);
-  const int nb = d.d_max + 2;
   const float* __restrict__ gwin = gwin_of(d, k0);
-  for (long long c0 = gw; c0 < nlines; c0 += nwaves * 8) {
-    long long n; int word;
-    unsigned long long bits = walk_word(d, d.tape_bits, false, n_lo, n_hi, c0, nwaves, &n, &word);
-    const int dlo = (int)(k0 - n);
-    int dhi = dlo + d.W < nb - 1 ? dlo + d.W : nb - 1;
-    if ((long long)dhi > T - n) dhi = (int)(T - n);    // arrivals n + D >= T are never delivered
-    if (dhi < dlo) dhi = dlo;
-    const int slot = (int)(n % d.R);
-    while (__ballot(bits != 0ull)) {
-      long long p0 = 0, g = 0; int len = 0, base = 0;
-      if (bits) {
-        const int bit = __ffsll((long long)bits) - 1;
-        bits &= bits - 1;
-        g = (long long)word * 64 + bit;
-        if (g < d.BN) {
-          const int b = (int)(g / d.N), i = (int)(g - (long long)b * d.N);
-          const unsigned* ds = d.dstart + (size_t)i * nb;
-          const unsigned q0 = ds[dlo], q1 = ds[dhi];
-          p0 = d.row_ptr[i] + q0; len = (int)(q1 - q0); base = b * d.N;
-        }
+  auto finish = [&](const Seg& o, float G) {
+    G = wave_sum_f(G);
+    if (lane == 0) {
+      float* ga = &d.Gacc[(size_t)o.slot * d.BN + o.g];
+      *ga += G;
+    }
+  };
+  auto one = [&](const Seg& o) {
+    float G = 0.0f;
+    for (int q = lane; q < o.len; q += 64) {
+      const uint2 e = d.synb[o.p0 + q];
+      const float x = gwin[(size_t)((int)(e.x & d.dmask) - o.dlo) * d.BN + (size_t)o.base + (e.x >> d.dbits)];
+      G += __uint_as_float(e.y) * x;
+      unsafeAtomicAdd(&d.gsum[o.p0 + q], x);
+    }
+    finish(o, G);
+  };
+  long long cnt[3] = {0, 0, 0};
+  walk_segments(d, L, d.tape_bits, false, k0, n_lo, n_hi, T, vb, nvb, n_hi, cnt, one);
+  const int qn = L.qn < kSegQueue ? L.qn : kSegQueue;
+  for (;;) {
+    int t = 0;
+    if (lane == 0) t = atomicAdd(&L.qhead, 4);
+    t = __shfl(t, 0, 64);
+    if (t >= qn) break;
+    Seg o[4];
+    uint2 ev[4][2];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      o[j].len = 0;
+      if (t + j < qn) o[j] = L.q[t + j];
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        ev[j][h] = make_uint2(0u, 0u);
+        if (lane + 64 * h < o[j].len) ev[j][h] = d.synb[o[j].p0 + lane + 64 * h];
       }
-      unsigned long long todo = __ballot(len > 0);
-      while (todo) {
-        int L[4];
+    }
+    float gv[4][2];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { L[j] = -1; if (todo) { L[j] = __ffsll((long long)todo) - 1; todo &= todo - 1; } }
-        long long P0[4]; int LEN[4], BASE[4], DLO[4];
-        uint2 ev[4][2];
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          LEN[j] = 0; P0[j] = 0; BASE[j] = 0; DLO[j] = 0;
-          if (L[j] >= 0) {
-            P0[j] = __shfl(p0, L[j], 64); LEN[j] = __shfl(len, L[j], 64);
-            BASE[j] = __shfl(base, L[j], 64); DLO[j] = __shfl(dlo, L[j], 64);
-          }
-#pragma unroll
-          for (int h = 0; h < 2; ++h) {
-            ev[j][h] = make_uint2(0u, 0u);
-            if (lane + 64 * h < LEN[j]) ev[j][h] = d.synb[P0[j] + lane + 64 * h];
-          }
-        }
-        float gv[4][2];
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-          for (int h = 0; h < 2; ++h) {
-            gv[j][h] = 0.0f;
-            if (lane + 64 * h < LEN[j])
-              gv[j][h] = gwin[(size_t)((int)(ev[j][h].x & d.dmask) - DLO[j]) * d.BN + (size_t)BASE[j] + (ev[j][h].x >> d.dbits)];
-          }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          if (L[j] < 0) continue;
-          float G = 0.0f;
-#pragma unroll
-          for (int h = 0; h < 2; ++h)
-            if (lane + 64 * h < LEN[j]) {
-              G += __uint_as_float(ev[j][h].y) * gv[j][h];
-              unsafeAtomicAdd(&d.gsum[P0[j] + lane + 64 * h], gv[j][h]);
-            }
-          for (int q = 128 + lane; q < LEN[j]; q += 64) {
-            const uint2 e = d.synb[P0[j] + q];
-            const float x = gwin[(size_t)((int)(e.x & d.dmask) - DLO[j]) * d.BN + (size_t)BASE[j] + (e.x >> d.dbits)];
-            G += __uint_as_float(e.y) * x;
-            unsafeAtomicAdd(&d.gsum[P0[j] + q], x);
-          }
-          G = wave_sum_f(G);
-          const long long GG = __shfl(g, L[j], 64);
-          const int SL = __shfl(slot, L[j], 64);
-          if (lane == 0) {
-            float* ga = &d.Gacc[(size_t)SL * d.BN + GG];
-            *ga += G;
-          }
-        }
+      for (int h = 0; h < 2; ++h) {
+        gv[j][h] = 0.0f;
+        if (lane + 64 * h < o[j].len)
+          gv[j][h] = gwin[(size_t)((int)(ev[j][h].x & d.dmask) - o[j].dlo) * d.BN + (size_t)o[j].base + (ev[j][h].x >> d.dbits)];
       }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (t + j >= qn) continue;
+      float G = 0.0f;
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+        if (lane + 64 * h < o[j].len) {
+          G += __uint_as_float(ev[j][h].y) * gv[j][h];
+          unsafeAtomicAdd(&d.gsum[o[j].p0 + lane + 64 * h], gv[j][h]);
+        }
+      for (int q = 128 + lane; q < o[j].len; q += 64) {
+        const uint2 e = d.synb[o[j].p0 + q];
+        const float x = gwin[(size_t)((int)(e.x & d.dmask) - o[j].dlo) * d.BN + (size_t)o[j].base + (e.x >> d.dbits)];
+        G += __uint_as_float(e.y) * x;
+        unsafeAtomicAdd(&d.gsum[o[j].p0 + q], x);
+      }
+      finish(o[j], G);
     }
   }
 }
 
+__global__ __launch_bounds__(kRingThreads) void k_bwd_win(Dev d, long long k0, long long n_lo, long long n_hi,
+                                                          long long T, int vb0, int nvb) {
+  __shared__ ExpandLds L;
+  role_gather(d, L, k0, n_lo, n_hi, T, vb0 + (int)blockIdx.x, nvb);
+}
+
 // grad_w[p] = f_p * gsum, grad_d[p] = a_p * dscale * gsum, back in the caller's synapse order.
+// One block per row: rows of up to kFinishRow entries are un-permuted through LDS so that both
+// the reads (sorted order) and the writes (caller's order) are coalesced; longer rows write
+// through perm directly.
+constexpr int kFinishRow = 4096;
 __global__ __launch_bounds__(kBlock) void k_grad_finish(Dev d, float dscale, float* __restrict__ grad_w,
                                                         float* __restrict__ grad_d) {
+  __shared__ float s_w[kFinishRow];
+  __shared__ float s_d[kFinishRow];
   for (long long i = blockIdx.x; i < d.N; i += gridDim.x) {
     const long long r0 = d.row_ptr[i], r1 = d.row_ptr[i + 1];
+    const bool small = r1 - r0 <= kFinishRow;   // uniform over the block
     for (long long q = r0 + threadIdx.x; q < r1; q += kBlock) {
       const float gs = d.gsum[q];
-      const long long p = r0 + d.perm[q];
-      grad_w[p] = (d.continuous ? d.fdec[q] : 1.0f) * gs;
-      grad_d[p] = __uint_as_float(d.synb[q].y) * dscale * gs;
+      const unsigned pp = d.perm[q];
+      const float gw = (d.continuous ? d.fdec[q] : 1.0f) * gs;
+      const float gd = __uint_as_float(d.synb[q].y) * dscale * gs;
+      if (small) { s_w[pp] = gw; s_d[pp] = gd; }
+      else { grad_w[r0 + pp] = gw; grad_d[r0 + pp] = gd; }
+    }
+    if (small) {
+      __syncthreads();
+      for (long long p = r0 + threadIdx.x; p < r1; p += kBlock) { grad_w[p] = s_w[p - r0]; grad_d[p] = s_d[p - r0]; }
+      __syncthreads();
     }
   }
 }

@@ -82,6 +82,7 @@ def test_null_handle_is_an_error_not_a_crash():
     assert lib.adseq_enqueue(None, 0, None, None, None) == -1
     assert lib.adseq_backward(None, None, None, None, None, None) == -1
     assert lib.adseq_drop_count(None, None, None, None, None) == -1
+    assert lib.adseq_spike_counts(None, None, None) == -1
     assert lib.adseq_profile(None, 1) == -1
     assert lib.adseq_profile_read(None, None, None, None) == -1
     assert lib.adseq_last_error(None) == b"null handle"
