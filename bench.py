@@ -138,6 +138,10 @@ def main():
                  "lif": "k_step_win (pop + drive + LIF + spike bits + in-window scatter)",
                  "bwd_gather": "k_bwd_win (far queue terms and gradient sums of one window)",
                  "bwd_neurons": "k_bwd_step_win (adjoint update + in-window gather)"}
+    else:
+        label = {"fan_out": "k_fanout (CSR fan-out, full-target drops, contender registration)",
+                 "lif": "k_neurons (admission + pop + drive + LIF + compaction)",
+                 "bwd_gather": "k_bwd_gather", "bwd_neurons": "k_bwd_neurons"}
     kernels = {}
     for k, v in prof.items():
         if v["launches"]:

@@ -128,8 +128,8 @@ int adseq_deliver(adseq_t *h, int64_t step, float *I_out, void *stream);
 /* Open-loop enqueue (the queue's enqueue, Section 4.2): fans out the spikes listed in
  * spike_ids[0 .. *n_spikes) (flat ids b*N + i, each id at most once per step; both DEVICE
  * pointers) with emission step `step`, which must be the step last delivered.  May be called
- * several times for one step; for the bounded kinds admission is then canonical within each
- * call and calls are served in order. */
+ * several times for one step; for the bounded kinds the events of all these calls are then
+ * admitted together, in canonical order. */
 int adseq_enqueue(adseq_t *h, int64_t step, const int32_t *spike_ids, const int32_t *n_spikes,
                   void *stream);
 
@@ -171,7 +171,10 @@ int adseq_counters(adseq_t *h, int64_t *out8, void *stream);
  * step_offset (NULL for ADSEQ_RING, whose fused step keeps no spike list): int64 [max_steps+1],
  * spikes of step n are spike_id[step_offset[n] .. step_offset[n+1]) (flat ids, unordered within
  * a step); event_base: int64 per recorded spike, index of its row's first admission flag;
- * admitted: one byte per emitted event (bounded kinds only, else NULL). */
+ * admitted: one byte per emitted event (bounded kinds only, else NULL).  FIFO / SORTED decide the
+ * admission of a step's events in the launch of the next step (or of adseq_counters,
+ * adseq_drop_count, adseq_backward); adseq_tape launches what is pending on the stream of the
+ * last enqueue, so the flags are final once that stream has been synchronised. */
 typedef struct {
   const float *membrane;
   const int64_t *step_offset;
@@ -180,7 +183,7 @@ typedef struct {
   const uint8_t *admitted;
   int64_t steps_recorded;
 } adseq_tape_view;
-int adseq_tape(const adseq_t *h, adseq_tape_view *out);
+int adseq_tape(adseq_t *h, adseq_tape_view *out);
 
 /* Spike count of every (trial, neuron) over the steps recorded since the last reset (the input of
  * the spike-count loss of the paper's recurrent-network benchmark, Section 5.1): counts int32

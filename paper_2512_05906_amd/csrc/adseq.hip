@@ -36,7 +36,6 @@ namespace {
 
 constexpr int kBlock = 256;
 constexpr int kFanoutBlocks = 1024;
-constexpr int kAdmitBlocks = 1024;
 
 enum : unsigned {
   ERR_DELAY = 1u, ERR_GRAPH = 2u, ERR_TAPE_SPIKES = 4u, ERR_TAPE_EVENTS = 8u, ERR_POOL = 16u
@@ -51,6 +50,14 @@ struct Counters {
   int pool_n[2];
   unsigned long long in_flight[2];  // scratch of k_ring_in_flight: events, Q8.24 sum
   unsigned long long fold[3];       // scratch of k_count_spikes: spikes, events, Q8.24 sum
+};
+
+// FIFO / SORTED: private event counters of one block of k_neurons / k_fanout (one 64-byte line
+// each, so that no two blocks add to the same address; summed on demand).
+struct BlkCtr {
+  unsigned long long offered, dropped, delivered;
+  long long sum_offered, sum_dropped, sum_delivered;
+  long long pad[2];
 };
 
 struct ExpCoef { double c[21]; };
@@ -95,10 +102,15 @@ struct Dev {
   int* slot_a;
   int* occ;
   int* head;
-  int* c_head;
+  unsigned* min_k;      // FIFO: earliest stored arrival step per target (0xffffffff: none)
+  int* cnt;             // contenders registered per target since its last admission
+  long long* cont_p;    // [kCont][BN] contender slots: synapse index,
+  unsigned* cont_k;     //   arrival step,
+  int* cont_a;          //   Q8.24 amplitude,
+  long long* cont_t;    //   index of the admission flag on the tape (recording only)
+  int* c_head;          // overflow list head per target (-1: empty)
   long long* pool_p;
   long long* pool_t;
-  int* pool_g;
   int* pool_next;
   unsigned* pool_k;
   int* pool_a;
@@ -112,6 +124,7 @@ struct Dev {
   float* bwd_carry;
   float* bwd_G;
   Counters* ctr;
+  BlkCtr* blk;   // FIFO / SORTED: [nblk + kFanoutBlocks]
   int nblk;      // neuron blocks of a step launch: ceil(BN / 256)
   int words;     // 64-neuron words per step in spike_bits (RING) = 4 * nblk
 };
@@ -218,12 +231,155 @@ __global__ __launch_bounds__(kBlock) void k_prepare(Dev d, ExpCoef ec) {
   }
 }
 
-// ---------------------------------------------------------------- pop + drive + LIF + compaction
+// ---------------------------------------------------------------- bounded queues (FIFO / SORTED)
+//
+// Every target owns `capacity` slots (arrival step, Q8.24 amplitude), slot-major so that one
+// slot of 64 consecutive targets is one line.  A step is two launches:
+//   k_fanout   one block per spike walks the CSR row; an event whose target is already full is
+//              dropped at once (the occupancy only grows during a step's enqueue phase); every
+//              other event registers as a contender of its target: ticket = atomic count,
+//              tickets below kCont go to the target's contender slots, later ones to an overflow
+//              list (linked list through a pool);
+//   k_neurons  the thread that owns target j first admits j's contenders of the step before --
+//              the min(K, free) with the smallest synapse index, the canonical order -- then pops
+//              the events due now, integrates and compacts the spikes.
+// So admission needs no atomics on the slots and no launch of its own; a contender's fate is known
+// one launch later (entry points that read counters or admission flags admit what is pending first).
+// FIFO keeps, per target, the earliest stored arrival step, so that only the targets with an event
+// due now scan their slots; SORTED keeps the slots ordered and pops from the front.
 
-// FIFO / SORTED.  One thread per (trial, neuron).  KIND selects how the due events are popped.
-// LIF = true: closed-loop step (drive, membrane update, spike compaction, tape);
-// LIF = false: open-loop delivery, writes the popped current to I_out.
-template <int KIND, bool LIF>
+constexpr int kCont = 8;   // contender slots per target and step before the overflow list is used
+
+// Stores one admitted event for target g (owner thread).  FIFO: into the next free slot.
+// SORTED: into its place in the circular array ordered by arrival step (behind the stored events
+// with the same step); the events behind it move up one slot, eight at a time so that the loads
+// of a group are in flight together.
+template <int KIND>
+__device__ __forceinline__ void store_event(const Dev& d, int g, int occ, int hd, unsigned k, int a) {
+  const size_t BN = (size_t)d.BN;
+  if (KIND == ADSEQ_FIFO) {
+    const size_t si = (size_t)occ * BN + g;
+    d.slot_k[si] = k; d.slot_a[si] = a;
+    return;
+  }
+  // position: first index (from the front) whose arrival step exceeds k; binary search
+  int lo = 0, hi = occ;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    int ph = hd + mid; if (ph >= d.C) ph -= d.C;
+    if (d.slot_k[(size_t)ph * BN + g] <= k) lo = mid + 1; else hi = mid;
+  }
+  for (int top = occ; top > lo;) {
+    const int nmove = top - lo < 8 ? top - lo : 8;     // move entries [top - nmove, top) up by one
+    unsigned mk[8]; int ma[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (j < nmove) {
+        int ph = hd + top - 1 - j; if (ph >= d.C) ph -= d.C;
+        mk[j] = d.slot_k[(size_t)ph * BN + g]; ma[j] = d.slot_a[(size_t)ph * BN + g];
+      }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (j < nmove) {
+        int pd = hd + top - j; if (pd >= d.C) pd -= d.C;
+        d.slot_k[(size_t)pd * BN + g] = mk[j]; d.slot_a[(size_t)pd * BN + g] = ma[j];
+      }
+    top -= nmove;
+  }
+  int pw = hd + lo; if (pw >= d.C) pw -= d.C;
+  d.slot_k[(size_t)pw * BN + g] = k; d.slot_a[(size_t)pw * BN + g] = a;
+}
+
+// Admits the contenders registered for target g (owner thread): the min(K, free) with the
+// smallest synapse index are stored, the others dropped (counted into c_drop / s_drop).
+template <int KIND>
+__device__ __forceinline__ void admit_contenders(const Dev& d, int g, long long* c_drop, long long* s_drop) {
+  const int K = d.cnt[g];
+  if (K <= 0) return;
+  d.cnt[g] = 0;
+  const size_t BN = (size_t)d.BN;
+  int occ = d.occ[g];
+  const int F = d.C - occ;
+  const int nc = K < kCont ? K : kCont;              // in the contender slots
+  const int ovf_head = K > kCont ? d.c_head[g] : -1; // the others: overflow list
+  if (K > kCont) d.c_head[g] = -1;
+  const int take = K < F ? K : F;
+  const int hd = KIND == ADSEQ_SORTED ? d.head[g] : 0;
+  unsigned mn = KIND == ADSEQ_FIFO ? d.min_k[g] : 0u;
+  // the contender slots, loaded together
+  long long cp[kCont], ct[kCont]; unsigned ck[kCont]; int ca[kCont];
+#pragma unroll
+  for (int x = 0; x < kCont; ++x) {
+    cp[x] = 0x7fffffffffffffffLL; ct[x] = -1; ck[x] = 0; ca[x] = 0;
+    if (x < nc) {
+      const size_t ci = (size_t)x * BN + g;
+      cp[x] = d.cont_p[ci]; ck[x] = d.cont_k[ci]; ca[x] = d.cont_a[ci];
+      if (d.record) ct[x] = d.cont_t[ci];
+    }
+  }
+  if (take == K) {
+    // room for all: any order
+#pragma unroll
+    for (int x = 0; x < kCont; ++x)
+      if (x < nc) {
+        store_event<KIND>(d, g, occ, hd, ck[x], ca[x]);
+        ++occ; mn = ck[x] < mn ? ck[x] : mn;
+        if (ct[x] >= 0) d.tape_adm[ct[x]] = 1;
+      }
+    for (int y = ovf_head; y >= 0; y = d.pool_next[y]) {
+      const unsigned k = d.pool_k[y];
+      store_event<KIND>(d, g, occ, hd, k, d.pool_a[y]);
+      ++occ; mn = k < mn ? k : mn;
+      const long long t = d.pool_t[y];
+      if (t >= 0) d.tape_adm[t] = 1;
+    }
+  } else {
+    // oversubscribed: the `take` smallest synapse indices win, the others are dropped
+    long long last = -1;
+    for (int r = 0; r < take; ++r) {
+      long long bp = 0x7fffffffffffffffLL; int bx = -1, by = -1;
+#pragma unroll
+      for (int x = 0; x < kCont; ++x)
+        if (cp[x] > last && cp[x] < bp) { bp = cp[x]; bx = x; }
+      for (int y = ovf_head; y >= 0; y = d.pool_next[y]) {
+        const long long pp = d.pool_p[y];
+        if (pp > last && pp < bp) { bp = pp; by = y; bx = -1; }
+      }
+      if (bx < 0 && by < 0) break;   // not reached: K counts exactly the registered contenders
+      last = bp;
+      unsigned k = 0; int a = 0; long long t = -1;
+      if (bx >= 0) {
+#pragma unroll
+        for (int x = 0; x < kCont; ++x) if (x == bx) { k = ck[x]; a = ca[x]; t = ct[x]; }
+      } else {
+        k = d.pool_k[by]; a = d.pool_a[by]; t = d.pool_t[by];
+      }
+      store_event<KIND>(d, g, occ, hd, k, a);
+      ++occ; mn = k < mn ? k : mn;
+      if (t >= 0) d.tape_adm[t] = 1;
+    }
+#pragma unroll
+    for (int x = 0; x < kCont; ++x)
+      if (x < nc && cp[x] > last) {
+        *c_drop += 1; *s_drop += ca[x];
+        if (ct[x] >= 0) d.tape_adm[ct[x]] = 0;
+      }
+    for (int y = ovf_head; y >= 0; y = d.pool_next[y]) {
+      if (d.pool_p[y] > last) {
+        *c_drop += 1; *s_drop += d.pool_a[y];
+        const long long t = d.pool_t[y];
+        if (t >= 0) d.tape_adm[t] = 0;
+      }
+    }
+  }
+  d.occ[g] = occ;
+  if (KIND == ADSEQ_FIFO) d.min_k[g] = mn;
+}
+
+// One thread per (trial, neuron).  MODE 0: admission only (what is pending); 1: admission + pop,
+// writes the popped current to I_out (open loop); 2: admission + pop + drive + LIF + spike
+// compaction + tape (closed loop).
+template <int KIND, int MODE>
 __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int parity,
                                                     const float* __restrict__ i_ext,
                                                     unsigned char* __restrict__ spikes_out,
@@ -231,51 +387,80 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
   const int g = blockIdx.x * kBlock + threadIdx.x;
   const bool act = g < d.BN;
   int acc = 0;
-  long long popped = 0;
+  long long popped = 0, c_drop = 0, s_drop = 0;
   const unsigned kn = (unsigned)n;
   if (blockIdx.x == 0 && threadIdx.x == 0) {
-    d.ctr->n_spk[parity ^ 1] = 0;  // next step's spike counter; nobody reads it now
+    d.ctr->pool_n[0] = 0;                        // the overflow pool is consumed by this launch
+    if (MODE == 2) d.ctr->n_spk[parity ^ 1] = 0;  // next step's spike counter; nobody reads it now
   }
   if (act) {
-    if (KIND == ADSEQ_FIFO) {
-      // bounded bag: every stored event due now leaves; survivors are packed to the front
-      const int occ = d.occ[g];
-      int keep = 0;
-      for (int s = 0; s < occ; ++s) {
-        const size_t si = (size_t)s * d.BN + g;
-        const unsigned k = d.slot_k[si];
-        if (k == kn) {
-          acc = wrap_add(acc, d.slot_a[si]);
-          ++popped;
-        } else {
-          if (keep != s) {
-            const size_t di = (size_t)keep * d.BN + g;
-            d.slot_k[di] = k;
-            d.slot_a[di] = d.slot_a[si];
+    admit_contenders<KIND>(d, g, &c_drop, &s_drop);
+    if (MODE != 0) {
+      const size_t BN = (size_t)d.BN;
+      if (KIND == ADSEQ_FIFO) {
+        // bounded bag: every stored event due now leaves.  Pass 1 only reads (all slot loads
+        // in flight together): sum of the due events, their positions, earliest arrival among
+        // the others.  Pass 2 fills each hole with the last stored event (the bag is unordered).
+        if (d.min_k[g] == kn) {
+          const int occ = d.occ[g];
+          unsigned mn = 0xffffffffu;
+          int ndue = 0;
+          int due[8];                      // positions of the first 8 due events, ascending
+          for (int s = 0; s < occ; ++s) {
+            const unsigned k = d.slot_k[(size_t)s * BN + g];
+            if (k == kn) { if (ndue < 8) due[ndue] = s; ++ndue; }
+            else mn = k < mn ? k : mn;
           }
-          ++keep;
+          int top = occ;
+          if (ndue <= 8) {
+            for (int j = ndue - 1; j >= 0; --j) {   // from the back, so that the last event is a survivor or the hole itself
+              const int s = due[j];
+              acc = wrap_add(acc, d.slot_a[(size_t)s * BN + g]);
+              --top;
+              if (s != top) {
+                d.slot_k[(size_t)s * BN + g] = d.slot_k[(size_t)top * BN + g];
+                d.slot_a[(size_t)s * BN + g] = d.slot_a[(size_t)top * BN + g];
+              }
+            }
+          } else {
+            // many due at once: pack the survivors to the front
+            int keep = 0;
+            for (int s = 0; s < occ; ++s) {
+              const size_t si = (size_t)s * BN + g;
+              const unsigned k = d.slot_k[si];
+              if (k == kn) {
+                acc = wrap_add(acc, d.slot_a[si]);
+              } else {
+                if (keep != s) { d.slot_k[(size_t)keep * BN + g] = k; d.slot_a[(size_t)keep * BN + g] = d.slot_a[si]; }
+                ++keep;
+              }
+            }
+            top = keep;
+          }
+          popped += ndue;
+          d.occ[g] = top;
+          d.min_k[g] = mn;
         }
-      }
-      if (keep != occ) d.occ[g] = keep;
-    } else {
-      // ordered by arrival: everything due now sits at the front of the circular array
-      int occ = d.occ[g];
-      if (occ > 0) {
-        int hd = d.head[g];
-        while (occ > 0 && d.slot_k[(size_t)hd * d.BN + g] == kn) {
-          acc = wrap_add(acc, d.slot_a[(size_t)hd * d.BN + g]);
-          hd = hd + 1 == d.C ? 0 : hd + 1;
-          --occ;
-          ++popped;
+      } else {
+        // ordered by arrival: everything due now sits at the front of the circular array
+        int occ = d.occ[g];
+        if (occ > 0) {
+          int hd = d.head[g];
+          while (occ > 0 && d.slot_k[(size_t)hd * BN + g] == kn) {
+            acc = wrap_add(acc, d.slot_a[(size_t)hd * BN + g]);
+            hd = hd + 1 == d.C ? 0 : hd + 1;
+            --occ;
+            ++popped;
+          }
+          if (popped) { d.occ[g] = occ; d.head[g] = hd; }
         }
-        if (popped) { d.occ[g] = occ; d.head[g] = hd; }
       }
     }
   }
   bool s = false;
-  if (act) {
+  if (act && MODE != 0) {
     float I = (float)acc * 0x1p-24f;
-    if (LIF) {
+    if (MODE == 2) {
       if (d.p_thresh) {
         const bool xi = (unsigned long long)drive_bits(d.seed, (unsigned long long)g,
                                                        (unsigned long long)n) < d.p_thresh;
@@ -291,7 +476,7 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
       I_out[g] = I;
     }
   }
-  if (LIF) {
+  if (MODE == 2) {
     // wavefront ballot + prefix popcount; one atomic per wavefront that has spikes
     const unsigned long long m = __ballot(s);
     const int lane = threadIdx.x & 63;
@@ -300,24 +485,23 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
     base = __shfl(base, 0, 64);
     if (s) d.cur_spk[base + __popcll(m & ((1ull << lane) - 1ull))] = g;
   }
-  block_add2(&d.ctr->delivered, popped, &d.ctr->sum_delivered, (long long)acc);
+  BlkCtr& bc = d.blk[blockIdx.x];
+  block_add2(&bc.delivered, popped, &bc.sum_delivered, (long long)acc);
+  block_add2(&bc.dropped, c_drop, &bc.sum_dropped, s_drop);
 }
 
-// ---------------------------------------------------------------- fan-out + enqueue
-
-// FIFO / SORTED.  One block per spike (grid-stride over the spike list); the block walks the
-// CSR row with coalesced reads of (packed, a_q).  Events whose target is already full are
-// dropped here; the others become contenders, pushed on their target's linked list for k_admit.
+// One block per spike (grid-stride over the spike list); the block walks the CSR row with
+// coalesced reads of (packed, a_q).  Events whose target is already full are dropped here; the
+// others register as contenders of their target (see above).
 template <int KIND>
 __global__ __launch_bounds__(kBlock) void k_fanout(Dev d, long long n, const int* __restrict__ spk,
-                                                   const int* __restrict__ n_spk_ptr, int parity,
-                                                   int record) {
+                                                   const int* __restrict__ n_spk_ptr, int record) {
   __shared__ long long s_evb;
   int nspk = *n_spk_ptr;
   nspk = nspk < 0 ? 0 : (nspk > d.BN ? d.BN : nspk);
-  if (blockIdx.x == 0 && threadIdx.x == 0) d.ctr->pool_n[parity ^ 1] = 0;
   const long long off = record ? d.step_off[n] : 0;
   const int lane = threadIdx.x & 63;
+  const size_t BN = (size_t)d.BN;
   long long c_off = 0, s_off = 0, c_drop = 0, s_drop = 0;
   for (int e = blockIdx.x; e < nspk; e += gridDim.x) {
     const int g = spk[e];
@@ -329,8 +513,6 @@ __global__ __launch_bounds__(kBlock) void k_fanout(Dev d, long long n, const int
       const bool fits = off + e < d.spike_cap;
       if (threadIdx.x == 0) {
         if (fits) d.tape_spk[off + e] = g; else atomicOr(&d.ctr->err, ERR_TAPE_SPIKES);
-      }
-      if (threadIdx.x == 0) {
         long long evb = (long long)atomicAdd((unsigned long long*)&d.ctr->tape_events,
                                              (unsigned long long)(r1 - r0));
         if (evb + (r1 - r0) > d.event_cap) { atomicOr(&d.ctr->err, ERR_TAPE_EVENTS); evb = -1; }
@@ -347,31 +529,38 @@ __global__ __launch_bounds__(kBlock) void k_fanout(Dev d, long long n, const int
       unsigned pk = 0; int a = 0;
       if (valid) { pk = d.packed[p]; a = d.a_q[p]; c_off += 1; s_off += a; }
       const int D = (int)(pk & d.dmask);
-      const int col = (int)(pk >> d.dbits);
-      {
-        const int gt = b * d.N + col;
-        const long long tidx = (valid && tbase >= 0) ? tbase + (p - r0) : -1;
-        bool contend = false;
-        if (valid) {
-          contend = d.occ[gt] < d.C;
-          if (!contend) { c_drop += 1; s_drop += a; if (tidx >= 0) d.tape_adm[tidx] = 0; }
-        }
-        // wavefront-aggregated claim of pool entries
-        const unsigned long long cm = __ballot(contend);
-        if (cm) {
-          int base = 0;
-          if (lane == __ffsll((long long)cm) - 1) base = atomicAdd(&d.ctr->pool_n[parity], __popcll(cm));
-          base = __shfl(base, __ffsll((long long)cm) - 1, 64);
-          if (contend) {
-            const int x = base + __popcll(cm & ((1ull << lane) - 1ull));
-            if (x >= d.pool_cap) {
-              atomicOr(&d.ctr->err, ERR_POOL);
-              c_drop += 1; s_drop += a; if (tidx >= 0) d.tape_adm[tidx] = 0;
-            } else {
-              d.pool_p[x] = p; d.pool_t[x] = tidx; d.pool_g[x] = gt;
-              d.pool_k[x] = (unsigned)(n + D); d.pool_a[x] = a;
-              d.pool_next[x] = atomicExch(&d.c_head[gt], x);
-            }
+      const int gt = b * d.N + (int)(pk >> d.dbits);
+      const long long tidx = (valid && tbase >= 0) ? tbase + (p - r0) : -1;
+      bool contend = false;
+      if (valid) {
+        contend = d.occ[gt] < d.C;
+        if (!contend) { c_drop += 1; s_drop += a; if (tidx >= 0) d.tape_adm[tidx] = 0; }
+      }
+      int ticket = -1;
+      if (contend) ticket = atomicAdd(&d.cnt[gt], 1);
+      if (contend && ticket < kCont) {
+        const size_t ci = (size_t)ticket * BN + gt;
+        d.cont_p[ci] = p; d.cont_k[ci] = (unsigned)(n + D); d.cont_a[ci] = a;
+        if (d.record) d.cont_t[ci] = tidx;
+      }
+      // the others: wavefront-aggregated claim of pool entries, pushed on the target's list
+      const bool over = contend && ticket >= kCont;
+      const unsigned long long cm = __ballot(over);
+      if (cm) {
+        int base = 0;
+        if (lane == __ffsll((long long)cm) - 1) base = atomicAdd(&d.ctr->pool_n[0], __popcll(cm));
+        base = __shfl(base, __ffsll((long long)cm) - 1, 64);
+        if (over) {
+          const int x = base + __popcll(cm & ((1ull << lane) - 1ull));
+          if (x >= d.pool_cap) {
+            // no room to remember it: it can only be dropped, and the run is flagged as invalid
+            atomicOr(&d.ctr->err, ERR_POOL);
+            atomicSub(&d.cnt[gt], 1);
+            c_drop += 1; s_drop += a; if (tidx >= 0) d.tape_adm[tidx] = 0;
+          } else {
+            d.pool_p[x] = p; d.pool_t[x] = tidx;
+            d.pool_k[x] = (unsigned)(n + D); d.pool_a[x] = a;
+            d.pool_next[x] = atomicExch(&d.c_head[gt], x);
           }
         }
       }
@@ -381,90 +570,9 @@ __global__ __launch_bounds__(kBlock) void k_fanout(Dev d, long long n, const int
     if (n + 1 <= d.max_steps) d.step_off[n + 1] = off + nspk;
     d.ctr->tape_spikes = off + nspk;
   }
-  block_add2(&d.ctr->offered, c_off, &d.ctr->sum_offered, s_off);
-  block_add2(&d.ctr->dropped, c_drop, &d.ctr->sum_dropped, s_drop);
-}
-
-// Admission for the bounded kinds.  One thread per contender; the thread whose entry is the head
-// of its target's list serves the whole list: the min(K, free) contenders with the smallest
-// synapse index are stored (canonical order), the rest are dropped.
-template <int KIND>
-__global__ __launch_bounds__(kBlock) void k_admit(Dev d, int parity) {
-  int np = d.ctr->pool_n[parity];
-  np = np > d.pool_cap ? d.pool_cap : np;
-  long long c_drop = 0, s_drop = 0;
-  for (int x0 = blockIdx.x * kBlock; x0 < np; x0 += gridDim.x * kBlock) {
-    const int x = x0 + threadIdx.x;
-    if (x >= np) continue;
-    const int gt = d.pool_g[x];
-    if (d.c_head[gt] != x) continue;
-    const int occ = d.occ[gt];
-    const int F = d.C - occ;
-    int K = 0;
-    for (int y = x; y >= 0; y = d.pool_next[y]) ++K;
-    const int take = K < F ? K : F;
-    int hd = KIND == ADSEQ_SORTED ? d.head[gt] : 0;
-    long long last = -1;
-    for (int r = 0; r < take; ++r) {
-      int best = -1; long long bp = 0x7fffffffffffffffLL;
-      for (int y = x; y >= 0; y = d.pool_next[y]) {
-        const long long pp = d.pool_p[y];
-        if (pp > last && pp < bp) { bp = pp; best = y; }
-      }
-      last = bp;
-      const unsigned k = d.pool_k[best];
-      const int a = d.pool_a[best];
-      if (KIND == ADSEQ_FIFO) {
-        const size_t si = (size_t)(occ + r) * d.BN + gt;
-        d.slot_k[si] = k; d.slot_a[si] = a;
-      } else {
-        // insertion from the back of the circular ordered array (stable for equal arrival steps)
-        int pos = occ + r;
-        while (pos > 0) {
-          int ph = hd + pos - 1; if (ph >= d.C) ph -= d.C;
-          const size_t si = (size_t)ph * d.BN + gt;
-          const unsigned kk = d.slot_k[si];
-          if (kk <= k) break;
-          int pd = ph + 1; if (pd >= d.C) pd -= d.C;
-          const size_t di = (size_t)pd * d.BN + gt;
-          d.slot_k[di] = kk; d.slot_a[di] = d.slot_a[si];
-          --pos;
-        }
-        int pw = hd + pos; if (pw >= d.C) pw -= d.C;
-        const size_t wi = (size_t)pw * d.BN + gt;
-        d.slot_k[wi] = k; d.slot_a[wi] = a;
-      }
-      const long long t = d.pool_t[best];
-      if (t >= 0) d.tape_adm[t] = 1;
-    }
-    if (take < K) {
-      for (int y = x; y >= 0; y = d.pool_next[y]) {
-        if (d.pool_p[y] > last) {
-          c_drop += 1; s_drop += d.pool_a[y];
-          const long long t = d.pool_t[y];
-          if (t >= 0) d.tape_adm[t] = 0;
-        }
-      }
-    }
-    d.occ[gt] = occ + take;
-    d.c_head[gt] = -1;
-  }
-  block_add2(&d.ctr->dropped, c_drop, &d.ctr->sum_dropped, s_drop);
-}
-
-// Ascending in-block list of the flagged threads: ballot + popcount prefix per wavefront,
-// wavefront totals through LDS.  Returns the number of entries and this thread's position.
-__device__ __forceinline__ int block_compact(bool flag, int* s_list, int* s_wcnt, int* pos_out) {
-  const unsigned long long m = __ballot(flag);
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  if (lane == 0) s_wcnt[w] = __popcll(m);
-  __syncthreads();
-  int base = 0, total = 0;
-  for (int x = 0; x < kBlock / 64; ++x) { const int c = s_wcnt[x]; if (x < w) base += c; total += c; }
-  const int pos = base + __popcll(m & ((1ull << lane) - 1ull));
-  if (flag) s_list[pos] = threadIdx.x;
-  *pos_out = pos;
-  return total;
+  BlkCtr& bc = d.blk[d.nblk + blockIdx.x];
+  block_add2(&bc.offered, c_off, &bc.sum_offered, s_off);
+  block_add2(&bc.dropped, c_drop, &bc.sum_dropped, s_drop);
 }
 
 // Spike counts from the recorded spike lists (FIFO / SORTED): counts must be zero on entry.
@@ -561,6 +669,8 @@ struct adseq {
   bool tape_ok;          // every step since reset went through adseq_step with recording
   char err[256];
   long long fold_upto = 0;  // RING: spikes of steps below this are in the device counters
+  bool pending_admit = false;  // FIFO/SORTED: contenders registered, admission not yet launched
+  hipStream_t last_stream = nullptr;  // stream of the last enqueue
   // optional kernel timing (adseq_profile): one event after each bracketed launch
   bool prof = false;
   std::vector<hipEvent_t> evs;
@@ -571,9 +681,9 @@ struct adseq {
 namespace {
 
 struct Layout {
-  size_t V, win, spike_bits, slot_k, slot_a, occ, head, c_head, pool_p, pool_t, pool_g, pool_next,
+  size_t V, win, spike_bits, slot_k, slot_a, occ, head, min_k, cnt, cont_p, cont_k, cont_a, cont_t, c_head, pool_p, pool_t, pool_next,
       pool_k, pool_a, cur_spk, packed, a_q, synf, synb, dstart, nearcnt, perm, rowsum, ebuf, ecnt, amp, fdec, tapeU,
-      tape_bits, step_off, tape_spk, tape_evb, tape_adm, bwd_ring, bwd_carry, bwd_G, gwin, Gacc, gsum, ctr,
+      tape_bits, step_off, tape_spk, tape_evb, tape_adm, bwd_ring, bwd_carry, bwd_G, gwin, Gacc, gsum, ctr, blk,
       total;
   long long spike_cap, event_cap, pool_cap;
   int R, dbits, nblk, words;
@@ -673,6 +783,7 @@ bool make_layout(const adseq_config* c, Layout* L) {
     L->cap = (int)(per > 65536.0 ? 65536.0 : per);
   }
   L->ctr = take(sizeof(Counters));
+  L->blk = take(bounded ? ((size_t)L->nblk + kFanoutBlocks) * sizeof(BlkCtr) : 0);
   L->V = take(BN * 4);
   L->win = take(bounded ? 0 : 2 * (size_t)L->W * BN * 4);
   L->spike_bits = take(bounded ? 0 : (size_t)L->R * L->words * 8);
@@ -680,10 +791,15 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->slot_a = take(bounded ? (size_t)c->capacity * BN * 4 : 0);
   L->occ = take(bounded ? BN * 4 : 0);
   L->head = take(bounded ? BN * 4 : 0);
+  L->min_k = take(bounded ? BN * 4 : 0);
+  L->cnt = take(bounded ? BN * 4 : 0);
+  L->cont_p = take(bounded ? (size_t)kCont * BN * 8 : 0);
+  L->cont_k = take(bounded ? (size_t)kCont * BN * 4 : 0);
+  L->cont_a = take(bounded ? (size_t)kCont * BN * 4 : 0);
+  L->cont_t = take(bounded && c->record_tape ? (size_t)kCont * BN * 8 : 0);
   L->c_head = take(bounded ? BN * 4 : 0);
   L->pool_p = take((size_t)L->pool_cap * 8);
   L->pool_t = take((size_t)L->pool_cap * 8);
-  L->pool_g = take((size_t)L->pool_cap * 4);
   L->pool_next = take((size_t)L->pool_cap * 4);
   L->pool_k = take((size_t)L->pool_cap * 4);
   L->pool_a = take((size_t)L->pool_cap * 4);
@@ -760,6 +876,10 @@ void launch_reset(adseq* h, hipStream_t st) {
     fill_u32(st, d.occ, 0u, BN);
     fill_u32(st, d.head, 0u, BN);
     fill_u32(st, d.c_head, 0xffffffffu, BN);
+    fill_u32(st, d.min_k, 0xffffffffu, BN);
+    fill_u32(st, d.cnt, 0u, BN);
+    fill_u32(st, d.blk, 0u, ((size_t)d.nblk + kFanoutBlocks) * sizeof(BlkCtr) / 4);
+    h->pending_admit = false;
   }
   if (d.record) fill_u32(st, d.step_off, 0u, 2);  // step_off[0] = 0 (int64)
   h->next_step = 0;
@@ -767,35 +887,34 @@ void launch_reset(adseq* h, hipStream_t st) {
   h->tape_ok = d.record != 0;
 }
 
-template <bool LIF>
+// FIFO / SORTED: admission of what is pending, then (MODE 1) pop or (MODE 2) the closed-loop step.
+template <int MODE>
 void launch_neurons(adseq* h, hipStream_t st, long long n, int parity, const float* i_ext,
                     unsigned char* spikes_out, float* I_out) {
   const Dev& d = h->dev;
   const dim3 grid(grid_for((size_t)d.BN)), block(kBlock);
-  switch (d.kind) {
-    case ADSEQ_FIFO:
-      hipLaunchKernelGGL((k_neurons<ADSEQ_FIFO, LIF>), grid, block, 0, st, d, n, parity, i_ext, spikes_out, I_out);
-      break;
-    default:
-      hipLaunchKernelGGL((k_neurons<ADSEQ_SORTED, LIF>), grid, block, 0, st, d, n, parity, i_ext, spikes_out, I_out);
-      break;
-  }
+  if (d.kind == ADSEQ_FIFO)
+    hipLaunchKernelGGL((k_neurons<ADSEQ_FIFO, MODE>), grid, block, 0, st, d, n, parity, i_ext, spikes_out, I_out);
+  else
+    hipLaunchKernelGGL((k_neurons<ADSEQ_SORTED, MODE>), grid, block, 0, st, d, n, parity, i_ext, spikes_out, I_out);
+  h->pending_admit = false;
 }
 
-void launch_fanout(adseq* h, hipStream_t st, long long n, const int* spk, const int* n_spk,
-                   int parity, int record) {
+void launch_fanout(adseq* h, hipStream_t st, long long n, const int* spk, const int* n_spk, int record) {
   const Dev& d = h->dev;
   const dim3 grid(kFanoutBlocks), block(kBlock);
-  switch (d.kind) {
-    case ADSEQ_FIFO:
-      hipLaunchKernelGGL((k_fanout<ADSEQ_FIFO>), grid, block, 0, st, d, n, spk, n_spk, parity, record);
-      hipLaunchKernelGGL((k_admit<ADSEQ_FIFO>), dim3(kAdmitBlocks), block, 0, st, d, parity);
-      break;
-    default:
-      hipLaunchKernelGGL((k_fanout<ADSEQ_SORTED>), grid, block, 0, st, d, n, spk, n_spk, parity, record);
-      hipLaunchKernelGGL((k_admit<ADSEQ_SORTED>), dim3(kAdmitBlocks), block, 0, st, d, parity);
-      break;
-  }
+  if (d.kind == ADSEQ_FIFO)
+    hipLaunchKernelGGL((k_fanout<ADSEQ_FIFO>), grid, block, 0, st, d, n, spk, n_spk, record);
+  else
+    hipLaunchKernelGGL((k_fanout<ADSEQ_SORTED>), grid, block, 0, st, d, n, spk, n_spk, record);
+  h->pending_admit = true;
+  h->last_stream = st;
+}
+
+// FIFO / SORTED: admits the contenders that the last enqueue registered, if that has not
+// happened yet (it normally rides on the next step's launch).
+void flush_admit(adseq* h, hipStream_t st) {
+  if (h->dev.kind != ADSEQ_RING && h->pending_admit) launch_neurons<0>(h, st, 0, 0, nullptr, nullptr, nullptr);
 }
 
 void mark(adseq* h, hipStream_t st, int kind);
@@ -849,9 +968,9 @@ int step_impl(adseq* h, long long step, const float* i_ext, unsigned char* spike
     mark(h, st, 1);
   } else {
     mark(h, st, -1);
-    launch_neurons<true>(h, st, step, parity, i_ext, spikes_out, nullptr);
+    launch_neurons<2>(h, st, step, parity, i_ext, spikes_out, nullptr);
     mark(h, st, 1);
-    launch_fanout(h, st, step, d.cur_spk, &d.ctr->n_spk[parity], parity, record);
+    launch_fanout(h, st, step, d.cur_spk, &d.ctr->n_spk[parity], record);
     mark(h, st, 0);
   }
   h->enq_calls += 1;
@@ -942,7 +1061,7 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   d.row_ptr = (const long long*)cfg->row_ptr; d.col = cfg->col; d.weight = cfg->weight;
   d.delay_steps = cfg->delay_steps; d.delay_ms = cfg->delay_ms;
   d.ctr = (Counters*)(ws + L.ctr);
-  d.nblk = L.nblk; d.words = L.words;
+  d.nblk = L.nblk; d.words = L.words; d.blk = (BlkCtr*)(ws + L.blk);
   d.V = (float*)(ws + L.V); d.spike_bits = (unsigned long long*)(ws + L.spike_bits);
   d.W = L.W; d.wshift = L.wshift; d.tp_shift = L.tp_shift; d.P = L.P; d.NB = L.NB; d.cap = L.cap;
   d.wgroups = L.wgroups;
@@ -955,7 +1074,10 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   d.slot_k = (unsigned*)(ws + L.slot_k); d.slot_a = (int*)(ws + L.slot_a);
   d.occ = (int*)(ws + L.occ); d.head = (int*)(ws + L.head); d.c_head = (int*)(ws + L.c_head);
   d.pool_p = (long long*)(ws + L.pool_p); d.pool_t = (long long*)(ws + L.pool_t);
-  d.pool_g = (int*)(ws + L.pool_g); d.pool_next = (int*)(ws + L.pool_next);
+  d.pool_next = (int*)(ws + L.pool_next);
+  d.min_k = (unsigned*)(ws + L.min_k); d.cnt = (int*)(ws + L.cnt);
+  d.cont_p = (long long*)(ws + L.cont_p); d.cont_k = (unsigned*)(ws + L.cont_k);
+  d.cont_a = (int*)(ws + L.cont_a); d.cont_t = (long long*)(ws + L.cont_t);
   d.pool_k = (unsigned*)(ws + L.pool_k); d.pool_a = (int*)(ws + L.pool_a);
   d.cur_spk = (int*)(ws + L.cur_spk);
   d.packed = (unsigned*)(ws + L.packed); d.a_q = (int*)(ws + L.a_q);
@@ -1029,7 +1151,7 @@ int adseq_deliver(adseq_t* h, int64_t step, float* I_out, void* stream) {
     hipLaunchKernelGGL(k_deliver_win, dim3((unsigned)h->dev.nblk), dim3(kBlock), 0, (hipStream_t)stream,
                        h->dev, (long long)step, I_out);
   } else {
-    launch_neurons<false>(h, (hipStream_t)stream, step, parity, nullptr, nullptr, I_out);
+    launch_neurons<1>(h, (hipStream_t)stream, step, parity, nullptr, nullptr, I_out);
   }
   h->next_step = step + 1;
   h->tape_ok = false;
@@ -1049,7 +1171,7 @@ int adseq_enqueue(adseq_t* h, int64_t step, const int32_t* spike_ids, const int3
     hipLaunchKernelGGL(k_enqueue_win, dim3(kFanoutBlocks), dim3(kBlock), 0, (hipStream_t)stream, h->dev,
                        (long long)step, spike_ids, n_spikes);
   else
-    launch_fanout(h, (hipStream_t)stream, step, spike_ids, n_spikes, parity, 0);
+    launch_fanout(h, (hipStream_t)stream, step, spike_ids, n_spikes, 0);
   h->enq_calls += 1;
   h->tape_ok = false;
   HIP_TRY(h, hipGetLastError());
@@ -1082,6 +1204,7 @@ int adseq_backward(adseq_t* h, const float* dL_dcount, const float* dL_dU, float
   if (!d.record || !h->tape_ok)
     return fail(h, ADSEQ_E_NO_TAPE, "adseq_backward: no complete recorded forward run");
   hipStream_t st = (hipStream_t)stream;
+  flush_admit(h, st);
   unsigned err = 0;
   HIP_TRY(h, hipMemcpyAsync(&err, &d.ctr->err, sizeof(err), hipMemcpyDeviceToHost, st));
   HIP_TRY(h, hipStreamSynchronize(st));
@@ -1118,6 +1241,7 @@ int adseq_counters(adseq_t* h, int64_t* out8, void* stream) {
   Counters c;
   hipStream_t st = (hipStream_t)stream;
   const Dev& d = h->dev;
+  flush_admit(h, st);
   if (d.kind == ADSEQ_RING) {
     // The ring keeps no per-event counters.  Spikes and the events they emit are counted from
     // the spike words: up to the last window boundary by the boundary pass (device counters),
@@ -1138,6 +1262,17 @@ int adseq_counters(adseq_t* h, int64_t* out8, void* stream) {
   out8[0] = (int64_t)c.offered; out8[1] = (int64_t)c.dropped; out8[2] = (int64_t)c.delivered;
   out8[3] = c.sum_offered; out8[4] = c.sum_dropped; out8[5] = c.sum_delivered;
   out8[6] = c.tape_spikes; out8[7] = (int64_t)c.err;
+  if (d.kind != ADSEQ_RING) {
+    // the kernels keep private counters per block: add them up here
+    const size_t nb = (size_t)d.nblk + kFanoutBlocks;
+    std::vector<BlkCtr> hb(nb);
+    HIP_TRY(h, hipMemcpyAsync(hb.data(), d.blk, sizeof(BlkCtr) * nb, hipMemcpyDeviceToHost, st));
+    HIP_TRY(h, hipStreamSynchronize(st));
+    for (const BlkCtr& b : hb) {
+      out8[0] += (int64_t)b.offered; out8[1] += (int64_t)b.dropped; out8[2] += (int64_t)b.delivered;
+      out8[3] += b.sum_offered; out8[4] += b.sum_dropped; out8[5] += b.sum_delivered;
+    }
+  }
   if (d.kind == ADSEQ_RING) {
     out8[6] += (int64_t)c.fold[0]; out8[0] += (int64_t)c.fold[1]; out8[3] += (int64_t)c.fold[2];
     out8[2] = out8[0] - (int64_t)c.in_flight[0];
@@ -1160,12 +1295,13 @@ int adseq_drop_count(adseq_t* h, uint64_t* dropped, uint64_t* enqueued, uint64_t
   return ADSEQ_OK;
 }
 
-int adseq_tape(const adseq_t* h, adseq_tape_view* out) {
+int adseq_tape(adseq_t* h, adseq_tape_view* out) {
   if (!h || !out) return ADSEQ_E_INVALID_ARG;
   const Dev& d = h->dev;
   if (!d.record) return ADSEQ_E_NO_TAPE;
+  flush_admit(h, h->last_stream);   // the last step's admission flags
   out->membrane = d.tapeU;
-  // the ring's fused step keeps no spike list: its spikes are exactly U >= v_thresh on the tape
+  // the ring keeps no spike list: its spikes are exactly U >= v_thresh on the tape
   out->step_offset = d.kind != ADSEQ_RING ? (const int64_t*)d.step_off : nullptr;
   out->spike_id = d.kind != ADSEQ_RING ? d.tape_spk : nullptr;
   out->event_base = d.kind != ADSEQ_RING ? (const int64_t*)d.tape_evb : nullptr;
