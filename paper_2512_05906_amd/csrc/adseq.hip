@@ -292,20 +292,24 @@ __device__ __forceinline__ void store_event(const Dev& d, int g, int occ, int hd
 
 // Admits the contenders registered for target g (owner thread): the min(K, free) with the
 // smallest synapse index are stored, the others dropped (counted into c_drop / s_drop).
+// Occupancy, earliest stored arrival (FIFO) and front index (SORTED) of a target: loaded once at
+// the start of k_neurons, kept in registers through admission and pop, written back at the end.
+struct QState { int occ; unsigned mn; int hd; };
+
 template <int KIND>
-__device__ __forceinline__ void admit_contenders(const Dev& d, int g, long long* c_drop, long long* s_drop) {
-  const int K = d.cnt[g];
+__device__ __forceinline__ void admit_contenders(const Dev& d, int g, int K, QState& q, long long* c_drop,
+                                                 long long* s_drop) {
   if (K <= 0) return;
   d.cnt[g] = 0;
   const size_t BN = (size_t)d.BN;
-  int occ = d.occ[g];
+  int occ = q.occ;
   const int F = d.C - occ;
   const int nc = K < kCont ? K : kCont;              // in the contender slots
   const int ovf_head = K > kCont ? d.c_head[g] : -1; // the others: overflow list
   if (K > kCont) d.c_head[g] = -1;
   const int take = K < F ? K : F;
-  const int hd = KIND == ADSEQ_SORTED ? d.head[g] : 0;
-  unsigned mn = KIND == ADSEQ_FIFO ? d.min_k[g] : 0u;
+  const int hd = q.hd;
+  unsigned mn = q.mn;
   // the contender slots, loaded together
   long long cp[kCont], ct[kCont]; unsigned ck[kCont]; int ca[kCont];
 #pragma unroll
@@ -372,8 +376,7 @@ __device__ __forceinline__ void admit_contenders(const Dev& d, int g, long long*
       }
     }
   }
-  d.occ[g] = occ;
-  if (KIND == ADSEQ_FIFO) d.min_k[g] = mn;
+  q.occ = occ; q.mn = mn;
 }
 
 // One thread per (trial, neuron).  MODE 0: admission only (what is pending); 1: admission + pop,
@@ -393,16 +396,25 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
     d.ctr->pool_n[0] = 0;                        // the overflow pool is consumed by this launch
     if (MODE == 2) d.ctr->n_spk[parity ^ 1] = 0;  // next step's spike counter; nobody reads it now
   }
+  float v = 0.0f;
   if (act) {
-    admit_contenders<KIND>(d, g, &c_drop, &s_drop);
+    // everything the thread needs first, loaded together
+    const int K = d.cnt[g];
+    QState q, q0;
+    q.occ = d.occ[g];
+    q.mn = KIND == ADSEQ_FIFO ? d.min_k[g] : 0u;
+    q.hd = KIND == ADSEQ_SORTED ? d.head[g] : 0;
+    if (MODE == 2) v = d.V[g];
+    q0 = q;
+    admit_contenders<KIND>(d, g, K, q, &c_drop, &s_drop);
     if (MODE != 0) {
       const size_t BN = (size_t)d.BN;
       if (KIND == ADSEQ_FIFO) {
         // bounded bag: every stored event due now leaves.  Pass 1 only reads (all slot loads
         // in flight together): sum of the due events, their positions, earliest arrival among
         // the others.  Pass 2 fills each hole with the last stored event (the bag is unordered).
-        if (d.min_k[g] == kn) {
-          const int occ = d.occ[g];
+        if (q.mn == kn) {
+          const int occ = q.occ;
           unsigned mn = 0xffffffffu;
           int ndue = 0;
           int due[8];                      // positions of the first 8 due events, ascending
@@ -438,24 +450,24 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
             top = keep;
           }
           popped += ndue;
-          d.occ[g] = top;
-          d.min_k[g] = mn;
+          q.occ = top;
+          q.mn = mn;
         }
       } else {
         // ordered by arrival: everything due now sits at the front of the circular array
-        int occ = d.occ[g];
-        if (occ > 0) {
-          int hd = d.head[g];
-          while (occ > 0 && d.slot_k[(size_t)hd * BN + g] == kn) {
-            acc = wrap_add(acc, d.slot_a[(size_t)hd * BN + g]);
-            hd = hd + 1 == d.C ? 0 : hd + 1;
-            --occ;
-            ++popped;
-          }
-          if (popped) { d.occ[g] = occ; d.head[g] = hd; }
+        int occ = q.occ, hd = q.hd;
+        while (occ > 0 && d.slot_k[(size_t)hd * BN + g] == kn) {
+          acc = wrap_add(acc, d.slot_a[(size_t)hd * BN + g]);
+          hd = hd + 1 == d.C ? 0 : hd + 1;
+          --occ;
+          ++popped;
         }
+        q.occ = occ; q.hd = hd;
       }
     }
+    if (q.occ != q0.occ) d.occ[g] = q.occ;
+    if (KIND == ADSEQ_FIFO && q.mn != q0.mn) d.min_k[g] = q.mn;
+    if (KIND == ADSEQ_SORTED && q.hd != q0.hd) d.head[g] = q.hd;
   }
   bool s = false;
   if (act && MODE != 0) {
@@ -467,7 +479,7 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
         I = I + (xi ? d.ext_w : 0.0f);
       }
       if (i_ext) I = I + i_ext[g];
-      const float U = __fmaf_rn(d.alpha, d.V[g], I);
+      const float U = __fmaf_rn(d.alpha, v, I);
       s = U >= d.theta;
       d.V[g] = s ? d.v_reset : U;
       if (d.record && n < d.max_steps) d.tapeU[(size_t)n * d.BN + g] = U;
@@ -523,44 +535,57 @@ __global__ __launch_bounds__(kBlock) void k_fanout(Dev d, long long n, const int
       tbase = s_evb;
       __syncthreads();
     }
-    for (long long p0 = r0; p0 < r1; p0 += kBlock) {
-      const long long p = p0 + threadIdx.x;
-      const bool valid = p < r1;
-      unsigned pk = 0; int a = 0;
-      if (valid) { pk = d.packed[p]; a = d.a_q[p]; c_off += 1; s_off += a; }
-      const int D = (int)(pk & d.dmask);
-      const int gt = b * d.N + (int)(pk >> d.dbits);
-      const long long tidx = (valid && tbase >= 0) ? tbase + (p - r0) : -1;
-      bool contend = false;
-      if (valid) {
-        contend = d.occ[gt] < d.C;
-        if (!contend) { c_drop += 1; s_drop += a; if (tidx >= 0) d.tape_adm[tidx] = 0; }
+    // four row entries per thread and trip, each stage for all four before the next, so that
+    // the loads, the occupancy gathers and the ticket atomics of a trip are in flight together
+    for (long long p0 = r0; p0 < r1; p0 += 4 * kBlock) {
+      long long p[4]; bool valid[4]; unsigned pk[4]; int a[4], gt[4], tk[4]; bool contend[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        p[j] = p0 + j * kBlock + threadIdx.x;
+        valid[j] = p[j] < r1;
+        pk[j] = 0; a[j] = 0;
+        if (valid[j]) { pk[j] = d.packed[p[j]]; a[j] = d.a_q[p[j]]; }
       }
-      int ticket = -1;
-      if (contend) ticket = atomicAdd(&d.cnt[gt], 1);
-      if (contend && ticket < kCont) {
-        const size_t ci = (size_t)ticket * BN + gt;
-        d.cont_p[ci] = p; d.cont_k[ci] = (unsigned)(n + D); d.cont_a[ci] = a;
-        if (d.record) d.cont_t[ci] = tidx;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        gt[j] = b * d.N + (int)(pk[j] >> d.dbits);
+        contend[j] = false;
+        if (valid[j]) { c_off += 1; s_off += a[j]; contend[j] = d.occ[gt[j]] < d.C; }
       }
-      // the others: wavefront-aggregated claim of pool entries, pushed on the target's list
-      const bool over = contend && ticket >= kCont;
-      const unsigned long long cm = __ballot(over);
-      if (cm) {
-        int base = 0;
-        if (lane == __ffsll((long long)cm) - 1) base = atomicAdd(&d.ctr->pool_n[0], __popcll(cm));
-        base = __shfl(base, __ffsll((long long)cm) - 1, 64);
-        if (over) {
-          const int x = base + __popcll(cm & ((1ull << lane) - 1ull));
-          if (x >= d.pool_cap) {
-            // no room to remember it: it can only be dropped, and the run is flagged as invalid
-            atomicOr(&d.ctr->err, ERR_POOL);
-            atomicSub(&d.cnt[gt], 1);
-            c_drop += 1; s_drop += a; if (tidx >= 0) d.tape_adm[tidx] = 0;
-          } else {
-            d.pool_p[x] = p; d.pool_t[x] = tidx;
-            d.pool_k[x] = (unsigned)(n + D); d.pool_a[x] = a;
-            d.pool_next[x] = atomicExch(&d.c_head[gt], x);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        tk[j] = -1;
+        if (contend[j]) tk[j] = atomicAdd(&d.cnt[gt[j]], 1);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int D = (int)(pk[j] & d.dmask);
+        const long long tidx = (valid[j] && tbase >= 0) ? tbase + (p[j] - r0) : -1;
+        if (valid[j] && !contend[j]) { c_drop += 1; s_drop += a[j]; if (tidx >= 0) d.tape_adm[tidx] = 0; }
+        if (contend[j] && tk[j] < kCont) {
+          const size_t ci = (size_t)tk[j] * BN + gt[j];
+          d.cont_p[ci] = p[j]; d.cont_k[ci] = (unsigned)(n + D); d.cont_a[ci] = a[j];
+          if (d.record) d.cont_t[ci] = tidx;
+        }
+        // the others: wavefront-aggregated claim of pool entries, pushed on the target's list
+        const bool over = contend[j] && tk[j] >= kCont;
+        const unsigned long long cm = __ballot(over);
+        if (cm) {
+          int base = 0;
+          if (lane == __ffsll((long long)cm) - 1) base = atomicAdd(&d.ctr->pool_n[0], __popcll(cm));
+          base = __shfl(base, __ffsll((long long)cm) - 1, 64);
+          if (over) {
+            const int x = base + __popcll(cm & ((1ull << lane) - 1ull));
+            if (x >= d.pool_cap) {
+              // no room to remember it: it can only be dropped, and the run is flagged as invalid
+              atomicOr(&d.ctr->err, ERR_POOL);
+              atomicSub(&d.cnt[gt[j]], 1);
+              c_drop += 1; s_drop += a[j]; if (tidx >= 0) d.tape_adm[tidx] = 0;
+            } else {
+              d.pool_p[x] = p[j]; d.pool_t[x] = tidx;
+              d.pool_k[x] = (unsigned)(n + D); d.pool_a[x] = a[j];
+              d.pool_next[x] = atomicExch(&d.c_head[gt[j]], x);
+            }
           }
         }
       }

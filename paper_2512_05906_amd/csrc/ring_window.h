@@ -20,22 +20,19 @@
 // tile [W][targets of the part] with LDS atomics and adds the tile to win with coalesced
 // accesses.  Events that do not fit their region fall back to a global atomic on win, so the
 // result never depends on the staging capacity.
-// Nor does the expansion wait for the window boundary.  The spikes older than the current window
-// ("old spikes": 15/16 of the next window's events for W = 16, d_max = 250) are known while the
-// current window runs, so the preparation of the next window from them is cut into W slices
-// (staging slices, then accumulation slices) and slice phi rides, as extra blocks, on the launch
-// of the current window's step phi, whose neuron blocks are latency-bound and leave most of the
-// chip idle.  Hence two window buffers.  At the boundary only the spikes of the window just
-// finished are left: one pass with plain atomics, which also counts those spikes and their
-// events into the device counters (the step kernel itself counts nothing).
+// Both passes run once per window, at its first step, on all spikes of the last d_max steps.
+// The first pass also counts the spikes of the window just finished, and the events they emit,
+// into the device counters (the step kernel itself counts nothing).  Two window buffers, used
+// alternately, so that the cells a window's steps clear are not the ones being filled for the
+// next.  (Measured and dropped: expanding the next window's old spikes on a second stream, or
+// in slices riding as extra blocks on the step launches -- the loaded memory system slows the
+// latency-bound step kernels by as much as is gained.)
 //
-// The reverse sweep mirrors it: gwin f32 [2][W][BN] holds the adjoint rows of the current window
-// and of the one swept before it.  A spike's queue term is the sum of a near part (gathered by
-// the step kernel) and one far part per later window, gathered from the window (6.4 MB: the L2
-// holds it) into Gacc[n mod R][g] -- for the spikes of the W steps swept next in a pass at the
-// boundary, for the older ones in W slices riding on those W step launches.  The per-synapse sum
-// of gathered adjoints goes to gsum in sorted order and is scaled and un-permuted into
-// grad_w / grad_d by k_grad_finish.
+// The reverse sweep mirrors it: gwin f32 [2][W][BN] holds the adjoint rows of the current
+// window.  A spike's queue term is the sum of a near part (gathered by the step kernel) and one
+// far part per later window, gathered by k_bwd_win from the window (6.4 MB: the L2 holds it) into
+// Gacc[n mod R][g].  The per-synapse sum of gathered adjoints goes to gsum in sorted order and is
+// scaled and un-permuted into grad_w / grad_d by k_grad_finish.
 
 constexpr int kRingThreads = 1024;  // threads per block of the ring's step and expansion kernels
 constexpr int kRingWaves = kRingThreads / 64;
