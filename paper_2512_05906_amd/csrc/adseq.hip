@@ -418,10 +418,17 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
           unsigned mn = 0xffffffffu;
           int ndue = 0;
           int due[8];                      // positions of the first 8 due events, ascending
-          for (int s = 0; s < occ; ++s) {
-            const unsigned k = d.slot_k[(size_t)s * BN + g];
-            if (k == kn) { if (ndue < 8) due[ndue] = s; ++ndue; }
-            else mn = k < mn ? k : mn;
+          for (int s0 = 0; s0 < occ; s0 += 16) {
+            unsigned kk[16];                // 16 slot loads in flight, then their tests
+#pragma unroll
+            for (int j = 0; j < 16; ++j) kk[j] = s0 + j < occ ? d.slot_k[(size_t)(s0 + j) * BN + g] : 0xffffffffu;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+              if (s0 + j < occ) {
+                if (kk[j] == kn) { if (ndue < 8) due[ndue] = s0 + j; ++ndue; }
+                else mn = kk[j] < mn ? kk[j] : mn;
+              }
+            }
           }
           int top = occ;
           if (ndue <= 8) {
