@@ -187,19 +187,22 @@ int adseq_tape(adseq_t *h, adseq_tape_view *out);
 
 /* Spike count of every (trial, neuron) over the steps recorded since the last reset (the input of
  * the spike-count loss of the paper's recurrent-network benchmark, Section 5.1): counts int32
- * [B*N], overwritten.  Needs record_tape = 1 and a complete recorded run.  Stream ordered for
- * ADSEQ_RING; FIFO / SORTED synchronise `stream` once (the spike list's length lives on the
- * device). */
+ * [B*N], overwritten.  Needs record_tape = 1 and a complete recorded run.  Stream ordered. */
 int adseq_spike_counts(adseq_t *h, int32_t *counts, void *stream);
 
 /* Kernel timing for benchmarks (not a call of the method; for callers that want per-kernel
  * durations without an external profiler).  While enabled, adseq_step / adseq_run /
- * adseq_backward record a HIP event on the caller's stream after every kernel they launch
- * (events are created by the library on first use and destroyed with the handle).
- * adseq_profile_read synchronises `stream` and returns, per kernel class, the summed time in ms and
- * the number of launches since the last read: [0] fan-out + enqueue, [1] pop + drive + LIF,
- * [2] backward queue term + gradients, [3] backward neuron update; then it forgets them.
- * For FIFO/SORTED class [0] covers the fan-out and admission launches together. */
+ * adseq_backward record HIP events on the caller's stream around the kernels they launch (events
+ * are created by the library on first use and destroyed with the handle).  adseq_profile_read
+ * synchronises `stream` and returns, per kernel class, the summed time in ms and the number of
+ * launches since the last read, then forgets them.  Classes for FIFO / SORTED (an event after
+ * every launch): [0] fan-out + contender registration, [1] admission + pop + drive + LIF,
+ * [2] backward queue term + gradients, [3] backward neuron update.  Classes for RING: [0] the
+ * expansion of one window (staging pass + accumulation pass, timed as a pair and counted as one
+ * launch), [1] forward step kernel, [2] backward far gather of one window, [3] backward step
+ * kernel; the step kernels are timed in groups (all the step launches between two window
+ * boundaries between one pair of events), because an event after every 5 us launch would add
+ * half as much again. */
 int adseq_profile(adseq_t *h, int enable);
 int adseq_profile_read(adseq_t *h, double *ms4 /*host*/, int64_t *launches4 /*host*/, void *stream);
 

@@ -116,6 +116,7 @@ struct Dev {
   int* pool_a;
   int* cur_spk;
   float* tapeU;
+  int* spk_count;       // [BN] spikes per (trial, neuron) over the recorded steps
   long long* step_off;
   int* tape_spk;
   long long* tape_evb;
@@ -489,7 +490,10 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
       const float U = __fmaf_rn(d.alpha, v, I);
       s = U >= d.theta;
       d.V[g] = s ? d.v_reset : U;
-      if (d.record && n < d.max_steps) d.tapeU[(size_t)n * d.BN + g] = U;
+      if (d.record && n < d.max_steps) {
+        d.tapeU[(size_t)n * d.BN + g] = U;
+        if (s) d.spk_count[g] += 1;
+      }
       if (spikes_out) spikes_out[g] = s ? 1 : 0;
     } else {
       I_out[g] = I;
@@ -607,12 +611,8 @@ __global__ __launch_bounds__(kBlock) void k_fanout(Dev d, long long n, const int
   block_add2(&bc.dropped, c_drop, &bc.sum_dropped, s_drop);
 }
 
-// Spike counts from the recorded spike lists (FIFO / SORTED): counts must be zero on entry.
-__global__ __launch_bounds__(kBlock) void k_spike_counts_list(Dev d, long long n_spikes, int* __restrict__ counts) {
-  for (long long e = (long long)blockIdx.x * kBlock + threadIdx.x; e < n_spikes; e += (long long)gridDim.x * kBlock) {
-    const int g = d.tape_spk[e];
-    if ((unsigned)g < (unsigned)d.BN) atomicAdd(&counts[g], 1);
-  }
+__global__ __launch_bounds__(kBlock) void k_copy_i32(const int* __restrict__ src, int* __restrict__ dst, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) dst[i] = src[i];
 }
 
 // ---------------------------------------------------------------- ring queue (windowed delay line)
@@ -707,6 +707,9 @@ struct adseq {
   bool prof = false;
   std::vector<hipEvent_t> evs;
   std::vector<int> ev_kind;   // kernel class the event closes, -1 = start marker
+  std::vector<int> ev_count;  // launches between the previous event and this one
+  bool grp_open = false;      // RING: a group of consecutive step launches is being timed
+  int grp_count = 0;
   size_t ev_used = 0;
 };
 
@@ -715,7 +718,7 @@ namespace {
 struct Layout {
   size_t V, win, spike_bits, slot_k, slot_a, occ, head, min_k, cnt, cont_p, cont_k, cont_a, cont_t, c_head, pool_p, pool_t, pool_next,
       pool_k, pool_a, cur_spk, packed, a_q, synf, synb, dstart, nearcnt, perm, rowsum, ebuf, ecnt, amp, fdec, tapeU,
-      tape_bits, step_off, tape_spk, tape_evb, tape_adm, bwd_ring, bwd_carry, bwd_G, gwin, Gacc, gsum, ctr, blk,
+      tape_bits, spk_count, step_off, tape_spk, tape_evb, tape_adm, bwd_ring, bwd_carry, bwd_G, gwin, Gacc, gsum, ctr, blk,
       total;
   long long spike_cap, event_cap, pool_cap;
   int R, dbits, nblk, words;
@@ -851,6 +854,7 @@ bool make_layout(const adseq_config* c, Layout* L) {
   const size_t T = c->record_tape ? (size_t)c->max_steps : 0;
   L->tapeU = take(T * BN * 4);
   L->tape_bits = take(bounded ? 0 : T * L->words * 8);
+  L->spk_count = take(c->record_tape ? BN * 4 : 0);
   L->step_off = take(c->record_tape ? (T + 1) * 8 : 0);
   L->tape_spk = take(bounded ? (size_t)L->spike_cap * 4 : 0);
   L->tape_evb = take(bounded ? (size_t)L->spike_cap * 8 : 0);
@@ -913,7 +917,10 @@ void launch_reset(adseq* h, hipStream_t st) {
     fill_u32(st, d.blk, 0u, ((size_t)d.nblk + kFanoutBlocks) * sizeof(BlkCtr) / 4);
     h->pending_admit = false;
   }
-  if (d.record) fill_u32(st, d.step_off, 0u, 2);  // step_off[0] = 0 (int64)
+  if (d.record) {
+    fill_u32(st, d.step_off, 0u, 2);  // step_off[0] = 0 (int64)
+    fill_u32(st, d.spk_count, 0u, BN);
+  }
   h->next_step = 0;
   h->enq_calls = 0;
   h->tape_ok = d.record != 0;
@@ -949,7 +956,8 @@ void flush_admit(adseq* h, hipStream_t st) {
   if (h->dev.kind != ADSEQ_RING && h->pending_admit) launch_neurons<0>(h, st, 0, 0, nullptr, nullptr, nullptr);
 }
 
-void mark(adseq* h, hipStream_t st, int kind);
+void mark(adseq* h, hipStream_t st, int kind, int count = 1);
+void close_group(adseq* h, hipStream_t st, int kind);
 
 // RING: called before step k0 is popped when k0 opens a window (k0 mod W = 0): expands the
 // events of the spikes of the last d_max steps that arrive in the window (staging pass, then
@@ -959,6 +967,7 @@ void mark(adseq* h, hipStream_t st, int kind);
 void ring_open_window(adseq* h, hipStream_t st, long long k0) {
   const Dev& d = h->dev;
   if ((k0 & (long long)(d.W - 1)) != 0 || k0 <= 0) return;
+  close_group(h, st, 1);
   mark(h, st, -1);
   const long long n_lo = k0 - d.d_max > 0 ? k0 - d.d_max : 0;
   hipLaunchKernelGGL(k_win_bin, dim3((unsigned)d.NB), dim3(kRingThreads), 0, st, d, k0, n_lo, k0, 0, d.NB,
@@ -972,16 +981,30 @@ void ring_open_window(adseq* h, hipStream_t st, long long k0) {
 }
 
 // Records an event that closes a launch of class `kind` (and opens the next one).
-void mark(adseq* h, hipStream_t st, int kind) {
+void mark(adseq* h, hipStream_t st, int kind, int count) {
   if (!h->prof) return;
   if (h->ev_used == h->evs.size()) {
     hipEvent_t e;
     if (hipEventCreate(&e) != hipSuccess) return;
-    h->evs.push_back(e); h->ev_kind.push_back(kind);
+    h->evs.push_back(e); h->ev_kind.push_back(kind); h->ev_count.push_back(count);
   }
   h->ev_kind[h->ev_used] = kind;
+  h->ev_count[h->ev_used] = count;
   (void)hipEventRecord(h->evs[h->ev_used], st);
   h->ev_used += 1;
+}
+
+// RING: the step launches are timed in groups (all the steps between two window boundaries
+// between one pair of events), since an event after every 5 us launch would add half as much.
+void open_group(adseq* h, hipStream_t st) {
+  if (!h->prof || h->grp_open) return;
+  mark(h, st, -1);
+  h->grp_open = true; h->grp_count = 0;
+}
+void close_group(adseq* h, hipStream_t st, int kind) {
+  if (!h->prof || !h->grp_open) return;
+  mark(h, st, kind, h->grp_count);
+  h->grp_open = false;
 }
 
 int step_impl(adseq* h, long long step, const float* i_ext, unsigned char* spikes_out, hipStream_t st) {
@@ -993,11 +1016,11 @@ int step_impl(adseq* h, long long step, const float* i_ext, unsigned char* spike
   if (d.record && step >= d.max_steps) h->tape_ok = false;
   if (d.kind == ADSEQ_RING) {
     ring_open_window(h, st, step);
-    mark(h, st, -1);
+    open_group(h, st);
     const dim3 grid((unsigned)d.nblk), block(kBlock);
     if (record) hipLaunchKernelGGL((k_step_win<true>), grid, block, 0, st, d, step, i_ext, spikes_out);
     else hipLaunchKernelGGL((k_step_win<false>), grid, block, 0, st, d, step, i_ext, spikes_out);
-    mark(h, st, 1);
+    h->grp_count += 1;
   } else {
     mark(h, st, -1);
     launch_neurons<2>(h, st, step, parity, i_ext, spikes_out, nullptr);
@@ -1031,16 +1054,19 @@ void ring_backward_launch(adseq* h, hipStream_t st, long long T, float dscale, c
   fill_u32(st, d.gwin, 0u, 2 * (size_t)d.W * d.BN);
   fill_u32(st, d.Gacc, 0u, (size_t)d.R * d.BN);
   for (long long n = T - 1; n >= 0; --n) {
-    mark(h, st, -1);
+    open_group(h, st);
     hipLaunchKernelGGL(k_bwd_step_win, gn, block, 0, st, d, n, T, dL_dcount, dL_dU);
-    mark(h, st, 3);
+    h->grp_count += 1;
     if ((n & (long long)(d.W - 1)) == 0 && n > 0) {
+      close_group(h, st, 3);
+      mark(h, st, -1);
       const long long lo = n - d.d_max > 0 ? n - d.d_max : 0;
       const int nvb = gather_blocks(d, lo, n);
       hipLaunchKernelGGL(k_bwd_win, dim3((unsigned)nvb), dim3(kRingThreads), 0, st, d, n, lo, n, T, 0, nvb);
       mark(h, st, 2);
     }
   }
+  close_group(h, st, 3);
   const unsigned gf = (unsigned)(d.N < 65536 ? d.N : 65536);
   hipLaunchKernelGGL(k_grad_finish, dim3(gf), block, 0, st, d, dscale, grad_w, grad_d);
 }
@@ -1102,6 +1128,7 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   d.perm = (unsigned*)(ws + L.perm); d.rowsum = (long long*)(ws + L.rowsum);
   d.ebuf = (uint2*)(ws + L.ebuf); d.ecnt = (int*)(ws + L.ecnt);
   d.tape_bits = (unsigned long long*)(ws + L.tape_bits);
+  d.spk_count = (int*)(ws + L.spk_count);
   d.gwin = (float*)(ws + L.gwin); d.Gacc = (float*)(ws + L.Gacc); d.gsum = (float*)(ws + L.gsum);
   d.slot_k = (unsigned*)(ws + L.slot_k); d.slot_a = (int*)(ws + L.slot_a);
   d.occ = (int*)(ws + L.occ); d.head = (int*)(ws + L.head); d.c_head = (int*)(ws + L.c_head);
@@ -1224,6 +1251,7 @@ int adseq_run(adseq_t* h, int64_t step0, int64_t n_steps, void* stream) {
     const int rc = step_impl(h, step0 + n, nullptr, nullptr, (hipStream_t)stream);
     if (rc != ADSEQ_OK) return rc;
   }
+  close_group(h, (hipStream_t)stream, 1);
   HIP_TRY(h, hipGetLastError());
   return ADSEQ_OK;
 }
@@ -1237,6 +1265,7 @@ int adseq_backward(adseq_t* h, const float* dL_dcount, const float* dL_dU, float
     return fail(h, ADSEQ_E_NO_TAPE, "adseq_backward: no complete recorded forward run");
   hipStream_t st = (hipStream_t)stream;
   flush_admit(h, st);
+  close_group(h, st, 1);
   unsigned err = 0;
   HIP_TRY(h, hipMemcpyAsync(&err, &d.ctr->err, sizeof(err), hipMemcpyDeviceToHost, st));
   HIP_TRY(h, hipStreamSynchronize(st));
@@ -1348,20 +1377,9 @@ int adseq_spike_counts(adseq_t* h, int32_t* counts, void* stream) {
   if (!d.record || !h->tape_ok)
     return fail(h, ADSEQ_E_NO_TAPE, "adseq_spike_counts: no complete recorded forward run");
   hipStream_t st = (hipStream_t)stream;
-  const long long T = h->next_step;
-  if (d.kind == ADSEQ_RING) {
-    hipLaunchKernelGGL(k_spike_counts_bits, dim3((unsigned)grid_for((size_t)d.BN)), dim3(kBlock), 0, st, d, T, counts);
-  } else {
-    // the number of recorded spikes lives on the device: read it (one synchronisation)
-    long long n_spikes = 0;
-    HIP_TRY(h, hipMemcpyAsync(&n_spikes, &d.ctr->tape_spikes, sizeof(n_spikes), hipMemcpyDeviceToHost, st));
-    HIP_TRY(h, hipStreamSynchronize(st));
-    if (n_spikes > d.spike_cap) n_spikes = d.spike_cap;
-    fill_u32(st, counts, 0u, (size_t)d.BN);
-    if (n_spikes > 0)
-      hipLaunchKernelGGL(k_spike_counts_list, dim3((unsigned)grid_for((size_t)n_spikes)), dim3(kBlock), 0, st, d,
-                         n_spikes, counts);
-  }
+  // the step kernels keep the counts (one owner thread per neuron and step)
+  hipLaunchKernelGGL(k_copy_i32, dim3((unsigned)grid_for((size_t)d.BN)), dim3(kBlock), 0, st, d.spk_count, counts,
+                     (size_t)d.BN);
   HIP_TRY(h, hipGetLastError());
   return ADSEQ_OK;
 }
@@ -1370,11 +1388,13 @@ int adseq_profile(adseq_t* h, int enable) {
   if (!h) return ADSEQ_E_INVALID_ARG;
   h->prof = enable != 0;
   h->ev_used = 0;
+  h->grp_open = false;
   return ADSEQ_OK;
 }
 
 int adseq_profile_read(adseq_t* h, double* ms4, int64_t* launches4, void* stream) {
   if (!h || !ms4 || !launches4) return ADSEQ_E_INVALID_ARG;
+  close_group(h, (hipStream_t)stream, 1);
   HIP_TRY(h, hipStreamSynchronize((hipStream_t)stream));
   for (int k = 0; k < 4; ++k) { ms4[k] = 0.0; launches4[k] = 0; }
   for (size_t i = 1; i < h->ev_used; ++i) {
@@ -1382,7 +1402,7 @@ int adseq_profile_read(adseq_t* h, double* ms4, int64_t* launches4, void* stream
     if (k < 0 || k > 3) continue;
     float ms = 0.0f;
     if (hipEventElapsedTime(&ms, h->evs[i - 1], h->evs[i]) != hipSuccess) continue;
-    ms4[k] += (double)ms; launches4[k] += 1;
+    ms4[k] += (double)ms; launches4[k] += h->ev_count[i];
   }
   h->ev_used = 0;
   return ADSEQ_OK;

@@ -223,7 +223,10 @@ __global__ __launch_bounds__(kBlock) void k_step_win(Dev d, long long n, const f
     const float U = __fmaf_rn(d.alpha, v, I);
     s = U >= d.theta;
     d.V[g] = s ? d.v_reset : U;
-    if (RECORD) d.tapeU[(size_t)n * d.BN + g] = U;
+    if (RECORD) {
+      d.tapeU[(size_t)n * d.BN + g] = U;
+      if (s) d.spk_count[g] += 1;
+    }
     if (spikes_out) spikes_out[g] = s ? 1 : 0;
   }
   const unsigned long long bits = __ballot(s);
@@ -588,18 +591,6 @@ __global__ __launch_bounds__(kBlock) void k_ring_in_flight(Dev d, long long n_en
     }
   }
   block_add2(&out[0], cnt, (long long*)&out[1], sum);
-}
-
-// Spike count of every (trial, neuron) over the recorded steps [0, T), from the recorded spike
-// words.  One thread per neuron; the 64 threads of a wavefront share each word.
-__global__ __launch_bounds__(kBlock) void k_spike_counts_bits(Dev d, long long T, int* __restrict__ counts) {
-  const int g = blockIdx.x * kBlock + threadIdx.x;
-  if (g >= d.BN) return;
-  const unsigned long long* __restrict__ w = d.tape_bits + (g >> 6);
-  const int sh = g & 63;
-  int c = 0;
-  for (long long n = 0; n < T; ++n) c += (int)((w[(size_t)n * d.words] >> sh) & 1ull);
-  counts[g] = c;
 }
 
 // ---------------------------------------------------------------- reverse sweep
