@@ -9,10 +9,12 @@
 //                                           word per wavefront): the events not yet in `win`
 //   dstart, nearcnt, perm, rowsum           RING: index of the rows sorted by arrival offset
 //   ebuf, ecnt                              RING: staging regions of the window expansion
-//   slot_k/a     u32/i32 [C][BN]            FIFO/SORTED: arrival step and Q8.24 amplitude, slot-major
-//                                           so that one slot of 64 consecutive targets is one line
-//   occ, head    i32   [BN]                 FIFO/SORTED: stored events; SORTED: index of the front
-//   c_head, pool_*                          per-step contender lists (one linked list per target)
+//   fkey, famp, vmask                       FIFO: per target, 16-bit arrival keys, Q8.24 amplitudes, occupied-slot bits
+//   slot, head, min_k                       SORTED: per target, circular ordered array {arrival step, amplitude},
+//                                           index of its front, earliest stored arrival step
+//   occ          i32   [BN]                 FIFO/SORTED: stored events
+//   cnt, cont, c_head, pool_*               contenders of the current step per target (slots, then a list)
+//   spk_words, stepcnt                      FIFO/SORTED: ballot words and per-block spike / event counts of the current step
 //   packed, a_q  u32/i32 [S]                FIFO/SORTED synapses: (col << dbits | D) and Q8.24 amplitude
 //   synf, synb   2 x u32 [S]                RING synapses, every row sorted by D: {packed, Q8.24 amplitude}
 //                                           for the forward pass, {packed, fp32 amplitude} for the reverse
@@ -46,7 +48,6 @@ struct Counters {
   long long sum_offered, sum_dropped, sum_delivered;
   long long tape_spikes, tape_events;
   unsigned err;
-  int n_spk[2];
   int pool_n[2];
   unsigned long long in_flight[2];  // scratch of k_ring_in_flight: events, Q8.24 sum
   unsigned long long fold[3];       // scratch of k_count_spikes: spikes, events, Q8.24 sum
@@ -55,8 +56,8 @@ struct Counters {
 // FIFO / SORTED: private event counters of one block of k_neurons / k_fanout (one 64-byte line
 // each, so that no two blocks add to the same address; summed on demand).
 struct BlkCtr {
-  unsigned long long offered, dropped, delivered;
-  long long sum_offered, sum_dropped, sum_delivered;
+  unsigned long long offered, admitted, delivered;
+  long long sum_offered, sum_admitted, sum_delivered;
   long long pad[2];
 };
 
@@ -87,7 +88,7 @@ struct Dev {
   unsigned* dstart;     // [N][d_max + 2]
   unsigned* nearcnt;    // [W + 1][N]
   unsigned* perm;       // [S]
-  long long* rowsum;    // [N]
+  long long* rowsum;    // [N] Q8.24 amplitude sum of every row (all kinds)
   uint2* ebuf;          // [min(P, kMaxParts)][NB][cap]
   int* ecnt;            // [min(P, kMaxParts)][NB]
   unsigned long long* tape_bits;  // [T][words]
@@ -98,26 +99,28 @@ struct Dev {
   float* fdec;
   float* V;
   unsigned long long* spike_bits;  // RING: [R][words] spikes of the last R steps
-  unsigned* slot_k;
-  int* slot_a;
+  uint2* slot;          // SORTED: [BN][C] {arrival step, Q8.24 amplitude}, circular, ordered by arrival
+  unsigned short* fkey; // FIFO: [BN][cpad] arrival step mod 2^16 of every slot
+  int* famp;            // FIFO: [BN][C] Q8.24 amplitude of every slot
+  unsigned* vmask;      // FIFO: [BN][nw] bit j of word w set = slot 32 w + j holds an event
+  int nw, cpad;         // FIFO: mask words per target = ceil(C / 32); C rounded up to a multiple of 8
   int* occ;
   int* head;
-  unsigned* min_k;      // FIFO: earliest stored arrival step per target (0xffffffff: none)
+  unsigned* min_k;      // FIFO/SORTED: earliest stored arrival step per target (0xffffffff: none)
   int* cnt;             // contenders registered per target since its last admission
-  long long* cont_p;    // [kCont][BN] contender slots: synapse index,
-  unsigned* cont_k;     //   arrival step,
-  int* cont_a;          //   Q8.24 amplitude,
-  long long* cont_t;    //   index of the admission flag on the tape (recording only)
+  uint4* cont;          // [kCont][BN] contender records (see bounded_queues.h)
   int* c_head;          // overflow list head per target (-1: empty)
   long long* pool_p;
   long long* pool_t;
   int* pool_next;
   unsigned* pool_k;
   int* pool_a;
-  int* cur_spk;
+  unsigned long long* spk_words;  // FIFO/SORTED: [2][words] ballot words of the step launch, by step parity
+  long long* stepcnt;   // FIFO/SORTED: [2][nblk][2] spikes and emitted events of every neuron block, by step parity
   float* tapeU;
   int* spk_count;       // [BN] spikes per (trial, neuron) over the recorded steps
   long long* step_off;
+  long long* step_evoff;  // FIFO/SORTED: events emitted before step n (index of its first admission flag)
   int* tape_spk;
   long long* tape_evb;
   unsigned char* tape_adm;
@@ -233,383 +236,8 @@ __global__ __launch_bounds__(kBlock) void k_prepare(Dev d, ExpCoef ec) {
 }
 
 // ---------------------------------------------------------------- bounded queues (FIFO / SORTED)
-//
-// Every target owns `capacity` slots (arrival step, Q8.24 amplitude), slot-major so that one
-// slot of 64 consecutive targets is one line.  A step is two launches:
-//   k_fanout   one block per spike walks the CSR row; an event whose target is already full is
-//              dropped at once (the occupancy only grows during a step's enqueue phase); every
-//              other event registers as a contender of its target: ticket = atomic count,
-//              tickets below kCont go to the target's contender slots, later ones to an overflow
-//              list (linked list through a pool);
-//   k_neurons  the thread that owns target j first admits j's contenders of the step before --
-//              the min(K, free) with the smallest synapse index, the canonical order -- then pops
-//              the events due now, integrates and compacts the spikes.
-// So admission needs no atomics on the slots and no launch of its own; a contender's fate is known
-// one launch later (entry points that read counters or admission flags admit what is pending first).
-// FIFO keeps, per target, the earliest stored arrival step, so that only the targets with an event
-// due now scan their slots; SORTED keeps the slots ordered and pops from the front.
 
-constexpr int kCont = 8;   // contender slots per target and step before the overflow list is used
-
-// Stores one admitted event for target g (owner thread).  FIFO: into the next free slot.
-// SORTED: into its place in the circular array ordered by arrival step (behind the stored events
-// with the same step); the events behind it move up one slot, eight at a time so that the loads
-// of a group are in flight together.
-template <int KIND>
-__device__ __forceinline__ void store_event(const Dev& d, int g, int occ, int hd, unsigned k, int a) {
-  const size_t BN = (size_t)d.BN;
-  if (KIND == ADSEQ_FIFO) {
-    const size_t si = (size_t)occ * BN + g;
-    d.slot_k[si] = k; d.slot_a[si] = a;
-    return;
-  }
-  // position: first index (from the front) whose arrival step exceeds k; binary search
-  int lo = 0, hi = occ;
-  while (lo < hi) {
-    const int mid = (lo + hi) >> 1;
-    int ph = hd + mid; if (ph >= d.C) ph -= d.C;
-    if (d.slot_k[(size_t)ph * BN + g] <= k) lo = mid + 1; else hi = mid;
-  }
-  for (int top = occ; top > lo;) {
-    const int nmove = top - lo < 8 ? top - lo : 8;     // move entries [top - nmove, top) up by one
-    unsigned mk[8]; int ma[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-      if (j < nmove) {
-        int ph = hd + top - 1 - j; if (ph >= d.C) ph -= d.C;
-        mk[j] = d.slot_k[(size_t)ph * BN + g]; ma[j] = d.slot_a[(size_t)ph * BN + g];
-      }
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-      if (j < nmove) {
-        int pd = hd + top - j; if (pd >= d.C) pd -= d.C;
-        d.slot_k[(size_t)pd * BN + g] = mk[j]; d.slot_a[(size_t)pd * BN + g] = ma[j];
-      }
-    top -= nmove;
-  }
-  int pw = hd + lo; if (pw >= d.C) pw -= d.C;
-  d.slot_k[(size_t)pw * BN + g] = k; d.slot_a[(size_t)pw * BN + g] = a;
-}
-
-// Admits the contenders registered for target g (owner thread): the min(K, free) with the
-// smallest synapse index are stored, the others dropped (counted into c_drop / s_drop).
-// Occupancy, earliest stored arrival (FIFO) and front index (SORTED) of a target: loaded once at
-// the start of k_neurons, kept in registers through admission and pop, written back at the end.
-struct QState { int occ; unsigned mn; int hd; };
-
-template <int KIND>
-__device__ __forceinline__ void admit_contenders(const Dev& d, int g, int K, QState& q, long long* c_drop,
-                                                 long long* s_drop) {
-  if (K <= 0) return;
-  d.cnt[g] = 0;
-  const size_t BN = (size_t)d.BN;
-  int occ = q.occ;
-  const int F = d.C - occ;
-  const int nc = K < kCont ? K : kCont;              // in the contender slots
-  const int ovf_head = K > kCont ? d.c_head[g] : -1; // the others: overflow list
-  if (K > kCont) d.c_head[g] = -1;
-  const int take = K < F ? K : F;
-  const int hd = q.hd;
-  unsigned mn = q.mn;
-  // the contender slots, loaded together
-  long long cp[kCont], ct[kCont]; unsigned ck[kCont]; int ca[kCont];
-#pragma unroll
-  for (int x = 0; x < kCont; ++x) {
-    cp[x] = 0x7fffffffffffffffLL; ct[x] = -1; ck[x] = 0; ca[x] = 0;
-    if (x < nc) {
-      const size_t ci = (size_t)x * BN + g;
-      cp[x] = d.cont_p[ci]; ck[x] = d.cont_k[ci]; ca[x] = d.cont_a[ci];
-      if (d.record) ct[x] = d.cont_t[ci];
-    }
-  }
-  if (take == K) {
-    // room for all: any order
-#pragma unroll
-    for (int x = 0; x < kCont; ++x)
-      if (x < nc) {
-        store_event<KIND>(d, g, occ, hd, ck[x], ca[x]);
-        ++occ; mn = ck[x] < mn ? ck[x] : mn;
-        if (ct[x] >= 0) d.tape_adm[ct[x]] = 1;
-      }
-    for (int y = ovf_head; y >= 0; y = d.pool_next[y]) {
-      const unsigned k = d.pool_k[y];
-      store_event<KIND>(d, g, occ, hd, k, d.pool_a[y]);
-      ++occ; mn = k < mn ? k : mn;
-      const long long t = d.pool_t[y];
-      if (t >= 0) d.tape_adm[t] = 1;
-    }
-  } else {
-    // oversubscribed: the `take` smallest synapse indices win, the others are dropped
-    long long last = -1;
-    for (int r = 0; r < take; ++r) {
-      long long bp = 0x7fffffffffffffffLL; int bx = -1, by = -1;
-#pragma unroll
-      for (int x = 0; x < kCont; ++x)
-        if (cp[x] > last && cp[x] < bp) { bp = cp[x]; bx = x; }
-      for (int y = ovf_head; y >= 0; y = d.pool_next[y]) {
-        const long long pp = d.pool_p[y];
-        if (pp > last && pp < bp) { bp = pp; by = y; bx = -1; }
-      }
-      if (bx < 0 && by < 0) break;   // not reached: K counts exactly the registered contenders
-      last = bp;
-      unsigned k = 0; int a = 0; long long t = -1;
-      if (bx >= 0) {
-#pragma unroll
-        for (int x = 0; x < kCont; ++x) if (x == bx) { k = ck[x]; a = ca[x]; t = ct[x]; }
-      } else {
-        k = d.pool_k[by]; a = d.pool_a[by]; t = d.pool_t[by];
-      }
-      store_event<KIND>(d, g, occ, hd, k, a);
-      ++occ; mn = k < mn ? k : mn;
-      if (t >= 0) d.tape_adm[t] = 1;
-    }
-#pragma unroll
-    for (int x = 0; x < kCont; ++x)
-      if (x < nc && cp[x] > last) {
-        *c_drop += 1; *s_drop += ca[x];
-        if (ct[x] >= 0) d.tape_adm[ct[x]] = 0;
-      }
-    for (int y = ovf_head; y >= 0; y = d.pool_next[y]) {
-      if (d.pool_p[y] > last) {
-        *c_drop += 1; *s_drop += d.pool_a[y];
-        const long long t = d.pool_t[y];
-        if (t >= 0) d.tape_adm[t] = 0;
-      }
-    }
-  }
-  q.occ = occ; q.mn = mn;
-}
-
-// One thread per (trial, neuron).  MODE 0: admission only (what is pending); 1: admission + pop,
-// writes the popped current to I_out (open loop); 2: admission + pop + drive + LIF + spike
-// compaction + tape (closed loop).
-template <int KIND, int MODE>
-__global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int parity,
-                                                    const float* __restrict__ i_ext,
-                                                    unsigned char* __restrict__ spikes_out,
-                                                    float* __restrict__ I_out) {
-  const int g = blockIdx.x * kBlock + threadIdx.x;
-  const bool act = g < d.BN;
-  int acc = 0;
-  long long popped = 0, c_drop = 0, s_drop = 0;
-  const unsigned kn = (unsigned)n;
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
-    d.ctr->pool_n[0] = 0;                        // the overflow pool is consumed by this launch
-    if (MODE == 2) d.ctr->n_spk[parity ^ 1] = 0;  // next step's spike counter; nobody reads it now
-  }
-  float v = 0.0f;
-  if (act) {
-    // everything the thread needs first, loaded together
-    const int K = d.cnt[g];
-    QState q, q0;
-    q.occ = d.occ[g];
-    q.mn = KIND == ADSEQ_FIFO ? d.min_k[g] : 0u;
-    q.hd = KIND == ADSEQ_SORTED ? d.head[g] : 0;
-    if (MODE == 2) v = d.V[g];
-    q0 = q;
-    admit_contenders<KIND>(d, g, K, q, &c_drop, &s_drop);
-    if (MODE != 0) {
-      const size_t BN = (size_t)d.BN;
-      if (KIND == ADSEQ_FIFO) {
-        // bounded bag: every stored event due now leaves.  Pass 1 only reads (all slot loads
-        // in flight together): sum of the due events, their positions, earliest arrival among
-        // the others.  Pass 2 fills each hole with the last stored event (the bag is unordered).
-        if (q.mn == kn) {
-          const int occ = q.occ;
-          unsigned mn = 0xffffffffu;
-          int ndue = 0;
-          int due[8];                      // positions of the first 8 due events, ascending
-          for (int s0 = 0; s0 < occ; s0 += 16) {
-            unsigned kk[16];                // 16 slot loads in flight, then their tests
-#pragma unroll
-            for (int j = 0; j < 16; ++j) kk[j] = s0 + j < occ ? d.slot_k[(size_t)(s0 + j) * BN + g] : 0xffffffffu;
-#pragma unroll
-            for (int j = 0; j < 16; ++j) {
-              if (s0 + j < occ) {
-                if (kk[j] == kn) { if (ndue < 8) due[ndue] = s0 + j; ++ndue; }
-                else mn = kk[j] < mn ? kk[j] : mn;
-              }
-            }
-          }
-          int top = occ;
-          if (ndue <= 8) {
-            for (int j = ndue - 1; j >= 0; --j) {   // from the back, so that the last event is a survivor or the hole itself
-              const int s = due[j];
-              acc = wrap_add(acc, d.slot_a[(size_t)s * BN + g]);
-              --top;
-              if (s != top) {
-                d.slot_k[(size_t)s * BN + g] = d.slot_k[(size_t)top * BN + g];
-                d.slot_a[(size_t)s * BN + g] = d.slot_a[(size_t)top * BN + g];
-              }
-            }
-          } else {
-            // many due at once: pack the survivors to the front
-            int keep = 0;
-            for (int s = 0; s < occ; ++s) {
-              const size_t si = (size_t)s * BN + g;
-              const unsigned k = d.slot_k[si];
-              if (k == kn) {
-                acc = wrap_add(acc, d.slot_a[si]);
-              } else {
-                if (keep != s) { d.slot_k[(size_t)keep * BN + g] = k; d.slot_a[(size_t)keep * BN + g] = d.slot_a[si]; }
-                ++keep;
-              }
-            }
-            top = keep;
-          }
-          popped += ndue;
-          q.occ = top;
-          q.mn = mn;
-        }
-      } else {
-        // ordered by arrival: everything due now sits at the front of the circular array
-        int occ = q.occ, hd = q.hd;
-        while (occ > 0 && d.slot_k[(size_t)hd * BN + g] == kn) {
-          acc = wrap_add(acc, d.slot_a[(size_t)hd * BN + g]);
-          hd = hd + 1 == d.C ? 0 : hd + 1;
-          --occ;
-          ++popped;
-        }
-        q.occ = occ; q.hd = hd;
-      }
-    }
-    if (q.occ != q0.occ) d.occ[g] = q.occ;
-    if (KIND == ADSEQ_FIFO && q.mn != q0.mn) d.min_k[g] = q.mn;
-    if (KIND == ADSEQ_SORTED && q.hd != q0.hd) d.head[g] = q.hd;
-  }
-  bool s = false;
-  if (act && MODE != 0) {
-    float I = (float)acc * 0x1p-24f;
-    if (MODE == 2) {
-      if (d.p_thresh) {
-        const bool xi = (unsigned long long)drive_bits(d.seed, (unsigned long long)g,
-                                                       (unsigned long long)n) < d.p_thresh;
-        I = I + (xi ? d.ext_w : 0.0f);
-      }
-      if (i_ext) I = I + i_ext[g];
-      const float U = __fmaf_rn(d.alpha, v, I);
-      s = U >= d.theta;
-      d.V[g] = s ? d.v_reset : U;
-      if (d.record && n < d.max_steps) {
-        d.tapeU[(size_t)n * d.BN + g] = U;
-        if (s) d.spk_count[g] += 1;
-      }
-      if (spikes_out) spikes_out[g] = s ? 1 : 0;
-    } else {
-      I_out[g] = I;
-    }
-  }
-  if (MODE == 2) {
-    // wavefront ballot + prefix popcount; one atomic per wavefront that has spikes
-    const unsigned long long m = __ballot(s);
-    const int lane = threadIdx.x & 63;
-    int base = 0;
-    if (lane == 0 && m) base = atomicAdd(&d.ctr->n_spk[parity], __popcll(m));
-    base = __shfl(base, 0, 64);
-    if (s) d.cur_spk[base + __popcll(m & ((1ull << lane) - 1ull))] = g;
-  }
-  BlkCtr& bc = d.blk[blockIdx.x];
-  block_add2(&bc.delivered, popped, &bc.sum_delivered, (long long)acc);
-  block_add2(&bc.dropped, c_drop, &bc.sum_dropped, s_drop);
-}
-
-// One block per spike (grid-stride over the spike list); the block walks the CSR row with
-// coalesced reads of (packed, a_q).  Events whose target is already full are dropped here; the
-// others register as contenders of their target (see above).
-template <int KIND>
-__global__ __launch_bounds__(kBlock) void k_fanout(Dev d, long long n, const int* __restrict__ spk,
-                                                   const int* __restrict__ n_spk_ptr, int record) {
-  __shared__ long long s_evb;
-  int nspk = *n_spk_ptr;
-  nspk = nspk < 0 ? 0 : (nspk > d.BN ? d.BN : nspk);
-  const long long off = record ? d.step_off[n] : 0;
-  const int lane = threadIdx.x & 63;
-  const size_t BN = (size_t)d.BN;
-  long long c_off = 0, s_off = 0, c_drop = 0, s_drop = 0;
-  for (int e = blockIdx.x; e < nspk; e += gridDim.x) {
-    const int g = spk[e];
-    if ((unsigned)g >= (unsigned)d.BN) continue;  // uniform over the block
-    const int b = g / d.N, i = g - b * d.N;
-    const long long r0 = d.row_ptr[i], r1 = d.row_ptr[i + 1];
-    long long tbase = -1;
-    if (record) {
-      const bool fits = off + e < d.spike_cap;
-      if (threadIdx.x == 0) {
-        if (fits) d.tape_spk[off + e] = g; else atomicOr(&d.ctr->err, ERR_TAPE_SPIKES);
-        long long evb = (long long)atomicAdd((unsigned long long*)&d.ctr->tape_events,
-                                             (unsigned long long)(r1 - r0));
-        if (evb + (r1 - r0) > d.event_cap) { atomicOr(&d.ctr->err, ERR_TAPE_EVENTS); evb = -1; }
-        if (fits) d.tape_evb[off + e] = evb;
-        s_evb = evb;
-      }
-      __syncthreads();
-      tbase = s_evb;
-      __syncthreads();
-    }
-    // four row entries per thread and trip, each stage for all four before the next, so that
-    // the loads, the occupancy gathers and the ticket atomics of a trip are in flight together
-    for (long long p0 = r0; p0 < r1; p0 += 4 * kBlock) {
-      long long p[4]; bool valid[4]; unsigned pk[4]; int a[4], gt[4], tk[4]; bool contend[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        p[j] = p0 + j * kBlock + threadIdx.x;
-        valid[j] = p[j] < r1;
-        pk[j] = 0; a[j] = 0;
-        if (valid[j]) { pk[j] = d.packed[p[j]]; a[j] = d.a_q[p[j]]; }
-      }
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        gt[j] = b * d.N + (int)(pk[j] >> d.dbits);
-        contend[j] = false;
-        if (valid[j]) { c_off += 1; s_off += a[j]; contend[j] = d.occ[gt[j]] < d.C; }
-      }
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        tk[j] = -1;
-        if (contend[j]) tk[j] = atomicAdd(&d.cnt[gt[j]], 1);
-      }
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int D = (int)(pk[j] & d.dmask);
-        const long long tidx = (valid[j] && tbase >= 0) ? tbase + (p[j] - r0) : -1;
-        if (valid[j] && !contend[j]) { c_drop += 1; s_drop += a[j]; if (tidx >= 0) d.tape_adm[tidx] = 0; }
-        if (contend[j] && tk[j] < kCont) {
-          const size_t ci = (size_t)tk[j] * BN + gt[j];
-          d.cont_p[ci] = p[j]; d.cont_k[ci] = (unsigned)(n + D); d.cont_a[ci] = a[j];
-          if (d.record) d.cont_t[ci] = tidx;
-        }
-        // the others: wavefront-aggregated claim of pool entries, pushed on the target's list
-        const bool over = contend[j] && tk[j] >= kCont;
-        const unsigned long long cm = __ballot(over);
-        if (cm) {
-          int base = 0;
-          if (lane == __ffsll((long long)cm) - 1) base = atomicAdd(&d.ctr->pool_n[0], __popcll(cm));
-          base = __shfl(base, __ffsll((long long)cm) - 1, 64);
-          if (over) {
-            const int x = base + __popcll(cm & ((1ull << lane) - 1ull));
-            if (x >= d.pool_cap) {
-              // no room to remember it: it can only be dropped, and the run is flagged as invalid
-              atomicOr(&d.ctr->err, ERR_POOL);
-              atomicSub(&d.cnt[gt[j]], 1);
-              c_drop += 1; s_drop += a[j]; if (tidx >= 0) d.tape_adm[tidx] = 0;
-            } else {
-              d.pool_p[x] = p[j]; d.pool_t[x] = tidx;
-              d.pool_k[x] = (unsigned)(n + D); d.pool_a[x] = a[j];
-              d.pool_next[x] = atomicExch(&d.c_head[gt[j]], x);
-            }
-          }
-        }
-      }
-    }
-  }
-  if (record && blockIdx.x == 0 && threadIdx.x == 0) {
-    if (n + 1 <= d.max_steps) d.step_off[n + 1] = off + nspk;
-    d.ctr->tape_spikes = off + nspk;
-  }
-  BlkCtr& bc = d.blk[d.nblk + blockIdx.x];
-  block_add2(&bc.offered, c_off, &bc.sum_offered, s_off);
-  block_add2(&bc.dropped, c_drop, &bc.sum_dropped, s_drop);
-}
+#include "bounded_queues.h"
 
 __global__ __launch_bounds__(kBlock) void k_copy_i32(const int* __restrict__ src, int* __restrict__ dst, size_t n) {
   for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) dst[i] = src[i];
@@ -716,9 +344,9 @@ struct adseq {
 namespace {
 
 struct Layout {
-  size_t V, win, spike_bits, slot_k, slot_a, occ, head, min_k, cnt, cont_p, cont_k, cont_a, cont_t, c_head, pool_p, pool_t, pool_next,
-      pool_k, pool_a, cur_spk, packed, a_q, synf, synb, dstart, nearcnt, perm, rowsum, ebuf, ecnt, amp, fdec, tapeU,
-      tape_bits, spk_count, step_off, tape_spk, tape_evb, tape_adm, bwd_ring, bwd_carry, bwd_G, gwin, Gacc, gsum, ctr, blk,
+  size_t V, win, spike_bits, slot, fkey, famp, vmask, occ, head, min_k, cnt, cont, c_head, pool_p, pool_t, pool_next,
+      pool_k, pool_a, spk_words, stepcnt, packed, a_q, synf, synb, dstart, nearcnt, perm, rowsum, ebuf, ecnt, amp, fdec, tapeU,
+      tape_bits, spk_count, step_off, step_evoff, tape_spk, tape_evb, tape_adm, bwd_ring, bwd_carry, bwd_G, gwin, Gacc, gsum, ctr, blk,
       total;
   long long spike_cap, event_cap, pool_cap;
   int R, dbits, nblk, words;
@@ -739,6 +367,12 @@ int ring_window_steps() { return env_pow2("ADSEQ_RING_WINDOW", 16, 2, 64); }
 // Cells (target, step) of the LDS tile of one target part.
 int ring_tile_cells() { return env_pow2("ADSEQ_RING_TILE", 4096, 1024, kMaxTileCells); }
 
+// Private counter slots of the fan-out kernels (closed loop: kFanSplit blocks per neuron block).
+size_t fan_slots(int nblk) {
+  const size_t a = (size_t)nblk * kFanSplit;
+  return a > (size_t)kFanoutBlocks ? a : (size_t)kFanoutBlocks;
+}
+
 int bit_width(unsigned v) { int b = 0; while (v) { ++b; v >>= 1; } return b; }
 
 bool host_validate(const adseq_config* c) {
@@ -750,7 +384,7 @@ bool host_validate(const adseq_config* c) {
   if (c->surrogate != ADSEQ_SURR_SUPERSPIKE && c->surrogate != ADSEQ_SURR_OFF) return false;
   if (!(c->dt_ms > 0.0f) || !(c->tau_m_ms > 0.0f) || c->dt_ms > c->tau_m_ms) return false;
   if (!(c->ext_rate_hz >= 0.0f)) return false;
-  if (c->n_synapses < 0) return false;
+  if (c->n_synapses < 0 || c->n_synapses >= (1LL << 40)) return false;   // synapse indices are packed into 40 bits
   if (c->record_tape && c->max_steps < 1) return false;
   if (c->tape_spike_capacity < 0 || c->tape_event_capacity < 0 || c->step_event_capacity < 0)
     return false;
@@ -773,6 +407,7 @@ bool make_layout(const adseq_config* c, Layout* L) {
     if (bounded) {
       const long long fan = (long long)((S + c->n_neurons - 1) / c->n_neurons);
       L->event_cap = c->tape_event_capacity ? c->tape_event_capacity : L->spike_cap * (fan ? fan : 1);
+      if (L->event_cap >= (1LL << 40) - 1) return false;   // admission-flag indices are packed into 40 bits
     }
   }
   if (bounded) {
@@ -788,11 +423,10 @@ bool make_layout(const adseq_config* c, Layout* L) {
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o += (bytes + 255) & ~(size_t)255; return at; };
   L->nblk = (int)((BN + kBlock - 1) / kBlock);
-  L->words = 0;
+  L->words = L->nblk * (kBlock / 64);
   L->W = L->wshift = L->tp_shift = L->P = L->NB = L->cap = L->wgroups = 0;
   size_t stage_parts = 0;
   if (!bounded) {
-    L->words = L->nblk * (kBlock / 64);
     // the window is no longer than the largest delay (so that a window boundary comes before
     // any spike word is overwritten)
     L->W = ring_window_steps();
@@ -818,27 +452,28 @@ bool make_layout(const adseq_config* c, Layout* L) {
     L->cap = (int)(per > 65536.0 ? 65536.0 : per);
   }
   L->ctr = take(sizeof(Counters));
-  L->blk = take(bounded ? ((size_t)L->nblk + kFanoutBlocks) * sizeof(BlkCtr) : 0);
+  L->blk = take(bounded ? ((size_t)L->nblk + fan_slots(L->nblk)) * sizeof(BlkCtr) : 0);
   L->V = take(BN * 4);
   L->win = take(bounded ? 0 : 2 * (size_t)L->W * BN * 4);
   L->spike_bits = take(bounded ? 0 : (size_t)L->R * L->words * 8);
-  L->slot_k = take(bounded ? (size_t)c->capacity * BN * 4 : 0);
-  L->slot_a = take(bounded ? (size_t)c->capacity * BN * 4 : 0);
+  const bool fifo = c->kind == ADSEQ_FIFO;
+  L->slot = take(c->kind == ADSEQ_SORTED ? (size_t)c->capacity * BN * 8 : 0);
+  L->fkey = take(fifo ? (size_t)((c->capacity + 7) / 8 * 8) * BN * 2 : 0);
+  L->famp = take(fifo ? (size_t)c->capacity * BN * 4 : 0);
+  L->vmask = take(fifo ? (size_t)((c->capacity + 31) / 32) * BN * 4 : 0);
   L->occ = take(bounded ? BN * 4 : 0);
   L->head = take(bounded ? BN * 4 : 0);
   L->min_k = take(bounded ? BN * 4 : 0);
   L->cnt = take(bounded ? BN * 4 : 0);
-  L->cont_p = take(bounded ? (size_t)kCont * BN * 8 : 0);
-  L->cont_k = take(bounded ? (size_t)kCont * BN * 4 : 0);
-  L->cont_a = take(bounded ? (size_t)kCont * BN * 4 : 0);
-  L->cont_t = take(bounded && c->record_tape ? (size_t)kCont * BN * 8 : 0);
+  L->cont = take(bounded ? (size_t)kCont * BN * 16 : 0);
   L->c_head = take(bounded ? BN * 4 : 0);
   L->pool_p = take((size_t)L->pool_cap * 8);
   L->pool_t = take((size_t)L->pool_cap * 8);
   L->pool_next = take((size_t)L->pool_cap * 4);
   L->pool_k = take((size_t)L->pool_cap * 4);
   L->pool_a = take((size_t)L->pool_cap * 4);
-  L->cur_spk = take(BN * 4);
+  L->spk_words = take(bounded ? 2 * (size_t)L->words * 8 : 0);
+  L->stepcnt = take(bounded ? 2 * (size_t)L->nblk * 16 : 0);
   L->packed = take(bounded ? S * 4 : 0);
   L->a_q = take(bounded ? S * 4 : 0);
   L->synf = take(bounded ? 0 : S * 8);
@@ -846,7 +481,7 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->dstart = take(bounded ? 0 : (size_t)c->n_neurons * (c->d_max_steps + 2) * 4);
   L->nearcnt = take(bounded ? 0 : (size_t)(L->W + 1) * c->n_neurons * 4);
   L->perm = take(bounded ? 0 : S * 4);
-  L->rowsum = take(bounded ? 0 : (size_t)c->n_neurons * 8);
+  L->rowsum = take((size_t)c->n_neurons * 8);
   L->ebuf = take(bounded ? 0 : stage_parts * L->NB * (size_t)L->cap * 8);
   L->ecnt = take(bounded ? 0 : stage_parts * L->NB * 4);
   L->amp = take(cont && bounded ? S * 4 : 0);
@@ -856,6 +491,7 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->tape_bits = take(bounded ? 0 : T * L->words * 8);
   L->spk_count = take(c->record_tape ? BN * 4 : 0);
   L->step_off = take(c->record_tape ? (T + 1) * 8 : 0);
+  L->step_evoff = take(c->record_tape && bounded ? (T + 1) * 8 : 0);
   L->tape_spk = take(bounded ? (size_t)L->spike_cap * 4 : 0);
   L->tape_evb = take(bounded ? (size_t)L->spike_cap * 8 : 0);
   L->tape_adm = take((size_t)L->event_cap);
@@ -913,12 +549,14 @@ void launch_reset(adseq* h, hipStream_t st) {
     fill_u32(st, d.head, 0u, BN);
     fill_u32(st, d.c_head, 0xffffffffu, BN);
     fill_u32(st, d.min_k, 0xffffffffu, BN);
+    if (d.kind == ADSEQ_FIFO) fill_u32(st, d.vmask, 0u, (size_t)d.nw * BN);
     fill_u32(st, d.cnt, 0u, BN);
-    fill_u32(st, d.blk, 0u, ((size_t)d.nblk + kFanoutBlocks) * sizeof(BlkCtr) / 4);
+    fill_u32(st, d.blk, 0u, ((size_t)d.nblk + fan_slots(d.nblk)) * sizeof(BlkCtr) / 4);
     h->pending_admit = false;
   }
   if (d.record) {
     fill_u32(st, d.step_off, 0u, 2);  // step_off[0] = 0 (int64)
+    if (d.kind != ADSEQ_RING) fill_u32(st, d.step_evoff, 0u, 2);
     fill_u32(st, d.spk_count, 0u, BN);
   }
   h->next_step = 0;
@@ -939,13 +577,20 @@ void launch_neurons(adseq* h, hipStream_t st, long long n, int parity, const flo
   h->pending_admit = false;
 }
 
-void launch_fanout(adseq* h, hipStream_t st, long long n, const int* spk, const int* n_spk, int record) {
+// FIFO / SORTED fan-out of step n: the spikes of this step's k_neurons launch (spk = nullptr,
+// closed loop) or the caller's list of neuron indices (open loop).
+void launch_fanout(adseq* h, hipStream_t st, long long n, const int* spk, const int* n_spk, int parity, int record) {
   const Dev& d = h->dev;
-  const dim3 grid(kFanoutBlocks), block(kBlock);
-  if (d.kind == ADSEQ_FIFO)
-    hipLaunchKernelGGL((k_fanout<ADSEQ_FIFO>), grid, block, 0, st, d, n, spk, n_spk, record);
-  else
-    hipLaunchKernelGGL((k_fanout<ADSEQ_SORTED>), grid, block, 0, st, d, n, spk, n_spk, record);
+  const dim3 block(kBlock);
+  if (!spk) {
+    const dim3 grid((unsigned)d.nblk * kFanSplit);
+    if (d.kind == ADSEQ_FIFO) hipLaunchKernelGGL((k_fanout_step<ADSEQ_FIFO>), grid, block, 0, st, d, n, parity, record);
+    else hipLaunchKernelGGL((k_fanout_step<ADSEQ_SORTED>), grid, block, 0, st, d, n, parity, record);
+  } else {
+    const dim3 grid(kFanoutBlocks);
+    if (d.kind == ADSEQ_FIFO) hipLaunchKernelGGL((k_fanout_list<ADSEQ_FIFO>), grid, block, 0, st, d, n, spk, n_spk);
+    else hipLaunchKernelGGL((k_fanout_list<ADSEQ_SORTED>), grid, block, 0, st, d, n, spk, n_spk);
+  }
   h->pending_admit = true;
   h->last_stream = st;
 }
@@ -953,7 +598,8 @@ void launch_fanout(adseq* h, hipStream_t st, long long n, const int* spk, const 
 // FIFO / SORTED: admits the contenders that the last enqueue registered, if that has not
 // happened yet (it normally rides on the next step's launch).
 void flush_admit(adseq* h, hipStream_t st) {
-  if (h->dev.kind != ADSEQ_RING && h->pending_admit) launch_neurons<0>(h, st, 0, 0, nullptr, nullptr, nullptr);
+  if (h->dev.kind != ADSEQ_RING && h->pending_admit)
+    launch_neurons<0>(h, st, h->next_step, 0, nullptr, nullptr, nullptr);
 }
 
 void mark(adseq* h, hipStream_t st, int kind, int count = 1);
@@ -1025,7 +671,7 @@ int step_impl(adseq* h, long long step, const float* i_ext, unsigned char* spike
     mark(h, st, -1);
     launch_neurons<2>(h, st, step, parity, i_ext, spikes_out, nullptr);
     mark(h, st, 1);
-    launch_fanout(h, st, step, d.cur_spk, &d.ctr->n_spk[parity], record);
+    launch_fanout(h, st, step, nullptr, nullptr, parity, record);
     mark(h, st, 0);
   }
   h->enq_calls += 1;
@@ -1130,20 +776,22 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   d.tape_bits = (unsigned long long*)(ws + L.tape_bits);
   d.spk_count = (int*)(ws + L.spk_count);
   d.gwin = (float*)(ws + L.gwin); d.Gacc = (float*)(ws + L.Gacc); d.gsum = (float*)(ws + L.gsum);
-  d.slot_k = (unsigned*)(ws + L.slot_k); d.slot_a = (int*)(ws + L.slot_a);
+  d.slot = (uint2*)(ws + L.slot); d.vmask = (unsigned*)(ws + L.vmask);
+  d.fkey = (unsigned short*)(ws + L.fkey); d.famp = (int*)(ws + L.famp);
+  d.nw = (cfg->capacity + 31) / 32; d.cpad = (cfg->capacity + 7) / 8 * 8;
   d.occ = (int*)(ws + L.occ); d.head = (int*)(ws + L.head); d.c_head = (int*)(ws + L.c_head);
   d.pool_p = (long long*)(ws + L.pool_p); d.pool_t = (long long*)(ws + L.pool_t);
   d.pool_next = (int*)(ws + L.pool_next);
   d.min_k = (unsigned*)(ws + L.min_k); d.cnt = (int*)(ws + L.cnt);
-  d.cont_p = (long long*)(ws + L.cont_p); d.cont_k = (unsigned*)(ws + L.cont_k);
-  d.cont_a = (int*)(ws + L.cont_a); d.cont_t = (long long*)(ws + L.cont_t);
+  d.cont = (uint4*)(ws + L.cont);
   d.pool_k = (unsigned*)(ws + L.pool_k); d.pool_a = (int*)(ws + L.pool_a);
-  d.cur_spk = (int*)(ws + L.cur_spk);
+  d.spk_words = (unsigned long long*)(ws + L.spk_words); d.stepcnt = (long long*)(ws + L.stepcnt);
   d.packed = (unsigned*)(ws + L.packed); d.a_q = (int*)(ws + L.a_q);
   d.amp = (d.continuous && d.kind != ADSEQ_RING) ? (float*)(ws + L.amp) : nullptr;
   d.synf = (uint2*)(ws + L.synf); d.synb = (uint2*)(ws + L.synb);
   d.fdec = d.continuous ? (float*)(ws + L.fdec) : nullptr;
   d.tapeU = (float*)(ws + L.tapeU); d.step_off = (long long*)(ws + L.step_off);
+  d.step_evoff = (long long*)(ws + L.step_evoff);
   d.tape_spk = (int*)(ws + L.tape_spk); d.tape_evb = (long long*)(ws + L.tape_evb);
   d.tape_adm = (unsigned char*)(ws + L.tape_adm);
   d.bwd_ring = (float*)(ws + L.bwd_ring); d.bwd_carry = (float*)(ws + L.bwd_carry);
@@ -1178,6 +826,10 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
     if (g < 1) g = 1;
     hipLaunchKernelGGL(k_prepare, dim3((unsigned)g), dim3(kBlock), 0, st, d, ec);
     e = read_err();
+    if (e == hipSuccess && !err) {
+      const unsigned gr = (unsigned)((d.N + 3) / 4 < 8192 ? (d.N + 3) / 4 : 8192);
+      hipLaunchKernelGGL(k_row_sums, dim3(gr), dim3(kBlock), 0, st, d);
+    }
   }
   if (e != hipSuccess) { delete h; return ADSEQ_E_HIP; }
   if (err & ERR_GRAPH) { delete h; return ADSEQ_E_GRAPH; }
@@ -1230,7 +882,7 @@ int adseq_enqueue(adseq_t* h, int64_t step, const int32_t* spike_ids, const int3
     hipLaunchKernelGGL(k_enqueue_win, dim3(kFanoutBlocks), dim3(kBlock), 0, (hipStream_t)stream, h->dev,
                        (long long)step, spike_ids, n_spikes);
   else
-    launch_fanout(h, (hipStream_t)stream, step, spike_ids, n_spikes, 0);
+    launch_fanout(h, (hipStream_t)stream, step, spike_ids, n_spikes, parity, 0);
   h->enq_calls += 1;
   h->tape_ok = false;
   HIP_TRY(h, hipGetLastError());
@@ -1325,14 +977,18 @@ int adseq_counters(adseq_t* h, int64_t* out8, void* stream) {
   out8[6] = c.tape_spikes; out8[7] = (int64_t)c.err;
   if (d.kind != ADSEQ_RING) {
     // the kernels keep private counters per block: add them up here
-    const size_t nb = (size_t)d.nblk + kFanoutBlocks;
+    const size_t nb = (size_t)d.nblk + fan_slots(d.nblk);
     std::vector<BlkCtr> hb(nb);
     HIP_TRY(h, hipMemcpyAsync(hb.data(), d.blk, sizeof(BlkCtr) * nb, hipMemcpyDeviceToHost, st));
     HIP_TRY(h, hipStreamSynchronize(st));
+    int64_t admitted = 0, sum_admitted = 0;
     for (const BlkCtr& b : hb) {
-      out8[0] += (int64_t)b.offered; out8[1] += (int64_t)b.dropped; out8[2] += (int64_t)b.delivered;
-      out8[3] += b.sum_offered; out8[4] += b.sum_dropped; out8[5] += b.sum_delivered;
+      out8[0] += (int64_t)b.offered; admitted += (int64_t)b.admitted; out8[2] += (int64_t)b.delivered;
+      out8[3] += b.sum_offered; sum_admitted += b.sum_admitted; out8[5] += b.sum_delivered;
     }
+    // every offered event has been admitted or refused by now (what was pending was admitted above)
+    out8[1] = out8[0] - admitted;
+    out8[4] = out8[3] - sum_admitted;
   }
   if (d.kind == ADSEQ_RING) {
     out8[6] += (int64_t)c.fold[0]; out8[0] += (int64_t)c.fold[1]; out8[3] += (int64_t)c.fold[2];

@@ -13,16 +13,16 @@ int main() {
   const size_t n = (size_t)1 << 26;  // float4 elements = 1 GiB
   float4 *a, *b;
   if (hipMalloc(&a, n * 16) != hipSuccess || hipMalloc(&b, n * 16) != hipSuccess) return 1;
-  hipMemset(a, 1, n * 16);
+  if (hipMemset(a, 1, n * 16) != hipSuccess) return 1;
   hipEvent_t e0, e1;
-  hipEventCreate(&e0); hipEventCreate(&e1);
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return 1;
   for (int r = 0; r < 4; ++r) {
-    hipEventRecord(e0);
-    k_copy_ref<<<8192, 256>>>(a, b, n);
-    hipEventRecord(e1);
-    hipEventSynchronize(e1);
     float ms = 0;
-    hipEventElapsedTime(&ms, e0, e1);
+    bool ok = hipEventRecord(e0) == hipSuccess;
+    k_copy_ref<<<8192, 256>>>(a, b, n);
+    ok = ok && hipEventRecord(e1) == hipSuccess && hipEventSynchronize(e1) == hipSuccess &&
+         hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+    if (!ok) return 1;
     printf("copy %zu B read + %zu B written: %.3f ms, %.1f GB/s\n", n * 16, n * 16, ms, 2.0 * n * 16 / ms / 1e6);
   }
   return 0;
