@@ -62,7 +62,8 @@ def main():
     kind = {"ring": adseq.RING, "fifo": adseq.FIFO, "sorted": adseq.SORTED}[args.queue]
     cap = 0 if kind == adseq.RING else args.capacity
     fan = wl.n_synapses // N
-    spike_cap = max(BN * T // 4, 4 * BN)
+    # room on the tape of the bounded kinds: ten times the spikes of a run at 20 Hz
+    spike_cap = max(int(10 * BN * T * 20.0 * wl.dt_ms * 1e-3), 4 * BN)
     sim = adseq.Adseq(wl, kind, cap, record_tape=True, max_steps=T, tape_spike_capacity=spike_cap,
                       tape_event_capacity=(spike_cap * fan if kind != adseq.RING else 0))
     y = torch.from_numpy(synth.spike_count_targets(wl)).to(dev).reshape(-1)
@@ -139,8 +140,8 @@ def main():
                  "bwd_gather": "k_bwd_win (far queue terms and gradient sums of one window)",
                  "bwd_neurons": "k_bwd_step_win (adjoint update + in-window gather)"}
     else:
-        label = {"fan_out": "k_fanout (CSR fan-out, full-target drops, contender registration)",
-                 "lif": "k_neurons (admission + pop + drive + LIF + compaction)",
+        label = {"fan_out": "k_fanout_step (CSR fan-out, full-target drops, contender registration)",
+                 "lif": "k_neurons (admission + pop + drive + LIF + spike words)",
                  "bwd_gather": "k_bwd_gather", "bwd_neurons": "k_bwd_neurons"}
     kernels = {}
     for k, v in prof.items():

@@ -89,6 +89,7 @@ struct Dev {
   unsigned* nearcnt;    // [W + 1][N]
   unsigned* perm;       // [S]
   long long* rowsum;    // [N] Q8.24 amplitude sum of every row (all kinds)
+  int* rowlen;          // FIFO/SORTED: [N] row lengths
   uint2* ebuf;          // [min(P, kMaxParts)][NB][cap]
   int* ecnt;            // [min(P, kMaxParts)][NB]
   unsigned long long* tape_bits;  // [T][words]
@@ -103,6 +104,7 @@ struct Dev {
   unsigned short* fkey; // FIFO: [BN][cpad] arrival step mod 2^16 of every slot
   int* famp;            // FIFO: [BN][C] Q8.24 amplitude of every slot
   unsigned* vmask;      // FIFO: [BN][nw] bit j of word w set = slot 32 w + j holds an event
+  int fsplit;           // FIFO/SORTED: blocks per neuron block of the closed-loop fan-out (1 .. kFanSplitMax)
   int nw, cpad;         // FIFO: mask words per target = ceil(C / 32); C rounded up to a multiple of 8
   int* occ;
   int* head;
@@ -116,6 +118,7 @@ struct Dev {
   unsigned* pool_k;
   int* pool_a;
   unsigned long long* spk_words;  // FIFO/SORTED: [2][words] ballot words of the step launch, by step parity
+  int* busy_hint;       // FIFO/SORTED: [nblk] 1 = an eighth or more of the block's targets held an event after the last step
   long long* stepcnt;   // FIFO/SORTED: [2][nblk][2] spikes and emitted events of every neuron block, by step parity
   float* tapeU;
   int* spk_count;       // [BN] spikes per (trial, neuron) over the recorded steps
@@ -345,7 +348,7 @@ namespace {
 
 struct Layout {
   size_t V, win, spike_bits, slot, fkey, famp, vmask, occ, head, min_k, cnt, cont, c_head, pool_p, pool_t, pool_next,
-      pool_k, pool_a, spk_words, stepcnt, packed, a_q, synf, synb, dstart, nearcnt, perm, rowsum, ebuf, ecnt, amp, fdec, tapeU,
+      pool_k, pool_a, spk_words, stepcnt, busy_hint, packed, a_q, synf, synb, dstart, nearcnt, perm, rowsum, rowlen, ebuf, ecnt, amp, fdec, tapeU,
       tape_bits, spk_count, step_off, step_evoff, tape_spk, tape_evb, tape_adm, bwd_ring, bwd_carry, bwd_G, gwin, Gacc, gsum, ctr, blk,
       total;
   long long spike_cap, event_cap, pool_cap;
@@ -367,9 +370,9 @@ int ring_window_steps() { return env_pow2("ADSEQ_RING_WINDOW", 16, 2, 64); }
 // Cells (target, step) of the LDS tile of one target part.
 int ring_tile_cells() { return env_pow2("ADSEQ_RING_TILE", 4096, 1024, kMaxTileCells); }
 
-// Private counter slots of the fan-out kernels (closed loop: kFanSplit blocks per neuron block).
+// Private counter slots of the fan-out kernels (closed loop: up to kFanSplitMax blocks per neuron block).
 size_t fan_slots(int nblk) {
-  const size_t a = (size_t)nblk * kFanSplit;
+  const size_t a = (size_t)nblk * kFanSplitMax;
   return a > (size_t)kFanoutBlocks ? a : (size_t)kFanoutBlocks;
 }
 
@@ -474,6 +477,7 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->pool_a = take((size_t)L->pool_cap * 4);
   L->spk_words = take(bounded ? 2 * (size_t)L->words * 8 : 0);
   L->stepcnt = take(bounded ? 2 * (size_t)L->nblk * 16 : 0);
+  L->busy_hint = take(bounded ? (size_t)L->nblk * 4 : 0);
   L->packed = take(bounded ? S * 4 : 0);
   L->a_q = take(bounded ? S * 4 : 0);
   L->synf = take(bounded ? 0 : S * 8);
@@ -482,6 +486,7 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->nearcnt = take(bounded ? 0 : (size_t)(L->W + 1) * c->n_neurons * 4);
   L->perm = take(bounded ? 0 : S * 4);
   L->rowsum = take((size_t)c->n_neurons * 8);
+  L->rowlen = take(bounded ? (size_t)c->n_neurons * 4 : 0);
   L->ebuf = take(bounded ? 0 : stage_parts * L->NB * (size_t)L->cap * 8);
   L->ecnt = take(bounded ? 0 : stage_parts * L->NB * 4);
   L->amp = take(cont && bounded ? S * 4 : 0);
@@ -551,6 +556,7 @@ void launch_reset(adseq* h, hipStream_t st) {
     fill_u32(st, d.min_k, 0xffffffffu, BN);
     if (d.kind == ADSEQ_FIFO) fill_u32(st, d.vmask, 0u, (size_t)d.nw * BN);
     fill_u32(st, d.cnt, 0u, BN);
+    fill_u32(st, d.busy_hint, 0u, (size_t)d.nblk);
     fill_u32(st, d.blk, 0u, ((size_t)d.nblk + fan_slots(d.nblk)) * sizeof(BlkCtr) / 4);
     h->pending_admit = false;
   }
@@ -583,7 +589,7 @@ void launch_fanout(adseq* h, hipStream_t st, long long n, const int* spk, const 
   const Dev& d = h->dev;
   const dim3 block(kBlock);
   if (!spk) {
-    const dim3 grid((unsigned)d.nblk * kFanSplit);
+    const dim3 grid((unsigned)d.nblk * d.fsplit);
     if (d.kind == ADSEQ_FIFO) hipLaunchKernelGGL((k_fanout_step<ADSEQ_FIFO>), grid, block, 0, st, d, n, parity, record);
     else hipLaunchKernelGGL((k_fanout_step<ADSEQ_SORTED>), grid, block, 0, st, d, n, parity, record);
   } else {
@@ -771,7 +777,7 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   d.wgroups = L.wgroups;
   d.win = (int*)(ws + L.win);
   d.dstart = (unsigned*)(ws + L.dstart); d.nearcnt = (unsigned*)(ws + L.nearcnt);
-  d.perm = (unsigned*)(ws + L.perm); d.rowsum = (long long*)(ws + L.rowsum);
+  d.perm = (unsigned*)(ws + L.perm); d.rowsum = (long long*)(ws + L.rowsum); d.rowlen = (int*)(ws + L.rowlen);
   d.ebuf = (uint2*)(ws + L.ebuf); d.ecnt = (int*)(ws + L.ecnt);
   d.tape_bits = (unsigned long long*)(ws + L.tape_bits);
   d.spk_count = (int*)(ws + L.spk_count);
@@ -779,6 +785,12 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   d.slot = (uint2*)(ws + L.slot); d.vmask = (unsigned*)(ws + L.vmask);
   d.fkey = (unsigned short*)(ws + L.fkey); d.famp = (int*)(ws + L.famp);
   d.nw = (cfg->capacity + 31) / 32; d.cpad = (cfg->capacity + 7) / 8 * 8;
+  {
+    // shares of 256 entries that a row of average length needs
+    const long long avg = cfg->n_synapses / cfg->n_neurons;
+    const long long f = (avg + kBlock - 1) / kBlock;
+    d.fsplit = (int)(f < 1 ? 1 : (f > kFanSplitMax ? kFanSplitMax : f));
+  }
   d.occ = (int*)(ws + L.occ); d.head = (int*)(ws + L.head); d.c_head = (int*)(ws + L.c_head);
   d.pool_p = (long long*)(ws + L.pool_p); d.pool_t = (long long*)(ws + L.pool_t);
   d.pool_next = (int*)(ws + L.pool_next);
@@ -786,6 +798,7 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   d.cont = (uint4*)(ws + L.cont);
   d.pool_k = (unsigned*)(ws + L.pool_k); d.pool_a = (int*)(ws + L.pool_a);
   d.spk_words = (unsigned long long*)(ws + L.spk_words); d.stepcnt = (long long*)(ws + L.stepcnt);
+  d.busy_hint = (int*)(ws + L.busy_hint);
   d.packed = (unsigned*)(ws + L.packed); d.a_q = (int*)(ws + L.a_q);
   d.amp = (d.continuous && d.kind != ADSEQ_RING) ? (float*)(ws + L.amp) : nullptr;
   d.synf = (uint2*)(ws + L.synf); d.synb = (uint2*)(ws + L.synb);

@@ -24,9 +24,11 @@
 // FIFO: an unordered bag.  Per target: a bit mask of the occupied slots (one 32-bit word per 32
 // slots), the arrival steps as 16-bit keys (arrival mod 2^16: unambiguous because every stored
 // arrival lies within d_max <= 1023 steps of now) and the Q8.24 amplitudes.  A pop moves nothing:
-// the owner thread loads its 64 bytes of keys per mask word with full-width loads beside the rest
-// of its state, compares them with the current step, clears the bits of the due slots and loads
-// only their amplitudes; an admitted event goes to the first free bit.
+// the owner thread loads its 64 bytes of keys per mask word with full-width loads, compares them
+// with the current step, clears the bits of the due slots and loads only their amplitudes; an
+// admitted event goes to the first free bit.  The keys are loaded beside the rest of the thread's
+// state when the block's queues were busy in the step before (a hint word per block), and only
+// after the mask word has shown that the target holds something when they were mostly empty.
 // SORTED: the slots {arrival step, amplitude} are a circular array ordered by arrival step; pop
 // takes from the front (only targets whose front is due now load anything: the earliest stored
 // arrival is kept per target), an admitted event is inserted at its place (binary search, then
@@ -227,11 +229,11 @@ __device__ __forceinline__ long long wave_total64(long long v) {
 }
 
 // Block-level event counters in LDS: [0] offered, [1] admitted, [2] delivered, [3..5] the same as
-// sums of Q8.24 amplitudes, [6] spikes, [7] events emitted by them.
-struct BlockCounts { unsigned long long c[8]; };
+// sums of Q8.24 amplitudes, [6] spikes, [7] events emitted by them, [8] targets that hold an event.
+struct BlockCounts { unsigned long long c[9]; };
 
 __device__ __forceinline__ void counts_clear(BlockCounts& bc) {
-  if (threadIdx.x < 8) bc.c[threadIdx.x] = 0ull;
+  if (threadIdx.x < 9) bc.c[threadIdx.x] = 0ull;
   __syncthreads();
 }
 // Adds a wavefront's total to counter k (call it from one lane).
@@ -268,29 +270,29 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
   StepAcc r; r.acc = 0; r.popped = 0; r.c_adm = 0; r.s_adm = 0;
   if (blockIdx.x == 0 && threadIdx.x == 0) d.ctr->pool_n[0] = 0;   // the overflow pool is consumed by this launch
   counts_clear(s_cnt);
+  const int dense = d.busy_hint[blockIdx.x];   // the block's queues were busy in the step before
   float v = 0.0f;
   int len = 0;
+  bool holds = false;
   if (act) {
     // everything the thread needs first, loaded together
     const int K = d.cnt[g];
     QState q;
-    q.occ = d.occ[g];
     q.mn = KIND == ADSEQ_SORTED ? d.min_k[g] : 0u;
     q.hd = KIND == ADSEQ_SORTED ? d.head[g] : 0;
     q.m0 = KIND == ADSEQ_FIFO ? d.vmask[(size_t)g * d.nw] : 0u;
+    // FIFO with one mask word: the occupancy is the number of set bits
+    q.occ = (KIND == ADSEQ_FIFO && d.nw == 1) ? __popc(q.m0) : d.occ[g];
     uint4 kq[4];   // FIFO: the keys of the first 32 slots
-    if (KIND == ADSEQ_FIFO && MODE != 0) {
-      const uint4* kp = reinterpret_cast<const uint4*>(d.fkey + (size_t)g * d.cpad);
+    const uint4* kp0 = reinterpret_cast<const uint4*>(d.fkey + (size_t)g * d.cpad);
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        kq[c] = make_uint4(0u, 0u, 0u, 0u);
-        if (8 * c < d.cpad) kq[c] = kp[c];
-      }
+    for (int c = 0; c < 4; ++c) kq[c] = make_uint4(0u, 0u, 0u, 0u);
+    if (KIND == ADSEQ_FIFO && MODE != 0 && dense) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) if (8 * c < d.cpad) kq[c] = kp0[c];
     }
     if (MODE == 2) {
       v = d.V[g];
-      const int i = g % d.N;
-      len = (int)(d.row_ptr[i + 1] - d.row_ptr[i]);
     }
     const QState q0 = q;
     // second round of loads: the contender records (and, below, the amplitudes of the due events)
@@ -305,10 +307,15 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
       if (MODE != 0) {
         const unsigned kn16 = kn & 0xffffu;
         int ndue = 0;
+        if (!dense && q.m0) {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) if (8 * c < d.cpad) kq[c] = kp0[c];
+        }
         for (int w = 0; w < d.nw; ++w) {
           unsigned m = q.m0;
           if (w > 0) {
             m = d.vmask[(size_t)g * d.nw + w];
+            if (!m) continue;
             const uint4* kp = reinterpret_cast<const uint4*>(d.fkey + (size_t)g * d.cpad + 32 * w);
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -378,6 +385,7 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
         q.occ = occ; q.hd = hd; q.mn = occ > 0 ? front : 0xffffffffu;
       }
     }
+    holds = q.occ > 0;
     if (q.occ != q0.occ) d.occ[g] = q.occ;
     if (KIND == ADSEQ_SORTED && q.mn != q0.mn) d.min_k[g] = q.mn;
     if (KIND == ADSEQ_FIFO && q.m0 != q0.m0) d.vmask[(size_t)g * d.nw] = q.m0;
@@ -396,6 +404,7 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
       const float U = __fmaf_rn(d.alpha, v, I);
       s = U >= d.theta;
       d.V[g] = s ? d.v_reset : U;
+      if (s) len = d.rowlen[g % d.N];
       if (d.record && n < d.max_steps) {
         d.tapeU[(size_t)n * d.BN + g] = U;
         if (s) d.spk_count[g] += 1;
@@ -406,14 +415,19 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
     }
   }
   {
-    // wavefront totals (every lane is active here), one LDS atomic per wavefront and counter
-    const long long t_pop = wave_total(r.popped), t_acc = wave_total(r.acc);
-    const long long t_adm = wave_total(r.c_adm), t_sadm = wave_total64(r.s_adm);
-    const unsigned long long m = __ballot(s);
-    const long long t_ev = MODE == 2 ? wave_total(s ? len : 0) : 0;
+    // wavefront totals (every lane is active here), one LDS atomic per wavefront and counter;
+    // a wavefront that delivered and admitted nothing, or has no spike, skips the sums
+    long long t_pop = 0, t_acc = 0, t_adm = 0, t_sadm = 0, t_ev = 0;
+    if (__ballot(r.popped != 0 || r.c_adm != 0)) {
+      t_pop = wave_total(r.popped); t_acc = wave_total(r.acc);
+      t_adm = wave_total(r.c_adm); t_sadm = wave_total64(r.s_adm);
+    }
+    const unsigned long long m = __ballot(s), busy = __ballot(holds);
+    if (MODE == 2 && m) t_ev = wave_total(s ? len : 0);
     if ((threadIdx.x & 63) == 0) {
       counts_add(s_cnt, 2, t_pop); counts_add(s_cnt, 5, t_acc);
       counts_add(s_cnt, 1, t_adm); counts_add(s_cnt, 4, t_sadm);
+      counts_add(s_cnt, 8, __popcll(busy));
       if (MODE == 2) {
         // the spikes go to the fan-out launch as one ballot word per wavefront, plus the block's
         // spike and event counts (plain stores)
@@ -423,6 +437,7 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
     }
   }
   counts_flush(s_cnt, d.blk[blockIdx.x]);
+  if (threadIdx.x == 2) d.busy_hint[blockIdx.x] = s_cnt.c[8] >= kBlock / 8 ? 1 : 0;
   if (MODE == 2 && threadIdx.x < 2)
     d.stepcnt[((size_t)parity * d.nblk + blockIdx.x) * 2 + threadIdx.x] = (long long)s_cnt.c[6 + threadIdx.x];
 }
@@ -496,107 +511,109 @@ __device__ __forceinline__ void offer_rows(const Dev& d, long long n, const RowR
   }
 }
 
-// Closed-loop fan-out of step n: kFanSplit blocks per neuron block.  Block (nb, c) reads the four
-// ballot words that neuron block nb of this step's k_neurons launch left (most blocks find them
-// zero and leave) and offers share c -- entries c * 256 .. c * 256 + 255 of every
-// kFanSplit * 256 -- of the row of every spike in them, four spikes at a time.  A row is thus
-// spread over kFanSplit compute units (one unit sustains well under 10^9 scattered accesses per
+// Closed-loop fan-out of step n: fsplit blocks per neuron block.  Block (nb, c) reads the four
+// ballot words that neuron block nb of this step's k_neurons launch left (most find them zero
+// and leave) and offers share c -- entries c * 256 .. c * 256 + 255 of every fsplit * 256 -- of
+// the row of every spike in them, four spikes at a time.  A row is thus spread over fsplit compute
+// units (one unit sustains well under 10^9 scattered accesses per
 // second).  With `record`, the spikes and the index of each row's first admission flag go to the
 // tape; the positions come from prefix sums over the per-block counts of the step launch.
-constexpr int kFanSplit = 4;
+constexpr int kFanSplitMax = 4;   // d.fsplit = blocks per neuron block: a row of average length needs 1 .. 4 shares of 256
 template <int KIND>
 __global__ __launch_bounds__(kBlock) void k_fanout_step(Dev d, long long n, int parity, int record) {
   __shared__ long long s_red[2][kBlock / 64];
-  const int nb = blockIdx.x / kFanSplit, c = blockIdx.x - nb * kFanSplit;
+  const int nb = blockIdx.x / d.fsplit, c = blockIdx.x - nb * d.fsplit;
   const unsigned long long* __restrict__ wp = d.spk_words + (size_t)parity * d.words + (size_t)nb * (kBlock / 64);
   unsigned long long w[kBlock / 64];
   int nspk = 0;
 #pragma unroll
   for (int x = 0; x < kBlock / 64; ++x) { w[x] = wp[x]; nspk += __popcll(w[x]); }
-  const bool closer = record && blockIdx.x == 0;   // also writes where the next step's spikes start
+  const bool closer = record && blockIdx.x == 0;      // also writes where the next step's spikes start
   if (nspk == 0 && !closer) return;
-  long long pre_s = 0, pre_e = 0;
-  if (record) {
-    // spikes and events of the neuron blocks before nb (the closing block: of all blocks)
-    const long long off = d.step_off[n], evoff = d.step_evoff[n];
-    const long long* __restrict__ sc = d.stepcnt + (size_t)parity * d.nblk * 2;
-    long long ts = 0, te = 0, as = 0, ae = 0;
-    for (int j = threadIdx.x; j < d.nblk; j += kBlock) {
-      const long long cs = sc[2 * j], ce = sc[2 * j + 1];
-      as += cs; ae += ce;
-      if (j < nb) { ts += cs; te += ce; }
-    }
-    ts = wave_total64(ts); te = wave_total64(te);
-    if ((threadIdx.x & 63) == 0) { s_red[0][threadIdx.x >> 6] = ts; s_red[1][threadIdx.x >> 6] = te; }
-    __syncthreads();
-    for (int x = 0; x < kBlock / 64; ++x) { pre_s += s_red[0][x]; pre_e += s_red[1][x]; }
-    if (closer) {
-      __syncthreads();
-      as = wave_total64(as); ae = wave_total64(ae);
-      if ((threadIdx.x & 63) == 0) { s_red[0][threadIdx.x >> 6] = as; s_red[1][threadIdx.x >> 6] = ae; }
-      __syncthreads();
-      if (threadIdx.x == 0) {
-        long long all_s = 0, all_e = 0;
-        for (int x = 0; x < kBlock / 64; ++x) { all_s += s_red[0][x]; all_e += s_red[1][x]; }
-        if (n + 1 <= d.max_steps) { d.step_off[n + 1] = off + all_s; d.step_evoff[n + 1] = evoff + all_e; }
-        d.ctr->tape_spikes = off + all_s;
-        d.ctr->tape_events = evoff + all_e;
-      }
-      if (nspk == 0) return;
-    }
-    pre_s += off; pre_e += evoff;
-  }
   long long c_off = 0, s_off = 0;   // offered events and their amplitude sum (share 0, thread 0)
-  int x = 0;
-  unsigned long long bits = w[0];
-  for (int rank0 = 0; rank0 < nspk; rank0 += 4) {
-    RowRef rr[4];
-    const int nrows = nspk - rank0 < 4 ? nspk - rank0 : 4;
-    int gs[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      rr[j].b = 0; rr[j].r0 = 0; rr[j].r1 = 0; rr[j].tbase = -1; rr[j].first = (long long)c * kBlock; gs[j] = 0;
-      if (j < nrows) {
-        while (!bits) { ++x; bits = x == 1 ? w[1] : x == 2 ? w[2] : w[3]; }
-        const int bit = __ffsll((long long)bits) - 1;
-        bits &= bits - 1;
-        gs[j] = (nb * (kBlock / 64) + x) * 64 + bit;
+  {
+    long long pre_s = 0, pre_e = 0;
+    if (record) {
+      // spikes and events of the neuron blocks before nb (the closing block: of all blocks)
+      const long long off = d.step_off[n], evoff = d.step_evoff[n];
+      const long long* __restrict__ sc = d.stepcnt + (size_t)parity * d.nblk * 2;
+      long long ts = 0, te = 0, as = 0, ae = 0;
+      for (int j = threadIdx.x; j < d.nblk; j += kBlock) {
+        const long long cs = sc[2 * j], ce = sc[2 * j + 1];
+        as += cs; ae += ce;
+        if (j < nb) { ts += cs; te += ce; }
       }
-    }
-    long long rs[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      rs[j] = 0;
-      if (j < nrows) {
-        rr[j].b = gs[j] / d.N;
-        const int i = gs[j] - rr[j].b * d.N;
-        rr[j].r0 = d.row_ptr[i]; rr[j].r1 = d.row_ptr[i + 1];
-        if (c == 0 && threadIdx.x == 0) rs[j] = d.rowsum[i];
+      ts = wave_total64(ts); te = wave_total64(te);
+      if ((threadIdx.x & 63) == 0) { s_red[0][threadIdx.x >> 6] = ts; s_red[1][threadIdx.x >> 6] = te; }
+      __syncthreads();
+      for (int x = 0; x < kBlock / 64; ++x) { pre_s += s_red[0][x]; pre_e += s_red[1][x]; }
+      if (closer) {
+        __syncthreads();
+        as = wave_total64(as); ae = wave_total64(ae);
+        if ((threadIdx.x & 63) == 0) { s_red[0][threadIdx.x >> 6] = as; s_red[1][threadIdx.x >> 6] = ae; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+          long long all_s = 0, all_e = 0;
+          for (int x = 0; x < kBlock / 64; ++x) { all_s += s_red[0][x]; all_e += s_red[1][x]; }
+          if (n + 1 <= d.max_steps) { d.step_off[n + 1] = off + all_s; d.step_evoff[n + 1] = evoff + all_e; }
+          d.ctr->tape_spikes = off + all_s;
+          d.ctr->tape_events = evoff + all_e;
+        }
+        if (nspk == 0) return;
       }
+      pre_s += off; pre_e += evoff;
     }
+    int x = 0;
+    unsigned long long bits = w[0];
+    for (int rank0 = 0; rank0 < nspk; rank0 += 4) {
+      RowRef rr[4];
+      const int nrows = nspk - rank0 < 4 ? nspk - rank0 : 4;
+      int gs[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      if (j < nrows) {
-        const long long len = rr[j].r1 - rr[j].r0;
-        c_off += len; s_off += rs[j];
-        if (record) {
-          const bool fits = pre_s + rank0 + j < d.spike_cap;
-          long long evb = pre_e;
-          const bool ev_fits = evb + len <= d.event_cap;
-          if (!ev_fits) evb = -1;
-          if (c == 0 && threadIdx.x == 0) {
-            if (fits) { d.tape_spk[pre_s + rank0 + j] = gs[j]; d.tape_evb[pre_s + rank0 + j] = evb; }
-            else atomicOr(&d.ctr->err, ERR_TAPE_SPIKES);
-            if (!ev_fits) atomicOr(&d.ctr->err, ERR_TAPE_EVENTS);
-          }
-          rr[j].tbase = evb;
-          pre_e += len;
+      for (int j = 0; j < 4; ++j) {
+        rr[j].b = 0; rr[j].r0 = 0; rr[j].r1 = 0; rr[j].tbase = -1; rr[j].first = (long long)c * kBlock; gs[j] = 0;
+        if (j < nrows) {
+          while (!bits) { ++x; bits = x == 1 ? w[1] : x == 2 ? w[2] : w[3]; }
+          const int bit = __ffsll((long long)bits) - 1;
+          bits &= bits - 1;
+          gs[j] = (nb * (kBlock / 64) + x) * 64 + bit;
         }
       }
+      long long rs[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        rs[j] = 0;
+        if (j < nrows) {
+          rr[j].b = gs[j] / d.N;
+          const int i = gs[j] - rr[j].b * d.N;
+          rr[j].r0 = d.row_ptr[i]; rr[j].r1 = d.row_ptr[i + 1];
+          if (c == 0 && threadIdx.x == 0) rs[j] = d.rowsum[i];
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (j < nrows) {
+          const long long len = rr[j].r1 - rr[j].r0;
+          c_off += len; s_off += rs[j];
+          if (record) {
+            const bool fits = pre_s + rank0 + j < d.spike_cap;
+            long long evb = pre_e;
+            const bool ev_fits = evb + len <= d.event_cap;
+            if (!ev_fits) evb = -1;
+            if (c == 0 && threadIdx.x == 0) {
+              if (fits) { d.tape_spk[pre_s + rank0 + j] = gs[j]; d.tape_evb[pre_s + rank0 + j] = evb; }
+              else atomicOr(&d.ctr->err, ERR_TAPE_SPIKES);
+              if (!ev_fits) atomicOr(&d.ctr->err, ERR_TAPE_EVENTS);
+            }
+            rr[j].tbase = evb;
+            pre_e += len;
+          }
+        }
+      }
+      offer_rows(d, n, rr, nrows, (long long)d.fsplit * kBlock);
     }
-    offer_rows(d, n, rr, nrows, (long long)kFanSplit * kBlock);
   }
-  if (c == 0 && threadIdx.x == 0) {
+  if (c == 0 && threadIdx.x == 0 && c_off) {
     BlkCtr& bc = d.blk[d.nblk + blockIdx.x];   // private to this block
     bc.offered += (unsigned long long)c_off; bc.sum_offered += s_off;
   }
@@ -627,7 +644,8 @@ __global__ __launch_bounds__(kBlock) void k_fanout_list(Dev d, long long n, cons
   }
 }
 
-// Q8.24 amplitude sum of every row (for the offered-event counters): one wavefront per row.
+// Q8.24 amplitude sum (for the offered-event counters) and length of every row: one wavefront
+// per row.
 __global__ __launch_bounds__(kBlock) void k_row_sums(Dev d) {
   const int lane = threadIdx.x & 63;
   const long long wave = ((long long)blockIdx.x * kBlock + threadIdx.x) >> 6;
@@ -636,6 +654,6 @@ __global__ __launch_bounds__(kBlock) void k_row_sums(Dev d) {
     long long sum = 0;
     for (long long p = d.row_ptr[i] + lane; p < d.row_ptr[i + 1]; p += 64) sum += d.a_q[p];
     sum = wave_sum(sum);
-    if (lane == 0) d.rowsum[i] = sum;
+    if (lane == 0) { d.rowsum[i] = sum; d.rowlen[i] = (int)(d.row_ptr[i + 1] - d.row_ptr[i]); }
   }
 }
