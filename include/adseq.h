@@ -35,8 +35,11 @@
  *   D_p = max(1, ceil(delay_ms[p] / dt)), a_p = weight[p] * exp(-(D_p dt - delay_ms[p]) / tau_m).
  *
  * Queue kinds (Section 4.3)
- *   ADSEQ_RING    dense delay line [d_max_steps + 1][batch * n_neurons]; events
- *                 are summed into slot (n + D) mod depth; lossless ("Ring").
+ *   ADSEQ_RING    dense delay line: one summed cell per (arrival step, target) for
+ *                 the arrival steps of the current window of 16 steps, plus the
+ *                 spikes of the last d_max_steps + 1 steps as bit masks, from
+ *                 which the cells of the next window are filled when it opens;
+ *                 lossless ("Ring").
  *   ADSEQ_FIFO    per target, `capacity` unordered slots; an incoming event is
  *                 dropped (and counted) when the target already holds `capacity`
  *                 undelivered events ("FIFORing": drops the incoming spikes when
@@ -87,7 +90,7 @@ typedef struct {
   float dt_ms, tau_m_ms, v_thresh, v_reset; /* LIF; requires 0 < dt_ms <= tau_m_ms            */
   float ext_rate_hz, ext_weight;            /* Poisson drive, 0 rate = none                   */
   uint64_t seed;                            /* of the drive's counter-based generator         */
-  int64_t n_synapses;                       /* S = row_ptr[N]                                 */
+  int64_t n_synapses;                       /* S = row_ptr[N], below 2^40                     */
   const int64_t *row_ptr;     /* [N+1] CSR by source neuron                                   */
   const int32_t *col;         /* [S] target neuron                                            */
   const float *weight;        /* [S] finite fp32; |amplitude| saturates at 128                */
@@ -99,8 +102,11 @@ typedef struct {
   int64_t tape_event_capacity; /* FIFO/SORTED with tape: emitted events it can hold (one
                                   admission flag each); 0 = default
                                   (tape_spike_capacity * ceil(S / N))                         */
-  int64_t step_event_capacity; /* FIFO/SORTED: events per step that may contend for free
-                                  slots; 0 = default min(B * S, 2^24)                         */
+  int64_t step_event_capacity; /* FIFO/SORTED: events per step that may wait in the overflow
+                                  list of their target (more than 8 contenders for one target
+                                  in one step); 0 = default min(B * S, 2^24).  RING: events
+                                  the staging buffer of a window holds (the rest takes a slower
+                                  route, same result); 0 = default                            */
   void *workspace;             /* device memory, 256-byte aligned                             */
   size_t workspace_bytes;      /* >= adseq_workspace_bytes(cfg)                               */
   void *stream;                /* stream for the preparation kernels of adseq_create          */
@@ -132,6 +138,16 @@ int adseq_deliver(adseq_t *h, int64_t step, float *I_out, void *stream);
  * admitted together, in canonical order. */
 int adseq_enqueue(adseq_t *h, int64_t step, const int32_t *spike_ids, const int32_t *n_spikes,
                   void *stream);
+
+/* n_steps open-loop steps from `step0`: for k = 0 .. n_steps-1, adseq_deliver(step0 + k) into
+ * I_out + k * I_stride (fp32 [B*N] each; I_stride = 0 overwrites one buffer), then
+ * adseq_enqueue(step0 + k) of the spikes spike_ids[spike_offsets[k] .. + n_spikes[k]).  spike_ids
+ * and n_spikes [n_steps] are DEVICE pointers, spike_offsets [n_steps] is a HOST array.  The shape
+ * of the paper's Poisson benchmark (Section 5.1: externally generated spike trains through the
+ * queues).  Stops at the first error. */
+int adseq_run_open(adseq_t *h, int64_t step0, int64_t n_steps, const int32_t *spike_ids,
+                   const int64_t *spike_offsets /*host*/, const int32_t *n_spikes, float *I_out,
+                   int64_t I_stride, void *stream);
 
 /* One closed-loop step (pop, drive, LIF, compaction, fan-out, enqueue; see the header comment).
  * i_ext: optional extra input current fp32 [B*N] or NULL.  spikes_out: optional 0/1 bytes

@@ -23,7 +23,7 @@ ERRORS = {0: "OK", -1: "INVALID_ARG", -2: "DELAY_RANGE", -3: "WORKSPACE", -4: "O
           -5: "NO_TAPE", -6: "HIP", -7: "CAPACITY", -8: "GRAPH"}
 
 EXPORTS = ["adseq_workspace_bytes", "adseq_create", "adseq_destroy", "adseq_reset", "adseq_deliver",
-           "adseq_enqueue", "adseq_step", "adseq_run", "adseq_backward", "adseq_drop_count",
+           "adseq_enqueue", "adseq_run_open", "adseq_step", "adseq_run", "adseq_backward", "adseq_drop_count",
            "adseq_counters", "adseq_tape", "adseq_spike_counts", "adseq_profile", "adseq_profile_read", "adseq_last_error"]
 
 
@@ -74,6 +74,7 @@ def load():
         L.adseq_deliver.argtypes = [vp, i64, vp, vp]
         L.adseq_enqueue.argtypes = [vp, i64, vp, vp, vp]
         L.adseq_step.argtypes = [vp, i64, vp, vp, vp]
+        L.adseq_run_open.argtypes = [vp, i64, i64, vp, vp, vp, vp, i64, vp]
         L.adseq_run.argtypes = [vp, i64, i64, vp]
         L.adseq_backward.argtypes = [vp, vp, vp, vp, vp, vp]
         L.adseq_drop_count.argtypes = [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64),
@@ -165,6 +166,13 @@ class Adseq:
 
     def enqueue(self, n: int, spike_ids: torch.Tensor, n_spikes: torch.Tensor):
         self._check(self.lib.adseq_enqueue(self.h, n, _dptr(spike_ids), _dptr(n_spikes), _stream()))
+
+    def run_open(self, step0: int, n_steps: int, spike_ids: torch.Tensor, spike_offsets: np.ndarray,
+                 n_spikes: torch.Tensor, I_out: torch.Tensor, I_stride: int):
+        """n_steps x (deliver, enqueue); spike_offsets is a host int64 array [n_steps]."""
+        offs = np.ascontiguousarray(spike_offsets, dtype=np.int64)
+        self._check(self.lib.adseq_run_open(self.h, step0, n_steps, _dptr(spike_ids), offs.ctypes.data,
+                                            _dptr(n_spikes), _dptr(I_out), I_stride, _stream()))
 
     def backward(self, dL_dcount: Optional[torch.Tensor], dL_dU: Optional[torch.Tensor],
                  grad_w: torch.Tensor, grad_d: torch.Tensor):

@@ -902,6 +902,19 @@ int adseq_enqueue(adseq_t* h, int64_t step, const int32_t* spike_ids, const int3
   return ADSEQ_OK;
 }
 
+int adseq_run_open(adseq_t* h, int64_t step0, int64_t n_steps, const int32_t* spike_ids,
+                   const int64_t* spike_offsets, const int32_t* n_spikes, float* I_out, int64_t I_stride,
+                   void* stream) {
+  if (!h || !spike_ids || !spike_offsets || !n_spikes || !I_out || n_steps < 0 || I_stride < 0)
+    return h ? fail(h, ADSEQ_E_INVALID_ARG, "adseq_run_open: null or negative argument") : ADSEQ_E_INVALID_ARG;
+  for (int64_t k = 0; k < n_steps; ++k) {
+    int rc = adseq_deliver(h, step0 + k, I_out + k * I_stride, stream);
+    if (rc == ADSEQ_OK) rc = adseq_enqueue(h, step0 + k, spike_ids + spike_offsets[k], n_spikes + k, stream);
+    if (rc != ADSEQ_OK) return rc;
+  }
+  return ADSEQ_OK;
+}
+
 int adseq_step(adseq_t* h, int64_t step, const float* i_ext, uint8_t* spikes_out, void* stream) {
   if (!h) return ADSEQ_E_INVALID_ARG;
   return step_impl(h, step, i_ext, spikes_out, (hipStream_t)stream);

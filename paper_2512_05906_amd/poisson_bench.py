@@ -1,0 +1,92 @@
+#!/usr/bin/env python3
+"""Open-loop Poisson benchmark and drop-rate sweep on one MI355X.
+
+The workload has the shape of the paper's Poisson benchmark (Section 5.1): many independent
+queues, each fed by its own Poisson source (mean interval lambda = 400 steps) through one
+homogeneous delay (80 steps, dt = 0.025 ms); per time step the queue is popped
+(adseq_deliver) and the step's spikes are enqueued (adseq_enqueue).  The spike lists are
+drawn beforehand (seeded) and are resident on the GPU when the timed region starts.
+
+Prints one JSON line per (queue kind, capacity, pressure): time per time step, delivered
+events/s, drop rate, and the Erlang-B blocking probability of a loss system with `capacity`
+servers and offered load a = delay / lambda (a bounded bag with on-time delivery is one: the
+holding time of a slot is the delay, and the loss formula does not depend on the holding-time
+distribution).  The paper's own rule of thumb (Section 5.4: pressure delay / lambda around 0.5
+needs only a very small queue) is the a << capacity corner of this table.
+"""
+import argparse
+import json
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def erlang_b(servers: int, load: float) -> float:
+    """Blocking probability B(c, a) by the standard recurrence B(0) = 1, B(k) = a B(k-1) / (k + a B(k-1))."""
+    b = 1.0
+    for k in range(1, servers + 1):
+        b = load * b / (k + load * b)
+    return b
+
+
+def run_case(torch, adseq, synth, kind_name, cap, n_queues, delay, interval, T, repeats=3):
+    import numpy as np
+    kind = {"ring": adseq.RING, "fifo": adseq.FIFO, "sorted": adseq.SORTED}[kind_name]
+    wl = synth.poisson_queues(n_queues, delay, n_steps=T)
+    rate_hz = 1.0 / (interval * wl.dt_ms * 1e-3)
+    lists = synth.poisson_spike_lists(n_queues, 1, T, rate_hz, wl.dt_ms, seed=11)
+    counts = np.array([len(x) for x in lists], np.int32)
+    offs = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
+    sim = adseq.Adseq(wl, kind, cap if kind != adseq.RING else 0)
+    dev = sim.dev
+    ids = torch.from_numpy(np.concatenate(lists + [np.zeros(1, np.int32)])).to(dev)
+    cnt = torch.from_numpy(counts).to(dev)
+    I = torch.empty(n_queues, dtype=torch.float32, device=dev)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    times = []
+    for _ in range(repeats + 1):
+        sim.reset()
+        ev[0].record()
+        sim.run_open(0, T, ids, offs[:T], cnt, I, 0)
+        ev[1].record()
+        torch.cuda.synchronize()
+        times.append(ev[0].elapsed_time(ev[1]))
+    ms = float(np.median(times[1:]))
+    c = sim.counters()
+    sim.close()
+    a = delay / interval
+    return {"queue": kind_name, "capacity": cap if kind != adseq.RING else None, "n_queues": n_queues,
+            "delay_steps": delay, "mean_interval_steps": interval, "pressure": a, "time_steps": T,
+            "us_per_time_step": ms * 1e3 / T, "ns_per_time_step_per_queue": ms * 1e6 / T / n_queues,
+            "delivered_events_per_s": c["delivered"] / (ms * 1e-3),
+            "offered": c["enqueued"], "dropped": c["dropped"],
+            "drop_rate": c["dropped"] / max(1, c["enqueued"]),
+            "erlang_b": None if kind == adseq.RING else erlang_b(cap, a)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--queues", type=int, default=10000)
+    ap.add_argument("--time-steps", type=int, default=4000)
+    ap.add_argument("--delay", type=int, default=80)
+    ap.add_argument("--sweep", action="store_true", help="capacity x pressure sweep of the drop rate")
+    args = ap.parse_args()
+    import torch
+    from paper_2512_05906_amd import adseq, synth
+    if not torch.cuda.is_available():
+        print("poisson_bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    cases = [("ring", 0, 400), ("fifo", 4, 400), ("sorted", 4, 400)]
+    if args.sweep:
+        cases = [(k, c, lam) for lam in (400, 160, 80, 40, 20) for k, c in
+                 (("fifo", 1), ("fifo", 2), ("fifo", 4), ("fifo", 8), ("sorted", 4))]
+    for kind, cap, lam in cases:
+        print(json.dumps(run_case(torch, adseq, synth, kind, cap, args.queues, args.delay, lam,
+                                  args.time_steps)), flush=True)
+
+
+if __name__ == "__main__":
+    main()

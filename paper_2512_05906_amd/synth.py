@@ -145,6 +145,19 @@ def ragged_network(n: int, max_fan: int, d_max: int, *, seed: int,
     return wl
 
 
+def poisson_queues(n_queues: int, delay_steps: int, *, n_steps: int = 4000, batch: int = 1,
+                   dt_ms: float = 0.025, seed: int = 7) -> Workload:
+    """The shape of the paper's Poisson benchmark (Section 5.1): `n_queues` independent
+    queues, each fed by one source of its own with one homogeneous delay.  Source i has the
+    single synapse i -> i with weight 1; the spikes come from outside (open loop)."""
+    n = n_queues
+    return Workload(name="poisson_queues", n_neurons=n, fan_out=1, n_steps=n_steps, batch=batch,
+                    d_max_steps=delay_steps, dt_ms=dt_ms, ext_rate_hz=0.0, seed=seed,
+                    row_ptr=np.arange(n + 1, dtype=np.int64), col=np.arange(n, dtype=np.int32),
+                    weight=np.ones(n, np.float32),
+                    delay_steps=np.full(n, delay_steps, np.uint8))
+
+
 def spike_count_targets(wl: Workload, seed_offset: int = 77) -> np.ndarray:
     """Seeded per-(trial, neuron) spike-count targets ~ U(0, 5), float32 [B, N]."""
     rng = np.random.default_rng(wl.seed + seed_offset)

@@ -1,0 +1,50 @@
+"""Open-loop queues fed by Poisson sources (the shape of the paper's Poisson benchmark,
+Section 5.1: independent queues, one source each, one homogeneous delay): HIP path vs oracle
+bit for bit, and the drop rate against the Erlang-B blocking probability."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import brute, oracle
+from paper_2512_05906_amd import adseq, synth
+
+pytestmark = pytest.mark.gpu
+
+KINDS = {"ring": oracle.RING, "fifo": oracle.FIFO, "sorted": oracle.SORTED}
+
+
+@pytest.mark.parametrize("kind,cap,interval", [("ring", 0, 400), ("fifo", 1, 400), ("fifo", 2, 80),
+                                               ("fifo", 4, 40), ("sorted", 4, 40), ("fifo", 40, 40)])
+def test_poisson_queues_open_loop(kind, cap, interval):
+    N, T, delay = 1500, 3000, 80          # 1,500 queues: several blocks and a ragged tail
+    wl = synth.poisson_queues(N, delay, n_steps=T)
+    rate_hz = 1.0 / (interval * wl.dt_ms * 1e-3)
+    lists = synth.poisson_spike_lists(N, 1, T, rate_hz, wl.dt_ms, seed=5)
+    forced = np.zeros((T, N), np.uint8)
+    for n, ids in enumerate(lists):
+        forced[n, ids] = 1
+    ref = oracle.Run(wl, KINDS[kind], cap, n_steps=T, forced_spikes=forced.reshape(T, 1, N), keep_currents=True)
+    sim = adseq.Adseq(wl, KINDS[kind], cap)
+    I = torch.zeros((T, N), dtype=torch.float32, device=sim.dev)
+    counts = torch.tensor([len(x) for x in lists], dtype=torch.int32, device=sim.dev)
+    offs = np.concatenate([[0], np.cumsum([len(x) for x in lists])])
+    ids = torch.from_numpy(np.concatenate(lists + [np.zeros(1, np.int32)])).to(sim.dev)
+    half = T // 2      # first half step by step, second half through the batched entry point
+    for n in range(half):
+        sim.deliver(n, I[n])
+        sim.enqueue(n, ids[int(offs[n]):], counts[n:])
+    sim.run_open(half, T - half, ids, offs[half:T], counts[half:], I[half:], N)
+    torch.cuda.synchronize()
+    want = ref.Iq.reshape(T, N).astype(np.float32) * np.float32(2.0 ** -24)
+    np.testing.assert_array_equal(I.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    c, rc = sim.counters(), ref.counters()
+    for key in ("enqueued", "dropped", "delivered", "sum_enqueued", "sum_dropped", "sum_delivered"):
+        assert c[key] == rc[key], key
+    sim.close()
+    if kind == "ring" or cap >= 40:
+        assert rc["dropped"] == 0
+    else:
+        # loss system with `cap` servers, offered load = delay / mean interval
+        want_b = brute.erlang_b(cap, delay / interval)
+        got = rc["dropped"] / rc["enqueued"]
+        assert abs(got - want_b) < 0.1 * want_b + 0.01, (got, want_b)
