@@ -63,7 +63,17 @@ extern "C" {
 typedef struct adseq adseq_t; /* opaque; host memory owned by the library, freed by adseq_destroy */
 
 enum { ADSEQ_RING = 0, ADSEQ_FIFO = 1, ADSEQ_SORTED = 2 };
-enum { ADSEQ_SURR_SUPERSPIKE = 0, ADSEQ_SURR_OFF = 1 };
+/* How a spike passes gradients back (config field `surrogate`):
+ *   ADSEQ_SURR_SUPERSPIKE  the spike function has the SuperSpike derivative 1/(|U - theta| + 1)^2 (eq. 7);
+ *   ADSEQ_SURR_OFF         it has derivative 0 (only the direct dependence of amplitudes on weights
+ *                          and delays remains);
+ *   ADSEQ_GRAD_SPIKE_TIME  no surrogate: the emission time of a spike depends on the membrane value
+ *                          v its step started from, dt_spk/dv = -1 / vdot (Section 3.1 eq. 8), vdot =
+ *                          (U - v) / dt from the first forward difference, 1 where that is 0 (the
+ *                          spike-detection rule of Section 4.1), and every event of the spike hands
+ *                          (amplitude / tau_m) dt_post to its receiver (eq. 17), dt_post/dt_spk = 1
+ *                          (eq. 13).  dL_dcount is ignored in this mode. */
+enum { ADSEQ_SURR_SUPERSPIKE = 0, ADSEQ_SURR_OFF = 1, ADSEQ_GRAD_SPIKE_TIME = 2 };
 
 enum {
   ADSEQ_OK = 0,
@@ -84,7 +94,7 @@ typedef struct {
   int32_t d_max_steps;  /* largest arrival offset in steps, 1..1023                           */
   int32_t capacity;     /* slots per target for FIFO / SORTED (1..32767); ignored for RING    */
   int32_t kind;         /* ADSEQ_RING / ADSEQ_FIFO / ADSEQ_SORTED                             */
-  int32_t surrogate;    /* ADSEQ_SURR_SUPERSPIKE: 1/(|U-theta|+1)^2 (eq. 7); ADSEQ_SURR_OFF: 0 */
+  int32_t surrogate;    /* ADSEQ_SURR_SUPERSPIKE / ADSEQ_SURR_OFF / ADSEQ_GRAD_SPIKE_TIME      */
   int32_t record_tape;  /* 1 = adseq_step keeps what adseq_backward needs                     */
   int32_t max_steps;    /* tape length in steps (needed when record_tape = 1)                 */
   float dt_ms, tau_m_ms, v_thresh, v_reset; /* LIF; requires 0 < dt_ms <= tau_m_ms            */
@@ -163,7 +173,9 @@ int adseq_run(adseq_t *h, int64_t step0, int64_t n_steps, void *stream);
  * that, eq. 17; the spike function's derivative is the surrogate of eq. 7, applied only where a
  * spike was emitted for the queue term).  With gU[T] = 0, for n = T-1 .. 0:
  *   G_i   = sum over admitted events p of row i emitted at n with n + D_p < T of a_p * gU[col_p][n + D_p]
- *   gU_i[n] = (1 - s_i[n]) * alpha * gU_i[n+1] + sigma'(U_i[n] - theta) * (dL_dcount_i + s_i[n] * G_i) + dL_dU_i[n]
+ *   gU_i[n] = (1 - s_i[n]) * c_i[n+1] + sigma'(U_i[n] - theta) * (dL_dcount_i + s_i[n] * G_i) + dL_dU_i[n]
+ *   c_i[n]  = alpha * gU_i[n] + E_i[n],  E_i[n] = -(1 / vdot_i[n]) (1 / tau_m) s_i[n] G_i in the spike-time
+ *             mode (sigma' = 0 there), 0 otherwise
  *   grad_w[p] += f_p * gU[col_p][n + D_p],   grad_d[p] += (a_p / tau_m) * unit * gU[col_p][n + D_p]
  * (f_p = a_p / weight_p; unit = 1 per ms for delay_ms, dt per step for delay_steps), summed over
  * trials.  dL_dcount: fp32 [B*N] or NULL; dL_dU: fp32 [T][B*N] or NULL; grad_w, grad_d: fp32 [S],

@@ -18,7 +18,11 @@
 //     derivative 1/(|x|+1)^2 (Section 2.2.1, eqs. 5-7);
 //   * the delay gradient enters through d t_post / d d = 1 (eq. 13) and the
 //     receive rule  dx+/dtheta = dx-/dtheta + (1/tau) dt_post/dtheta (eq. 17),
-//     here scaled by the jump amplitude a because the jump is a, not 1.
+//     here scaled by the jump amplitude a because the jump is a, not 1;
+//   * spike-time mode (no surrogate): the emission time of a spike depends on
+//     the membrane value the step started from, dt_spk/dv = -1/vdot (Section 3.1
+//     eq. 8), vdot from the first forward difference, 1 where that is 0 (the
+//     spike-detection rule of Section 4.1).
 //
 // Readings of points the paper leaves open (all restated in the design notes):
 //   step order      pop(n) -> drive -> LIF -> enqueue(arrival n + D), D >= 1
@@ -39,7 +43,8 @@
 // D==1 sparse mat-vec, exactly-once delivery and weight conservation, closed-form
 // LIF charge curve, one-synapse closed-form delay gradient, central finite
 // differences on a frozen raster, forward-mode tangent vs reverse-mode
-// dot-product identity, bounded-bag replay, FIFO(1) == hold-one-spike.
+// dot-product identity (surrogate and spike-time modes), closed-form spike-time
+// gradient along a three-neuron chain, bounded-bag replay, FIFO(1) == hold-one-spike.
 // Unpinned: nothing in the forward pass; the surrogate-through-spike-count
 // gradient is pinned only by the dot-product identity (a surrogate is not the
 // derivative of anything finite differences can see).
@@ -58,7 +63,7 @@ struct oracle_config {
   int32_t n_neurons, batch, d_max_steps, capacity;
   int32_t kind;        // 0 ring (lossless), 1 fifo (bounded), 2 sorted (bounded)
   int32_t n_steps;
-  int32_t surrogate;   // 0 SuperSpike, 1 off (sigma' == 0)
+  int32_t surrogate;   // 0 SuperSpike, 1 off (sigma' == 0), 2 spike-time gradient (no surrogate)
   int32_t exact_f64;   // 0: fp32 state + Q8.24 sums (the method), 1: fp64, no quantisation
   float dt_ms, tau_m_ms, v_thresh, v_reset, ext_rate_hz, ext_weight;
   uint64_t seed;
@@ -290,10 +295,14 @@ void backward_trial(const oracle_run& r, int b, const float* dL_dcount, const fl
   const double d_unit = c.delay_ms ? 1.0 : (double)c.dt_ms;
   // dU[n+1]/dV[n]: the leak factor the forward pass actually multiplied by
   const double alpha = exact ? r.alpha_d : (double)r.alpha_f;
-  // gU[n][i] = dL/dU_i[n], with gU[T] == 0
+  // gU[n][i] = dL/dU_i[n], with gU[T] == 0.  carry[i] = dL/dV_i[n] = what reaches the membrane
+  // state that step n left behind: alpha gU[n+1], plus, in the spike-time mode, the cotangent
+  // that the emission time of a spike at n+1 hands to the state it started from.
   std::vector<double> gU((size_t)(T + 1) * N, 0.0);
+  std::vector<double> carry(N, 0.0);
   int64_t sp = (int64_t)tr.spikes.size() - 1;  // spikes are stored in emission order
   std::vector<double> G(N);
+  const bool spike_time = c.surrogate == 2;
   for (int n = T - 1; n >= 0; --n) {
     const size_t base = ((size_t)n * B + b) * N;
     std::fill(G.begin(), G.end(), 0.0);
@@ -323,8 +332,24 @@ void backward_trial(const oracle_run& r, int b, const float* dL_dcount, const fl
       const double sg = c.surrogate == 0 ? 1.0 / ((std::fabs(x) + 1.0) * (std::fabs(x) + 1.0)) : 0.0;
       const double direct = dL_dU ? (double)dL_dU[base + i] : 0.0;
       const double dc = dL_dcount ? (double)dL_dcount[(size_t)b * N + i] : 0.0;
-      gU[(size_t)n * N + i] = (1.0 - s) * alpha * gU[(size_t)(n + 1) * N + i]
-                              + sg * (dc + s * G[i]) + direct;
+      const double g_now = (1.0 - s) * carry[i] + sg * (dc + s * G[i]) + direct;
+      gU[(size_t)n * N + i] = g_now;
+      // Spike-time mode: the spike's emission time depends on the membrane value v the step
+      // started from, dt_spk/dv = -1 / vdot with vdot = (U - v) / dt from the first forward
+      // difference (1 where that is 0), and every event of the spike hands (jump / tau) dt_post
+      // to its receiver, dt_post/dt_spk = 1: the state before the step gets -(1/vdot)(1/tau) G.
+      double e = 0.0;
+      if (spike_time && s != 0.0) {
+        double vprev = 0.0;   // V starts at 0
+        if (n > 0) {
+          const size_t pb = ((size_t)(n - 1) * B + b) * N + i;
+          vprev = r.S[pb] ? (double)c.v_reset : (exact ? r.U64[pb] : (double)r.U[pb]);
+        }
+        double vdot = (u - vprev) / (double)c.dt_ms;
+        if (vdot == 0.0) vdot = 1.0;
+        e = -(1.0 / vdot) * (1.0 / tau) * G[i];
+      }
+      carry[i] = alpha * g_now + e;
     }
   }
   if (gU_out)

@@ -17,6 +17,7 @@ _SRC = os.path.join(_HERE, "adseq_oracle.cpp")
 _LIB = os.path.join(_HERE, "liboracle.so")
 
 RING, FIFO, SORTED = 0, 1, 2
+SURR_SUPERSPIKE, SURR_OFF, GRAD_SPIKE_TIME = 0, 1, 2
 
 
 def build(force: bool = False) -> str:

@@ -12,14 +12,19 @@ paper's own JVP -> VJP check, Section 4.4):
   * the tangent queue stores one float per event in transit (Section 4.2);
   * the spike function's tangent is the SuperSpike surrogate times the
     membrane tangent (eq. 7), and only an emitted spike has a queue entry to
-    carry it (event-sparse reading).
+    carry it (event-sparse reading);
+  * spike-time mode (no surrogate): the emission time of a spike has the tangent
+    t_spk' = -v' / vdot, with v the membrane value the step started from and vdot the
+    first forward difference (U - v) / dt, 1 where that is 0 (Section 3.1 eq. 8 and the
+    spike-detection rule of Section 4.1); the event then carries t_post' = t_spk' + d'.
 """
 from __future__ import annotations
 
 import numpy as np
 
 
-def jvp(U, S, events, col, src, a, f, alpha, theta, tau, d_unit, w_t, d_t, surrogate=True):
+def jvp(U, S, events, col, src, a, f, alpha, theta, tau, d_unit, w_t, d_t, surrogate=True,
+        spike_time=False, dt=None, v_reset=0.0):
     """Tangents of (U [T,N], spike counts [N]) for one trial.
 
     U, S        recorded membrane values / spikes [T, N]
@@ -36,15 +41,26 @@ def jvp(U, S, events, col, src, a, f, alpha, theta, tau, d_unit, w_t, d_t, surro
             by_arrival[k].append((int(p), int(n)))
     x = U.astype(np.float64) - theta
     sg = 1.0 / (np.abs(x) + 1.0) ** 2 if surrogate else np.zeros_like(x)
+    if spike_time:
+        sg = np.zeros_like(x)
     U_t = np.zeros((T, N))
     s_t = np.zeros((T, N))
+    tspk_t = np.zeros((T, N))      # tangent of the emission time (ms) of the spike at (n, i)
     V_t = np.zeros(N)
+    V = np.zeros(N)                # membrane value each step starts from
     for n in range(T):
         I_t = np.zeros(N)
         for p, n_emit in by_arrival[n]:
             # amplitude tangent (weight and delay) + amplitude * tangent of the emitting spike
             I_t[col[p]] += f[p] * w_t[p] + (a[p] / tau) * d_unit * d_t[p] + a[p] * s_t[n_emit, src[p]]
+            if spike_time:
+                I_t[col[p]] += (a[p] / tau) * tspk_t[n_emit, src[p]]
+        if spike_time:
+            vdot = (U[n].astype(np.float64) - V) / dt
+            vdot = np.where(vdot == 0.0, 1.0, vdot)
+            tspk_t[n] = np.where(S[n] != 0, -V_t / vdot, 0.0)
         U_t[n] = alpha * V_t + I_t
         s_t[n] = sg[n] * U_t[n]
         V_t = (1.0 - S[n]) * U_t[n]
+        V = np.where(S[n] != 0, v_reset, U[n].astype(np.float64))
     return U_t, s_t.sum(axis=0)

@@ -296,26 +296,18 @@ __global__ __launch_bounds__(kBlock) void k_bwd_gather(Dev d, long long n, long 
   }
 }
 
-// Neuron part of the reverse sweep at step n:
-//   gU[n] = (1 - s) alpha gU[n+1] + sigma'(U - theta) (dL/dcount + s G) + dL/dU[n]
+// Neuron part of the reverse sweep at step n for the bounded kinds (see bwd_update).
 __global__ __launch_bounds__(kBlock) void k_bwd_neurons(Dev d, long long n,
                                                         const float* __restrict__ dL_dcount,
                                                         const float* __restrict__ dL_dU) {
   const int g = blockIdx.x * kBlock + threadIdx.x;
   if (g >= d.BN) return;
   const float U = d.tapeU[(size_t)n * d.BN + g];
+  const float Uprev = (d.surrogate == ADSEQ_GRAD_SPIKE_TIME && n > 0) ? d.tapeU[(size_t)(n - 1) * d.BN + g] : 0.0f;
   const bool s = U >= d.theta;
-  float sg = 0.0f;
-  if (d.surrogate == ADSEQ_SURR_SUPERSPIKE) {
-    const float x = fabsf(U - d.theta) + 1.0f;
-    sg = 1.0f / (x * x);
-  }
-  float inner = dL_dcount ? dL_dcount[g] : 0.0f;
-  if (s) inner += d.bwd_G[g];
-  float gu = sg * inner;
-  if (!s) gu = __fmaf_rn(d.alpha, d.bwd_carry[g], gu);
-  if (dL_dU) gu += dL_dU[(size_t)n * d.BN + g];
-  d.bwd_carry[g] = gu;
+  float gu;
+  d.bwd_carry[g] = bwd_update(d, n, U, Uprev, s, d.bwd_carry[g], dL_dcount ? dL_dcount[g] : 0.0f,
+                              s ? d.bwd_G[g] : 0.0f, dL_dU ? dL_dU[(size_t)n * d.BN + g] : 0.0f, &gu);
   d.bwd_ring[(size_t)(n % d.R) * d.BN + g] = gu;
 }
 
@@ -384,7 +376,8 @@ bool host_validate(const adseq_config* c) {
   if ((long long)c->n_neurons * c->batch > 0x7fffffffLL) return false;
   if (c->kind != ADSEQ_RING && c->kind != ADSEQ_FIFO && c->kind != ADSEQ_SORTED) return false;
   if (c->kind != ADSEQ_RING && (c->capacity < 1 || c->capacity > 32767)) return false;
-  if (c->surrogate != ADSEQ_SURR_SUPERSPIKE && c->surrogate != ADSEQ_SURR_OFF) return false;
+  if (c->surrogate != ADSEQ_SURR_SUPERSPIKE && c->surrogate != ADSEQ_SURR_OFF &&
+      c->surrogate != ADSEQ_GRAD_SPIKE_TIME) return false;
   if (!(c->dt_ms > 0.0f) || !(c->tau_m_ms > 0.0f) || c->dt_ms > c->tau_m_ms) return false;
   if (!(c->ext_rate_hz >= 0.0f)) return false;
   if (c->n_synapses < 0 || c->n_synapses >= (1LL << 40)) return false;   // synapse indices are packed into 40 bits

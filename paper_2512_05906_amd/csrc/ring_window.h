@@ -595,6 +595,38 @@ __global__ __launch_bounds__(kBlock) void k_ring_in_flight(Dev d, long long n_en
 
 // ---------------------------------------------------------------- reverse sweep
 
+// Neuron part of a reverse step (all queue kinds).  U: recorded membrane value of step n, Uprev:
+// that of step n - 1 (spike-time mode only), s: spike at n, carry: what step n + 1 handed back to
+// the membrane state (alpha gU[n+1] + E[n+1]), dcount: dL/dcount, G: queue term, dU: dL/dU[n].
+// Writes gU[n] to *gu_out and returns the new carry.
+//   gU[n] = (1 - s) carry + sigma'(U - theta) (dL/dcount + s G) + dL/dU[n]       (Section 2.2 eq. 7)
+// Spike-time mode (no surrogate; Section 3.1 eq. 8, Section 4.1 spike detection): a spike's
+// emission time depends on the membrane value v the step started from, dt_spk/dv = -1 / vdot with
+// vdot = (U - v) / dt (1 where that is 0), and hands (1 / tau) G to its receivers (eq. 17), so
+// E = -(1 / vdot)(1 / tau) G goes back to the state before the step.
+__device__ __forceinline__ float bwd_update(const Dev& d, long long n, float U, float Uprev, bool s, float carry,
+                                            float dcount, float G, float dU, float* gu_out) {
+  float sg = 0.0f;
+  if (d.surrogate == ADSEQ_SURR_SUPERSPIKE) {
+    const float x = fabsf(U - d.theta) + 1.0f;
+    sg = 1.0f / (x * x);
+  }
+  float inner = dcount;
+  if (s) inner += G;
+  float gu = sg * inner;
+  if (!s) gu += carry;
+  gu += dU;
+  *gu_out = gu;
+  float e = 0.0f;
+  if (d.surrogate == ADSEQ_GRAD_SPIKE_TIME && s) {
+    const float vprev = n > 0 ? (Uprev >= d.theta ? d.v_reset : Uprev) : 0.0f;
+    float vdot = (U - vprev) / d.dt;
+    if (vdot == 0.0f) vdot = 1.0f;
+    e = -(1.0f / vdot) * (1.0f / d.tau) * G;
+  }
+  return __fmaf_rn(d.alpha, gu, e);
+}
+
 // Gathers the adjoint at the arrival cell of the entries [0, cnt) of the sorted row at pr0
 // (a spike at step n, window phase phi; arrivals inside the same window), adds it to gsum and
 // returns the wavefront's sum of amplitude * adjoint in every lane.
@@ -618,7 +650,9 @@ __device__ __forceinline__ float near_gather(const Dev& d, const float* __restri
 // Reverse step n: queue term of the block's spikes = far part (left in Gacc by the windows
 // already swept) + near part (gathered here from the rows of this window written by the earlier
 // launches), then
-//   gU[n] = (1 - s) alpha gU[n+1] + sigma'(U - theta) (dL/dcount + s G) + dL/dU[n]
+//   gU[n] = (1 - s) carry + sigma'(U - theta) (dL/dcount + s G) + dL/dU[n]
+//   carry <- alpha gU[n] + E,  E = -(1 / vdot)(1 / tau) G for a spike in the spike-time mode
+// (see bwd_update)
 __global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, long long T,
                                                          const float* __restrict__ dL_dcount,
                                                          const float* __restrict__ dL_dU) {
@@ -627,7 +661,7 @@ __global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, lon
   const int phi = (int)(n & (long long)(d.W - 1));
   int near_h = d.W - 1 - phi;
   if (near_h > d.d_max) near_h = d.d_max;
-  float U = 0.0f, carry = 0.0f, inner = 0.0f, G = 0.0f, dU = 0.0f;
+  float U = 0.0f, Uprev = 0.0f, carry = 0.0f, inner = 0.0f, G = 0.0f, dU = 0.0f;
   bool s = false;
   int b = 0;
   long long r0 = 0;
@@ -637,6 +671,7 @@ __global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, lon
     b = g / d.N;
     const int i = g - b * d.N;
     U = d.tapeU[(size_t)n * d.BN + g];
+    if (d.surrogate == ADSEQ_GRAD_SPIKE_TIME && n > 0) Uprev = d.tapeU[(size_t)(n - 1) * d.BN + g];
     carry = d.bwd_carry[g];
     r0 = d.row_ptr[i];
     if (near_h >= 1) ncnt = d.nearcnt[(size_t)near_h * d.N + i];
@@ -658,16 +693,8 @@ __global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, lon
     if (lane == L) G += t;
   }
   if (act) {
-    float sg = 0.0f;
-    if (d.surrogate == ADSEQ_SURR_SUPERSPIKE) {
-      const float x = fabsf(U - d.theta) + 1.0f;
-      sg = 1.0f / (x * x);
-    }
-    if (s) inner += G;
-    float gu = sg * inner;
-    if (!s) gu = __fmaf_rn(d.alpha, carry, gu);
-    gu += dU;
-    d.bwd_carry[g] = gu;
+    float gu;
+    d.bwd_carry[g] = bwd_update(d, n, U, Uprev, s, carry, inner, G, dU, &gu);
     gwin[(size_t)phi * d.BN + g] = gu;
   }
 }

@@ -250,6 +250,25 @@ def test_backward_small_ragged(kind, cap, continuous):
         assert ref.counters()["dropped"] > 0
 
 
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 4), ("sorted", 6)])
+@pytest.mark.parametrize("continuous", [False, True])
+def test_backward_spike_time_mode(kind, cap, continuous):
+    """No surrogate: gradients flow through the emission times of the spikes
+    (dt_spk/dv = -1 / vdot, Section 3.1 eq. 8) and the receive rule (eq. 17)."""
+    wl = synth.ragged_network(120, 300, 30, seed=14, rate_hz=300.0, t=150, b=2, continuous=continuous,
+                              w_mean=0.01, w_std=0.01)
+    ref = _compare_backward(wl, KINDS[kind], cap, 150, 2, surrogate=adseq.GRAD_SPIKE_TIME,
+                            tape_spike_capacity=2 * 150 * 120)
+    assert ref.spikes.sum() > 100
+    # the spike-time paths carry weight: the result differs from the one without them
+    off = oracle.Run(wl, KINDS[kind], cap, n_steps=150, batch=2, surrogate=oracle.SURR_OFF)
+    wl_t = synth.Workload(**{**wl.__dict__, "n_steps": 150, "batch": 2})
+    dU = synth.random_cotangent(wl_t, scale=1e-3)
+    g_off, _ = off.backward(None, dU)
+    g_on, _ = ref.backward(None, dU)
+    assert np.linalg.norm(g_on - g_off) > 1e-3 * np.linalg.norm(g_on)
+
+
 @pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 32), ("fifo", 2), ("sorted", 128)])
 def test_cfg1_forward_backward(kind, cap):
     """Config 1 (1,000 neurons, fan-out 100, batch 16, 2,000 steps), MSE spike-count loss."""

@@ -151,3 +151,80 @@ def test_surrogate_is_superspike():
     for n in range(T - 1, -1, -1):
         g = (1 - S[n]) * alpha * g + 1.0 / (abs(U[n] - 1.0) + 1.0) ** 2
         np.testing.assert_allclose(gU[n, 0, 0], g, rtol=1e-12)
+
+
+# ---------------------------------------------------------------- spike-time gradient (no surrogate)
+
+def test_spike_time_gradient_chain_closed_form():
+    """Three neurons in a chain A -> B -> C.  A fires once (input pulse), its event reaches B
+    ten steps later; B, charged by a constant input current, crosses the threshold some 80 steps
+    after that; B's event reaches C, and the loss is C's membrane value 20 steps on.  The only
+    way w1 and d1 (synapse A -> B) reach the loss is B's emission time, t_B' = -v_B' / vdot_B
+    (Section 3.1 eq. 8), received by C with (w2 / tau) t_post' (eq. 17):
+        dL/dw1 = (w2 / tau) alpha^(m - k2) * (-dt / (U_B[n_B] - U_B[n_B - 1])) * alpha^(n_B - 1 - k1)
+        dL/dd1 = (w1 dt / tau) dL/dw1,   dL/dw2 = alpha^(m - k2),   dL/dd2 = (w2 dt / tau) alpha^(m - k2)."""
+    T = 200
+    wl = synth.Workload("chain", 3, 1, T, 1, 20, ext_rate_hz=0.0,
+                        row_ptr=np.array([0, 1, 2, 2], np.int64), col=np.array([1, 2], np.int32),
+                        weight=np.array([0.05, 0.3], np.float32), delay_steps=np.array([10, 7], np.uint8))
+    i_ext = np.zeros((T, 1, 3), np.float32)
+    i_ext[5, 0, 0] = 1.5          # A fires at step 5
+    i_ext[:, 0, 1] = 0.012        # B charges towards 2.4 thresholds
+    r = oracle.Run(wl, oracle.RING, i_ext=i_ext, surrogate=2)
+    S, U = r.spikes[:, 0], r.U[:, 0].astype(np.float64)
+    assert S[:, 0].sum() == 1 and S[5, 0] == 1
+    n_B = int(np.nonzero(S[:, 1])[0][0])
+    k1, k2 = 5 + 10, n_B + 7
+    assert k1 + 20 < n_B < 150 and S[:, 2].sum() == 0
+    m = k2 + 20
+    dU = np.zeros((T, 1, 3), np.float32)
+    dU[m, 0, 2] = 1.0
+    gw, gd = r.backward(None, dU)
+    alpha = float(np.float32(math.exp(-float(np.float32(wl.dt_ms)) / float(np.float32(wl.tau_m_ms)))))
+    dt, tau = float(np.float32(wl.dt_ms)), float(np.float32(wl.tau_m_ms))
+    w1, w2 = float(r.a_f[0]), float(r.a_f[1])
+    direct = alpha ** (m - k2)
+    via_tB = (w2 / tau) * direct * (-dt / (U[n_B, 1] - U[n_B - 1, 1])) * alpha ** (n_B - 1 - k1)
+    np.testing.assert_allclose(gw, [via_tB, direct], rtol=1e-9)
+    np.testing.assert_allclose(gd, [(w1 * dt / tau) * via_tB, (w2 * dt / tau) * direct], rtol=1e-9)
+    assert via_tB < 0          # a larger w1 makes B fire earlier, C's jump has decayed more by step m
+    # with the surrogate switched off and no spike-time rule, w1 cannot reach the loss at all
+    r0 = oracle.Run(wl, oracle.RING, i_ext=i_ext, surrogate=1)
+    gw0, gd0 = r0.backward(None, dU)
+    np.testing.assert_allclose(gw0, [0.0, direct], rtol=1e-9)
+
+
+@pytest.mark.parametrize("kind,cap,continuous", [(oracle.RING, 0, False), (oracle.FIFO, 3, True)])
+def test_spike_time_reverse_mode_is_transpose_of_forward_mode(kind, cap, continuous):
+    """<u, J v> == <J^T u, v> for the spike-time rules, J propagated in forward mode by
+    oracle/tangent.py from the paper's tangent rules."""
+    B = 2
+    wl = synth.ragged_network(12, 7, 10, seed=29, rate_hz=1500.0, t=120, b=B, continuous=continuous,
+                              w_mean=0.2, w_std=0.15)
+    r = oracle.Run(wl, kind, cap, log_events=True, surrogate=2)
+    assert r.spikes.sum() > 80
+    u_U = synth.random_cotangent(wl)
+    gw, gd = r.backward(None, u_U)
+    rng = np.random.default_rng(6)
+    w_t = rng.standard_normal(wl.n_synapses)
+    d_t = rng.standard_normal(wl.n_synapses)
+    dl = r.event_log("delivered")
+    U, S = r.U, r.spikes
+    alpha = float(np.float32(math.exp(-float(np.float32(wl.dt_ms)) / float(np.float32(wl.tau_m_ms)))))
+    d_unit = 1.0 if continuous else float(np.float32(wl.dt_ms))
+    lhs = 0.0
+    for b in range(B):
+        sel = dl["b"] == b
+        ev = list(zip(dl["syn"][sel], dl["n_emit"][sel], dl["k"][sel]))
+        U_t, _ = tangent.jvp(U[:, b], S[:, b], ev, wl.col, _src(wl), r.a_f.astype(np.float64),
+                             r.f_f.astype(np.float64), alpha, float(wl.v_thresh),
+                             float(np.float32(wl.tau_m_ms)), d_unit, w_t, d_t, spike_time=True,
+                             dt=float(np.float32(wl.dt_ms)), v_reset=float(wl.v_reset))
+        lhs += float((u_U[:, b].astype(np.float64) * U_t).sum())
+    rhs = float(gw @ w_t + gd @ d_t)
+    assert abs(lhs) > 1e-3
+    np.testing.assert_allclose(lhs, rhs, rtol=1e-9)
+    # the spike-time paths matter: without them the same product is different
+    r1 = oracle.Run(wl, kind, cap, surrogate=1)
+    gw1, gd1 = r1.backward(None, u_U)
+    assert abs(float(gw1 @ w_t + gd1 @ d_t) - rhs) > 1e-6 * abs(rhs)
