@@ -104,6 +104,7 @@ struct Dev {
   unsigned short* fkey; // FIFO: [BN][cpad] arrival step mod 2^16 of every slot
   int* famp;            // FIFO: [BN][C] Q8.24 amplitude of every slot
   unsigned* vmask;      // FIFO: [BN][nw] bit j of word w set = slot 32 w + j holds an event
+  int prefetch;         // FIFO/SORTED: 1 = few targets (B N <= 2^18): the step kernel loads keys and row lengths up front
   int fsplit;           // FIFO/SORTED: blocks per neuron block of the closed-loop fan-out (1 .. kFanSplitMax)
   int nw, cpad;         // FIFO: mask words per target = ceil(C / 32); C rounded up to a multiple of 8
   int* occ;
@@ -118,7 +119,6 @@ struct Dev {
   unsigned* pool_k;
   int* pool_a;
   unsigned long long* spk_words;  // FIFO/SORTED: [2][words] ballot words of the step launch, by step parity
-  int* busy_hint;       // FIFO/SORTED: [nblk] 1 = an eighth or more of the block's targets held an event after the last step
   long long* stepcnt;   // FIFO/SORTED: [2][nblk][2] spikes and emitted events of every neuron block, by step parity
   float* tapeU;
   int* spk_count;       // [BN] spikes per (trial, neuron) over the recorded steps
@@ -340,7 +340,7 @@ namespace {
 
 struct Layout {
   size_t V, win, spike_bits, slot, fkey, famp, vmask, occ, head, min_k, cnt, cont, c_head, pool_p, pool_t, pool_next,
-      pool_k, pool_a, spk_words, stepcnt, busy_hint, packed, a_q, synf, synb, dstart, nearcnt, perm, rowsum, rowlen, ebuf, ecnt, amp, fdec, tapeU,
+      pool_k, pool_a, spk_words, stepcnt, packed, a_q, synf, synb, dstart, nearcnt, perm, rowsum, rowlen, ebuf, ecnt, amp, fdec, tapeU,
       tape_bits, spk_count, step_off, step_evoff, tape_spk, tape_evb, tape_adm, bwd_ring, bwd_carry, bwd_G, gwin, Gacc, gsum, ctr, blk,
       total;
   long long spike_cap, event_cap, pool_cap;
@@ -470,7 +470,6 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->pool_a = take((size_t)L->pool_cap * 4);
   L->spk_words = take(bounded ? 2 * (size_t)L->words * 8 : 0);
   L->stepcnt = take(bounded ? 2 * (size_t)L->nblk * 16 : 0);
-  L->busy_hint = take(bounded ? (size_t)L->nblk * 4 : 0);
   L->packed = take(bounded ? S * 4 : 0);
   L->a_q = take(bounded ? S * 4 : 0);
   L->synf = take(bounded ? 0 : S * 8);
@@ -549,7 +548,6 @@ void launch_reset(adseq* h, hipStream_t st) {
     fill_u32(st, d.min_k, 0xffffffffu, BN);
     if (d.kind == ADSEQ_FIFO) fill_u32(st, d.vmask, 0u, (size_t)d.nw * BN);
     fill_u32(st, d.cnt, 0u, BN);
-    fill_u32(st, d.busy_hint, 0u, (size_t)d.nblk);
     fill_u32(st, d.blk, 0u, ((size_t)d.nblk + fan_slots(d.nblk)) * sizeof(BlkCtr) / 4);
     h->pending_admit = false;
   }
@@ -783,6 +781,7 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
     const long long avg = cfg->n_synapses / cfg->n_neurons;
     const long long f = (avg + kBlock - 1) / kBlock;
     d.fsplit = (int)(f < 1 ? 1 : (f > kFanSplitMax ? kFanSplitMax : f));
+    d.prefetch = (long long)cfg->n_neurons * cfg->batch <= (1LL << 18) ? 1 : 0;
   }
   d.occ = (int*)(ws + L.occ); d.head = (int*)(ws + L.head); d.c_head = (int*)(ws + L.c_head);
   d.pool_p = (long long*)(ws + L.pool_p); d.pool_t = (long long*)(ws + L.pool_t);
@@ -791,7 +790,6 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   d.cont = (uint4*)(ws + L.cont);
   d.pool_k = (unsigned*)(ws + L.pool_k); d.pool_a = (int*)(ws + L.pool_a);
   d.spk_words = (unsigned long long*)(ws + L.spk_words); d.stepcnt = (long long*)(ws + L.stepcnt);
-  d.busy_hint = (int*)(ws + L.busy_hint);
   d.packed = (unsigned*)(ws + L.packed); d.a_q = (int*)(ws + L.a_q);
   d.amp = (d.continuous && d.kind != ADSEQ_RING) ? (float*)(ws + L.amp) : nullptr;
   d.synf = (uint2*)(ws + L.synf); d.synb = (uint2*)(ws + L.synb);

@@ -26,9 +26,10 @@
 // arrival lies within d_max <= 1023 steps of now) and the Q8.24 amplitudes.  A pop moves nothing:
 // the owner thread loads its 64 bytes of keys per mask word with full-width loads, compares them
 // with the current step, clears the bits of the due slots and loads only their amplitudes; an
-// admitted event goes to the first free bit.  The keys are loaded beside the rest of the thread's
-// state when the block's queues were busy in the step before (a hint word per block), and only
-// after the mask word has shown that the target holds something when they were mostly empty.
+// admitted event goes to the first free bit.  With few targets (a step is then bound by the chain
+// of dependent accesses) the keys are loaded beside the rest of the thread's state; with many (a
+// step is then bound by bytes and instructions) only after the mask word has shown that the target
+// holds something.
 // SORTED: the slots {arrival step, amplitude} are a circular array ordered by arrival step; pop
 // takes from the front (only targets whose front is due now load anything: the earliest stored
 // arrival is kept per target), an admitted event is inserted at its place (binary search, then
@@ -147,17 +148,14 @@ __device__ __forceinline__ void take_event(const Dev& d, int g, unsigned kn, QSt
   q.occ += 1;
 }
 
-// Admits the contenders registered for target g (owner thread): the min(K, free) with the
-// smallest synapse index are admitted, the others dropped (their admission flags cleared).
-// `free_slots` is the room the target had when the contenders were emitted (before this step's pop).
+// The rare case: more than kCont contenders for one target in one step, the later ones in the
+// overflow list.  Same rule, general selection.
 template <int KIND, int MODE>
-__device__ __forceinline__ void admit_contenders(const Dev& d, int g, int K, int free_slots, unsigned kn,
-                                                 QState& q, StepAcc& r, const uint4* cc) {
-  d.cnt[g] = 0;
-  const int nc = K < kCont ? K : kCont;              // in the contender slots
-  const int ovf_head = K > kCont ? d.c_head[g] : -1; // the others: overflow list
-  if (K > kCont) d.c_head[g] = -1;
-  const int take = K < free_slots ? K : free_slots;
+__device__ __forceinline__ void admit_overflowed(const Dev& d, int g, int K, int take, unsigned kn,
+                                              QState& q, StepAcc& r, const uint4* cc) {
+  const int nc = kCont;                // the contender slots are all taken
+  const int ovf_head = d.c_head[g];    // the others: overflow list
+  d.c_head[g] = -1;
   if (take == K) {
     // room for all: any order
 #pragma unroll
@@ -203,6 +201,52 @@ __device__ __forceinline__ void admit_contenders(const Dev& d, int g, int K, int
   }
 }
 
+// Admits the contenders registered for target g (owner thread): the min(K, free) with the
+// smallest synapse index are admitted, the others dropped (their admission flags cleared).
+// `free_slots` is the room the target had when the contenders were emitted (before this step's
+// pop).  Common case: all K contenders sit in the record slots; a contender's rank among them
+// (number of records with a smaller synapse index) decides, and is only computed when there are
+// more contenders than free slots.
+template <int KIND, int MODE>
+__device__ __forceinline__ void admit_contenders(const Dev& d, int g, int K, int free_slots, unsigned kn,
+                                                 QState& q, StepAcc& r, const uint4* cc) {
+  d.cnt[g] = 0;
+  const int take = K < free_slots ? K : free_slots;
+  if (K <= kCont) {
+    int rank[kCont];
+#pragma unroll
+    for (int x = 0; x < kCont; ++x) rank[x] = 0;
+    if (take < K) {
+      long long p[kCont];
+#pragma unroll
+      for (int x = 0; x < kCont; ++x) p[x] = x < K ? cont_syn(cc[x]) : 0x7fffffffffffffffLL;
+#pragma unroll
+      for (int x = 1; x < kCont; ++x) {
+        if (!__ballot(x < K)) break;          // no lane of the wavefront has that many contenders
+#pragma unroll
+        for (int y = 0; y < x; ++y) {
+          const bool lt = p[y] < p[x];         // each pair once
+          rank[x] += lt ? 1 : 0; rank[y] += lt ? 0 : 1;
+        }
+      }
+    }
+#pragma unroll
+    for (int x = 0; x < kCont; ++x) {
+      if (!__ballot(x < K)) break;
+      if (x < K) {
+        if (rank[x] < take) {
+          take_event<KIND, MODE>(d, g, kn, q, r, cont_arrival(cc[x], kn), (int)cc[x].w);
+        } else {
+          const long long t = cont_flag(cc[x]);
+          if (t >= 0) d.tape_adm[t] = 0;
+        }
+      }
+    }
+    return;
+  }
+  admit_overflowed<KIND, MODE>(d, g, K, take, kn, q, r, cc);
+}
+
 // Inclusive scan (sum) over the 64 lanes of a wavefront with DPP row shifts and row broadcasts;
 // lane 63 ends up with the total.  Every lane of the wavefront must be active.
 __device__ __forceinline__ int dpp_scan_add(int v) {
@@ -229,11 +273,11 @@ __device__ __forceinline__ long long wave_total64(long long v) {
 }
 
 // Block-level event counters in LDS: [0] offered, [1] admitted, [2] delivered, [3..5] the same as
-// sums of Q8.24 amplitudes, [6] spikes, [7] events emitted by them, [8] targets that hold an event.
-struct BlockCounts { unsigned long long c[9]; };
+// sums of Q8.24 amplitudes, [6] spikes, [7] events emitted by them.
+struct BlockCounts { unsigned long long c[8]; };
 
 __device__ __forceinline__ void counts_clear(BlockCounts& bc) {
-  if (threadIdx.x < 9) bc.c[threadIdx.x] = 0ull;
+  if (threadIdx.x < 8) bc.c[threadIdx.x] = 0ull;
   __syncthreads();
 }
 // Adds a wavefront's total to counter k (call it from one lane).
@@ -250,7 +294,7 @@ __device__ __forceinline__ void counts_flush(BlockCounts& bc, BlkCtr& out) {
                           : threadIdx.x == 3 ? (unsigned long long*)&out.sum_offered
                           : threadIdx.x == 4 ? (unsigned long long*)&out.sum_admitted
                                              : (unsigned long long*)&out.sum_delivered;
-    if (v) *o += v;   // the line is private to this block
+    if (v) atomicAdd(o, v);   // private to this block; an atomic without return value, so that nobody waits for a load
   }
 }
 
@@ -270,10 +314,9 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
   StepAcc r; r.acc = 0; r.popped = 0; r.c_adm = 0; r.s_adm = 0;
   if (blockIdx.x == 0 && threadIdx.x == 0) d.ctr->pool_n[0] = 0;   // the overflow pool is consumed by this launch
   counts_clear(s_cnt);
-  const int dense = d.busy_hint[blockIdx.x];   // the block's queues were busy in the step before
+  const bool dense = d.prefetch != 0;   // few targets: latency-bound, load everything in the first round
   float v = 0.0f;
   int len = 0;
-  bool holds = false;
   if (act) {
     // everything the thread needs first, loaded together
     const int K = d.cnt[g];
@@ -293,6 +336,7 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
     }
     if (MODE == 2) {
       v = d.V[g];
+      if (dense) len = d.rowlen[d.B == 1 ? g : g % d.N];
     }
     const QState q0 = q;
     // second round of loads: the contender records (and, below, the amplitudes of the due events)
@@ -385,7 +429,6 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
         q.occ = occ; q.hd = hd; q.mn = occ > 0 ? front : 0xffffffffu;
       }
     }
-    holds = q.occ > 0;
     if (q.occ != q0.occ) d.occ[g] = q.occ;
     if (KIND == ADSEQ_SORTED && q.mn != q0.mn) d.min_k[g] = q.mn;
     if (KIND == ADSEQ_FIFO && q.m0 != q0.m0) d.vmask[(size_t)g * d.nw] = q.m0;
@@ -404,10 +447,10 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
       const float U = __fmaf_rn(d.alpha, v, I);
       s = U >= d.theta;
       d.V[g] = s ? d.v_reset : U;
-      if (s) len = d.rowlen[g % d.N];
+      if (s && !dense) len = d.rowlen[d.B == 1 ? g : g % d.N];
       if (d.record && n < d.max_steps) {
         d.tapeU[(size_t)n * d.BN + g] = U;
-        if (s) d.spk_count[g] += 1;
+        if (s) atomicAdd(&d.spk_count[g], 1);   // no return value: the wavefront does not wait for it
       }
       if (spikes_out) spikes_out[g] = s ? 1 : 0;
     } else {
@@ -422,12 +465,11 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
       t_pop = wave_total(r.popped); t_acc = wave_total(r.acc);
       t_adm = wave_total(r.c_adm); t_sadm = wave_total64(r.s_adm);
     }
-    const unsigned long long m = __ballot(s), busy = __ballot(holds);
+    const unsigned long long m = __ballot(s);
     if (MODE == 2 && m) t_ev = wave_total(s ? len : 0);
     if ((threadIdx.x & 63) == 0) {
       counts_add(s_cnt, 2, t_pop); counts_add(s_cnt, 5, t_acc);
       counts_add(s_cnt, 1, t_adm); counts_add(s_cnt, 4, t_sadm);
-      counts_add(s_cnt, 8, __popcll(busy));
       if (MODE == 2) {
         // the spikes go to the fan-out launch as one ballot word per wavefront, plus the block's
         // spike and event counts (plain stores)
@@ -437,7 +479,6 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
     }
   }
   counts_flush(s_cnt, d.blk[blockIdx.x]);
-  if (threadIdx.x == 2) d.busy_hint[blockIdx.x] = s_cnt.c[8] >= kBlock / 8 ? 1 : 0;
   if (MODE == 2 && threadIdx.x < 2)
     d.stepcnt[((size_t)parity * d.nblk + blockIdx.x) * 2 + threadIdx.x] = (long long)s_cnt.c[6 + threadIdx.x];
 }
@@ -584,7 +625,7 @@ __global__ __launch_bounds__(kBlock) void k_fanout_step(Dev d, long long n, int 
       for (int j = 0; j < 4; ++j) {
         rs[j] = 0;
         if (j < nrows) {
-          rr[j].b = gs[j] / d.N;
+          rr[j].b = d.B == 1 ? 0 : gs[j] / d.N;
           const int i = gs[j] - rr[j].b * d.N;
           rr[j].r0 = d.row_ptr[i]; rr[j].r1 = d.row_ptr[i + 1];
           if (c == 0 && threadIdx.x == 0) rs[j] = d.rowsum[i];
@@ -615,7 +656,8 @@ __global__ __launch_bounds__(kBlock) void k_fanout_step(Dev d, long long n, int 
   }
   if (c == 0 && threadIdx.x == 0 && c_off) {
     BlkCtr& bc = d.blk[d.nblk + blockIdx.x];   // private to this block
-    bc.offered += (unsigned long long)c_off; bc.sum_offered += s_off;
+    atomicAdd(&bc.offered, (unsigned long long)c_off);   // atomics without return value: nobody waits for a load
+    atomicAdd((unsigned long long*)&bc.sum_offered, (unsigned long long)s_off);
   }
 }
 
@@ -640,7 +682,8 @@ __global__ __launch_bounds__(kBlock) void k_fanout_list(Dev d, long long n, cons
   }
   if (threadIdx.x == 0 && c_off) {
     BlkCtr& bc = d.blk[d.nblk + blockIdx.x];   // private to this block
-    bc.offered += (unsigned long long)c_off; bc.sum_offered += s_off;
+    atomicAdd(&bc.offered, (unsigned long long)c_off);   // atomics without return value: nobody waits for a load
+    atomicAdd((unsigned long long*)&bc.sum_offered, (unsigned long long)s_off);
   }
 }
 

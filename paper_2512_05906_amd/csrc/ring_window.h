@@ -225,7 +225,7 @@ __global__ __launch_bounds__(kBlock) void k_step_win(Dev d, long long n, const f
     d.V[g] = s ? d.v_reset : U;
     if (RECORD) {
       d.tapeU[(size_t)n * d.BN + g] = U;
-      if (s) d.spk_count[g] += 1;
+      if (s) atomicAdd(&d.spk_count[g], 1);   // no return value: the wavefront does not wait for it
     }
     if (spikes_out) spikes_out[g] = s ? 1 : 0;
   }
