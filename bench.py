@@ -39,6 +39,7 @@ def main():
     ap.add_argument("--queue", default="ring", choices=["ring", "fifo", "sorted"])
     ap.add_argument("--capacity", type=int, default=32)
     ap.add_argument("--time-steps", type=int, default=0, help="override the workload's T")
+    ap.add_argument("--drive-hz", type=float, default=0.0, help="override the rate of the Poisson drive")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-events", type=float, default=4e7)
     args = ap.parse_args()
@@ -56,6 +57,8 @@ def main():
         sys.exit(3)
     dev = torch.device("cuda:0")
     wl = getattr(synth, args.workload)()
+    if args.drive_hz > 0.0:
+        wl.ext_rate_hz = args.drive_hz
     T = args.time_steps or wl.n_steps
     B, N = wl.batch, wl.n_neurons
     BN = B * N
