@@ -23,7 +23,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# algorithmic bytes: per event and per neuron-step
+# algorithmic bytes per event and per neuron-step: forward 8 B row entry + 1 B delay share + 8 B
+# cell read-modify-write (ring) or 9 + 8 B slot write + 8 B occupancy (bounded); backward 9 + 4 B
+# adjoint gather + 16 B of gradient read-modify-writes
 FWD_B_EVENT = {"ring": 17, "fifo": 25, "sorted": 25}
 FWD_B_NEURON = 20          # queue row read + clear, V read + write, U tape write
 BWD_B_EVENT = 29
@@ -117,7 +119,7 @@ def main():
     prof = sim.profile_read()
     sim.profile(False)
     in_run = delivered  # admitted events that arrive inside the run: the ones backward touches
-    alg = {  # algorithmic bytes per run of each kernel class ("Roofline")
+    alg = {  # algorithmic bytes per run of each kernel class
         "fan_out": (FWD_B_EVENT[args.queue]) * offered,
         "lif": FWD_B_NEURON * BN * T,
         "bwd_gather": BWD_B_EVENT * in_run,

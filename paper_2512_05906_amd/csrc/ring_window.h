@@ -203,7 +203,7 @@ __global__ __launch_bounds__(kBlock) void k_step_win(Dev d, long long n, const f
   unsigned ncnt = 0;
   int* __restrict__ win = win_of(d, n);
   if (act) {
-    b = g / d.N;
+    b = d.B == 1 ? 0 : g / d.N;   // one trial: no division
     const int i = g - b * d.N;
     const size_t idx = (size_t)phi * d.BN + g;
     const int acc = win[idx];
@@ -235,11 +235,34 @@ __global__ __launch_bounds__(kBlock) void k_step_win(Dev d, long long n, const f
     d.spike_bits[(size_t)(n % d.R) * d.words + word] = bits;
     if (RECORD) d.tape_bits[(size_t)n * d.words + word] = bits;
   }
+  // in-window events of the wavefront's spikes, up to four spikes at a time: the row loads of all
+  // four are in flight before the first atomic, so that a wavefront with several spikes does not
+  // pay one memory round trip per spike
   unsigned long long m = __ballot(s && ncnt > 0);
+  const int lane = threadIdx.x & 63;
   while (m) {
-    const int L = __ffsll((long long)m) - 1;
-    m &= m - 1;
-    near_scatter(d, win, phi, __shfl(r0, L, 64), __shfl(ncnt, L, 64), __shfl(b, L, 64) * d.N);
+    long long pr[4]; unsigned cn[4]; int bs[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      pr[j] = 0; cn[j] = 0; bs[j] = 0;
+      if (m) {
+        const int L = __ffsll((long long)m) - 1;
+        m &= m - 1;
+        pr[j] = __shfl(r0, L, 64); cn[j] = __shfl(ncnt, L, 64); bs[j] = __shfl(b, L, 64) * d.N;
+      }
+    }
+    uint2 e[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      e[j] = make_uint2(0u, 0u);
+      if ((unsigned)lane < cn[j]) e[j] = d.synf[pr[j] + lane];
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if ((unsigned)lane < cn[j])
+        atomicAdd(&win[(size_t)(phi + (int)(e[j].x & d.dmask)) * d.BN + (size_t)bs[j] + (e[j].x >> d.dbits)], (int)e[j].y);
+      if (cn[j] > 64u) near_scatter(d, win, phi, pr[j] + 64, cn[j] - 64u, bs[j]);   // rows with many in-window entries
+    }
   }
 }
 
@@ -668,7 +691,7 @@ __global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, lon
   unsigned ncnt = 0;
   float* __restrict__ gwin = gwin_of(d, n);
   if (act) {
-    b = g / d.N;
+    b = d.B == 1 ? 0 : g / d.N;
     const int i = g - b * d.N;
     U = d.tapeU[(size_t)n * d.BN + g];
     if (d.surrogate == ADSEQ_GRAD_SPIKE_TIME && n > 0) Uprev = d.tapeU[(size_t)(n - 1) * d.BN + g];
@@ -684,13 +707,49 @@ __global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, lon
     s = U >= d.theta;
     if (G != 0.0f) *ga = 0.0f;
   }
+  // in-window part of the queue term of the wavefront's spikes, up to four spikes at a time (row
+  // loads, then adjoint gathers, each for all four before the next stage)
   unsigned long long m = __ballot(s && ncnt > 0);
   const int lane = threadIdx.x & 63;
   while (m) {
-    const int L = __ffsll((long long)m) - 1;
-    m &= m - 1;
-    const float t = near_gather(d, gwin, n, T, phi, __shfl(r0, L, 64), __shfl(ncnt, L, 64), __shfl(b, L, 64) * d.N);
-    if (lane == L) G += t;
+    long long pr[4]; unsigned cn[4]; int bs[4], Ls[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      pr[j] = 0; cn[j] = 0; bs[j] = 0; Ls[j] = -1;
+      if (m) {
+        const int L = __ffsll((long long)m) - 1;
+        m &= m - 1;
+        Ls[j] = L;
+        pr[j] = __shfl(r0, L, 64); cn[j] = __shfl(ncnt, L, 64); bs[j] = __shfl(b, L, 64) * d.N;
+      }
+    }
+    uint2 e[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      e[j] = make_uint2(0u, 0u);
+      if ((unsigned)lane < cn[j]) e[j] = d.synb[pr[j] + lane];
+    }
+    float gv[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      gv[j] = 0.0f;
+      const int D = (int)(e[j].x & d.dmask);
+      if ((unsigned)lane < cn[j] && n + D < T)
+        gv[j] = gwin[(size_t)(phi + D) * d.BN + (size_t)bs[j] + (e[j].x >> d.dbits)];
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (Ls[j] < 0) continue;    // uniform
+      const int D = (int)(e[j].x & d.dmask);
+      float part = 0.0f;
+      if ((unsigned)lane < cn[j] && n + D < T) {
+        part = __uint_as_float(e[j].y) * gv[j];
+        unsafeAtomicAdd(&d.gsum[pr[j] + lane], gv[j]);
+      }
+      for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
+      if (cn[j] > 64u) part += near_gather(d, gwin, n, T, phi, pr[j] + 64, cn[j] - 64u, bs[j]);
+      if (lane == Ls[j]) G += part;
+    }
   }
   if (act) {
     float gu;
