@@ -78,6 +78,8 @@ struct oracle_config {
   int32_t log_events;          // keep delivered / dropped event logs
   int32_t keep_currents;       // keep the popped fixed-point sums per step
   int32_t n_threads;           // trials are spread over this many threads
+  float tau_syn_ms;            // > 0: first-order synapse, the jump goes into a synaptic current state
+                               // with this time constant (Section 2.1 eq. 1); 0: straight into the membrane
 };
 
 }  // extern "C"
@@ -165,6 +167,8 @@ struct oracle_run {
   std::vector<float> a_f, f_f;  // fp32 amplitude w*f and decay factor f
   std::vector<double> a_d, f_d; // exact amplitude and decay factor (fp64 mode)
   double alpha_d = 0; float alpha_f = 0; uint64_t p_thresh = 0;
+  double alpha_s_d = 0; float alpha_s_f = 0;   // leak of the synaptic current state (0: no such state)
+  double tau_rcv = 0;                          // time constant of the state that receives the jump
   // tape [T,B,N]
   std::vector<float> U; std::vector<double> U64; std::vector<uint8_t> S;
   std::vector<int32_t> Iq; std::vector<float> I;
@@ -179,7 +183,7 @@ int prepare_synapses(oracle_run& r) {
   const int64_t S = c.n_synapses;
   if ((c.delay_steps == nullptr) == (c.delay_ms == nullptr)) return -1;
   r.D.resize(S); r.a_q.resize(S); r.a_f.resize(S); r.f_f.resize(S); r.a_d.resize(S); r.f_d.resize(S);
-  const double dt = (double)c.dt_ms, tau = (double)c.tau_m_ms;
+  const double dt = (double)c.dt_ms, tau = r.tau_rcv;
   for (int64_t p = 0; p < S; ++p) {
     const double w = (double)c.weight[p];
     double f = 1.0; int64_t D;
@@ -213,8 +217,9 @@ void run_trial(oracle_run& r, int b) {
   Trial& tr = r.trials[b];
   std::priority_queue<Event, std::vector<Event>, Later> pq;
   std::vector<int32_t> occ(N, 0);
-  std::vector<float> V(N, 0.0f);
-  std::vector<double> V64(N, 0.0);
+  std::vector<float> V(N, 0.0f), J(N, 0.0f);       // membrane state, synaptic current state
+  std::vector<double> V64(N, 0.0), J64(N, 0.0);
+  const bool syn_state = c.tau_syn_ms > 0.0f;
   std::vector<int32_t> acc(N);
   std::vector<double> acc64(N);
   std::vector<int32_t> fired;
@@ -240,6 +245,7 @@ void run_trial(oracle_run& r, int b) {
       bool s;
       if (!exact) {
         float I = (float)acc[j] * 0x1p-24f;
+        if (syn_state) { I = std::fmaf(r.alpha_s_f, J[j], I); J[j] = I; }   // isyn = alpha_s isyn + jumps
         I = I + (xi ? c.ext_weight : 0.0f);
         if (c.i_ext) I = I + c.i_ext[base + j];
         const float u = std::fmaf(r.alpha_f, V[j], I);
@@ -247,7 +253,9 @@ void run_trial(oracle_run& r, int b) {
         V[j] = s ? c.v_reset : u;
         r.U[base + j] = u; r.I[base + j] = I;
       } else {
-        double I = acc64[j] + (xi ? (double)c.ext_weight : 0.0);
+        double I = acc64[j];
+        if (syn_state) { I = r.alpha_s_d * J64[j] + I; J64[j] = I; }
+        I += xi ? (double)c.ext_weight : 0.0;
         if (c.i_ext) I += (double)c.i_ext[base + j];
         const double u = r.alpha_d * V64[j] + I;
         s = c.forced_spikes ? (c.forced_spikes[base + j] != 0) : (u >= (double)c.v_thresh);
@@ -290,7 +298,7 @@ void backward_trial(const oracle_run& r, int b, const float* dL_dcount, const fl
   const int N = c.n_neurons, T = c.n_steps, B = c.batch;
   const bool exact = c.exact_f64 != 0;
   const Trial& tr = r.trials[b];
-  const double tau = (double)c.tau_m_ms, theta = (double)c.v_thresh;
+  const double tau = r.tau_rcv, theta = (double)c.v_thresh;
   // gradient per unit the delay was given in: ms, or steps of dt ms
   const double d_unit = c.delay_ms ? 1.0 : (double)c.dt_ms;
   // dU[n+1]/dV[n]: the leak factor the forward pass actually multiplied by
@@ -300,6 +308,10 @@ void backward_trial(const oracle_run& r, int b, const float* dL_dcount, const fl
   // that the emission time of a spike at n+1 hands to the state it started from.
   std::vector<double> gU((size_t)(T + 1) * N, 0.0);
   std::vector<double> carry(N, 0.0);
+  // gR[n][j]: what an event delivered to j at step n gathers = dL/d(state that received the jump):
+  // dL/dU_j[n] without a synaptic current state; with one, dL/dJ_j[n] = gU_j[n] + alpha_s dL/dJ_j[n+1]
+  std::vector<double> gR((size_t)(T + 1) * N, 0.0);
+  const double alpha_s = exact ? r.alpha_s_d : (double)r.alpha_s_f;
   int64_t sp = (int64_t)tr.spikes.size() - 1;  // spikes are stored in emission order
   std::vector<double> G(N);
   const bool spike_time = c.surrogate == 2;
@@ -315,7 +327,7 @@ void backward_trial(const oracle_run& r, int b, const float* dL_dcount, const fl
         if (!tr.admitted[rec.ev_base + (p - c.row_ptr[i])]) continue;
         const int k = n + r.D[p];
         if (k >= T) continue;  // never delivered inside the run
-        const double g = gU[(size_t)k * N + c.col[p]];
+        const double g = gR[(size_t)k * N + c.col[p]];
         const double a = exact ? r.a_d[p] : (double)r.a_f[p];
         const double f = exact ? r.f_d[p] : (double)r.f_f[p];
         g_sum += a * g;
@@ -334,6 +346,7 @@ void backward_trial(const oracle_run& r, int b, const float* dL_dcount, const fl
       const double dc = dL_dcount ? (double)dL_dcount[(size_t)b * N + i] : 0.0;
       const double g_now = (1.0 - s) * carry[i] + sg * (dc + s * G[i]) + direct;
       gU[(size_t)n * N + i] = g_now;
+      gR[(size_t)n * N + i] = g_now + alpha_s * gR[(size_t)(n + 1) * N + i];
       // Spike-time mode: the spike's emission time depends on the membrane value v the step
       // started from, dt_spk/dv = -1 / vdot with vdot = (U - v) / dt from the first forward
       // difference (1 where that is 0), and every event of the spike hands (jump / tau) dt_post
@@ -371,10 +384,16 @@ oracle_run* oracle_forward(const oracle_config* cfg) {
       !(c.dt_ms > 0.0f) || !(c.tau_m_ms > 0.0f) || c.dt_ms > c.tau_m_ms) {
     r->status = -1; return r;
   }
+  if (c.tau_syn_ms < 0.0f || (c.tau_syn_ms > 0.0f && c.dt_ms > c.tau_syn_ms)) { r->status = -1; return r; }
+  r->tau_rcv = c.tau_syn_ms > 0.0f ? (double)c.tau_syn_ms : (double)c.tau_m_ms;
   r->status = prepare_synapses(*r);
   if (r->status != 0) return r;
   r->alpha_d = std::exp(-(double)c.dt_ms / (double)c.tau_m_ms);
   r->alpha_f = (float)r->alpha_d;
+  if (c.tau_syn_ms > 0.0f) {
+    r->alpha_s_d = std::exp(-(double)c.dt_ms / (double)c.tau_syn_ms);
+    r->alpha_s_f = (float)r->alpha_s_d;
+  }
   {
     // Bernoulli probability per step rate*dt, as a 32-bit threshold
     double p = (double)c.ext_rate_hz * (double)c.dt_ms * 1e-3;

@@ -24,7 +24,7 @@ import numpy as np
 
 
 def jvp(U, S, events, col, src, a, f, alpha, theta, tau, d_unit, w_t, d_t, surrogate=True,
-        spike_time=False, dt=None, v_reset=0.0):
+        spike_time=False, dt=None, v_reset=0.0, alpha_s=0.0):
     """Tangents of (U [T,N], spike counts [N]) for one trial.
 
     U, S        recorded membrane values / spikes [T, N]
@@ -33,6 +33,8 @@ def jvp(U, S, events, col, src, a, f, alpha, theta, tau, d_unit, w_t, d_t, surro
     a, f        amplitude a = w f and decay factor f per synapse (float64)
     w_t, d_t    tangent directions on weights and delays [S]
     d_unit      1 for delays in ms, dt for delays in steps
+    tau         time constant of the state that receives the jump (synaptic current state if
+                alpha_s > 0, eq. 1: isyn = alpha_s isyn + jumps, U = alpha V + isyn; else the membrane)
     """
     T, N = U.shape
     by_arrival = [[] for _ in range(T)]
@@ -48,6 +50,7 @@ def jvp(U, S, events, col, src, a, f, alpha, theta, tau, d_unit, w_t, d_t, surro
     tspk_t = np.zeros((T, N))      # tangent of the emission time (ms) of the spike at (n, i)
     V_t = np.zeros(N)
     V = np.zeros(N)                # membrane value each step starts from
+    J_t = np.zeros(N)              # tangent of the synaptic current state
     for n in range(T):
         I_t = np.zeros(N)
         for p, n_emit in by_arrival[n]:
@@ -59,6 +62,9 @@ def jvp(U, S, events, col, src, a, f, alpha, theta, tau, d_unit, w_t, d_t, surro
             vdot = (U[n].astype(np.float64) - V) / dt
             vdot = np.where(vdot == 0.0, 1.0, vdot)
             tspk_t[n] = np.where(S[n] != 0, -V_t / vdot, 0.0)
+        if alpha_s > 0.0:
+            J_t = alpha_s * J_t + I_t
+            I_t = J_t
         U_t[n] = alpha * V_t + I_t
         s_t[n] = sg[n] * U_t[n]
         V_t = (1.0 - S[n]) * U_t[n]

@@ -51,14 +51,15 @@ def test_single_synapse_closed_form_delay_and_weight_gradient():
     np.testing.assert_allclose(gw[0], alpha ** (m - k), rtol=1e-6)
 
 
-@pytest.mark.parametrize("kind,cap", [(oracle.RING, 0), (oracle.FIFO, 3)])
-def test_central_finite_differences_frozen_raster(kind, cap):
+@pytest.mark.parametrize("kind,cap,tau_syn", [(oracle.RING, 0, 0.0), (oracle.FIFO, 3, 0.0), (oracle.RING, 0, 2.0)])
+def test_central_finite_differences_frozen_raster(kind, cap, tau_syn):
     """Smooth loss L = sum c[n,j] U_j[n] on a 10-neuron net, raster frozen, fp64
     without quantisation, surrogate off: reverse-mode grad_w / grad_d must equal
     central differences.  (With the raster frozen the surrogate terms are not a
     derivative of anything, hence off.)"""
     wl = synth.ragged_network(10, 6, 12, seed=17, rate_hz=1500.0, t=150, continuous=True,
                               w_mean=0.2, w_std=0.1)
+    wl.tau_syn_ms = tau_syn     # > 0: the jumps go into a synaptic current state (eq. 1)
     free = oracle.Run(wl, kind, cap)
     forced = free.spikes
     assert forced.sum() > 50
@@ -228,3 +229,79 @@ def test_spike_time_reverse_mode_is_transpose_of_forward_mode(kind, cap, continu
     r1 = oracle.Run(wl, kind, cap, surrogate=1)
     gw1, gd1 = r1.backward(None, u_U)
     assert abs(float(gw1 @ w_t + gd1 @ d_t) - rhs) > 1e-6 * abs(rhs)
+
+
+# ---------------------------------------------------------------- first-order synapse (synaptic current state)
+
+def test_first_order_synapse_closed_form():
+    """One synapse 0 -> 1 with a synaptic current state (Section 2.1 eq. 1, discretised as
+    isyn = alpha_s isyn + jump, U = alpha V + isyn), one spike at n0, arrival k = n0 + D.  For
+    m >= k:  U_1[m] = a sum_{r=k..m} alpha^(m-r) alpha_s^(r-k) = a (alpha^(L+1) - alpha_s^(L+1)) / (alpha - alpha_s),
+    L = m - k;  dU_1[m]/dw = that / w,  dU_1[m]/dd = (a / tau_syn) dt times the same kernel
+    (receive rule, eq. 17, with the time constant of the state that takes the jump)."""
+    T, n0, m, D = 80, 5, 50, 7
+    w, tau_syn, tau_m, dt = 0.3, 2.0, 20.0, float(np.float32(0.1))
+    wl = synth.Workload("pair", 2, 1, T, 1, 20, ext_rate_hz=0.0, tau_syn_ms=tau_syn,
+                        row_ptr=np.array([0, 1, 1], np.int64), col=np.array([1], np.int32),
+                        weight=np.array([w], np.float32), delay_steps=np.array([D], np.uint8))
+    forced = np.zeros((T, 1, 2), np.uint8)
+    forced[n0, 0, 0] = 1
+    dL_dU = np.zeros((T, 1, 2), np.float32)
+    dL_dU[m, 0, 1] = 1.0
+    k = n0 + D
+    al, als = math.exp(-dt / tau_m), math.exp(-dt / tau_syn)
+    kern = (al ** (m - k + 1) - als ** (m - k + 1)) / (al - als)
+    a = float(np.float32(w))
+    r = oracle.Run(wl, oracle.RING, forced_spikes=forced, exact_f64=True, surrogate=1)
+    np.testing.assert_allclose(r.U64[m, 0, 1], a * kern, rtol=1e-12)
+    assert r.U64[k - 1, 0, 1] == 0.0 and r.U64[k, 0, 1] == a
+    gw, gd = r.backward(None, dL_dU)
+    np.testing.assert_allclose(gw[0], kern, rtol=1e-12)
+    np.testing.assert_allclose(gd[0], a / tau_syn * dt * kern, rtol=1e-12)
+    # fp32 path (Q8.24 amplitude, fused multiply-adds): same values to rounding
+    r32 = oracle.Run(wl, oracle.RING, forced_spikes=forced, surrogate=1)
+    np.testing.assert_allclose(r32.U[m, 0, 1], a * kern, rtol=1e-5)
+    # continuous delay: the decay between true arrival and grid step is that of the synaptic state
+    d_ms = 0.6543
+    wl2 = copy.copy(wl)
+    wl2.delay_steps, wl2.delay_ms = None, np.array([d_ms], np.float32)
+    r2 = oracle.Run(wl2, oracle.RING, forced_spikes=forced, exact_f64=True, surrogate=1)
+    D2 = math.ceil(float(np.float32(d_ms)) / dt)
+    f = math.exp(-(D2 * dt - float(np.float32(d_ms))) / tau_syn)
+    np.testing.assert_allclose(r2.a_d[0], a * f, rtol=1e-12)
+
+
+@pytest.mark.parametrize("mode", [0, 2])
+def test_first_order_synapse_reverse_mode_is_transpose_of_forward_mode(mode):
+    """<u, J v> == <J^T u, v> with a synaptic current state, surrogate and spike-time modes."""
+    B = 2
+    wl = synth.ragged_network(12, 7, 10, seed=31, rate_hz=1500.0, t=120, b=B, continuous=True,
+                              w_mean=0.25, w_std=0.15)
+    wl.tau_syn_ms = 1.5
+    r = oracle.Run(wl, oracle.FIFO, 4, log_events=True, surrogate=mode)
+    assert r.spikes.sum() > 60 and r.counters()["dropped"] > 0
+    u_U = synth.random_cotangent(wl)
+    u_c = synth.spike_count_targets(wl) - 2.5 if mode == 0 else None
+    gw, gd = r.backward(u_c, u_U)
+    rng = np.random.default_rng(8)
+    w_t = rng.standard_normal(wl.n_synapses)
+    d_t = rng.standard_normal(wl.n_synapses)
+    dl = r.event_log("delivered")
+    U, S = r.U, r.spikes
+    dt = float(np.float32(wl.dt_ms))
+    alpha = float(np.float32(math.exp(-dt / float(np.float32(wl.tau_m_ms)))))
+    alpha_s = float(np.float32(math.exp(-dt / float(np.float32(wl.tau_syn_ms)))))
+    lhs = 0.0
+    for b in range(B):
+        sel = dl["b"] == b
+        ev = list(zip(dl["syn"][sel], dl["n_emit"][sel], dl["k"][sel]))
+        U_t, c_t = tangent.jvp(U[:, b], S[:, b], ev, wl.col, _src(wl), r.a_f.astype(np.float64),
+                               r.f_f.astype(np.float64), alpha, float(wl.v_thresh),
+                               float(np.float32(wl.tau_syn_ms)), 1.0, w_t, d_t, surrogate=(mode == 0),
+                               spike_time=(mode == 2), dt=dt, v_reset=float(wl.v_reset), alpha_s=alpha_s)
+        lhs += float((u_U[:, b].astype(np.float64) * U_t).sum())
+        if mode == 0:
+            lhs += float((u_c[b].astype(np.float64) * c_t).sum())
+    rhs = float(gw @ w_t + gd @ d_t)
+    assert abs(lhs) > 1e-3
+    np.testing.assert_allclose(lhs, rhs, rtol=1e-9)
