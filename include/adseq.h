@@ -24,7 +24,9 @@
  *   1. pop     Iq_j = sum of the amplitudes of the stored events with arrival
  *              step n and target j (summed as 32-bit fixed point Q8.24, so the
  *              result does not depend on the order of arrival);
- *   2. drive   I_j = Iq_j * 2^-24 + (xi_j ? ext_weight : 0) (+ i_ext_j), xi_j a
+ *   2. drive   I_j = Iq_j * 2^-24 + (xi_j ? ext_weight : 0) (+ i_ext_j)   [with tau_syn_ms > 0:
+ *              J_j = fma(alpha_s, J_j, Iq_j * 2^-24), alpha_s = (float)exp(-dt/tau_syn), takes the
+ *              place of Iq_j * 2^-24], xi_j a
  *              Bernoulli(ext_rate_hz * dt) draw from a counter-based hash of
  *              (seed, b * N + j, n);
  *   3. LIF     U_j = fma(alpha, V_j, I_j), alpha = (float)exp(-dt/tau_m);
@@ -32,7 +34,8 @@
  *   4. enqueue for every spiking i and every synapse p of row i: an event with
  *              target col[p], arrival n + D_p and amplitude a_p.
  *   Integer delays: D_p = delay_steps[p], a_p = weight[p].  Continuous delays:
- *   D_p = max(1, ceil(delay_ms[p] / dt)), a_p = weight[p] * exp(-(D_p dt - delay_ms[p]) / tau_m).
+ *   D_p = max(1, ceil(delay_ms[p] / dt)), a_p = weight[p] * exp(-(D_p dt - delay_ms[p]) / tau),
+ *   tau = the time constant of the state that takes the jump (tau_syn_ms if > 0, else tau_m_ms).
  *
  * Queue kinds (Section 4.3)
  *   ADSEQ_RING    dense delay line: one summed cell per (arrival step, target) for
@@ -99,6 +102,12 @@ typedef struct {
   int32_t max_steps;    /* tape length in steps (needed when record_tape = 1)                 */
   float dt_ms, tau_m_ms, v_thresh, v_reset; /* LIF; requires 0 < dt_ms <= tau_m_ms            */
   float ext_rate_hz, ext_weight;            /* Poisson drive, 0 rate = none                   */
+  float tau_syn_ms;                         /* > 0: first-order synapse (Section 2.1 eq. 1): the events
+                                               jump into a synaptic current state J with this time
+                                               constant (dt_ms <= tau_syn_ms), J <- alpha_s J + Iq,
+                                               and J is what the membrane integrates; 0: the events
+                                               jump straight into the membrane state               */
+  float reserved0;                          /* 0                                              */
   uint64_t seed;                            /* of the drive's counter-based generator         */
   int64_t n_synapses;                       /* S = row_ptr[N], below 2^40                     */
   const int64_t *row_ptr;     /* [N+1] CSR by source neuron                                   */
@@ -177,7 +186,9 @@ int adseq_run(adseq_t *h, int64_t step0, int64_t n_steps, void *stream);
  *   c_i[n]  = alpha * gU_i[n] + E_i[n],  E_i[n] = -(1 / vdot_i[n]) (1 / tau_m) s_i[n] G_i in the spike-time
  *             mode (sigma' = 0 there), 0 otherwise
  *   grad_w[p] += f_p * gU[col_p][n + D_p],   grad_d[p] += (a_p / tau_m) * unit * gU[col_p][n + D_p]
- * (f_p = a_p / weight_p; unit = 1 per ms for delay_ms, dt per step for delay_steps), summed over
+ * (f_p = a_p / weight_p; unit = 1 per ms for delay_ms, dt per step for delay_steps; with a synaptic
+ * current state, gJ_j[n] = gU_j[n] + alpha_s gJ_j[n+1] takes the place of gU in G_i, grad_w and
+ * grad_d, and tau_syn that of tau_m in grad_d and E), summed over
  * trials.  dL_dcount: fp32 [B*N] or NULL; dL_dU: fp32 [T][B*N] or NULL; grad_w, grad_d: fp32 [S],
  * overwritten.  Synchronises the stream once at the start to read the device error word. */
 int adseq_backward(adseq_t *h, const float *dL_dcount, const float *dL_dU, float *grad_w,

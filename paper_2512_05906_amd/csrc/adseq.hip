@@ -67,7 +67,11 @@ struct Dev {
   int N, B, BN, R, C, kind, dbits, d_max;
   unsigned dmask;
   int continuous, record, surrogate, max_steps, pool_cap;
-  float alpha, theta, v_reset, ext_w, dt, tau;
+  float alpha, theta, v_reset, ext_w, dt;
+  float tau;            // time constant of the state that takes the jump: tau_syn if there is a synaptic state, else tau_m
+  float alpha_s;        // exp(-dt / tau_syn), 0 = no synaptic current state
+  float* J;             // [BN] synaptic current state (alpha_s > 0)
+  float* bwd_carryJ;    // [BN] its adjoint dL/dJ[n+1]
   unsigned long long p_thresh, seed;
   long long S, spike_cap, event_cap;
   const long long* row_ptr;
@@ -152,6 +156,15 @@ __device__ __forceinline__ unsigned drive_bits(unsigned long long seed, unsigned
   z = mix64(z + G * (n + 1));
   return (unsigned)(z >> 32);
 }
+
+// Makes a kernel fetch fields of its argument block where this is called: an empty asm statement
+// that takes the values in scalar registers.  Without it the compiler fetches each field in the
+// block that first uses it, and a step kernel starts with a chain of four to six dependent scalar
+// loads (each a trip to memory: the argument block of a fresh dispatch is in no cache) before its
+// first vector load.  pin_args(a, b, ...) at the top turns the chain into one batch.  (Measured per
+// kernel: it pays in the short step kernels, not in the ones with many arguments and early exits.)
+template <class T> __device__ __forceinline__ void pin_arg(T v) { asm volatile("" ::"s"(v)); }
+template <class... Ts> __device__ __forceinline__ void pin_args(Ts... vs) { (pin_arg(vs), ...); }
 
 __device__ __forceinline__ int wrap_add(int a, int b) { return (int)((unsigned)a + (unsigned)b); }
 
@@ -300,6 +313,8 @@ __global__ __launch_bounds__(kBlock) void k_bwd_gather(Dev d, long long n, long 
 __global__ __launch_bounds__(kBlock) void k_bwd_neurons(Dev d, long long n,
                                                         const float* __restrict__ dL_dcount,
                                                         const float* __restrict__ dL_dU) {
+  pin_args(d.tapeU, d.bwd_carry, d.bwd_carryJ, d.bwd_G, d.bwd_ring, d.BN, d.R, d.surrogate, d.alpha, d.alpha_s,
+           d.theta, d.v_reset, d.dt, d.tau, n, dL_dcount, dL_dU);
   const int g = blockIdx.x * kBlock + threadIdx.x;
   if (g >= d.BN) return;
   const float U = d.tapeU[(size_t)n * d.BN + g];
@@ -308,7 +323,7 @@ __global__ __launch_bounds__(kBlock) void k_bwd_neurons(Dev d, long long n,
   float gu;
   d.bwd_carry[g] = bwd_update(d, n, U, Uprev, s, d.bwd_carry[g], dL_dcount ? dL_dcount[g] : 0.0f,
                               s ? d.bwd_G[g] : 0.0f, dL_dU ? dL_dU[(size_t)n * d.BN + g] : 0.0f, &gu);
-  d.bwd_ring[(size_t)(n % d.R) * d.BN + g] = gu;
+  d.bwd_ring[(size_t)(n % d.R) * d.BN + g] = bwd_receiver(d, g, gu);
 }
 
 }  // namespace
@@ -339,7 +354,7 @@ struct adseq {
 namespace {
 
 struct Layout {
-  size_t V, win, spike_bits, slot, fkey, famp, vmask, occ, head, min_k, cnt, cont, c_head, pool_p, pool_t, pool_next,
+  size_t V, J, bwd_carryJ, win, spike_bits, slot, fkey, famp, vmask, occ, head, min_k, cnt, cont, c_head, pool_p, pool_t, pool_next,
       pool_k, pool_a, spk_words, stepcnt, packed, a_q, synf, synb, dstart, nearcnt, perm, rowsum, rowlen, ebuf, ecnt, amp, fdec, tapeU,
       tape_bits, spk_count, step_off, step_evoff, tape_spk, tape_evb, tape_adm, bwd_ring, bwd_carry, bwd_G, gwin, Gacc, gsum, ctr, blk,
       total;
@@ -379,6 +394,7 @@ bool host_validate(const adseq_config* c) {
   if (c->surrogate != ADSEQ_SURR_SUPERSPIKE && c->surrogate != ADSEQ_SURR_OFF &&
       c->surrogate != ADSEQ_GRAD_SPIKE_TIME) return false;
   if (!(c->dt_ms > 0.0f) || !(c->tau_m_ms > 0.0f) || c->dt_ms > c->tau_m_ms) return false;
+  if (!(c->tau_syn_ms >= 0.0f) || (c->tau_syn_ms > 0.0f && c->dt_ms > c->tau_syn_ms)) return false;
   if (!(c->ext_rate_hz >= 0.0f)) return false;
   if (c->n_synapses < 0 || c->n_synapses >= (1LL << 40)) return false;   // synapse indices are packed into 40 bits
   if (c->record_tape && c->max_steps < 1) return false;
@@ -450,6 +466,7 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->ctr = take(sizeof(Counters));
   L->blk = take(bounded ? ((size_t)L->nblk + fan_slots(L->nblk)) * sizeof(BlkCtr) : 0);
   L->V = take(BN * 4);
+  L->J = take(c->tau_syn_ms > 0.0f ? BN * 4 : 0);
   L->win = take(bounded ? 0 : 2 * (size_t)L->W * BN * 4);
   L->spike_bits = take(bounded ? 0 : (size_t)L->R * L->words * 8);
   const bool fifo = c->kind == ADSEQ_FIFO;
@@ -495,6 +512,7 @@ bool make_layout(const adseq_config* c, Layout* L) {
   const bool tape = c->record_tape != 0;
   L->bwd_ring = take(tape && bounded ? (size_t)L->R * BN * 4 : 0);
   L->bwd_carry = take(tape ? BN * 4 : 0);
+  L->bwd_carryJ = take(tape && c->tau_syn_ms > 0.0f ? BN * 4 : 0);
   L->bwd_G = take(tape && bounded ? BN * 4 : 0);
   L->gwin = take(tape && !bounded ? 2 * (size_t)L->W * BN * 4 : 0);
   L->Gacc = take(tape && !bounded ? (size_t)L->R * BN * 4 : 0);
@@ -538,6 +556,7 @@ void launch_reset(adseq* h, hipStream_t st) {
   const size_t BN = (size_t)d.BN;
   fill_u32(st, d.ctr, 0u, sizeof(Counters) / 4);
   fill_u32(st, d.V, 0u, BN);
+  if (d.alpha_s > 0.0f) fill_u32(st, d.J, 0u, BN);
   if (d.kind == ADSEQ_RING) {
     fill_u32(st, d.win, 0u, 2 * (size_t)d.W * BN);
     fill_u32(st, d.spike_bits, 0u, (size_t)d.R * d.words * 2);
@@ -661,8 +680,11 @@ int step_impl(adseq* h, long long step, const float* i_ext, unsigned char* spike
     ring_open_window(h, st, step);
     open_group(h, st);
     const dim3 grid((unsigned)d.nblk), block(kBlock);
-    if (record) hipLaunchKernelGGL((k_step_win<true>), grid, block, 0, st, d, step, i_ext, spikes_out);
-    else hipLaunchKernelGGL((k_step_win<false>), grid, block, 0, st, d, step, i_ext, spikes_out);
+    const bool syn = d.alpha_s > 0.0f;
+    if (record && !syn) hipLaunchKernelGGL((k_step_win<true, false>), grid, block, 0, st, d, step, i_ext, spikes_out);
+    else if (record) hipLaunchKernelGGL((k_step_win<true, true>), grid, block, 0, st, d, step, i_ext, spikes_out);
+    else if (!syn) hipLaunchKernelGGL((k_step_win<false, false>), grid, block, 0, st, d, step, i_ext, spikes_out);
+    else hipLaunchKernelGGL((k_step_win<false, true>), grid, block, 0, st, d, step, i_ext, spikes_out);
     h->grp_count += 1;
   } else {
     mark(h, st, -1);
@@ -693,12 +715,14 @@ void ring_backward_launch(adseq* h, hipStream_t st, long long T, float dscale, c
   const Dev& d = h->dev;
   const dim3 block(kBlock), gn((unsigned)d.nblk);
   fill_u32(st, d.bwd_carry, 0u, (size_t)d.BN);
+  if (d.alpha_s > 0.0f) fill_u32(st, d.bwd_carryJ, 0u, (size_t)d.BN);
   fill_u32(st, d.gsum, 0u, (size_t)d.S);
   fill_u32(st, d.gwin, 0u, 2 * (size_t)d.W * d.BN);
   fill_u32(st, d.Gacc, 0u, (size_t)d.R * d.BN);
   for (long long n = T - 1; n >= 0; --n) {
     open_group(h, st);
-    hipLaunchKernelGGL(k_bwd_step_win, gn, block, 0, st, d, n, T, dL_dcount, dL_dU);
+    if (d.alpha_s > 0.0f) hipLaunchKernelGGL((k_bwd_step_win<true>), gn, block, 0, st, d, n, T, dL_dcount, dL_dU);
+    else hipLaunchKernelGGL((k_bwd_step_win<false>), gn, block, 0, st, d, n, T, dL_dcount, dL_dU);
     h->grp_count += 1;
     if ((n & (long long)(d.W - 1)) == 0 && n > 0) {
       close_group(h, st, 3);
@@ -750,7 +774,10 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   d.pool_cap = (int)L.pool_cap;
   d.alpha = (float)std::exp(-(double)cfg->dt_ms / (double)cfg->tau_m_ms);
   d.theta = cfg->v_thresh; d.v_reset = cfg->v_reset; d.ext_w = cfg->ext_weight;
-  d.dt = cfg->dt_ms; d.tau = cfg->tau_m_ms;
+  d.dt = cfg->dt_ms;
+  d.tau = cfg->tau_syn_ms > 0.0f ? cfg->tau_syn_ms : cfg->tau_m_ms;
+  d.alpha_s = cfg->tau_syn_ms > 0.0f ? (float)std::exp(-(double)cfg->dt_ms / (double)cfg->tau_syn_ms) : 0.0f;
+  d.J = (float*)(ws + L.J); d.bwd_carryJ = (float*)(ws + L.bwd_carryJ);
   {
     double p = (double)cfg->ext_rate_hz * (double)cfg->dt_ms * 1e-3;
     if (p < 0.0) p = 0.0;
@@ -951,6 +978,7 @@ int adseq_backward(adseq_t* h, const float* dL_dcount, const float* dL_dU, float
     return ADSEQ_OK;
   }
   fill_u32(st, d.bwd_carry, 0u, (size_t)d.BN);
+  if (d.alpha_s > 0.0f) fill_u32(st, d.bwd_carryJ, 0u, (size_t)d.BN);
   fill_u32(st, grad_w, 0u, (size_t)d.S);
   fill_u32(st, grad_d, 0u, (size_t)d.S);
   fill_u32(st, d.bwd_ring, 0u, (size_t)d.R * d.BN);

@@ -315,7 +315,7 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
   if (blockIdx.x == 0 && threadIdx.x == 0) d.ctr->pool_n[0] = 0;   // the overflow pool is consumed by this launch
   counts_clear(s_cnt);
   const bool dense = d.prefetch != 0;   // few targets: latency-bound, load everything in the first round
-  float v = 0.0f;
+  float v = 0.0f, jsyn = 0.0f;
   int len = 0;
   if (act) {
     // everything the thread needs first, loaded together
@@ -336,6 +336,7 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
     }
     if (MODE == 2) {
       v = d.V[g];
+      if (d.alpha_s > 0.0f) jsyn = d.J[g];
       if (dense) len = d.rowlen[d.B == 1 ? g : g % d.N];
     }
     const QState q0 = q;
@@ -438,6 +439,7 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
   if (act && MODE != 0) {
     float I = (float)r.acc * 0x1p-24f;
     if (MODE == 2) {
+      if (d.alpha_s > 0.0f) { I = __fmaf_rn(d.alpha_s, jsyn, I); d.J[g] = I; }   // first-order synapse: the jumps go into J
       if (d.p_thresh) {
         const bool xi = (unsigned long long)drive_bits(d.seed, (unsigned long long)g,
                                                        (unsigned long long)n) < d.p_thresh;
@@ -571,6 +573,9 @@ __global__ __launch_bounds__(kBlock) void k_fanout_step(Dev d, long long n, int 
   for (int x = 0; x < kBlock / 64; ++x) { w[x] = wp[x]; nspk += __popcll(w[x]); }
   const bool closer = record && blockIdx.x == 0;      // also writes where the next step's spikes start
   if (nspk == 0 && !closer) return;
+  pin_args(d.stepcnt, d.step_off, d.step_evoff, d.row_ptr, d.rowsum, d.packed, d.a_q, d.occ, d.cnt, d.cont,
+           d.tape_adm, d.tape_spk, d.tape_evb, d.blk, d.ctr, d.N, d.B, d.BN, d.C, d.nblk, d.dbits, d.dmask,
+           d.max_steps, d.spike_cap, d.event_cap, d.pool_cap, n);
   long long c_off = 0, s_off = 0;   // offered events and their amplitude sum (share 0, thread 0)
   {
     long long pre_s = 0, pre_e = 0;

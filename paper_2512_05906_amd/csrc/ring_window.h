@@ -189,9 +189,12 @@ __device__ __forceinline__ void near_scatter(const Dev& d, int* __restrict__ win
 // row phi = n mod W, adds the drive, integrates, records the membrane value and the spike bits,
 // and scatters the in-window events of its own spikes.  No block-level synchronisation and no
 // counter: spikes and offered events are counted from the spike bits when a window closes.
-template <bool RECORD>
+template <bool RECORD, bool SYN>
 __global__ __launch_bounds__(kBlock) void k_step_win(Dev d, long long n, const float* __restrict__ i_ext,
                                                      unsigned char* __restrict__ spikes_out) {
+  pin_args(d.win, d.V, d.row_ptr, d.nearcnt, d.tapeU, d.spk_count, d.spike_bits, d.tape_bits, d.synf, d.J,
+           d.N, d.B, d.BN, d.W, d.wshift, d.d_max, d.R, d.words, d.dbits, d.dmask, d.alpha, d.theta,
+           d.v_reset, d.ext_w, d.alpha_s, d.p_thresh, d.seed, n, i_ext, spikes_out);
   const int g = blockIdx.x * kBlock + threadIdx.x;
   const bool act = g < d.BN;
   const int phi = (int)(n & (long long)(d.W - 1));
@@ -212,8 +215,10 @@ __global__ __launch_bounds__(kBlock) void k_step_win(Dev d, long long n, const f
     r0 = d.row_ptr[i];
     if (near_h >= 1) ncnt = d.nearcnt[(size_t)near_h * d.N + i];
     const float v = d.V[g];
+    const float jsyn = SYN ? d.J[g] : 0.0f;
     if (acc != 0) win[idx] = 0;
     float I = (float)acc * 0x1p-24f;
+    if (SYN) { I = __fmaf_rn(d.alpha_s, jsyn, I); d.J[g] = I; }   // first-order synapse: the jumps go into J
     if (d.p_thresh) {
       const bool xi = (unsigned long long)drive_bits(d.seed, (unsigned long long)g,
                                                      (unsigned long long)n) < d.p_thresh;
@@ -650,6 +655,16 @@ __device__ __forceinline__ float bwd_update(const Dev& d, long long n, float U, 
   return __fmaf_rn(d.alpha, gu, e);
 }
 
+// What an event delivered to neuron g at this step gathers: the adjoint of the state that took its
+// jump.  Without a synaptic current state that is gU itself; with one, dL/dJ[n] = gU[n] + alpha_s
+// dL/dJ[n+1] (kept in bwd_carryJ).
+__device__ __forceinline__ float bwd_receiver(const Dev& d, int g, float gu) {
+  if (!(d.alpha_s > 0.0f)) return gu;
+  const float gj = __fmaf_rn(d.alpha_s, d.bwd_carryJ[g], gu);
+  d.bwd_carryJ[g] = gj;
+  return gj;
+}
+
 // Gathers the adjoint at the arrival cell of the entries [0, cnt) of the sorted row at pr0
 // (a spike at step n, window phase phi; arrivals inside the same window), adds it to gsum and
 // returns the wavefront's sum of amplitude * adjoint in every lane.
@@ -676,9 +691,13 @@ __device__ __forceinline__ float near_gather(const Dev& d, const float* __restri
 //   gU[n] = (1 - s) carry + sigma'(U - theta) (dL/dcount + s G) + dL/dU[n]
 //   carry <- alpha gU[n] + E,  E = -(1 / vdot)(1 / tau) G for a spike in the spike-time mode
 // (see bwd_update)
+template <bool SYN>
 __global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, long long T,
                                                          const float* __restrict__ dL_dcount,
                                                          const float* __restrict__ dL_dU) {
+  pin_args(d.gwin, d.tapeU, d.bwd_carry, d.bwd_carryJ, d.row_ptr, d.nearcnt, d.Gacc, d.synb, d.gsum,
+           d.N, d.B, d.BN, d.W, d.wshift, d.d_max, d.R, d.dbits, d.dmask, d.surrogate, d.alpha, d.alpha_s,
+           d.theta, d.v_reset, d.dt, d.tau, n, T, dL_dcount, dL_dU);
   const int g = blockIdx.x * kBlock + threadIdx.x;
   const bool act = g < d.BN;
   const int phi = (int)(n & (long long)(d.W - 1));
@@ -754,7 +773,7 @@ __global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, lon
   if (act) {
     float gu;
     d.bwd_carry[g] = bwd_update(d, n, U, Uprev, s, carry, inner, G, dU, &gu);
-    gwin[(size_t)phi * d.BN + g] = gu;
+    gwin[(size_t)phi * d.BN + g] = SYN ? bwd_receiver(d, g, gu) : gu;
   }
 }
 

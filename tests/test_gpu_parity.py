@@ -269,6 +269,20 @@ def test_backward_spike_time_mode(kind, cap, continuous):
     assert np.linalg.norm(g_on - g_off) > 1e-3 * np.linalg.norm(g_on)
 
 
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 4), ("sorted", 6)])
+@pytest.mark.parametrize("mode", [0, 2])
+def test_first_order_synapse_forward_backward(kind, cap, mode):
+    """Synaptic current state with its own time constant (Section 2.1 eq. 1): the events jump
+    into it, the membrane integrates it; continuous delays decay with that time constant."""
+    wl = synth.ragged_network(150, 300, 30, seed=15, rate_hz=250.0, t=160, b=2, continuous=True,
+                              w_mean=0.004, w_std=0.004)
+    wl.tau_syn_ms = 1.7
+    ref = _compare_backward(wl, KINDS[kind], cap, 160, 2, surrogate=mode, tape_spike_capacity=2 * 160 * 150)
+    assert ref.spikes.sum() > 100
+    plain = oracle.Run(synth.Workload(**{**wl.__dict__, "tau_syn_ms": 0.0}), KINDS[kind], cap, n_steps=160, batch=2)
+    assert not np.array_equal(plain.U, ref.U)      # the synaptic state changes the dynamics
+
+
 @pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 32), ("fifo", 2), ("sorted", 128)])
 def test_cfg1_forward_backward(kind, cap):
     """Config 1 (1,000 neurons, fan-out 100, batch 16, 2,000 steps), MSE spike-count loss."""
