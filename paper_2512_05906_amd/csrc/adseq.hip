@@ -62,6 +62,7 @@ struct BlkCtr {
 };
 
 struct ExpCoef { double c[21]; };
+struct RowSpan { long long r0, r1; };
 
 struct Dev {
   int N, B, BN, R, C, kind, dbits, d_max;
@@ -130,10 +131,11 @@ struct Dev {
   long long* step_evoff;  // FIFO/SORTED: events emitted before step n (index of its first admission flag)
   int* tape_spk;
   long long* tape_evb;
+  RowSpan* tape_row;    // FIFO/SORTED: row bounds of every recorded spike
   unsigned char* tape_adm;
   float* bwd_ring;
   float* bwd_carry;
-  float* bwd_G;
+  float* bwd_G;         // FIFO/SORTED: [fsplit][BN] partial queue terms of the spikes of the step being swept
   Counters* ctr;
   BlkCtr* blk;   // FIFO / SORTED: [nblk + kFanoutBlocks]
   int nblk;      // neuron blocks of a step launch: ceil(BN / 256)
@@ -265,47 +267,64 @@ __global__ __launch_bounds__(kBlock) void k_copy_i32(const int* __restrict__ src
 
 // ---------------------------------------------------------------- backward (FIFO / SORTED)
 
-// Queue term of the reverse sweep at step n: one block per recorded spike (b, i, n).  Gathers the
-// adjoint at each admitted event's arrival slot, reduces G_i, and accumulates the weight and
-// delay gradients of the row.
-template <bool ATOMIC>
-__global__ __launch_bounds__(kBlock) void k_bwd_gather(Dev d, long long n, long long T, float dscale,
-                                                       float* __restrict__ grad_w,
-                                                       float* __restrict__ grad_d) {
+// Queue term of the reverse sweep at step n for the bounded kinds: fsplit blocks per recorded
+// spike (b, i, n), the spikes being tape entries [off, off + gridDim.x / fsplit).  Block (e, c)
+// takes share c of the row (entries c * 256 .. + 255 of every fsplit * 256), four entries per
+// thread in flight: row entry + admission flag, then the adjoint at the event's arrival slot of
+// the adjoint delay line, then the gradient sums (atomics that return nothing: for one trial a
+// synapse gets at most one term per launch, so the result is still deterministic) and the
+// block's partial queue term.
+__global__ __launch_bounds__(kBlock) void k_bwd_rows(Dev d, long long n, long long T, float dscale,
+                                                     float* __restrict__ grad_w, float* __restrict__ grad_d,
+                                                     long long off) {
   __shared__ float red[kBlock / 64];
-  const long long off = d.step_off[n];
-  const int cnt = (int)(d.step_off[n + 1] - off);
+  const int e = blockIdx.x / d.fsplit, c = blockIdx.x - e * d.fsplit;
+  const int g = d.tape_spk[off + e];
+  const long long evb = d.tape_evb[off + e];
+  const RowSpan row = d.tape_row[off + e];
+  const int b = d.B == 1 ? 0 : g / d.N;
   const int m = (int)(n % d.R);
-  for (int e = blockIdx.x; e < cnt; e += gridDim.x) {
-    const int g = d.tape_spk[off + e];
-    const int b = g / d.N, i = g - b * d.N;
-    const long long r0 = d.row_ptr[i], r1 = d.row_ptr[i + 1];
-    const long long evb = d.tape_evb[off + e];
-    float G = 0.0f;
-    for (long long p = r0 + threadIdx.x; p < r1; p += kBlock) {
-      const unsigned pk = d.packed[p];
-      const int D = (int)(pk & d.dmask);
-      const int col = (int)(pk >> d.dbits);
-      if (n + D >= T) continue;                               // not delivered inside the run
-      if (!d.tape_adm[evb + (p - r0)]) continue;              // refused by a full queue
-      int slot = m + D; if (slot >= d.R) slot -= d.R;
-      const float gv = d.bwd_ring[(size_t)slot * d.BN + (size_t)b * d.N + col];
-      const float a = d.continuous ? d.amp[p] : d.weight[p];
-      const float f = d.continuous ? d.fdec[p] : 1.0f;
-      G += a * gv;
-      const float gw = f * gv, gd = a * dscale * gv;
-      if (ATOMIC) { unsafeAtomicAdd(&grad_w[p], gw); unsafeAtomicAdd(&grad_d[p], gd); }
-      else { grad_w[p] += gw; grad_d[p] += gd; }
+  const long long stride = (long long)d.fsplit * kBlock;
+  float G = 0.0f;
+  for (long long p0 = row.r0 + (long long)c * kBlock + threadIdx.x; p0 < row.r1; p0 += 4 * stride) {
+    long long p[4]; bool use[4]; unsigned pk[4]; unsigned char adm[4]; float a[4], f[4], gv[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      p[j] = p0 + j * stride;
+      use[j] = p[j] < row.r1;
+      pk[j] = 0; adm[j] = 0; a[j] = 0.0f; f[j] = 1.0f;
+      if (use[j]) {
+        pk[j] = d.packed[p[j]];
+        adm[j] = d.tape_adm[evb + (p[j] - row.r0)];
+        a[j] = d.continuous ? d.amp[p[j]] : d.weight[p[j]];
+        if (d.continuous) f[j] = d.fdec[p[j]];
+      }
     }
-    G = wave_sum_f(G);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = G;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      float t = 0.0f;
-      for (int w = 0; w < kBlock / 64; ++w) t += red[w];
-      d.bwd_G[g] = t;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int D = (int)(pk[j] & d.dmask);
+      use[j] = use[j] && adm[j] != 0 && n + D < T;   // admitted, and delivered inside the run
+      gv[j] = 0.0f;
+      if (use[j]) {
+        int slot = m + D; if (slot >= d.R) slot -= d.R;
+        gv[j] = d.bwd_ring[(size_t)slot * d.BN + (size_t)b * d.N + (pk[j] >> d.dbits)];
+      }
     }
-    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (use[j]) {
+        G += a[j] * gv[j];
+        unsafeAtomicAdd(&grad_w[p[j]], f[j] * gv[j]);
+        unsafeAtomicAdd(&grad_d[p[j]], a[j] * dscale * gv[j]);
+      }
+  }
+  G = wave_sum_f(G);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = G;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float t = 0.0f;
+    for (int w = 0; w < kBlock / 64; ++w) t += red[w];
+    d.bwd_G[(size_t)c * d.BN + g] = t;
   }
 }
 
@@ -313,7 +332,7 @@ __global__ __launch_bounds__(kBlock) void k_bwd_gather(Dev d, long long n, long 
 __global__ __launch_bounds__(kBlock) void k_bwd_neurons(Dev d, long long n,
                                                         const float* __restrict__ dL_dcount,
                                                         const float* __restrict__ dL_dU) {
-  pin_args(d.tapeU, d.bwd_carry, d.bwd_carryJ, d.bwd_G, d.bwd_ring, d.BN, d.R, d.surrogate, d.alpha, d.alpha_s,
+  pin_args(d.tapeU, d.bwd_carry, d.bwd_carryJ, d.bwd_G, d.bwd_ring, d.BN, d.R, d.fsplit, d.surrogate, d.alpha, d.alpha_s,
            d.theta, d.v_reset, d.dt, d.tau, n, dL_dcount, dL_dU);
   const int g = blockIdx.x * kBlock + threadIdx.x;
   if (g >= d.BN) return;
@@ -321,8 +340,11 @@ __global__ __launch_bounds__(kBlock) void k_bwd_neurons(Dev d, long long n,
   const float Uprev = (d.surrogate == ADSEQ_GRAD_SPIKE_TIME && n > 0) ? d.tapeU[(size_t)(n - 1) * d.BN + g] : 0.0f;
   const bool s = U >= d.theta;
   float gu;
+  float G = 0.0f;
+  if (s)
+    for (int c = 0; c < d.fsplit; ++c) G += d.bwd_G[(size_t)c * d.BN + g];   // the shares of the spike's row
   d.bwd_carry[g] = bwd_update(d, n, U, Uprev, s, d.bwd_carry[g], dL_dcount ? dL_dcount[g] : 0.0f,
-                              s ? d.bwd_G[g] : 0.0f, dL_dU ? dL_dU[(size_t)n * d.BN + g] : 0.0f, &gu);
+                              G, dL_dU ? dL_dU[(size_t)n * d.BN + g] : 0.0f, &gu);
   d.bwd_ring[(size_t)(n % d.R) * d.BN + g] = bwd_receiver(d, g, gu);
 }
 
@@ -356,7 +378,7 @@ namespace {
 struct Layout {
   size_t V, J, bwd_carryJ, win, spike_bits, slot, fkey, famp, vmask, occ, head, min_k, cnt, cont, c_head, pool_p, pool_t, pool_next,
       pool_k, pool_a, spk_words, stepcnt, packed, a_q, synf, synb, dstart, nearcnt, perm, rowsum, rowlen, ebuf, ecnt, amp, fdec, tapeU,
-      tape_bits, spk_count, step_off, step_evoff, tape_spk, tape_evb, tape_adm, bwd_ring, bwd_carry, bwd_G, gwin, Gacc, gsum, ctr, blk,
+      tape_bits, spk_count, step_off, step_evoff, tape_spk, tape_evb, tape_row, tape_adm, bwd_ring, bwd_carry, bwd_G, gwin, Gacc, gsum, ctr, blk,
       total;
   long long spike_cap, event_cap, pool_cap;
   int R, dbits, nblk, words;
@@ -508,12 +530,13 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->step_evoff = take(c->record_tape && bounded ? (T + 1) * 8 : 0);
   L->tape_spk = take(bounded ? (size_t)L->spike_cap * 4 : 0);
   L->tape_evb = take(bounded ? (size_t)L->spike_cap * 8 : 0);
+  L->tape_row = take(bounded ? (size_t)L->spike_cap * sizeof(RowSpan) : 0);
   L->tape_adm = take((size_t)L->event_cap);
   const bool tape = c->record_tape != 0;
   L->bwd_ring = take(tape && bounded ? (size_t)L->R * BN * 4 : 0);
   L->bwd_carry = take(tape ? BN * 4 : 0);
   L->bwd_carryJ = take(tape && c->tau_syn_ms > 0.0f ? BN * 4 : 0);
-  L->bwd_G = take(tape && bounded ? BN * 4 : 0);
+  L->bwd_G = take(tape && bounded ? (size_t)kFanSplitMax * BN * 4 : 0);
   L->gwin = take(tape && !bounded ? 2 * (size_t)L->W * BN * 4 : 0);
   L->Gacc = take(tape && !bounded ? (size_t)L->R * BN * 4 : 0);
   L->gsum = take(tape && !bounded ? S * 4 : 0);
@@ -824,6 +847,7 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   d.tapeU = (float*)(ws + L.tapeU); d.step_off = (long long*)(ws + L.step_off);
   d.step_evoff = (long long*)(ws + L.step_evoff);
   d.tape_spk = (int*)(ws + L.tape_spk); d.tape_evb = (long long*)(ws + L.tape_evb);
+  d.tape_row = (RowSpan*)(ws + L.tape_row);
   d.tape_adm = (unsigned char*)(ws + L.tape_adm);
   d.bwd_ring = (float*)(ws + L.bwd_ring); d.bwd_carry = (float*)(ws + L.bwd_carry);
   d.bwd_G = (float*)(ws + L.bwd_G);
@@ -970,8 +994,8 @@ int adseq_backward(adseq_t* h, const float* dL_dcount, const float* dL_dU, float
   const long long T = h->next_step;
   // gradient per unit the delay was given in: 1/tau per ms, dt/tau per step
   const float dscale = d.continuous ? (float)(1.0 / (double)d.tau) : (float)((double)d.dt / (double)d.tau);
-  const dim3 block(kBlock), gn(grid_for((size_t)d.BN)), gg(kFanoutBlocks);
-  const bool bounded = d.kind != ADSEQ_RING, atomic = d.B > 1;
+  const dim3 block(kBlock), gn(grid_for((size_t)d.BN));
+  const bool bounded = d.kind != ADSEQ_RING;
   if (!bounded) {
     ring_backward_launch(h, st, T, dscale, dL_dcount, dL_dU, grad_w, grad_d);
     HIP_TRY(h, hipGetLastError());
@@ -982,10 +1006,16 @@ int adseq_backward(adseq_t* h, const float* dL_dcount, const float* dL_dU, float
   fill_u32(st, grad_w, 0u, (size_t)d.S);
   fill_u32(st, grad_d, 0u, (size_t)d.S);
   fill_u32(st, d.bwd_ring, 0u, (size_t)d.R * d.BN);
+  // where the spikes of every step sit on the tape (the launch grids are sized by it)
+  std::vector<long long> offs((size_t)T + 1);
+  HIP_TRY(h, hipMemcpyAsync(offs.data(), d.step_off, sizeof(long long) * ((size_t)T + 1), hipMemcpyDeviceToHost, st));
+  HIP_TRY(h, hipStreamSynchronize(st));
   mark(h, st, -1);
   for (long long n = T - 1; n >= 0; --n) {
-    if (atomic) hipLaunchKernelGGL((k_bwd_gather<true>), gg, block, 0, st, d, n, T, dscale, grad_w, grad_d);
-    else hipLaunchKernelGGL((k_bwd_gather<false>), gg, block, 0, st, d, n, T, dscale, grad_w, grad_d);
+    const long long cnt = offs[n + 1] - offs[n];
+    if (cnt > 0)
+      hipLaunchKernelGGL(k_bwd_rows, dim3((unsigned)(cnt * d.fsplit)), block, 0, st, d, n, T, dscale, grad_w, grad_d,
+                         offs[n]);
     mark(h, st, 2);
     hipLaunchKernelGGL(k_bwd_neurons, gn, block, 0, st, d, n, dL_dcount, dL_dU);
     mark(h, st, 3);

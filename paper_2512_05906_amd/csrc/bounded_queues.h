@@ -647,7 +647,11 @@ __global__ __launch_bounds__(kBlock) void k_fanout_step(Dev d, long long n, int 
             const bool ev_fits = evb + len <= d.event_cap;
             if (!ev_fits) evb = -1;
             if (c == 0 && threadIdx.x == 0) {
-              if (fits) { d.tape_spk[pre_s + rank0 + j] = gs[j]; d.tape_evb[pre_s + rank0 + j] = evb; }
+              if (fits) {
+                d.tape_spk[pre_s + rank0 + j] = gs[j]; d.tape_evb[pre_s + rank0 + j] = evb;
+                RowSpan rsn; rsn.r0 = rr[j].r0; rsn.r1 = rr[j].r1;
+                d.tape_row[pre_s + rank0 + j] = rsn;
+              }
               else atomicOr(&d.ctr->err, ERR_TAPE_SPIKES);
               if (!ev_fits) atomicOr(&d.ctr->err, ERR_TAPE_EVENTS);
             }
