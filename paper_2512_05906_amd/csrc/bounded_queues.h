@@ -554,6 +554,28 @@ __device__ __forceinline__ void offer_rows(const Dev& d, long long n, const RowR
   }
 }
 
+// Takes the next NROWS (<= 4) spikes of neuron block nb from its ballot words and requests their
+// row bounds (and, for share 0, the row sums).  A macro, so that the ballot words stay in registers.
+#define ADSEQ_LOAD_GROUP(NROWS)                                                                         \
+  _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                       \
+    rr[j].b = 0; rr[j].r0 = 0; rr[j].r1 = 0; rr[j].tbase = -1; rr[j].first = (long long)c * kBlock; gs[j] = 0; \
+    if (j < (NROWS)) {                                                                                  \
+      while (!bits) { ++x; bits = x == 1 ? w[1] : x == 2 ? w[2] : w[3]; }                               \
+      const int bit = __ffsll((long long)bits) - 1;                                                     \
+      bits &= bits - 1;                                                                                 \
+      gs[j] = (nb * (kBlock / 64) + x) * 64 + bit;                                                      \
+    }                                                                                                   \
+  }                                                                                                     \
+  _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                       \
+    rs[j] = 0;                                                                                          \
+    if (j < (NROWS)) {                                                                                  \
+      rr[j].b = d.B == 1 ? 0 : gs[j] / d.N;                                                             \
+      const int i = gs[j] - rr[j].b * d.N;                                                              \
+      rr[j].r0 = d.row_ptr[i]; rr[j].r1 = d.row_ptr[i + 1];                                             \
+      if (c == 0 && threadIdx.x == 0) rs[j] = d.rowsum[i];                                              \
+    }                                                                                                   \
+  }
+
 // Closed-loop fan-out of step n: fsplit blocks per neuron block.  Block (nb, c) reads the four
 // ballot words that neuron block nb of this step's k_neurons launch left (most find them zero
 // and leave) and offers share c -- entries c * 256 .. c * 256 + 255 of every fsplit * 256 -- of
@@ -578,6 +600,13 @@ __global__ __launch_bounds__(kBlock) void k_fanout_step(Dev d, long long n, int 
            d.max_steps, d.spike_cap, d.event_cap, d.pool_cap, n);
   long long c_off = 0, s_off = 0;   // offered events and their amplitude sum (share 0, thread 0)
   {
+    // the first group's row bounds are requested before the prefix sums, so that the two overlap
+    int x = 0;
+    unsigned long long bits = w[0];
+    RowRef rr[4];
+    int gs[4];
+    long long rs[4];
+    { ADSEQ_LOAD_GROUP(nspk < 4 ? nspk : 4) }
     long long pre_s = 0, pre_e = 0;
     if (record) {
       // spikes and events of the neuron blocks before nb (the closing block: of all blocks)
@@ -609,33 +638,9 @@ __global__ __launch_bounds__(kBlock) void k_fanout_step(Dev d, long long n, int 
       }
       pre_s += off; pre_e += evoff;
     }
-    int x = 0;
-    unsigned long long bits = w[0];
     for (int rank0 = 0; rank0 < nspk; rank0 += 4) {
-      RowRef rr[4];
       const int nrows = nspk - rank0 < 4 ? nspk - rank0 : 4;
-      int gs[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        rr[j].b = 0; rr[j].r0 = 0; rr[j].r1 = 0; rr[j].tbase = -1; rr[j].first = (long long)c * kBlock; gs[j] = 0;
-        if (j < nrows) {
-          while (!bits) { ++x; bits = x == 1 ? w[1] : x == 2 ? w[2] : w[3]; }
-          const int bit = __ffsll((long long)bits) - 1;
-          bits &= bits - 1;
-          gs[j] = (nb * (kBlock / 64) + x) * 64 + bit;
-        }
-      }
-      long long rs[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        rs[j] = 0;
-        if (j < nrows) {
-          rr[j].b = d.B == 1 ? 0 : gs[j] / d.N;
-          const int i = gs[j] - rr[j].b * d.N;
-          rr[j].r0 = d.row_ptr[i]; rr[j].r1 = d.row_ptr[i + 1];
-          if (c == 0 && threadIdx.x == 0) rs[j] = d.rowsum[i];
-        }
-      }
+      if (rank0 > 0) { ADSEQ_LOAD_GROUP(nrows) }
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         if (j < nrows) {
@@ -669,6 +674,8 @@ __global__ __launch_bounds__(kBlock) void k_fanout_step(Dev d, long long n, int 
     atomicAdd((unsigned long long*)&bc.sum_offered, (unsigned long long)s_off);
   }
 }
+
+#undef ADSEQ_LOAD_GROUP
 
 // Open-loop fan-out: the spikes come as the caller's list of flat neuron indices; one block per
 // spike (grid-stride over the list).
