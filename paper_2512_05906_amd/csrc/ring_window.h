@@ -547,10 +547,9 @@ __device__ __forceinline__ void role_acc(const Dev& d, int* tile, long long k0, 
     const int v = tile[x];
     const int r = x >> d.tp_shift;
     const long long t = (long long)part * tp + (x & (tp - 1));
-    if (v != 0 && t < d.BN) {
-      int* cell = &win[(size_t)r * d.BN + t];
-      *cell = wrap_add(*cell, v);
-    }
+    // the part's cells have no other writer during this pass; an atomic without return value, so
+    // that nobody waits for a load
+    if (v != 0 && t < d.BN) atomicAdd(&win[(size_t)r * d.BN + t], v);
   }
 }
 
@@ -782,7 +781,7 @@ __global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, lon
 // virtual block vb of nvb.  The piece of each spike's sorted row that arrives in the window
 // gathers its adjoints from the window (6.4 MB: the L2 holds it), adds them to gsum, and the
 // wavefront's sum of amplitude * adjoint is added to Gacc[n mod R][g] (one wavefront per piece,
-// one piece per spike and window: plain update).
+// one piece per spike and window).
 __device__ __forceinline__ void role_gather(const Dev& d, ExpandLds& L, long long k0, long long n_lo, long long n_hi,
                                             long long T, int vb, int nvb) {
   if (threadIdx.x == 0) { L.qn = 0; L.qhead = 0; }
@@ -792,8 +791,9 @@ __device__ __forceinline__ void role_gather(const Dev& d, ExpandLds& L, long lon
   auto finish = [&](const Seg& o, float G) {
     G = wave_sum_f(G);
     if (lane == 0) {
-      float* ga = &d.Gacc[(size_t)o.slot * d.BN + o.g];
-      *ga += G;
+      // one wavefront per piece, one piece per spike and window: the add has no competitor; an
+      // atomic without return value so that the wavefront does not wait for a load
+      unsafeAtomicAdd(&d.Gacc[(size_t)o.slot * d.BN + o.g], G);
     }
   };
   auto one = [&](const Seg& o) {
