@@ -147,7 +147,8 @@ def main():
     else:
         label = {"fan_out": "k_fanout_step (CSR fan-out, full-target drops, contender registration)",
                  "lif": "k_neurons (admission + pop + drive + LIF + spike words)",
-                 "bwd_gather": "k_bwd_gather", "bwd_neurons": "k_bwd_neurons"}
+                 "bwd_gather": "k_bwd_rows (adjoint gathers and gradient sums of the step's recorded spikes)",
+                 "bwd_neurons": "k_bwd_neurons (adjoint update)"}
     kernels = {}
     for k, v in prof.items():
         if v["launches"]:
