@@ -53,8 +53,9 @@ struct Counters {
   unsigned long long fold[3];       // scratch of k_count_spikes: spikes, events, Q8.24 sum
 };
 
-// FIFO / SORTED: private event counters of one block of k_neurons / k_fanout (one 64-byte line
-// each, so that no two blocks add to the same address; summed on demand).
+// Private event counters of one block of k_neurons / k_fanout (FIFO / SORTED) or of one virtual
+// block of the ring's staging pass (pad[0] = spikes): one 64-byte line each, so that no two blocks
+// add to the same address; summed on demand.
 struct BlkCtr {
   unsigned long long offered, admitted, delivered;
   long long sum_offered, sum_admitted, sum_delivered;
@@ -170,13 +171,54 @@ template <class... Ts> __device__ __forceinline__ void pin_args(Ts... vs) { (pin
 
 __device__ __forceinline__ int wrap_add(int a, int b) { return (int)((unsigned)a + (unsigned)b); }
 
-__device__ __forceinline__ long long wave_sum(long long v) {
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+// Inclusive scan (sum) over the 64 lanes of a wavefront with DPP row shifts and row broadcasts;
+// lane 63 ends up with the total.  Every lane of the wavefront must be active.
+__device__ __forceinline__ int dpp_scan_add(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
   return v;
 }
+// Sum of v over the wavefront, the same value in every lane.  |v| < 2^31 per lane.
+__device__ __forceinline__ long long wave_total(int v) {
+  const int lo = __builtin_amdgcn_readlane(dpp_scan_add(v & 0xffff), 63);
+  const int hi = __builtin_amdgcn_readlane(dpp_scan_add(v >> 16), 63);
+  return ((long long)hi << 16) + lo;
+}
+// The same for 64-bit values, |v| < 2^62 per lane: three slices of 21 bits.
+__device__ __forceinline__ long long wave_total64(long long v) {
+  const int s0 = __builtin_amdgcn_readlane(dpp_scan_add((int)(v & 0x1fffff)), 63);
+  const int s1 = __builtin_amdgcn_readlane(dpp_scan_add((int)((v >> 21) & 0x1fffff)), 63);
+  const int s2 = __builtin_amdgcn_readlane(dpp_scan_add((int)(v >> 42)), 63);
+  return ((long long)s2 << 42) + ((long long)s1 << 21) + s0;
+}
+
+// Sum over the wavefront, the same value in every lane; every lane must be active.  (DPP row
+// operations run at register speed; a butterfly of cross-lane shuffles goes through the LDS
+// crossbar six times in a row, which shows in the short kernels.)
+__device__ __forceinline__ long long wave_sum(long long v) { return wave_total64(v); }
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add_f(float v) {
+  return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
 __device__ __forceinline__ float wave_sum_f(float v) {
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
-  return v;
+  v = dpp_add_f<0x111, 0xf>(v); v = dpp_add_f<0x112, 0xf>(v);
+  v = dpp_add_f<0x114, 0xf>(v); v = dpp_add_f<0x118, 0xf>(v);
+  v = dpp_add_f<0x142, 0xa>(v); v = dpp_add_f<0x143, 0xc>(v);
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+// Value of lane src (src the same in every lane) in every lane, through scalar registers.
+__device__ __forceinline__ int lane_get(int v, int src) { return __builtin_amdgcn_readlane(v, src); }
+__device__ __forceinline__ unsigned lane_get(unsigned v, int src) {
+  return (unsigned)__builtin_amdgcn_readlane((int)v, src);
+}
+__device__ __forceinline__ long long lane_get(long long v, int src) {
+  const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)v, src);
+  const int hi = __builtin_amdgcn_readlane((int)(v >> 32), src);
+  return ((long long)hi << 32) | lo;
 }
 
 // Adds the block's totals of two per-thread values to two global 64-bit counters
@@ -486,7 +528,7 @@ bool make_layout(const adseq_config* c, Layout* L) {
     L->cap = (int)(per > 65536.0 ? 65536.0 : per);
   }
   L->ctr = take(sizeof(Counters));
-  L->blk = take(bounded ? ((size_t)L->nblk + fan_slots(L->nblk)) * sizeof(BlkCtr) : 0);
+  L->blk = take(bounded ? ((size_t)L->nblk + fan_slots(L->nblk)) * sizeof(BlkCtr) : kMaxBinBlocks * sizeof(BlkCtr));
   L->V = take(BN * 4);
   L->J = take(c->tau_syn_ms > 0.0f ? BN * 4 : 0);
   L->win = take(bounded ? 0 : 2 * (size_t)L->W * BN * 4);
@@ -583,6 +625,7 @@ void launch_reset(adseq* h, hipStream_t st) {
   if (d.kind == ADSEQ_RING) {
     fill_u32(st, d.win, 0u, 2 * (size_t)d.W * BN);
     fill_u32(st, d.spike_bits, 0u, (size_t)d.R * d.words * 2);
+    fill_u32(st, d.blk, 0u, kMaxBinBlocks * sizeof(BlkCtr) / 4);
   } else {
     fill_u32(st, d.occ, 0u, BN);
     fill_u32(st, d.head, 0u, BN);
@@ -655,8 +698,11 @@ void ring_open_window(adseq* h, hipStream_t st, long long k0) {
   close_group(h, st, 1);
   mark(h, st, -1);
   const long long n_lo = k0 - d.d_max > 0 ? k0 - d.d_max : 0;
+  // staging mode: 0 none (atomics), 1 one store per event, 2 ordered by part in LDS first
+  static const int sort_stage = env_pow2("ADSEQ_RING_SORTSTAGE", 1, 0, 1);
+  const int stage = d.cap > 0 ? ((sort_stage && d.P <= kSortParts) ? 2 : 1) : 0;
   hipLaunchKernelGGL(k_win_bin, dim3((unsigned)d.NB), dim3(kRingThreads), 0, st, d, k0, n_lo, k0, 0, d.NB,
-                     d.cap > 0 ? 1 : 0, h->fold_upto);
+                     stage, h->fold_upto);
   if (d.cap > 0) {
     const int parts = d.P < kMaxParts ? d.P : kMaxParts;
     hipLaunchKernelGGL(k_win_acc, dim3((unsigned)parts), dim3(kRingThreads), 0, st, d, k0, 0);
@@ -1066,6 +1112,12 @@ int adseq_counters(adseq_t* h, int64_t* out8, void* stream) {
     out8[4] = out8[3] - sum_admitted;
   }
   if (d.kind == ADSEQ_RING) {
+    // spikes and offered events up to the last window boundary: private counters of the staging
+    // pass's blocks; since then: c.fold
+    std::vector<BlkCtr> hb(kMaxBinBlocks);
+    HIP_TRY(h, hipMemcpyAsync(hb.data(), d.blk, sizeof(BlkCtr) * kMaxBinBlocks, hipMemcpyDeviceToHost, st));
+    HIP_TRY(h, hipStreamSynchronize(st));
+    for (const BlkCtr& b : hb) { out8[6] += b.pad[0]; out8[0] += (int64_t)b.offered; out8[3] += b.sum_offered; }
     out8[6] += (int64_t)c.fold[0]; out8[0] += (int64_t)c.fold[1]; out8[3] += (int64_t)c.fold[2];
     out8[2] = out8[0] - (int64_t)c.in_flight[0];
     out8[5] = out8[3] - (int64_t)c.in_flight[1];

@@ -247,31 +247,6 @@ __device__ __forceinline__ void admit_contenders(const Dev& d, int g, int K, int
   admit_overflowed<KIND, MODE>(d, g, K, take, kn, q, r, cc);
 }
 
-// Inclusive scan (sum) over the 64 lanes of a wavefront with DPP row shifts and row broadcasts;
-// lane 63 ends up with the total.  Every lane of the wavefront must be active.
-__device__ __forceinline__ int dpp_scan_add(int v) {
-  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
-  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
-  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
-  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
-  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
-  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
-  return v;
-}
-// Sum of v over the wavefront, the same value in every lane.  |v| < 2^31 per lane.
-__device__ __forceinline__ long long wave_total(int v) {
-  const int lo = __builtin_amdgcn_readlane(dpp_scan_add(v & 0xffff), 63);
-  const int hi = __builtin_amdgcn_readlane(dpp_scan_add(v >> 16), 63);
-  return ((long long)hi << 16) + lo;
-}
-// The same for 64-bit values, |v| < 2^62 per lane: three slices of 21 bits.
-__device__ __forceinline__ long long wave_total64(long long v) {
-  const int s0 = __builtin_amdgcn_readlane(dpp_scan_add((int)(v & 0x1fffff)), 63);
-  const int s1 = __builtin_amdgcn_readlane(dpp_scan_add((int)((v >> 21) & 0x1fffff)), 63);
-  const int s2 = __builtin_amdgcn_readlane(dpp_scan_add((int)(v >> 42)), 63);
-  return ((long long)s2 << 42) + ((long long)s1 << 21) + s0;
-}
-
 // Block-level event counters in LDS: [0] offered, [1] admitted, [2] delivered, [3..5] the same as
 // sums of Q8.24 amplitudes, [6] spikes, [7] events emitted by them.
 struct BlockCounts { unsigned long long c[8]; };
@@ -535,7 +510,7 @@ __device__ __forceinline__ void offer_rows(const Dev& d, long long n, const RowR
       if (cm) {
         int base = 0;
         if (lane == __ffsll((long long)cm) - 1) base = atomicAdd(&d.ctr->pool_n[0], __popcll(cm));
-        base = __shfl(base, __ffsll((long long)cm) - 1, 64);
+        base = lane_get(base, __ffsll((long long)cm) - 1);
         if (over) {
           const int x = base + __popcll(cm & ((1ull << lane) - 1ull));
           if (x >= d.pool_cap) {

@@ -253,7 +253,7 @@ __global__ __launch_bounds__(kBlock) void k_step_win(Dev d, long long n, const f
       if (m) {
         const int L = __ffsll((long long)m) - 1;
         m &= m - 1;
-        pr[j] = __shfl(r0, L, 64); cn[j] = __shfl(ncnt, L, 64); bs[j] = __shfl(b, L, 64) * d.N;
+        pr[j] = lane_get(r0, L); cn[j] = lane_get(ncnt, L); bs[j] = lane_get(b, L) * d.N;
       }
     }
     uint2 e[4];
@@ -406,10 +406,14 @@ __device__ __forceinline__ void walk_segments(const Dev& d, ExpandLds& L, const 
         if (g < d.BN) {
           const int b = (int)(g / d.N), i = (int)(g - (long long)b * d.N);
           const unsigned* ds = d.dstart + (size_t)i * nb;
+          // all loads of the spike are requested before the first is used
           const unsigned q0 = ds[dlo], q1 = ds[dhi];
           const long long r0 = d.row_ptr[i];
+          // (the row's length and sum are loaded for every spike, counted or not: under a branch
+          // of their own they would be a second round trip to memory)
+          const long long r1 = d.row_ptr[i + 1], rs = d.rowsum[i];
           sg.p0 = r0 + q0; sg.len = (int)(q1 - q0); sg.base = b * d.N; sg.g = g;
-          if (counted) { cnt[0] += 1; cnt[1] += d.row_ptr[i + 1] - r0; cnt[2] += d.rowsum[i]; }
+          cnt[0] += counted ? 1 : 0; cnt[1] += counted ? r1 - r0 : 0; cnt[2] += counted ? rs : 0;
         }
       }
       const bool has = sg.len > 0;
@@ -417,7 +421,7 @@ __device__ __forceinline__ void walk_segments(const Dev& d, ExpandLds& L, const 
       if (mask) {
         int pos = 0;
         if (lane == 0) pos = atomicAdd(&L.qn, __popcll(mask));
-        pos = __shfl(pos, 0, 64) + __popcll(mask & ((1ull << lane) - 1ull));
+        pos = __builtin_amdgcn_readfirstlane(pos) + __popcll(mask & ((1ull << lane) - 1ull));
         if (has && pos < kSegQueue) L.q[pos] = sg;
         unsigned long long ovf = __ballot(has && pos >= kSegQueue);
         while (ovf) {
@@ -434,19 +438,151 @@ __device__ __forceinline__ void walk_segments(const Dev& d, ExpandLds& L, const 
   __syncthreads();
 }
 
-// Adds the block's totals of cnt[0..3) to ctr->tape_spikes / offered / sum_offered.
-__device__ __forceinline__ void fold_counts(const Dev& d, ExpandLds& L, long long* cnt) {
+// Adds the block's totals of cnt[0..3) (spikes, their events, Q8.24 sum of those) to the private
+// counters of virtual block vb: 256 blocks adding to three shared addresses would queue up behind
+// one another at the end of the pass.
+__device__ __forceinline__ void fold_counts(const Dev& d, ExpandLds& L, long long* cnt, int vb) {
   for (int k = 0; k < 3; ++k) {
-    const long long v = wave_sum(cnt[k]);
+    const long long v = wave_total64(cnt[k]);
     if ((threadIdx.x & 63) == 0) L.red[k][threadIdx.x >> 6] = v;
   }
   __syncthreads();
-  if (threadIdx.x == 0) {
-    long long t[3] = {0, 0, 0};
-    for (int k = 0; k < 3; ++k) for (int w = 0; w < kRingWaves; ++w) t[k] += L.red[k][w];
-    if (t[0]) atomicAdd((unsigned long long*)&d.ctr->tape_spikes, (unsigned long long)t[0]);
-    if (t[1]) atomicAdd(&d.ctr->offered, (unsigned long long)t[1]);
-    if (t[2]) atomicAdd((unsigned long long*)&d.ctr->sum_offered, (unsigned long long)t[2]);
+  if (threadIdx.x < 3) {
+    const int k = threadIdx.x;
+    long long t = 0;
+    for (int w = 0; w < kRingWaves; ++w) t += L.red[k][w];
+    BlkCtr& bc = d.blk[vb & (kMaxBinBlocks - 1)];
+    unsigned long long* dst = k == 0 ? (unsigned long long*)&bc.pad[0]
+                            : k == 1 ? &bc.offered : (unsigned long long*)&bc.sum_offered;
+    if (t) atomicAdd(dst, (unsigned long long)t);
+  }
+}
+
+// LDS of the ordered staging (role_bin with stage = 2): the block's events are taken in chunks
+// of kSortChunk, ordered by target part in LDS (counting sort) and written to the staging regions
+// as runs of consecutive events, instead of one scattered 8-byte store per event.
+constexpr int kSortParts = 512;     // parts the ordered staging handles
+constexpr int kSortChunk = 8192;    // events per chunk = 8 per thread
+struct SortLds {
+  int cnt[kSortParts];              // events of the chunk per part (zero between chunks)
+  int base[kSortParts + 1];         // exclusive prefix of cnt: the part's first position in ev
+  int g0[kSortParts];               // the part's first free position of its staging region
+  int off[kSegQueue + 1];           // exclusive prefix of the queued pieces' lengths
+  int map[kSortChunk / 64];         // piece that holds the first event of each 64-event group of the chunk
+  int scan[kRingWaves];
+  uint2 ev[kSortChunk];
+};
+
+// Exclusive prefix of v over the block's threads (total in *total).  Two block barriers.
+__device__ __forceinline__ int block_scan_excl(int v, int* s_w, int* total) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int x = dpp_scan_add(v);
+  if (lane == 63) s_w[wv] = x;
+  __syncthreads();
+  int add = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kRingWaves; ++w) {
+    const int c = s_w[w];
+    if (w < wv) add += c;
+    tot += c;
+  }
+  __syncthreads();
+  *total = tot;
+  return add + x - v;
+}
+
+// Ordered staging of the pieces L.q[0, qn): see SortLds.  L.cur[part] stays the cursor of the
+// part's staging region (the pieces that overflowed the queue during the walk used it too).
+__device__ __forceinline__ void stage_sorted(const Dev& d, ExpandLds& L, SortLds& S, int* __restrict__ win,
+                                             int nparts, int vb, int qn) {
+  const int t = threadIdx.x;
+  int total = 0;
+  {
+    const int len = t < qn ? L.q[t].len : 0;
+    const int ex = block_scan_excl(len, S.scan, &total);
+    if (t < qn) S.off[t] = ex;
+    if (t == 0) S.off[qn] = total;
+    if (t < kSortParts) S.cnt[t] = 0;
+  }
+  __syncthreads();
+  const unsigned lmask = (1u << d.tp_shift) - 1u;
+  constexpr int kPer = kSortChunk / kRingThreads;
+  for (int c0 = 0; c0 < total; c0 += kSortChunk) {
+    const int cend = c0 + kSortChunk < total ? c0 + kSortChunk : total;
+    // every piece enters itself for the 64-event groups of the chunk that start inside it
+    if (t < qn) {
+      const int p_lo = S.off[t], p_hi = S.off[t + 1] < cend ? S.off[t + 1] : cend;
+      int b = ((p_lo > c0 ? p_lo : c0) + 63) >> 6;
+      for (; (b << 6) < p_hi; ++b) S.map[b - (c0 >> 6)] = t;
+    }
+    __syncthreads();
+    // A: this thread's events of the chunk (all row entries requested before the first is used):
+    // piece, row entry, part, rank within (chunk, part)
+    uint2 e[kPer]; int dlo[kPer], tb[kPer];
+#pragma unroll
+    for (int m = 0; m < kPer; ++m) {
+      const int x = c0 + m * kRingThreads + t;
+      e[m] = make_uint2(0u, 0u); dlo[m] = 0; tb[m] = -1;
+      if (x < cend) {
+        int lo = S.map[(x - c0) >> 6];
+        while (x >= S.off[lo + 1]) ++lo;
+        const Seg& o = L.q[lo];
+        dlo[m] = o.dlo; tb[m] = o.base;
+        e[m] = load_stream(&d.synf[o.p0 + (x - S.off[lo])]);
+      }
+    }
+    unsigned w0[kPer]; int pr[kPer];   // staged word | part << 16, rank
+#pragma unroll
+    for (int m = 0; m < kPer; ++m) {
+      w0[m] = 0u; pr[m] = -1;
+      if (tb[m] >= 0) {
+        const int r = (int)(e[m].x & d.dmask) - dlo[m];
+        const int gt = tb[m] + (int)(e[m].x >> d.dbits);
+        const int part = gt >> d.tp_shift;
+        if (part < nparts) {
+          w0[m] = ((unsigned)part << 16) | ((unsigned)r << d.tp_shift) | ((unsigned)gt & lmask);
+          pr[m] = atomicAdd(&S.cnt[part], 1);
+        } else {
+          atomicAdd(&win[(size_t)r * d.BN + gt], (int)e[m].y);
+        }
+      }
+    }
+    __syncthreads();
+    // B: positions of the parts in the chunk and in their staging regions
+    {
+      const int c = t < nparts ? S.cnt[t] : 0;
+      int tot;
+      const int ex = block_scan_excl(c, S.scan, &tot);
+      if (t < nparts) {
+        S.base[t] = ex;
+        S.g0[t] = L.cur[t];
+        L.cur[t] += c;
+        S.cnt[t] = 0;
+      }
+      if (t == 0) S.base[nparts] = tot;
+    }
+    __syncthreads();
+    // C: order the chunk by part
+#pragma unroll
+    for (int m = 0; m < kPer; ++m)
+      if (pr[m] >= 0) S.ev[S.base[w0[m] >> 16] + pr[m]] = make_uint2(w0[m], e[m].y);
+    __syncthreads();
+    // D: write the runs
+    const int staged = S.base[nparts];
+    for (int x = t; x < staged; x += kRingThreads) {
+      const uint2 e = S.ev[x];
+      const int part = (int)(e.x >> 16);
+      const unsigned word = e.x & 0xffffu;
+      const int pos = S.g0[part] + (x - S.base[part]);
+      if (pos < d.cap) {
+        d.ebuf[((size_t)part * d.NB + vb) * d.cap + pos] = make_uint2(word, e.y);
+      } else {
+        const int r = (int)(word >> d.tp_shift);
+        const long long gt = ((long long)part << d.tp_shift) | (word & lmask);
+        atomicAdd(&win[(size_t)r * d.BN + gt], (int)e.y);
+      }
+    }
+    __syncthreads();
   }
 }
 
@@ -456,8 +592,8 @@ __device__ __forceinline__ void fold_counts(const Dev& d, ExpandLds& L, long lon
 // in flight) and stage the events by target part.  stage = 0: every event is added to the window
 // with a global atomic instead.  With stage != 0, nvb must be d.NB (one staging region per part
 // and virtual block).
-__device__ __forceinline__ void role_bin(const Dev& d, ExpandLds& L, long long k0, long long n_lo, long long n_hi,
-                                         int vb, int nvb, int stage, long long count_from) {
+__device__ __forceinline__ void role_bin(const Dev& d, ExpandLds& L, SortLds& S, long long k0, long long n_lo,
+                                         long long n_hi, int vb, int nvb, int stage, long long count_from) {
   const int nparts = (stage && d.cap > 0) ? (d.P < kMaxParts ? d.P : kMaxParts) : 0;
   int* __restrict__ win = win_of(d, k0);
   for (int x = threadIdx.x; x < nparts; x += kRingThreads) L.cur[x] = 0;
@@ -472,33 +608,39 @@ __device__ __forceinline__ void role_bin(const Dev& d, ExpandLds& L, long long k
   };
   long long cnt[3] = {0, 0, 0};
   walk_segments(d, L, d.spike_bits, true, k0, n_lo, n_hi, -1, vb, nvb, count_from, cnt, one);
+  // counters first: their atomics complete while the events are staged
+  if (count_from < n_hi) fold_counts(d, L, cnt, vb);
   const int qn = L.qn < kSegQueue ? L.qn : kSegQueue;
-  for (;;) {
-    int t = 0;
-    if (lane == 0) t = atomicAdd(&L.qhead, 4);
-    t = __shfl(t, 0, 64);
-    if (t >= qn) break;
-    Seg o[4];
-    uint2 ev[4][2];
+  if (stage == 2 && nparts > 0 && nparts <= kSortParts) {
+    stage_sorted(d, L, S, win, nparts, vb, qn);
+  } else {
+    for (;;) {
+      int t = 0;
+      if (lane == 0) t = atomicAdd(&L.qhead, 4);
+      t = __builtin_amdgcn_readfirstlane(t);
+      if (t >= qn) break;
+      Seg o[4];
+      uint2 ev[4][2];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      o[j].len = 0;
-      if (t + j < qn) o[j] = L.q[t + j];
+      for (int j = 0; j < 4; ++j) {
+        o[j].len = 0;
+        if (t + j < qn) o[j] = L.q[t + j];
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        ev[j][h] = make_uint2(0u, 0u);
-        if (lane + 64 * h < o[j].len) ev[j][h] = load_stream(&d.synf[o[j].p0 + lane + 64 * h]);
+        for (int h = 0; h < 2; ++h) {
+          ev[j][h] = make_uint2(0u, 0u);
+          if (lane + 64 * h < o[j].len) ev[j][h] = load_stream(&d.synf[o[j].p0 + lane + 64 * h]);
+        }
       }
-    }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+      for (int j = 0; j < 4; ++j) {
 #pragma unroll
-      for (int h = 0; h < 2; ++h)
-        if (lane + 64 * h < o[j].len)
-          stage_event(d, win, L.cur, nparts, vb, ev[j][h].x, (int)ev[j][h].y, o[j].dlo, o[j].base);
-      for (int q = 128 + lane; q < o[j].len; q += 64) {
-        const uint2 e = d.synf[o[j].p0 + q];
-        stage_event(d, win, L.cur, nparts, vb, e.x, (int)e.y, o[j].dlo, o[j].base);
+        for (int h = 0; h < 2; ++h)
+          if (lane + 64 * h < o[j].len)
+            stage_event(d, win, L.cur, nparts, vb, ev[j][h].x, (int)ev[j][h].y, o[j].dlo, o[j].base);
+        for (int q = 128 + lane; q < o[j].len; q += 64) {
+          const uint2 e = d.synf[o[j].p0 + q];
+          stage_event(d, win, L.cur, nparts, vb, e.x, (int)e.y, o[j].dlo, o[j].base);
+        }
       }
     }
   }
@@ -507,7 +649,6 @@ __device__ __forceinline__ void role_bin(const Dev& d, ExpandLds& L, long long k
     const int c = L.cur[x];
     d.ecnt[(size_t)x * d.NB + vb] = c < d.cap ? c : d.cap;
   }
-  if (count_from < n_hi) fold_counts(d, L, cnt);
 }
 
 // Accumulation role (pass 2): sums the staged events of target part `part` into an LDS tile
@@ -558,7 +699,8 @@ __device__ __forceinline__ void role_acc(const Dev& d, int* tile, long long k0, 
 __global__ __launch_bounds__(kRingThreads) void k_win_bin(Dev d, long long k0, long long n_lo, long long n_hi,
                                                           int vb0, int nvb, int stage, long long count_from) {
   __shared__ ExpandLds L;
-  role_bin(d, L, k0, n_lo, n_hi, vb0 + (int)blockIdx.x, nvb, stage, count_from);
+  __shared__ SortLds S;
+  role_bin(d, L, S, k0, n_lo, n_hi, vb0 + (int)blockIdx.x, nvb, stage, count_from);
 }
 __global__ __launch_bounds__(kRingThreads) void k_win_acc(Dev d, long long k0, int p0) {
   __shared__ int tile[kMaxTileCells];
@@ -680,8 +822,7 @@ __device__ __forceinline__ float near_gather(const Dev& d, const float* __restri
       unsafeAtomicAdd(&d.gsum[pr0 + q], gv);
     }
   }
-  for (int o = 32; o > 0; o >>= 1) G += __shfl_xor(G, o, 64);
-  return G;
+  return wave_sum_f(G);
 }
 
 // Reverse step n: queue term of the block's spikes = far part (left in Gacc by the windows
@@ -738,7 +879,7 @@ __global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, lon
         const int L = __ffsll((long long)m) - 1;
         m &= m - 1;
         Ls[j] = L;
-        pr[j] = __shfl(r0, L, 64); cn[j] = __shfl(ncnt, L, 64); bs[j] = __shfl(b, L, 64) * d.N;
+        pr[j] = lane_get(r0, L); cn[j] = lane_get(ncnt, L); bs[j] = lane_get(b, L) * d.N;
       }
     }
     uint2 e[4];
@@ -764,7 +905,7 @@ __global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, lon
         part = __uint_as_float(e[j].y) * gv[j];
         unsafeAtomicAdd(&d.gsum[pr[j] + lane], gv[j]);
       }
-      for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
+      part = wave_sum_f(part);
       if (cn[j] > 64u) part += near_gather(d, gwin, n, T, phi, pr[j] + 64, cn[j] - 64u, bs[j]);
       if (lane == Ls[j]) G += part;
     }
@@ -812,7 +953,7 @@ __device__ __forceinline__ void role_gather(const Dev& d, ExpandLds& L, long lon
   for (;;) {
     int t = 0;
     if (lane == 0) t = atomicAdd(&L.qhead, 4);
-    t = __shfl(t, 0, 64);
+    t = __builtin_amdgcn_readfirstlane(t);
     if (t >= qn) break;
     Seg o[4];
     uint2 ev[4][2];
