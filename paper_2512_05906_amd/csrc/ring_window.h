@@ -16,7 +16,9 @@
 //     D in [k0 - n, k0 - n + W) of its row, read with full-width loads.
 // The expansion does not scatter with one memory-side atomic per event.  It stages the events
 // by target range ("part") into per-(part, block) regions of a buffer (LDS cursors, no global
-// atomics); then every part is given to one workgroup, which sums the part's events into an LDS
+// atomics; a block first orders a chunk of its events by part in LDS, so that a region receives
+// runs of consecutive events instead of one scattered store per event); then every part is given
+// to one workgroup, which sums the part's events into an LDS
 // tile [W][targets of the part] with LDS atomics and adds the tile to win with coalesced
 // accesses.  Events that do not fit their region fall back to a global atomic on win, so the
 // result never depends on the staging capacity.
