@@ -82,6 +82,17 @@ def test_ring_window_length_and_staging_capacity(window, stage, monkeypatch):
     assert ref.spikes.sum() > 300
 
 
+def test_ring_rows_longer_than_a_staging_chunk():
+    """Rows of up to 60,000 synapses with delays of 1..6 steps: the piece of a row that lands in
+    one window (4 steps here) holds tens of thousands of events, so one piece spans several of
+    the 8,192-event chunks in which the window expansion orders its events, and 40 targets make
+    a single target part."""
+    wl = synth.ragged_network(40, 60000, 6, seed=21, rate_hz=300.0, t=80, b=1, w_mean=0.00002, w_std=0.00002,
+                              empty_rows=False)
+    ref, _ = _compare_forward(wl, oracle.RING, 0)
+    assert ref.spikes.sum() > 20 and ref.counters()["enqueued"] > 500000
+
+
 @pytest.mark.parametrize("window", [4, 32])
 def test_ring_backward_other_window_lengths(window, monkeypatch):
     monkeypatch.setenv("ADSEQ_RING_WINDOW", str(window))
