@@ -35,6 +35,13 @@
 //                   an incoming event is refused iff the target already holds
 //                   `capacity` undelivered events at that point of the canonical
 //                   order (step, source index, position in the row)
+//   per-synapse     kind 3: the paper's own organisation (Section 4.1 listing 1:
+//                   one queue per synapse; Section 4.3 "FIFORing(n)",
+//                   "SingleSpike(Hold)" = capacity 1): an incoming event is
+//                   refused iff its own synapse already holds `capacity`
+//                   undelivered events; all events of a synapse share one delay,
+//                   so arrival order is emission order and an ordered queue
+//                   ("SortedArray") gives the same result
 //   continuous d    arrival D = max(1, ceil(d/dt)) steps, amplitude
 //                   a = w * exp(-(D*dt - d)/tau_m)
 //   backward        event-sparse: the queue term exists only for emitted spikes
@@ -61,7 +68,7 @@ extern "C" {
 
 struct oracle_config {
   int32_t n_neurons, batch, d_max_steps, capacity;
-  int32_t kind;        // 0 ring (lossless), 1 fifo (bounded), 2 sorted (bounded)
+  int32_t kind;        // 0 ring (lossless), 1 fifo (bounded), 2 sorted (bounded), 3 one bounded FIFO per synapse
   int32_t n_steps;
   int32_t surrogate;   // 0 SuperSpike, 1 off (sigma' == 0), 2 spike-time gradient (no surrogate)
   int32_t exact_f64;   // 0: fp32 state + Q8.24 sums (the method), 1: fp64, no quantisation
@@ -216,7 +223,8 @@ void run_trial(oracle_run& r, int b) {
   const bool exact = c.exact_f64 != 0;
   Trial& tr = r.trials[b];
   std::priority_queue<Event, std::vector<Event>, Later> pq;
-  std::vector<int32_t> occ(N, 0);
+  const bool per_syn = c.kind == 3;   // occupancy counted per synapse instead of per target
+  std::vector<int32_t> occ(per_syn ? (size_t)c.n_synapses : (size_t)N, 0);
   std::vector<float> V(N, 0.0f), J(N, 0.0f);       // membrane state, synaptic current state
   std::vector<double> V64(N, 0.0), J64(N, 0.0);
   const bool syn_state = c.tau_syn_ms > 0.0f;
@@ -234,7 +242,7 @@ void run_trial(oracle_run& r, int b) {
       const int j = c.col[e.syn];
       acc[j] = (int32_t)((uint32_t)acc[j] + (uint32_t)r.a_q[e.syn]);  // wrapping add
       acc64[j] += r.a_d[e.syn];
-      occ[j] -= 1;
+      occ[per_syn ? (size_t)e.syn : (size_t)j] -= 1;
       tr.n_delivered += 1; tr.sum_deliv += r.a_q[e.syn];
       if (c.log_events) tr.delivered.add(e.syn, e.n_emit, e.k, b);
     }
@@ -274,15 +282,16 @@ void run_trial(oracle_run& r, int b) {
         const int j = c.col[p];
         const int32_t k = n + r.D[p];
         tr.enqueued += 1; tr.sum_enq += r.a_q[p];
-        if (bounded && occ[j] >= c.capacity) {
+        const size_t oi = per_syn ? (size_t)p : (size_t)j;
+        if (bounded && occ[oi] >= c.capacity) {
           tr.admitted.push_back(0);
           tr.n_dropped += 1; tr.sum_drop += r.a_q[p];
           if (c.log_events) tr.dropped.add(p, n, k, b);
           continue;
         }
         tr.admitted.push_back(1);
-        occ[j] += 1;
-        tr.max_occ = std::max(tr.max_occ, occ[j]);
+        occ[oi] += 1;
+        tr.max_occ = std::max(tr.max_occ, occ[oi]);
         pq.push(Event{k, p, n});
       }
     }
@@ -380,7 +389,7 @@ oracle_run* oracle_forward(const oracle_config* cfg) {
   r->cfg = *cfg;
   const oracle_config& c = r->cfg;
   if (c.n_neurons < 1 || c.batch < 1 || c.n_steps < 0 || c.d_max_steps < 1 ||
-      (c.kind != 0 && c.capacity < 1) || c.kind < 0 || c.kind > 2 ||
+      (c.kind != 0 && c.capacity < 1) || c.kind < 0 || c.kind > 3 ||
       !(c.dt_ms > 0.0f) || !(c.tau_m_ms > 0.0f) || c.dt_ms > c.tau_m_ms) {
     r->status = -1; return r;
   }

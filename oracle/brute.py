@@ -78,6 +78,32 @@ def hold_one_spike(spikes: np.ndarray, row_ptr, col, D):
     return out
 
 
+def replay_per_synapse(spikes: np.ndarray, row_ptr, D, capacity: int):
+    """One first-in-first-out queue of `capacity` spike times per synapse (the organisation of
+    Section 4.1, listing 1, with the "FIFORing(n)" of Section 4.3; capacity 1 is its
+    "SingleSpike(Hold)").  Written per synapse from the spike train of its source alone: a
+    synapse's queue is a list of arrival times; at step n the head leaves if it is due, then a
+    spike of the source at n enters unless the list is full.  Returns (admitted, dropped) as sets
+    of (syn, n_emit, k)."""
+    T, N = spikes.shape
+    admitted, dropped = set(), set()
+    for i in range(N):
+        times = np.nonzero(spikes[:, i])[0]
+        for p in range(int(row_ptr[i]), int(row_ptr[i + 1])):
+            d = int(D[p])
+            queue = []                       # arrival times, oldest first
+            for n in times:
+                n = int(n)
+                while queue and queue[0] <= n:
+                    queue.pop(0)
+                if len(queue) >= capacity:
+                    dropped.add((p, n, n + d))
+                else:
+                    queue.append(n + d)
+                    admitted.add((p, n, n + d))
+    return admitted, dropped
+
+
 def currents_from_events(events, col, amp, T: int, N: int) -> np.ndarray:
     """Sum the amplitudes of a list of (syn, n_emit, k) at their arrival step."""
     I = np.zeros((T, N), np.float64)

@@ -170,6 +170,63 @@ def test_fifo_capacity_one_is_hold_one_spike():
     assert r.counters()["dropped"] > 0
 
 
+def _bursty(seed, n=20, fan=6, d_max=9, t=260):
+    """A small net whose neurons fire in bursts (strong drive), so that a single synapse often
+    holds several events at once."""
+    return synth.ragged_network(n, fan, d_max, seed=seed, rate_hz=3000.0, t=t, w_mean=0.3, w_std=0.2)
+
+
+@pytest.mark.parametrize("cap", [1, 2, 3])
+def test_per_synapse_queue_replay(cap):
+    """Kind 3 (one bounded FIFO per synapse) against a replay written per synapse from the
+    source's spike train alone."""
+    wl = _bursty(6)
+    r = oracle.Run(wl, oracle.SYN_FIFO, cap, log_events=True)
+    S = r.spikes[:, 0, :]
+    adm, drp = brute.replay_per_synapse(S, wl.row_ptr, wl.delay_steps, cap)
+    dr = r.event_log("dropped")
+    assert set(zip(dr["syn"].tolist(), dr["n_emit"].tolist(), dr["k"].tolist())) == drp
+    dl = r.event_log("delivered")
+    assert set(zip(dl["syn"].tolist(), dl["n_emit"].tolist(), dl["k"].tolist())) == {e for e in adm if e[2] < wl.n_steps}
+    c = r.counters()
+    assert len(drp) > 50 and c["dropped"] == len(drp) and c["max_occupancy"] == cap
+    assert c["enqueued"] == c["delivered"] + c["dropped"] + c["in_flight"]
+
+
+@pytest.mark.parametrize("cap", [1, 2, 4, 7])
+def test_per_synapse_queue_periodic_source_closed_form(cap):
+    """A source that fires at every step, through synapses with delays 1..7: the event emitted at
+    step n is admitted iff (n mod D) < C when C < D (the queue fills in C steps and a place frees
+    every time the oldest event arrives, D steps after it entered), and always when C >= D."""
+    n, T = 8, 90
+    delays = np.arange(1, 8, dtype=np.uint8)
+    row_ptr = np.zeros(n + 1, np.int64); row_ptr[1:] = len(delays)      # all synapses leave neuron 0
+    wl = synth.Workload(name="periodic", n_neurons=n, fan_out=len(delays), n_steps=T, batch=1, d_max_steps=7,
+                        ext_rate_hz=0.0, seed=1, row_ptr=row_ptr, col=np.arange(1, 8, dtype=np.int32),
+                        weight=np.full(len(delays), 0.01, np.float32), delay_steps=delays)
+    forced = np.zeros((T, 1, n), np.uint8); forced[:, 0, 0] = 1
+    r = oracle.Run(wl, oracle.SYN_FIFO, cap, forced_spikes=forced, log_events=True)
+    dr = r.event_log("dropped")
+    got = set(zip(dr["syn"].tolist(), dr["n_emit"].tolist()))
+    want = {(p, t) for p, d in enumerate(delays.tolist()) for t in range(T) if cap < d and t % d >= cap}
+    assert got == want
+
+
+def test_per_synapse_queue_lossless_equals_ring_and_differs_from_per_target():
+    wl = _bursty(9)
+    base = oracle.Run(wl, oracle.RING, keep_currents=True)
+    occ = oracle.Run(wl, oracle.SYN_FIFO, 10**6).counters()["max_occupancy"]
+    assert occ >= 2
+    r = oracle.Run(wl, oracle.SYN_FIFO, occ, keep_currents=True)
+    np.testing.assert_array_equal(r.U, base.U)
+    np.testing.assert_array_equal(r.Iq, base.Iq)
+    assert r.counters()["dropped"] == 0
+    lossy = oracle.Run(wl, oracle.SYN_FIFO, occ - 1)
+    assert lossy.counters()["dropped"] > 0
+    # the same capacity per target loses far more: a target's queue is shared by its whole fan-in
+    assert oracle.Run(wl, oracle.FIFO, occ - 1).counters()["dropped"] > lossy.counters()["dropped"]
+
+
 def test_queue_kinds_agree_when_lossless():
     wl = synth.cfg0(seed=21)
     base = oracle.Run(wl, oracle.RING, keep_currents=True)
