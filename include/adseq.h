@@ -50,6 +50,15 @@
  *                 its arrival step.
  *   ADSEQ_SORTED  per target, `capacity` slots kept ordered by arrival step; pop
  *                 takes from the front ("SortedArray"); same admission rule.
+ *   ADSEQ_SYN_FIFO one first-in-first-out queue of `capacity` (1..8) arrival times per
+ *                 synapse and trial, the organisation of Section 4.1 (one queue per
+ *                 synapse; "FIFORing(n)", capacity 1 = "SingleSpike(Hold)"): an incoming
+ *                 event is dropped (and counted) when its own synapse already holds
+ *                 `capacity` undelivered events.  All events of a synapse share one
+ *                 delay, so arrival order is emission order and an ordered queue
+ *                 ("SortedArray") behaves the same.  Every queue is looked at in every
+ *                 step (the cost the per-target kinds avoid); state: 2 capacity + 4
+ *                 bytes per synapse and trial.
  *   Admission order within a step is canonical: ascending global synapse index
  *   (= ascending source neuron, then position in the row), independently per trial.
  */
@@ -65,7 +74,7 @@ extern "C" {
 
 typedef struct adseq adseq_t; /* opaque; host memory owned by the library, freed by adseq_destroy */
 
-enum { ADSEQ_RING = 0, ADSEQ_FIFO = 1, ADSEQ_SORTED = 2 };
+enum { ADSEQ_RING = 0, ADSEQ_FIFO = 1, ADSEQ_SORTED = 2, ADSEQ_SYN_FIFO = 3 };
 /* How a spike passes gradients back (config field `surrogate`):
  *   ADSEQ_SURR_SUPERSPIKE  the spike function has the SuperSpike derivative 1/(|U - theta| + 1)^2 (eq. 7);
  *   ADSEQ_SURR_OFF         it has derivative 0 (only the direct dependence of amplitudes on weights
@@ -95,8 +104,9 @@ typedef struct {
   int32_t n_neurons;    /* N >= 1                                                             */
   int32_t batch;        /* B >= 1 independent trials sharing the network                      */
   int32_t d_max_steps;  /* largest arrival offset in steps, 1..1023                           */
-  int32_t capacity;     /* slots per target for FIFO / SORTED (1..32767); ignored for RING    */
-  int32_t kind;         /* ADSEQ_RING / ADSEQ_FIFO / ADSEQ_SORTED                             */
+  int32_t capacity;     /* slots per target for FIFO / SORTED (1..32767), per synapse for
+                           SYN_FIFO (1..8); ignored for RING                                  */
+  int32_t kind;         /* ADSEQ_RING / ADSEQ_FIFO / ADSEQ_SORTED / ADSEQ_SYN_FIFO            */
   int32_t surrogate;    /* ADSEQ_SURR_SUPERSPIKE / ADSEQ_SURR_OFF / ADSEQ_GRAD_SPIKE_TIME      */
   int32_t record_tape;  /* 1 = adseq_step keeps what adseq_backward needs                     */
   int32_t max_steps;    /* tape length in steps (needed when record_tape = 1)                 */

@@ -124,6 +124,11 @@ struct Dev {
   int* pool_next;
   unsigned* pool_k;
   int* pool_a;
+  unsigned short* sq_next; // SYN_FIFO: [ceil(B S / 8) * 8] arrival step of the head of every per-synapse queue (0xffff: empty)
+  unsigned short* sq_hs;   // SYN_FIFO: [B S] head << 8 | size
+  unsigned short* sq_key;  // SYN_FIFO: [B S][C] arrival step mod 2^16 of every slot
+  int* I_acc;              // SYN_FIFO: [BN] Q8.24 sum of the events popped for the step being run
+  int blk_pop;             // SYN_FIFO: index of the first counter line of k_synq_pop's blocks in blk
   unsigned long long* spk_words;  // FIFO/SORTED: [2][words] ballot words of the step launch, by step parity
   long long* stepcnt;   // FIFO/SORTED: [2][nblk][2] spikes and emitted events of every neuron block, by step parity
   float* tapeU;
@@ -298,6 +303,7 @@ __global__ __launch_bounds__(kBlock) void k_prepare(Dev d, ExpCoef ec) {
 // ---------------------------------------------------------------- bounded queues (FIFO / SORTED)
 
 #include "bounded_queues.h"
+#include "synapse_queues.h"
 
 __global__ __launch_bounds__(kBlock) void k_copy_i32(const int* __restrict__ src, int* __restrict__ dst, size_t n) {
   for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) dst[i] = src[i];
@@ -418,7 +424,7 @@ struct adseq {
 namespace {
 
 struct Layout {
-  size_t V, J, bwd_carryJ, win, spike_bits, slot, fkey, famp, vmask, occ, head, min_k, cnt, cont, c_head, pool_p, pool_t, pool_next,
+  size_t V, J, bwd_carryJ, win, spike_bits, sq_next, sq_hs, sq_key, I_acc, slot, fkey, famp, vmask, occ, head, min_k, cnt, cont, c_head, pool_p, pool_t, pool_next,
       pool_k, pool_a, spk_words, stepcnt, packed, a_q, synf, synb, dstart, nearcnt, perm, rowsum, rowlen, ebuf, ecnt, amp, fdec, tapeU,
       tape_bits, spk_count, step_off, step_evoff, tape_spk, tape_evb, tape_row, tape_adm, bwd_ring, bwd_carry, bwd_G, gwin, Gacc, gsum, ctr, blk,
       total;
@@ -453,8 +459,9 @@ bool host_validate(const adseq_config* c) {
   if (!c) return false;
   if (c->n_neurons < 1 || c->batch < 1 || c->d_max_steps < 1 || c->d_max_steps > 1023) return false;
   if ((long long)c->n_neurons * c->batch > 0x7fffffffLL) return false;
-  if (c->kind != ADSEQ_RING && c->kind != ADSEQ_FIFO && c->kind != ADSEQ_SORTED) return false;
+  if (c->kind != ADSEQ_RING && c->kind != ADSEQ_FIFO && c->kind != ADSEQ_SORTED && c->kind != ADSEQ_SYN_FIFO) return false;
   if (c->kind != ADSEQ_RING && (c->capacity < 1 || c->capacity > 32767)) return false;
+  if (c->kind == ADSEQ_SYN_FIFO && c->capacity > kSynqCapMax) return false;
   if (c->surrogate != ADSEQ_SURR_SUPERSPIKE && c->surrogate != ADSEQ_SURR_OFF &&
       c->surrogate != ADSEQ_GRAD_SPIKE_TIME) return false;
   if (!(c->dt_ms > 0.0f) || !(c->tau_m_ms > 0.0f) || c->dt_ms > c->tau_m_ms) return false;
@@ -473,6 +480,8 @@ bool make_layout(const adseq_config* c, Layout* L) {
   const size_t BN = (size_t)c->n_neurons * c->batch;
   const size_t S = (size_t)c->n_synapses;
   const bool bounded = c->kind != ADSEQ_RING;
+  const bool ptq = c->kind == ADSEQ_FIFO || c->kind == ADSEQ_SORTED;   // bounded queues per target
+  const bool synq = c->kind == ADSEQ_SYN_FIFO;                         // one bounded queue per synapse
   const bool cont = c->delay_ms != nullptr;
   L->R = c->d_max_steps + 1;
   L->dbits = bit_width((unsigned)c->d_max_steps);
@@ -486,7 +495,7 @@ bool make_layout(const adseq_config* c, Layout* L) {
       if (L->event_cap >= (1LL << 40) - 1) return false;   // admission-flag indices are packed into 40 bits
     }
   }
-  if (bounded) {
+  if (ptq) {
     long long cap = c->step_event_capacity;
     if (!cap) {
       const double bs = (double)c->batch * (double)S;
@@ -528,7 +537,8 @@ bool make_layout(const adseq_config* c, Layout* L) {
     L->cap = (int)(per > 65536.0 ? 65536.0 : per);
   }
   L->ctr = take(sizeof(Counters));
-  L->blk = take(bounded ? ((size_t)L->nblk + fan_slots(L->nblk)) * sizeof(BlkCtr) : kMaxBinBlocks * sizeof(BlkCtr));
+  L->blk = take(bounded ? ((size_t)L->nblk + fan_slots(L->nblk) + (synq ? kSynqBlocks : 0)) * sizeof(BlkCtr)
+                        : kMaxBinBlocks * sizeof(BlkCtr));
   L->V = take(BN * 4);
   L->J = take(c->tau_syn_ms > 0.0f ? BN * 4 : 0);
   L->win = take(bounded ? 0 : 2 * (size_t)L->W * BN * 4);
@@ -538,17 +548,24 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->fkey = take(fifo ? (size_t)((c->capacity + 7) / 8 * 8) * BN * 2 : 0);
   L->famp = take(fifo ? (size_t)c->capacity * BN * 4 : 0);
   L->vmask = take(fifo ? (size_t)((c->capacity + 31) / 32) * BN * 4 : 0);
-  L->occ = take(bounded ? BN * 4 : 0);
-  L->head = take(bounded ? BN * 4 : 0);
-  L->min_k = take(bounded ? BN * 4 : 0);
-  L->cnt = take(bounded ? BN * 4 : 0);
-  L->cont = take(bounded ? (size_t)kCont * BN * 16 : 0);
-  L->c_head = take(bounded ? BN * 4 : 0);
+  L->occ = take(ptq ? BN * 4 : 0);
+  L->head = take(ptq ? BN * 4 : 0);
+  L->min_k = take(ptq ? BN * 4 : 0);
+  L->cnt = take(ptq ? BN * 4 : 0);
+  L->cont = take(ptq ? (size_t)kCont * BN * 16 : 0);
+  L->c_head = take(ptq ? BN * 4 : 0);
   L->pool_p = take((size_t)L->pool_cap * 8);
   L->pool_t = take((size_t)L->pool_cap * 8);
   L->pool_next = take((size_t)L->pool_cap * 4);
   L->pool_k = take((size_t)L->pool_cap * 4);
   L->pool_a = take((size_t)L->pool_cap * 4);
+  {
+    const size_t Q = (size_t)c->batch * S;
+    L->sq_next = take(synq ? (Q + 7) / 8 * 16 : 0);
+    L->sq_hs = take(synq ? Q * 2 : 0);
+    L->sq_key = take(synq ? Q * (size_t)c->capacity * 2 : 0);
+    L->I_acc = take(synq ? BN * 4 : 0);
+  }
   L->spk_words = take(bounded ? 2 * (size_t)L->words * 8 : 0);
   L->stepcnt = take(bounded ? 2 * (size_t)L->nblk * 16 : 0);
   L->packed = take(bounded ? S * 4 : 0);
@@ -626,6 +643,12 @@ void launch_reset(adseq* h, hipStream_t st) {
     fill_u32(st, d.win, 0u, 2 * (size_t)d.W * BN);
     fill_u32(st, d.spike_bits, 0u, (size_t)d.R * d.words * 2);
     fill_u32(st, d.blk, 0u, kMaxBinBlocks * sizeof(BlkCtr) / 4);
+  } else if (d.kind == ADSEQ_SYN_FIFO) {
+    fill_u32(st, d.sq_next, 0xffffffffu, ((size_t)d.B * d.S + 7) / 8 * 4);   // every queue empty
+    fill_u32(st, d.sq_hs, 0u, ((size_t)d.B * d.S + 1) / 2);                  // (the keys need no clearing)
+    fill_u32(st, d.I_acc, 0u, BN);
+    fill_u32(st, d.blk, 0u, ((size_t)d.blk_pop + kSynqBlocks) * sizeof(BlkCtr) / 4);
+    h->pending_admit = false;
   } else {
     fill_u32(st, d.occ, 0u, BN);
     fill_u32(st, d.head, 0u, BN);
@@ -652,7 +675,12 @@ void launch_neurons(adseq* h, hipStream_t st, long long n, int parity, const flo
                     unsigned char* spikes_out, float* I_out) {
   const Dev& d = h->dev;
   const dim3 grid(grid_for((size_t)d.BN)), block(kBlock);
-  if (d.kind == ADSEQ_FIFO)
+  if (d.kind == ADSEQ_SYN_FIFO) {
+    // per-synapse queues: every queue is looked at first (nothing is pending for MODE 0)
+    if (MODE == 0) return;
+    hipLaunchKernelGGL(k_synq_pop, dim3(kSynqBlocks), block, 0, st, d, n);
+    hipLaunchKernelGGL((k_neurons<ADSEQ_SYN_FIFO, MODE>), grid, block, 0, st, d, n, parity, i_ext, spikes_out, I_out);
+  } else if (d.kind == ADSEQ_FIFO)
     hipLaunchKernelGGL((k_neurons<ADSEQ_FIFO, MODE>), grid, block, 0, st, d, n, parity, i_ext, spikes_out, I_out);
   else
     hipLaunchKernelGGL((k_neurons<ADSEQ_SORTED, MODE>), grid, block, 0, st, d, n, parity, i_ext, spikes_out, I_out);
@@ -667,13 +695,15 @@ void launch_fanout(adseq* h, hipStream_t st, long long n, const int* spk, const 
   if (!spk) {
     const dim3 grid((unsigned)d.nblk * d.fsplit);
     if (d.kind == ADSEQ_FIFO) hipLaunchKernelGGL((k_fanout_step<ADSEQ_FIFO>), grid, block, 0, st, d, n, parity, record);
+    else if (d.kind == ADSEQ_SYN_FIFO) hipLaunchKernelGGL((k_fanout_step<ADSEQ_SYN_FIFO>), grid, block, 0, st, d, n, parity, record);
     else hipLaunchKernelGGL((k_fanout_step<ADSEQ_SORTED>), grid, block, 0, st, d, n, parity, record);
   } else {
     const dim3 grid(kFanoutBlocks);
     if (d.kind == ADSEQ_FIFO) hipLaunchKernelGGL((k_fanout_list<ADSEQ_FIFO>), grid, block, 0, st, d, n, spk, n_spk);
+    else if (d.kind == ADSEQ_SYN_FIFO) hipLaunchKernelGGL((k_fanout_list<ADSEQ_SYN_FIFO>), grid, block, 0, st, d, n, spk, n_spk);
     else hipLaunchKernelGGL((k_fanout_list<ADSEQ_SORTED>), grid, block, 0, st, d, n, spk, n_spk);
   }
-  h->pending_admit = true;
+  h->pending_admit = d.kind != ADSEQ_SYN_FIFO;   // a per-synapse push is final
   h->last_stream = st;
 }
 
@@ -886,6 +916,8 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   d.cont = (uint4*)(ws + L.cont);
   d.pool_k = (unsigned*)(ws + L.pool_k); d.pool_a = (int*)(ws + L.pool_a);
   d.spk_words = (unsigned long long*)(ws + L.spk_words); d.stepcnt = (long long*)(ws + L.stepcnt);
+  d.sq_next = (unsigned short*)(ws + L.sq_next); d.sq_hs = (unsigned short*)(ws + L.sq_hs); d.sq_key = (unsigned short*)(ws + L.sq_key);
+  d.I_acc = (int*)(ws + L.I_acc); d.blk_pop = L.nblk + (int)fan_slots(L.nblk);
   d.packed = (unsigned*)(ws + L.packed); d.a_q = (int*)(ws + L.a_q);
   d.amp = (d.continuous && d.kind != ADSEQ_RING) ? (float*)(ws + L.amp) : nullptr;
   d.synf = (uint2*)(ws + L.synf); d.synb = (uint2*)(ws + L.synb);
@@ -1098,7 +1130,7 @@ int adseq_counters(adseq_t* h, int64_t* out8, void* stream) {
   out8[6] = c.tape_spikes; out8[7] = (int64_t)c.err;
   if (d.kind != ADSEQ_RING) {
     // the kernels keep private counters per block: add them up here
-    const size_t nb = (size_t)d.nblk + fan_slots(d.nblk);
+    const size_t nb = (size_t)d.nblk + fan_slots(d.nblk) + (d.kind == ADSEQ_SYN_FIFO ? kSynqBlocks : 0);
     std::vector<BlkCtr> hb(nb);
     HIP_TRY(h, hipMemcpyAsync(hb.data(), d.blk, sizeof(BlkCtr) * nb, hipMemcpyDeviceToHost, st));
     HIP_TRY(h, hipStreamSynchronize(st));

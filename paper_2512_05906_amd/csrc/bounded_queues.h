@@ -287,12 +287,22 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
   const size_t BN = (size_t)d.BN;
   const unsigned kn = (unsigned)n;
   StepAcc r; r.acc = 0; r.popped = 0; r.c_adm = 0; r.s_adm = 0;
-  if (blockIdx.x == 0 && threadIdx.x == 0) d.ctr->pool_n[0] = 0;   // the overflow pool is consumed by this launch
+  if (KIND != ADSEQ_SYN_FIFO && blockIdx.x == 0 && threadIdx.x == 0) d.ctr->pool_n[0] = 0;   // the overflow pool is consumed by this launch
   counts_clear(s_cnt);
   const bool dense = d.prefetch != 0;   // few targets: latency-bound, load everything in the first round
   float v = 0.0f, jsyn = 0.0f;
   int len = 0;
-  if (act) {
+  if (KIND == ADSEQ_SYN_FIFO) {
+    // per-synapse queues: k_synq_pop has summed the events due now into the target's cell
+    if (act) {
+      if (MODE != 0) { r.acc = d.I_acc[g]; if (r.acc != 0) d.I_acc[g] = 0; }
+      if (MODE == 2) {
+        v = d.V[g];
+        if (d.alpha_s > 0.0f) jsyn = d.J[g];
+        if (dense) len = d.rowlen[d.B == 1 ? g : g % d.N];
+      }
+    }
+  } else if (act) {
     // everything the thread needs first, loaded together
     const int K = d.cnt[g];
     QState q;
@@ -438,7 +448,7 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
     // wavefront totals (every lane is active here), one LDS atomic per wavefront and counter;
     // a wavefront that delivered and admitted nothing, or has no spike, skips the sums
     long long t_pop = 0, t_acc = 0, t_adm = 0, t_sadm = 0, t_ev = 0;
-    if (__ballot(r.popped != 0 || r.c_adm != 0)) {
+    if (KIND != ADSEQ_SYN_FIFO && __ballot(r.popped != 0 || r.c_adm != 0)) {
       t_pop = wave_total(r.popped); t_acc = wave_total(r.acc);
       t_adm = wave_total(r.c_adm); t_sadm = wave_total64(r.s_adm);
     }
@@ -463,6 +473,11 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
 // A share of the row of a spike that is being offered: trial, row bounds, index of the row's first
 // admission flag on the tape (-1: none), offset of the share's first entry in the row.
 struct RowRef { int b; long long r0, r1, tbase, first; };
+
+// Per-synapse queues (synapse_queues.h): the push that takes the place of offer_rows.
+__device__ __forceinline__ void push_rows(const Dev& d, long long n, const RowRef* rr, int nrows, long long stride,
+                                          int& c_adm, long long& s_adm);
+__device__ __forceinline__ void push_counts_flush(const Dev& d, int c_adm, long long s_adm, BlkCtr& bc);
 
 // Offers, for each of up to four row shares of step n, the entries r0 + first + threadIdx.x +
 // t * stride (t = 0, 1, ...) to their targets.  An event whose target is already full
@@ -574,6 +589,8 @@ __global__ __launch_bounds__(kBlock) void k_fanout_step(Dev d, long long n, int 
            d.tape_adm, d.tape_spk, d.tape_evb, d.blk, d.ctr, d.N, d.B, d.BN, d.C, d.nblk, d.dbits, d.dmask,
            d.max_steps, d.spike_cap, d.event_cap, d.pool_cap, n);
   long long c_off = 0, s_off = 0;   // offered events and their amplitude sum (share 0, thread 0)
+  int c_adm = 0;                    // per-synapse queues: events this thread admitted, and their sum
+  long long s_adm = 0;
   {
     // the first group's row bounds are requested before the prefix sums, so that the two overlap
     int x = 0;
@@ -640,9 +657,11 @@ __global__ __launch_bounds__(kBlock) void k_fanout_step(Dev d, long long n, int 
           }
         }
       }
-      offer_rows(d, n, rr, nrows, (long long)d.fsplit * kBlock);
+      if (KIND == ADSEQ_SYN_FIFO) push_rows(d, n, rr, nrows, (long long)d.fsplit * kBlock, c_adm, s_adm);
+      else offer_rows(d, n, rr, nrows, (long long)d.fsplit * kBlock);
     }
   }
+  if (KIND == ADSEQ_SYN_FIFO) push_counts_flush(d, c_adm, s_adm, d.blk[d.nblk + blockIdx.x]);
   if (c == 0 && threadIdx.x == 0 && c_off) {
     BlkCtr& bc = d.blk[d.nblk + blockIdx.x];   // private to this block
     atomicAdd(&bc.offered, (unsigned long long)c_off);   // atomics without return value: nobody waits for a load
@@ -660,6 +679,8 @@ __global__ __launch_bounds__(kBlock) void k_fanout_list(Dev d, long long n, cons
   int nspk = *n_spk_ptr;
   nspk = nspk < 0 ? 0 : (nspk > d.BN ? d.BN : nspk);
   long long c_off = 0, s_off = 0;
+  int c_adm = 0;
+  long long s_adm = 0;
   for (int e = blockIdx.x; e < nspk; e += gridDim.x) {
     const int g = spk[e];
     if ((unsigned)g >= (unsigned)d.BN) continue;  // uniform over the block
@@ -669,8 +690,10 @@ __global__ __launch_bounds__(kBlock) void k_fanout_list(Dev d, long long n, cons
 #pragma unroll
     for (int j = 0; j < 4; ++j) { rr[j].b = b; rr[j].r0 = r0; rr[j].r1 = r1; rr[j].tbase = -1; rr[j].first = (long long)j * kBlock; }
     if (threadIdx.x == 0) { c_off += r1 - r0; s_off += d.rowsum[i]; }
-    offer_rows(d, n, rr, 4, 4LL * kBlock);
+    if (KIND == ADSEQ_SYN_FIFO) push_rows(d, n, rr, 4, 4LL * kBlock, c_adm, s_adm);
+    else offer_rows(d, n, rr, 4, 4LL * kBlock);
   }
+  if (KIND == ADSEQ_SYN_FIFO) push_counts_flush(d, c_adm, s_adm, d.blk[d.nblk + blockIdx.x]);
   if (threadIdx.x == 0 && c_off) {
     BlkCtr& bc = d.blk[d.nblk + blockIdx.x];   // private to this block
     atomicAdd(&bc.offered, (unsigned long long)c_off);   // atomics without return value: nobody waits for a load

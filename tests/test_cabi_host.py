@@ -39,11 +39,18 @@ def test_workspace_size_grows_with_the_queue():
     assert ring % 256 == 0
     no_tape = lib.adseq_workspace_bytes(C.byref(_cfg(record_tape=0, max_steps=0)))
     assert no_tape < ring
+    # one queue per synapse and trial: a 16-bit arrival key per slot
+    c2 = _cfg(kind=adseq.SYN_FIFO, capacity=2)
+    syn2 = lib.adseq_workspace_bytes(C.byref(c2))
+    syn8 = lib.adseq_workspace_bytes(C.byref(_cfg(kind=adseq.SYN_FIFO, capacity=8)))
+    queues = c2.batch * c2.n_synapses
+    assert abs((syn8 - syn2) - 6 * 2 * queues) <= 256      # up to the 256-byte alignment of the array
 
 
 @pytest.mark.parametrize("bad", [
     dict(n_neurons=0), dict(batch=0), dict(d_max_steps=0), dict(d_max_steps=1024),
-    dict(kind=3), dict(kind=adseq.FIFO, capacity=0), dict(kind=adseq.SORTED, capacity=40000),
+    dict(kind=4), dict(kind=adseq.SYN_FIFO, capacity=0), dict(kind=adseq.SYN_FIFO, capacity=9),
+    dict(kind=adseq.FIFO, capacity=0), dict(kind=adseq.SORTED, capacity=40000),
     dict(dt_ms=0.0), dict(tau_m_ms=0.05), dict(ext_rate_hz=-1.0), dict(n_synapses=-1),
     dict(record_tape=1, max_steps=0), dict(surrogate=5), dict(tau_syn_ms=-1.0), dict(tau_syn_ms=0.05), dict(n_neurons=2**23, d_max_steps=1023),
 ])

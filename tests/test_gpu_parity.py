@@ -9,7 +9,7 @@ from tests import helpers as H
 
 pytestmark = pytest.mark.gpu
 
-KINDS = {"ring": oracle.RING, "fifo": oracle.FIFO, "sorted": oracle.SORTED}
+KINDS = {"ring": oracle.RING, "fifo": oracle.FIFO, "sorted": oracle.SORTED, "syn": oracle.SYN_FIFO}
 
 
 def _compare_forward(wl, kind, cap, T=None, B=None, i_ext=None, check_sets=True, **kw):
@@ -38,12 +38,12 @@ def _compare_forward(wl, kind, cap, T=None, B=None, i_ext=None, check_sets=True,
     return ref, out
 
 
-@pytest.mark.parametrize("kind", ["ring", "sorted", "fifo"])
+@pytest.mark.parametrize("kind", ["ring", "sorted", "fifo", "syn"])
 def test_cfg0_forward_lossless(kind):
     """Config 0 with the ring and with the exact ordered queue (capacity = the
     largest occupancy the oracle sees, so nothing is dropped)."""
     wl = synth.cfg0()
-    cap = oracle.Run(wl, oracle.FIFO, 10**6).counters()["max_occupancy"] if kind != "ring" else 0
+    cap = oracle.Run(wl, KINDS[kind], 10**6).counters()["max_occupancy"] if kind != "ring" else 0
     ref, out = _compare_forward(wl, KINDS[kind], cap)
     assert ref.counters()["dropped"] == 0 and ref.spikes.sum() > 100
 
@@ -56,7 +56,7 @@ def test_cfg0_forward_lossy(kind, cap):
     assert ref.counters()["dropped"] > 0
 
 
-@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 4), ("sorted", 4)])
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 4), ("sorted", 4), ("syn", 1)])
 @pytest.mark.parametrize("continuous", [False, True])
 def test_ragged_rows_batched(kind, cap, continuous):
     """Rows of 0..700 synapses (several 256-wide tiles plus a ragged tail, empty rows,
@@ -66,7 +66,19 @@ def test_ragged_rows_batched(kind, cap, continuous):
     ref, _ = _compare_forward(wl, KINDS[kind], cap, check_sets=(kind != "ring"))
     assert ref.spikes.sum() > 300
     if kind != "ring":
-        assert ref.counters()["dropped"] > 1000
+        assert ref.counters()["dropped"] > (1000 if kind != "syn" else 100)
+
+
+@pytest.mark.parametrize("cap", [1, 2, 3, 8])
+def test_per_synapse_queues_bursty(cap):
+    """One bounded FIFO per synapse (Section 4.1 listing 1, Section 4.3 "FIFORing"): neurons that
+    fire in bursts, so that a synapse often holds several events; rasters, membrane values,
+    counters and the dropped / delivered event sets against the oracle."""
+    wl = synth.ragged_network(200, 90, 25, seed=6, rate_hz=3000.0, t=200, b=3, w_mean=0.02, w_std=0.02)
+    ref, _ = _compare_forward(wl, oracle.SYN_FIFO, cap, tape_spike_capacity=200 * 3 * 200)
+    assert ref.spikes.sum() > 2000
+    if cap < 8:
+        assert ref.counters()["dropped"] > 500
 
 
 @pytest.mark.parametrize("window", [2, 8, 16, 64])
@@ -119,7 +131,7 @@ def test_no_spikes_and_zero_steps():
     assert out["counters"]["delivered"] == 0
 
 
-@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 2), ("sorted", 3)])
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 2), ("sorted", 3), ("syn", 1)])
 def test_open_loop_enqueue_deliver(kind, cap):
     """adseq_enqueue / adseq_deliver with externally generated spike lists (the
     shape of the paper's Poisson benchmark, Section 5.1)."""
@@ -250,7 +262,7 @@ def _compare_backward(wl, kind, cap, T, B, use_dU=True, surrogate=0, **kw):
     return ref
 
 
-@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 4), ("sorted", 6)])
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 4), ("sorted", 6), ("syn", 1)])
 @pytest.mark.parametrize("continuous", [False, True])
 def test_backward_small_ragged(kind, cap, continuous):
     wl = synth.ragged_network(120, 300, 30, seed=12, rate_hz=300.0, t=150, b=1, continuous=continuous,
@@ -261,7 +273,7 @@ def test_backward_small_ragged(kind, cap, continuous):
         assert ref.counters()["dropped"] > 0
 
 
-@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 4), ("sorted", 6)])
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 4), ("sorted", 6), ("syn", 1)])
 @pytest.mark.parametrize("continuous", [False, True])
 def test_backward_spike_time_mode(kind, cap, continuous):
     """No surrogate: gradients flow through the emission times of the spikes
@@ -294,7 +306,7 @@ def test_first_order_synapse_forward_backward(kind, cap, mode):
     assert not np.array_equal(plain.U, ref.U)      # the synaptic state changes the dynamics
 
 
-@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 32), ("fifo", 2), ("sorted", 128)])
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 32), ("fifo", 2), ("sorted", 128), ("syn", 4)])
 def test_cfg1_forward_backward(kind, cap):
     """Config 1 (1,000 neurons, fan-out 100, batch 16, 2,000 steps), MSE spike-count loss."""
     wl = synth.cfg1()
