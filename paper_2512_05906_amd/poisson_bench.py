@@ -34,10 +34,13 @@ def erlang_b(servers: int, load: float) -> float:
 
 def run_case(torch, adseq, synth, kind_name, cap, n_queues, delay, interval, T, repeats=3):
     import numpy as np
-    kind = {"ring": adseq.RING, "fifo": adseq.FIFO, "sorted": adseq.SORTED}[kind_name]
+    kind = {"ring": adseq.RING, "fifo": adseq.FIFO, "sorted": adseq.SORTED, "syn": adseq.SYN_FIFO}[kind_name]
     wl = synth.poisson_queues(n_queues, delay, n_steps=T)
-    rate_hz = 1.0 / (interval * wl.dt_ms * 1e-3)
-    lists = synth.poisson_spike_lists(n_queues, 1, T, rate_hz, wl.dt_ms, seed=11)
+    if interval > 0:
+        rate_hz = 1.0 / (interval * wl.dt_ms * 1e-3)
+        lists = synth.poisson_spike_lists(n_queues, 1, T, rate_hz, wl.dt_ms, seed=11)
+    else:   # control: no source ever fires
+        lists = [np.zeros(0, np.int32) for _ in range(T)]
     counts = np.array([len(x) for x in lists], np.int32)
     offs = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
     sim = adseq.Adseq(wl, kind, cap if kind != adseq.RING else 0)
@@ -57,8 +60,8 @@ def run_case(torch, adseq, synth, kind_name, cap, n_queues, delay, interval, T, 
     ms = float(np.median(times[1:]))
     c = sim.counters()
     sim.close()
-    a = delay / interval
-    return {"queue": kind_name, "capacity": cap if kind != adseq.RING else None, "n_queues": n_queues,
+    a = delay / interval if interval > 0 else 0.0
+    return {"queue": kind_name if interval > 0 else kind_name + " (control: no events)", "capacity": cap if kind != adseq.RING else None, "n_queues": n_queues,
             "delay_steps": delay, "mean_interval_steps": interval, "pressure": a, "time_steps": T,
             "us_per_time_step": ms * 1e3 / T, "ns_per_time_step_per_queue": ms * 1e6 / T / n_queues,
             "delivered_events_per_s": c["delivered"] / (ms * 1e-3),
@@ -79,10 +82,12 @@ def main():
     if not torch.cuda.is_available():
         print("poisson_bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
-    cases = [("ring", 0, 400), ("fifo", 4, 400), ("sorted", 4, 400)]
+    # the last case is the control the paper's "DoNothing" queue gives (Section 4.3): the same
+    # calls with no event ever inserted, i.e. the cost that does not depend on the queue's content
+    cases = [("ring", 0, 400), ("fifo", 4, 400), ("sorted", 4, 400), ("syn", 4, 400), ("ring", 0, 0)]
     if args.sweep:
         cases = [(k, c, lam) for lam in (400, 160, 80, 40, 20) for k, c in
-                 (("fifo", 1), ("fifo", 2), ("fifo", 4), ("fifo", 8), ("sorted", 4))]
+                 (("fifo", 1), ("fifo", 2), ("fifo", 4), ("fifo", 8), ("sorted", 4), ("syn", 4))]
     for kind, cap, lam in cases:
         print(json.dumps(run_case(torch, adseq, synth, kind, cap, args.queues, args.delay, lam,
                                   args.time_steps)), flush=True)

@@ -10,11 +10,12 @@ from paper_2512_05906_amd import adseq, synth
 
 pytestmark = pytest.mark.gpu
 
-KINDS = {"ring": oracle.RING, "fifo": oracle.FIFO, "sorted": oracle.SORTED}
+KINDS = {"ring": oracle.RING, "fifo": oracle.FIFO, "sorted": oracle.SORTED, "syn": oracle.SYN_FIFO}
 
 
 @pytest.mark.parametrize("kind,cap,interval", [("ring", 0, 400), ("fifo", 1, 400), ("fifo", 2, 80),
-                                               ("fifo", 4, 40), ("sorted", 4, 40), ("fifo", 40, 40)])
+                                               ("fifo", 4, 40), ("sorted", 4, 40), ("fifo", 40, 40), ("syn", 4, 40),
+                                               ("syn", 1, 400)])
 def test_poisson_queues_open_loop(kind, cap, interval):
     N, T, delay = 1500, 3000, 80          # 1,500 queues: several blocks and a ragged tail
     wl = synth.poisson_queues(N, delay, n_steps=T)
