@@ -173,7 +173,8 @@ int adseq_enqueue(adseq_t *h, int64_t step, const int32_t *spike_ids, const int3
  * adseq_enqueue(step0 + k) of the spikes spike_ids[spike_offsets[k] .. + n_spikes[k]).  spike_ids
  * and n_spikes [n_steps] are DEVICE pointers, spike_offsets [n_steps] is a HOST array.  The shape
  * of the paper's Poisson benchmark (Section 5.1: externally generated spike trains through the
- * queues).  Stops at the first error. */
+ * queues).  Same results as those calls; the ring does the two of a step in one launch.  Stops at
+ * the first error. */
 int adseq_run_open(adseq_t *h, int64_t step0, int64_t n_steps, const int32_t *spike_ids,
                    const int64_t *spike_offsets /*host*/, const int32_t *n_spikes, float *I_out,
                    int64_t I_stride, void *stream);

@@ -407,6 +407,7 @@ struct adseq {
   long long next_step;   // next step to deliver
   long long enq_calls;   // parity source for the pool / spike counters
   bool tape_ok;          // every step since reset went through adseq_step with recording
+  long long bits_clear_for;  // RING, open loop: the spike words of this step's slot have been cleared ahead (-1: of none)
   char err[256];
   long long fold_upto = 0;  // RING: spikes of steps below this are in the device counters
   bool pending_admit = false;  // FIFO/SORTED: contenders registered, admission not yet launched
@@ -667,6 +668,7 @@ void launch_reset(adseq* h, hipStream_t st) {
   h->next_step = 0;
   h->enq_calls = 0;
   h->tape_ok = d.record != 0;
+  h->bits_clear_for = -1;
 }
 
 // FIFO / SORTED: admission of what is pending, then (MODE 1) pop or (MODE 2) the closed-loop step.
@@ -1027,6 +1029,27 @@ int adseq_run_open(adseq_t* h, int64_t step0, int64_t n_steps, const int32_t* sp
                    void* stream) {
   if (!h || !spike_ids || !spike_offsets || !n_spikes || !I_out || n_steps < 0 || I_stride < 0)
     return h ? fail(h, ADSEQ_E_INVALID_ARG, "adseq_run_open: null or negative argument") : ADSEQ_E_INVALID_ARG;
+  if (h->dev.kind == ADSEQ_RING) {
+    // pop and enqueue of a step in one launch (k_open_step_win)
+    const Dev& d = h->dev;
+    hipStream_t st = (hipStream_t)stream;
+    for (int64_t k = 0; k < n_steps; ++k) {
+      const long long step = step0 + k;
+      if (step != h->next_step)
+        return fail(h, ADSEQ_E_ORDER, "adseq_run_open: got step %lld, expected %lld", step, h->next_step);
+      ring_open_window(h, st, step);
+      if (h->bits_clear_for != step)
+        fill_u32(st, d.spike_bits + (size_t)(step % d.R) * d.words, 0u, (size_t)d.words * 2);
+      hipLaunchKernelGGL(k_open_step_win, dim3((unsigned)d.nblk), dim3(kBlock), 0, st, d, step,
+                         spike_ids + spike_offsets[k], n_spikes + k, I_out + k * I_stride);
+      h->bits_clear_for = step + 1;
+      h->next_step = step + 1;
+      h->enq_calls += 1;
+      h->tape_ok = false;
+    }
+    HIP_TRY(h, hipGetLastError());
+    return ADSEQ_OK;
+  }
   for (int64_t k = 0; k < n_steps; ++k) {
     int rc = adseq_deliver(h, step0 + k, I_out + k * I_stride, stream);
     if (rc == ADSEQ_OK) rc = adseq_enqueue(h, step0 + k, spike_ids + spike_offsets[k], n_spikes + k, stream);

@@ -310,6 +310,42 @@ __global__ __launch_bounds__(kBlock) void k_enqueue_win(Dev d, long long n, cons
   }
 }
 
+// Open loop, pop and enqueue of one step in ONE launch (adseq_run_open knows both): block b pops
+// its 256 cells of row phi as k_deliver_win does, then the wavefronts share out the listed spikes
+// as in k_enqueue_win (their events go to later rows of the window, so the two parts never touch
+// the same cell).  The spike words being set are those of slot n mod R; nobody may clear them in
+// the same launch, so every launch clears the words of the NEXT step's slot instead (the host
+// clears this step's slot itself when the launch before was not one of these).
+__global__ __launch_bounds__(kBlock) void k_open_step_win(Dev d, long long n, const int* __restrict__ spk,
+                                                          const int* __restrict__ n_spk_ptr,
+                                                          float* __restrict__ I_out) {
+  int nspk = *n_spk_ptr;
+  nspk = nspk < 0 ? 0 : (nspk > d.BN ? d.BN : nspk);
+  const int g0 = blockIdx.x * kBlock + threadIdx.x;
+  const int phi = (int)(n & (long long)(d.W - 1));
+  int* __restrict__ win = win_of(d, n);
+  if (g0 < d.BN) {
+    const size_t idx = (size_t)phi * d.BN + g0;
+    const int acc = win[idx];
+    if (acc != 0) win[idx] = 0;
+    I_out[g0] = (float)acc * 0x1p-24f;
+  }
+  if ((threadIdx.x & 63) == 0 && blockIdx.x < d.nblk)
+    d.spike_bits[(size_t)((n + 1) % d.R) * d.words + (size_t)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6)] = 0ull;
+  int near_h = d.W - 1 - phi;
+  if (near_h > d.d_max) near_h = d.d_max;
+  const int lane = threadIdx.x & 63;
+  const int wave = (blockIdx.x * kBlock + threadIdx.x) >> 6, nwaves = (gridDim.x * kBlock) >> 6;
+  for (int e = wave; e < nspk; e += nwaves) {
+    const int g = spk[e];
+    if ((unsigned)g >= (unsigned)d.BN) continue;  // uniform over the wavefront
+    const int b = g / d.N, i = g - b * d.N;
+    if (lane == 0) atomicOr(&d.spike_bits[(size_t)(n % d.R) * d.words + (g >> 6)], 1ull << (g & 63));
+    if (near_h >= 1)
+      near_scatter(d, win, phi, d.row_ptr[i], d.nearcnt[(size_t)near_h * d.N + i], b * d.N);
+  }
+}
+
 // ---------------------------------------------------------------- forward: window expansion
 
 // Streaming loads of the expansion and gather passes (row pieces and staged events are read

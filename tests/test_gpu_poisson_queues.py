@@ -30,11 +30,14 @@ def test_poisson_queues_open_loop(kind, cap, interval):
     counts = torch.tensor([len(x) for x in lists], dtype=torch.int32, device=sim.dev)
     offs = np.concatenate([[0], np.cumsum([len(x) for x in lists])])
     ids = torch.from_numpy(np.concatenate(lists + [np.zeros(1, np.int32)])).to(sim.dev)
-    half = T // 2      # first half step by step, second half through the batched entry point
-    for n in range(half):
+    # first third through the batched entry point, second step by step, the rest batched again
+    # (for the ring the batched entry point pops and enqueues a step in one launch: both hand-overs)
+    a, b = T // 3, 2 * T // 3
+    sim.run_open(0, a, ids, offs[:a], counts, I, N)
+    for n in range(a, b):
         sim.deliver(n, I[n])
         sim.enqueue(n, ids[int(offs[n]):], counts[n:])
-    sim.run_open(half, T - half, ids, offs[half:T], counts[half:], I[half:], N)
+    sim.run_open(b, T - b, ids, offs[b:T], counts[b:], I[b:], N)
     torch.cuda.synchronize()
     want = ref.Iq.reshape(T, N).astype(np.float32) * np.float32(2.0 ** -24)
     np.testing.assert_array_equal(I.cpu().numpy().view(np.uint32), want.view(np.uint32))
