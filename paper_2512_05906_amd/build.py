@@ -36,6 +36,16 @@ def build_copy_reference() -> str:
     return out
 
 
+def build_chip_rates() -> str:
+    """The program that measures the launch, atomic, store and gather rates the design rests on."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    out = os.path.join(HERE, "chip_rates")
+    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang",
+                           "-packed-fp32-ops", "-o", out, os.path.join(HERE, "csrc", "chip_rates.hip")])
+    return out
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
     print(build_copy_reference())
+    print(build_chip_rates())

@@ -12,7 +12,8 @@
 //              the min(K, free) with the smallest synapse index, the canonical order -- then pops
 //              the events due now, integrates, and hands the spikes on as one ballot word per
 //              wavefront plus the block's spike and event counts (no shared counter: atomics on
-//              one address serialise at about 60 ns each on this chip).
+//              one address go through one at a time, and one that returns a value costs its
+//              wavefront a round trip).
 // So admission needs no atomics on the slots and no launch of its own; a contender's fate is known
 // one launch later (entry points that read counters or admission flags admit what is pending first).
 // An admitted event that is due in the very step it is admitted in (arrival offset 1) is
