@@ -105,6 +105,24 @@ def test_ring_rows_longer_than_a_staging_chunk():
     assert ref.spikes.sum() > 20 and ref.counters()["enqueued"] > 500000
 
 
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 5), ("sorted", 5), ("syn", 2)])
+def test_largest_delay_range(kind, cap):
+    """Delays up to the largest the interface allows (1,023 steps) over a run longer than that, so
+    that the delay line, the spike history and the arrival keys wrap around; forward and both
+    gradients."""
+    wl = synth.ragged_network(90, 60, 1023, seed=33, rate_hz=120.0, t=1500, b=2, w_mean=0.03, w_std=0.03)
+    # delays spread over the whole range, with both ends present
+    rng = np.random.default_rng(33)
+    d = rng.integers(1, 1024, size=wl.n_synapses)
+    d[:4] = (1, 1023, 1022, 2)
+    wl.delay_steps = None
+    wl.delay_ms = (d.astype(np.float32) * np.float32(wl.dt_ms)) - np.float32(0.03)   # continuous, just short of the grid
+    # (a small membrane cotangent: over 1,500 steps the gradient entries are sums of thousands of
+    # terms that partly cancel, and fp32 keeps 1e-6 absolute only if the terms are not large)
+    ref = _compare_backward(wl, KINDS[kind], cap, 1500, 2, dU_scale=1e-4, tape_spike_capacity=1500 * 2 * 90)
+    assert ref.spikes.sum() > 300 and int(ref.D.max()) == 1023 and int(ref.D.min()) == 1
+
+
 @pytest.mark.parametrize("window", [4, 32])
 def test_ring_backward_other_window_lengths(window, monkeypatch):
     monkeypatch.setenv("ADSEQ_RING_WINDOW", str(window))
@@ -239,13 +257,13 @@ def test_create_rejects_bad_delays_and_graph():
 
 # ---------------------------------------------------------------- backward
 
-def _compare_backward(wl, kind, cap, T, B, use_dU=True, surrogate=0, **kw):
+def _compare_backward(wl, kind, cap, T, B, use_dU=True, surrogate=0, dU_scale=1e-3, **kw):
     ref = oracle.Run(wl, kind, cap, n_steps=T, batch=B, surrogate=surrogate, n_threads=8)
     wl_t = synth.Workload(**{**wl.__dict__, "n_steps": T, "batch": B})
     y = synth.spike_count_targets(wl_t)
     counts = ref.spikes.sum(axis=0).astype(np.float32)
     dL_dc = (2.0 * (counts - y) / np.float32(B * wl.n_neurons)).astype(np.float32)
-    dL_dU = synth.random_cotangent(wl_t, scale=1e-3) if use_dU else None
+    dL_dU = synth.random_cotangent(wl_t, scale=dU_scale) if use_dU else None
     gw, gd = ref.backward(dL_dc, dL_dU)
     sim, out = H.run_gpu(wl, kind, cap, n_steps=T, batch=B, per_step=False, surrogate=surrogate, **kw)
     np.testing.assert_array_equal(out["U"].view(np.uint32), ref.U.view(np.uint32))
