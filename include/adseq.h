@@ -124,7 +124,8 @@ typedef struct {
   const int32_t *col;         /* [S] target neuron                                            */
   const float *weight;        /* [S] finite fp32; |amplitude| saturates at 128                */
   const uint8_t *delay_steps; /* [S] integer delays in steps, or NULL                         */
-  const float *delay_ms;      /* [S] continuous delays in ms, or NULL (exactly one is given)  */
+  const float *delay_ms;      /* [S] continuous delays in ms, or NULL (exactly one is given;
+                                 with S = 0 the four per-synapse arrays may all be NULL)       */
   /* The four arrays above must stay valid and unchanged for the life of the handle. */
   int64_t tape_spike_capacity; /* FIFO/SORTED with tape: spikes the tape's spike list can hold
                                   in total; 0 = default (max_steps * B * N / 16 + B * N)      */

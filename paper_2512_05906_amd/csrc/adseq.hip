@@ -853,8 +853,13 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   if (!cfg || !out) return ADSEQ_E_INVALID_ARG;
   Layout L;
   if (!make_layout(cfg, &L)) return ADSEQ_E_INVALID_ARG;
-  if (!cfg->row_ptr || !cfg->weight || (!cfg->col && cfg->n_synapses > 0)) return ADSEQ_E_INVALID_ARG;
-  if ((cfg->delay_steps == nullptr) == (cfg->delay_ms == nullptr)) return ADSEQ_E_INVALID_ARG;
+  if (!cfg->row_ptr) return ADSEQ_E_INVALID_ARG;
+  if (cfg->n_synapses > 0) {   // a network without synapses needs none of the per-synapse arrays
+    if (!cfg->weight || !cfg->col) return ADSEQ_E_INVALID_ARG;
+    if ((cfg->delay_steps == nullptr) == (cfg->delay_ms == nullptr)) return ADSEQ_E_INVALID_ARG;
+  } else if (cfg->delay_steps && cfg->delay_ms) {
+    return ADSEQ_E_INVALID_ARG;
+  }
   if (!cfg->workspace || ((uintptr_t)cfg->workspace & 255) || cfg->workspace_bytes < L.total)
     return ADSEQ_E_WORKSPACE;
   adseq* h = new (std::nothrow) adseq();

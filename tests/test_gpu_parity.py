@@ -123,6 +123,26 @@ def test_largest_delay_range(kind, cap):
     assert ref.spikes.sum() > 300 and int(ref.D.max()) == 1023 and int(ref.D.min()) == 1
 
 
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 2), ("sorted", 2), ("syn", 1)])
+def test_degenerate_networks(kind, cap):
+    """One neuron that talks to itself through three synapses (every block, word and part has a
+    single valid lane), and a network without any synapse (empty rows only, nothing ever queued)."""
+    one = synth.Workload(name="one", n_neurons=1, fan_out=3, n_steps=300, batch=3, d_max_steps=4,
+                         ext_rate_hz=900.0, seed=8, row_ptr=np.array([0, 3], np.int64),
+                         col=np.zeros(3, np.int32), weight=np.array([0.3, -0.1, 0.25], np.float32),
+                         delay_steps=np.array([1, 4, 2], np.uint8))
+    ref = _compare_backward(one, KINDS[kind], cap, 300, 3, tape_spike_capacity=900)
+    assert ref.spikes.sum() > 30
+    if kind != "ring":
+        assert ref.counters()["dropped"] > 0
+    none = synth.Workload(name="none", n_neurons=70, fan_out=0, n_steps=100, batch=2, d_max_steps=5,
+                          ext_rate_hz=900.0, seed=9, row_ptr=np.zeros(71, np.int64),
+                          col=np.zeros(0, np.int32), weight=np.zeros(0, np.float32),
+                          delay_steps=np.zeros(0, np.uint8))
+    ref, out = _compare_forward(none, KINDS[kind], cap, check_sets=False)
+    assert ref.spikes.sum() > 100 and out["counters"]["enqueued"] == 0
+
+
 @pytest.mark.parametrize("window", [4, 32])
 def test_ring_backward_other_window_lengths(window, monkeypatch):
     monkeypatch.setenv("ADSEQ_RING_WINDOW", str(window))
