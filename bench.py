@@ -169,6 +169,17 @@ def main():
         tj = json.load(open(tpath))
         traffic = tj.get(f"{args.workload}/{args.queue}", {}).get(dom)
 
+    # what a plain device-to-device copy of 1 GiB reaches on this machine (read + write bytes per second):
+    # the practical ceiling next to the datasheet peak
+    ca = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+    cb = torch.empty_like(ca)
+    ce = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    copy_gbs = 0.0
+    for _ in range(3):
+        ce[0].record(); cb.copy_(ca); ce[1].record(); torch.cuda.synchronize()
+        copy_gbs = max(copy_gbs, 2.0 * ca.numel() * 4 / (ce[0].elapsed_time(ce[1]) * 1e-3) / 1e9)
+    del ca, cb
+
     out = {
         "metric": "synaptic events delivered/s (fwd)",
         "value": value,
@@ -198,7 +209,9 @@ def main():
                      "avg_launch_us": kernels[dom]["avg_us"],
                      "algorithmic_bytes_per_launch": kernels[dom]["algorithmic_bytes_per_launch"],
                      "whole_run_achieved_GBs": achieved_run,
-                     "whole_run_frac": achieved_run / HBM_PEAK_GBS},
+                     "whole_run_frac": achieved_run / HBM_PEAK_GBS,
+                     "measured_copy_GBs": copy_gbs,
+                     "frac_of_measured_copy": kernels[dom]["achieved_GBs"] / copy_gbs if copy_gbs else None},
         "kernels": kernels,
     }
 
@@ -215,7 +228,8 @@ def main():
         U = sim.tape()["U"][:Ts].cpu().numpy()
         parity = bool(np.array_equal(U.view(np.uint32), ref.U.view(np.uint32)))
         out["cpu_baseline"] = {"value": rc["delivered"] / t_or, "unit": "events/s",
-                               "cores": min(B, os.cpu_count() or 1), "kind": "oracle",
+                               "cores": min(B, os.cpu_count() or 1), "cores_available": os.cpu_count(),
+                               "kind": "oracle",
                                "sample": f"first {Ts} of {T} time steps of the same network "
                                          f"({rc['enqueued']} events offered, {rc['delivered']} delivered), "
                                          f"forward only, {t_or:.1f} s",
