@@ -32,10 +32,15 @@ def erlang_b(servers: int, load: float) -> float:
     return b
 
 
-def run_case(torch, adseq, synth, kind_name, cap, n_queues, delay, interval, T, repeats=3):
+def run_case(torch, adseq, synth, kind_name, cap, n_queues, delay, interval, T, repeats=3, network=None):
+    """One open-loop run.  network = None: n_queues independent queues with one source each and one
+    delay; else a Workload whose neurons all fire as Poisson sources with mean interval `interval`
+    steps (the network's own delays and fan-out)."""
     import numpy as np
     kind = {"ring": adseq.RING, "fifo": adseq.FIFO, "sorted": adseq.SORTED, "syn": adseq.SYN_FIFO}[kind_name]
-    wl = synth.poisson_queues(n_queues, delay, n_steps=T)
+    wl = network if network is not None else synth.poisson_queues(n_queues, delay, n_steps=T)
+    if network is not None:
+        n_queues = wl.n_neurons
     if interval > 0:
         rate_hz = 1.0 / (interval * wl.dt_ms * 1e-3)
         lists = synth.poisson_spike_lists(n_queues, 1, T, rate_hz, wl.dt_ms, seed=11)
@@ -61,6 +66,10 @@ def run_case(torch, adseq, synth, kind_name, cap, n_queues, delay, interval, T, 
     c = sim.counters()
     sim.close()
     a = delay / interval if interval > 0 else 0.0
+    if network is not None and interval > 0:
+        # offered load of one target's queue: fan-in x rate x mean delay (all in steps)
+        fan_in = wl.n_synapses / wl.n_neurons
+        a = fan_in * (1.0 + wl.d_max_steps) / 2.0 / interval
     return {"queue": kind_name if interval > 0 else kind_name + " (control: no events)", "capacity": cap if kind != adseq.RING else None, "n_queues": n_queues,
             "delay_steps": delay, "mean_interval_steps": interval, "pressure": a, "time_steps": T,
             "us_per_time_step": ms * 1e3 / T, "ns_per_time_step_per_queue": ms * 1e6 / T / n_queues,
@@ -76,6 +85,9 @@ def main():
     ap.add_argument("--time-steps", type=int, default=4000)
     ap.add_argument("--delay", type=int, default=80)
     ap.add_argument("--sweep", action="store_true", help="capacity x pressure sweep of the drop rate")
+    ap.add_argument("--cfg2-rates", action="store_true",
+                    help="the 10,000-neuron x 1,000-fan-out network driven open loop at exactly 5, 20 and 80 Hz: "
+                         "ring against per-target FIFOs of capacity 8 and 32")
     args = ap.parse_args()
     import torch
     from paper_2512_05906_amd import adseq, synth
@@ -88,6 +100,15 @@ def main():
     if args.sweep:
         cases = [(k, c, lam) for lam in (400, 160, 80, 40, 20) for k, c in
                  (("fifo", 1), ("fifo", 2), ("fifo", 4), ("fifo", 8), ("sorted", 4), ("syn", 4))]
+    if args.cfg2_rates:
+        net = synth.cfg2(n_steps=min(args.time_steps, 2000))
+        for hz in (5.0, 20.0, 80.0):
+            interval = 1.0 / (hz * net.dt_ms * 1e-3)
+            for kind, cap in (("ring", 0), ("fifo", 8), ("fifo", 32)):
+                r = run_case(torch, adseq, synth, kind, cap, 0, 0, interval, net.n_steps, network=net)
+                r["rate_hz"] = hz
+                print(json.dumps(r), flush=True)
+        return
     for kind, cap, lam in cases:
         print(json.dumps(run_case(torch, adseq, synth, kind, cap, args.queues, args.delay, lam,
                                   args.time_steps)), flush=True)
