@@ -55,8 +55,10 @@ def main():
 
     import numpy as np
     import torch
-    from paper_2512_05906_amd import adseq, synth
+    from paper_2512_05906_amd import adseq, build, synth
 
+    if not os.path.exists(build.LIB):   # load what is built; build only if nothing is
+        build.build_library()
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
