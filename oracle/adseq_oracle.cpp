@@ -42,6 +42,9 @@
 //                   undelivered events; all events of a synapse share one delay,
 //                   so arrival order is emission order and an ordered queue
 //                   ("SortedArray") gives the same result
+//   latest spike    kind 4: one slot per synapse in which a new spike always takes
+//                   the place of the one held (Section 4.3 "SingleSpike(Drop)"): the
+//                   event that was held is lost (counted as dropped, never delivered)
 //   continuous d    arrival D = max(1, ceil(d/dt)) steps, amplitude
 //                   a = w * exp(-(D*dt - d)/tau_m)
 //   backward        event-sparse: the queue term exists only for emitted spikes
@@ -68,7 +71,8 @@ extern "C" {
 
 struct oracle_config {
   int32_t n_neurons, batch, d_max_steps, capacity;
-  int32_t kind;        // 0 ring (lossless), 1 fifo (bounded), 2 sorted (bounded), 3 one bounded FIFO per synapse
+  int32_t kind;        // 0 ring (lossless), 1 fifo (bounded), 2 sorted (bounded), 3 one bounded FIFO per synapse,
+                       // 4 one slot per synapse that holds the latest spike
   int32_t n_steps;
   int32_t surrogate;   // 0 SuperSpike, 1 off (sigma' == 0), 2 spike-time gradient (no surrogate)
   int32_t exact_f64;   // 0: fp32 state + Q8.24 sums (the method), 1: fp64, no quantisation
@@ -97,6 +101,7 @@ struct Event {
   int32_t k;       // arrival step
   int64_t syn;     // global synapse index
   int32_t n_emit;  // emission step
+  int64_t idx;     // its admission flag (kind 4 looks at it again when the event comes up)
 };
 struct Later {     // std::priority_queue is a max-heap: "less" = arrives later
   bool operator()(const Event& a, const Event& b) const {
@@ -224,7 +229,10 @@ void run_trial(oracle_run& r, int b) {
   Trial& tr = r.trials[b];
   std::priority_queue<Event, std::vector<Event>, Later> pq;
   const bool per_syn = c.kind == 3;   // occupancy counted per synapse instead of per target
-  std::vector<int32_t> occ(per_syn ? (size_t)c.n_synapses : (size_t)N, 0);
+  const bool latest = c.kind == 4;    // one slot per synapse, the newest spike replaces the held one
+  std::vector<int64_t> held(latest ? (size_t)c.n_synapses : 0, -1);   // admission flag of the held event
+  std::vector<int32_t> held_n(latest ? (size_t)c.n_synapses : 0, 0);
+  std::vector<int32_t> occ(per_syn ? (size_t)c.n_synapses : (latest ? (size_t)0 : (size_t)N), 0);
   std::vector<float> V(N, 0.0f), J(N, 0.0f);       // membrane state, synaptic current state
   std::vector<double> V64(N, 0.0), J64(N, 0.0);
   const bool syn_state = c.tau_syn_ms > 0.0f;
@@ -239,10 +247,14 @@ void run_trial(oracle_run& r, int b) {
     std::fill(acc64.begin(), acc64.end(), 0.0);
     while (!pq.empty() && pq.top().k == n) {
       const Event e = pq.top(); pq.pop();
+      if (latest) {
+        if (!tr.admitted[e.idx]) continue;     // it was replaced while in transit
+        held[e.syn] = -1;
+      }
       const int j = c.col[e.syn];
       acc[j] = (int32_t)((uint32_t)acc[j] + (uint32_t)r.a_q[e.syn]);  // wrapping add
       acc64[j] += r.a_d[e.syn];
-      occ[per_syn ? (size_t)e.syn : (size_t)j] -= 1;
+      if (!latest) occ[per_syn ? (size_t)e.syn : (size_t)j] -= 1;
       tr.n_delivered += 1; tr.sum_deliv += r.a_q[e.syn];
       if (c.log_events) tr.delivered.add(e.syn, e.n_emit, e.k, b);
     }
@@ -282,6 +294,18 @@ void run_trial(oracle_run& r, int b) {
         const int j = c.col[p];
         const int32_t k = n + r.D[p];
         tr.enqueued += 1; tr.sum_enq += r.a_q[p];
+        if (latest) {
+          if (held[p] >= 0) {                  // the spike held so far is lost
+            tr.admitted[held[p]] = 0;
+            tr.n_dropped += 1; tr.sum_drop += r.a_q[p];
+            if (c.log_events) tr.dropped.add(p, held_n[p], held_n[p] + r.D[p], b);
+          }
+          held[p] = (int64_t)tr.admitted.size(); held_n[p] = n;
+          tr.admitted.push_back(1);
+          tr.max_occ = 1;
+          pq.push(Event{k, p, n, held[p]});
+          continue;
+        }
         const size_t oi = per_syn ? (size_t)p : (size_t)j;
         if (bounded && occ[oi] >= c.capacity) {
           tr.admitted.push_back(0);
@@ -292,12 +316,15 @@ void run_trial(oracle_run& r, int b) {
         tr.admitted.push_back(1);
         occ[oi] += 1;
         tr.max_occ = std::max(tr.max_occ, occ[oi]);
-        pq.push(Event{k, p, n});
+        pq.push(Event{k, p, n, (int64_t)tr.admitted.size() - 1});
       }
     }
   }
-  tr.in_flight = (int64_t)pq.size();
-  while (!pq.empty()) { tr.sum_flight += r.a_q[pq.top().syn]; pq.pop(); }
+  tr.in_flight = 0;
+  while (!pq.empty()) {
+    if (!latest || tr.admitted[pq.top().idx]) { tr.in_flight += 1; tr.sum_flight += r.a_q[pq.top().syn]; }
+    pq.pop();
+  }
 }
 
 // Reverse-time sweep for one trial; adds this trial's contribution to gw, gd.
@@ -389,7 +416,7 @@ oracle_run* oracle_forward(const oracle_config* cfg) {
   r->cfg = *cfg;
   const oracle_config& c = r->cfg;
   if (c.n_neurons < 1 || c.batch < 1 || c.n_steps < 0 || c.d_max_steps < 1 ||
-      (c.kind != 0 && c.capacity < 1) || c.kind < 0 || c.kind > 3 ||
+      (c.kind != 0 && c.capacity < 1) || c.kind < 0 || c.kind > 4 ||
       !(c.dt_ms > 0.0f) || !(c.tau_m_ms > 0.0f) || c.dt_ms > c.tau_m_ms) {
     r->status = -1; return r;
   }

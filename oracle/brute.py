@@ -104,6 +104,24 @@ def replay_per_synapse(spikes: np.ndarray, row_ptr, D, capacity: int):
     return admitted, dropped
 
 
+def replay_latest(spikes: np.ndarray, row_ptr, D):
+    """One slot per synapse in which a new spike always replaces the one held (Section 4.3
+    "SingleSpike(Drop)").  Stated directly from the source's spike train: the event a spike at n
+    sends through a synapse of delay d is delivered iff the source does not fire again before it
+    arrives, i.e. at no step in (n, n + d); otherwise it is lost.  Returns (delivered-or-in-flight,
+    lost) as sets of (syn, n_emit, k)."""
+    T, N = spikes.shape
+    kept, lost = set(), set()
+    for i in range(N):
+        times = [int(t) for t in np.nonzero(spikes[:, i])[0]]
+        for p in range(int(row_ptr[i]), int(row_ptr[i + 1])):
+            d = int(D[p])
+            for x, n in enumerate(times):
+                nxt = times[x + 1] if x + 1 < len(times) else None
+                (lost if nxt is not None and nxt < n + d else kept).add((p, n, n + d))
+    return kept, lost
+
+
 def currents_from_events(events, col, amp, T: int, N: int) -> np.ndarray:
     """Sum the amplitudes of a list of (syn, n_emit, k) at their arrival step."""
     I = np.zeros((T, N), np.float64)

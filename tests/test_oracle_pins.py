@@ -227,6 +227,46 @@ def test_per_synapse_queue_lossless_equals_ring_and_differs_from_per_target():
     assert oracle.Run(wl, oracle.FIFO, occ - 1).counters()["dropped"] > lossy.counters()["dropped"]
 
 
+def test_latest_spike_slot_replay():
+    """Kind 4 (one slot per synapse, the newest spike replaces the held one) against the rule
+    stated from the source's spike train: an event is lost iff its source fires again before it
+    arrives."""
+    wl = _bursty(12)
+    r = oracle.Run(wl, oracle.SYN_LATEST, 1, log_events=True)
+    S = r.spikes[:, 0, :]
+    kept, lost = brute.replay_latest(S, wl.row_ptr, wl.delay_steps)
+    dr = r.event_log("dropped")
+    assert set(zip(dr["syn"].tolist(), dr["n_emit"].tolist(), dr["k"].tolist())) == lost
+    dl = r.event_log("delivered")
+    assert set(zip(dl["syn"].tolist(), dl["n_emit"].tolist(), dl["k"].tolist())) == {e for e in kept if e[2] < wl.n_steps}
+    c = r.counters()
+    assert len(lost) > 50 and c["dropped"] == len(lost)
+    assert c["enqueued"] == c["delivered"] + c["dropped"] + c["in_flight"]
+    assert c["sum_enqueued"] == c["sum_delivered"] + c["sum_dropped"] + c["sum_in_flight"]
+    # it differs from the slot that keeps the spike it holds (capacity-1 FIFO per synapse)
+    assert not np.array_equal(oracle.Run(wl, oracle.SYN_FIFO, 1).U, r.U)
+
+
+@pytest.mark.parametrize("period", [1, 3, 5, 8])
+def test_latest_spike_slot_periodic_source_closed_form(period):
+    """A source that fires every `period` steps, synapses with delays 1..7: every event of a synapse
+    with delay <= period is delivered, every event of a slower synapse is replaced before it
+    arrives (except the last one of the run, which nothing replaces)."""
+    n, T = 8, 96
+    delays = np.arange(1, 8, dtype=np.uint8)
+    row_ptr = np.zeros(n + 1, np.int64); row_ptr[1:] = len(delays)
+    wl = synth.Workload(name="periodic", n_neurons=n, fan_out=len(delays), n_steps=T, batch=1, d_max_steps=7,
+                        ext_rate_hz=0.0, seed=1, row_ptr=row_ptr, col=np.arange(1, 8, dtype=np.int32),
+                        weight=np.full(len(delays), 0.01, np.float32), delay_steps=delays)
+    forced = np.zeros((T, 1, n), np.uint8); forced[::period, 0, 0] = 1
+    r = oracle.Run(wl, oracle.SYN_LATEST, 1, forced_spikes=forced, log_events=True)
+    dr = r.event_log("dropped")
+    got = set(zip(dr["syn"].tolist(), dr["n_emit"].tolist()))
+    last = (T - 1) // period * period
+    want = {(p, t) for p, d in enumerate(delays.tolist()) for t in range(0, T, period) if d > period and t != last}
+    assert got == want
+
+
 def test_queue_kinds_agree_when_lossless():
     wl = synth.cfg0(seed=21)
     base = oracle.Run(wl, oracle.RING, keep_currents=True)
