@@ -44,6 +44,9 @@
 
 constexpr int kCont = 8;   // contender slots per target and step before the overflow list is used
 
+// The kinds with one queue per synapse.
+__device__ __host__ constexpr bool per_synapse_kind(int kind) { return kind == ADSEQ_SYN_FIFO || kind == ADSEQ_SYN_LATEST; }
+
 // Contender record, 128 bits: synapse index (40 bits), index of the admission flag on the tape
 // (40 bits, all ones = none), arrival step mod 2^16, Q8.24 amplitude.
 constexpr long long kMask40 = (1LL << 40) - 1;
@@ -288,12 +291,12 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
   const size_t BN = (size_t)d.BN;
   const unsigned kn = (unsigned)n;
   StepAcc r; r.acc = 0; r.popped = 0; r.c_adm = 0; r.s_adm = 0;
-  if (KIND != ADSEQ_SYN_FIFO && blockIdx.x == 0 && threadIdx.x == 0) d.ctr->pool_n[0] = 0;   // the overflow pool is consumed by this launch
+  if (!per_synapse_kind(KIND) && blockIdx.x == 0 && threadIdx.x == 0) d.ctr->pool_n[0] = 0;   // the overflow pool is consumed by this launch
   counts_clear(s_cnt);
   const bool dense = d.prefetch != 0;   // few targets: latency-bound, load everything in the first round
   float v = 0.0f, jsyn = 0.0f;
   int len = 0;
-  if (KIND == ADSEQ_SYN_FIFO) {
+  if (per_synapse_kind(KIND)) {
     // per-synapse queues: k_synq_pop has summed the events due now into the target's cell
     if (act) {
       if (MODE != 0) { r.acc = d.I_acc[g]; if (r.acc != 0) d.I_acc[g] = 0; }
@@ -449,7 +452,7 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
     // wavefront totals (every lane is active here), one LDS atomic per wavefront and counter;
     // a wavefront that delivered and admitted nothing, or has no spike, skips the sums
     long long t_pop = 0, t_acc = 0, t_adm = 0, t_sadm = 0, t_ev = 0;
-    if (KIND != ADSEQ_SYN_FIFO && __ballot(r.popped != 0 || r.c_adm != 0)) {
+    if (!per_synapse_kind(KIND) && __ballot(r.popped != 0 || r.c_adm != 0)) {
       t_pop = wave_total(r.popped); t_acc = wave_total(r.acc);
       t_adm = wave_total(r.c_adm); t_sadm = wave_total64(r.s_adm);
     }
@@ -472,13 +475,16 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
 }
 
 // A share of the row of a spike that is being offered: trial, row bounds, index of the row's first
-// admission flag on the tape (-1: none), offset of the share's first entry in the row.
-struct RowRef { int b; long long r0, r1, tbase, first; };
+// admission flag on the tape (-1: none), offset of the share's first entry in the row, and
+// (ADSEQ_SYN_LATEST) index of the first admission flag of the source's previous spike (-1: none).
+struct RowRef { int b; long long r0, r1, tbase, first, obase; };
 
 // Per-synapse queues (synapse_queues.h): the push that takes the place of offer_rows.
 __device__ __forceinline__ void push_rows(const Dev& d, long long n, const RowRef* rr, int nrows, long long stride,
                                           int& c_adm, long long& s_adm);
 __device__ __forceinline__ void push_counts_flush(const Dev& d, int c_adm, long long s_adm, BlkCtr& bc);
+__device__ __forceinline__ void push_rows_latest(const Dev& d, long long n, const RowRef* rr, int nrows,
+                                                 long long stride, int& c_adm, long long& s_adm);
 
 // Offers, for each of up to four row shares of step n, the entries r0 + first + threadIdx.x +
 // t * stride (t = 0, 1, ...) to their targets.  An event whose target is already full
@@ -549,7 +555,7 @@ __device__ __forceinline__ void offer_rows(const Dev& d, long long n, const RowR
 // row bounds (and, for share 0, the row sums).  A macro, so that the ballot words stay in registers.
 #define ADSEQ_LOAD_GROUP(NROWS)                                                                         \
   _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                       \
-    rr[j].b = 0; rr[j].r0 = 0; rr[j].r1 = 0; rr[j].tbase = -1; rr[j].first = (long long)c * kBlock; gs[j] = 0; \
+    rr[j].b = 0; rr[j].r0 = 0; rr[j].r1 = 0; rr[j].tbase = -1; rr[j].obase = -1; rr[j].first = (long long)c * kBlock; gs[j] = 0; \
     if (j < (NROWS)) {                                                                                  \
       while (!bits) { ++x; bits = x == 1 ? w[1] : x == 2 ? w[2] : w[3]; }                               \
       const int bit = __ffsll((long long)bits) - 1;                                                     \
@@ -558,12 +564,13 @@ __device__ __forceinline__ void offer_rows(const Dev& d, long long n, const RowR
     }                                                                                                   \
   }                                                                                                     \
   _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                       \
-    rs[j] = 0;                                                                                          \
+    rs[j] = 0; kc[j] = 0;                                                                               \
     if (j < (NROWS)) {                                                                                  \
       rr[j].b = d.B == 1 ? 0 : gs[j] / d.N;                                                             \
       const int i = gs[j] - rr[j].b * d.N;                                                              \
       rr[j].r0 = d.row_ptr[i]; rr[j].r1 = d.row_ptr[i + 1];                                             \
       if (c == 0 && threadIdx.x == 0) rs[j] = d.rowsum[i];                                              \
+      if (KIND == ADSEQ_SYN_LATEST && record) kc[j] = d.spk_count[gs[j]];                               \
     }                                                                                                   \
   }
 
@@ -599,6 +606,7 @@ __global__ __launch_bounds__(kBlock) void k_fanout_step(Dev d, long long n, int 
     RowRef rr[4];
     int gs[4];
     long long rs[4];
+    int kc[4];   // ADSEQ_SYN_LATEST with tape: spikes of the neuron so far, this one included
     { ADSEQ_LOAD_GROUP(nspk < 4 ? nspk : 4) }
     long long pre_s = 0, pre_e = 0;
     if (record) {
@@ -654,15 +662,22 @@ __global__ __launch_bounds__(kBlock) void k_fanout_step(Dev d, long long n, int 
               if (!ev_fits) atomicOr(&d.ctr->err, ERR_TAPE_EVENTS);
             }
             rr[j].tbase = evb;
+            if (KIND == ADSEQ_SYN_LATEST) {
+              // where the flags of the neuron's previous spike start (two cells per neuron, used in
+              // turn, so that the shares of this row read the old one while share 0 writes the new)
+              if (kc[j] >= 2) rr[j].obase = d.last_evb[(size_t)((kc[j] - 1) & 1) * d.BN + gs[j]];
+              if (c == 0 && threadIdx.x == 0) d.last_evb[(size_t)(kc[j] & 1) * d.BN + gs[j]] = evb;
+            }
             pre_e += len;
           }
         }
       }
       if (KIND == ADSEQ_SYN_FIFO) push_rows(d, n, rr, nrows, (long long)d.fsplit * kBlock, c_adm, s_adm);
+      else if (KIND == ADSEQ_SYN_LATEST) push_rows_latest(d, n, rr, nrows, (long long)d.fsplit * kBlock, c_adm, s_adm);
       else offer_rows(d, n, rr, nrows, (long long)d.fsplit * kBlock);
     }
   }
-  if (KIND == ADSEQ_SYN_FIFO) push_counts_flush(d, c_adm, s_adm, d.blk[d.nblk + blockIdx.x]);
+  if (per_synapse_kind(KIND)) push_counts_flush(d, c_adm, s_adm, d.blk[d.nblk + blockIdx.x]);
   if (c == 0 && threadIdx.x == 0 && c_off) {
     BlkCtr& bc = d.blk[d.nblk + blockIdx.x];   // private to this block
     atomicAdd(&bc.offered, (unsigned long long)c_off);   // atomics without return value: nobody waits for a load
@@ -689,12 +704,13 @@ __global__ __launch_bounds__(kBlock) void k_fanout_list(Dev d, long long n, cons
     const long long r0 = d.row_ptr[i], r1 = d.row_ptr[i + 1];
     RowRef rr[4];   // the one row as four interleaved shares: four entries per thread in flight
 #pragma unroll
-    for (int j = 0; j < 4; ++j) { rr[j].b = b; rr[j].r0 = r0; rr[j].r1 = r1; rr[j].tbase = -1; rr[j].first = (long long)j * kBlock; }
+    for (int j = 0; j < 4; ++j) { rr[j].b = b; rr[j].r0 = r0; rr[j].r1 = r1; rr[j].tbase = -1; rr[j].obase = -1; rr[j].first = (long long)j * kBlock; }
     if (threadIdx.x == 0) { c_off += r1 - r0; s_off += d.rowsum[i]; }
     if (KIND == ADSEQ_SYN_FIFO) push_rows(d, n, rr, 4, 4LL * kBlock, c_adm, s_adm);
+    else if (KIND == ADSEQ_SYN_LATEST) push_rows_latest(d, n, rr, 4, 4LL * kBlock, c_adm, s_adm);
     else offer_rows(d, n, rr, 4, 4LL * kBlock);
   }
-  if (KIND == ADSEQ_SYN_FIFO) push_counts_flush(d, c_adm, s_adm, d.blk[d.nblk + blockIdx.x]);
+  if (per_synapse_kind(KIND)) push_counts_flush(d, c_adm, s_adm, d.blk[d.nblk + blockIdx.x]);
   if (threadIdx.x == 0 && c_off) {
     BlkCtr& bc = d.blk[d.nblk + blockIdx.x];   // private to this block
     atomicAdd(&bc.offered, (unsigned long long)c_off);   // atomics without return value: nobody waits for a load

@@ -30,6 +30,8 @@ constexpr unsigned kSynqEmpty = 0xffffu;
 
 __device__ __forceinline__ unsigned synq_key(long long k) { return (unsigned)(k % 65535); }
 
+// LATEST: the queue is a single slot (ADSEQ_SYN_LATEST): nothing but the head key exists.
+template <bool LATEST>
 __global__ __launch_bounds__(kBlock) void k_synq_pop(Dev d, long long n) {
   __shared__ BlockCounts s_cnt;
   counts_clear(s_cnt);
@@ -59,14 +61,17 @@ __global__ __launch_bounds__(kBlock) void k_synq_pop(Dev d, long long n) {
         if (((j & 1) ? (x >> 16) : (x & 0xffffu)) != 0u) continue;
         const long long q = gi[h] * 8 + j;
         const long long b = q / d.S, p = q - b * d.S;
-        const unsigned hs = d.sq_hs[q];
         const int a = d.a_q[p];
         atomicAdd(&d.I_acc[(size_t)b * d.N + (d.packed[p] >> d.dbits)], a);
-        unsigned head = (hs >> 8) + 1u;
-        if (head >= (unsigned)d.C) head = 0u;
-        const unsigned size = (hs & 0xffu) - 1u;
-        const unsigned next = size ? (unsigned)d.sq_key[(size_t)q * d.C + head] : kSynqEmpty;
-        d.sq_hs[q] = (unsigned short)(size ? ((head << 8) | size) : 0u);
+        unsigned next = kSynqEmpty;
+        if (!LATEST) {
+          const unsigned hs = d.sq_hs[q];
+          unsigned head = (hs >> 8) + 1u;
+          if (head >= (unsigned)d.C) head = 0u;
+          const unsigned size = (hs & 0xffu) - 1u;
+          if (size) next = (unsigned)d.sq_key[(size_t)q * d.C + head];
+          d.sq_hs[q] = (unsigned short)(size ? ((head << 8) | size) : 0u);
+        }
         w[j >> 1] = (w[j >> 1] & ~(0xffffu << (16 * (j & 1)))) | (next << (16 * (j & 1)));
         popped += 1; sum += a;
         changed = true;
@@ -126,5 +131,40 @@ __device__ __forceinline__ void push_counts_flush(const Dev& d, int c_adm, long 
   if ((threadIdx.x & 63) == 0 && tc) {
     atomicAdd(&bc.admitted, (unsigned long long)tc);   // private to this block: no contention; without return value
     atomicAdd((unsigned long long*)&bc.sum_admitted, (unsigned long long)ts);
+  }
+}
+
+// ADSEQ_SYN_LATEST: the push of a slot that always takes the newest spike.  The event it held, if
+// any, is lost: it came from the source's previous spike, whose row of admission flags starts at
+// rr.obase on the tape (-1: no tape), so its flag is cleared here.  c_adm / s_adm count the net
+// change of the admitted events (a replacement changes neither: same synapse, same amplitude).
+__device__ __forceinline__ void push_rows_latest(const Dev& d, long long n, const RowRef* rr, int nrows,
+                                                 long long stride, int& c_adm, long long& s_adm) {
+  long long longest = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    if (j < nrows && rr[j].r1 - rr[j].r0 - rr[j].first > longest) longest = rr[j].r1 - rr[j].r0 - rr[j].first;
+  for (long long o = 0; o < longest; o += stride) {
+    long long p[4]; bool valid[4]; unsigned pk[4], old[4]; int a[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      p[j] = rr[j].r0 + rr[j].first + o + threadIdx.x;
+      valid[j] = j < nrows && p[j] < rr[j].r1;
+      pk[j] = 0; a[j] = 0; old[j] = kSynqEmpty;
+      if (valid[j]) {
+        pk[j] = d.packed[p[j]]; a[j] = d.a_q[p[j]];
+        old[j] = d.sq_next[(size_t)rr[j].b * d.S + p[j]];
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (!valid[j]) continue;
+      const size_t q = (size_t)rr[j].b * d.S + p[j];
+      d.sq_next[q] = (unsigned short)synq_key(n + (long long)(pk[j] & d.dmask));
+      const bool replaced = old[j] != kSynqEmpty;
+      if (!replaced) { c_adm += 1; s_adm += a[j]; }
+      if (rr[j].tbase >= 0) d.tape_adm[rr[j].tbase + (p[j] - rr[j].r0)] = 1;
+      if (replaced && rr[j].obase >= 0) d.tape_adm[rr[j].obase + (p[j] - rr[j].r0)] = 0;
+    }
   }
 }
