@@ -23,6 +23,10 @@
 //                   consecutive states: no atomics, no contenders, admission flags written once.
 // The dense first launch is the cost the per-target kinds avoid: it streams 2 bytes per synapse
 // and trial per step whether or not anything is in flight.
+//
+// ADSEQ_SYN_LATEST ("SingleSpike(Drop)": one slot per synapse, a new spike always replaces the one
+// held) uses sq_next alone: the pop is the same launch without the rest of the state, the push
+// overwrites (push_rows_latest at the end of this file).
 
 constexpr int kSynqCapMax = 8;
 constexpr int kSynqBlocks = 2048;   // blocks of k_synq_pop (grid-stride), each with a private counter line
