@@ -34,11 +34,39 @@ constexpr unsigned kSynqEmpty = 0xffffu;
 
 __device__ __forceinline__ unsigned synq_key(long long k) { return (unsigned)(k % 65535); }
 
+// Two phases per block, so that the scan stays a pure stream: the scan only notes the queues whose
+// head is due in an LDS list; then every thread takes one listed queue (all their loads in flight
+// together) -- delivers, moves the head on, and stores the new head key.
+constexpr int kSynqList = 2048;   // due queues a block notes before it works them off
+
+template <bool LATEST>
+__device__ __forceinline__ void synq_deliver(const Dev& d, long long q, int& popped, long long& sum) {
+  const long long b = q / d.S, p = q - b * d.S;
+  const int a = d.a_q[p];
+  const unsigned pk = d.packed[p];
+  unsigned next = kSynqEmpty;
+  if (!LATEST) {
+    const unsigned hs = d.sq_hs[q];
+    unsigned head = (hs >> 8) + 1u;
+    if (head >= (unsigned)d.C) head = 0u;
+    const unsigned size = (hs & 0xffu) - 1u;
+    if (size) next = (unsigned)d.sq_key[(size_t)q * d.C + head];
+    d.sq_hs[q] = (unsigned short)(size ? ((head << 8) | size) : 0u);
+  }
+  d.sq_next[q] = (unsigned short)next;
+  atomicAdd(&d.I_acc[(size_t)b * d.N + (pk >> d.dbits)], a);
+  popped += 1; sum += a;
+}
+
 // LATEST: the queue is a single slot (ADSEQ_SYN_LATEST): nothing but the head key exists.
 template <bool LATEST>
 __global__ __launch_bounds__(kBlock) void k_synq_pop(Dev d, long long n) {
   __shared__ BlockCounts s_cnt;
+  __shared__ long long s_list[kSynqList];
+  __shared__ int s_n;
   counts_clear(s_cnt);
+  if (threadIdx.x == 0) s_n = 0;
+  __syncthreads();
   const unsigned nk = synq_key(n);
   const unsigned nk2 = nk | (nk << 16);
   const long long Q = (long long)d.B * d.S;
@@ -46,7 +74,10 @@ __global__ __launch_bounds__(kBlock) void k_synq_pop(Dev d, long long n) {
   int popped = 0;
   long long sum = 0;
   const long long stride = (long long)gridDim.x * kBlock;
-  for (long long g0 = (long long)blockIdx.x * kBlock + threadIdx.x; g0 < groups; g0 += 4 * stride) {
+  // the same number of trips for every thread of the block (block barriers inside)
+  const long long first = (long long)blockIdx.x * kBlock;
+  for (long long base = first; base < groups; base += 4 * stride) {
+    const long long g0 = base + threadIdx.x;
     // four groups of eight queues per trip: their loads in flight together
     const long long gi[4] = {g0, g0 + stride, g0 + 2 * stride, g0 + 3 * stride};
     uint4 st[4];
@@ -57,30 +88,24 @@ __global__ __launch_bounds__(kBlock) void k_synq_pop(Dev d, long long n) {
     }
 #pragma unroll
     for (int h = 0; h < 4; ++h) {
-      unsigned w[4] = {st[h].x, st[h].y, st[h].z, st[h].w};
-      bool changed = false;
+      const unsigned w[4] = {st[h].x, st[h].y, st[h].z, st[h].w};
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const unsigned x = w[j >> 1] ^ nk2;                 // a zero half = a head that is due now
         if (((j & 1) ? (x >> 16) : (x & 0xffffu)) != 0u) continue;
         const long long q = gi[h] * 8 + j;
-        const long long b = q / d.S, p = q - b * d.S;
-        const int a = d.a_q[p];
-        atomicAdd(&d.I_acc[(size_t)b * d.N + (d.packed[p] >> d.dbits)], a);
-        unsigned next = kSynqEmpty;
-        if (!LATEST) {
-          const unsigned hs = d.sq_hs[q];
-          unsigned head = (hs >> 8) + 1u;
-          if (head >= (unsigned)d.C) head = 0u;
-          const unsigned size = (hs & 0xffu) - 1u;
-          if (size) next = (unsigned)d.sq_key[(size_t)q * d.C + head];
-          d.sq_hs[q] = (unsigned short)(size ? ((head << 8) | size) : 0u);
-        }
-        w[j >> 1] = (w[j >> 1] & ~(0xffffu << (16 * (j & 1)))) | (next << (16 * (j & 1)));
-        popped += 1; sum += a;
-        changed = true;
+        const int pos = atomicAdd(&s_n, 1);
+        if (pos < kSynqList) s_list[pos] = q;
+        else synq_deliver<LATEST>(d, q, popped, sum);       // no room to note it: done at once
       }
-      if (changed) reinterpret_cast<uint4*>(d.sq_next)[gi[h]] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    __syncthreads();
+    const int cnt = s_n < kSynqList ? s_n : kSynqList;
+    if (cnt > kSynqList / 2 || base + 4 * stride >= groups) {   // list half full, or the last trip
+      for (int x = threadIdx.x; x < cnt; x += kBlock) synq_deliver<LATEST>(d, s_list[x], popped, sum);
+      __syncthreads();
+      if (threadIdx.x == 0) s_n = 0;
+      __syncthreads();
     }
   }
   const long long t_pop = wave_total(popped), t_sum = wave_total64(sum);
