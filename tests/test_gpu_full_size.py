@@ -25,9 +25,9 @@ def wl():
     return synth.cfg3(rate_hz=55.0, n_steps=T)
 
 
-@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 32)])
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 32), ("latest", 1)])
 def test_cfg3_full_size_forward_backward(wl, kind, cap):
-    k = {"ring": oracle.RING, "fifo": oracle.FIFO}[kind]
+    k = {"ring": oracle.RING, "fifo": oracle.FIFO, "latest": oracle.SYN_LATEST}[kind]
     print(f"cfg3 full size, {kind}[{cap}], T={T}: oracle forward", flush=True)
     ref = oracle.Run(wl, k, cap, n_steps=T)
     rc = ref.counters()
@@ -54,6 +54,8 @@ def test_cfg3_full_size_forward_backward(wl, kind, cap):
     assert rc["enqueued"] > 2e7 and rc["delivered"] > 4e6
     if kind == "fifo":
         assert rc["dropped"] > 1e7
+    if kind == "latest":     # one slot per synapse and trial: 1e8 queues, looked at in every step
+        assert rc["dropped"] > 1e5
     cnt = torch.empty(wl.n_neurons, dtype=torch.int32, device=sim.dev)
     sim.spike_counts(cnt)
     np.testing.assert_array_equal(cnt.cpu().numpy(), counts.astype(np.int32).reshape(-1))
