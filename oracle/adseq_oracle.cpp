@@ -45,6 +45,13 @@
 //   latest spike    kind 4: one slot per synapse in which a new spike always takes
 //                   the place of the one held (Section 4.3 "SingleSpike(Drop)"): the
 //                   event that was held is lost (counted as dropped, never delivered)
+//   time bins       kind 5: `capacity` bins per synapse, an event with arrival step k
+//                   goes to bin k mod capacity and takes the place of whatever
+//                   undelivered event is there (Section 4.3 "LossyRingDelay(n)": a ring
+//                   shorter than the delay, which loses events that fall into the same
+//                   bin; the paper does not say which of the two is lost -- a plain ring
+//                   write keeps the newer, and with one bin that is exactly
+//                   "SingleSpike(Drop)", as "FIFORing(1)" is "SingleSpike(Hold)")
 //   continuous d    arrival D = max(1, ceil(d/dt)) steps, amplitude
 //                   a = w * exp(-(D*dt - d)/tau_m)
 //   backward        event-sparse: the queue term exists only for emitted spikes
@@ -72,7 +79,7 @@ extern "C" {
 struct oracle_config {
   int32_t n_neurons, batch, d_max_steps, capacity;
   int32_t kind;        // 0 ring (lossless), 1 fifo (bounded), 2 sorted (bounded), 3 one bounded FIFO per synapse,
-                       // 4 one slot per synapse that holds the latest spike
+                       // 4 one slot per synapse that holds the latest spike, 5 `capacity` time bins per synapse
   int32_t n_steps;
   int32_t surrogate;   // 0 SuperSpike, 1 off (sigma' == 0), 2 spike-time gradient (no surrogate)
   int32_t exact_f64;   // 0: fp32 state + Q8.24 sums (the method), 1: fp64, no quantisation
@@ -229,9 +236,10 @@ void run_trial(oracle_run& r, int b) {
   Trial& tr = r.trials[b];
   std::priority_queue<Event, std::vector<Event>, Later> pq;
   const bool per_syn = c.kind == 3;   // occupancy counted per synapse instead of per target
-  const bool latest = c.kind == 4;    // one slot per synapse, the newest spike replaces the held one
-  std::vector<int64_t> held(latest ? (size_t)c.n_synapses : 0, -1);   // admission flag of the held event
-  std::vector<int32_t> held_n(latest ? (size_t)c.n_synapses : 0, 0);
+  const bool latest = c.kind == 4 || c.kind == 5;   // the newest event replaces the one held in its slot / bin
+  const int nbins = c.kind == 5 ? c.capacity : 1;    // kind 4: one slot; kind 5: bin = arrival step mod capacity
+  std::vector<int64_t> held(latest ? (size_t)c.n_synapses * nbins : 0, -1);   // admission flag of the held event
+  std::vector<int32_t> held_n(latest ? (size_t)c.n_synapses * nbins : 0, 0);
   std::vector<int32_t> occ(per_syn ? (size_t)c.n_synapses : (latest ? (size_t)0 : (size_t)N), 0);
   std::vector<float> V(N, 0.0f), J(N, 0.0f);       // membrane state, synaptic current state
   std::vector<double> V64(N, 0.0), J64(N, 0.0);
@@ -249,7 +257,7 @@ void run_trial(oracle_run& r, int b) {
       const Event e = pq.top(); pq.pop();
       if (latest) {
         if (!tr.admitted[e.idx]) continue;     // it was replaced while in transit
-        held[e.syn] = -1;
+        held[(size_t)e.syn * nbins + e.k % nbins] = -1;
       }
       const int j = c.col[e.syn];
       acc[j] = (int32_t)((uint32_t)acc[j] + (uint32_t)r.a_q[e.syn]);  // wrapping add
@@ -295,15 +303,16 @@ void run_trial(oracle_run& r, int b) {
         const int32_t k = n + r.D[p];
         tr.enqueued += 1; tr.sum_enq += r.a_q[p];
         if (latest) {
-          if (held[p] >= 0) {                  // the spike held so far is lost
-            tr.admitted[held[p]] = 0;
+          const size_t hb = (size_t)p * nbins + k % nbins;
+          if (held[hb] >= 0) {                 // the event held there so far is lost
+            tr.admitted[held[hb]] = 0;
             tr.n_dropped += 1; tr.sum_drop += r.a_q[p];
-            if (c.log_events) tr.dropped.add(p, held_n[p], held_n[p] + r.D[p], b);
+            if (c.log_events) tr.dropped.add(p, held_n[hb], held_n[hb] + r.D[p], b);
           }
-          held[p] = (int64_t)tr.admitted.size(); held_n[p] = n;
+          held[hb] = (int64_t)tr.admitted.size(); held_n[hb] = n;
           tr.admitted.push_back(1);
-          tr.max_occ = 1;
-          pq.push(Event{k, p, n, held[p]});
+          tr.max_occ = std::max(tr.max_occ, 1);
+          pq.push(Event{k, p, n, held[hb]});
           continue;
         }
         const size_t oi = per_syn ? (size_t)p : (size_t)j;
@@ -416,7 +425,7 @@ oracle_run* oracle_forward(const oracle_config* cfg) {
   r->cfg = *cfg;
   const oracle_config& c = r->cfg;
   if (c.n_neurons < 1 || c.batch < 1 || c.n_steps < 0 || c.d_max_steps < 1 ||
-      (c.kind != 0 && c.capacity < 1) || c.kind < 0 || c.kind > 4 ||
+      (c.kind != 0 && c.capacity < 1) || c.kind < 0 || c.kind > 5 ||
       !(c.dt_ms > 0.0f) || !(c.tau_m_ms > 0.0f) || c.dt_ms > c.tau_m_ms) {
     r->status = -1; return r;
   }

@@ -122,6 +122,35 @@ def replay_latest(spikes: np.ndarray, row_ptr, D):
     return kept, lost
 
 
+def replay_time_bins(spikes: np.ndarray, row_ptr, D, bins: int):
+    """`bins` time bins per synapse (Section 4.3 "LossyRingDelay(n)", read as a ring of spike times
+    shorter than the delay): an event with arrival step k is written to bin k mod bins, over
+    whatever is there; at step t bin t mod bins is looked at and delivers if its event is due.
+    Replayed per synapse step by step.  Returns (delivered-or-in-flight, lost) as sets of
+    (syn, n_emit, k)."""
+    T, N = spikes.shape
+    kept, lost = set(), set()
+    for i in range(N):
+        fired = spikes[:, i] != 0
+        for p in range(int(row_ptr[i]), int(row_ptr[i + 1])):
+            d = int(D[p])
+            ring = [None] * bins                     # (n_emit, k) or None
+            for t in range(T):
+                held = ring[t % bins]
+                if held is not None and held[1] == t:
+                    kept.add((p, held[0], held[1]))
+                    ring[t % bins] = None
+                if fired[t]:
+                    k = t + d
+                    if ring[k % bins] is not None:
+                        lost.add((p,) + ring[k % bins])
+                    ring[k % bins] = (t, k)
+            for held in ring:                        # still in flight when the run ends
+                if held is not None:
+                    kept.add((p,) + held)
+    return kept, lost
+
+
 def currents_from_events(events, col, amp, T: int, N: int) -> np.ndarray:
     """Sum the amplitudes of a list of (syn, n_emit, k) at their arrival step."""
     I = np.zeros((T, N), np.float64)

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "adseq_oracle.cpp")
 _LIB = os.path.join(_HERE, "liboracle.so")
 
-RING, FIFO, SORTED, SYN_FIFO, SYN_LATEST = 0, 1, 2, 3, 4
+RING, FIFO, SORTED, SYN_FIFO, SYN_LATEST, SYN_BINS = 0, 1, 2, 3, 4, 5
 SURR_SUPERSPIKE, SURR_OFF, GRAD_SPIKE_TIME = 0, 1, 2
 
 

@@ -52,7 +52,8 @@ def test_single_synapse_closed_form_delay_and_weight_gradient():
 
 
 @pytest.mark.parametrize("kind,cap,tau_syn", [(oracle.RING, 0, 0.0), (oracle.FIFO, 3, 0.0), (oracle.RING, 0, 2.0),
-                                              (oracle.SYN_FIFO, 1, 0.0), (oracle.SYN_LATEST, 1, 0.0)])
+                                              (oracle.SYN_FIFO, 1, 0.0), (oracle.SYN_LATEST, 1, 0.0),
+                                              (oracle.SYN_BINS, 2, 0.0)])
 def test_central_finite_differences_frozen_raster(kind, cap, tau_syn):
     """Smooth loss L = sum c[n,j] U_j[n] on a 10-neuron net, raster frozen, fp64
     without quantisation, surrogate off: reverse-mode grad_w / grad_d must equal
@@ -72,7 +73,7 @@ def test_central_finite_differences_frozen_raster(kind, cap, tau_syn):
 
     L0, r0 = loss(wl)
     gw, gd = r0.backward(None, c)
-    if kind in (oracle.FIFO, oracle.SYN_FIFO, oracle.SYN_LATEST):
+    if kind in (oracle.FIFO, oracle.SYN_FIFO, oracle.SYN_LATEST, oracle.SYN_BINS):
         assert r0.counters()["dropped"] > 0
     rng = np.random.default_rng(1)
     dt = float(np.float32(wl.dt_ms))
@@ -106,7 +107,7 @@ def test_central_finite_differences_frozen_raster(kind, cap, tau_syn):
 
 @pytest.mark.parametrize("kind,cap,continuous", [(oracle.RING, 0, False), (oracle.FIFO, 3, False),
                                                   (oracle.SORTED, 4, True), (oracle.SYN_FIFO, 1, True),
-                                                  (oracle.SYN_LATEST, 1, False)])
+                                                  (oracle.SYN_LATEST, 1, False), (oracle.SYN_BINS, 2, True)])
 def test_reverse_mode_is_transpose_of_forward_mode(kind, cap, continuous):
     """<u, J v> == <J^T u, v> with J propagated in forward mode by oracle/tangent.py
     (surrogate on, spike-count and membrane cotangents, several trials)."""

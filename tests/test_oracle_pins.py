@@ -267,6 +267,61 @@ def test_latest_spike_slot_periodic_source_closed_form(period):
     assert got == want
 
 
+@pytest.mark.parametrize("bins", [1, 2, 3, 5])
+def test_time_bins_replay(bins):
+    """Kind 5 (time bins per synapse, the newer event takes the bin) against a step-by-step replay
+    of one ring of spike times per synapse."""
+    wl = _bursty(15)
+    r = oracle.Run(wl, oracle.SYN_BINS, bins, log_events=True)
+    S = r.spikes[:, 0, :]
+    kept, lost = brute.replay_time_bins(S, wl.row_ptr, wl.delay_steps, bins)
+    dr = r.event_log("dropped")
+    assert set(zip(dr["syn"].tolist(), dr["n_emit"].tolist(), dr["k"].tolist())) == lost
+    dl = r.event_log("delivered")
+    assert set(zip(dl["syn"].tolist(), dl["n_emit"].tolist(), dl["k"].tolist())) == {e for e in kept if e[2] < wl.n_steps}
+    c = r.counters()
+    assert len(lost) > 20 and c["dropped"] == len(lost)
+    assert c["enqueued"] == c["delivered"] + c["dropped"] + c["in_flight"]
+    assert c["sum_enqueued"] == c["sum_delivered"] + c["sum_dropped"] + c["sum_in_flight"]
+
+
+def test_time_bins_special_cases():
+    """One bin is the slot that holds the latest spike; as many bins as the largest delay lose
+    nothing (the arrivals in flight on a synapse are distinct and less than its delay apart)."""
+    wl = _bursty(16)
+    one = oracle.Run(wl, oracle.SYN_BINS, 1)
+    np.testing.assert_array_equal(one.U, oracle.Run(wl, oracle.SYN_LATEST, 1).U)
+    assert one.counters() == oracle.Run(wl, oracle.SYN_LATEST, 1).counters()
+    full = oracle.Run(wl, oracle.SYN_BINS, int(wl.delay_steps.max()), keep_currents=True)
+    base = oracle.Run(wl, oracle.RING, keep_currents=True)
+    np.testing.assert_array_equal(full.U, base.U)
+    np.testing.assert_array_equal(full.Iq, base.Iq)
+    assert full.counters()["dropped"] == 0
+    assert oracle.Run(wl, oracle.SYN_BINS, 2).counters()["dropped"] > 0
+
+
+@pytest.mark.parametrize("bins,period", [(2, 1), (3, 2), (4, 3), (4, 2), (5, 1)])
+def test_time_bins_periodic_source_closed_form(bins, period):
+    """A source that fires every `period` steps: the events in flight on a synapse arrive `period`
+    apart, so an event is overwritten iff a later one, m periods on, lands in its bin (m * period a
+    multiple of `bins`) while it is still in flight (m * period < delay): iff lcm(period, bins) <
+    delay -- except the events so late in the run that the overwriting spike never comes."""
+    n, T = 8, 120
+    delays = np.arange(1, 8, dtype=np.uint8)
+    row_ptr = np.zeros(n + 1, np.int64); row_ptr[1:] = len(delays)
+    wl = synth.Workload(name="periodic", n_neurons=n, fan_out=len(delays), n_steps=T, batch=1, d_max_steps=7,
+                        ext_rate_hz=0.0, seed=1, row_ptr=row_ptr, col=np.arange(1, 8, dtype=np.int32),
+                        weight=np.full(len(delays), 0.01, np.float32), delay_steps=delays)
+    forced = np.zeros((T, 1, n), np.uint8); forced[::period, 0, 0] = 1
+    r = oracle.Run(wl, oracle.SYN_BINS, bins, forced_spikes=forced, log_events=True)
+    dr = r.event_log("dropped")
+    got = set(zip(dr["syn"].tolist(), dr["n_emit"].tolist()))
+    lcm = math.lcm(period, bins)
+    want = {(p, t) for p, d in enumerate(delays.tolist()) for t in range(0, T, period)
+            if lcm < d and t + lcm < T}
+    assert got == want
+
+
 def test_queue_kinds_agree_when_lossless():
     wl = synth.cfg0(seed=21)
     base = oracle.Run(wl, oracle.RING, keep_currents=True)
