@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0
 # adjoint gather + 16 B of gradient read-modify-writes; per-synapse queues: 9 + 2 B key write + 4 B
 # state read-modify-write per event, and 2 B of queue state per synapse, trial and time step (every
 # queue is looked at in every step: that is what the organisation costs)
-FWD_B_EVENT = {"ring": 17, "fifo": 25, "sorted": 25, "syn": 15, "latest": 13}
+FWD_B_EVENT = {"ring": 17, "fifo": 25, "sorted": 25, "syn": 15, "latest": 13, "bins": 21}
 SYN_B_QUEUE_STEP = 2
 FWD_B_NEURON = 20          # queue row read + clear, V read + write, U tape write
 BWD_B_EVENT = 29
@@ -41,7 +41,7 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="cfg3", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4"])
-    ap.add_argument("--queue", default="ring", choices=["ring", "fifo", "sorted", "syn", "latest"])
+    ap.add_argument("--queue", default="ring", choices=["ring", "fifo", "sorted", "syn", "latest", "bins"])
     ap.add_argument("--capacity", type=int, default=32)
     ap.add_argument("--time-steps", type=int, default=0, help="override the workload's T")
     ap.add_argument("--drive-hz", type=float, default=0.0, help="override the rate of the Poisson drive")
@@ -69,7 +69,7 @@ def main():
     T = args.time_steps or wl.n_steps
     B, N = wl.batch, wl.n_neurons
     BN = B * N
-    kind = {"ring": adseq.RING, "fifo": adseq.FIFO, "sorted": adseq.SORTED, "syn": adseq.SYN_FIFO, "latest": adseq.SYN_LATEST}[args.queue]
+    kind = {"ring": adseq.RING, "fifo": adseq.FIFO, "sorted": adseq.SORTED, "syn": adseq.SYN_FIFO, "latest": adseq.SYN_LATEST, "bins": adseq.SYN_BINS}[args.queue]
     cap = 0 if kind == adseq.RING else (1 if kind == adseq.SYN_LATEST else args.capacity)
     fan = wl.n_synapses // N
     # room on the tape of the bounded kinds: ten times the spikes of a run at 20 Hz
@@ -114,7 +114,7 @@ def main():
     value = delivered / (fwd_ms * 1e-3)
     admitted = offered - dropped
     fwd_bytes = FWD_B_EVENT[args.queue] * offered + FWD_B_NEURON * BN * T
-    if args.queue in ("syn", "latest"):
+    if args.queue in ("syn", "latest", "bins"):
         fwd_bytes += SYN_B_QUEUE_STEP * B * wl.n_synapses * T
     bwd_bytes = BWD_B_EVENT * admitted + BWD_B_NEURON * BN * T
     achieved_run = (fwd_bytes + bwd_bytes) / ((fwd_ms + bwd_ms) * 1e-3) / 1e9
@@ -128,7 +128,7 @@ def main():
     in_run = delivered  # admitted events that arrive inside the run: the ones backward touches
     alg = {  # algorithmic bytes per run of each kernel class
         "fan_out": (FWD_B_EVENT[args.queue]) * offered,
-        "lif": FWD_B_NEURON * BN * T + (SYN_B_QUEUE_STEP * B * wl.n_synapses * T if args.queue in ("syn", "latest") else 0),
+        "lif": FWD_B_NEURON * BN * T + (SYN_B_QUEUE_STEP * B * wl.n_synapses * T if args.queue in ("syn", "latest", "bins") else 0),
         "bwd_gather": BWD_B_EVENT * in_run,
         "bwd_neurons": BWD_B_NEURON * BN * T,
     }
@@ -154,7 +154,7 @@ def main():
     else:
         label = {"fan_out": "k_fanout_step (CSR fan-out, full-target drops, contender registration)",
                  "lif": ("k_synq_pop + k_neurons (look at every queue, then drive + LIF + spike words)"
-                         if args.queue in ("syn", "latest") else "k_neurons (admission + pop + drive + LIF + spike words)"),
+                         if args.queue in ("syn", "latest", "bins") else "k_neurons (admission + pop + drive + LIF + spike words)"),
                  "bwd_gather": "k_bwd_rows (adjoint gathers and gradient sums of the step's recorded spikes)",
                  "bwd_neurons": "k_bwd_neurons (adjoint update)"}
     kernels = {}

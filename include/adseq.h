@@ -63,6 +63,12 @@
  *                 of the one held ("SingleSpike(Drop)"): the event that was held is lost --
  *                 counted as dropped, never delivered, its admission flag on the tape
  *                 cleared.  capacity must be 1.  State: 2 bytes per synapse and trial.
+ *   ADSEQ_SYN_BINS `capacity` (1..8) time bins per synapse and trial: an event with arrival step k
+ *                 goes to bin k mod capacity and takes the place of whatever undelivered
+ *                 event is there, which is lost ("LossyRingDelay(n)", a ring shorter than the
+ *                 delay, read as a ring of arrival times in which a write keeps the newer
+ *                 event; one bin is ADSEQ_SYN_LATEST).  State: 2 capacity bytes per synapse
+ *                 and trial, with a tape 8 capacity more (where each held event's flag is).
  *   Admission order within a step is canonical: ascending global synapse index
  *   (= ascending source neuron, then position in the row), independently per trial.
  */
@@ -78,7 +84,7 @@ extern "C" {
 
 typedef struct adseq adseq_t; /* opaque; host memory owned by the library, freed by adseq_destroy */
 
-enum { ADSEQ_RING = 0, ADSEQ_FIFO = 1, ADSEQ_SORTED = 2, ADSEQ_SYN_FIFO = 3, ADSEQ_SYN_LATEST = 4 };
+enum { ADSEQ_RING = 0, ADSEQ_FIFO = 1, ADSEQ_SORTED = 2, ADSEQ_SYN_FIFO = 3, ADSEQ_SYN_LATEST = 4, ADSEQ_SYN_BINS = 5 };
 /* How a spike passes gradients back (config field `surrogate`):
  *   ADSEQ_SURR_SUPERSPIKE  the spike function has the SuperSpike derivative 1/(|U - theta| + 1)^2 (eq. 7);
  *   ADSEQ_SURR_OFF         it has derivative 0 (only the direct dependence of amplitudes on weights
@@ -109,8 +115,8 @@ typedef struct {
   int32_t batch;        /* B >= 1 independent trials sharing the network                      */
   int32_t d_max_steps;  /* largest arrival offset in steps, 1..1023                           */
   int32_t capacity;     /* slots per target for FIFO / SORTED (1..32767), per synapse for
-                           SYN_FIFO (1..8), 1 for SYN_LATEST; ignored for RING                */
-  int32_t kind;         /* ADSEQ_RING / _FIFO / _SORTED / _SYN_FIFO / _SYN_LATEST               */
+                           SYN_FIFO and SYN_BINS (1..8), 1 for SYN_LATEST; ignored for RING   */
+  int32_t kind;         /* ADSEQ_RING / _FIFO / _SORTED / _SYN_FIFO / _SYN_LATEST / _SYN_BINS   */
   int32_t surrogate;    /* ADSEQ_SURR_SUPERSPIKE / ADSEQ_SURR_OFF / ADSEQ_GRAD_SPIKE_TIME      */
   int32_t record_tape;  /* 1 = adseq_step keeps what adseq_backward needs                     */
   int32_t max_steps;    /* tape length in steps (needed when record_tape = 1)                 */

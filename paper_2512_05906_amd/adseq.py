@@ -16,7 +16,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("ADSEQ_LIB", os.path.join(_HERE, "libadseq.so"))
 
-RING, FIFO, SORTED, SYN_FIFO, SYN_LATEST = 0, 1, 2, 3, 4
+RING, FIFO, SORTED, SYN_FIFO, SYN_LATEST, SYN_BINS = 0, 1, 2, 3, 4, 5
 SURR_SUPERSPIKE, SURR_OFF, GRAD_SPIKE_TIME = 0, 1, 2
 
 ERRORS = {0: "OK", -1: "INVALID_ARG", -2: "DELAY_RANGE", -3: "WORKSPACE", -4: "ORDER",

@@ -127,6 +127,7 @@ struct Dev {
   unsigned short* sq_next; // SYN_FIFO: [ceil(B S / 8) * 8] arrival step of the head of every per-synapse queue (0xffff: empty)
   unsigned short* sq_hs;   // SYN_FIFO: [B S] head << 8 | size
   unsigned short* sq_key;  // SYN_FIFO: [B S][C] arrival step mod 2^16 of every slot
+  long long* sq_flag;      // SYN_BINS with tape: [C][ceil(B S / 8) * 8] index on the tape of the admission flag of the event every bin holds
   long long* last_evb;     // SYN_LATEST with tape: [2][BN] index of the first admission flag of the neuron's last spike and of the one before, in turn
   int* I_acc;              // SYN_FIFO / SYN_LATEST: [BN] Q8.24 sum of the events popped for the step being run
   int blk_pop;             // SYN_FIFO: index of the first counter line of k_synq_pop's blocks in blk
@@ -426,7 +427,7 @@ struct adseq {
 namespace {
 
 struct Layout {
-  size_t V, J, bwd_carryJ, win, spike_bits, sq_next, sq_hs, sq_key, I_acc, last_evb, slot, fkey, famp, vmask, occ, head, min_k, cnt, cont, c_head, pool_p, pool_t, pool_next,
+  size_t V, J, bwd_carryJ, win, spike_bits, sq_next, sq_hs, sq_key, sq_flag, I_acc, last_evb, slot, fkey, famp, vmask, occ, head, min_k, cnt, cont, c_head, pool_p, pool_t, pool_next,
       pool_k, pool_a, spk_words, stepcnt, packed, a_q, synf, synb, dstart, nearcnt, perm, rowsum, rowlen, ebuf, ecnt, amp, fdec, tapeU,
       tape_bits, spk_count, step_off, step_evoff, tape_spk, tape_evb, tape_row, tape_adm, bwd_ring, bwd_carry, bwd_G, gwin, Gacc, gsum, ctr, blk,
       total;
@@ -462,9 +463,9 @@ bool host_validate(const adseq_config* c) {
   if (c->n_neurons < 1 || c->batch < 1 || c->d_max_steps < 1 || c->d_max_steps > 1023) return false;
   if ((long long)c->n_neurons * c->batch > 0x7fffffffLL) return false;
   if (c->kind != ADSEQ_RING && c->kind != ADSEQ_FIFO && c->kind != ADSEQ_SORTED && c->kind != ADSEQ_SYN_FIFO &&
-      c->kind != ADSEQ_SYN_LATEST) return false;
+      c->kind != ADSEQ_SYN_LATEST && c->kind != ADSEQ_SYN_BINS) return false;
   if (c->kind != ADSEQ_RING && (c->capacity < 1 || c->capacity > 32767)) return false;
-  if (c->kind == ADSEQ_SYN_FIFO && c->capacity > kSynqCapMax) return false;
+  if ((c->kind == ADSEQ_SYN_FIFO || c->kind == ADSEQ_SYN_BINS) && c->capacity > kSynqCapMax) return false;
   if (c->kind == ADSEQ_SYN_LATEST && c->capacity != 1) return false;
   if (c->surrogate != ADSEQ_SURR_SUPERSPIKE && c->surrogate != ADSEQ_SURR_OFF &&
       c->surrogate != ADSEQ_GRAD_SPIKE_TIME) return false;
@@ -566,7 +567,9 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->pool_a = take((size_t)L->pool_cap * 4);
   {
     const size_t Q = (size_t)c->batch * S;
-    L->sq_next = take(synq ? (Q + 7) / 8 * 16 : 0);
+    const size_t nbins = c->kind == ADSEQ_SYN_BINS ? (size_t)c->capacity : 1;
+    L->sq_next = take(synq ? nbins * ((Q + 7) / 8 * 16) : 0);
+    L->sq_flag = take(c->kind == ADSEQ_SYN_BINS && c->record_tape ? nbins * ((Q + 7) / 8 * 8) * 8 : 0);
     L->sq_hs = take(synfifo ? Q * 2 : 0);
     L->sq_key = take(synfifo ? Q * (size_t)c->capacity * 2 : 0);
     L->I_acc = take(synq ? BN * 4 : 0);
@@ -650,7 +653,8 @@ void launch_reset(adseq* h, hipStream_t st) {
     fill_u32(st, d.spike_bits, 0u, (size_t)d.R * d.words * 2);
     fill_u32(st, d.blk, 0u, kMaxBinBlocks * sizeof(BlkCtr) / 4);
   } else if (per_synapse_kind(d.kind)) {
-    fill_u32(st, d.sq_next, 0xffffffffu, ((size_t)d.B * d.S + 7) / 8 * 4);   // every queue empty
+    fill_u32(st, d.sq_next, 0xffffffffu,
+             (size_t)(d.kind == ADSEQ_SYN_BINS ? d.C : 1) * (((size_t)d.B * d.S + 7) / 8 * 4));   // every queue empty
     if (d.kind == ADSEQ_SYN_FIFO) fill_u32(st, d.sq_hs, 0u, ((size_t)d.B * d.S + 1) / 2);   // (the keys need no clearing)
     fill_u32(st, d.I_acc, 0u, BN);
     fill_u32(st, d.blk, 0u, ((size_t)d.blk_pop + kSynqBlocks) * sizeof(BlkCtr) / 4);
@@ -686,11 +690,16 @@ void launch_neurons(adseq* h, hipStream_t st, long long n, int parity, const flo
     // per-synapse queues: every queue is looked at first (nothing is pending for MODE 0)
     if (MODE == 0) return;
     if (d.kind == ADSEQ_SYN_FIFO) {
-      hipLaunchKernelGGL(k_synq_pop<false>, dim3(kSynqBlocks), block, 0, st, d, n);
+      hipLaunchKernelGGL(k_synq_pop<false>, dim3(kSynqBlocks), block, 0, st, d, n, 0LL);
       hipLaunchKernelGGL((k_neurons<ADSEQ_SYN_FIFO, MODE>), grid, block, 0, st, d, n, parity, i_ext, spikes_out, I_out);
-    } else {
-      hipLaunchKernelGGL(k_synq_pop<true>, dim3(kSynqBlocks), block, 0, st, d, n);
+    } else if (d.kind == ADSEQ_SYN_LATEST) {
+      hipLaunchKernelGGL(k_synq_pop<true>, dim3(kSynqBlocks), block, 0, st, d, n, 0LL);
       hipLaunchKernelGGL((k_neurons<ADSEQ_SYN_LATEST, MODE>), grid, block, 0, st, d, n, parity, i_ext, spikes_out, I_out);
+    } else {
+      // the bin of this step: its keys are contiguous
+      const long long qpad = (((long long)d.B * d.S + 7) >> 3) << 3;
+      hipLaunchKernelGGL(k_synq_pop<true>, dim3(kSynqBlocks), block, 0, st, d, n, (n % d.C) * qpad);
+      hipLaunchKernelGGL((k_neurons<ADSEQ_SYN_BINS, MODE>), grid, block, 0, st, d, n, parity, i_ext, spikes_out, I_out);
     }
   } else if (d.kind == ADSEQ_FIFO)
     hipLaunchKernelGGL((k_neurons<ADSEQ_FIFO, MODE>), grid, block, 0, st, d, n, parity, i_ext, spikes_out, I_out);
@@ -709,12 +718,14 @@ void launch_fanout(adseq* h, hipStream_t st, long long n, const int* spk, const 
     if (d.kind == ADSEQ_FIFO) hipLaunchKernelGGL((k_fanout_step<ADSEQ_FIFO>), grid, block, 0, st, d, n, parity, record);
     else if (d.kind == ADSEQ_SYN_FIFO) hipLaunchKernelGGL((k_fanout_step<ADSEQ_SYN_FIFO>), grid, block, 0, st, d, n, parity, record);
     else if (d.kind == ADSEQ_SYN_LATEST) hipLaunchKernelGGL((k_fanout_step<ADSEQ_SYN_LATEST>), grid, block, 0, st, d, n, parity, record);
+    else if (d.kind == ADSEQ_SYN_BINS) hipLaunchKernelGGL((k_fanout_step<ADSEQ_SYN_BINS>), grid, block, 0, st, d, n, parity, record);
     else hipLaunchKernelGGL((k_fanout_step<ADSEQ_SORTED>), grid, block, 0, st, d, n, parity, record);
   } else {
     const dim3 grid(kFanoutBlocks);
     if (d.kind == ADSEQ_FIFO) hipLaunchKernelGGL((k_fanout_list<ADSEQ_FIFO>), grid, block, 0, st, d, n, spk, n_spk);
     else if (d.kind == ADSEQ_SYN_FIFO) hipLaunchKernelGGL((k_fanout_list<ADSEQ_SYN_FIFO>), grid, block, 0, st, d, n, spk, n_spk);
     else if (d.kind == ADSEQ_SYN_LATEST) hipLaunchKernelGGL((k_fanout_list<ADSEQ_SYN_LATEST>), grid, block, 0, st, d, n, spk, n_spk);
+    else if (d.kind == ADSEQ_SYN_BINS) hipLaunchKernelGGL((k_fanout_list<ADSEQ_SYN_BINS>), grid, block, 0, st, d, n, spk, n_spk);
     else hipLaunchKernelGGL((k_fanout_list<ADSEQ_SORTED>), grid, block, 0, st, d, n, spk, n_spk);
   }
   h->pending_admit = !per_synapse_kind(d.kind);   // a per-synapse push is final
@@ -936,6 +947,7 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   d.pool_k = (unsigned*)(ws + L.pool_k); d.pool_a = (int*)(ws + L.pool_a);
   d.spk_words = (unsigned long long*)(ws + L.spk_words); d.stepcnt = (long long*)(ws + L.stepcnt);
   d.sq_next = (unsigned short*)(ws + L.sq_next); d.sq_hs = (unsigned short*)(ws + L.sq_hs); d.sq_key = (unsigned short*)(ws + L.sq_key);
+  d.sq_flag = (long long*)(ws + L.sq_flag);
   d.I_acc = (int*)(ws + L.I_acc); d.last_evb = (long long*)(ws + L.last_evb); d.blk_pop = L.nblk + (int)fan_slots(L.nblk);
   d.packed = (unsigned*)(ws + L.packed); d.a_q = (int*)(ws + L.a_q);
   d.amp = (d.continuous && d.kind != ADSEQ_RING) ? (float*)(ws + L.amp) : nullptr;

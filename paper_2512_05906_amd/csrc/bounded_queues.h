@@ -45,7 +45,9 @@
 constexpr int kCont = 8;   // contender slots per target and step before the overflow list is used
 
 // The kinds with one queue per synapse.
-__device__ __host__ constexpr bool per_synapse_kind(int kind) { return kind == ADSEQ_SYN_FIFO || kind == ADSEQ_SYN_LATEST; }
+__device__ __host__ constexpr bool per_synapse_kind(int kind) {
+  return kind == ADSEQ_SYN_FIFO || kind == ADSEQ_SYN_LATEST || kind == ADSEQ_SYN_BINS;
+}
 
 // Contender record, 128 bits: synapse index (40 bits), index of the admission flag on the tape
 // (40 bits, all ones = none), arrival step mod 2^16, Q8.24 amplitude.
@@ -485,6 +487,8 @@ __device__ __forceinline__ void push_rows(const Dev& d, long long n, const RowRe
 __device__ __forceinline__ void push_counts_flush(const Dev& d, int c_adm, long long s_adm, BlkCtr& bc);
 __device__ __forceinline__ void push_rows_latest(const Dev& d, long long n, const RowRef* rr, int nrows,
                                                  long long stride, int& c_adm, long long& s_adm);
+__device__ __forceinline__ void push_rows_bins(const Dev& d, long long n, const RowRef* rr, int nrows,
+                                               long long stride, int& c_adm, long long& s_adm);
 
 // Offers, for each of up to four row shares of step n, the entries r0 + first + threadIdx.x +
 // t * stride (t = 0, 1, ...) to their targets.  An event whose target is already full
@@ -674,6 +678,7 @@ __global__ __launch_bounds__(kBlock) void k_fanout_step(Dev d, long long n, int 
       }
       if (KIND == ADSEQ_SYN_FIFO) push_rows(d, n, rr, nrows, (long long)d.fsplit * kBlock, c_adm, s_adm);
       else if (KIND == ADSEQ_SYN_LATEST) push_rows_latest(d, n, rr, nrows, (long long)d.fsplit * kBlock, c_adm, s_adm);
+      else if (KIND == ADSEQ_SYN_BINS) push_rows_bins(d, n, rr, nrows, (long long)d.fsplit * kBlock, c_adm, s_adm);
       else offer_rows(d, n, rr, nrows, (long long)d.fsplit * kBlock);
     }
   }
@@ -708,6 +713,7 @@ __global__ __launch_bounds__(kBlock) void k_fanout_list(Dev d, long long n, cons
     if (threadIdx.x == 0) { c_off += r1 - r0; s_off += d.rowsum[i]; }
     if (KIND == ADSEQ_SYN_FIFO) push_rows(d, n, rr, 4, 4LL * kBlock, c_adm, s_adm);
     else if (KIND == ADSEQ_SYN_LATEST) push_rows_latest(d, n, rr, 4, 4LL * kBlock, c_adm, s_adm);
+    else if (KIND == ADSEQ_SYN_BINS) push_rows_bins(d, n, rr, 4, 4LL * kBlock, c_adm, s_adm);
     else offer_rows(d, n, rr, 4, 4LL * kBlock);
   }
   if (per_synapse_kind(KIND)) push_counts_flush(d, c_adm, s_adm, d.blk[d.nblk + blockIdx.x]);

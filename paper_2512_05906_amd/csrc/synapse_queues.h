@@ -26,7 +26,8 @@
 //
 // ADSEQ_SYN_LATEST ("SingleSpike(Drop)": one slot per synapse, a new spike always replaces the one
 // held) uses sq_next alone: the pop is the same launch without the rest of the state, the push
-// overwrites (push_rows_latest at the end of this file).
+// overwrites (push_rows_latest at the end of this file).  ADSEQ_SYN_BINS ("LossyRingDelay(n)") keeps
+// one such key array per time bin (push_rows_bins).
 
 constexpr int kSynqCapMax = 8;
 constexpr int kSynqBlocks = 2048;   // blocks of k_synq_pop (grid-stride), each with a private counter line
@@ -40,7 +41,7 @@ __device__ __forceinline__ unsigned synq_key(long long k) { return (unsigned)(k 
 constexpr int kSynqList = 2048;   // due queues a block notes before it works them off
 
 template <bool LATEST>
-__device__ __forceinline__ void synq_deliver(const Dev& d, long long q, int& popped, long long& sum) {
+__device__ __forceinline__ void synq_deliver(const Dev& d, long long q, long long off, int& popped, long long& sum) {
   const long long b = q / d.S, p = q - b * d.S;
   const int a = d.a_q[p];
   const unsigned pk = d.packed[p];
@@ -53,14 +54,15 @@ __device__ __forceinline__ void synq_deliver(const Dev& d, long long q, int& pop
     if (size) next = (unsigned)d.sq_key[(size_t)q * d.C + head];
     d.sq_hs[q] = (unsigned short)(size ? ((head << 8) | size) : 0u);
   }
-  d.sq_next[q] = (unsigned short)next;
+  d.sq_next[off + q] = (unsigned short)next;
   atomicAdd(&d.I_acc[(size_t)b * d.N + (pk >> d.dbits)], a);
   popped += 1; sum += a;
 }
 
-// LATEST: the queue is a single slot (ADSEQ_SYN_LATEST): nothing but the head key exists.
+// LATEST: the keys looked at are all there is (ADSEQ_SYN_LATEST: one slot per queue; ADSEQ_SYN_BINS:
+// the bin of this step, whose keys start `off` elements into sq_next).
 template <bool LATEST>
-__global__ __launch_bounds__(kBlock) void k_synq_pop(Dev d, long long n) {
+__global__ __launch_bounds__(kBlock) void k_synq_pop(Dev d, long long n, long long off) {
   __shared__ BlockCounts s_cnt;
   __shared__ long long s_list[kSynqList];
   __shared__ int s_n;
@@ -84,7 +86,7 @@ __global__ __launch_bounds__(kBlock) void k_synq_pop(Dev d, long long n) {
 #pragma unroll
     for (int h = 0; h < 4; ++h) {
       st[h] = make_uint4(0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu);
-      if (gi[h] < groups) st[h] = reinterpret_cast<const uint4*>(d.sq_next)[gi[h]];
+      if (gi[h] < groups) st[h] = reinterpret_cast<const uint4*>(d.sq_next + off)[gi[h]];
     }
 #pragma unroll
     for (int h = 0; h < 4; ++h) {
@@ -96,13 +98,13 @@ __global__ __launch_bounds__(kBlock) void k_synq_pop(Dev d, long long n) {
         const long long q = gi[h] * 8 + j;
         const int pos = atomicAdd(&s_n, 1);
         if (pos < kSynqList) s_list[pos] = q;
-        else synq_deliver<LATEST>(d, q, popped, sum);       // no room to note it: done at once
+        else synq_deliver<LATEST>(d, q, off, popped, sum);  // no room to note it: done at once
       }
     }
     __syncthreads();
     const int cnt = s_n < kSynqList ? s_n : kSynqList;
     if (cnt > kSynqList / 2 || base + 4 * stride >= groups) {   // list half full, or the last trip
-      for (int x = threadIdx.x; x < cnt; x += kBlock) synq_deliver<LATEST>(d, s_list[x], popped, sum);
+      for (int x = threadIdx.x; x < cnt; x += kBlock) synq_deliver<LATEST>(d, s_list[x], off, popped, sum);
       __syncthreads();
       if (threadIdx.x == 0) s_n = 0;
       __syncthreads();
@@ -194,6 +196,52 @@ __device__ __forceinline__ void push_rows_latest(const Dev& d, long long n, cons
       if (!replaced) { c_adm += 1; s_adm += a[j]; }
       if (rr[j].tbase >= 0) d.tape_adm[rr[j].tbase + (p[j] - rr[j].r0)] = 1;
       if (replaced && rr[j].obase >= 0) d.tape_adm[rr[j].obase + (p[j] - rr[j].r0)] = 0;
+    }
+  }
+}
+
+// ADSEQ_SYN_BINS: `capacity` time bins per queue, bin b of all queues contiguous (sq_next[b][.]),
+// so that the pop of a step streams one bin.  An event with arrival step k is written to bin
+// k mod capacity, over whatever is there; an undelivered event that is overwritten is lost, and
+// its admission flag -- whose index on the tape is kept beside the key (sq_flag, with a tape
+// only) -- is cleared.
+__device__ __forceinline__ void push_rows_bins(const Dev& d, long long n, const RowRef* rr, int nrows,
+                                               long long stride, int& c_adm, long long& s_adm) {
+  const long long qpad = (((long long)d.B * d.S + 7) >> 3) << 3;
+  long long longest = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    if (j < nrows && rr[j].r1 - rr[j].r0 - rr[j].first > longest) longest = rr[j].r1 - rr[j].r0 - rr[j].first;
+  for (long long o = 0; o < longest; o += stride) {
+    long long p[4], idx[4]; bool valid[4]; unsigned pk[4], old[4]; int a[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      p[j] = rr[j].r0 + rr[j].first + o + threadIdx.x;
+      valid[j] = j < nrows && p[j] < rr[j].r1;
+      pk[j] = 0; a[j] = 0;
+      if (valid[j]) { pk[j] = d.packed[p[j]]; a[j] = d.a_q[p[j]]; }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      old[j] = kSynqEmpty; idx[j] = 0;
+      if (valid[j]) {
+        const long long k = n + (long long)(pk[j] & d.dmask);
+        idx[j] = (k % d.C) * qpad + (long long)rr[j].b * d.S + p[j];
+        old[j] = d.sq_next[idx[j]];
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (!valid[j]) continue;
+      d.sq_next[idx[j]] = (unsigned short)synq_key(n + (long long)(pk[j] & d.dmask));
+      const bool replaced = old[j] != kSynqEmpty;
+      if (!replaced) { c_adm += 1; s_adm += a[j]; }
+      if (rr[j].tbase >= 0) {
+        const long long flag = rr[j].tbase + (p[j] - rr[j].r0);
+        if (replaced) d.tape_adm[d.sq_flag[idx[j]]] = 0;
+        d.sq_flag[idx[j]] = flag;
+        d.tape_adm[flag] = 1;
+      }
     }
   }
 }

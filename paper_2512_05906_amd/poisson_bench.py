@@ -37,7 +37,7 @@ def run_case(torch, adseq, synth, kind_name, cap, n_queues, delay, interval, T, 
     delay; else a Workload whose neurons all fire as Poisson sources with mean interval `interval`
     steps (the network's own delays and fan-out)."""
     import numpy as np
-    kind = {"ring": adseq.RING, "fifo": adseq.FIFO, "sorted": adseq.SORTED, "syn": adseq.SYN_FIFO, "latest": adseq.SYN_LATEST}[kind_name]
+    kind = {"ring": adseq.RING, "fifo": adseq.FIFO, "sorted": adseq.SORTED, "syn": adseq.SYN_FIFO, "latest": adseq.SYN_LATEST, "bins": adseq.SYN_BINS}[kind_name]
     wl = network if network is not None else synth.poisson_queues(n_queues, delay, n_steps=T)
     if network is not None:
         n_queues = wl.n_neurons
@@ -76,7 +76,7 @@ def run_case(torch, adseq, synth, kind_name, cap, n_queues, delay, interval, T, 
             "delivered_events_per_s": c["delivered"] / (ms * 1e-3),
             "offered": c["enqueued"], "dropped": c["dropped"],
             "drop_rate": c["dropped"] / max(1, c["enqueued"]),
-            "erlang_b": None if kind in (adseq.RING, adseq.SYN_LATEST) else erlang_b(cap, a)}
+            "erlang_b": None if kind in (adseq.RING, adseq.SYN_LATEST, adseq.SYN_BINS) else erlang_b(cap, a)}
 
 
 def main():
@@ -96,7 +96,7 @@ def main():
         sys.exit(3)
     # the last case is the control the paper's "DoNothing" queue gives (Section 4.3): the same
     # calls with no event ever inserted, i.e. the cost that does not depend on the queue's content
-    cases = [("ring", 0, 400), ("fifo", 4, 400), ("sorted", 4, 400), ("syn", 4, 400), ("latest", 1, 400), ("ring", 0, 0)]
+    cases = [("ring", 0, 400), ("fifo", 4, 400), ("sorted", 4, 400), ("syn", 4, 400), ("latest", 1, 400), ("bins", 4, 400), ("ring", 0, 0)]
     if args.sweep:
         cases = [(k, c, lam) for lam in (400, 160, 80, 40, 20) for k, c in
                  (("fifo", 1), ("fifo", 2), ("fifo", 4), ("fifo", 8), ("sorted", 4), ("syn", 4))]

@@ -49,7 +49,7 @@ def test_workspace_size_grows_with_the_queue():
 
 @pytest.mark.parametrize("bad", [
     dict(n_neurons=0), dict(batch=0), dict(d_max_steps=0), dict(d_max_steps=1024),
-    dict(kind=5), dict(kind=adseq.SYN_LATEST, capacity=2), dict(kind=adseq.SYN_FIFO, capacity=0), dict(kind=adseq.SYN_FIFO, capacity=9),
+    dict(kind=6), dict(kind=adseq.SYN_LATEST, capacity=2), dict(kind=adseq.SYN_BINS, capacity=9), dict(kind=adseq.SYN_FIFO, capacity=0), dict(kind=adseq.SYN_FIFO, capacity=9),
     dict(kind=adseq.FIFO, capacity=0), dict(kind=adseq.SORTED, capacity=40000),
     dict(dt_ms=0.0), dict(tau_m_ms=0.05), dict(ext_rate_hz=-1.0), dict(n_synapses=-1),
     dict(record_tape=1, max_steps=0), dict(surrogate=5), dict(tau_syn_ms=-1.0), dict(tau_syn_ms=0.05), dict(n_neurons=2**23, d_max_steps=1023),

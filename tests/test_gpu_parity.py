@@ -9,7 +9,7 @@ from tests import helpers as H
 
 pytestmark = pytest.mark.gpu
 
-KINDS = {"ring": oracle.RING, "fifo": oracle.FIFO, "sorted": oracle.SORTED, "syn": oracle.SYN_FIFO, "latest": oracle.SYN_LATEST}
+KINDS = {"ring": oracle.RING, "fifo": oracle.FIFO, "sorted": oracle.SORTED, "syn": oracle.SYN_FIFO, "latest": oracle.SYN_LATEST, "bins": oracle.SYN_BINS}
 
 
 def _compare_forward(wl, kind, cap, T=None, B=None, i_ext=None, check_sets=True, **kw):
@@ -56,7 +56,7 @@ def test_cfg0_forward_lossy(kind, cap):
     assert ref.counters()["dropped"] > 0
 
 
-@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 4), ("sorted", 4), ("syn", 1), ("latest", 1)])
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 4), ("sorted", 4), ("syn", 1), ("latest", 1), ("bins", 3)])
 @pytest.mark.parametrize("continuous", [False, True])
 def test_ragged_rows_batched(kind, cap, continuous):
     """Rows of 0..700 synapses (several 256-wide tiles plus a ragged tail, empty rows,
@@ -66,7 +66,7 @@ def test_ragged_rows_batched(kind, cap, continuous):
     ref, _ = _compare_forward(wl, KINDS[kind], cap, check_sets=(kind != "ring"))
     assert ref.spikes.sum() > 300
     if kind != "ring":
-        assert ref.counters()["dropped"] > (1000 if kind not in ("syn", "latest") else 100)
+        assert ref.counters()["dropped"] > (1000 if kind not in ("syn", "latest", "bins") else 100)
 
 
 @pytest.mark.parametrize("cap", [1, 2, 3, 8])
@@ -79,6 +79,16 @@ def test_per_synapse_queues_bursty(cap):
     assert ref.spikes.sum() > 2000
     if cap < 8:
         assert ref.counters()["dropped"] > 500
+
+
+@pytest.mark.parametrize("bins", [1, 2, 3, 8])
+def test_time_bins_bursty(bins):
+    """Time bins per synapse (Section 4.3 "LossyRingDelay(n)": bin = arrival step mod n, the newer
+    event takes the bin): bursting neurons; rasters, membrane values, counters and the lost /
+    delivered event sets (from the admission flags) against the oracle."""
+    wl = synth.ragged_network(200, 90, 25, seed=6, rate_hz=3000.0, t=200, b=3, w_mean=0.02, w_std=0.02)
+    ref, _ = _compare_forward(wl, oracle.SYN_BINS, bins, tape_spike_capacity=200 * 3 * 200)
+    assert ref.spikes.sum() > 2000 and ref.counters()["dropped"] > 500
 
 
 def test_latest_spike_slots_bursty():
@@ -115,7 +125,7 @@ def test_ring_rows_longer_than_a_staging_chunk():
     assert ref.spikes.sum() > 20 and ref.counters()["enqueued"] > 500000
 
 
-@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 5), ("sorted", 5), ("syn", 2), ("latest", 1)])
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 5), ("sorted", 5), ("syn", 2), ("latest", 1), ("bins", 5)])
 def test_largest_delay_range(kind, cap):
     """Delays up to the largest the interface allows (1,023 steps) over a run longer than that, so
     that the delay line, the spike history and the arrival keys wrap around; forward and both
@@ -133,7 +143,7 @@ def test_largest_delay_range(kind, cap):
     assert ref.spikes.sum() > 300 and int(ref.D.max()) == 1023 and int(ref.D.min()) == 1
 
 
-@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 2), ("sorted", 2), ("syn", 1), ("latest", 1)])
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 2), ("sorted", 2), ("syn", 1), ("latest", 1), ("bins", 2)])
 def test_degenerate_networks(kind, cap):
     """One neuron that talks to itself through three synapses (every block, word and part has a
     single valid lane), and a network without any synapse (empty rows only, nothing ever queued)."""
@@ -179,7 +189,7 @@ def test_no_spikes_and_zero_steps():
     assert out["counters"]["delivered"] == 0
 
 
-@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 2), ("sorted", 3), ("syn", 1), ("latest", 1)])
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 2), ("sorted", 3), ("syn", 1), ("latest", 1), ("bins", 2)])
 def test_open_loop_enqueue_deliver(kind, cap):
     """adseq_enqueue / adseq_deliver with externally generated spike lists (the
     shape of the paper's Poisson benchmark, Section 5.1)."""
@@ -310,7 +320,7 @@ def _compare_backward(wl, kind, cap, T, B, use_dU=True, surrogate=0, dU_scale=1e
     return ref
 
 
-@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 4), ("sorted", 6), ("syn", 1), ("latest", 1)])
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 4), ("sorted", 6), ("syn", 1), ("latest", 1), ("bins", 2)])
 @pytest.mark.parametrize("continuous", [False, True])
 def test_backward_small_ragged(kind, cap, continuous):
     wl = synth.ragged_network(120, 300, 30, seed=12, rate_hz=300.0, t=150, b=1, continuous=continuous,
@@ -321,7 +331,7 @@ def test_backward_small_ragged(kind, cap, continuous):
         assert ref.counters()["dropped"] > 0
 
 
-@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 4), ("sorted", 6), ("syn", 1), ("latest", 1)])
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 4), ("sorted", 6), ("syn", 1), ("latest", 1), ("bins", 2)])
 @pytest.mark.parametrize("continuous", [False, True])
 def test_backward_spike_time_mode(kind, cap, continuous):
     """No surrogate: gradients flow through the emission times of the spikes

@@ -10,12 +10,12 @@ from paper_2512_05906_amd import adseq, synth
 
 pytestmark = pytest.mark.gpu
 
-KINDS = {"ring": oracle.RING, "fifo": oracle.FIFO, "sorted": oracle.SORTED, "syn": oracle.SYN_FIFO, "latest": oracle.SYN_LATEST}
+KINDS = {"ring": oracle.RING, "fifo": oracle.FIFO, "sorted": oracle.SORTED, "syn": oracle.SYN_FIFO, "latest": oracle.SYN_LATEST, "bins": oracle.SYN_BINS}
 
 
 @pytest.mark.parametrize("kind,cap,interval", [("ring", 0, 400), ("fifo", 1, 400), ("fifo", 2, 80),
                                                ("fifo", 4, 40), ("sorted", 4, 40), ("fifo", 40, 40), ("syn", 4, 40),
-                                               ("syn", 1, 400), ("latest", 1, 40)])
+                                               ("syn", 1, 400), ("latest", 1, 40), ("bins", 4, 40)])
 def test_poisson_queues_open_loop(kind, cap, interval):
     N, T, delay = 1500, 3000, 80          # 1,500 queues: several blocks and a ragged tail
     wl = synth.poisson_queues(N, delay, n_steps=T)
@@ -47,6 +47,12 @@ def test_poisson_queues_open_loop(kind, cap, interval):
     sim.close()
     if kind == "ring" or cap >= 40:
         assert rc["dropped"] == 0
+    elif kind == "bins":
+        # an event is lost iff its source fires again a multiple of `cap` steps later, before it
+        # arrives: at one of the (delay - 1) // cap such steps
+        want_p = 1.0 - (1.0 - 1.0 / interval) ** ((delay - 1) // cap)
+        got = rc["dropped"] / rc["enqueued"]
+        assert abs(got - want_p) < 0.03, (got, want_p)
     elif kind == "latest":
         # an event is lost iff its source fires again in one of the delay - 1 steps before it arrives
         want_p = 1.0 - (1.0 - 1.0 / interval) ** (delay - 1)
