@@ -98,6 +98,9 @@ struct oracle_config {
   int32_t n_threads;           // trials are spread over this many threads
   float tau_syn_ms;            // > 0: first-order synapse, the jump goes into a synaptic current state
                                // with this time constant (Section 2.1 eq. 1); 0: straight into the membrane
+  float tau_rise_ms;           // > 0 (needs tau_syn_ms > tau_rise_ms and integer delays): double-exponential
+                               // synapse built from two such states (Section 3.2, closing remark): A with
+                               // tau_syn_ms, B with tau_rise_ms, both take every jump, isyn = A - B
 };
 
 }  // extern "C"
@@ -187,6 +190,7 @@ struct oracle_run {
   std::vector<double> a_d, f_d; // exact amplitude and decay factor (fp64 mode)
   double alpha_d = 0; float alpha_f = 0; uint64_t p_thresh = 0;
   double alpha_s_d = 0; float alpha_s_f = 0;   // leak of the synaptic current state (0: no such state)
+  double alpha_r_d = 0; float alpha_r_f = 0;   // leak of the second (fast) state of the double-exponential synapse
   double tau_rcv = 0;                          // time constant of the state that receives the jump
   // tape [T,B,N]
   std::vector<float> U; std::vector<double> U64; std::vector<uint8_t> S;
@@ -241,8 +245,9 @@ void run_trial(oracle_run& r, int b) {
   std::vector<int64_t> held(latest ? (size_t)c.n_synapses * nbins : 0, -1);   // admission flag of the held event
   std::vector<int32_t> held_n(latest ? (size_t)c.n_synapses * nbins : 0, 0);
   std::vector<int32_t> occ(per_syn ? (size_t)c.n_synapses : (latest ? (size_t)0 : (size_t)N), 0);
-  std::vector<float> V(N, 0.0f), J(N, 0.0f);       // membrane state, synaptic current state
-  std::vector<double> V64(N, 0.0), J64(N, 0.0);
+  std::vector<float> V(N, 0.0f), J(N, 0.0f), J2(N, 0.0f);   // membrane state, synaptic current state(s)
+  std::vector<double> V64(N, 0.0), J64(N, 0.0), J264(N, 0.0);
+  const bool dexp = c.tau_rise_ms > 0.0f;          // two states A = J, B = J2; isyn = A - B
   const bool syn_state = c.tau_syn_ms > 0.0f;
   std::vector<int32_t> acc(N);
   std::vector<double> acc64(N);
@@ -273,7 +278,11 @@ void run_trial(oracle_run& r, int b) {
       bool s;
       if (!exact) {
         float I = (float)acc[j] * 0x1p-24f;
-        if (syn_state) { I = std::fmaf(r.alpha_s_f, J[j], I); J[j] = I; }   // isyn = alpha_s isyn + jumps
+        if (dexp) {
+          const float jump = I;
+          J[j] = std::fmaf(r.alpha_s_f, J[j], jump); J2[j] = std::fmaf(r.alpha_r_f, J2[j], jump);
+          I = J[j] - J2[j];
+        } else if (syn_state) { I = std::fmaf(r.alpha_s_f, J[j], I); J[j] = I; }   // isyn = alpha_s isyn + jumps
         I = I + (xi ? c.ext_weight : 0.0f);
         if (c.i_ext) I = I + c.i_ext[base + j];
         const float u = std::fmaf(r.alpha_f, V[j], I);
@@ -282,7 +291,11 @@ void run_trial(oracle_run& r, int b) {
         r.U[base + j] = u; r.I[base + j] = I;
       } else {
         double I = acc64[j];
-        if (syn_state) { I = r.alpha_s_d * J64[j] + I; J64[j] = I; }
+        if (dexp) {
+          const double jump = I;
+          J64[j] = r.alpha_s_d * J64[j] + jump; J264[j] = r.alpha_r_d * J264[j] + jump;
+          I = J64[j] - J264[j];
+        } else if (syn_state) { I = r.alpha_s_d * J64[j] + I; J64[j] = I; }
         I += xi ? (double)c.ext_weight : 0.0;
         if (c.i_ext) I += (double)c.i_ext[base + j];
         const double u = r.alpha_d * V64[j] + I;
@@ -357,6 +370,16 @@ void backward_trial(const oracle_run& r, int b, const float* dL_dcount, const fl
   // dL/dU_j[n] without a synaptic current state; with one, dL/dJ_j[n] = gU_j[n] + alpha_s dL/dJ_j[n+1]
   std::vector<double> gR((size_t)(T + 1) * N, 0.0);
   const double alpha_s = exact ? r.alpha_s_d : (double)r.alpha_s_f;
+  // Double-exponential synapse: every event jumps into two states, A (tau_syn) and B (tau_rise),
+  // and isyn = A - B.  dL/dA[n] = gU[n] + alpha_s dL/dA[n+1], dL/dB[n] = -gU[n] + alpha_r dL/dB[n+1].
+  // An event delivered at k gathers gX = dL/dA[k] + dL/dB[k] for its amplitude, and, by the receive
+  // rule applied to each state with its own time constant, gY = dL/dA[k]/tau_A + dL/dB[k]/tau_B for
+  // its arrival time.
+  const bool dexp = c.tau_rise_ms > 0.0f;
+  const double alpha_r = exact ? r.alpha_r_d : (double)r.alpha_r_f;
+  const double tau_a = (double)c.tau_syn_ms, tau_b = (double)c.tau_rise_ms;
+  std::vector<double> gA(dexp ? N : 0, 0.0), gB(dexp ? N : 0, 0.0);
+  std::vector<double> gY(dexp ? (size_t)(T + 1) * N : 0, 0.0);   // (gX is kept in gR)
   int64_t sp = (int64_t)tr.spikes.size() - 1;  // spikes are stored in emission order
   std::vector<double> G(N);
   const bool spike_time = c.surrogate == 2;
@@ -375,6 +398,13 @@ void backward_trial(const oracle_run& r, int b, const float* dL_dcount, const fl
         const double g = gR[(size_t)k * N + c.col[p]];
         const double a = exact ? r.a_d[p] : (double)r.a_f[p];
         const double f = exact ? r.f_d[p] : (double)r.f_f[p];
+        if (dexp) {
+          const double gy = gY[(size_t)k * N + c.col[p]];
+          g_sum += a * (spike_time ? gy : g);   // what the emitting spike's time (value) is worth
+          gw[p] += f * g;
+          gd[p] += a * d_unit * gy;
+          continue;
+        }
         g_sum += a * g;
         gw[p] += f * g;                   // dI/dw = f (amplitude a = w f)
         gd[p] += (a / tau) * d_unit * g;  // receive rule: (jump / tau) * dt_post/dd, dt_post/dd = 1
@@ -391,7 +421,14 @@ void backward_trial(const oracle_run& r, int b, const float* dL_dcount, const fl
       const double dc = dL_dcount ? (double)dL_dcount[(size_t)b * N + i] : 0.0;
       const double g_now = (1.0 - s) * carry[i] + sg * (dc + s * G[i]) + direct;
       gU[(size_t)n * N + i] = g_now;
-      gR[(size_t)n * N + i] = g_now + alpha_s * gR[(size_t)(n + 1) * N + i];
+      if (dexp) {
+        gA[i] = g_now + alpha_s * gA[i];
+        gB[i] = -g_now + alpha_r * gB[i];
+        gR[(size_t)n * N + i] = gA[i] + gB[i];
+        gY[(size_t)n * N + i] = gA[i] / tau_a + gB[i] / tau_b;
+      } else {
+        gR[(size_t)n * N + i] = g_now + alpha_s * gR[(size_t)(n + 1) * N + i];
+      }
       // Spike-time mode: the spike's emission time depends on the membrane value v the step
       // started from, dt_spk/dv = -1 / vdot with vdot = (U - v) / dt from the first forward
       // difference (1 where that is 0), and every event of the spike hands (jump / tau) dt_post
@@ -405,7 +442,7 @@ void backward_trial(const oracle_run& r, int b, const float* dL_dcount, const fl
         }
         double vdot = (u - vprev) / (double)c.dt_ms;
         if (vdot == 0.0) vdot = 1.0;
-        e = -(1.0 / vdot) * (1.0 / tau) * G[i];
+        e = dexp ? -(1.0 / vdot) * G[i] : -(1.0 / vdot) * (1.0 / tau) * G[i];   // (gY holds the 1/tau factors)
       }
       carry[i] = alpha * g_now + e;
     }
@@ -430,6 +467,10 @@ oracle_run* oracle_forward(const oracle_config* cfg) {
     r->status = -1; return r;
   }
   if (c.tau_syn_ms < 0.0f || (c.tau_syn_ms > 0.0f && c.dt_ms > c.tau_syn_ms)) { r->status = -1; return r; }
+  if (c.tau_rise_ms < 0.0f ||
+      (c.tau_rise_ms > 0.0f && (c.dt_ms > c.tau_rise_ms || !(c.tau_syn_ms > c.tau_rise_ms) || c.delay_ms))) {
+    r->status = -1; return r;   // the two states would decay a sub-step arrival differently: integer delays only
+  }
   r->tau_rcv = c.tau_syn_ms > 0.0f ? (double)c.tau_syn_ms : (double)c.tau_m_ms;
   r->status = prepare_synapses(*r);
   if (r->status != 0) return r;
@@ -438,6 +479,10 @@ oracle_run* oracle_forward(const oracle_config* cfg) {
   if (c.tau_syn_ms > 0.0f) {
     r->alpha_s_d = std::exp(-(double)c.dt_ms / (double)c.tau_syn_ms);
     r->alpha_s_f = (float)r->alpha_s_d;
+  }
+  if (c.tau_rise_ms > 0.0f) {
+    r->alpha_r_d = std::exp(-(double)c.dt_ms / (double)c.tau_rise_ms);
+    r->alpha_r_f = (float)r->alpha_r_d;
   }
   {
     // Bernoulli probability per step rate*dt, as a 32-bit threshold

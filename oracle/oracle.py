@@ -40,7 +40,7 @@ class _Cfg(C.Structure):
         ("delay_steps", C.c_void_p), ("delay_ms", C.c_void_p),
         ("i_ext", C.c_void_p), ("forced_spikes", C.c_void_p),
         ("log_events", C.c_int32), ("keep_currents", C.c_int32), ("n_threads", C.c_int32),
-        ("tau_syn_ms", C.c_float),
+        ("tau_syn_ms", C.c_float), ("tau_rise_ms", C.c_float),
     ]
 
 
@@ -125,7 +125,8 @@ class Run:
                    delay_ms=_ptr(k["delay_ms"]), i_ext=_ptr(k["i_ext"]),
                    forced_spikes=_ptr(k["forced"]), log_events=int(log_events),
                    keep_currents=int(keep_currents), n_threads=n_threads,
-                   tau_syn_ms=float(getattr(wl, "tau_syn_ms", 0.0)))
+                   tau_syn_ms=float(getattr(wl, "tau_syn_ms", 0.0)),
+                   tau_rise_ms=float(getattr(wl, "tau_rise_ms", 0.0)))
         self._exact = bool(exact_f64)
         self._keep_currents = keep_currents
         self._h = L.oracle_forward(C.byref(cfg))

@@ -24,7 +24,7 @@ import numpy as np
 
 
 def jvp(U, S, events, col, src, a, f, alpha, theta, tau, d_unit, w_t, d_t, surrogate=True,
-        spike_time=False, dt=None, v_reset=0.0, alpha_s=0.0):
+        spike_time=False, dt=None, v_reset=0.0, alpha_s=0.0, alpha_r=0.0, tau_r=None):
     """Tangents of (U [T,N], spike counts [N]) for one trial.
 
     U, S        recorded membrane values / spikes [T, N]
@@ -35,6 +35,9 @@ def jvp(U, S, events, col, src, a, f, alpha, theta, tau, d_unit, w_t, d_t, surro
     d_unit      1 for delays in ms, dt for delays in steps
     tau         time constant of the state that receives the jump (synaptic current state if
                 alpha_s > 0, eq. 1: isyn = alpha_s isyn + jumps, U = alpha V + isyn; else the membrane)
+    alpha_r, tau_r   > 0: double-exponential synapse (Section 3.2, closing remark): a second state
+                with leak alpha_r and time constant tau_r takes every jump too, isyn = A - B; the
+                receive rule applies to each state with its own time constant
     """
     T, N = U.shape
     by_arrival = [[] for _ in range(T)]
@@ -50,19 +53,26 @@ def jvp(U, S, events, col, src, a, f, alpha, theta, tau, d_unit, w_t, d_t, surro
     tspk_t = np.zeros((T, N))      # tangent of the emission time (ms) of the spike at (n, i)
     V_t = np.zeros(N)
     V = np.zeros(N)                # membrane value each step starts from
-    J_t = np.zeros(N)              # tangent of the synaptic current state
+    J_t = np.zeros(N)              # tangent of the synaptic current state (A)
+    B_t = np.zeros(N)              # tangent of the second state of the double-exponential synapse
     for n in range(T):
-        I_t = np.zeros(N)
+        I_w = np.zeros(N)          # tangent of the delivered amplitude (weight, emitting spike's value)
+        I_k = np.zeros(N)          # amplitude x tangent of the delivery time (delay, emission time)
         for p, n_emit in by_arrival[n]:
-            # amplitude tangent (weight and delay) + amplitude * tangent of the emitting spike
-            I_t[col[p]] += f[p] * w_t[p] + (a[p] / tau) * d_unit * d_t[p] + a[p] * s_t[n_emit, src[p]]
+            I_w[col[p]] += f[p] * w_t[p] + a[p] * s_t[n_emit, src[p]]
+            I_k[col[p]] += a[p] * d_unit * d_t[p]
             if spike_time:
-                I_t[col[p]] += (a[p] / tau) * tspk_t[n_emit, src[p]]
+                I_k[col[p]] += a[p] * tspk_t[n_emit, src[p]]
+        I_t = I_w + I_k / tau      # receive rule: (jump / tau) x tangent of the delivery time
         if spike_time:
             vdot = (U[n].astype(np.float64) - V) / dt
             vdot = np.where(vdot == 0.0, 1.0, vdot)
             tspk_t[n] = np.where(S[n] != 0, -V_t / vdot, 0.0)
-        if alpha_s > 0.0:
+        if alpha_r > 0.0:
+            J_t = alpha_s * J_t + I_w + I_k / tau
+            B_t = alpha_r * B_t + I_w + I_k / tau_r
+            I_t = J_t - B_t
+        elif alpha_s > 0.0:
             J_t = alpha_s * J_t + I_t
             I_t = J_t
         U_t[n] = alpha * V_t + I_t

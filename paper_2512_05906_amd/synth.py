@@ -41,6 +41,7 @@ class Workload:
     ext_weight: float = 0.5
     seed: int = 0
     tau_syn_ms: float = 0.0   # > 0: first-order synapse with this time constant; 0: delta synapse
+    tau_rise_ms: float = 0.0  # > 0 (with tau_syn_ms > tau_rise_ms, integer delays): double-exponential synapse
     # CSR (host, numpy)
     row_ptr: Optional[np.ndarray] = None      # int64 [N+1]
     col: Optional[np.ndarray] = None          # int32 [S]

@@ -308,3 +308,108 @@ def test_first_order_synapse_reverse_mode_is_transpose_of_forward_mode(mode):
     rhs = float(gw @ w_t + gd @ d_t)
     assert abs(lhs) > 1e-3
     np.testing.assert_allclose(lhs, rhs, rtol=1e-9)
+
+
+def test_double_exponential_synapse_closed_form():
+    """One synapse 0 -> 1 through a double-exponential synapse built from two first-order states
+    (Section 3.2, closing remark): A (tau_syn) and B (tau_rise) both take the jump a at the arrival
+    step k, isyn = A - B, U = alpha V + isyn.  For m >= k, with L = m - k and
+    K(x) = (alpha^(L+1) - x^(L+1)) / (alpha - x):
+      U_1[m] = a (K(alpha_A) - K(alpha_B)),  dU_1[m]/dw = U_1[m] / w,
+      dU_1[m]/dd = a dt (K(alpha_A) / tau_A - K(alpha_B) / tau_B)   (receive rule, eq. 17, per state).
+    There is no jump in the current itself: isyn[k] = 0."""
+    T, n0, m, D = 90, 5, 60, 7
+    w, tau_a, tau_b, tau_m, dt = 0.3, 3.0, 0.8, 20.0, float(np.float32(0.1))
+    wl = synth.Workload("pair", 2, 1, T, 1, 20, ext_rate_hz=0.0, tau_syn_ms=tau_a, tau_rise_ms=tau_b,
+                        row_ptr=np.array([0, 1, 1], np.int64), col=np.array([1], np.int32),
+                        weight=np.array([w], np.float32), delay_steps=np.array([D], np.uint8))
+    forced = np.zeros((T, 1, 2), np.uint8)
+    forced[n0, 0, 0] = 1
+    dL_dU = np.zeros((T, 1, 2), np.float32)
+    dL_dU[m, 0, 1] = 1.0
+    k = n0 + D
+    al = math.exp(-dt / tau_m)
+    ala, alb = math.exp(-dt / float(np.float32(tau_a))), math.exp(-dt / float(np.float32(tau_b)))
+    L = m - k
+    Ka = (al ** (L + 1) - ala ** (L + 1)) / (al - ala)
+    Kb = (al ** (L + 1) - alb ** (L + 1)) / (al - alb)
+    a = float(np.float32(w))
+    r = oracle.Run(wl, oracle.RING, forced_spikes=forced, exact_f64=True, surrogate=1)
+    np.testing.assert_allclose(r.U64[m, 0, 1], a * (Ka - Kb), rtol=1e-11)
+    assert r.U64[k, 0, 1] == 0.0 and r.U64[k + 1, 0, 1] > 0.0       # the current rises from zero
+    gw, gd = r.backward(None, dL_dU)
+    np.testing.assert_allclose(gw[0], Ka - Kb, rtol=1e-11)
+    np.testing.assert_allclose(gd[0], a * dt * (Ka / float(np.float32(tau_a)) - Kb / float(np.float32(tau_b))), rtol=1e-11)
+    r32 = oracle.Run(wl, oracle.RING, forced_spikes=forced, surrogate=1)
+    np.testing.assert_allclose(r32.U[m, 0, 1], a * (Ka - Kb), rtol=2e-5)
+    # continuous delays are refused: the two states would decay a sub-step arrival differently
+    wl2 = copy.copy(wl)
+    wl2.delay_steps, wl2.delay_ms = None, np.array([0.65], np.float32)
+    with pytest.raises(Exception):
+        oracle.Run(wl2, oracle.RING, forced_spikes=forced)
+
+
+def test_double_exponential_weight_gradient_finite_differences():
+    """Central differences in the weights on a frozen raster (fp64, no quantisation): the part of the
+    double-exponential reverse sweep that a finite difference can see (delays are whole steps here)."""
+    wl = synth.ragged_network(10, 6, 12, seed=19, rate_hz=1500.0, t=150, w_mean=0.4, w_std=0.2)
+    wl.tau_syn_ms, wl.tau_rise_ms = 2.5, 0.7
+    forced = oracle.Run(wl, oracle.FIFO, 3).spikes
+    assert forced.sum() > 40
+    c = synth.random_cotangent(wl)
+
+    def loss(w):
+        r = oracle.Run(w, oracle.FIFO, 3, forced_spikes=forced, exact_f64=True, surrogate=1)
+        return float((c.astype(np.float64) * r.U64).sum()), r
+
+    _, r0 = loss(wl)
+    gw, _ = r0.backward(None, c)
+    rng = np.random.default_rng(2)
+    for p in rng.permutation(wl.n_synapses)[:20]:
+        h = 1e-3
+        wp, wm = copy.copy(wl), copy.copy(wl)
+        wp.weight, wm.weight = wl.weight.copy(), wl.weight.copy()
+        wp.weight[p] += np.float32(h)
+        wm.weight[p] -= np.float32(h)
+        hh = (float(wp.weight[p]) - float(wm.weight[p])) / 2
+        fd = (loss(wp)[0] - loss(wm)[0]) / (2 * hh)
+        np.testing.assert_allclose(gw[p], fd, rtol=1e-6, atol=1e-9)
+    assert np.abs(gw).max() > 0
+
+
+@pytest.mark.parametrize("mode", [0, 2])
+def test_double_exponential_reverse_mode_is_transpose_of_forward_mode(mode):
+    """<u, J v> == <J^T u, v> with the double-exponential synapse (weights and delays, surrogate and
+    spike-time modes, lossy queue)."""
+    B = 2
+    wl = synth.ragged_network(12, 7, 10, seed=37, rate_hz=1500.0, t=120, b=B, w_mean=0.5, w_std=0.3)
+    wl.tau_syn_ms, wl.tau_rise_ms = 2.0, 0.6
+    r = oracle.Run(wl, oracle.FIFO, 4, log_events=True, surrogate=mode)
+    assert r.spikes.sum() > 60 and r.counters()["dropped"] > 0
+    u_U = synth.random_cotangent(wl)
+    u_c = synth.spike_count_targets(wl) - 2.5 if mode == 0 else None
+    gw, gd = r.backward(u_c, u_U)
+    rng = np.random.default_rng(9)
+    w_t = rng.standard_normal(wl.n_synapses)
+    d_t = rng.standard_normal(wl.n_synapses)
+    dl = r.event_log("delivered")
+    U, S = r.U, r.spikes
+    dt = float(np.float32(wl.dt_ms))
+    alpha = float(np.float32(math.exp(-dt / float(np.float32(wl.tau_m_ms)))))
+    alpha_s = float(np.float32(math.exp(-dt / float(np.float32(wl.tau_syn_ms)))))
+    alpha_r = float(np.float32(math.exp(-dt / float(np.float32(wl.tau_rise_ms)))))
+    lhs = 0.0
+    for b in range(B):
+        sel = dl["b"] == b
+        ev = list(zip(dl["syn"][sel], dl["n_emit"][sel], dl["k"][sel]))
+        U_t, c_t = tangent.jvp(U[:, b], S[:, b], ev, wl.col, _src(wl), r.a_f.astype(np.float64),
+                               r.f_f.astype(np.float64), alpha, float(wl.v_thresh),
+                               float(np.float32(wl.tau_syn_ms)), dt, w_t, d_t, surrogate=(mode == 0),
+                               spike_time=(mode == 2), dt=dt, v_reset=float(wl.v_reset), alpha_s=alpha_s,
+                               alpha_r=alpha_r, tau_r=float(np.float32(wl.tau_rise_ms)))
+        lhs += float((u_U[:, b].astype(np.float64) * U_t).sum())
+        if mode == 0:
+            lhs += float((u_c[b].astype(np.float64) * c_t).sum())
+    rhs = float(gw @ w_t + gd @ d_t)
+    assert abs(lhs) > 1e-3
+    np.testing.assert_allclose(lhs, rhs, rtol=1e-9)
