@@ -26,7 +26,8 @@
  *              result does not depend on the order of arrival);
  *   2. drive   I_j = Iq_j * 2^-24 + (xi_j ? ext_weight : 0) (+ i_ext_j)   [with tau_syn_ms > 0:
  *              J_j = fma(alpha_s, J_j, Iq_j * 2^-24), alpha_s = (float)exp(-dt/tau_syn), takes the
- *              place of Iq_j * 2^-24], xi_j a
+ *              place of Iq_j * 2^-24; with tau_rise_ms > 0 as well, J_j - B_j does,
+ *              B_j = fma(alpha_r, B_j, Iq_j * 2^-24), alpha_r = (float)exp(-dt/tau_rise)], xi_j a
  *              Bernoulli(ext_rate_hz * dt) draw from a counter-based hash of
  *              (seed, b * N + j, n);
  *   3. LIF     U_j = fma(alpha, V_j, I_j), alpha = (float)exp(-dt/tau_m);
@@ -127,7 +128,12 @@ typedef struct {
                                                constant (dt_ms <= tau_syn_ms), J <- alpha_s J + Iq,
                                                and J is what the membrane integrates; 0: the events
                                                jump straight into the membrane state               */
-  float reserved0;                          /* 0                                              */
+  float tau_rise_ms;                        /* > 0: double-exponential synapse (Section 3.2, closing
+                                               remark): a second, faster state B with this time
+                                               constant takes every jump too, B <- alpha_r B + Iq,
+                                               and the membrane integrates J - B; needs
+                                               dt_ms <= tau_rise_ms < tau_syn_ms and whole-step
+                                               delays (delay_steps); 0: none                       */
   uint64_t seed;                            /* of the drive's counter-based generator         */
   int64_t n_synapses;                       /* S = row_ptr[N], below 2^40                     */
   const int64_t *row_ptr;     /* [N+1] CSR by source neuron                                   */
@@ -210,7 +216,10 @@ int adseq_run(adseq_t *h, int64_t step0, int64_t n_steps, void *stream);
  *   grad_w[p] += f_p * gU[col_p][n + D_p],   grad_d[p] += (a_p / tau_m) * unit * gU[col_p][n + D_p]
  * (f_p = a_p / weight_p; unit = 1 per ms for delay_ms, dt per step for delay_steps; with a synaptic
  * current state, gJ_j[n] = gU_j[n] + alpha_s gJ_j[n+1] takes the place of gU in G_i, grad_w and
- * grad_d, and tau_syn that of tau_m in grad_d and E), summed over
+ * grad_d, and tau_syn that of tau_m in grad_d and E; with the double-exponential synapse,
+ * gB_j[n] = -gU_j[n] + alpha_r gB_j[n+1] beside it, gJ + gB takes the place of gU in grad_w and in
+ * G_i of the surrogate modes, and gJ / tau_syn + gB / tau_rise that of gU / tau_m in grad_d and in
+ * the spike-time mode's E), summed over
  * trials.  dL_dcount: fp32 [B*N] or NULL; dL_dU: fp32 [T][B*N] or NULL; grad_w, grad_d: fp32 [S],
  * overwritten.  Synchronises the stream once at the start to read the device error word. */
 int adseq_backward(adseq_t *h, const float *dL_dcount, const float *dL_dU, float *grad_w,

@@ -40,7 +40,7 @@ class Config(C.Structure):
         ("record_tape", C.c_int32), ("max_steps", C.c_int32),
         ("dt_ms", C.c_float), ("tau_m_ms", C.c_float), ("v_thresh", C.c_float), ("v_reset", C.c_float),
         ("ext_rate_hz", C.c_float), ("ext_weight", C.c_float),
-        ("tau_syn_ms", C.c_float), ("reserved0", C.c_float),
+        ("tau_syn_ms", C.c_float), ("tau_rise_ms", C.c_float),
         ("seed", C.c_uint64), ("n_synapses", C.c_int64),
         ("row_ptr", C.c_void_p), ("col", C.c_void_p), ("weight", C.c_void_p),
         ("delay_steps", C.c_void_p), ("delay_ms", C.c_void_p),
@@ -127,7 +127,8 @@ class Adseq:
                      kind=kind, surrogate=surrogate, record_tape=int(record_tape),
                      max_steps=self.max_steps, dt_ms=wl.dt_ms, tau_m_ms=wl.tau_m_ms,
                      v_thresh=wl.v_thresh, v_reset=wl.v_reset, ext_rate_hz=wl.ext_rate_hz,
-                     ext_weight=wl.ext_weight, tau_syn_ms=float(getattr(wl, "tau_syn_ms", 0.0)), seed=wl.seed,
+                     ext_weight=wl.ext_weight, tau_syn_ms=float(getattr(wl, "tau_syn_ms", 0.0)),
+                     tau_rise_ms=float(getattr(wl, "tau_rise_ms", 0.0)), seed=wl.seed,
                      n_synapses=self.S,
                      row_ptr=_dptr(self.row_ptr), col=_dptr(self.col), weight=_dptr(self.weight),
                      delay_steps=_dptr(self.delay_steps), delay_ms=_dptr(self.delay_ms),

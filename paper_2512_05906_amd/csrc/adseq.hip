@@ -72,8 +72,11 @@ struct Dev {
   float alpha, theta, v_reset, ext_w, dt;
   float tau;            // time constant of the state that takes the jump: tau_syn if there is a synaptic state, else tau_m
   float alpha_s;        // exp(-dt / tau_syn), 0 = no synaptic current state
-  float* J;             // [BN] synaptic current state (alpha_s > 0)
-  float* bwd_carryJ;    // [BN] its adjoint dL/dJ[n+1]
+  float alpha_r;        // exp(-dt / tau_rise), 0 = no second (fast) state: double-exponential synapse if > 0
+  float alpha_diff;     // alpha_s - alpha_r
+  float inv_tau_b, inv_tau_diff;   // 1 / tau_rise, 1 / tau_rise - 1 / tau_syn
+  float* J;             // [BN] synaptic current state (alpha_s > 0); [2][BN] with the fast state behind it (alpha_r > 0)
+  float* bwd_carryJ;    // [BN] its adjoint dL/dJ[n+1] ([2][BN] if alpha_r > 0: the slow state's adjoint, the sum of both states')
   unsigned long long p_thresh, seed;
   long long S, spike_cap, event_cap;
   const long long* row_ptr;
@@ -335,9 +338,11 @@ __global__ __launch_bounds__(kBlock) void k_bwd_rows(Dev d, long long n, long lo
   const int b = d.B == 1 ? 0 : g / d.N;
   const int m = (int)(n % d.R);
   const long long stride = (long long)d.fsplit * kBlock;
+  const bool dexp = d.alpha_r > 0.0f;              // double-exponential synapse: two adjoint delay lines,
+  const size_t second = (size_t)d.R * d.BN;        // Y behind X (see bwd_receiver)
   float G = 0.0f;
   for (long long p0 = row.r0 + (long long)c * kBlock + threadIdx.x; p0 < row.r1; p0 += 4 * stride) {
-    long long p[4]; bool use[4]; unsigned pk[4]; unsigned char adm[4]; float a[4], f[4], gv[4];
+    long long p[4]; bool use[4]; unsigned pk[4]; unsigned char adm[4]; float a[4], f[4], gv[4], gy[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       p[j] = p0 + j * stride;
@@ -354,18 +359,26 @@ __global__ __launch_bounds__(kBlock) void k_bwd_rows(Dev d, long long n, long lo
     for (int j = 0; j < 4; ++j) {
       const int D = (int)(pk[j] & d.dmask);
       use[j] = use[j] && adm[j] != 0 && n + D < T;   // admitted, and delivered inside the run
-      gv[j] = 0.0f;
+      gv[j] = 0.0f; gy[j] = 0.0f;
       if (use[j]) {
         int slot = m + D; if (slot >= d.R) slot -= d.R;
-        gv[j] = d.bwd_ring[(size_t)slot * d.BN + (size_t)b * d.N + (pk[j] >> d.dbits)];
+        const size_t cell = (size_t)slot * d.BN + (size_t)b * d.N + (pk[j] >> d.dbits);
+        gv[j] = d.bwd_ring[cell];
+        if (dexp) gy[j] = d.bwd_ring[second + cell];
       }
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j)
       if (use[j]) {
-        G += a[j] * gv[j];
-        unsafeAtomicAdd(&grad_w[p[j]], f[j] * gv[j]);
-        unsafeAtomicAdd(&grad_d[p[j]], a[j] * dscale * gv[j]);
+        if (dexp) {   // X for the weight, Y (with the 1 / tau factors in it) for the delay
+          G += a[j] * queue_term_of(d, gv[j], gy[j]);
+          unsafeAtomicAdd(&grad_w[p[j]], f[j] * gv[j]);
+          unsafeAtomicAdd(&grad_d[p[j]], a[j] * dscale * gy[j]);
+        } else {
+          G += a[j] * gv[j];
+          unsafeAtomicAdd(&grad_w[p[j]], f[j] * gv[j]);
+          unsafeAtomicAdd(&grad_d[p[j]], a[j] * dscale * gv[j]);
+        }
       }
   }
   G = wave_sum_f(G);
@@ -383,7 +396,7 @@ __global__ __launch_bounds__(kBlock) void k_bwd_neurons(Dev d, long long n,
                                                         const float* __restrict__ dL_dcount,
                                                         const float* __restrict__ dL_dU) {
   pin_args(d.tapeU, d.bwd_carry, d.bwd_carryJ, d.bwd_G, d.bwd_ring, d.BN, d.R, d.fsplit, d.surrogate, d.alpha, d.alpha_s,
-           d.theta, d.v_reset, d.dt, d.tau, n, dL_dcount, dL_dU);
+           d.alpha_r, d.alpha_diff, d.inv_tau_b, d.inv_tau_diff, d.theta, d.v_reset, d.dt, d.tau, n, dL_dcount, dL_dU);
   const int g = blockIdx.x * kBlock + threadIdx.x;
   if (g >= d.BN) return;
   const float U = d.tapeU[(size_t)n * d.BN + g];
@@ -395,7 +408,9 @@ __global__ __launch_bounds__(kBlock) void k_bwd_neurons(Dev d, long long n,
     for (int c = 0; c < d.fsplit; ++c) G += d.bwd_G[(size_t)c * d.BN + g];   // the shares of the spike's row
   d.bwd_carry[g] = bwd_update(d, n, U, Uprev, s, d.bwd_carry[g], dL_dcount ? dL_dcount[g] : 0.0f,
                               G, dL_dU ? dL_dU[(size_t)n * d.BN + g] : 0.0f, &gu);
-  d.bwd_ring[(size_t)(n % d.R) * d.BN + g] = bwd_receiver(d, g, gu);
+  float y = 0.0f;
+  d.bwd_ring[(size_t)(n % d.R) * d.BN + g] = bwd_receiver(d, g, gu, &y);
+  if (d.alpha_r > 0.0f) d.bwd_ring[(size_t)d.R * d.BN + (size_t)(n % d.R) * d.BN + g] = y;
 }
 
 }  // namespace
@@ -471,6 +486,8 @@ bool host_validate(const adseq_config* c) {
       c->surrogate != ADSEQ_GRAD_SPIKE_TIME) return false;
   if (!(c->dt_ms > 0.0f) || !(c->tau_m_ms > 0.0f) || c->dt_ms > c->tau_m_ms) return false;
   if (!(c->tau_syn_ms >= 0.0f) || (c->tau_syn_ms > 0.0f && c->dt_ms > c->tau_syn_ms)) return false;
+  if (!(c->tau_rise_ms >= 0.0f) || (c->tau_rise_ms > 0.0f && (c->dt_ms > c->tau_rise_ms || !(c->tau_syn_ms > c->tau_rise_ms) || c->delay_ms)))
+    return false;
   if (!(c->ext_rate_hz >= 0.0f)) return false;
   if (c->n_synapses < 0 || c->n_synapses >= (1LL << 40)) return false;   // synapse indices are packed into 40 bits
   if (c->record_tape && c->max_steps < 1) return false;
@@ -546,7 +563,8 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->blk = take(bounded ? ((size_t)L->nblk + fan_slots(L->nblk) + (synq ? kSynqBlocks : 0)) * sizeof(BlkCtr)
                         : kMaxBinBlocks * sizeof(BlkCtr));
   L->V = take(BN * 4);
-  L->J = take(c->tau_syn_ms > 0.0f ? BN * 4 : 0);
+  const size_t nstates = c->tau_rise_ms > 0.0f ? 2 : 1;   // double-exponential synapse: every adjoint twice
+  L->J = take(c->tau_syn_ms > 0.0f ? nstates * BN * 4 : 0);
   L->win = take(bounded ? 0 : 2 * (size_t)L->W * BN * 4);
   L->spike_bits = take(bounded ? 0 : (size_t)L->R * L->words * 8);
   const bool fifo = c->kind == ADSEQ_FIFO;
@@ -601,13 +619,13 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->tape_row = take(bounded ? (size_t)L->spike_cap * sizeof(RowSpan) : 0);
   L->tape_adm = take((size_t)L->event_cap);
   const bool tape = c->record_tape != 0;
-  L->bwd_ring = take(tape && bounded ? (size_t)L->R * BN * 4 : 0);
+  L->bwd_ring = take(tape && bounded ? nstates * (size_t)L->R * BN * 4 : 0);
   L->bwd_carry = take(tape ? BN * 4 : 0);
-  L->bwd_carryJ = take(tape && c->tau_syn_ms > 0.0f ? BN * 4 : 0);
+  L->bwd_carryJ = take(tape && c->tau_syn_ms > 0.0f ? nstates * BN * 4 : 0);
   L->bwd_G = take(tape && bounded ? (size_t)kFanSplitMax * BN * 4 : 0);
-  L->gwin = take(tape && !bounded ? 2 * (size_t)L->W * BN * 4 : 0);
+  L->gwin = take(tape && !bounded ? nstates * 2 * (size_t)L->W * BN * 4 : 0);
   L->Gacc = take(tape && !bounded ? (size_t)L->R * BN * 4 : 0);
-  L->gsum = take(tape && !bounded ? S * 4 : 0);
+  L->gsum = take(tape && !bounded ? nstates * S * 4 : 0);
   L->total = o;
   return true;
 }
@@ -647,7 +665,7 @@ void launch_reset(adseq* h, hipStream_t st) {
   const size_t BN = (size_t)d.BN;
   fill_u32(st, d.ctr, 0u, sizeof(Counters) / 4);
   fill_u32(st, d.V, 0u, BN);
-  if (d.alpha_s > 0.0f) fill_u32(st, d.J, 0u, BN);
+  if (d.alpha_s > 0.0f) fill_u32(st, d.J, 0u, (d.alpha_r > 0.0f ? 2 : 1) * BN);
   if (d.kind == ADSEQ_RING) {
     fill_u32(st, d.win, 0u, 2 * (size_t)d.W * BN);
     fill_u32(st, d.spike_bits, 0u, (size_t)d.R * d.words * 2);
@@ -804,11 +822,13 @@ int step_impl(adseq* h, long long step, const float* i_ext, unsigned char* spike
     ring_open_window(h, st, step);
     open_group(h, st);
     const dim3 grid((unsigned)d.nblk), block(kBlock);
-    const bool syn = d.alpha_s > 0.0f;
-    if (record && !syn) hipLaunchKernelGGL((k_step_win<true, false>), grid, block, 0, st, d, step, i_ext, spikes_out);
-    else if (record) hipLaunchKernelGGL((k_step_win<true, true>), grid, block, 0, st, d, step, i_ext, spikes_out);
-    else if (!syn) hipLaunchKernelGGL((k_step_win<false, false>), grid, block, 0, st, d, step, i_ext, spikes_out);
-    else hipLaunchKernelGGL((k_step_win<false, true>), grid, block, 0, st, d, step, i_ext, spikes_out);
+    const int syn = d.alpha_r > 0.0f ? 2 : (d.alpha_s > 0.0f ? 1 : 0);   // synaptic current states
+    if (record && syn == 0) hipLaunchKernelGGL((k_step_win<true, 0>), grid, block, 0, st, d, step, i_ext, spikes_out);
+    else if (record && syn == 1) hipLaunchKernelGGL((k_step_win<true, 1>), grid, block, 0, st, d, step, i_ext, spikes_out);
+    else if (record) hipLaunchKernelGGL((k_step_win<true, 2>), grid, block, 0, st, d, step, i_ext, spikes_out);
+    else if (syn == 0) hipLaunchKernelGGL((k_step_win<false, 0>), grid, block, 0, st, d, step, i_ext, spikes_out);
+    else if (syn == 1) hipLaunchKernelGGL((k_step_win<false, 1>), grid, block, 0, st, d, step, i_ext, spikes_out);
+    else hipLaunchKernelGGL((k_step_win<false, 2>), grid, block, 0, st, d, step, i_ext, spikes_out);
     h->grp_count += 1;
   } else {
     mark(h, st, -1);
@@ -838,22 +858,25 @@ void ring_backward_launch(adseq* h, hipStream_t st, long long T, float dscale, c
                           const float* dL_dU, float* grad_w, float* grad_d) {
   const Dev& d = h->dev;
   const dim3 block(kBlock), gn((unsigned)d.nblk);
+  const size_t nst = d.alpha_r > 0.0f ? 2 : 1;
   fill_u32(st, d.bwd_carry, 0u, (size_t)d.BN);
-  if (d.alpha_s > 0.0f) fill_u32(st, d.bwd_carryJ, 0u, (size_t)d.BN);
-  fill_u32(st, d.gsum, 0u, (size_t)d.S);
-  fill_u32(st, d.gwin, 0u, 2 * (size_t)d.W * d.BN);
+  if (d.alpha_s > 0.0f) fill_u32(st, d.bwd_carryJ, 0u, nst * (size_t)d.BN);
+  fill_u32(st, d.gsum, 0u, nst * (size_t)d.S);
+  fill_u32(st, d.gwin, 0u, nst * 2 * (size_t)d.W * d.BN);
   fill_u32(st, d.Gacc, 0u, (size_t)d.R * d.BN);
   for (long long n = T - 1; n >= 0; --n) {
     open_group(h, st);
-    if (d.alpha_s > 0.0f) hipLaunchKernelGGL((k_bwd_step_win<true>), gn, block, 0, st, d, n, T, dL_dcount, dL_dU);
-    else hipLaunchKernelGGL((k_bwd_step_win<false>), gn, block, 0, st, d, n, T, dL_dcount, dL_dU);
+    if (d.alpha_r > 0.0f) hipLaunchKernelGGL((k_bwd_step_win<2>), gn, block, 0, st, d, n, T, dL_dcount, dL_dU);
+    else if (d.alpha_s > 0.0f) hipLaunchKernelGGL((k_bwd_step_win<1>), gn, block, 0, st, d, n, T, dL_dcount, dL_dU);
+    else hipLaunchKernelGGL((k_bwd_step_win<0>), gn, block, 0, st, d, n, T, dL_dcount, dL_dU);
     h->grp_count += 1;
     if ((n & (long long)(d.W - 1)) == 0 && n > 0) {
       close_group(h, st, 3);
       mark(h, st, -1);
       const long long lo = n - d.d_max > 0 ? n - d.d_max : 0;
       const int nvb = gather_blocks(d, lo, n);
-      hipLaunchKernelGGL(k_bwd_win, dim3((unsigned)nvb), dim3(kRingThreads), 0, st, d, n, lo, n, T, 0, nvb);
+      if (d.alpha_r > 0.0f) hipLaunchKernelGGL((k_bwd_win<true>), dim3((unsigned)nvb), dim3(kRingThreads), 0, st, d, n, lo, n, T, 0, nvb);
+      else hipLaunchKernelGGL((k_bwd_win<false>), dim3((unsigned)nvb), dim3(kRingThreads), 0, st, d, n, lo, n, T, 0, nvb);
       mark(h, st, 2);
     }
   }
@@ -906,6 +929,10 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   d.dt = cfg->dt_ms;
   d.tau = cfg->tau_syn_ms > 0.0f ? cfg->tau_syn_ms : cfg->tau_m_ms;
   d.alpha_s = cfg->tau_syn_ms > 0.0f ? (float)std::exp(-(double)cfg->dt_ms / (double)cfg->tau_syn_ms) : 0.0f;
+  d.alpha_r = cfg->tau_rise_ms > 0.0f ? (float)std::exp(-(double)cfg->dt_ms / (double)cfg->tau_rise_ms) : 0.0f;
+  d.alpha_diff = (float)((double)d.alpha_s - (double)d.alpha_r);
+  d.inv_tau_b = cfg->tau_rise_ms > 0.0f ? (float)(1.0 / (double)cfg->tau_rise_ms) : 0.0f;
+  d.inv_tau_diff = cfg->tau_rise_ms > 0.0f ? (float)(1.0 / (double)cfg->tau_rise_ms - 1.0 / (double)cfg->tau_syn_ms) : 0.0f;
   d.J = (float*)(ws + L.J); d.bwd_carryJ = (float*)(ws + L.bwd_carryJ);
   {
     double p = (double)cfg->ext_rate_hz * (double)cfg->dt_ms * 1e-3;
@@ -1123,19 +1150,22 @@ int adseq_backward(adseq_t* h, const float* dL_dcount, const float* dL_dU, float
     return fail(h, ADSEQ_E_CAPACITY, "adseq_backward: tape or contender pool overflowed (bits %u)", err);
   const long long T = h->next_step;
   // gradient per unit the delay was given in: 1/tau per ms, dt/tau per step
-  const float dscale = d.continuous ? (float)(1.0 / (double)d.tau) : (float)((double)d.dt / (double)d.tau);
+  // (double-exponential synapse: the 1/tau factors are in the gathered adjoint, one per state)
+  const float dscale = d.alpha_r > 0.0f ? d.dt
+                       : d.continuous ? (float)(1.0 / (double)d.tau) : (float)((double)d.dt / (double)d.tau);
   const dim3 block(kBlock), gn(grid_for((size_t)d.BN));
   const bool bounded = d.kind != ADSEQ_RING;
+  const size_t nst = d.alpha_r > 0.0f ? 2 : 1;
   if (!bounded) {
     ring_backward_launch(h, st, T, dscale, dL_dcount, dL_dU, grad_w, grad_d);
     HIP_TRY(h, hipGetLastError());
     return ADSEQ_OK;
   }
   fill_u32(st, d.bwd_carry, 0u, (size_t)d.BN);
-  if (d.alpha_s > 0.0f) fill_u32(st, d.bwd_carryJ, 0u, (size_t)d.BN);
+  if (d.alpha_s > 0.0f) fill_u32(st, d.bwd_carryJ, 0u, nst * (size_t)d.BN);
   fill_u32(st, grad_w, 0u, (size_t)d.S);
   fill_u32(st, grad_d, 0u, (size_t)d.S);
-  fill_u32(st, d.bwd_ring, 0u, (size_t)d.R * d.BN);
+  fill_u32(st, d.bwd_ring, 0u, nst * (size_t)d.R * d.BN);
   // where the spikes of every step sit on the tape (the launch grids are sized by it)
   std::vector<long long> offs((size_t)T + 1);
   HIP_TRY(h, hipMemcpyAsync(offs.data(), d.step_off, sizeof(long long) * ((size_t)T + 1), hipMemcpyDeviceToHost, st));

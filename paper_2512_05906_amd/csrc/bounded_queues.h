@@ -296,7 +296,7 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
   if (!per_synapse_kind(KIND) && blockIdx.x == 0 && threadIdx.x == 0) d.ctr->pool_n[0] = 0;   // the overflow pool is consumed by this launch
   counts_clear(s_cnt);
   const bool dense = d.prefetch != 0;   // few targets: latency-bound, load everything in the first round
-  float v = 0.0f, jsyn = 0.0f;
+  float v = 0.0f, jsyn = 0.0f, jfast = 0.0f;
   int len = 0;
   if (per_synapse_kind(KIND)) {
     // per-synapse queues: k_synq_pop has summed the events due now into the target's cell
@@ -305,6 +305,7 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
       if (MODE == 2) {
         v = d.V[g];
         if (d.alpha_s > 0.0f) jsyn = d.J[g];
+        if (d.alpha_r > 0.0f) jfast = d.J[(size_t)d.BN + g];
         if (dense) len = d.rowlen[d.B == 1 ? g : g % d.N];
       }
     }
@@ -328,6 +329,7 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
     if (MODE == 2) {
       v = d.V[g];
       if (d.alpha_s > 0.0f) jsyn = d.J[g];
+      if (d.alpha_r > 0.0f) jfast = d.J[(size_t)d.BN + g];
       if (dense) len = d.rowlen[d.B == 1 ? g : g % d.N];
     }
     const QState q0 = q;
@@ -430,7 +432,16 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
   if (act && MODE != 0) {
     float I = (float)r.acc * 0x1p-24f;
     if (MODE == 2) {
-      if (d.alpha_s > 0.0f) { I = __fmaf_rn(d.alpha_s, jsyn, I); d.J[g] = I; }   // first-order synapse: the jumps go into J
+      if (d.alpha_s > 0.0f) {   // the jumps go into the synaptic current state(s)
+        const float jump = I;
+        I = __fmaf_rn(d.alpha_s, jsyn, jump);
+        d.J[g] = I;
+        if (d.alpha_r > 0.0f) {   // double-exponential synapse: current = slow state - fast state
+          const float fast = __fmaf_rn(d.alpha_r, jfast, jump);
+          d.J[(size_t)d.BN + g] = fast;
+          I = I - fast;
+        }
+      }
       if (d.p_thresh) {
         const bool xi = (unsigned long long)drive_bits(d.seed, (unsigned long long)g,
                                                        (unsigned long long)n) < d.p_thresh;

@@ -191,12 +191,14 @@ __device__ __forceinline__ void near_scatter(const Dev& d, int* __restrict__ win
 // row phi = n mod W, adds the drive, integrates, records the membrane value and the spike bits,
 // and scatters the in-window events of its own spikes.  No block-level synchronisation and no
 // counter: spikes and offered events are counted from the spike bits when a window closes.
-template <bool RECORD, bool SYN>
+// SYN: synaptic current states (0: the jumps go into the membrane, 1: first-order synapse, 2: double-
+// exponential synapse, the slow and the fast state both take the jump and the current is their difference)
+template <bool RECORD, int SYN>
 __global__ __launch_bounds__(kBlock) void k_step_win(Dev d, long long n, const float* __restrict__ i_ext,
                                                      unsigned char* __restrict__ spikes_out) {
   pin_args(d.win, d.V, d.row_ptr, d.nearcnt, d.tapeU, d.spk_count, d.spike_bits, d.tape_bits, d.synf, d.J,
            d.N, d.B, d.BN, d.W, d.wshift, d.d_max, d.R, d.words, d.dbits, d.dmask, d.alpha, d.theta,
-           d.v_reset, d.ext_w, d.alpha_s, d.p_thresh, d.seed, n, i_ext, spikes_out);
+           d.v_reset, d.ext_w, d.alpha_s, d.alpha_r, d.p_thresh, d.seed, n, i_ext, spikes_out);
   const int g = blockIdx.x * kBlock + threadIdx.x;
   const bool act = g < d.BN;
   const int phi = (int)(n & (long long)(d.W - 1));
@@ -218,9 +220,19 @@ __global__ __launch_bounds__(kBlock) void k_step_win(Dev d, long long n, const f
     if (near_h >= 1) ncnt = d.nearcnt[(size_t)near_h * d.N + i];
     const float v = d.V[g];
     const float jsyn = SYN ? d.J[g] : 0.0f;
+    const float jfast = SYN == 2 ? d.J[(size_t)d.BN + g] : 0.0f;
     if (acc != 0) win[idx] = 0;
     float I = (float)acc * 0x1p-24f;
-    if (SYN) { I = __fmaf_rn(d.alpha_s, jsyn, I); d.J[g] = I; }   // first-order synapse: the jumps go into J
+    if (SYN) {   // the jumps go into the synaptic current state(s)
+      const float jump = I;
+      I = __fmaf_rn(d.alpha_s, jsyn, jump);
+      d.J[g] = I;
+      if (SYN == 2) {
+        const float fast = __fmaf_rn(d.alpha_r, jfast, jump);
+        d.J[(size_t)d.BN + g] = fast;
+        I = I - fast;
+      }
+    }
     if (d.p_thresh) {
       const bool xi = (unsigned long long)drive_bits(d.seed, (unsigned long long)g,
                                                      (unsigned long long)n) < d.p_thresh;
@@ -829,7 +841,8 @@ __device__ __forceinline__ float bwd_update(const Dev& d, long long n, float U, 
     const float vprev = n > 0 ? (Uprev >= d.theta ? d.v_reset : Uprev) : 0.0f;
     float vdot = (U - vprev) / d.dt;
     if (vdot == 0.0f) vdot = 1.0f;
-    e = -(1.0f / vdot) * (1.0f / d.tau) * G;
+    // (double-exponential synapse: G was gathered with the 1 / tau factors of the two states in it)
+    e = d.alpha_r > 0.0f ? -(1.0f / vdot) * G : -(1.0f / vdot) * (1.0f / d.tau) * G;
   }
   return __fmaf_rn(d.alpha, gu, e);
 }
@@ -837,27 +850,52 @@ __device__ __forceinline__ float bwd_update(const Dev& d, long long n, float U, 
 // What an event delivered to neuron g at this step gathers: the adjoint of the state that took its
 // jump.  Without a synaptic current state that is gU itself; with one, dL/dJ[n] = gU[n] + alpha_s
 // dL/dJ[n+1] (kept in bwd_carryJ).
-__device__ __forceinline__ float bwd_receiver(const Dev& d, int g, float gu) {
+// Double-exponential synapse (states A, B; current A - B): gA[n] = dL/dA[n] = gU[n] + alpha_s gA[n+1],
+// gB[n] = dL/dB[n] = -gU[n] + alpha_r gB[n+1]; the weight gathers X = gA + gB (returned), the
+// delay and the emission time gather Y = gA / tau_syn + gB / tau_rise (*y_out).  Kept are gA and X
+// rather than gA and gB: gU cancels in the sum, X[n] = alpha_r X[n+1] + (alpha_s - alpha_r) gA[n+1],
+// which fp32 follows without the loss of digits that adding two nearly opposite numbers has.
+__device__ __forceinline__ float bwd_receiver(const Dev& d, int g, float gu, float* y_out) {
   if (!(d.alpha_s > 0.0f)) return gu;
-  const float gj = __fmaf_rn(d.alpha_s, d.bwd_carryJ[g], gu);
+  const float ga_next = d.bwd_carryJ[g];
+  const float gj = __fmaf_rn(d.alpha_s, ga_next, gu);
   d.bwd_carryJ[g] = gj;
-  return gj;
+  if (!(d.alpha_r > 0.0f)) return gj;
+  const float x = __fmaf_rn(d.alpha_r, d.bwd_carryJ[(size_t)d.BN + g], d.alpha_diff * ga_next);
+  d.bwd_carryJ[(size_t)d.BN + g] = x;
+  *y_out = x * d.inv_tau_b - gj * d.inv_tau_diff;   // = gA / tau_syn + (X - gA) / tau_rise
+  return x;
+}
+
+// Double-exponential synapse: which of the two gathered adjoints the queue term of the emitting
+// spike is made of (its value in the surrogate modes, its time in the spike-time mode).
+__device__ __forceinline__ float queue_term_of(const Dev& d, float x, float y) {
+  return d.surrogate == ADSEQ_GRAD_SPIKE_TIME ? y : x;
 }
 
 // Gathers the adjoint at the arrival cell of the entries [0, cnt) of the sorted row at pr0
 // (a spike at step n, window phase phi; arrivals inside the same window), adds it to gsum and
 // returns the wavefront's sum of amplitude * adjoint in every lane.
+template <bool DEXP>
 __device__ __forceinline__ float near_gather(const Dev& d, const float* __restrict__ gwin, long long n,
                                              long long T, int phi, long long pr0, unsigned cnt, int base) {
   const int lane = threadIdx.x & 63;
+  const size_t second = 2 * (size_t)d.W * d.BN;   // the Y rows lie behind the two window buffers of X
   float G = 0.0f;
   for (unsigned q = lane; q < cnt; q += 64) {
     const uint2 e = d.synb[pr0 + q];
     const int D = (int)(e.x & d.dmask);
     if (n + D < T) {
-      const float gv = gwin[(size_t)(phi + D) * d.BN + (size_t)base + (e.x >> d.dbits)];
-      G += __uint_as_float(e.y) * gv;
+      const size_t cell = (size_t)(phi + D) * d.BN + (size_t)base + (e.x >> d.dbits);
+      const float gv = gwin[cell];
       unsafeAtomicAdd(&d.gsum[pr0 + q], gv);
+      if (DEXP) {
+        const float gy = gwin[second + cell];
+        unsafeAtomicAdd(&d.gsum[(size_t)d.S + pr0 + q], gy);
+        G += __uint_as_float(e.y) * queue_term_of(d, gv, gy);
+      } else {
+        G += __uint_as_float(e.y) * gv;
+      }
     }
   }
   return wave_sum_f(G);
@@ -869,7 +907,9 @@ __device__ __forceinline__ float near_gather(const Dev& d, const float* __restri
 //   gU[n] = (1 - s) carry + sigma'(U - theta) (dL/dcount + s G) + dL/dU[n]
 //   carry <- alpha gU[n] + E,  E = -(1 / vdot)(1 / tau) G for a spike in the spike-time mode
 // (see bwd_update)
-template <bool SYN>
+// SYN: synaptic current states, as in k_step_win; 2 = double-exponential synapse: every gather
+// takes two adjoints, X for the weight and Y for the delay (see bwd_receiver)
+template <int SYN>
 __global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, long long T,
                                                          const float* __restrict__ dL_dcount,
                                                          const float* __restrict__ dL_dU) {
@@ -887,6 +927,8 @@ __global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, lon
   long long r0 = 0;
   unsigned ncnt = 0;
   float* __restrict__ gwin = gwin_of(d, n);
+  constexpr bool DEXP = SYN == 2;
+  const size_t second = 2 * (size_t)d.W * d.BN;   // the Y rows lie behind the two window buffers of X
   if (act) {
     b = d.B == 1 ? 0 : g / d.N;
     const int i = g - b * d.N;
@@ -926,13 +968,16 @@ __global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, lon
       e[j] = make_uint2(0u, 0u);
       if ((unsigned)lane < cn[j]) e[j] = d.synb[pr[j] + lane];
     }
-    float gv[4];
+    float gv[4], gy[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      gv[j] = 0.0f;
+      gv[j] = 0.0f; gy[j] = 0.0f;
       const int D = (int)(e[j].x & d.dmask);
-      if ((unsigned)lane < cn[j] && n + D < T)
-        gv[j] = gwin[(size_t)(phi + D) * d.BN + (size_t)bs[j] + (e[j].x >> d.dbits)];
+      if ((unsigned)lane < cn[j] && n + D < T) {
+        const size_t cell = (size_t)(phi + D) * d.BN + (size_t)bs[j] + (e[j].x >> d.dbits);
+        gv[j] = gwin[cell];
+        if (DEXP) gy[j] = gwin[second + cell];
+      }
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -940,18 +985,21 @@ __global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, lon
       const int D = (int)(e[j].x & d.dmask);
       float part = 0.0f;
       if ((unsigned)lane < cn[j] && n + D < T) {
-        part = __uint_as_float(e[j].y) * gv[j];
+        part = __uint_as_float(e[j].y) * (DEXP ? queue_term_of(d, gv[j], gy[j]) : gv[j]);
         unsafeAtomicAdd(&d.gsum[pr[j] + lane], gv[j]);
+        if (DEXP) unsafeAtomicAdd(&d.gsum[(size_t)d.S + pr[j] + lane], gy[j]);
       }
       part = wave_sum_f(part);
-      if (cn[j] > 64u) part += near_gather(d, gwin, n, T, phi, pr[j] + 64, cn[j] - 64u, bs[j]);
+      if (cn[j] > 64u) part += near_gather<DEXP>(d, gwin, n, T, phi, pr[j] + 64, cn[j] - 64u, bs[j]);
       if (lane == Ls[j]) G += part;
     }
   }
   if (act) {
     float gu;
     d.bwd_carry[g] = bwd_update(d, n, U, Uprev, s, carry, inner, G, dU, &gu);
-    gwin[(size_t)phi * d.BN + g] = SYN ? bwd_receiver(d, g, gu) : gu;
+    float y = 0.0f;
+    gwin[(size_t)phi * d.BN + g] = SYN ? bwd_receiver(d, g, gu, &y) : gu;
+    if (DEXP) gwin[second + (size_t)phi * d.BN + g] = y;
   }
 }
 
@@ -961,12 +1009,25 @@ __global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, lon
 // gathers its adjoints from the window (6.4 MB: the L2 holds it), adds them to gsum, and the
 // wavefront's sum of amplitude * adjoint is added to Gacc[n mod R][g] (one wavefront per piece,
 // one piece per spike and window).
+// DEXP (double-exponential synapse): two adjoints per arrival cell, X and Y (see bwd_receiver).
+template <bool DEXP>
 __device__ __forceinline__ void role_gather(const Dev& d, ExpandLds& L, long long k0, long long n_lo, long long n_hi,
                                             long long T, int vb, int nvb) {
   if (threadIdx.x == 0) { L.qn = 0; L.qhead = 0; }
   __syncthreads();
   const int lane = threadIdx.x & 63;
   const float* __restrict__ gwin = gwin_of(d, k0);
+  const size_t second = 2 * (size_t)d.W * d.BN;   // the Y rows lie behind the two window buffers of X
+  // one gathered entry: amplitude bits ab, arrival cell `cell`, sorted-row position q
+  auto take = [&](unsigned ab, size_t cell, long long q, float x) -> float {
+    unsafeAtomicAdd(&d.gsum[q], x);
+    if (DEXP) {
+      const float y = gwin[second + cell];
+      unsafeAtomicAdd(&d.gsum[(size_t)d.S + q], y);
+      return __uint_as_float(ab) * queue_term_of(d, x, y);
+    }
+    return __uint_as_float(ab) * x;
+  };
   auto finish = [&](const Seg& o, float G) {
     G = wave_sum_f(G);
     if (lane == 0) {
@@ -979,9 +1040,8 @@ __device__ __forceinline__ void role_gather(const Dev& d, ExpandLds& L, long lon
     float G = 0.0f;
     for (int q = lane; q < o.len; q += 64) {
       const uint2 e = d.synb[o.p0 + q];
-      const float x = gwin[(size_t)((int)(e.x & d.dmask) - o.dlo) * d.BN + (size_t)o.base + (e.x >> d.dbits)];
-      G += __uint_as_float(e.y) * x;
-      unsafeAtomicAdd(&d.gsum[o.p0 + q], x);
+      const size_t cell = (size_t)((int)(e.x & d.dmask) - o.dlo) * d.BN + (size_t)o.base + (e.x >> d.dbits);
+      G += take(e.y, cell, o.p0 + q, gwin[cell]);
     }
     finish(o, G);
   };
@@ -1006,13 +1066,14 @@ __device__ __forceinline__ void role_gather(const Dev& d, ExpandLds& L, long lon
       }
     }
     float gv[4][2];
+    size_t cell[4][2];
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         gv[j][h] = 0.0f;
-        if (lane + 64 * h < o[j].len)
-          gv[j][h] = gwin[(size_t)((int)(ev[j][h].x & d.dmask) - o[j].dlo) * d.BN + (size_t)o[j].base + (ev[j][h].x >> d.dbits)];
+        cell[j][h] = (size_t)((int)(ev[j][h].x & d.dmask) - o[j].dlo) * d.BN + (size_t)o[j].base + (ev[j][h].x >> d.dbits);
+        if (lane + 64 * h < o[j].len) gv[j][h] = gwin[cell[j][h]];
       }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -1020,25 +1081,22 @@ __device__ __forceinline__ void role_gather(const Dev& d, ExpandLds& L, long lon
       float G = 0.0f;
 #pragma unroll
       for (int h = 0; h < 2; ++h)
-        if (lane + 64 * h < o[j].len) {
-          G += __uint_as_float(ev[j][h].y) * gv[j][h];
-          unsafeAtomicAdd(&d.gsum[o[j].p0 + lane + 64 * h], gv[j][h]);
-        }
+        if (lane + 64 * h < o[j].len) G += take(ev[j][h].y, cell[j][h], o[j].p0 + lane + 64 * h, gv[j][h]);
       for (int q = 128 + lane; q < o[j].len; q += 64) {
         const uint2 e = d.synb[o[j].p0 + q];
-        const float x = gwin[(size_t)((int)(e.x & d.dmask) - o[j].dlo) * d.BN + (size_t)o[j].base + (e.x >> d.dbits)];
-        G += __uint_as_float(e.y) * x;
-        unsafeAtomicAdd(&d.gsum[o[j].p0 + q], x);
+        const size_t c = (size_t)((int)(e.x & d.dmask) - o[j].dlo) * d.BN + (size_t)o[j].base + (e.x >> d.dbits);
+        G += take(e.y, c, o[j].p0 + q, gwin[c]);
       }
       finish(o[j], G);
     }
   }
 }
 
+template <bool DEXP>
 __global__ __launch_bounds__(kRingThreads) void k_bwd_win(Dev d, long long k0, long long n_lo, long long n_hi,
                                                           long long T, int vb0, int nvb) {
   __shared__ ExpandLds L;
-  role_gather(d, L, k0, n_lo, n_hi, T, vb0 + (int)blockIdx.x, nvb);
+  role_gather<DEXP>(d, L, k0, n_lo, n_hi, T, vb0 + (int)blockIdx.x, nvb);
 }
 
 // grad_w[p] = f_p * gsum, grad_d[p] = a_p * dscale * gsum, back in the caller's synapse order.
@@ -1057,7 +1115,8 @@ __global__ __launch_bounds__(kBlock) void k_grad_finish(Dev d, float dscale, flo
       const float gs = d.gsum[q];
       const unsigned pp = d.perm[q];
       const float gw = (d.continuous ? d.fdec[q] : 1.0f) * gs;
-      const float gd = __uint_as_float(d.synb[q].y) * dscale * gs;
+      // (double-exponential synapse: the delay's own sum lies behind the weight's)
+      const float gd = __uint_as_float(d.synb[q].y) * dscale * (d.alpha_r > 0.0f ? d.gsum[(size_t)d.S + q] : gs);
       if (small) { s_w[pp] = gw; s_d[pp] = gd; }
       else { grad_w[r0 + pp] = gw; grad_d[r0 + pp] = gd; }
     }

@@ -53,6 +53,7 @@ def test_workspace_size_grows_with_the_queue():
     dict(kind=adseq.FIFO, capacity=0), dict(kind=adseq.SORTED, capacity=40000),
     dict(dt_ms=0.0), dict(tau_m_ms=0.05), dict(ext_rate_hz=-1.0), dict(n_synapses=-1),
     dict(record_tape=1, max_steps=0), dict(surrogate=5), dict(tau_syn_ms=-1.0), dict(tau_syn_ms=0.05), dict(n_neurons=2**23, d_max_steps=1023),
+    dict(tau_rise_ms=0.5), dict(tau_syn_ms=1.0, tau_rise_ms=1.0), dict(tau_syn_ms=1.0, tau_rise_ms=0.05), dict(tau_syn_ms=1.0, tau_rise_ms=-0.5),
 ])
 def test_invalid_configurations_are_rejected_on_the_host(bad):
     lib = adseq.load()

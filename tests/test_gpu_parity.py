@@ -364,6 +364,30 @@ def test_first_order_synapse_forward_backward(kind, cap, mode):
     assert not np.array_equal(plain.U, ref.U)      # the synaptic state changes the dynamics
 
 
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 4), ("sorted", 6), ("syn", 2), ("latest", 1), ("bins", 3)])
+@pytest.mark.parametrize("mode", [0, 2])
+def test_double_exponential_synapse_forward_backward(kind, cap, mode):
+    """Double-exponential synapse (Section 3.2, closing remark): two synaptic states take every
+    jump, the membrane integrates their difference; the weight gathers the sum of their adjoints,
+    the delay (and, in the spike-time mode, the emitting spike) each adjoint over its own time
+    constant.  Whole-step delays."""
+    wl = synth.ragged_network(150, 300, 30, seed=15, rate_hz=250.0, t=160, b=2, w_mean=0.003, w_std=0.003)
+    wl.tau_syn_ms, wl.tau_rise_ms = 1.7, 0.5
+    ref = _compare_backward(wl, KINDS[kind], cap, 160, 2, surrogate=mode, tape_spike_capacity=2 * 160 * 150)
+    assert ref.spikes.sum() > 100
+    one = oracle.Run(synth.Workload(**{**wl.__dict__, "tau_rise_ms": 0.0}), KINDS[kind], cap, n_steps=160, batch=2)
+    assert not np.array_equal(one.U, ref.U)      # the second state changes the dynamics
+    if kind != "ring":
+        assert ref.counters()["dropped"] > 0
+
+
+def test_double_exponential_synapse_needs_whole_step_delays():
+    wl = synth.ragged_network(20, 10, 10, seed=3, continuous=True)
+    wl.tau_syn_ms, wl.tau_rise_ms = 1.7, 0.5
+    with pytest.raises(adseq.AdseqError):
+        adseq.Adseq(wl, adseq.RING)
+
+
 @pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 32), ("fifo", 2), ("sorted", 128), ("syn", 4)])
 def test_cfg1_forward_backward(kind, cap):
     """Config 1 (1,000 neurons, fan-out 100, batch 16, 2,000 steps), MSE spike-count loss."""
