@@ -85,6 +85,10 @@ def main():
     ap.add_argument("--time-steps", type=int, default=4000)
     ap.add_argument("--delay", type=int, default=80)
     ap.add_argument("--sweep", action="store_true", help="capacity x pressure sweep of the drop rate")
+    ap.add_argument("--capacities", default="1,2,4,8", help="FIFO capacities of the sweep")
+    ap.add_argument("--pressures", default="0.2,0.5,1,2,4",
+                    help="pressures a = delay / mean interval of the sweep (keep the interval well above one step: "
+                         "a source fires at most once per step, so short intervals are not Poisson any more)")
     ap.add_argument("--cfg2-rates", action="store_true",
                     help="the 10,000-neuron x 1,000-fan-out network driven open loop at exactly 5, 20 and 80 Hz: "
                          "ring against per-target FIFOs of capacity 8 and 32")
@@ -98,8 +102,9 @@ def main():
     # calls with no event ever inserted, i.e. the cost that does not depend on the queue's content
     cases = [("ring", 0, 400), ("fifo", 4, 400), ("sorted", 4, 400), ("syn", 4, 400), ("latest", 1, 400), ("bins", 4, 400), ("ring", 0, 0)]
     if args.sweep:
-        cases = [(k, c, lam) for lam in (400, 160, 80, 40, 20) for k, c in
-                 (("fifo", 1), ("fifo", 2), ("fifo", 4), ("fifo", 8), ("sorted", 4), ("syn", 4))]
+        caps = [int(x) for x in args.capacities.split(",")]
+        kinds = [("fifo", c) for c in caps] + [(k, c) for k, c in (("sorted", 4), ("syn", 4)) if c in caps]
+        cases = [(k, c, args.delay / float(a)) for a in args.pressures.split(",") for k, c in kinds]
     if args.cfg2_rates:
         net = synth.cfg2(n_steps=min(args.time_steps, 2000))
         for hz in (5.0, 20.0, 80.0):
