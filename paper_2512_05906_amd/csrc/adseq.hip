@@ -68,6 +68,7 @@ struct RowSpan { long long r0, r1; };
 struct Dev {
   int N, B, BN, R, C, kind, dbits, d_max;
   unsigned dmask;
+  unsigned n_magic;     // floor(2^32 / N) (2^32 - 1 for N = 1): see trial_of
   int continuous, record, surrogate, max_steps, pool_cap;
   float alpha, theta, v_reset, ext_w, dt;
   float tau;            // time constant of the state that takes the jump: tau_syn if there is a synaptic state, else tau_m
@@ -152,6 +153,16 @@ struct Dev {
   int nblk;      // neuron blocks of a step launch: ceil(BN / 256)
   int words;     // 64-neuron words per step in spike_bits (RING) = 4 * nblk
 };
+
+// Trial b = g / N of the state index g = b * N + i (0 <= g < 2^31) without an integer division:
+// with M = floor(2^32 / N), floor(g M / 2^32) is g / N or one less (g M / 2^32 > g / N - g / 2^32
+// > g / N - 1/2), so one correction step makes it exact.
+__device__ __forceinline__ int trial_of(const Dev& d, int g) {
+  if (d.B == 1) return 0;
+  unsigned q = __umulhi((unsigned)g, d.n_magic);
+  if ((unsigned)g - q * (unsigned)d.N >= (unsigned)d.N) ++q;
+  return (int)q;
+}
 
 // ---------------------------------------------------------------- device helpers
 
@@ -335,7 +346,7 @@ __global__ __launch_bounds__(kBlock) void k_bwd_rows(Dev d, long long n, long lo
   const int g = d.tape_spk[off + e];
   const long long evb = d.tape_evb[off + e];
   const RowSpan row = d.tape_row[off + e];
-  const int b = d.B == 1 ? 0 : g / d.N;
+  const int b = trial_of(d, g);
   const int m = (int)(n % d.R);
   const long long stride = (long long)d.fsplit * kBlock;
   const bool dexp = d.alpha_r > 0.0f;              // double-exponential synapse: two adjoint delay lines,
@@ -917,6 +928,7 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   memset(&d, 0, sizeof(d));
   char* ws = (char*)cfg->workspace;
   d.N = cfg->n_neurons; d.B = cfg->batch; d.BN = cfg->n_neurons * cfg->batch;
+  d.n_magic = cfg->n_neurons == 1 ? 0xffffffffu : (unsigned)(0x100000000ull / (unsigned long long)cfg->n_neurons);
   d.R = L.R; d.C = cfg->capacity; d.kind = cfg->kind; d.dbits = L.dbits; d.d_max = cfg->d_max_steps;
   d.dmask = (1u << L.dbits) - 1u;
   d.continuous = cfg->delay_ms ? 1 : 0;

@@ -306,7 +306,7 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
         v = d.V[g];
         if (d.alpha_s > 0.0f) jsyn = d.J[g];
         if (d.alpha_r > 0.0f) jfast = d.J[(size_t)d.BN + g];
-        if (dense) len = d.rowlen[d.B == 1 ? g : g % d.N];
+        if (dense) len = d.rowlen[g - trial_of(d, g) * d.N];
       }
     }
   } else if (act) {
@@ -330,7 +330,7 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
       v = d.V[g];
       if (d.alpha_s > 0.0f) jsyn = d.J[g];
       if (d.alpha_r > 0.0f) jfast = d.J[(size_t)d.BN + g];
-      if (dense) len = d.rowlen[d.B == 1 ? g : g % d.N];
+      if (dense) len = d.rowlen[g - trial_of(d, g) * d.N];
     }
     const QState q0 = q;
     // second round of loads: the contender records (and, below, the amplitudes of the due events)
@@ -451,7 +451,7 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
       const float U = __fmaf_rn(d.alpha, v, I);
       s = U >= d.theta;
       d.V[g] = s ? d.v_reset : U;
-      if (s && !dense) len = d.rowlen[d.B == 1 ? g : g % d.N];
+      if (s && !dense) len = d.rowlen[g - trial_of(d, g) * d.N];
       if (d.record && n < d.max_steps) {
         d.tapeU[(size_t)n * d.BN + g] = U;
         if (s) atomicAdd(&d.spk_count[g], 1);   // no return value: the wavefront does not wait for it
@@ -581,7 +581,7 @@ __device__ __forceinline__ void offer_rows(const Dev& d, long long n, const RowR
   _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                       \
     rs[j] = 0; kc[j] = 0;                                                                               \
     if (j < (NROWS)) {                                                                                  \
-      rr[j].b = d.B == 1 ? 0 : gs[j] / d.N;                                                             \
+      rr[j].b = trial_of(d, gs[j]);                                                             \
       const int i = gs[j] - rr[j].b * d.N;                                                              \
       rr[j].r0 = d.row_ptr[i]; rr[j].r1 = d.row_ptr[i + 1];                                             \
       if (c == 0 && threadIdx.x == 0) rs[j] = d.rowsum[i];                                              \
@@ -716,7 +716,7 @@ __global__ __launch_bounds__(kBlock) void k_fanout_list(Dev d, long long n, cons
   for (int e = blockIdx.x; e < nspk; e += gridDim.x) {
     const int g = spk[e];
     if ((unsigned)g >= (unsigned)d.BN) continue;  // uniform over the block
-    const int b = g / d.N, i = g - b * d.N;
+    const int b = trial_of(d, g), i = g - b * d.N;
     const long long r0 = d.row_ptr[i], r1 = d.row_ptr[i + 1];
     RowRef rr[4];   // the one row as four interleaved shares: four entries per thread in flight
 #pragma unroll

@@ -39,6 +39,67 @@ __global__ void k_random(int* arr, unsigned M, size_t n_ops, int per) {
 
 __global__ void k_empty(int* p) { if (p && threadIdx.x == 9999) p[0] = 1; }
 
+// Dense neuron step as a stream: per neuron one cell (int) and one state (float) read, the state
+// and a trace value written.  VEC = neurons per thread (1: 4-byte accesses, 4: 16-byte accesses).
+template <int VEC>
+__global__ void k_dense_step(const int* __restrict__ cell, float* __restrict__ state, float* __restrict__ trace, size_t n) {
+  const size_t t = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * VEC;
+  if (t >= n) return;
+  if (VEC == 1) {
+    const float u = 0.995f * state[t] + (float)cell[t] * 0x1p-24f;
+    state[t] = u >= 1.0f ? 0.0f : u;
+    trace[t] = u;
+  } else {
+    const int4 c = *reinterpret_cast<const int4*>(cell + t);
+    const float4 v = *reinterpret_cast<const float4*>(state + t);
+    float4 u;
+    u.x = 0.995f * v.x + (float)c.x * 0x1p-24f; u.y = 0.995f * v.y + (float)c.y * 0x1p-24f;
+    u.z = 0.995f * v.z + (float)c.z * 0x1p-24f; u.w = 0.995f * v.w + (float)c.w * 0x1p-24f;
+    *reinterpret_cast<float4*>(trace + t) = u;
+    u.x = u.x >= 1.0f ? 0.0f : u.x; u.y = u.y >= 1.0f ? 0.0f : u.y;
+    u.z = u.z >= 1.0f ? 0.0f : u.z; u.w = u.w >= 1.0f ? 0.0f : u.w;
+    *reinterpret_cast<float4*>(state + t) = u;
+  }
+}
+
+// The same step with four neurons per thread, 64 apart (4-byte accesses, a quarter of the wavefronts).
+__global__ void k_dense_step_strided(const int* __restrict__ cell, float* __restrict__ state, float* __restrict__ trace, size_t n) {
+  const size_t base = ((size_t)blockIdx.x * blockDim.x + (threadIdx.x & ~63u)) * 4 + (threadIdx.x & 63u);
+  int c[4]; float v[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) { const size_t t = base + 64 * j; c[j] = t < n ? cell[t] : 0; v[j] = t < n ? state[t] : 0.0f; }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const size_t t = base + 64 * j;
+    const float u = 0.995f * v[j] + (float)c[j] * 0x1p-24f;
+    if (t < n) { state[t] = u >= 1.0f ? 0.0f : u; trace[t] = u; }
+  }
+}
+
+template <int VEC>
+static int run_dense(size_t n, hipEvent_t e0, hipEvent_t e1) {
+  const int steps = 256, rows = 16;
+  int* cell = nullptr; float *state = nullptr, *trace = nullptr;
+  CK(hipMalloc(&cell, n * 4 * rows)); CK(hipMalloc(&state, n * 4)); CK(hipMalloc(&trace, n * 4 * steps));
+  CK(hipMemset(cell, 0, n * 4 * rows)); CK(hipMemset(state, 0, n * 4));
+  const int per = VEC < 0 ? -VEC : VEC;
+  const unsigned grid = (unsigned)((n / per + 255) / 256);
+  float ms = 0;
+  for (int rep = 0; rep < 2; ++rep) {
+    CK(hipEventRecord(e0));
+    for (int i = 0; i < steps; ++i) {
+      if (VEC < 0) k_dense_step_strided<<<grid, 256>>>(cell + (size_t)(i % rows) * n, state, trace + (size_t)i * n, n);
+      else k_dense_step<(VEC < 0 ? 1 : VEC)><<<grid, 256>>>(cell + (size_t)(i % rows) * n, state, trace + (size_t)i * n, n);
+    }
+    CK(hipEventRecord(e1)); CK(hipEventSynchronize(e1)); CK(hipEventElapsedTime(&ms, e0, e1));
+  }
+  printf("  %8zu neurons, %2d-byte accesses, %d per thread: %6.2f us per launch, %6.0f GB/s (16 B per neuron)\n", n,
+         VEC < 0 ? 4 : 4 * VEC, per,
+         ms * 1e3 / steps, (double)n * 16.0 * steps / ms / 1e6);
+  CK(hipFree(cell)); CK(hipFree(state)); CK(hipFree(trace));
+  return 0;
+}
+
 template <int MODE>
 static int run(const char* name, int* arr, unsigned M, size_t n_ops, unsigned grid_limit, hipEvent_t e0, hipEvent_t e1,
                int per = 16) {
@@ -66,6 +127,12 @@ int main() {
     CK(hipEventRecord(e1)); CK(hipEventSynchronize(e1)); CK(hipEventElapsedTime(&ms, e0, e1));
   }
   printf("1000 empty launches of 391 x 256 threads on one stream: %.2f us each\n", ms);
+  printf("dense neuron step as a stream (cell + state read, state + trace written), 256 launches on one stream:\n");
+  for (size_t n : {(size_t)102400, (size_t)1048576, (size_t)4194304}) {
+    if (run_dense<1>(n, e0, e1)) return 1;
+    if (run_dense<4>(n, e0, e1)) return 1;
+    if (run_dense<-4>(n, e0, e1)) return 1;
+  }
   const size_t sizes[] = {100000, 1600000, 25100000, 251000000};
   for (size_t M : sizes) {
     int* arr = nullptr;

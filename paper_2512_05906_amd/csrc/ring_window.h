@@ -210,7 +210,7 @@ __global__ __launch_bounds__(kBlock) void k_step_win(Dev d, long long n, const f
   unsigned ncnt = 0;
   int* __restrict__ win = win_of(d, n);
   if (act) {
-    b = d.B == 1 ? 0 : g / d.N;   // one trial: no division
+    b = trial_of(d, g);
     const int i = g - b * d.N;
     const size_t idx = (size_t)phi * d.BN + g;
     const int acc = win[idx];
@@ -315,7 +315,7 @@ __global__ __launch_bounds__(kBlock) void k_enqueue_win(Dev d, long long n, cons
   for (int e = wave; e < nspk; e += nwaves) {
     const int g = spk[e];
     if ((unsigned)g >= (unsigned)d.BN) continue;  // uniform over the wavefront
-    const int b = g / d.N, i = g - b * d.N;
+    const int b = trial_of(d, g), i = g - b * d.N;
     if (lane == 0) atomicOr(&d.spike_bits[(size_t)(n % d.R) * d.words + (g >> 6)], 1ull << (g & 63));
     if (near_h >= 1)
       near_scatter(d, win_of(d, n), phi, d.row_ptr[i], d.nearcnt[(size_t)near_h * d.N + i], b * d.N);
@@ -351,7 +351,7 @@ __global__ __launch_bounds__(kBlock) void k_open_step_win(Dev d, long long n, co
   for (int e = wave; e < nspk; e += nwaves) {
     const int g = spk[e];
     if ((unsigned)g >= (unsigned)d.BN) continue;  // uniform over the wavefront
-    const int b = g / d.N, i = g - b * d.N;
+    const int b = trial_of(d, g), i = g - b * d.N;
     if (lane == 0) atomicOr(&d.spike_bits[(size_t)(n % d.R) * d.words + (g >> 6)], 1ull << (g & 63));
     if (near_h >= 1)
       near_scatter(d, win, phi, d.row_ptr[i], d.nearcnt[(size_t)near_h * d.N + i], b * d.N);
@@ -454,7 +454,7 @@ __device__ __forceinline__ void walk_segments(const Dev& d, ExpandLds& L, const 
         bits &= bits - 1;
         const long long g = (long long)word * 64 + bit;
         if (g < d.BN) {
-          const int b = (int)(g / d.N), i = (int)(g - (long long)b * d.N);
+          const int b = trial_of(d, (int)g), i = (int)g - b * d.N;
           const unsigned* ds = d.dstart + (size_t)i * nb;
           // all loads of the spike are requested before the first is used
           const unsigned q0 = ds[dlo], q1 = ds[dhi];
@@ -930,7 +930,7 @@ __global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, lon
   constexpr bool DEXP = SYN == 2;
   const size_t second = 2 * (size_t)d.W * d.BN;   // the Y rows lie behind the two window buffers of X
   if (act) {
-    b = d.B == 1 ? 0 : g / d.N;
+    b = trial_of(d, g);
     const int i = g - b * d.N;
     U = d.tapeU[(size_t)n * d.BN + g];
     if (d.surrogate == ADSEQ_GRAD_SPIKE_TIME && n > 0) Uprev = d.tapeU[(size_t)(n - 1) * d.BN + g];
