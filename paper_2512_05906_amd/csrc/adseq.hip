@@ -681,6 +681,8 @@ void launch_reset(adseq* h, hipStream_t st) {
     fill_u32(st, d.win, 0u, 2 * (size_t)d.W * BN);
     fill_u32(st, d.spike_bits, 0u, (size_t)d.R * d.words * 2);
     fill_u32(st, d.blk, 0u, kMaxBinBlocks * sizeof(BlkCtr) / 4);
+    // staging counters: zero except between the two passes of a window's expansion
+    if (d.cap > 0) fill_u32(st, d.ecnt, 0u, (size_t)(d.P < kMaxParts ? d.P : kMaxParts) * d.NB);
   } else if (per_synapse_kind(d.kind)) {
     fill_u32(st, d.sq_next, 0xffffffffu,
              (size_t)(d.kind == ADSEQ_SYN_BINS ? d.C : 1) * (((size_t)d.B * d.S + 7) / 8 * 4));   // every queue empty

@@ -376,7 +376,7 @@ constexpr int kSegQueue = 768;   // queue entries per block (32 B each)
 struct ExpandLds {
   int cur[kMaxParts];        // staging cursors of k_win_bin's parts
   Seg q[kSegQueue];          // segments found by the walk, shared out among the wavefronts
-  int qn, qhead;
+  int qn, qhead, qlen;       // queued pieces, next to hand out, events in the queued pieces
   long long red[3][kRingWaves];
 };
 static_assert(sizeof(ExpandLds) <= kMaxTileCells * 4, "roles share one LDS buffer");
@@ -402,23 +402,17 @@ __device__ __forceinline__ void stage_event(const Dev& d, int* __restrict__ win,
 // A wavefront's share of a walk over the spike words of steps [n_lo, n_hi): the words of a step
 // are cut into lines of 8 (64 bytes); the line numbered c = gw + nwaves * (8 t + group) belongs
 // to the 8-lane group `group` of wavefront gw in trip t, so that lines are dealt round-robin over
-// all wavefronts and one wavefront sees up to 8 lines of different steps at once.  Sets the step
-// and the spike word of this lane (0 if it has none).
-__device__ __forceinline__ unsigned long long walk_word(const Dev& d, const unsigned long long* __restrict__ words,
-                                                        bool circular, long long n_lo, long long n_hi,
-                                                        long long c0, long long nwaves, long long* n_out,
-                                                        int* word_out) {
-  const int lane = threadIdx.x & 63;
-  const long long lps = (d.words + 7) >> 3;
-  const long long c = c0 + nwaves * (lane >> 3);
-  *n_out = n_lo; *word_out = 0;
-  if (c >= (n_hi - n_lo) * lps) return 0ull;
-  const long long si = c / lps;
-  const long long n = n_lo + si;
-  const int word = (int)(c - si * lps) * 8 + (lane & 7);
-  *n_out = n; *word_out = word;
-  if (word >= d.words) return 0ull;
-  return words[(size_t)(circular ? n % d.R : n) * d.words + word];
+// all wavefronts and one wavefront sees up to 8 lines of different steps at once.  A lane keeps
+// its line as (step index si, line of the step rem) and moves on by a fixed stride per trip, so
+// the walk divides once per lane and not once per trip.
+struct WalkPos {
+  long long si;   // step n_lo + si
+  int rem;        // line of that step, 0 .. lps - 1
+};
+__device__ __forceinline__ void walk_advance(WalkPos& p, long long dq, int dr, int lps) {
+  p.si += dq;
+  p.rem += dr;
+  if (p.rem >= lps) { p.rem -= lps; p.si += 1; }
 }
 
 // Walks the spike words of steps [n_lo, n_hi) as virtual block vb of nvb (16 wavefronts each)
@@ -434,53 +428,86 @@ __device__ __forceinline__ void walk_segments(const Dev& d, ExpandLds& L, const 
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const long long gw = vb + (long long)nvb * wv;   // blocks interleaved: every block sees every step
   const long long nwaves = (long long)nvb * kRingWaves;
-  const long long nlines = (n_hi - n_lo) * ((d.words + 7) >> 3);
+  const int lps = (d.words + 7) >> 3;                   // lines per step
+  const long long nsteps = n_hi - n_lo;                  // at most d_max + 1 <= R
+  const long long nlines = nsteps * lps;
   const int nb = d.d_max + 2;
-  for (long long c0 = gw; c0 < nlines; c0 += nwaves * 8) {
-    long long n; int word;
-    unsigned long long bits = walk_word(d, words, circular, n_lo, n_hi, c0, nwaves, &n, &word);
-    const int dlo = (int)(k0 - n);                      // 1 .. d_max
-    int dhi = dlo + d.W < nb - 1 ? dlo + d.W : nb - 1;
-    if (T >= 0) {
-      if ((long long)dhi > T - n) dhi = (int)(T - n);   // arrivals n + D >= T are never delivered
-      if (dhi < dlo) dhi = dlo;
-    }
-    const bool counted = n >= count_from;
-    while (__ballot(bits != 0ull)) {
-      // every lane that still has a spike takes its lowest one
-      Seg sg; sg.p0 = 0; sg.len = 0; sg.base = 0; sg.dlo = dlo; sg.slot = (int)(n % d.R); sg.g = 0;
-      if (bits) {
-        const int bit = __ffsll((long long)bits) - 1;
-        bits &= bits - 1;
-        const long long g = (long long)word * 64 + bit;
-        if (g < d.BN) {
-          const int b = trial_of(d, (int)g), i = (int)g - b * d.N;
-          const unsigned* ds = d.dstart + (size_t)i * nb;
-          // all loads of the spike are requested before the first is used
-          const unsigned q0 = ds[dlo], q1 = ds[dhi];
-          const long long r0 = d.row_ptr[i];
-          // (the row's length and sum are loaded for every spike, counted or not: under a branch
-          // of their own they would be a second round trip to memory)
-          const long long r1 = d.row_ptr[i + 1], rs = d.rowsum[i];
-          sg.p0 = r0 + q0; sg.len = (int)(q1 - q0); sg.base = b * d.N; sg.g = g;
-          cnt[0] += counted ? 1 : 0; cnt[1] += counted ? r1 - r0 : 0; cnt[2] += counted ? rs : 0;
-        }
+  // this lane's first line, the stride of a trip (the same for every lane), and the row of the
+  // circular spike words that holds step n_lo
+  WalkPos pos;
+  {
+    const long long c = gw + nwaves * (lane >> 3);
+    pos.si = c / lps;
+    pos.rem = (int)(c - pos.si * lps);
+  }
+  const long long stride = nwaves * 8;
+  const long long dq = stride / lps;
+  const int dr = (int)(stride - dq * lps);
+  const int slot_lo = (int)(n_lo % d.R);
+  // four trips' words are requested before the first is looked at
+  for (long long c00 = gw; c00 < nlines; c00 += stride * 4) {
+    unsigned long long bw[4]; long long nn[4]; int ww[4], sl[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      bw[j] = 0ull; nn[j] = n_lo; ww[j] = 0; sl[j] = slot_lo;
+      if (pos.si < nsteps) {   // (a trip past the end gives no word)
+        nn[j] = n_lo + pos.si;
+        ww[j] = pos.rem * 8 + (lane & 7);
+        int slot = slot_lo + (int)pos.si;
+        if (slot >= d.R) slot -= d.R;
+        sl[j] = slot;
+        if (ww[j] < d.words) bw[j] = words[(size_t)(circular ? (long long)slot : nn[j]) * d.words + ww[j]];
       }
-      const bool has = sg.len > 0;
-      const unsigned long long mask = __ballot(has);
-      if (mask) {
-        int pos = 0;
-        if (lane == 0) pos = atomicAdd(&L.qn, __popcll(mask));
-        pos = __builtin_amdgcn_readfirstlane(pos) + __popcll(mask & ((1ull << lane) - 1ull));
-        if (has && pos < kSegQueue) L.q[pos] = sg;
-        unsigned long long ovf = __ballot(has && pos >= kSegQueue);
-        while (ovf) {
-          const int src = __ffsll((long long)ovf) - 1;
-          ovf &= ovf - 1;
-          Seg o;
-          o.p0 = __shfl(sg.p0, src, 64); o.len = __shfl(sg.len, src, 64); o.base = __shfl(sg.base, src, 64);
-          o.dlo = __shfl(sg.dlo, src, 64); o.slot = __shfl(sg.slot, src, 64); o.g = __shfl(sg.g, src, 64);
-          handle(o);
+      walk_advance(pos, dq, dr, lps);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      unsigned long long bits = bw[j];
+      const long long n = nn[j];
+      const int word = ww[j];
+      const int dlo = (int)(k0 - n);                      // 1 .. d_max
+      int dhi = dlo + d.W < nb - 1 ? dlo + d.W : nb - 1;
+      if (T >= 0) {
+        if ((long long)dhi > T - n) dhi = (int)(T - n);   // arrivals n + D >= T are never delivered
+        if (dhi < dlo) dhi = dlo;
+      }
+      const bool counted = n >= count_from;
+      while (__ballot(bits != 0ull)) {
+        // every lane that still has a spike takes its lowest one
+        Seg sg; sg.p0 = 0; sg.len = 0; sg.base = 0; sg.dlo = dlo; sg.slot = sl[j]; sg.g = 0;
+        if (bits) {
+          const int bit = __ffsll((long long)bits) - 1;
+          bits &= bits - 1;
+          const long long g = (long long)word * 64 + bit;
+          if (g < d.BN) {
+            const int b = trial_of(d, (int)g), i = (int)g - b * d.N;
+            const unsigned* ds = d.dstart + (size_t)i * nb;
+            // all loads of the spike are requested before the first is used
+            const unsigned q0 = ds[dlo], q1 = ds[dhi];
+            const long long r0 = d.row_ptr[i];
+            // (the row's length and sum are loaded for every spike, counted or not: under a branch
+            // of their own they would be a second round trip to memory)
+            const long long r1 = d.row_ptr[i + 1], rs = d.rowsum[i];
+            sg.p0 = r0 + q0; sg.len = (int)(q1 - q0); sg.base = b * d.N; sg.g = g;
+            cnt[0] += counted ? 1 : 0; cnt[1] += counted ? r1 - r0 : 0; cnt[2] += counted ? rs : 0;
+          }
+        }
+        const bool has = sg.len > 0;
+        const unsigned long long mask = __ballot(has);
+        if (mask) {
+          int pos = 0;
+          if (lane == 0) pos = atomicAdd(&L.qn, __popcll(mask));
+          pos = __builtin_amdgcn_readfirstlane(pos) + __popcll(mask & ((1ull << lane) - 1ull));
+          if (has && pos < kSegQueue) L.q[pos] = sg;
+          unsigned long long ovf = __ballot(has && pos >= kSegQueue);
+          while (ovf) {
+            const int src = __ffsll((long long)ovf) - 1;
+            ovf &= ovf - 1;
+            Seg o;
+            o.p0 = __shfl(sg.p0, src, 64); o.len = __shfl(sg.len, src, 64); o.base = __shfl(sg.base, src, 64);
+            o.dlo = __shfl(sg.dlo, src, 64); o.slot = __shfl(sg.slot, src, 64); o.g = __shfl(sg.g, src, 64);
+            handle(o);
+          }
         }
       }
     }
@@ -644,10 +671,10 @@ __device__ __forceinline__ void stage_sorted(const Dev& d, ExpandLds& L, SortLds
 // and virtual block).
 __device__ __forceinline__ void role_bin(const Dev& d, ExpandLds& L, SortLds& S, long long k0, long long n_lo,
                                          long long n_hi, int vb, int nvb, int stage, long long count_from) {
-  const int nparts = (stage && d.cap > 0) ? (d.P < kMaxParts ? d.P : kMaxParts) : 0;
+  int nparts = (stage && d.cap > 0) ? (d.P < kMaxParts ? d.P : kMaxParts) : 0;
   int* __restrict__ win = win_of(d, k0);
   for (int x = threadIdx.x; x < nparts; x += kRingThreads) L.cur[x] = 0;
-  if (threadIdx.x == 0) { L.qn = 0; L.qhead = 0; }
+  if (threadIdx.x == 0) { L.qn = 0; L.qhead = 0; L.qlen = 0; }
   __syncthreads();
   const int lane = threadIdx.x & 63;
   auto one = [&](const Seg& o) {
@@ -661,6 +688,21 @@ __device__ __forceinline__ void role_bin(const Dev& d, ExpandLds& L, SortLds& S,
   // counters first: their atomics complete while the events are staged
   if (count_from < n_hi) fold_counts(d, L, cnt, vb);
   const int qn = L.qn < kSegQueue ? L.qn : kSegQueue;
+  // Few events for many parts (fewer queued events than parts: large B x N, low rates): a staging
+  // region would hold one event at most, and the pass would cost its cursors (one counter per
+  // part and block, written here and read again by the accumulation pass) rather than its
+  // events.  Such a block adds its events to the window with global atomics and leaves its
+  // counters as they are: zero.  (Pieces that did not fit the queue were staged during the walk:
+  // then the block stays with staging.)
+  if (nparts > 0) {
+    int mine = 0;
+    for (int x = threadIdx.x; x < qn; x += kRingThreads) mine += L.q[x].len;
+    mine = (int)wave_total64((long long)mine);
+    if (lane == 0 && mine) atomicAdd(&L.qlen, mine);
+    __syncthreads();
+    if (L.qn <= kSegQueue && L.qlen < nparts) nparts = 0;   // uniform over the block
+  }
+  const bool staged = nparts > 0;
   if (stage == 2 && nparts > 0 && nparts <= kSortParts) {
     stage_sorted(d, L, S, win, nparts, vb, qn);
   } else {
@@ -695,10 +737,12 @@ __device__ __forceinline__ void role_bin(const Dev& d, ExpandLds& L, SortLds& S,
     }
   }
   __syncthreads();
-  for (int x = threadIdx.x; x < nparts; x += kRingThreads) {
-    const int c = L.cur[x];
-    d.ecnt[(size_t)x * d.NB + vb] = c < d.cap ? c : d.cap;
-  }
+  // (the counters are zero when the pass begins: the accumulation pass clears what it has read)
+  if (staged)
+    for (int x = threadIdx.x; x < nparts; x += kRingThreads) {
+      const int c = L.cur[x];
+      if (c) d.ecnt[(size_t)x * d.NB + vb] = c < d.cap ? c : d.cap;
+    }
 }
 
 // Accumulation role (pass 2): sums the staged events of target part `part` into an LDS tile
@@ -708,17 +752,22 @@ __device__ __forceinline__ void role_bin(const Dev& d, ExpandLds& L, SortLds& S,
 __device__ __forceinline__ void role_acc(const Dev& d, int* tile, long long k0, int part) {
   const int cells = d.W << d.tp_shift;
   const int nb_runs = d.NB;
+  int* __restrict__ cnts = d.ecnt + (size_t)part * nb_runs;
+  // nothing staged for this part (its blocks of pass 1 chose atomics, or had no event for it):
+  // leave before the tile is touched
+  int any = 0;
+  for (int x = threadIdx.x; x < nb_runs; x += kRingThreads) any |= cnts[x];
   for (int x = threadIdx.x; x < cells; x += kRingThreads) tile[x] = 0;
-  __syncthreads();
+  if (!__syncthreads_or(any)) return;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int sub = lane & 15, grp = lane >> 4;
-  const int* __restrict__ cnts = d.ecnt + (size_t)part * nb_runs;
   for (int r0 = (wv * 4 + grp) * 4; r0 < nb_runs; r0 += kRingWaves * 16) {
     int cn[4]; uint2 ev[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) cn[j] = r0 + j < nb_runs ? cnts[r0 + j] : 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
+      if (sub == 0 && cn[j]) cnts[r0 + j] = 0;   // consumed: zero again for the next window
       ev[j] = make_uint2(0u, 0u);
       if (sub < cn[j]) ev[j] = load_stream(&d.ebuf[((size_t)part * nb_runs + r0 + j) * d.cap + sub]);
     }

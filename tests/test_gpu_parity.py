@@ -114,6 +114,17 @@ def test_ring_window_length_and_staging_capacity(window, stage, monkeypatch):
     assert ref.spikes.sum() > 300
 
 
+@pytest.mark.parametrize("rate_hz", [40.0, 80.0, 160.0])
+def test_ring_sparse_windows_take_atomics_block_by_block(rate_hz):
+    """48,000 state cells (188 target parts) and a firing rate that climbs from zero: a block of
+    the window expansion with fewer events than parts adds them to the window directly and leaves
+    its staging counters untouched, one with more stages them, so a run passes through windows
+    of either sort and windows in which the blocks differ (the results do not: integer sums)."""
+    wl = synth.ragged_network(3000, 40, 60, seed=33, rate_hz=rate_hz, t=200, b=16, w_mean=0.01, w_std=0.01)
+    ref, _ = _compare_forward(wl, oracle.RING, 0, check_sets=False)
+    assert ref.spikes.sum() > 1000
+
+
 def test_ring_rows_longer_than_a_staging_chunk():
     """Rows of up to 60,000 synapses with delays of 1..6 steps: the piece of a row that lands in
     one window (4 steps here) holds tens of thousands of events, so one piece spans several of
