@@ -127,6 +127,15 @@ int main() {
     CK(hipEventRecord(e1)); CK(hipEventSynchronize(e1)); CK(hipEventElapsedTime(&ms, e0, e1));
   }
   printf("1000 empty launches of 391 x 256 threads on one stream: %.2f us each\n", ms);
+  const int shapes[][2] = {{4096, 256}, {2048, 512}, {1024, 1024}, {16384, 64}};
+  for (auto& sh : shapes) {
+    for (int rep = 0; rep < 2; ++rep) {
+      CK(hipEventRecord(e0));
+      for (int i = 0; i < 1000; ++i) k_empty<<<sh[0], sh[1]>>>(nullptr);
+      CK(hipEventRecord(e1)); CK(hipEventSynchronize(e1)); CK(hipEventElapsedTime(&ms, e0, e1));
+    }
+    printf("1000 empty launches of %d x %d threads on one stream: %.2f us each\n", sh[0], sh[1], ms);
+  }
   printf("dense neuron step as a stream (cell + state read, state + trace written), 256 launches on one stream:\n");
   for (size_t n : {(size_t)102400, (size_t)1048576, (size_t)4194304}) {
     if (run_dense<1>(n, e0, e1)) return 1;
