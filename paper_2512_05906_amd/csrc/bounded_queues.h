@@ -450,10 +450,10 @@ __global__ __launch_bounds__(kBlock) void k_neurons(Dev d, long long n, int pari
       if (i_ext) I = I + i_ext[g];
       const float U = __fmaf_rn(d.alpha, v, I);
       s = U >= d.theta;
-      d.V[g] = s ? d.v_reset : U;
+      __builtin_nontemporal_store(s ? d.v_reset : U, &d.V[g]);   // (written once, not read again by this launch)
       if (s && !dense) len = d.rowlen[g - trial_of(d, g) * d.N];
       if (d.record && n < d.max_steps) {
-        d.tapeU[(size_t)n * d.BN + g] = U;
+        __builtin_nontemporal_store(U, &d.tapeU[(size_t)n * d.BN + g]);
         if (s) atomicAdd(&d.spk_count[g], 1);   // no return value: the wavefront does not wait for it
       }
       if (spikes_out) spikes_out[g] = s ? 1 : 0;
