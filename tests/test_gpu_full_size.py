@@ -112,3 +112,58 @@ def test_cfg4_full_batch_forward_backward(kind, cap, drive_hz):
     H.grad_close(g_d.cpu().numpy(), gd)
     assert np.abs(gw).max() > 0 and np.abs(gd).max() > 0
     sim.close()
+
+
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 32)])
+def test_cfg3_bench_run_properties(kind, cap):
+    """The run bench.py times (1,000 steps, the drive tuned for 20 Hz), where the oracle would need
+    minutes: what must hold at any size.  Two runs give the same bits in the membrane trace and the
+    counters (integer sums: nothing depends on the order in which atomics land) and the same
+    gradients up to the order of a synapse's fp32 terms; the events that are
+    neither delivered nor dropped number no more than the queues can still hold; the spike counts
+    and the offered events are those of the recorded trace."""
+    w = synth.cfg3()
+    k = {"ring": adseq.RING, "fifo": adseq.FIFO}[kind]
+    Tb = w.n_steps
+    spike_cap = 4 * w.n_neurons
+    sim = adseq.Adseq(w, k, cap, record_tape=True, max_steps=Tb, tape_spike_capacity=spike_cap,
+                      tape_event_capacity=(spike_cap * w.fan_out if kind != "ring" else 0))
+    y = torch.from_numpy(synth.spike_count_targets(w).reshape(-1)).to(sim.dev)
+    runs = []
+    for rep in range(2):
+        print(f"cfg3 bench run, {kind}[{cap}], pass {rep}", flush=True)
+        if rep:
+            sim.reset()
+        sim.run(0, Tb)
+        cnt = torch.empty(w.n_neurons, dtype=torch.int32, device=sim.dev)
+        sim.spike_counts(cnt)
+        dL_dc = 2.0 * (cnt.float() - y) / w.n_neurons
+        g_w = torch.full((w.n_synapses,), 7.0, dtype=torch.float32, device=sim.dev)
+        g_d = torch.full((w.n_synapses,), 7.0, dtype=torch.float32, device=sim.dev)
+        sim.backward(dL_dc, None, g_w, g_d)
+        torch.cuda.synchronize()
+        U = sim.tape()["U"]
+        c = sim.counters()
+        assert c["error_bits"] == 0
+        in_flight = c["enqueued"] - c["delivered"] - c["dropped"]
+        # what is neither delivered nor dropped is still stored: at most what the queues hold
+        # (bounded kinds), at most the events of the last d_max steps' spikes (ring)
+        last = int((U[Tb - w.d_max_steps:] >= w.v_thresh).sum().item()) * w.fan_out
+        assert 0 <= in_flight <= (min(cap * w.n_neurons, last) if kind != "ring" else last)
+        spikes = int((U >= w.v_thresh).sum().item())
+        assert int(cnt.sum().item()) == spikes and c["enqueued"] == spikes * w.fan_out
+        assert bool(torch.isfinite(g_w).all()) and bool(torch.isfinite(g_d).all())
+        assert float(g_w.abs().max()) > 0 and float(g_d.abs().max()) > 0
+        runs.append((U.clone(), g_w, g_d, c))
+    assert torch.equal(runs[0][0].view(torch.int32), runs[1][0].view(torch.int32))
+    # gradients: the same up to the order in which the terms of one synapse are added (two spikes
+    # of one neuron whose events land in the same window are gathered by the same launch)
+    for a, b in ((runs[0][1], runs[1][1]), (runs[0][2], runs[1][2])):
+        assert float((a - b).norm()) <= 1e-6 * float(a.norm())
+        assert float((a - b).abs().max()) <= 1e-5 * float(a.abs().max())
+    assert runs[0][3] == runs[1][3]
+    if kind == "ring":
+        assert runs[0][3]["dropped"] == 0 and 15.0 < spikes / (w.n_neurons * Tb * w.dt_ms * 1e-3) < 25.0
+    else:
+        assert runs[0][3]["dropped"] > 1e7
+    sim.close()
