@@ -76,11 +76,30 @@ struct Dev {
   float alpha_r;        // exp(-dt / tau_rise), 0 = no second (fast) state: double-exponential synapse if > 0
   float alpha_diff;     // alpha_s - alpha_r
   float inv_tau_b, inv_tau_diff;   // 1 / tau_rise, 1 / tau_rise - 1 / tau_syn
-  float* J;             // [BN] synaptic current state (alpha_s > 0); [2][BN] with the fast state behind it (alpha_r > 0)
-  float* bwd_carryJ;    // [BN] its adjoint dL/dJ[n+1] ([2][BN] if alpha_r > 0: the slow state's adjoint, the sum of both states')
-  unsigned long long p_thresh, seed;
-  long long S, spike_cap, event_cap;
+  // what the ring's step kernels read, side by side: a launch fetches a few lines of its argument
+  // block instead of a dozen
+  int W, wshift;        // window length in steps (power of two) and its log2
+  int nblk;      // neuron blocks of a step launch: ceil(BN / 256)
+  int words;     // 64-neuron words per step in spike_bits (RING) = 4 * nblk
+  int* win;             // [W][BN]
+  float* V;
   const long long* row_ptr;
+  unsigned* nearcnt;    // [W + 1][N]
+  float* tapeU;
+  int* spk_count;       // [BN] spikes per (trial, neuron) over the recorded steps
+  unsigned long long* spike_bits;  // RING: [R][words] spikes of the last R steps
+  unsigned long long* tape_bits;  // [T][words]
+  uint2* synf;          // [S] sorted rows: {col << dbits | D, Q8.24 amplitude}
+  float* J;             // [BN] synaptic current state (alpha_s > 0); [2][BN] with the fast state behind it (alpha_r > 0)
+  unsigned long long p_thresh, seed;
+  float* gwin;          // [W][BN]
+  float* bwd_carry;
+  float* bwd_carryJ;    // [BN] its adjoint dL/dJ[n+1] ([2][BN] if alpha_r > 0: the slow state's adjoint, the sum of both states')
+  float* Gacc;          // [R][BN]
+  uint2* synb;          // [S] sorted rows: {col << dbits | D, fp32 amplitude bits}
+  float* gsum;          // [S]
+  // the rest
+  long long S, spike_cap, event_cap;
   const int* col;
   const float* weight;
   const unsigned char* delay_steps;
@@ -88,28 +107,17 @@ struct Dev {
   unsigned* packed;
   int* a_q;
   // RING (windowed delay line, see ring_window.h)
-  int W, wshift;        // window length in steps (power of two) and its log2
   int tp_shift;         // log2 of the targets per part (W << tp_shift = cells of one LDS tile)
   int P, NB, cap;       // target parts, blocks of the staging pass, events per (part, block) region
   int wgroups;          // 8-word lines (64 bytes) per step in spike_bits
-  int* win;             // [W][BN]
-  uint2* synf;          // [S] sorted rows: {col << dbits | D, Q8.24 amplitude}
-  uint2* synb;          // [S] sorted rows: {col << dbits | D, fp32 amplitude bits}
   unsigned* dstart;     // [N][d_max + 2]
-  unsigned* nearcnt;    // [W + 1][N]
   unsigned* perm;       // [S]
   long long* rowsum;    // [N] Q8.24 amplitude sum of every row (all kinds)
   int* rowlen;          // FIFO/SORTED: [N] row lengths
   uint2* ebuf;          // [min(P, kMaxParts)][NB][cap]
   int* ecnt;            // [min(P, kMaxParts)][NB]
-  unsigned long long* tape_bits;  // [T][words]
-  float* gwin;          // [W][BN]
-  float* Gacc;          // [R][BN]
-  float* gsum;          // [S]
   float* amp;
   float* fdec;
-  float* V;
-  unsigned long long* spike_bits;  // RING: [R][words] spikes of the last R steps
   uint2* slot;          // SORTED: [BN][C] {arrival step, Q8.24 amplitude}, circular, ordered by arrival
   unsigned short* fkey; // FIFO: [BN][cpad] arrival step mod 2^16 of every slot
   int* famp;            // FIFO: [BN][C] Q8.24 amplitude of every slot
@@ -137,8 +145,6 @@ struct Dev {
   int blk_pop;             // SYN_FIFO: index of the first counter line of k_synq_pop's blocks in blk
   unsigned long long* spk_words;  // FIFO/SORTED: [2][words] ballot words of the step launch, by step parity
   long long* stepcnt;   // FIFO/SORTED: [2][nblk][2] spikes and emitted events of every neuron block, by step parity
-  float* tapeU;
-  int* spk_count;       // [BN] spikes per (trial, neuron) over the recorded steps
   long long* step_off;
   long long* step_evoff;  // FIFO/SORTED: events emitted before step n (index of its first admission flag)
   int* tape_spk;
@@ -146,12 +152,9 @@ struct Dev {
   RowSpan* tape_row;    // FIFO/SORTED: row bounds of every recorded spike
   unsigned char* tape_adm;
   float* bwd_ring;
-  float* bwd_carry;
   float* bwd_G;         // FIFO/SORTED: [fsplit][BN] partial queue terms of the spikes of the step being swept
   Counters* ctr;
   BlkCtr* blk;   // FIFO / SORTED: [nblk + kFanoutBlocks]
-  int nblk;      // neuron blocks of a step launch: ceil(BN / 256)
-  int words;     // 64-neuron words per step in spike_bits (RING) = 4 * nblk
 };
 
 // Trial b = g / N of the state index g = b * N + i (0 <= g < 2^31) without an integer division:
