@@ -839,12 +839,12 @@ int step_impl(adseq* h, long long step, const float* i_ext, unsigned char* spike
     open_group(h, st);
     const dim3 grid((unsigned)d.nblk), block(kBlock);
     const int syn = d.alpha_r > 0.0f ? 2 : (d.alpha_s > 0.0f ? 1 : 0);   // synaptic current states
-    if (record && syn == 0) hipLaunchKernelGGL((k_step_win<true, 0>), grid, block, 0, st, d, step, i_ext, spikes_out);
-    else if (record && syn == 1) hipLaunchKernelGGL((k_step_win<true, 1>), grid, block, 0, st, d, step, i_ext, spikes_out);
-    else if (record) hipLaunchKernelGGL((k_step_win<true, 2>), grid, block, 0, st, d, step, i_ext, spikes_out);
-    else if (syn == 0) hipLaunchKernelGGL((k_step_win<false, 0>), grid, block, 0, st, d, step, i_ext, spikes_out);
-    else if (syn == 1) hipLaunchKernelGGL((k_step_win<false, 1>), grid, block, 0, st, d, step, i_ext, spikes_out);
-    else hipLaunchKernelGGL((k_step_win<false, 2>), grid, block, 0, st, d, step, i_ext, spikes_out);
+    if (record && syn == 0) hipLaunchKernelGGL((k_step_win<true, 0>), grid, block, 0, st, step, i_ext, spikes_out, d);
+    else if (record && syn == 1) hipLaunchKernelGGL((k_step_win<true, 1>), grid, block, 0, st, step, i_ext, spikes_out, d);
+    else if (record) hipLaunchKernelGGL((k_step_win<true, 2>), grid, block, 0, st, step, i_ext, spikes_out, d);
+    else if (syn == 0) hipLaunchKernelGGL((k_step_win<false, 0>), grid, block, 0, st, step, i_ext, spikes_out, d);
+    else if (syn == 1) hipLaunchKernelGGL((k_step_win<false, 1>), grid, block, 0, st, step, i_ext, spikes_out, d);
+    else hipLaunchKernelGGL((k_step_win<false, 2>), grid, block, 0, st, step, i_ext, spikes_out, d);
     h->grp_count += 1;
   } else {
     mark(h, st, -1);
@@ -882,9 +882,9 @@ void ring_backward_launch(adseq* h, hipStream_t st, long long T, float dscale, c
   fill_u32(st, d.Gacc, 0u, (size_t)d.R * d.BN);
   for (long long n = T - 1; n >= 0; --n) {
     open_group(h, st);
-    if (d.alpha_r > 0.0f) hipLaunchKernelGGL((k_bwd_step_win<2>), gn, block, 0, st, d, n, T, dL_dcount, dL_dU);
-    else if (d.alpha_s > 0.0f) hipLaunchKernelGGL((k_bwd_step_win<1>), gn, block, 0, st, d, n, T, dL_dcount, dL_dU);
-    else hipLaunchKernelGGL((k_bwd_step_win<0>), gn, block, 0, st, d, n, T, dL_dcount, dL_dU);
+    if (d.alpha_r > 0.0f) hipLaunchKernelGGL((k_bwd_step_win<2>), gn, block, 0, st, n, T, dL_dcount, dL_dU, d);
+    else if (d.alpha_s > 0.0f) hipLaunchKernelGGL((k_bwd_step_win<1>), gn, block, 0, st, n, T, dL_dcount, dL_dU, d);
+    else hipLaunchKernelGGL((k_bwd_step_win<0>), gn, block, 0, st, n, T, dL_dcount, dL_dU, d);
     h->grp_count += 1;
     if ((n & (long long)(d.W - 1)) == 0 && n > 0) {
       close_group(h, st, 3);

@@ -194,8 +194,8 @@ __device__ __forceinline__ void near_scatter(const Dev& d, int* __restrict__ win
 // SYN: synaptic current states (0: the jumps go into the membrane, 1: first-order synapse, 2: double-
 // exponential synapse, the slow and the fast state both take the jump and the current is their difference)
 template <bool RECORD, int SYN>
-__global__ __launch_bounds__(kBlock) void k_step_win(Dev d, long long n, const float* __restrict__ i_ext,
-                                                     unsigned char* __restrict__ spikes_out) {
+__global__ __launch_bounds__(kBlock) void k_step_win(long long n, const float* __restrict__ i_ext,
+                                                     unsigned char* __restrict__ spikes_out, Dev d) {
   pin_args(d.win, d.V, d.row_ptr, d.nearcnt, d.tapeU, d.spk_count, d.spike_bits, d.tape_bits, d.synf, d.J,
            d.N, d.B, d.BN, d.W, d.wshift, d.d_max, d.R, d.words, d.dbits, d.dmask, d.alpha, d.theta,
            d.v_reset, d.ext_w, d.alpha_s, d.alpha_r, d.p_thresh, d.seed, n, i_ext, spikes_out);
@@ -961,9 +961,9 @@ __device__ __forceinline__ float near_gather(const Dev& d, const float* __restri
 // SYN: synaptic current states, as in k_step_win; 2 = double-exponential synapse: every gather
 // takes two adjoints, X for the weight and Y for the delay (see bwd_receiver)
 template <int SYN>
-__global__ __launch_bounds__(kBlock) void k_bwd_step_win(Dev d, long long n, long long T,
+__global__ __launch_bounds__(kBlock) void k_bwd_step_win(long long n, long long T,
                                                          const float* __restrict__ dL_dcount,
-                                                         const float* __restrict__ dL_dU) {
+                                                         const float* __restrict__ dL_dU, Dev d) {
   pin_args(d.gwin, d.tapeU, d.bwd_carry, d.bwd_carryJ, d.row_ptr, d.nearcnt, d.Gacc, d.synb, d.gsum,
            d.N, d.B, d.BN, d.W, d.wshift, d.d_max, d.R, d.dbits, d.dmask, d.surrogate, d.alpha, d.alpha_s,
            d.theta, d.v_reset, d.dt, d.tau, n, T, dL_dcount, dL_dU);
