@@ -467,3 +467,35 @@ def test_cfg4_shape_forward_backward(kind, cap):
     ref = _compare_backward(wl, KINDS[kind], cap, 300, 6, use_dU=False,
                             tape_spike_capacity=300 * 6 * 4096 // 4)
     assert ref.spikes.sum() > 3000
+
+
+@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 4)])
+def test_library_kernel_timing_counts_its_launches(kind, cap):
+    """adseq_profile / adseq_profile_read: per kernel class, the launches of a run and times that
+    are positive and add up to less than the run took; the results of the run are unchanged."""
+    import time
+    wl = synth.ragged_network(300, 200, 40, seed=8, rate_hz=250.0, t=100, b=2, w_mean=0.01, w_std=0.01)
+    T = 100
+    ref = oracle.Run(wl, KINDS[kind], cap, n_steps=T, batch=2)
+    sim = adseq.Adseq(wl, KINDS[kind], cap, batch=2, record_tape=True, max_steps=T)
+    sim.profile(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    sim.run(0, T)
+    g_w = torch.empty(wl.n_synapses, device=sim.dev)
+    g_d = torch.empty(wl.n_synapses, device=sim.dev)
+    sim.backward(torch.full((2 * wl.n_neurons,), 1e-3, device=sim.dev), None, g_w, g_d)
+    p = sim.profile_read()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    np.testing.assert_array_equal(sim.tape()["U"].cpu().numpy().view(np.uint32), ref.U.view(np.uint32))
+    assert p["lif"]["launches"] == T and p["bwd_neurons"]["launches"] == T
+    if kind == "ring":      # one expansion and one far gather per window boundary inside the run
+        assert p["fan_out"]["launches"] == (T - 1) // 16 and p["bwd_gather"]["launches"] == (T - 1) // 16
+    else:                   # one fan-out per step; a reverse gather for every step that has spikes
+        assert p["fan_out"]["launches"] == T and 0 < p["bwd_gather"]["launches"] <= T
+    total = sum(v["ms"] for v in p.values())
+    assert all(v["ms"] > 0 for v in p.values()) and total < wall_ms
+    again = sim.profile_read()                      # read and forgotten
+    assert all(v["launches"] == 0 for v in again.values())
+    sim.profile(False)
+    sim.close()
