@@ -2,10 +2,20 @@
 // launches, random 4-byte atomic adds (with and without return value, several footprints, one
 // address, one compute unit), random 4-byte stores and gathers.  Every index is reduced modulo the
 // array length; every loop has a fixed trip count.
+//
+// `chip_rates resident` measures instead what a kernel that stays resident over many time steps
+// would pay for synchronising its blocks: which XCD (compute die, one L2 each) every block of a
+// grid runs on, the hand-over of a word between two blocks on one XCD and on two (by kind of store
+// and load), grid barriers (one counter, one counter per XCD under a top word, a flag per block;
+// all blocks or the blocks of one XCD), whether data passed between blocks of one XCD arrives,
+// dependent-access latencies, and what one XCD alone streams and scatters.  Every wait is a
+// bounded spin: a wait that runs out sets an error word, and the blocks go on to the end.
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
+#include <vector>
 
 #define CK(x)                                                                       \
   do {                                                                              \
@@ -117,7 +127,10 @@ static int run(const char* name, int* arr, unsigned M, size_t n_ops, unsigned gr
   return 0;
 }
 
-int main() {
+#include "resident_rates.h"
+
+int main(int argc, char** argv) {
+  if (argc > 1 && strcmp(argv[1], "resident") == 0) return resident_main();
   hipEvent_t e0, e1;
   CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
   float ms = 0;

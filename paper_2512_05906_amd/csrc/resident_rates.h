@@ -1,0 +1,447 @@
+// `chip_rates resident`: what a kernel that stays resident over many time steps pays for
+// synchronising its blocks on this chip.  Included by chip_rates.hip.
+//
+// The chip has 8 XCDs with an L2 each.  Memory-scope bits of a vector access: none = wavefront
+// scope (may hit in the compute unit's own cache), sc0 = workgroup scope, sc1 = agent scope
+// (coherent over the whole chip), sc0 sc1 = system scope.  The accesses below are spelled out
+// with their bits so that each combination can be timed; atomic read-modify-writes carry no scope
+// bit below system scope and are the same instruction at every scope.
+//
+// Every wait is a bounded spin.  A wait that runs out sets Sync::err and the block stops
+// waiting for the rest of the kernel, so every block reaches the end whatever happens.
+
+constexpr int kResThreads = 1024;
+constexpr int kMaxSpins = 1 << 16;
+
+__device__ __forceinline__ unsigned xcc_id() { return __builtin_amdgcn_s_getreg((3 << 11) | 20) & 15u; }   // HW_REG_XCC_ID
+__device__ __forceinline__ unsigned hw_id() { return __builtin_amdgcn_s_getreg((31 << 11) | 4); }          // HW_REG_HW_ID
+
+// loads and stores by scope bits: 0 none, 1 sc0, 2 sc1, 3 sc0 sc1, 4 nt
+template <int F> __device__ __forceinline__ unsigned ld(const unsigned* p) {
+  unsigned v;
+  if (F == 0) asm volatile("global_load_dword %0, %1, off\n s_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
+  else if (F == 1) asm volatile("global_load_dword %0, %1, off sc0\n s_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
+  else if (F == 2) asm volatile("global_load_dword %0, %1, off sc1\n s_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
+  else if (F == 3) asm volatile("global_load_dword %0, %1, off sc0 sc1\n s_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
+  else asm volatile("global_load_dword %0, %1, off nt\n s_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
+  return v;
+}
+template <int F> __device__ __forceinline__ void st(unsigned* p, unsigned v) {
+  if (F == 0) asm volatile("global_store_dword %0, %1, off" ::"v"(p), "v"(v) : "memory");
+  else if (F == 1) asm volatile("global_store_dword %0, %1, off sc0" ::"v"(p), "v"(v) : "memory");
+  else if (F == 2) asm volatile("global_store_dword %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+  else if (F == 3) asm volatile("global_store_dword %0, %1, off sc0 sc1" ::"v"(p), "v"(v) : "memory");
+  else asm volatile("global_store_dword %0, %1, off nt" ::"v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+struct Sync {
+  unsigned top; unsigned pad0[31];
+  unsigned xc[8][32];        // one counter per XCD, a 128-byte line each
+  unsigned packed[256];      // one flag per block, side by side
+  unsigned err, ticket, mism, pad1[29];
+  unsigned box[2][32];       // the two words of the hand-over test
+  unsigned long long ticks[8];
+  unsigned where[512];       // XCD / hardware id of every block
+};
+
+// ---------------------------------------------------------------- where blocks run
+__global__ void k_where(Sync* s) {
+  if (threadIdx.x == 0) { s->where[2 * blockIdx.x] = xcc_id(); s->where[2 * blockIdx.x + 1] = hw_id(); }
+}
+
+// ---------------------------------------------------------------- hand-over of one word between two blocks
+template <int W, int R>
+__global__ void k_pingpong(Sync* s, int a_id, int b_id, int iters) {
+  if (threadIdx.x != 0) return;
+  const bool a = (int)blockIdx.x == a_id, b = (int)blockIdx.x == b_id;
+  if (!a && !b) return;
+  s->where[a ? 0 : 1] = xcc_id();
+  const unsigned long long t0 = wall_clock64();
+  for (int k = 1; k <= iters; ++k) {
+    if (a) st<W>(&s->box[0][0], (unsigned)k);
+    unsigned* mine = a ? &s->box[1][0] : &s->box[0][0];
+    int spins = 0;
+    while (ld<R>(mine) != (unsigned)k) {
+      if (++spins > kMaxSpins) { atomicOr(&s->err, 1u); return; }
+    }
+    if (b) st<W>(&s->box[1][0], (unsigned)k);
+  }
+  if (a) s->ticks[0] = wall_clock64() - t0;
+}
+
+// ---------------------------------------------------------------- grid barriers
+// KIND 0: one counter (atomic add, then poll it); 1: one counter per XCD, the last arrival of an
+// XCD adds to the top word, everybody polls the top word; 2: one flag per block (a store), the
+// first lanes of the block poll all flags side by side.  W / R: scope bits of the flag store and
+// of the polling load.  FENCE: agent-scope release before the arrival and acquire after the wait
+// (write back / invalidate: what passing ordinary data through the barrier would need).
+// only_xcc >= 0: only the blocks that run on that XCD take part (P of them); the others leave.
+template <int KIND, int W, int R, bool FENCE>
+__global__ __launch_bounds__(kResThreads) void k_barrier(Sync* s, int iters, int only_xcc, int P, int per_xcc, int nxcc) {
+  __shared__ int s_rank;
+  const unsigned x = xcc_id();
+  if (only_xcc >= 0 && (int)x != only_xcc) return;
+  if (threadIdx.x == 0) s_rank = (int)atomicAdd(&s->ticket, 1u);
+  __syncthreads();
+  const int rank = s_rank;
+  if (rank >= P) return;
+  bool dead = false;
+  const unsigned long long t0 = wall_clock64();
+  for (int k = 1; k <= iters; ++k) {
+    __syncthreads();
+    const int pollers = KIND == 2 ? ((P + 63) & ~63) : 64;
+    if ((int)threadIdx.x < pollers && !dead) {
+      if (FENCE) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+      if (KIND == 0) {
+        if (threadIdx.x == 0) {
+          atomicAdd(&s->top, 1u);
+          int spins = 0;
+          while ((int)(ld<R>(&s->top) - (unsigned)(k * P)) < 0)
+            if (++spins > kMaxSpins) { atomicOr(&s->err, 1u); dead = true; break; }
+        }
+      } else if (KIND == 1) {
+        if (threadIdx.x == 0) {
+          const unsigned old = atomicAdd(&s->xc[x & 7][0], 1u);
+          if (old + 1u == (unsigned)(k * per_xcc)) atomicAdd(&s->top, 1u);
+          int spins = 0;
+          while ((int)(ld<R>(&s->top) - (unsigned)(k * nxcc)) < 0)
+            if (++spins > kMaxSpins) { atomicOr(&s->err, 1u); dead = true; break; }
+        }
+      } else {
+        // every polling wavefront watches 64 flags, one per lane
+        if (threadIdx.x == 0) st<W>(&s->packed[rank], (unsigned)k);
+        const int f = (int)threadIdx.x < P ? (int)threadIdx.x : 0;
+        int spins = 0;
+        while (!__all((int)(ld<R>(&s->packed[f]) - (unsigned)k) >= 0))
+          if (++spins > kMaxSpins) { if ((threadIdx.x & 63) == 0) atomicOr(&s->err, 1u); dead = true; break; }
+      }
+      if (FENCE) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    }
+  }
+  __syncthreads();
+  if (rank == 0 && threadIdx.x == 0) s->ticks[0] = wall_clock64() - t0;
+}
+
+// ---------------------------------------------------------------- data through a barrier, one XCD
+// Block r writes cell t of block (r + 1 + k) mod P (DW 0: store of the expected value with scope
+// bits WF; DW 1: atomic add of the increment), waits for its own writes, passes a flag barrier,
+// reads its own cells with scope bits RF and compares.  Counts the cells that differ.
+template <int DW, int WF, int RF, int BW, int BR>
+__global__ __launch_bounds__(kResThreads) void k_pass_data(Sync* s, unsigned* cells, int iters, int only_xcc, int P) {
+  __shared__ int s_rank;
+  if ((int)xcc_id() != only_xcc) return;
+  if (threadIdx.x == 0) s_rank = (int)atomicAdd(&s->ticket, 1u);
+  __syncthreads();
+  const int rank = s_rank;
+  if (rank >= P) return;
+  bool dead = false;
+  unsigned mism = 0;
+  int phase = 0;
+  auto barrier = [&]() {
+    ++phase;
+    __syncthreads();
+    if (threadIdx.x < 64 && !dead) {
+      if (threadIdx.x == 0) st<BW>(&s->packed[rank], (unsigned)phase);
+      int spins = 0;
+      for (;;) {
+        bool ok = true;
+        for (int f = threadIdx.x; f < P; f += 64) ok = ok && (int)(ld<BR>(&s->packed[f]) - (unsigned)phase) >= 0;
+        if (__all(ok)) break;
+        if (++spins > kMaxSpins) { if (threadIdx.x == 0) atomicOr(&s->err, 1u); dead = true; break; }
+      }
+    }
+    __syncthreads();
+  };
+  const unsigned long long t0 = wall_clock64();
+  unsigned expect = 0;
+  for (int k = 1; k <= iters; ++k) {
+    const int dst = (rank + 1 + k) % P;
+    unsigned* c = &cells[(size_t)dst * kResThreads + threadIdx.x];
+    const unsigned inc = (unsigned)k * 2654435761u + threadIdx.x;
+    expect += inc;       // (the cell of thread t of every block receives the same increments)
+    if (DW == 0) st<WF>(c, expect); else atomicAdd(c, inc);
+    wait_vm();
+    barrier();
+    const unsigned got = ld<RF>(&cells[(size_t)rank * kResThreads + threadIdx.x]);
+    if (got != expect) ++mism;
+    barrier();
+  }
+  if (mism) atomicAdd(&s->mism, mism);
+  if (rank == 0 && threadIdx.x == 0) s->ticks[0] = wall_clock64() - t0;
+}
+
+// ---------------------------------------------------------------- dependent accesses (one lane)
+// arr holds a random cycle over its 128-byte lines (word 0 of a line = index of the next line's
+// word 0).  KIND 0..4: load with those scope bits; 5: atomic add of `zero` with return value;
+// 6: atomic add without return value, then wait for it (the next index comes from a hash).
+template <int KIND>
+__global__ void k_chase(unsigned* arr, unsigned lines, int warm, int timed, unsigned zero, Sync* s) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  unsigned idx = 0;
+  auto hop = [&](int i) {
+    if (KIND <= 4) idx = ld<(KIND <= 4 ? KIND : 0)>(&arr[idx]);
+    else if (KIND == 5) idx = atomicAdd(&arr[idx], zero);
+    else { atomicAdd(&arr[idx + 1], 1u); wait_vm(); idx = (hash32((unsigned)i * 2654435761u + 7u) % lines) * 32u; }
+  };
+  for (int i = 0; i < warm; ++i) hop(i);
+  const unsigned long long t0 = wall_clock64();
+  for (int i = 0; i < timed; ++i) hop(warm + i);
+  s->ticks[0] = wall_clock64() - t0;
+  s->ticks[1] = idx;
+}
+
+// ---------------------------------------------------------------- what one XCD streams and scatters
+// Every taking-part block reads its share of a row of n ints and writes as many (non-temporal),
+// iters times over rotating rows.
+__global__ __launch_bounds__(kResThreads) void k_xcd_stream(Sync* s, const int* __restrict__ src, float* __restrict__ dst, int n,
+                                                           int rows, int iters, int only_xcc, int P) {
+  __shared__ int s_rank;
+  if (only_xcc >= 0 && (int)xcc_id() != only_xcc) return;
+  if (threadIdx.x == 0) s_rank = (int)atomicAdd(&s->ticket, 1u);
+  __syncthreads();
+  const int rank = s_rank;
+  if (rank >= P) return;
+  const int per = (n + P - 1) / P;
+  const int lo = rank * per, hi = lo + per < n ? lo + per : n;
+  const unsigned long long t0 = wall_clock64();
+  for (int k = 0; k < iters; ++k) {
+    const int* a = src + (size_t)((k * 7) % rows) * n;
+    float* b = dst + (size_t)(k % rows) * n;
+    for (int i = lo + threadIdx.x; i < hi; i += kResThreads)
+      __builtin_nontemporal_store((float)a[i] * 0x1p-24f, &b[i]);
+  }
+  __syncthreads();
+  if (rank == 0 && threadIdx.x == 0) s->ticks[0] = wall_clock64() - t0;
+}
+
+__global__ __launch_bounds__(kResThreads) void k_xcd_atomics(Sync* s, int* cells, unsigned M, int per, int only_xcc, int P) {
+  __shared__ int s_rank;
+  if (only_xcc >= 0 && (int)xcc_id() != only_xcc) return;
+  if (threadIdx.x == 0) s_rank = (int)atomicAdd(&s->ticket, 1u);
+  __syncthreads();
+  const int rank = s_rank;
+  if (rank >= P) return;
+  const unsigned long long t0 = wall_clock64();
+  for (int r = 0; r < per; ++r) {
+    const unsigned e = ((unsigned)r * P + rank) * kResThreads + threadIdx.x;
+    atomicAdd(&cells[hash32(e * 2654435761u + 12345u) % M], 1);
+  }
+  wait_vm();
+  __syncthreads();
+  if (rank == 0 && threadIdx.x == 0) s->ticks[0] = wall_clock64() - t0;
+}
+
+// ---------------------------------------------------------------- host
+static const char* kBits[] = {"none", "sc0", "sc1", "sc0 sc1", "nt"};
+
+struct ResCtx {
+  Sync* s;
+  Sync h;
+  hipEvent_t e0, e1;
+};
+
+static int res_reset(ResCtx& c) { CK(hipMemset(c.s, 0, sizeof(Sync))); return 0; }
+static int res_read(ResCtx& c) { CK(hipMemcpy(&c.h, c.s, sizeof(Sync), hipMemcpyDeviceToHost)); return 0; }
+
+template <int W, int R>
+static int res_pingpong(ResCtx& c, int a, int b, const char* what) {
+  const int iters = 2000;
+  if (res_reset(c)) return 1;
+  k_pingpong<W, R><<<16, 64>>>(c.s, a, b, iters);
+  CK(hipDeviceSynchronize());
+  if (res_read(c)) return 1;
+  if (c.h.err) printf("  %-12s store %-8s load %-8s : does not arrive (wait ran out)\n", what, kBits[W], kBits[R]);
+  else printf("  %-12s store %-8s load %-8s : %7.0f ns per hand-over (XCD %u -> XCD %u)\n", what, kBits[W], kBits[R],
+              (double)c.h.ticks[0] * 10.0 / (2.0 * iters), c.h.where[0], c.h.where[1]);
+  return 0;
+}
+
+template <int KIND, int W, int R, bool FENCE>
+static int res_barrier(ResCtx& c, int grid, int only_xcc, int P, const char* what) {
+  const int iters = 2000;
+  float ms = 0;
+  if (res_reset(c)) return 1;
+  CK(hipEventRecord(c.e0));
+  k_barrier<KIND, W, R, FENCE><<<grid, kResThreads>>>(c.s, iters, only_xcc, P, P / 8, 8);
+  CK(hipEventRecord(c.e1)); CK(hipEventSynchronize(c.e1)); CK(hipEventElapsedTime(&ms, c.e0, c.e1));
+  if (res_read(c)) return 1;
+  if (c.h.err) printf("  %-58s: a wait ran out\n", what);
+  else printf("  %-58s: %6.2f us per barrier (kernel %.2f ms)\n", what, (double)c.h.ticks[0] * 0.01 / iters, ms);
+  return 0;
+}
+
+template <int DW, int WF, int RF, int BW, int BR>
+static int res_pass(ResCtx& c, unsigned* cells, int P, const char* what) {
+  const int iters = 1000;
+  if (res_reset(c)) return 1;
+  CK(hipMemset(cells, 0, (size_t)P * kResThreads * 4));
+  k_pass_data<DW, WF, RF, BW, BR><<<256, kResThreads>>>(c.s, cells, iters, 0, P);
+  CK(hipDeviceSynchronize());
+  if (res_read(c)) return 1;
+  if (c.h.err) printf("  %-64s: a wait ran out\n", what);
+  else printf("  %-64s: %8u of %d cells differ, %6.2f us per round (write, barrier, read, barrier)\n", what, c.h.mism,
+              iters * P * kResThreads, (double)c.h.ticks[0] * 0.01 / iters);
+  return 0;
+}
+
+template <int KIND>
+static int res_chase(ResCtx& c, unsigned* arr, unsigned lines, int warm, int timed, const char* what) {
+  if (res_reset(c)) return 1;
+  k_chase<KIND><<<1, 64>>>(arr, lines, warm, timed, 0u, c.s);
+  CK(hipDeviceSynchronize());
+  if (res_read(c)) return 1;
+  printf("  %-60s: %7.0f ns per access\n", what, (double)c.h.ticks[0] * 10.0 / timed);
+  return 0;
+}
+
+static int make_cycle(unsigned* d_arr, unsigned lines) {
+  std::vector<unsigned> perm(lines), h((size_t)lines * 32, 0u);
+  for (unsigned i = 0; i < lines; ++i) perm[i] = i;
+  unsigned long long z = 88172645463325252ull;
+  for (unsigned i = lines - 1; i > 0; --i) {
+    z ^= z << 13; z ^= z >> 7; z ^= z << 17;
+    const unsigned j = (unsigned)(z % (i + 1));
+    const unsigned t = perm[i]; perm[i] = perm[j]; perm[j] = t;
+  }
+  for (unsigned i = 0; i < lines; ++i) h[(size_t)perm[i] * 32] = perm[(i + 1) % lines] * 32u;
+  CK(hipMemcpy(d_arr, h.data(), (size_t)lines * 128, hipMemcpyHostToDevice));
+  return 0;
+}
+
+static int resident_main() {
+  ResCtx c;
+  CK(hipMalloc(&c.s, sizeof(Sync)));
+  CK(hipEventCreate(&c.e0)); CK(hipEventCreate(&c.e1));
+
+  printf("where the blocks of a 256 x 1024-thread grid run (XCD of block b, by b mod 8):\n");
+  if (res_reset(c)) return 1;
+  k_where<<<256, kResThreads>>>(c.s);
+  CK(hipDeviceSynchronize());
+  if (res_read(c)) return 1;
+  {
+    int tab[8][8] = {};
+    for (int b = 0; b < 256; ++b) tab[b & 7][c.h.where[2 * b] & 7] += 1;
+    bool rr = true;
+    for (int r = 0; r < 8; ++r)
+      for (int x = 0; x < 8; ++x) if ((x == r) != (tab[r][x] == 32)) rr = false;
+    for (int r = 0; r < 8; ++r) {
+      printf("  b mod 8 = %d:", r);
+      for (int x = 0; x < 8; ++x) printf(" %3d", tab[r][x]);
+      printf("\n");
+    }
+    printf("  block b runs on XCD b mod 8: %s\n", rr ? "yes" : "NO");
+  }
+
+  printf("hand-over of one word between two single-wavefront blocks (store by one, polling load by the other):\n");
+  // same XCD: blocks 0 and 8; two XCDs: blocks 0 and 1
+  if (res_pingpong<0, 0>(c, 0, 8, "one XCD")) return 1;
+  if (res_pingpong<0, 1>(c, 0, 8, "one XCD")) return 1;
+  if (res_pingpong<1, 1>(c, 0, 8, "one XCD")) return 1;
+  if (res_pingpong<0, 2>(c, 0, 8, "one XCD")) return 1;
+  if (res_pingpong<2, 2>(c, 0, 8, "one XCD")) return 1;
+  if (res_pingpong<3, 3>(c, 0, 8, "one XCD")) return 1;
+  if (res_pingpong<0, 4>(c, 0, 8, "one XCD")) return 1;
+  if (res_pingpong<1, 1>(c, 0, 1, "two XCDs")) return 1;
+  if (res_pingpong<2, 2>(c, 0, 1, "two XCDs")) return 1;
+  if (res_pingpong<0, 2>(c, 0, 1, "two XCDs")) return 1;
+  if (res_pingpong<3, 3>(c, 0, 1, "two XCDs")) return 1;
+
+  printf("grid barriers, 1024-thread blocks, 2000 in a row (time inside the kernel, per barrier):\n");
+  if (res_barrier<0, 2, 2, false>(c, 64, -1, 64, "64 blocks, one counter, poll sc1")) return 1;
+  if (res_barrier<0, 2, 2, false>(c, 128, -1, 128, "128 blocks, one counter, poll sc1")) return 1;
+  if (res_barrier<0, 2, 2, false>(c, 256, -1, 256, "256 blocks, one counter, poll sc1")) return 1;
+  if (res_barrier<0, 2, 2, true>(c, 256, -1, 256, "256 blocks, one counter, poll sc1, release/acquire fences")) return 1;
+  if (res_barrier<1, 2, 2, false>(c, 64, -1, 64, "64 blocks, counter per XCD + top word, poll sc1")) return 1;
+  if (res_barrier<1, 2, 2, false>(c, 256, -1, 256, "256 blocks, counter per XCD + top word, poll sc1")) return 1;
+  if (res_barrier<1, 2, 2, true>(c, 256, -1, 256, "256 blocks, counter per XCD + top word, poll sc1, fences")) return 1;
+  if (res_barrier<2, 2, 2, false>(c, 64, -1, 64, "64 blocks, flag per block, sc1 store / sc1 load")) return 1;
+  if (res_barrier<2, 2, 2, false>(c, 256, -1, 256, "256 blocks, flag per block, sc1 store / sc1 load")) return 1;
+  if (res_barrier<2, 2, 2, true>(c, 256, -1, 256, "256 blocks, flag per block, sc1 / sc1, fences")) return 1;
+  if (res_barrier<0, 2, 2, false>(c, 256, 0, 32, "32 blocks of ONE XCD, one counter, poll sc1")) return 1;
+  if (res_barrier<2, 2, 2, false>(c, 256, 0, 32, "32 blocks of ONE XCD, flag per block, sc1 / sc1")) return 1;
+  if (res_barrier<2, 1, 1, false>(c, 256, 0, 32, "32 blocks of ONE XCD, flag per block, sc0 / sc0")) return 1;
+  if (res_barrier<2, 0, 1, false>(c, 256, 0, 32, "32 blocks of ONE XCD, flag per block, none / sc0")) return 1;
+  if (res_barrier<2, 0, 0, false>(c, 256, 0, 32, "32 blocks of ONE XCD, flag per block, none / none")) return 1;
+  if (res_barrier<2, 1, 1, false>(c, 128, 0, 16, "16 blocks of ONE XCD, flag per block, sc0 / sc0")) return 1;
+
+  printf("data through a flag barrier, 32 blocks of ONE XCD, 1024 cells each (1000 rounds):\n");
+  {
+    unsigned* cells = nullptr;
+    CK(hipMalloc(&cells, 32 * kResThreads * 4));
+    if (res_pass<0, 0, 0, 1, 1>(c, cells, 32, "store none, read none, barrier sc0/sc0")) return 1;
+    if (res_pass<0, 0, 1, 1, 1>(c, cells, 32, "store none, read sc0, barrier sc0/sc0")) return 1;
+    if (res_pass<0, 1, 1, 1, 1>(c, cells, 32, "store sc0, read sc0, barrier sc0/sc0")) return 1;
+    if (res_pass<0, 0, 4, 1, 1>(c, cells, 32, "store none, read nt, barrier sc0/sc0")) return 1;
+    if (res_pass<0, 2, 2, 2, 2>(c, cells, 32, "store sc1, read sc1, barrier sc1/sc1")) return 1;
+    if (res_pass<1, 0, 0, 1, 1>(c, cells, 32, "atomic add, read none, barrier sc0/sc0")) return 1;
+    if (res_pass<1, 0, 1, 1, 1>(c, cells, 32, "atomic add, read sc0, barrier sc0/sc0")) return 1;
+    if (res_pass<1, 0, 2, 1, 1>(c, cells, 32, "atomic add, read sc1, barrier sc0/sc0")) return 1;
+    if (res_pass<1, 0, 2, 2, 2>(c, cells, 32, "atomic add, read sc1, barrier sc1/sc1")) return 1;
+    CK(hipFree(cells));
+  }
+
+  printf("dependent accesses of one lane (a random cycle over 128-byte lines):\n");
+  {
+    unsigned* arr = nullptr;
+    const unsigned big = 1u << 23;   // 1 GiB of lines
+    CK(hipMalloc(&arr, (size_t)big * 128));
+    if (make_cycle(arr, 8192)) return 1;
+    if (res_chase<0>(c, arr, 8192, 8192, 8192, "1 MB, load, second pass")) return 1;
+    if (res_chase<1>(c, arr, 8192, 8192, 8192, "1 MB, load sc0, second pass")) return 1;
+    if (res_chase<2>(c, arr, 8192, 8192, 8192, "1 MB, load sc1, second pass")) return 1;
+    if (res_chase<3>(c, arr, 8192, 8192, 8192, "1 MB, load sc0 sc1, second pass")) return 1;
+    if (res_chase<5>(c, arr, 8192, 8192, 8192, "1 MB, atomic add with return value, second pass")) return 1;
+    if (res_chase<6>(c, arr, 8192, 8192, 8192, "1 MB, atomic add without return value + wait")) return 1;
+    if (make_cycle(arr, 1u << 19)) return 1;
+    if (res_chase<0>(c, arr, 1u << 19, 1 << 19, 8192, "64 MB, load, lines touched 64 MB ago")) return 1;
+    if (res_chase<2>(c, arr, 1u << 19, 1 << 19, 8192, "64 MB, load sc1, lines touched 64 MB ago")) return 1;
+    if (res_chase<5>(c, arr, 1u << 19, 1 << 19, 8192, "64 MB, atomic add with return value, touched 64 MB ago")) return 1;
+    if (make_cycle(arr, big)) return 1;
+    if (res_chase<0>(c, arr, big, 0, 8192, "1 GB, load, first touch")) return 1;
+    if (res_chase<2>(c, arr, big, 0, 8192, "1 GB, load sc1, first touch")) return 1;
+    if (res_chase<5>(c, arr, big, 0, 8192, "1 GB, atomic add with return value, first touch")) return 1;
+    CK(hipFree(arr));
+  }
+
+  printf("streaming by the blocks of ONE XCD and of all (row of 100,000 ints read, as many floats written, 2000 rows):\n");
+  {
+    const int n = 100000, rows = 256, iters = 2000;
+    int* src = nullptr; float* dst = nullptr;
+    CK(hipMalloc(&src, (size_t)n * rows * 4)); CK(hipMalloc(&dst, (size_t)n * rows * 4));
+    CK(hipMemset(src, 0, (size_t)n * rows * 4));
+    const int cfgs[][3] = {{256, 0, 32}, {512, 0, 64}, {256, -1, 256}, {512, -1, 512}};
+    for (auto& g : cfgs) {
+      if (res_reset(c)) return 1;
+      k_xcd_stream<<<g[0], kResThreads>>>(c.s, src, dst, n, rows, iters, g[1], g[2]);
+      CK(hipDeviceSynchronize());
+      if (res_read(c)) return 1;
+      const double us = (double)c.h.ticks[0] * 0.01 / iters;
+      printf("  %3d blocks %-12s: %6.2f us per row, %6.0f GB/s\n", g[2], g[1] >= 0 ? "of one XCD" : "(all XCDs)", us,
+             8.0 * n / us / 1e3);
+    }
+    CK(hipFree(src)); CK(hipFree(dst));
+  }
+
+  printf("random atomic adds by the blocks of ONE XCD and of all (64 per thread):\n");
+  {
+    const unsigned Ms[] = {200000u, 1600000u};
+    for (unsigned M : Ms) {
+      int* cells = nullptr;
+      CK(hipMalloc(&cells, (size_t)M * 4)); CK(hipMemset(cells, 0, (size_t)M * 4));
+      const int cfgs[][3] = {{256, 0, 32}, {256, -1, 256}};
+      for (auto& g : cfgs) {
+        if (res_reset(c)) return 1;
+        k_xcd_atomics<<<g[0], kResThreads>>>(c.s, cells, M, 64, g[1], g[2]);
+        CK(hipDeviceSynchronize());
+        if (res_read(c)) return 1;
+        const double us = (double)c.h.ticks[0] * 0.01;
+        printf("  %.1f MB of cells, %3d blocks %-12s: %8.1f us, %6.2f G adds/s\n", M * 4 / 1e6, g[2],
+               g[1] >= 0 ? "of one XCD" : "(all XCDs)", us, 64.0 * g[2] * kResThreads / us / 1e3);
+      }
+      CK(hipFree(cells));
+    }
+  }
+  CK(hipFree(c.s));
+  return 0;
+}
