@@ -107,8 +107,9 @@ enum {
   ADSEQ_E_NO_TAPE = -5,     /* backward without a complete recorded forward run                 */
   ADSEQ_E_HIP = -6,         /* a HIP call failed; adseq_last_error has the text                 */
   ADSEQ_E_CAPACITY = -7,    /* tape (steps, spikes, events) or per-step contender pool overflow */
-  ADSEQ_E_GRAPH = -8        /* CSR malformed: row_ptr not monotone from 0 to n_synapses, or a
+  ADSEQ_E_GRAPH = -8,       /* CSR malformed: row_ptr not monotone from 0 to n_synapses, or a
                                column index outside [0, n_neurons)                             */
+  ADSEQ_E_HOST_MEMORY = -9  /* the host-side handle could not be allocated                     */
 };
 
 typedef struct {
@@ -165,6 +166,19 @@ size_t adseq_workspace_bytes(const adseq_config *cfg);
  * packed internal form, validates delays and the CSR on the device, clears all state, and
  * synchronises that stream once.  *out is written only on success. */
 int adseq_create(const adseq_config *cfg, adseq_t **out);
+
+/* For callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  The same as adseq_create, except that the state lives in a workspace
+ * of ADSEQ_STATIC_WORKSPACE_BYTES that is part of the library's device image (every GPU the
+ * library runs on holds its own copy until the process ends) and the handle in static host
+ * storage: no device or host allocation, no allocating library call.  cfg->workspace and
+ * cfg->workspace_bytes are ignored.  The device current at the call is the one used.  Returns
+ * ADSEQ_E_WORKSPACE if adseq_workspace_bytes(cfg) exceeds the limit, or if the device's static
+ * workspace already holds a live handle (one at a time per device: two would share the memory
+ * and race); adseq_destroy releases it.  The workspace keeps the last handle's contents;
+ * everything a new handle needs to start from zero is cleared here. */
+#define ADSEQ_STATIC_WORKSPACE_BYTES (32u << 20)
+int adseq_create_static(const adseq_config *cfg, adseq_t **out);
 
 /* Frees the host-side handle.  The workspace stays the caller's. */
 int adseq_destroy(adseq_t *h);

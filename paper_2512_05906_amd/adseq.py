@@ -20,9 +20,10 @@ RING, FIFO, SORTED, SYN_FIFO, SYN_LATEST, SYN_BINS = 0, 1, 2, 3, 4, 5
 SURR_SUPERSPIKE, SURR_OFF, GRAD_SPIKE_TIME = 0, 1, 2
 
 ERRORS = {0: "OK", -1: "INVALID_ARG", -2: "DELAY_RANGE", -3: "WORKSPACE", -4: "ORDER",
-          -5: "NO_TAPE", -6: "HIP", -7: "CAPACITY", -8: "GRAPH"}
+          -5: "NO_TAPE", -6: "HIP", -7: "CAPACITY", -8: "GRAPH", -9: "HOST_MEMORY"}
+STATIC_WORKSPACE_BYTES = 32 << 20
 
-EXPORTS = ["adseq_workspace_bytes", "adseq_create", "adseq_destroy", "adseq_reset", "adseq_deliver",
+EXPORTS = ["adseq_workspace_bytes", "adseq_create", "adseq_create_static", "adseq_destroy", "adseq_reset", "adseq_deliver",
            "adseq_enqueue", "adseq_run_open", "adseq_step", "adseq_run", "adseq_backward", "adseq_drop_count",
            "adseq_counters", "adseq_tape", "adseq_spike_counts", "adseq_profile", "adseq_profile_read", "adseq_last_error"]
 
@@ -70,6 +71,7 @@ def load():
         L.adseq_workspace_bytes.restype = C.c_size_t
         L.adseq_workspace_bytes.argtypes = [C.POINTER(Config)]
         L.adseq_create.argtypes = [C.POINTER(Config), C.POINTER(vp)]
+        L.adseq_create_static.argtypes = [C.POINTER(Config), C.POINTER(vp)]
         L.adseq_destroy.argtypes = [vp]
         L.adseq_reset.argtypes = [vp, vp]
         L.adseq_deliver.argtypes = [vp, i64, vp, vp]
@@ -94,6 +96,20 @@ def load():
     return _lib
 
 
+class _RawDeviceBytes:
+    """nbytes of device memory at a raw address, for torch.as_tensor (zero-copy view)."""
+
+    def __init__(self, ptr: int, nbytes: int):
+        self.__cuda_array_interface__ = {"shape": (nbytes,), "typestr": "|u1", "data": (ptr, False), "version": 2}
+
+
+def _copy_out(ptr: int, nbytes: int, dev) -> torch.Tensor:
+    """uint8 view of device memory that no tensor owns (the library's static workspace)."""
+    if nbytes == 0:
+        return torch.empty(0, dtype=torch.uint8, device=dev)
+    return torch.as_tensor(_RawDeviceBytes(ptr, nbytes), device=dev)
+
+
 def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
@@ -109,7 +125,7 @@ class Adseq:
                  record_tape: bool = False, max_steps: Optional[int] = None,
                  surrogate: int = SURR_SUPERSPIKE, tape_spike_capacity: int = 0,
                  tape_event_capacity: int = 0, step_event_capacity: int = 0,
-                 device: str = "cuda:0"):
+                 device: str = "cuda:0", static_workspace: bool = False):
         self.lib = load()
         self.dev = torch.device(device)
         self.N, self.B = wl.n_neurons, wl.batch if batch is None else batch
@@ -137,16 +153,21 @@ class Adseq:
         nbytes = self.lib.adseq_workspace_bytes(C.byref(cfg))
         if nbytes == 0:
             raise AdseqError(-1, "adseq_workspace_bytes rejected the configuration")
-        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.dev)
-        base = self.workspace.data_ptr()
-        cfg.workspace = (base + 255) & ~255
-        cfg.workspace_bytes = nbytes
+        self.workspace = None
+        if not static_workspace:
+            self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.dev)
+            base = self.workspace.data_ptr()
+            cfg.workspace = (base + 255) & ~255
+            cfg.workspace_bytes = nbytes
         with torch.cuda.device(self.dev):
             cfg.stream = _stream()
             h = C.c_void_p()
-            rc = self.lib.adseq_create(C.byref(cfg), C.byref(h))
+            if static_workspace:   # the library's own workspace: nothing is allocated
+                rc = self.lib.adseq_create_static(C.byref(cfg), C.byref(h))
+            else:
+                rc = self.lib.adseq_create(C.byref(cfg), C.byref(h))
         if rc != 0:
-            raise AdseqError(rc, "adseq_create")
+            raise AdseqError(rc, "adseq_create_static" if static_workspace else "adseq_create")
         self.h = h
         self.cfg = cfg
         self.workspace_bytes = nbytes
@@ -212,11 +233,12 @@ class Adseq:
         """Zero-copy torch views of the tape inside the workspace."""
         tv = TapeView()
         self._check(self.lib.adseq_tape(self.h, C.byref(tv)))
-        base = self.workspace.data_ptr()
         BN = self.B * self.N
 
         def view(ptr, nbytes, dtype):
-            off = ptr - base
+            if self.workspace is None:   # the library's static workspace is no torch tensor: copy out
+                return _copy_out(ptr, nbytes, self.dev).view(dtype)
+            off = ptr - self.workspace.data_ptr()
             return self.workspace[off:off + nbytes].view(dtype)
 
         T = int(tv.steps_recorded)

@@ -451,6 +451,7 @@ struct adseq {
   bool grp_open = false;      // RING: a group of consecutive step launches is being timed
   int grp_count = 0;
   size_t ev_used = 0;
+  bool in_static = false;     // the handle is the device's static one (adseq_create_static): never deleted
 };
 
 namespace {
@@ -903,6 +904,36 @@ void ring_backward_launch(adseq* h, hipStream_t st, long long T, float dscale, c
 
 }  // namespace
 
+// Workspace of adseq_create_static: one array per GPU the library runs on, held until the
+// process ends.  In host code the name stands for the symbol, not for device memory: its device
+// address is looked up once per device (static_workspace) and only that pointer is handed on.
+static __device__ __align__(256) unsigned char scratch[ADSEQ_STATIC_WORKSPACE_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];      // device address of `scratch` on every device, once looked up
+adseq g_static_handle[kMaxDevices];    // the one handle per device that lives in the static workspace
+bool g_static_busy[kMaxDevices];
+
+// Device address of this device's copy of `scratch` (nullptr, with *dev_out = -1, on failure).
+void* static_workspace(int* dev_out) {
+  int dev = -1;
+  *dev_out = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+    g_scratch_ptr[dev] = p;
+  }
+  *dev_out = dev;
+  return g_scratch_ptr[dev];
+}
+
+int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, adseq* storage, adseq_t** out);
+
+}  // namespace
+
 extern "C" {
 
 size_t adseq_workspace_bytes(const adseq_config* cfg) {
@@ -913,6 +944,30 @@ size_t adseq_workspace_bytes(const adseq_config* cfg) {
 
 int adseq_create(const adseq_config* cfg, adseq_t** out) {
   if (!cfg || !out) return ADSEQ_E_INVALID_ARG;
+  return create_in(cfg, cfg->workspace, cfg->workspace_bytes, nullptr, out);
+}
+
+int adseq_create_static(const adseq_config* cfg, adseq_t** out) {
+  if (!cfg || !out) return ADSEQ_E_INVALID_ARG;
+  Layout L;
+  if (!make_layout(cfg, &L)) return ADSEQ_E_INVALID_ARG;
+  if (L.total > (size_t)ADSEQ_STATIC_WORKSPACE_BYTES) return ADSEQ_E_WORKSPACE;   // does not fit the static workspace
+  int dev = -1;
+  void* ws = static_workspace(&dev);
+  if (!ws) return ADSEQ_E_HIP;
+  if (g_static_busy[dev]) return ADSEQ_E_WORKSPACE;   // this device's static workspace already holds a live handle
+  const int rc = create_in(cfg, ws, (size_t)ADSEQ_STATIC_WORKSPACE_BYTES, &g_static_handle[dev], out);
+  if (rc == ADSEQ_OK) g_static_busy[dev] = true;
+  return rc;
+}
+
+}  // extern "C"
+
+namespace {
+
+// Body of adseq_create / adseq_create_static: the handle lives in `storage` if given (nothing is
+// allocated then), else on the heap.
+int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, adseq* storage, adseq_t** out) {
   Layout L;
   if (!make_layout(cfg, &L)) return ADSEQ_E_INVALID_ARG;
   if (!cfg->row_ptr) return ADSEQ_E_INVALID_ARG;
@@ -922,16 +977,26 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
   } else if (cfg->delay_steps && cfg->delay_ms) {
     return ADSEQ_E_INVALID_ARG;
   }
-  if (!cfg->workspace || ((uintptr_t)cfg->workspace & 255) || cfg->workspace_bytes < L.total)
+  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < L.total)
     return ADSEQ_E_WORKSPACE;
-  adseq* h = new (std::nothrow) adseq();
-  if (!h) return ADSEQ_E_INVALID_ARG;
+  adseq* h = storage;
+  if (h) {
+    for (hipEvent_t e : h->evs) (void)hipEventDestroy(e);
+    *h = adseq();
+    h->in_static = true;
+  } else {
+    h = new (std::nothrow) adseq();
+    if (!h) return ADSEQ_E_HOST_MEMORY;
+  }
+  auto drop = [&]() { if (!storage) delete h; };
   h->cfg = *cfg;
+  h->cfg.workspace = workspace;
+  h->cfg.workspace_bytes = workspace_bytes;
   h->ws_bytes = L.total;
   h->err[0] = 0;
   Dev& d = h->dev;
   memset(&d, 0, sizeof(d));
-  char* ws = (char*)cfg->workspace;
+  char* ws = (char*)workspace;
   d.N = cfg->n_neurons; d.B = cfg->batch; d.BN = cfg->n_neurons * cfg->batch;
   d.n_magic = cfg->n_neurons == 1 ? 0xffffffffu : (unsigned)(0x100000000ull / (unsigned long long)cfg->n_neurons);
   d.R = L.R; d.C = cfg->capacity; d.kind = cfg->kind; d.dbits = L.dbits; d.d_max = cfg->d_max_steps;
@@ -1039,16 +1104,25 @@ int adseq_create(const adseq_config* cfg, adseq_t** out) {
       hipLaunchKernelGGL(k_row_sums, dim3(gr), dim3(kBlock), 0, st, d);
     }
   }
-  if (e != hipSuccess) { delete h; return ADSEQ_E_HIP; }
-  if (err & ERR_GRAPH) { delete h; return ADSEQ_E_GRAPH; }
-  if (err & ERR_DELAY) { delete h; return ADSEQ_E_DELAY_RANGE; }
+  if (e != hipSuccess) { drop(); return ADSEQ_E_HIP; }
+  if (err & ERR_GRAPH) { drop(); return ADSEQ_E_GRAPH; }
+  if (err & ERR_DELAY) { drop(); return ADSEQ_E_DELAY_RANGE; }
   *out = h;
   return ADSEQ_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
 int adseq_destroy(adseq_t* h) {
   if (!h) return ADSEQ_E_INVALID_ARG;
   for (hipEvent_t e : h->evs) (void)hipEventDestroy(e);
+  if (h->in_static) {
+    h->evs.clear();
+    g_static_busy[h - g_static_handle] = false;
+    return ADSEQ_OK;
+  }
   delete h;
   return ADSEQ_OK;
 }
