@@ -40,7 +40,8 @@ constexpr int kBlock = 256;
 constexpr int kFanoutBlocks = 1024;
 
 enum : unsigned {
-  ERR_DELAY = 1u, ERR_GRAPH = 2u, ERR_TAPE_SPIKES = 4u, ERR_TAPE_EVENTS = 8u, ERR_POOL = 16u
+  ERR_DELAY = 1u, ERR_GRAPH = 2u, ERR_TAPE_SPIKES = 4u, ERR_TAPE_EVENTS = 8u, ERR_POOL = 16u,
+  ERR_BARRIER = 32u   // a bounded wait of a resident kernel ran out
 };
 
 struct Counters {
@@ -51,6 +52,7 @@ struct Counters {
   int pool_n[2];
   unsigned long long in_flight[2];  // scratch of k_ring_in_flight: events, Q8.24 sum
   unsigned long long fold[3];       // scratch of k_count_spikes: spikes, events, Q8.24 sum
+  alignas(128) unsigned bar[32];    // bar[0]: arrivals at the barriers of the resident step kernels (a line of its own)
 };
 
 // Private event counters of one block of k_neurons / k_fanout (FIFO / SORTED) or of one virtual
@@ -331,6 +333,7 @@ __global__ __launch_bounds__(kBlock) void k_copy_i32(const int* __restrict__ src
 // ---------------------------------------------------------------- ring queue (windowed delay line)
 
 #include "ring_window.h"
+#include "ring_resident.h"
 
 // ---------------------------------------------------------------- backward (FIFO / SORTED)
 
@@ -451,6 +454,8 @@ struct adseq {
   bool grp_open = false;      // RING: a group of consecutive step launches is being timed
   int grp_count = 0;
   size_t ev_used = 0;
+  unsigned bar_base = 0;      // RING, resident kernels: value of the barrier counter after the launches so far
+  int res_P = 0, res_chunk = 0, res_npt = 0;   // RING: taking-part blocks, neurons per block, per thread (0: one launch per step)
   bool in_static = false;     // the handle is the device's static one (adseq_create_static): never deleted
 };
 
@@ -677,6 +682,7 @@ void fill_u32(hipStream_t st, void* p, unsigned v, size_t count) {
 void launch_reset(adseq* h, hipStream_t st) {
   const Dev& d = h->dev;
   h->fold_upto = 0;
+  h->bar_base = 0;   // (the counter itself is cleared with the other counters)
   const size_t BN = (size_t)d.BN;
   fill_u32(st, d.ctr, 0u, sizeof(Counters) / 4);
   fill_u32(st, d.V, 0u, BN);
@@ -858,6 +864,45 @@ int step_impl(adseq* h, long long step, const float* i_ext, unsigned char* spike
   h->next_step = step + 1;
   HIP_TRY(h, hipGetLastError());
   return ADSEQ_OK;
+}
+
+// RING: steps step0 .. step0 + n_steps - 1 with one resident launch per window (ring_resident.h).
+template <bool RECORD, int NPT>
+void launch_run_xcd(const Dev& d, hipStream_t st, int syn, long long n0, int cnt, unsigned bar_base, int P, int chunk) {
+  const dim3 grid((unsigned)(P * kResStride)), block(kResThreads);
+  if (syn == 0) hipLaunchKernelGGL((k_run_xcd<RECORD, 0, NPT>), grid, block, 0, st, n0, cnt, bar_base, P, chunk, d);
+  else if (syn == 1) hipLaunchKernelGGL((k_run_xcd<RECORD, 1, NPT>), grid, block, 0, st, n0, cnt, bar_base, P, chunk, d);
+  else hipLaunchKernelGGL((k_run_xcd<RECORD, 2, NPT>), grid, block, 0, st, n0, cnt, bar_base, P, chunk, d);
+}
+void ring_run_resident(adseq* h, hipStream_t st, long long step0, long long n_steps) {
+  const Dev& d = h->dev;
+  const int syn = d.alpha_r > 0.0f ? 2 : (d.alpha_s > 0.0f ? 1 : 0);
+  long long n = step0;
+  const long long end = step0 + n_steps;
+  while (n < end) {
+    ring_open_window(h, st, n);
+    open_group(h, st);
+    const long long in_win = (long long)d.W - (n & (long long)(d.W - 1));
+    int cnt = (int)(end - n < in_win ? end - n : in_win);
+    // a launch either records all its steps or none: it ends where the tape ends
+    const bool record = d.record && h->tape_ok && n < d.max_steps;
+    if (record && n + cnt > d.max_steps) cnt = (int)(d.max_steps - n);
+    if (d.record && n >= d.max_steps) h->tape_ok = false;
+    if (record) {
+      if (h->res_npt == 1) launch_run_xcd<true, 1>(d, st, syn, n, cnt, h->bar_base, h->res_P, h->res_chunk);
+      else if (h->res_npt == 4) launch_run_xcd<true, 4>(d, st, syn, n, cnt, h->bar_base, h->res_P, h->res_chunk);
+      else launch_run_xcd<true, 8>(d, st, syn, n, cnt, h->bar_base, h->res_P, h->res_chunk);
+    } else {
+      if (h->res_npt == 1) launch_run_xcd<false, 1>(d, st, syn, n, cnt, h->bar_base, h->res_P, h->res_chunk);
+      else if (h->res_npt == 4) launch_run_xcd<false, 4>(d, st, syn, n, cnt, h->bar_base, h->res_P, h->res_chunk);
+      else launch_run_xcd<false, 8>(d, st, syn, n, cnt, h->bar_base, h->res_P, h->res_chunk);
+    }
+    h->bar_base += (unsigned)(cnt - 1) * (unsigned)h->res_P;
+    h->grp_count += cnt;
+    h->enq_calls += cnt;
+    n += cnt;
+    h->next_step = n;
+  }
 }
 
 // RING: virtual blocks of one far gather over the spikes of steps [n_lo, n_hi): about four
@@ -1070,6 +1115,18 @@ int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, 
   d.bwd_ring = (float*)(ws + L.bwd_ring); d.bwd_carry = (float*)(ws + L.bwd_carry);
   d.bwd_G = (float*)(ws + L.bwd_G);
 
+  if (d.kind == ADSEQ_RING) {
+    // resident step kernels (ring_resident.h): up to 32 blocks of 1,024 threads, up to 8 neurons
+    // per thread; larger state arrays keep one launch per step, which uses the whole chip
+    const int resident = env_pow2("ADSEQ_RING_RESIDENT", 1, 0, 1);
+    long long chunk = ((long long)d.BN + kResBlocks - 1) / kResBlocks;
+    chunk = (chunk + 63) / 64 * 64;
+    if (resident && chunk <= 8 * kResThreads) {
+      h->res_chunk = (int)chunk;
+      h->res_P = (int)(((long long)d.BN + chunk - 1) / chunk);
+      h->res_npt = chunk <= kResThreads ? 1 : (chunk <= 4 * kResThreads ? 4 : 8);
+    }
+  }
   hipStream_t st = (hipStream_t)cfg->stream;
   launch_reset(h, st);
   ExpCoef ec;
@@ -1215,9 +1272,13 @@ int adseq_run(adseq_t* h, int64_t step0, int64_t n_steps, void* stream) {
   if (n_steps < 0) return fail(h, ADSEQ_E_INVALID_ARG, "adseq_run: negative step count");
   if (step0 != h->next_step)
     return fail(h, ADSEQ_E_ORDER, "adseq_run: got step %lld, expected %lld", (long long)step0, h->next_step);
-  for (int64_t n = 0; n < n_steps; ++n) {
-    const int rc = step_impl(h, step0 + n, nullptr, nullptr, (hipStream_t)stream);
-    if (rc != ADSEQ_OK) return rc;
+  if (h->dev.kind == ADSEQ_RING && h->res_P > 0) {
+    ring_run_resident(h, (hipStream_t)stream, step0, n_steps);
+  } else {
+    for (int64_t n = 0; n < n_steps; ++n) {
+      const int rc = step_impl(h, step0 + n, nullptr, nullptr, (hipStream_t)stream);
+      if (rc != ADSEQ_OK) return rc;
+    }
   }
   close_group(h, (hipStream_t)stream, 1);
   HIP_TRY(h, hipGetLastError());
@@ -1237,6 +1298,8 @@ int adseq_backward(adseq_t* h, const float* dL_dcount, const float* dL_dU, float
   unsigned err = 0;
   HIP_TRY(h, hipMemcpyAsync(&err, &d.ctr->err, sizeof(err), hipMemcpyDeviceToHost, st));
   HIP_TRY(h, hipStreamSynchronize(st));
+  if (err & ERR_BARRIER)
+    return fail(h, ADSEQ_E_HIP, "adseq_backward: a wait inside a resident kernel ran out (the blocks of a launch were not running together); the run is void, reset and run again");
   if (err & (ERR_TAPE_SPIKES | ERR_TAPE_EVENTS | ERR_POOL))
     return fail(h, ADSEQ_E_CAPACITY, "adseq_backward: tape or contender pool overflowed (bits %u)", err);
   const long long T = h->next_step;
@@ -1339,6 +1402,8 @@ int adseq_drop_count(adseq_t* h, uint64_t* dropped, uint64_t* enqueued, uint64_t
   if (dropped) *dropped = (uint64_t)c[1];
   if (enqueued) *enqueued = (uint64_t)c[0];
   if (delivered) *delivered = (uint64_t)c[2];
+  if (c[7] & ERR_BARRIER)
+    return fail(h, ADSEQ_E_HIP, "a wait inside a resident kernel ran out; the run is void");
   if (c[7] & (ERR_TAPE_SPIKES | ERR_TAPE_EVENTS | ERR_POOL))
     return fail(h, ADSEQ_E_CAPACITY, "tape or contender pool overflowed (bits %lld)", (long long)c[7]);
   return ADSEQ_OK;

@@ -1,0 +1,93 @@
+"""The ring's resident step kernels (adseq_run: all the steps of a window in one launch on the
+blocks of one XCD, ring_resident.h) against the CPU oracle, through the C ABI: membrane trace bit
+for bit, counters, spike counts; every register layout (1, 4, 8 neurons per thread), several
+window lengths, batches, the synaptic current states, runs cut into pieces and mixed with single
+steps, resets, and agreement with the one-launch-per-step path."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2512_05906_amd import adseq, synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_pieces(wl, T, B, pieces, **kw):
+    """Forward run through adseq_run / adseq_step in the given pieces (int = that many steps in one
+    adseq_run call, 's' = one adseq_step call); returns (sim, U, counters, counts)."""
+    sim = adseq.Adseq(wl, adseq.RING, 0, batch=B, record_tape=True, max_steps=T, **kw)
+    n = 0
+    for p in pieces:
+        if p == "s":
+            sim.step(n); n += 1
+        else:
+            sim.run(n, p); n += p
+    assert n == T
+    torch.cuda.synchronize()
+    U = sim.tape()["U"].cpu().numpy().copy()
+    counts = torch.empty(B * wl.n_neurons, dtype=torch.int32, device=sim.dev)
+    sim.spike_counts(counts)
+    return sim, U, sim.counters(), counts.cpu().numpy()
+
+
+def _check(wl, T, B, pieces, **kw):
+    ref = oracle.Run(wl, oracle.RING, 0, n_steps=T, batch=B, n_threads=8)
+    sim, U, c, counts = _run_pieces(wl, T, B, pieces, **kw)
+    np.testing.assert_array_equal(U.view(np.uint32), ref.U.view(np.uint32))
+    rc = ref.counters()
+    for key in ("enqueued", "dropped", "delivered", "sum_enqueued", "sum_dropped", "sum_delivered"):
+        assert c[key] == rc[key], key
+    assert c["error_bits"] == 0
+    np.testing.assert_array_equal(counts.reshape(B, -1), ref.spikes.sum(axis=0))
+    sim.close()
+    return ref
+
+
+@pytest.mark.parametrize("n,fan,b", [(100, 30, 1), (300, 200, 3), (2500, 60, 16), (40000, 20, 1), (9000, 30, 20)])
+def test_resident_forward_sizes(n, fan, b):
+    """1, 4 and 8 neurons per thread; one block to 32 blocks; one trial and many."""
+    wl = synth.ragged_network(n, fan, 40, seed=n + b, rate_hz=700.0, t=120, b=b, w_mean=0.6 / fan, w_std=0.4 / fan)
+    ref = _check(wl, 120, b, [120])
+    assert ref.spikes.sum() > 100
+
+
+@pytest.mark.parametrize("window", [2, 8, 16, 64])
+def test_resident_window_lengths_and_pieces(window, monkeypatch):
+    monkeypatch.setenv("ADSEQ_RING_WINDOW", str(window))
+    wl = synth.ragged_network(700, 300, 37, seed=5, rate_hz=300.0, t=150, b=2, w_mean=0.004, w_std=0.003)
+    ref = _check(wl, 150, 2, [1, 30, "s", "s", 7, 64, "s", 45])
+    assert ref.spikes.sum() > 300
+
+
+@pytest.mark.parametrize("tau_syn,tau_rise", [(5.0, 0.0), (5.0, 1.0)])
+def test_resident_synaptic_states(tau_syn, tau_rise):
+    wl = synth.ragged_network(400, 150, 30, seed=8, rate_hz=250.0, t=140, b=2, w_mean=0.004, w_std=0.003)
+    wl.tau_syn_ms, wl.tau_rise_ms = tau_syn, tau_rise
+    ref = _check(wl, 140, 2, [50, "s", 89])
+    assert ref.spikes.sum() > 100
+
+
+def test_resident_matches_step_launches(monkeypatch):
+    """The same run with the resident kernels switched off: identical trace and counters."""
+    wl = synth.ragged_network(5000, 80, 50, seed=12, rate_hz=200.0, t=100, b=4, w_mean=0.008, w_std=0.006)
+    sim, U1, c1, n1 = _run_pieces(wl, 100, 4, [100])
+    sim.close()
+    monkeypatch.setenv("ADSEQ_RING_RESIDENT", "0")
+    sim, U0, c0, n0 = _run_pieces(wl, 100, 4, [100])
+    sim.close()
+    np.testing.assert_array_equal(U1.view(np.uint32), U0.view(np.uint32))
+    assert c1 == c0 and c1["tape_spikes"] > 500
+    np.testing.assert_array_equal(n1, n0)
+
+
+def test_resident_reset_and_rerun():
+    wl = synth.ragged_network(1200, 100, 20, seed=3, rate_hz=200.0, t=90, b=2, w_mean=0.006, w_std=0.004)
+    sim, U1, c1, _ = _run_pieces(wl, 90, 2, [90])
+    sim.reset()
+    sim.run(0, 40); sim.run(40, 50)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(sim.tape()["U"].cpu().numpy().view(np.uint32), U1.view(np.uint32))
+    assert sim.counters() == c1
+    sim.close()
