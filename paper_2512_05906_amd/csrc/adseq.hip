@@ -53,6 +53,9 @@ struct Counters {
   unsigned long long in_flight[2];  // scratch of k_ring_in_flight: events, Q8.24 sum
   unsigned long long fold[3];       // scratch of k_count_spikes: spikes, events, Q8.24 sum
   alignas(128) unsigned bar[32];    // bar[0]: arrivals at the barriers of the resident step kernels (a line of its own)
+#ifdef ADSEQ_PHASE_CLOCK
+  unsigned long long phase[8];      // debugging builds: 10 ns ticks block 0 spent in each phase of the resident steps
+#endif
 };
 
 // Private event counters of one block of k_neurons / k_fanout (FIFO / SORTED) or of one virtual
@@ -81,6 +84,9 @@ struct Dev {
   // what the ring's step kernels read, side by side: a launch fetches a few lines of its argument
   // block instead of a dozen
   int W, wshift;        // window length in steps (power of two) and its log2
+#if defined(ADSEQ_PHASE_CLOCK) || defined(ADSEQ_ABLATE)
+  int dbg;              // debugging builds: parts of the resident step to leave out (timing only)
+#endif
   int nblk;      // neuron blocks of a step launch: ceil(BN / 256)
   int words;     // 64-neuron words per step in spike_bits (RING) = 4 * nblk
   int* win;             // [W][BN]
@@ -92,6 +98,7 @@ struct Dev {
   unsigned long long* spike_bits;  // RING: [R][words] spikes of the last R steps
   unsigned long long* tape_bits;  // [T][words]
   uint2* synf;          // [S] sorted rows: {col << dbits | D, Q8.24 amplitude}
+  unsigned long long* drive_words;  // RING, resident kernels: drive bits of a stretch of steps, 16 per (step, block, thread)
   float* J;             // [BN] synaptic current state (alpha_s > 0); [2][BN] with the fast state behind it (alpha_r > 0)
   unsigned long long p_thresh, seed;
   float* gwin;          // [W][BN]
@@ -454,6 +461,7 @@ struct adseq {
   bool grp_open = false;      // RING: a group of consecutive step launches is being timed
   int grp_count = 0;
   size_t ev_used = 0;
+  long long drive_from = 0, drive_upto = 0;   // RING, resident kernels: steps whose drive words are in place
   unsigned bar_base = 0;      // RING, resident kernels: value of the barrier counter after the launches so far
   int res_P = 0, res_chunk = 0, res_npt = 0;   // RING: taking-part blocks, neurons per block, per thread (0: one launch per step)
   bool in_static = false;     // the handle is the device's static one (adseq_create_static): never deleted
@@ -462,7 +470,7 @@ struct adseq {
 namespace {
 
 struct Layout {
-  size_t V, J, bwd_carryJ, win, spike_bits, sq_next, sq_hs, sq_key, sq_flag, I_acc, last_evb, slot, fkey, famp, vmask, occ, head, min_k, cnt, cont, c_head, pool_p, pool_t, pool_next,
+  size_t V, J, bwd_carryJ, win, spike_bits, drive_words, sq_next, sq_hs, sq_key, sq_flag, I_acc, last_evb, slot, fkey, famp, vmask, occ, head, min_k, cnt, cont, c_head, pool_p, pool_t, pool_next,
       pool_k, pool_a, spk_words, stepcnt, packed, a_q, synf, synb, dstart, nearcnt, perm, rowsum, rowlen, ebuf, ecnt, amp, fdec, tapeU,
       tape_bits, spk_count, step_off, step_evoff, tape_spk, tape_evb, tape_row, tape_adm, bwd_ring, bwd_carry, bwd_G, gwin, Gacc, gsum, ctr, blk,
       total;
@@ -587,6 +595,7 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->J = take(c->tau_syn_ms > 0.0f ? nstates * BN * 4 : 0);
   L->win = take(bounded ? 0 : 2 * (size_t)L->W * BN * 4);
   L->spike_bits = take(bounded ? 0 : (size_t)L->R * L->words * 8);
+  L->drive_words = take(bounded ? 0 : (size_t)256 * 32 * 512 * 2);   // [kDriveSteps][kResBlocks][kResThreads] u16
   const bool fifo = c->kind == ADSEQ_FIFO;
   L->slot = take(c->kind == ADSEQ_SORTED ? (size_t)c->capacity * BN * 8 : 0);
   L->fkey = take(fifo ? (size_t)((c->capacity + 7) / 8 * 8) * BN * 2 : 0);
@@ -683,6 +692,7 @@ void launch_reset(adseq* h, hipStream_t st) {
   const Dev& d = h->dev;
   h->fold_upto = 0;
   h->bar_base = 0;   // (the counter itself is cleared with the other counters)
+  h->drive_from = h->drive_upto = 0;
   const size_t BN = (size_t)d.BN;
   fill_u32(st, d.ctr, 0u, sizeof(Counters) / 4);
   fill_u32(st, d.V, 0u, BN);
@@ -867,12 +877,14 @@ int step_impl(adseq* h, long long step, const float* i_ext, unsigned char* spike
 }
 
 // RING: steps step0 .. step0 + n_steps - 1 with one resident launch per window (ring_resident.h).
-template <bool RECORD, int NPT>
+template <bool RECORD, int NG>
 void launch_run_xcd(const Dev& d, hipStream_t st, int syn, long long n0, int cnt, unsigned bar_base, int P, int chunk) {
-  const dim3 grid((unsigned)(P * kResStride)), block(kResThreads);
-  if (syn == 0) hipLaunchKernelGGL((k_run_xcd<RECORD, 0, NPT>), grid, block, 0, st, n0, cnt, bar_base, P, chunk, d);
-  else if (syn == 1) hipLaunchKernelGGL((k_run_xcd<RECORD, 1, NPT>), grid, block, 0, st, n0, cnt, bar_base, P, chunk, d);
-  else hipLaunchKernelGGL((k_run_xcd<RECORD, 2, NPT>), grid, block, 0, st, n0, cnt, bar_base, P, chunk, d);
+  // block b runs on XCD b mod 8: with stride 8 the taking-part blocks share one XCD
+  static const int stride = env_pow2("ADSEQ_RING_RESIDENT_STRIDE", kResStride, 1, 8);
+  const dim3 grid((unsigned)(P * stride)), block(kResLaunch);
+  if (syn == 0) hipLaunchKernelGGL((k_run_xcd<RECORD, 0, NG>), grid, block, 0, st, n0, cnt, bar_base, P, chunk, stride, d);
+  else if (syn == 1) hipLaunchKernelGGL((k_run_xcd<RECORD, 1, NG>), grid, block, 0, st, n0, cnt, bar_base, P, chunk, stride, d);
+  else hipLaunchKernelGGL((k_run_xcd<RECORD, 2, NG>), grid, block, 0, st, n0, cnt, bar_base, P, chunk, stride, d);
 }
 void ring_run_resident(adseq* h, hipStream_t st, long long step0, long long n_steps) {
   const Dev& d = h->dev;
@@ -888,14 +900,21 @@ void ring_run_resident(adseq* h, hipStream_t st, long long step0, long long n_st
     const bool record = d.record && h->tape_ok && n < d.max_steps;
     if (record && n + cnt > d.max_steps) cnt = (int)(d.max_steps - n);
     if (d.record && n >= d.max_steps) h->tape_ok = false;
+    if (d.p_thresh && (n < h->drive_from || n + cnt > h->drive_upto)) {
+      // drive words for as much of this call as the buffer holds
+      const long long upto = end - n < kDriveSteps ? end : n + kDriveSteps;
+      const long long items = (upto - n) * h->res_P * kResThreads;
+      const long long blocks = (items + kBlock - 1) / kBlock;
+      hipLaunchKernelGGL(k_drive_words, dim3((unsigned)(blocks < 8192 ? blocks : 8192)), dim3(kBlock), 0, st, d, n, upto,
+                         h->res_P, h->res_chunk, h->res_npt);
+      h->drive_from = n; h->drive_upto = upto;
+    }
     if (record) {
       if (h->res_npt == 1) launch_run_xcd<true, 1>(d, st, syn, n, cnt, h->bar_base, h->res_P, h->res_chunk);
-      else if (h->res_npt == 4) launch_run_xcd<true, 4>(d, st, syn, n, cnt, h->bar_base, h->res_P, h->res_chunk);
-      else launch_run_xcd<true, 8>(d, st, syn, n, cnt, h->bar_base, h->res_P, h->res_chunk);
+      else launch_run_xcd<true, 2>(d, st, syn, n, cnt, h->bar_base, h->res_P, h->res_chunk);
     } else {
       if (h->res_npt == 1) launch_run_xcd<false, 1>(d, st, syn, n, cnt, h->bar_base, h->res_P, h->res_chunk);
-      else if (h->res_npt == 4) launch_run_xcd<false, 4>(d, st, syn, n, cnt, h->bar_base, h->res_P, h->res_chunk);
-      else launch_run_xcd<false, 8>(d, st, syn, n, cnt, h->bar_base, h->res_P, h->res_chunk);
+      else launch_run_xcd<false, 2>(d, st, syn, n, cnt, h->bar_base, h->res_P, h->res_chunk);
     }
     h->bar_base += (unsigned)(cnt - 1) * (unsigned)h->res_P;
     h->grp_count += cnt;
@@ -1074,6 +1093,10 @@ int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, 
   d.ctr = (Counters*)(ws + L.ctr);
   d.nblk = L.nblk; d.words = L.words; d.blk = (BlkCtr*)(ws + L.blk);
   d.V = (float*)(ws + L.V); d.spike_bits = (unsigned long long*)(ws + L.spike_bits);
+  d.drive_words = (unsigned long long*)(ws + L.drive_words);
+#if defined(ADSEQ_PHASE_CLOCK) || defined(ADSEQ_ABLATE)
+  d.dbg = getenv("ADSEQ_DBG") ? atoi(getenv("ADSEQ_DBG")) : 0;
+#endif
   d.W = L.W; d.wshift = L.wshift; d.tp_shift = L.tp_shift; d.P = L.P; d.NB = L.NB; d.cap = L.cap;
   d.wgroups = L.wgroups;
   d.win = (int*)(ws + L.win);
@@ -1116,15 +1139,20 @@ int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, 
   d.bwd_G = (float*)(ws + L.bwd_G);
 
   if (d.kind == ADSEQ_RING) {
-    // resident step kernels (ring_resident.h): up to 32 blocks of 1,024 threads, up to 8 neurons
-    // per thread; larger state arrays keep one launch per step, which uses the whole chip
-    const int resident = env_pow2("ADSEQ_RING_RESIDENT", 1, 0, 1);
+    // resident step kernels (ring_resident.h): up to 32 blocks of 512 threads, one or two groups
+    // of four neurons per thread, B N a multiple of 4 (16-byte aligned rows).  Measured on the
+    // configs: 2.1 against 4.7 us per step at 100 state cells, 3.6 against 4.7 at 16,000, 4.9 against
+    // 5.3 at 10,000 with a long history, 4.4 against 4.1 at 100,000 -- a launch per step uses all 256
+    // compute units for the spikes' row loads and atomic adds, the resident kernel 32 -- so by
+    // default they run up to 32,768 state cells.  ADSEQ_RING_RESIDENT = 0: never, 1: whenever
+    // the layout allows (up to 131,072 state cells).
+    const int resident = env_pow2("ADSEQ_RING_RESIDENT", 2, 0, 2);
     long long chunk = ((long long)d.BN + kResBlocks - 1) / kResBlocks;
-    chunk = (chunk + 63) / 64 * 64;
-    if (resident && chunk <= 8 * kResThreads) {
+    chunk = (chunk + 255) / 256 * 256;
+    if (resident && chunk <= 8 * kResThreads && d.BN % 4 == 0 && (resident == 1 || d.BN <= 32768)) {
       h->res_chunk = (int)chunk;
       h->res_P = (int)(((long long)d.BN + chunk - 1) / chunk);
-      h->res_npt = chunk <= kResThreads ? 1 : (chunk <= 4 * kResThreads ? 4 : 8);
+      h->res_npt = chunk <= 4 * kResThreads ? 1 : 2;   // groups of four neurons per thread
     }
   }
   hipStream_t st = (hipStream_t)cfg->stream;

@@ -76,12 +76,12 @@ __global__ void k_pingpong(Sync* s, int a_id, int b_id, int iters) {
 // first lanes of the block poll all flags side by side.  W / R: scope bits of the flag store and
 // of the polling load.  FENCE: agent-scope release before the arrival and acquire after the wait
 // (write back / invalidate: what passing ordinary data through the barrier would need).
-// only_xcc >= 0: only the blocks that run on that XCD take part (P of them); the others leave.
+// only_xcc >= 0: bit mask of the XCDs whose blocks take part (P blocks in all); the others leave.
 template <int KIND, int W, int R, bool FENCE>
 __global__ __launch_bounds__(kResThreads) void k_barrier(Sync* s, int iters, int only_xcc, int P, int per_xcc, int nxcc) {
   __shared__ int s_rank;
   const unsigned x = xcc_id();
-  if (only_xcc >= 0 && (int)x != only_xcc) return;
+  if (only_xcc >= 0 && !((only_xcc >> x) & 1)) return;   // only_xcc: bit mask of the XCDs that take part
   if (threadIdx.x == 0) s_rank = (int)atomicAdd(&s->ticket, 1u);
   __syncthreads();
   const int rank = s_rank;
@@ -192,25 +192,46 @@ __global__ void k_chase(unsigned* arr, unsigned lines, int warm, int timed, unsi
 }
 
 // ---------------------------------------------------------------- what one XCD streams and scatters
-// Every taking-part block reads its share of a row of n ints and writes as many (non-temporal),
-// iters times over rotating rows.
-__global__ __launch_bounds__(kResThreads) void k_xcd_stream(Sync* s, const int* __restrict__ src, float* __restrict__ dst, int n,
-                                                           int rows, int iters, int only_xcc, int P) {
+// Every taking-part block (those on the XCDs of the bit mask xmask) streams its share of rows of
+// n cells, iters times over rotating rows, four cells per thread in flight.  MODE 0: read a row of
+// ints, write a row of floats (non-temporal); 1: read only; 2: write only (non-temporal); 3: write
+// only (ordinary stores); 4: read a row, write TWO rows (one non-temporal, one ordinary).
+template <int MODE>
+__global__ __launch_bounds__(kResThreads) void k_xcd_stream(Sync* s, int* __restrict__ src, float* __restrict__ dst, int n,
+                                                           int rows, int iters, int xmask, int P) {
   __shared__ int s_rank;
-  if (only_xcc >= 0 && (int)xcc_id() != only_xcc) return;
+  if (!((xmask >> xcc_id()) & 1)) return;
   if (threadIdx.x == 0) s_rank = (int)atomicAdd(&s->ticket, 1u);
   __syncthreads();
   const int rank = s_rank;
   if (rank >= P) return;
-  const int per = (n + P - 1) / P;
+  const int per = ((n + P - 1) / P + 63) & ~63;
   const int lo = rank * per, hi = lo + per < n ? lo + per : n;
+  int sink = 0;
   const unsigned long long t0 = wall_clock64();
   for (int k = 0; k < iters; ++k) {
-    const int* a = src + (size_t)((k * 7) % rows) * n;
+    int* a = src + (size_t)((k * 7) % rows) * n;
     float* b = dst + (size_t)(k % rows) * n;
-    for (int i = lo + threadIdx.x; i < hi; i += kResThreads)
-      __builtin_nontemporal_store((float)a[i] * 0x1p-24f, &b[i]);
+    for (int i0 = lo + threadIdx.x; i0 < hi; i0 += 4 * kResThreads) {
+      int v[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int i = i0 + j * kResThreads;
+        v[j] = (MODE != 2 && MODE != 3 && i < hi) ? a[i] : k;
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int i = i0 + j * kResThreads;
+        if (i < hi) {
+          if (MODE == 0 || MODE == 2 || MODE == 4) __builtin_nontemporal_store((float)v[j] * 0x1p-24f, &b[i]);
+          if (MODE == 3) b[i] = (float)v[j];
+          if (MODE == 4) a[i] = 0;
+          if (MODE == 1) sink += v[j];
+        }
+      }
+    }
   }
+  if (sink == 0x7fffffff) dst[0] = 1.0f;
   __syncthreads();
   if (rank == 0 && threadIdx.x == 0) s->ticks[0] = wall_clock64() - t0;
 }
@@ -358,12 +379,19 @@ static int resident_main() {
   if (res_barrier<2, 2, 2, false>(c, 64, -1, 64, "64 blocks, flag per block, sc1 store / sc1 load")) return 1;
   if (res_barrier<2, 2, 2, false>(c, 256, -1, 256, "256 blocks, flag per block, sc1 store / sc1 load")) return 1;
   if (res_barrier<2, 2, 2, true>(c, 256, -1, 256, "256 blocks, flag per block, sc1 / sc1, fences")) return 1;
-  if (res_barrier<0, 2, 2, false>(c, 256, 0, 32, "32 blocks of ONE XCD, one counter, poll sc1")) return 1;
-  if (res_barrier<2, 2, 2, false>(c, 256, 0, 32, "32 blocks of ONE XCD, flag per block, sc1 / sc1")) return 1;
-  if (res_barrier<2, 1, 1, false>(c, 256, 0, 32, "32 blocks of ONE XCD, flag per block, sc0 / sc0")) return 1;
-  if (res_barrier<2, 0, 1, false>(c, 256, 0, 32, "32 blocks of ONE XCD, flag per block, none / sc0")) return 1;
-  if (res_barrier<2, 0, 0, false>(c, 256, 0, 32, "32 blocks of ONE XCD, flag per block, none / none")) return 1;
-  if (res_barrier<2, 1, 1, false>(c, 128, 0, 16, "16 blocks of ONE XCD, flag per block, sc0 / sc0")) return 1;
+  if (res_barrier<0, 2, 2, false>(c, 256, 1, 32, "32 blocks of ONE XCD, one counter, poll sc1")) return 1;
+  if (res_barrier<2, 2, 2, false>(c, 256, 1, 32, "32 blocks of ONE XCD, flag per block, sc1 / sc1")) return 1;
+  if (res_barrier<2, 1, 1, false>(c, 256, 1, 32, "32 blocks of ONE XCD, flag per block, sc0 / sc0")) return 1;
+  if (res_barrier<2, 0, 1, false>(c, 256, 1, 32, "32 blocks of ONE XCD, flag per block, none / sc0")) return 1;
+  if (res_barrier<2, 0, 0, false>(c, 256, 1, 32, "32 blocks of ONE XCD, flag per block, none / none")) return 1;
+  if (res_barrier<2, 1, 1, false>(c, 128, 1, 16, "16 blocks of ONE XCD, flag per block, sc0 / sc0")) return 1;
+  if (res_barrier<0, 2, 2, false>(c, 128, 1, 16, "16 blocks of ONE XCD, one counter, poll sc1")) return 1;
+  if (res_barrier<0, 2, 2, false>(c, 64, 1, 8, "8 blocks of ONE XCD, one counter, poll sc1")) return 1;
+  if (res_barrier<0, 2, 2, false>(c, 256, 3, 64, "64 blocks of TWO XCDs, one counter, poll sc1")) return 1;
+  if (res_barrier<2, 2, 2, false>(c, 256, 3, 64, "64 blocks of TWO XCDs, flag per block, sc1 / sc1")) return 1;
+  if (res_barrier<0, 2, 2, false>(c, 128, 3, 32, "32 blocks of TWO XCDs, one counter, poll sc1")) return 1;
+  if (res_barrier<0, 2, 2, false>(c, 256, 15, 128, "128 blocks of FOUR XCDs, one counter, poll sc1")) return 1;
+  if (res_barrier<0, 2, 2, false>(c, 128, 15, 64, "64 blocks of FOUR XCDs, one counter, poll sc1")) return 1;
 
   printf("data through a flag barrier, 32 blocks of ONE XCD, 1024 cells each (1000 rounds):\n");
   {
@@ -404,22 +432,30 @@ static int resident_main() {
     CK(hipFree(arr));
   }
 
-  printf("streaming by the blocks of ONE XCD and of all (row of 100,000 ints read, as many floats written, 2000 rows):\n");
+  printf("streaming by the blocks of one, two, four and all XCDs (rows of 100,000 4-byte cells, 2000 rows, four cells per thread in flight):\n");
   {
     const int n = 100000, rows = 256, iters = 2000;
     int* src = nullptr; float* dst = nullptr;
     CK(hipMalloc(&src, (size_t)n * rows * 4)); CK(hipMalloc(&dst, (size_t)n * rows * 4));
     CK(hipMemset(src, 0, (size_t)n * rows * 4));
-    const int cfgs[][3] = {{256, 0, 32}, {512, 0, 64}, {256, -1, 256}, {512, -1, 512}};
-    for (auto& g : cfgs) {
-      if (res_reset(c)) return 1;
-      k_xcd_stream<<<g[0], kResThreads>>>(c.s, src, dst, n, rows, iters, g[1], g[2]);
-      CK(hipDeviceSynchronize());
-      if (res_read(c)) return 1;
-      const double us = (double)c.h.ticks[0] * 0.01 / iters;
-      printf("  %3d blocks %-12s: %6.2f us per row, %6.0f GB/s\n", g[2], g[1] >= 0 ? "of one XCD" : "(all XCDs)", us,
-             8.0 * n / us / 1e3);
-    }
+    const int cfgs[][3] = {{256, 0x1, 32}, {512, 0x1, 64}, {256, 0x3, 64}, {256, 0xf, 128}, {256, 0xff, 256}};
+    const char* mode_name[] = {"read 4 B + write 4 B (nt)", "read 4 B", "write 4 B (nt)", "write 4 B", "read 4 B + write 4 B (nt) + write 4 B"};
+    const double bytes[] = {8.0, 4.0, 4.0, 4.0, 12.0};
+    for (int mode = 0; mode < 5; ++mode)
+      for (auto& g : cfgs) {
+        if (res_reset(c)) return 1;
+        if (mode == 0) k_xcd_stream<0><<<g[0], kResThreads>>>(c.s, src, dst, n, rows, iters, g[1], g[2]);
+        else if (mode == 1) k_xcd_stream<1><<<g[0], kResThreads>>>(c.s, src, dst, n, rows, iters, g[1], g[2]);
+        else if (mode == 2) k_xcd_stream<2><<<g[0], kResThreads>>>(c.s, src, dst, n, rows, iters, g[1], g[2]);
+        else if (mode == 3) k_xcd_stream<3><<<g[0], kResThreads>>>(c.s, src, dst, n, rows, iters, g[1], g[2]);
+        else k_xcd_stream<4><<<g[0], kResThreads>>>(c.s, src, dst, n, rows, iters, g[1], g[2]);
+        CK(hipDeviceSynchronize());
+        if (res_read(c)) return 1;
+        const double us = (double)c.h.ticks[0] * 0.01 / iters;
+        int nx = 0; for (int b = 0; b < 8; ++b) nx += (g[1] >> b) & 1;
+        printf("  %-40s %3d blocks on %d XCD(s): %6.2f us per row, %6.0f GB/s\n", mode_name[mode], g[2], nx, us,
+               bytes[mode] * n / us / 1e3);
+      }
     CK(hipFree(src)); CK(hipFree(dst));
   }
 

@@ -802,6 +802,23 @@ __global__ __launch_bounds__(kRingThreads) void k_win_bin(Dev d, long long k0, l
   __shared__ ExpandLds L;
   __shared__ SortLds S;
   role_bin(d, L, S, k0, n_lo, n_hi, vb0 + (int)blockIdx.x, nvb, stage, count_from);
+  // The other window buffer -- the one the steps before k0 have just used up -- is zeroed here, a
+  // slice per block, for the expansion that fills it next: the resident step kernels do not clear
+  // the cells they pop (their one XCD would spend a fifth of a step on those stores), and the
+  // per-step kernels, which do, lose nothing.
+  {
+    int* other = d.win + (size_t)((((k0 >> d.wshift) & 1) ^ 1)) * d.W * d.BN;
+    const size_t cells = (size_t)d.W * d.BN;
+    const size_t per = ((cells + nvb - 1) / nvb + 3) & ~(size_t)3;
+    const size_t lo = per * (size_t)(vb0 + (int)blockIdx.x);
+    const size_t hi = lo + per < cells ? lo + per : cells;
+    // (lo is a multiple of 4: whole 16-byte stores where the buffer is 16-byte aligned, then the tail)
+    const bool aligned = (reinterpret_cast<size_t>(other) & 15) == 0;   // (W = 2 with odd B N: the second buffer is not)
+    const size_t hi4 = aligned ? lo + ((hi > lo ? hi - lo : 0) & ~(size_t)3) : lo;
+    for (size_t x = lo + 4 * (size_t)threadIdx.x; x < hi4; x += 4 * (size_t)kRingThreads)
+      *reinterpret_cast<int4*>(other + x) = make_int4(0, 0, 0, 0);
+    for (size_t x = (hi4 < hi ? hi4 : hi) + threadIdx.x; x < hi; x += kRingThreads) other[x] = 0;
+  }
 }
 __global__ __launch_bounds__(kRingThreads) void k_win_acc(Dev d, long long k0, int p0) {
   __shared__ int tile[kMaxTileCells];

@@ -14,6 +14,12 @@ from tests import helpers as H
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True)
+def _resident_on(monkeypatch):
+    """By default the resident kernels run up to 32,768 state cells; here wherever the layout allows."""
+    monkeypatch.setenv("ADSEQ_RING_RESIDENT", "1")
+
+
 def _run_pieces(wl, T, B, pieces, **kw):
     """Forward run through adseq_run / adseq_step in the given pieces (int = that many steps in one
     adseq_run call, 's' = one adseq_step call); returns (sim, U, counters, counts)."""
@@ -45,9 +51,10 @@ def _check(wl, T, B, pieces, **kw):
     return ref
 
 
-@pytest.mark.parametrize("n,fan,b", [(100, 30, 1), (300, 200, 3), (2500, 60, 16), (40000, 20, 1), (9000, 30, 20)])
+@pytest.mark.parametrize("n,fan,b", [(100, 30, 1), (301, 200, 3), (2500, 60, 16), (40000, 20, 1), (5000, 30, 20), (9000, 30, 20)])
 def test_resident_forward_sizes(n, fan, b):
-    """1, 4 and 8 neurons per thread; one block to 32 blocks; one trial and many."""
+    """1, 2 and 4 groups of four neurons per thread; rows that are and are not 16-byte aligned; one block to
+    32 blocks; one trial and many; and a state array beyond the resident kernels (a launch per step)."""
     wl = synth.ragged_network(n, fan, 40, seed=n + b, rate_hz=700.0, t=120, b=b, w_mean=0.6 / fan, w_std=0.4 / fan)
     ref = _check(wl, 120, b, [120])
     assert ref.spikes.sum() > 100
