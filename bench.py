@@ -9,7 +9,8 @@ ring queue), synthetic and seeded.
 
 Prints ONE JSON line: metric "synaptic events delivered/s (fwd)" plus the
 forward+backward time per time step, the HBM roofline of the dominant kernel,
-the FIFO drop rate when a bounded queue is selected, and the CPU oracle timed
+the drop rate (of the selected queue, and of FIFO[32] on the same network in a
+short leg of its own when the default workload runs), and the CPU oracle timed
 on a bounded sample of the same workload.
 """
 import argparse
@@ -46,6 +47,7 @@ def main():
     ap.add_argument("--time-steps", type=int, default=0, help="override the workload's T")
     ap.add_argument("--drive-hz", type=float, default=0.0, help="override the rate of the Poisson drive")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-fifo-leg", action="store_true", help="skip the FIFO[32] comparison leg of the default workload")
     ap.add_argument("--cpu-sample-events", type=float, default=4e7)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -112,11 +114,15 @@ def main():
     spikes = c["tape_spikes"]
     mean_rate_hz = spikes / BN / (T * wl.dt_ms * 1e-3)
     value = delivered / (fwd_ms * 1e-3)
-    admitted = offered - dropped
-    fwd_bytes = FWD_B_EVENT[args.queue] * offered + FWD_B_NEURON * BN * T
+    # Events the passes actually handle.  The ring materialises an event only when the window that
+    # holds its arrival step opens, so its forward pass handles the events delivered inside the run
+    # (not the ones still implicit at its end); the bounded kinds read every offered row entry.  The
+    # reverse sweep of every kind gathers for the events delivered inside the run.
+    fwd_events = delivered if args.queue == "ring" else offered
+    fwd_bytes = FWD_B_EVENT[args.queue] * fwd_events + FWD_B_NEURON * BN * T
     if args.queue in ("syn", "latest", "bins"):
         fwd_bytes += SYN_B_QUEUE_STEP * B * wl.n_synapses * T
-    bwd_bytes = BWD_B_EVENT * admitted + BWD_B_NEURON * BN * T
+    bwd_bytes = BWD_B_EVENT * delivered + BWD_B_NEURON * BN * T
     achieved_run = (fwd_bytes + bwd_bytes) / ((fwd_ms + bwd_ms) * 1e-3) / 1e9
 
     # Per-kernel durations, measured live with HIP events on the launch stream in one extra
@@ -127,7 +133,7 @@ def main():
     sim.profile(False)
     in_run = delivered  # admitted events that arrive inside the run: the ones backward touches
     alg = {  # algorithmic bytes per run of each kernel class
-        "fan_out": (FWD_B_EVENT[args.queue]) * offered,
+        "fan_out": (FWD_B_EVENT[args.queue]) * fwd_events,
         "lif": FWD_B_NEURON * BN * T + (SYN_B_QUEUE_STEP * B * wl.n_synapses * T if args.queue in ("syn", "latest", "bins") else 0),
         "bwd_gather": BWD_B_EVENT * in_run,
         "bwd_neurons": BWD_B_NEURON * BN * T,
@@ -143,8 +149,8 @@ def main():
             D = np.bincount(np.maximum(1, np.ceil(wl.delay_ms.astype(np.float64) / wl.dt_ms)).astype(np.int64),
                             minlength=W + 1).astype(np.float64)
         near = float((D[:W] * (W - np.arange(W))).sum() / (W * D.sum()))
-        alg["lif"] += FWD_B_EVENT["ring"] * offered * near
-        alg["fan_out"] = FWD_B_EVENT["ring"] * offered * (1.0 - near)
+        alg["lif"] += FWD_B_EVENT["ring"] * fwd_events * near
+        alg["fan_out"] = FWD_B_EVENT["ring"] * fwd_events * (1.0 - near)
         alg["bwd_neurons"] += BWD_B_EVENT * in_run * near
         alg["bwd_gather"] = BWD_B_EVENT * in_run * (1.0 - near)
         label = {"fan_out": "k_win_bin + k_win_acc (expansion of one window: stage by target part, sum in LDS)",
@@ -165,11 +171,15 @@ def main():
                           "algorithmic_bytes_per_launch": alg[k] / v["launches"],
                           "achieved_GBs": alg[k] / (v["ms"] * 1e-3) / 1e9}
     dom = max(kernels, key=lambda k: kernels[k]["ms_per_run"])
+    # HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc runs (not
+    # measured in this run: counters need the profiler), with the commit they were taken at
     traffic = None
+    traffic_at = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         tj = json.load(open(tpath))
         traffic = tj.get(f"{args.workload}/{args.queue}", {}).get(dom)
+        traffic_at = tj.get("_taken_at")
 
     # what a plain device-to-device copy of 1 GiB reaches on this machine (read + write bytes per second):
     # the practical ceiling next to the datasheet peak
@@ -207,7 +217,7 @@ def main():
         "drop_rate": dropped / max(1, offered),
         "roofline": {"bound": "hbm", "achieved": kernels[dom]["achieved_GBs"], "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": kernels[dom]["achieved_GBs"] / HBM_PEAK_GBS,
-                     "traffic": traffic, "kernel": label[dom],
+                     "traffic": traffic, "traffic_taken_at_commit": traffic_at, "kernel": label[dom],
                      "avg_launch_us": kernels[dom]["avg_us"],
                      "algorithmic_bytes_per_launch": kernels[dom]["algorithmic_bytes_per_launch"],
                      "whole_run_achieved_GBs": achieved_run,
@@ -216,6 +226,40 @@ def main():
                      "frac_of_measured_copy": kernels[dom]["achieved_GBs"] / copy_gbs if copy_gbs else None},
         "kernels": kernels,
     }
+
+    # The comparison the headline config asks for (ring against FIFO[32], Section 6.5 "Spike drop
+    # rates"): a short leg with the bounded FIFO on the same network and drive.  The lost recurrent
+    # input lowers the firing rate, so its events per second are not comparable one to one; the
+    # drop rate is the figure.
+    if args.queue == "ring" and args.workload == "cfg3" and not args.no_fifo_leg:
+        fsim = adseq.Adseq(wl, adseq.FIFO, 32, record_tape=True, max_steps=T, tape_spike_capacity=spike_cap,
+                           tape_event_capacity=spike_cap * fan)
+        fev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+
+        def fifo_step(evs=None):
+            fsim.reset()
+            if evs:
+                evs[0].record()
+            fsim.run(0, T)
+            if evs:
+                evs[1].record()
+            fsim.spike_counts(counts_i)
+            dc = (2.0 / BN) * (counts_i.to(torch.float32) - y)
+            fsim.backward(dc, None, g_w, g_d)
+            if evs:
+                evs[2].record()
+
+        fifo_step()
+        fifo_step(fev)
+        torch.cuda.synchronize()
+        fc = fsim.counters()
+        assert fc["error_bits"] == 0, fc
+        f_fwd, f_bwd = fev[0].elapsed_time(fev[1]), fev[1].elapsed_time(fev[2])
+        out["fifo32"] = {"fwd_ms": f_fwd, "bwd_ms": f_bwd, "events_per_s": fc["delivered"] / (f_fwd * 1e-3),
+                         "drop_rate": fc["dropped"] / max(1, fc["enqueued"]),
+                         "mean_rate_hz": fc["tape_spikes"] / BN / (T * wl.dt_ms * 1e-3),
+                         "offered": fc["enqueued"], "dropped": fc["dropped"], "delivered": fc["delivered"]}
+        fsim.close()
 
     if not args.no_cpu_baseline:
         from oracle import oracle

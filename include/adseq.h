@@ -46,9 +46,9 @@
  *                 lossless ("Ring").
  *   ADSEQ_FIFO    per target, `capacity` unordered slots; an incoming event is
  *                 dropped (and counted) when the target already holds `capacity`
- *                 undelivered events ("FIFORing": drops the incoming spikes when
- *                 the queue is full); every stored event is delivered exactly at
- *                 its arrival step.
+ *                 undelivered events (the rule of the paper's "FIFORing": a full
+ *                 queue refuses what comes in); every stored event is delivered
+ *                 exactly at its arrival step.
  *   ADSEQ_SORTED  per target, `capacity` slots kept ordered by arrival step; pop
  *                 takes from the front ("SortedArray"); same admission rule.
  *   ADSEQ_SYN_FIFO one first-in-first-out queue of `capacity` (1..8) arrival times per
@@ -162,7 +162,9 @@ typedef struct {
 /* Bytes of device workspace `cfg` needs (pointer fields are not read). 0 if cfg is invalid. */
 size_t adseq_workspace_bytes(const adseq_config *cfg);
 
-/* Builds a handle: validates cfg (host), then on cfg->stream converts the synapses into the
+/* The queues' "init" (Section 4.2: every queue structure offers init, enqueue and pop; the kinds
+ * are those of Section 4.3), for the whole network at once.
+ * Builds a handle: validates cfg (host), then on cfg->stream converts the synapses into the
  * packed internal form, validates delays and the CSR on the device, clears all state, and
  * synchronises that stream once.  *out is written only on success. */
 int adseq_create(const adseq_config *cfg, adseq_t **out);
@@ -240,7 +242,13 @@ int adseq_backward(adseq_t *h, const float *dL_dcount, const float *dL_dU, float
                    float *grad_d, void *stream);
 
 /* Event counters since the last reset (host pointers, any may be NULL): events refused by a
- * full queue, events offered to the queues, events delivered.  Synchronises `stream`.
+ * full queue (Section 4.3 "FIFORing": a lossy queue drops what arrives while it is full; Section
+ * 6.5 "Spike drop rates" reports these losses), events offered to the queues, events delivered.
+ * ADSEQ_RING keeps no per-event counters: its `enqueued` is counted from the recorded spikes and
+ * their row lengths, and its `delivered` is derived from that as enqueued minus the events still in
+ * flight (rows of the spikes of the last d_max_steps steps whose arrival lies ahead); the Q8.24
+ * sum of what each step actually popped is counted separately, see adseq_counters.
+ * Synchronises `stream`.
  * Returns ADSEQ_E_CAPACITY if a tape or pool overflow happened since the last reset. */
 int adseq_drop_count(adseq_t *h, uint64_t *dropped, uint64_t *enqueued, uint64_t *delivered,
                      void *stream);
@@ -269,8 +277,9 @@ typedef struct {
 } adseq_tape_view;
 int adseq_tape(adseq_t *h, adseq_tape_view *out);
 
-/* Spike count of every (trial, neuron) over the steps recorded since the last reset (the input of
- * the spike-count loss of the paper's recurrent-network benchmark, Section 5.1): counts int32
+/* Spike count of every (trial, neuron) over the steps recorded since the last reset (what a
+ * spike-count loss such as the mean squared error of this build's gradient configs needs; the
+ * paper's recurrent-network benchmark, Section 5.1, names no loss): counts int32
  * [B*N], overwritten.  Needs record_tape = 1 and a complete recorded run.  Stream ordered. */
 int adseq_spike_counts(adseq_t *h, int32_t *counts, void *stream);
 

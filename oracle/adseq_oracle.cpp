@@ -68,6 +68,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <queue>
@@ -253,7 +254,14 @@ void run_trial(oracle_run& r, int b) {
   std::vector<double> acc64(N);
   std::vector<int32_t> fired;
 
+  // Long runs say how far they are: a line per 50 steps of trial 0 appended to the file named by
+  // ORACLE_PROGRESS_FILE, if set (a run of the largest configuration takes minutes).
+  FILE* progress = nullptr;
+  if (b == 0)
+    if (const char* path = getenv("ORACLE_PROGRESS_FILE")) progress = fopen(path, "a");
+
   for (int n = 0; n < T; ++n) {
+    if (progress && n % 50 == 0) { fprintf(progress, "oracle run: kind %d, N %d, step %d of %d\n", c.kind, N, n, T); fflush(progress); }
     const size_t base = ((size_t)n * B + b) * N;
     // (1) pop every event whose arrival step is n
     std::fill(acc.begin(), acc.end(), 0);
@@ -342,6 +350,7 @@ void run_trial(oracle_run& r, int b) {
       }
     }
   }
+  if (progress) fclose(progress);
   tr.in_flight = 0;
   while (!pq.empty()) {
     if (!latest || tr.admitted[pq.top().idx]) { tr.in_flight += 1; tr.sum_flight += r.a_q[pq.top().syn]; }

@@ -84,6 +84,7 @@ struct Dev {
   // what the ring's step kernels read, side by side: a launch fetches a few lines of its argument
   // block instead of a dozen
   int W, wshift;        // window length in steps (power of two) and its log2
+  int count_pop;        // RING: the step kernels add up the Q8.24 sums they pop (checking aid, off by default)
 #if defined(ADSEQ_PHASE_CLOCK) || defined(ADSEQ_ABLATE)
   int dbg;              // debugging builds: parts of the resident step to leave out (timing only)
 #endif
@@ -1097,6 +1098,7 @@ int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, 
 #if defined(ADSEQ_PHASE_CLOCK) || defined(ADSEQ_ABLATE)
   d.dbg = getenv("ADSEQ_DBG") ? atoi(getenv("ADSEQ_DBG")) : 0;
 #endif
+  d.count_pop = env_pow2("ADSEQ_RING_COUNT_POPPED", 0, 0, 1);
   d.W = L.W; d.wshift = L.wshift; d.tp_shift = L.tp_shift; d.P = L.P; d.NB = L.NB; d.cap = L.cap;
   d.wgroups = L.wgroups;
   d.win = (int*)(ws + L.win);
@@ -1417,6 +1419,12 @@ int adseq_counters(adseq_t* h, int64_t* out8, void* stream) {
     out8[6] += (int64_t)c.fold[0]; out8[0] += (int64_t)c.fold[1]; out8[3] += (int64_t)c.fold[2];
     out8[2] = out8[0] - (int64_t)c.in_flight[0];
     out8[5] = out8[3] - (int64_t)c.in_flight[1];
+    if (d.count_pop) {
+      // counted instead of derived: what the step kernels popped, cell by cell
+      int64_t popped = 0;
+      for (const BlkCtr& b : hb) popped += b.sum_delivered;
+      out8[5] = popped;
+    }
   }
   return ADSEQ_OK;
 }

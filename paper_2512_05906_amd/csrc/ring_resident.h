@@ -136,6 +136,7 @@ __global__ __launch_bounds__(kResLaunch) void k_run_xcd(long long n0, int nsteps
   long long r0[NPT];
   float V[NPT], J[NPT], Jf[NPT];
   unsigned actmask = 0;   // bit j: neuron j of this thread exists
+  long long popped = 0;   // Q8.24 sum of what this thread has popped (counted for the whole launch at its end)
 #pragma unroll
   for (int q = 0; q < NG; ++q) {
     g0[q] = lo + q * 4 * kResThreads + 4 * (int)threadIdx.x;
@@ -214,6 +215,7 @@ __global__ __launch_bounds__(kResLaunch) void k_run_xcd(long long n0, int nsteps
     unsigned smask = 0;   // bit j: neuron j spiked
 #pragma unroll
     for (int j = 0; j < NPT; ++j) {
+      popped += acc[j >> 2][j & 3];
       float I = (float)acc[j >> 2][j & 3] * 0x1p-24f;
       if (SYN) {
         const float jump = I;
@@ -359,6 +361,7 @@ __global__ __launch_bounds__(kResLaunch) void k_run_xcd(long long n0, int nsteps
   if (threadIdx.x == 0 && rank == 0)
     for (int i = 0; i < 8; ++i) atomicAdd(&d.ctr->phase[i], pc[i]);
 #endif
+  if (d.count_pop) count_popped(d, popped);
 #pragma unroll
   for (int j = 0; j < NPT; ++j)
     if ((actmask >> j) & 1u) {

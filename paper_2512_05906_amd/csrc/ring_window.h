@@ -187,6 +187,15 @@ __device__ __forceinline__ void near_scatter(const Dev& d, int* __restrict__ win
   }
 }
 
+// Checking aid (count_pop): adds the wavefront's sum of the Q8.24 values it has popped to a
+// private counter line of the block.  The ring's delivered counters are otherwise derived from the
+// spikes (offered minus still in flight); this one is counted cell by cell, so a lost add shows.
+// Every lane of the wavefront must call it.
+__device__ __forceinline__ void count_popped(const Dev& d, long long v) {
+  const long long t = wave_sum(v);
+  if ((threadIdx.x & 63) == 0 && t) atomicAdd((unsigned long long*)&d.blk[blockIdx.x & (kMaxBinBlocks - 1)].sum_delivered, (unsigned long long)t);
+}
+
 // One launch per time step.  Block b owns neurons [256 b, 256 b + 256): pops their cells of
 // row phi = n mod W, adds the drive, integrates, records the membrane value and the spike bits,
 // and scatters the in-window events of its own spikes.  No block-level synchronisation and no
@@ -208,12 +217,14 @@ __global__ __launch_bounds__(kBlock) void k_step_win(long long n, const float* _
   bool s = false;
   long long r0 = 0;
   unsigned ncnt = 0;
+  int popped = 0;
   int* __restrict__ win = win_of(d, n);
   if (act) {
     b = trial_of(d, g);
     const int i = g - b * d.N;
     const size_t idx = (size_t)phi * d.BN + g;
     const int acc = win[idx];
+    popped = acc;
     // row start and in-window entry count of every neuron, loaded beside the pop so that a
     // spiking neuron's fan-out does not wait for them (both arrays stay in the L2)
     r0 = d.row_ptr[i];
@@ -256,6 +267,7 @@ __global__ __launch_bounds__(kBlock) void k_step_win(long long n, const float* _
     d.spike_bits[(size_t)(n % d.R) * d.words + word] = bits;
     if (RECORD) d.tape_bits[(size_t)n * d.words + word] = bits;
   }
+  if (d.count_pop) count_popped(d, popped);
   // in-window events of the wavefront's spikes, up to four spikes at a time: the row loads of all
   // four are in flight before the first atomic, so that a wavefront with several spikes does not
   // pay one memory round trip per spike
@@ -293,12 +305,15 @@ __global__ __launch_bounds__(kBlock) void k_deliver_win(Dev d, long long n, floa
   const int g = blockIdx.x * kBlock + threadIdx.x;
   const int phi = (int)(n & (long long)(d.W - 1));
   int* __restrict__ win = win_of(d, n);
+  int popped = 0;
   if (g < d.BN) {
     const size_t idx = (size_t)phi * d.BN + g;
     const int acc = win[idx];
+    popped = acc;
     if (acc != 0) win[idx] = 0;
     I_out[g] = (float)acc * 0x1p-24f;
   }
+  if (d.count_pop) count_popped(d, popped);
   if ((threadIdx.x & 63) == 0)
     d.spike_bits[(size_t)(n % d.R) * d.words + (size_t)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6)] = 0ull;
 }
@@ -338,12 +353,15 @@ __global__ __launch_bounds__(kBlock) void k_open_step_win(Dev d, long long n, co
   const int g0 = blockIdx.x * kBlock + threadIdx.x;
   const int phi = (int)(n & (long long)(d.W - 1));
   int* __restrict__ win = win_of(d, n);
+  int popped = 0;
   if (g0 < d.BN) {
     const size_t idx = (size_t)phi * d.BN + g0;
     const int acc = win[idx];
+    popped = acc;
     if (acc != 0) win[idx] = 0;
     I_out[g0] = (float)acc * 0x1p-24f;
   }
+  if (d.count_pop) count_popped(d, popped);
   if ((threadIdx.x & 63) == 0 && blockIdx.x < d.nblk)
     d.spike_bits[(size_t)((n + 1) % d.R) * d.words + (size_t)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6)] = 0ull;
   int near_h = d.W - 1 - phi;

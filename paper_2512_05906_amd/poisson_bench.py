@@ -11,7 +11,7 @@ Prints one JSON line per (queue kind, capacity, pressure): time per time step, d
 events/s, drop rate, and the Erlang-B blocking probability of a loss system with `capacity`
 servers and offered load a = delay / lambda (a bounded bag with on-time delivery is one: the
 holding time of a slot is the delay, and the loss formula does not depend on the holding-time
-distribution).  The paper's own rule of thumb (Section 5.4: pressure delay / lambda around 0.5
+distribution).  The paper's own rule of thumb (Section 6.5 "Spike drop rates": pressure delay / lambda around 0.5
 needs only a very small queue) is the a << capacity corner of this table.
 """
 import argparse

@@ -98,3 +98,20 @@ def test_resident_reset_and_rerun():
     np.testing.assert_array_equal(sim.tape()["U"].cpu().numpy().view(np.uint32), U1.view(np.uint32))
     assert sim.counters() == c1
     sim.close()
+
+
+@pytest.mark.parametrize("resident", ["0", "1"])
+def test_ring_popped_sum_is_counted(resident, monkeypatch):
+    """The ring derives its delivered counters from the spikes (offered minus still in flight).
+    With ADSEQ_RING_COUNT_POPPED = 1 the step kernels add up, cell by cell, the Q8.24 values they
+    pop, and sum_delivered is that count: it must equal the oracle's sum over delivered events
+    (a lost or doubled add anywhere in the scatter or the window expansion would show), and the
+    derived figure must agree with it."""
+    wl = synth.ragged_network(3000, 120, 45, seed=17, rate_hz=300.0, t=160, b=2, w_mean=0.005, w_std=0.004)
+    ref = oracle.Run(wl, oracle.RING, 0, n_steps=160, batch=2, n_threads=2)
+    monkeypatch.setenv("ADSEQ_RING_RESIDENT", resident)
+    _, _, derived, _ = _run_pieces(wl, 160, 2, [70, "s", 89])
+    monkeypatch.setenv("ADSEQ_RING_COUNT_POPPED", "1")
+    _, _, counted, _ = _run_pieces(wl, 160, 2, [70, "s", 89])
+    assert counted["sum_delivered"] == ref.counters()["sum_delivered"] == derived["sum_delivered"]
+    assert counted["sum_delivered"] != 0 and counted["delivered"] == ref.counters()["delivered"]

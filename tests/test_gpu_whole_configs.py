@@ -1,14 +1,18 @@
-"""HIP path vs CPU oracle on the network of the headline benchmark at its full size
-(100,000 neurons x fan-out 1,000 = 1e8 synapses, delays 1..250 steps), in the launch
-configuration bench.py times (same grids, same window length, same staging regions).
+"""HIP path vs CPU oracle on the large configurations at their own size and length, in the launch
+configuration bench.py times (same grids, same window length, same staging regions):
 
-The oracle needs minutes for the benchmark's 1,000 steps, so the run here is 300 steps (longer
-than the largest delay, so the circular spike history wraps) with a drive of 55 Hz, which
-makes the network emit 2.5e7 events in them; everything is compared: the membrane trace bit
-for bit, all counters, and every entry of both gradients.
+* the headline network (100,000 neurons x fan-out 1,000 = 1e8 synapses, delays 1..250 steps) over
+  the 1,000 steps and with the drive of the run bench.py times, ring and FIFO[32]: membrane trace
+  bit for bit, all counters, spike counts, and every entry of both gradients;
+* the same network with the sorted queue and with the latest-spike slot per synapse (300 steps at
+  a stronger drive: 2.5e7 events, longer than the largest delay, so the spike history wraps);
+* config 2 (10,000 neurons x 1,000) over its 10,000 steps with the drive tuned for 5 Hz: ring,
+  FIFO[8], FIFO[32]: membrane trace, counters, drop rate;
+* config 4 at its full batch (256 trials of 4,096 neurons: 2^20 state cells, the largest grids of
+  the step kernels) for 200 steps.
 
-The batched configuration (256 trials of 4,096 neurons: 2^20 state cells, the largest grids of
-the step kernels) is run the same way at its full batch for 200 steps.
+The oracle runs of the first three groups are started in background threads when the session
+begins (tests/whole_refs.py); each test runs the GPU side first and then takes its reference.
 """
 import numpy as np
 import pytest
@@ -17,58 +21,81 @@ import torch
 from oracle import oracle
 from paper_2512_05906_amd import adseq, synth
 from tests import helpers as H
+from tests import whole_refs
 
 pytestmark = pytest.mark.gpu
 
-T = 300
 
-
-@pytest.fixture(scope="module")
-def wl():
-    return synth.cfg3(rate_hz=55.0, n_steps=T)
-
-
-@pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 32), ("latest", 1)])
-def test_cfg3_full_size_forward_backward(wl, kind, cap):
-    k = {"ring": oracle.RING, "fifo": oracle.FIFO, "latest": oracle.SYN_LATEST}[kind]
-    print(f"cfg3 full size, {kind}[{cap}], T={T}: oracle forward", flush=True)
-    ref = oracle.Run(wl, k, cap, n_steps=T)
-    rc = ref.counters()
-    counts = ref.spikes.sum(axis=0).astype(np.float32)
-    y = synth.spike_count_targets(wl)
-    dL_dc = (2.0 * (counts - y) / np.float32(wl.n_neurons)).astype(np.float32)
-    print("oracle backward", flush=True)
-    gw, gd = ref.backward(dL_dc, None)
-    U_ref = ref.U
-    ref.close()
-
-    print("GPU forward + backward", flush=True)
-    spike_cap = 4 * wl.n_neurons
-    sim = adseq.Adseq(wl, k, cap, record_tape=True, max_steps=T, tape_spike_capacity=spike_cap,
-                      tape_event_capacity=(spike_cap * wl.fan_out if kind != "ring" else 0))
+def _gpu_run(wl, kind, cap, T, ring):
+    spike_cap = max(4 * wl.n_neurons, int(10 * wl.n_neurons * T * 20.0 * wl.dt_ms * 1e-3))
+    sim = adseq.Adseq(wl, kind, cap, record_tape=True, max_steps=T, tape_spike_capacity=spike_cap,
+                      tape_event_capacity=(0 if ring else spike_cap * wl.fan_out))
     sim.run(0, T)
     torch.cuda.synchronize()
+    return sim
+
+
+def _check_forward(sim, ref, T):
     U = sim.tape()["U"].cpu().numpy()
-    np.testing.assert_array_equal(U.view(np.uint32), U_ref.view(np.uint32))
-    c = sim.counters()
+    np.testing.assert_array_equal(U.view(np.uint32), ref["U"].view(np.uint32))
+    c, rc = sim.counters(), ref["counters"]
     for key in ("enqueued", "dropped", "delivered", "sum_enqueued", "sum_dropped", "sum_delivered"):
         assert c[key] == rc[key], key
     assert c["error_bits"] == 0
-    assert rc["enqueued"] > 2e7 and rc["delivered"] > 4e6
-    if kind == "fifo":
-        assert rc["dropped"] > 1e7
-    if kind == "latest":     # one slot per synapse and trial: 1e8 queues, looked at in every step
-        assert rc["dropped"] > 1e5
-    cnt = torch.empty(wl.n_neurons, dtype=torch.int32, device=sim.dev)
+    cnt = torch.empty(sim.B * sim.N, dtype=torch.int32, device=sim.dev)
     sim.spike_counts(cnt)
-    np.testing.assert_array_equal(cnt.cpu().numpy(), counts.astype(np.int32).reshape(-1))
+    np.testing.assert_array_equal(cnt.cpu().numpy(), ref["counts"].reshape(-1))
+    return rc
+
+
+@pytest.mark.parametrize("name", ["cfg3_sorted32_T300", "cfg3_latest_T300", "cfg3_fifo32_T1000", "cfg3_ring_T1000"])
+def test_cfg3_whole(name):
+    key, kind, cap, T, _ = whole_refs.JOBS[name]
+    wl = whole_refs.workload(key)
+    print(f"{name}: GPU forward", flush=True)
+    sim = _gpu_run(wl, kind, cap, T, kind == oracle.RING)
+    print("waiting for the oracle run", flush=True)
+    ref = whole_refs.get(name)
+    rc = _check_forward(sim, ref, T)
+    if name.endswith("T1000"):   # the run bench.py times: 2e8 events offered to the ring
+        assert rc["enqueued"] > (1.5e8 if kind == oracle.RING else 5e7)
+        if kind == oracle.RING:
+            rate = ref["counts"].sum() / (wl.n_neurons * T * wl.dt_ms * 1e-3)
+            assert 19.0 < rate < 21.0 and rc["dropped"] == 0
+        else:
+            assert 0.6 < rc["dropped"] / rc["enqueued"] < 0.8
+    else:
+        assert rc["enqueued"] > 2e7 and rc["dropped"] > 1e5
     g_w = torch.full((wl.n_synapses,), 7.0, dtype=torch.float32, device=sim.dev)
     g_d = torch.full((wl.n_synapses,), 7.0, dtype=torch.float32, device=sim.dev)
-    sim.backward(torch.from_numpy(dL_dc).to(sim.dev), None, g_w, g_d)
+    sim.backward(torch.from_numpy(ref["dL_dc"].reshape(-1)).to(sim.dev), None, g_w, g_d)
     torch.cuda.synchronize()
-    H.grad_close(g_w.cpu().numpy(), gw)
-    H.grad_close(g_d.cpu().numpy(), gd)
-    assert np.abs(gw).max() > 0 and np.abs(gd).max() > 0
+    H.grad_close(g_w.cpu().numpy(), ref["gw"])
+    H.grad_close(g_d.cpu().numpy(), ref["gd"])
+    assert np.abs(ref["gw"]).max() > 0 and np.abs(ref["gd"]).max() > 0
+    sim.close()
+
+
+@pytest.mark.parametrize("name", ["cfg2_fifo8_T10000", "cfg2_fifo32_T10000", "cfg2_ring_T10000"])
+def test_cfg2_whole(name):
+    """Config 2 over its 10,000 steps with the drive tuned (on the ring) for a 5 Hz run average:
+    the bounded queues lose most of what they are offered, and the lost recurrent input lowers
+    the rate -- the drop rate per setting is what the config asks to be reported."""
+    key, kind, cap, T, _ = whole_refs.JOBS[name]
+    wl = whole_refs.workload(key)
+    print(f"{name}: GPU forward", flush=True)
+    sim = _gpu_run(wl, kind, cap, T, kind == oracle.RING)
+    print("waiting for the oracle run", flush=True)
+    ref = whole_refs.get(name)
+    rc = _check_forward(sim, ref, T)
+    rate = ref["counts"].sum() / (wl.n_neurons * T * wl.dt_ms * 1e-3)
+    drop = rc["dropped"] / max(1, rc["enqueued"])
+    print(f"{name}: rate {rate:.2f} Hz, drop rate {drop:.3f}", flush=True)
+    if kind == oracle.RING:
+        assert 4.5 < rate < 5.5 and rc["dropped"] == 0
+    else:
+        assert (0.65 < drop < 0.80) if cap == 8 else (0.18 < drop < 0.32)
+        assert sim.drop_count()["dropped"] == rc["dropped"]
     sim.close()
 
 
@@ -115,14 +142,11 @@ def test_cfg4_full_batch_forward_backward(kind, cap, drive_hz):
 
 
 @pytest.mark.parametrize("kind,cap", [("ring", 0), ("fifo", 32)])
-def test_cfg3_bench_run_properties(kind, cap):
-    """The run bench.py times (1,000 steps, the drive tuned for 20 Hz), where the oracle would need
-    minutes: what must hold at any size.  Two runs give the same bits in the membrane trace and the
+def test_cfg3_bench_run_twice(kind, cap):
+    """The run bench.py times, twice on one handle: the same bits in the membrane trace and the
     counters (integer sums: nothing depends on the order in which atomics land) and the same
-    gradients up to the order of a synapse's fp32 terms; the events that are
-    neither delivered nor dropped number no more than the queues can still hold; the spike counts
-    and the offered events are those of the recorded trace."""
-    w = synth.cfg3()
+    gradients up to the order of a synapse's fp32 terms."""
+    w = whole_refs.workload("cfg3")
     k = {"ring": adseq.RING, "fifo": adseq.FIFO}[kind]
     Tb = w.n_steps
     spike_cap = 4 * w.n_neurons
@@ -142,28 +166,12 @@ def test_cfg3_bench_run_properties(kind, cap):
         g_d = torch.full((w.n_synapses,), 7.0, dtype=torch.float32, device=sim.dev)
         sim.backward(dL_dc, None, g_w, g_d)
         torch.cuda.synchronize()
-        U = sim.tape()["U"]
         c = sim.counters()
         assert c["error_bits"] == 0
-        in_flight = c["enqueued"] - c["delivered"] - c["dropped"]
-        # what is neither delivered nor dropped is still stored: at most what the queues hold
-        # (bounded kinds), at most the events of the last d_max steps' spikes (ring)
-        last = int((U[Tb - w.d_max_steps:] >= w.v_thresh).sum().item()) * w.fan_out
-        assert 0 <= in_flight <= (min(cap * w.n_neurons, last) if kind != "ring" else last)
-        spikes = int((U >= w.v_thresh).sum().item())
-        assert int(cnt.sum().item()) == spikes and c["enqueued"] == spikes * w.fan_out
-        assert bool(torch.isfinite(g_w).all()) and bool(torch.isfinite(g_d).all())
-        assert float(g_w.abs().max()) > 0 and float(g_d.abs().max()) > 0
-        runs.append((U.clone(), g_w, g_d, c))
+        runs.append((sim.tape()["U"].clone(), g_w, g_d, c))
     assert torch.equal(runs[0][0].view(torch.int32), runs[1][0].view(torch.int32))
-    # gradients: the same up to the order in which the terms of one synapse are added (two spikes
-    # of one neuron whose events land in the same window are gathered by the same launch)
     for a, b in ((runs[0][1], runs[1][1]), (runs[0][2], runs[1][2])):
         assert float((a - b).norm()) <= 1e-6 * float(a.norm())
         assert float((a - b).abs().max()) <= 1e-5 * float(a.abs().max())
     assert runs[0][3] == runs[1][3]
-    if kind == "ring":
-        assert runs[0][3]["dropped"] == 0 and 15.0 < spikes / (w.n_neurons * Tb * w.dt_ms * 1e-3) < 25.0
-    else:
-        assert runs[0][3]["dropped"] > 1e7
     sim.close()

@@ -1,0 +1,88 @@
+"""Oracle runs of the large configurations at their own length, for tests/test_gpu_whole_configs.py.
+
+One oracle run of the headline network over its 1,000 steps takes minutes on one core (2e8 events
+through one priority queue), so all the long runs are started in background threads when the test
+session has collected that module (tests/conftest.py) and overlap with each other and with the
+GPU tests that come before; a test takes its reference with get(name), which waits for the run.
+Every run appends a line per 50 time steps to gpurun_out/oracle_progress.log (the oracle's own
+progress hook), so that a long wait is not mistaken for a hang."""
+import os
+import threading
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+from oracle import oracle
+from paper_2512_05906_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+_lock = threading.Lock()
+_workloads = {}
+_pool = None
+_futures = {}
+
+# name -> (workload key, oracle kind, capacity, steps, gradients wanted)
+JOBS = {
+    "cfg3_ring_T1000": ("cfg3", oracle.RING, 0, 1000, True),
+    "cfg3_fifo32_T1000": ("cfg3", oracle.FIFO, 32, 1000, True),
+    "cfg3_sorted32_T300": ("cfg3_55hz", oracle.SORTED, 32, 300, True),
+    "cfg3_latest_T300": ("cfg3_55hz", oracle.SYN_LATEST, 1, 300, True),
+    "cfg2_ring_T10000": ("cfg2_5hz", oracle.RING, 0, 10000, False),
+    "cfg2_fifo8_T10000": ("cfg2_5hz", oracle.FIFO, 8, 10000, False),
+    "cfg2_fifo32_T10000": ("cfg2_5hz", oracle.FIFO, 32, 10000, False),
+}
+
+
+def workload(key):
+    with _lock:
+        if key not in _workloads:
+            if key == "cfg3":            # the run bench.py times: drive tuned for a 20 Hz run average
+                _workloads[key] = synth.cfg3()
+            elif key == "cfg3_55hz":     # a stronger drive, so that 300 steps already carry 2.5e7 events
+                _workloads[key] = synth.cfg3(rate_hz=55.0, n_steps=300)
+            elif key == "cfg2_5hz":      # config 2 with the drive tuned for 5 Hz
+                _workloads[key] = synth.cfg2(rate_hz=synth.CFG2_DRIVE_HZ[5])
+            else:
+                raise KeyError(key)
+        return _workloads[key]
+
+
+def dL_dcount(wl, counts):
+    """Cotangent of the mean squared error between spike counts and the seeded targets."""
+    y = synth.spike_count_targets(wl)
+    return (2.0 * (counts.astype(np.float32) - y) / np.float32(wl.batch * wl.n_neurons)).astype(np.float32)
+
+
+def _job(name):
+    key, kind, cap, T, grads = JOBS[name]
+    wl = workload(key)
+    ref = oracle.Run(wl, kind, cap, n_steps=T)
+    out = dict(U=ref.U, counters=ref.counters())
+    counts = ref.spikes.sum(axis=0)
+    out["counts"] = counts.astype(np.int32)
+    if grads:
+        out["dL_dc"] = dL_dcount(wl, counts)
+        out["gw"], out["gd"] = ref.backward(out["dL_dc"], None)
+    ref.close()
+    return out
+
+
+def start(names=None):
+    """Starts the oracle runs in background threads (once)."""
+    global _pool
+    with _lock:
+        if _pool is not None:
+            return
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        os.environ.setdefault("ORACLE_PROGRESS_FILE", os.path.join(ROOT, "gpurun_out", "oracle_progress.log"))
+        _pool = ThreadPoolExecutor(max_workers=len(JOBS))
+    for name in (names or JOBS):
+        _futures[name] = _pool.submit(_job, name)
+
+
+def get(name):
+    """The reference of one run (waits for it; starts it if nothing was started ahead)."""
+    if name not in _futures:
+        start([name])
+    return _futures[name].result()
