@@ -48,6 +48,8 @@ def main():
     ap.add_argument("--drive-hz", type=float, default=0.0, help="override the rate of the Poisson drive")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fifo-leg", action="store_true", help="skip the FIFO[32] comparison leg of the default workload")
+    ap.add_argument("--graph-forward", action="store_true",
+                    help="also time the forward run replayed from a captured HIP graph (reported as graph_forward_ms)")
     ap.add_argument("--cpu-sample-events", type=float, default=4e7)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -226,6 +228,32 @@ def main():
                      "frac_of_measured_copy": kernels[dom]["achieved_GBs"] / copy_gbs if copy_gbs else None},
         "kernels": kernels,
     }
+
+    if args.graph_forward:
+        # The forward run (reset + T steps) captured once into a HIP graph and replayed: what graph
+        # launch would buy over the launches issued one by one (it does not shorten the gaps between
+        # dependent kernels).  The reset's clearing is done by fill kernels, never by memset nodes.
+        gstream = torch.cuda.Stream()
+        gstream.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(gstream):
+            sim.reset()
+            sim.run(0, T)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=gstream):
+            sim.reset()
+            sim.run(0, T)
+        ge = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        times = []
+        for _ in range(3):
+            torch.cuda.synchronize()
+            ge[0].record(); graph.replay(); ge[1].record()
+            torch.cuda.synchronize()
+            times.append(ge[0].elapsed_time(ge[1]))
+        U_graph = sim.membrane_tape(T).clone()
+        sim.reset(); sim.run(0, T); torch.cuda.synchronize()
+        out["graph_forward_ms"] = min(times)
+        out["graph_forward_matches_eager"] = bool(torch.equal(U_graph.view(torch.int32), sim.membrane_tape(T).view(torch.int32)))
 
     # The comparison the headline config asks for (ring against FIFO[32], Section 6.5 "Spike drop
     # rates"): a short leg with the bounded FIFO on the same network and drive.  The lost recurrent

@@ -108,6 +108,14 @@ struct Dev {
   float* Gacc;          // [R][BN]
   uint2* synb;          // [S] sorted rows: {col << dbits | D, fp32 amplitude bits}
   float* gsum;          // [S]
+  // RING, reverse sweep by windows (ring_reverse.h)
+  unsigned long long* wspk;   // [BN] spikes of the window being swept, one bit per step
+  int* near_nspk;       // [64] numbered spikes per step of the window
+  int* near_nev;        // [64] staged near events per step of the window
+  uint4* near_ev;       // [W][near_ev_cap] staged near events
+  int* near_spk;        // [W][kNearSpikeCap] neuron of every numbered spike
+  int* near_counts;     // [2][max_steps] spikes and near events of every recorded step
+  int near_ev_cap;
   // the rest
   long long S, spike_cap, event_cap;
   const int* col;
@@ -342,6 +350,7 @@ __global__ __launch_bounds__(kBlock) void k_copy_i32(const int* __restrict__ src
 
 #include "ring_window.h"
 #include "ring_resident.h"
+#include "ring_reverse.h"
 
 // ---------------------------------------------------------------- backward (FIFO / SORTED)
 
@@ -473,11 +482,12 @@ namespace {
 struct Layout {
   size_t V, J, bwd_carryJ, win, spike_bits, drive_words, sq_next, sq_hs, sq_key, sq_flag, I_acc, last_evb, slot, fkey, famp, vmask, occ, head, min_k, cnt, cont, c_head, pool_p, pool_t, pool_next,
       pool_k, pool_a, spk_words, stepcnt, packed, a_q, synf, synb, dstart, nearcnt, perm, rowsum, rowlen, ebuf, ecnt, amp, fdec, tapeU,
-      tape_bits, spk_count, step_off, step_evoff, tape_spk, tape_evb, tape_row, tape_adm, bwd_ring, bwd_carry, bwd_G, gwin, Gacc, gsum, ctr, blk,
+      tape_bits, spk_count, step_off, step_evoff, tape_spk, tape_evb, tape_row, tape_adm, bwd_ring, bwd_carry, bwd_G, gwin, Gacc, gsum, wspk, near_cnt, near_ev, near_spk, near_counts, ctr, blk,
       total;
   long long spike_cap, event_cap, pool_cap;
   int R, dbits, nblk, words;
   int W, wshift, tp_shift, P, NB, cap, wgroups;  // RING
+  int near_ev_cap;
 };
 
 // A power of two in [lo, hi] from the environment, else the default (tuning knobs of the ring:
@@ -656,6 +666,19 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->gwin = take(tape && !bounded ? nstates * 2 * (size_t)L->W * BN * 4 : 0);
   L->Gacc = take(tape && !bounded ? (size_t)L->R * BN * 4 : 0);
   L->gsum = take(tape && !bounded ? nstates * S * 4 : 0);
+  {
+    // reverse sweep by windows (delta synapse only): staging of a window's near events, 4 per state
+    // cell and step, between 4,096 and 262,144
+    const bool byw = tape && !bounded && !(c->tau_syn_ms > 0.0f);
+    size_t cap = 4 * BN;
+    cap = cap < 4096 ? 4096 : (cap > 262144 ? 262144 : cap);
+    L->near_ev_cap = byw ? (int)cap : 0;
+    L->wspk = take(byw ? BN * 8 : 0);
+    L->near_cnt = take(byw ? 2 * 64 * 4 : 0);
+    L->near_ev = take(byw ? (size_t)L->W * cap * 16 : 0);
+    L->near_spk = take(byw ? (size_t)L->W * kNearSpikeCap * 4 : 0);
+    L->near_counts = take(byw ? 2 * T * 4 : 0);
+  }
   L->total = o;
   return true;
 }
@@ -933,11 +956,14 @@ int gather_blocks(const Dev& d, long long n_lo, long long n_hi) {
   return env_pow2("ADSEQ_RING_GATHERBLOCKS", (int)(g < 1 ? 1 : (g > 256 ? 256 : g)), 1, 2048);
 }
 
-// RING: the whole reverse sweep on `st`.  One launch per reverse step; when a step closes a
-// window (n mod W = 0) the far queue terms of all earlier spikes that arrive in that window are
-// gathered in one pass.
+// RING: the whole reverse sweep on `st`.  A window is swept as a whole (ring_reverse.h: one dense
+// pass, the near corrections step by step inside one workgroup, then the far gather) when
+// `counts` (spikes and near events of every step, from k_bwd_near_counts; null: never) says that
+// its staging fits; otherwise with one launch per reverse step (k_bwd_step_win).  Either way, when
+// a window is complete the far queue terms of all earlier spikes that arrive in it are gathered in
+// one pass.
 void ring_backward_launch(adseq* h, hipStream_t st, long long T, float dscale, const float* dL_dcount,
-                          const float* dL_dU, float* grad_w, float* grad_d) {
+                          const float* dL_dU, float* grad_w, float* grad_d, const int* counts) {
   const Dev& d = h->dev;
   const dim3 block(kBlock), gn((unsigned)d.nblk);
   const size_t nst = d.alpha_r > 0.0f ? 2 : 1;
@@ -946,19 +972,46 @@ void ring_backward_launch(adseq* h, hipStream_t st, long long T, float dscale, c
   fill_u32(st, d.gsum, 0u, nst * (size_t)d.S);
   fill_u32(st, d.gwin, 0u, nst * 2 * (size_t)d.W * d.BN);
   fill_u32(st, d.Gacc, 0u, (size_t)d.R * d.BN);
-  for (long long n = T - 1; n >= 0; --n) {
+  if (counts) fill_u32(st, d.near_nspk, 0u, 128);
+  for (long long k0 = (T - 1) & ~(long long)(d.W - 1); k0 >= 0; k0 -= d.W) {
+    const long long k1 = k0 + d.W < T ? k0 + d.W : T;
+    const int nsteps = (int)(k1 - k0);
+    bool whole = counts != nullptr;
+    for (long long n = k0; whole && n < k1; ++n)
+      whole = counts[n] <= kNearSpikeCap && counts[T + n] <= d.near_ev_cap;
     open_group(h, st);
-    if (d.alpha_r > 0.0f) hipLaunchKernelGGL((k_bwd_step_win<2>), gn, block, 0, st, n, T, dL_dcount, dL_dU, d);
-    else if (d.alpha_s > 0.0f) hipLaunchKernelGGL((k_bwd_step_win<1>), gn, block, 0, st, n, T, dL_dcount, dL_dU, d);
-    else hipLaunchKernelGGL((k_bwd_step_win<0>), gn, block, 0, st, n, T, dL_dcount, dL_dU, d);
-    h->grp_count += 1;
-    if ((n & (long long)(d.W - 1)) == 0 && n > 0) {
+    if (whole) {
+      hipLaunchKernelGGL(k_bwd_dense_win, gn, block, 0, st, k0, nsteps, dL_dcount, dL_dU, d);
+      if (nsteps >= 2) {
+        long long spikes = 0;
+        for (long long n = k0; n < k1; ++n) spikes += counts[n];
+        if (spikes > 0) {
+          // about four 8-word lines of the window's spike words per wavefront
+          const long long lines = (long long)nsteps * d.wgroups;
+          long long nvb = (lines + 4 * kRingWaves - 1) / (4 * kRingWaves);
+          nvb = nvb < 1 ? 1 : (nvb > 64 ? 64 : nvb);
+          hipLaunchKernelGGL(k_bwd_near_stage, dim3((unsigned)nvb), dim3(kRingThreads), 0, st, d, k0, k1, T, (int)nvb);
+          hipLaunchKernelGGL(k_bwd_near_seq, dim3(1), dim3(kRingThreads), 0, st, d, k0, nsteps);
+        }
+      }
+    } else {
+      for (long long n = k1 - 1; n >= k0; --n) {
+        if (d.alpha_r > 0.0f) hipLaunchKernelGGL((k_bwd_step_win<2>), gn, block, 0, st, n, T, dL_dcount, dL_dU, d);
+        else if (d.alpha_s > 0.0f) hipLaunchKernelGGL((k_bwd_step_win<1>), gn, block, 0, st, n, T, dL_dcount, dL_dU, d);
+        else hipLaunchKernelGGL((k_bwd_step_win<0>), gn, block, 0, st, n, T, dL_dcount, dL_dU, d);
+      }
+    }
+    h->grp_count += nsteps;
+    // far gather into the window (and, after a sweep of the whole window, the per-synapse sums of
+    // its own near events): spikes of steps [lo, hi)
+    const long long lo = k0 - d.d_max > 0 ? k0 - d.d_max : 0;
+    const long long hi = whole ? k1 : k0;
+    if (hi > lo) {
       close_group(h, st, 3);
       mark(h, st, -1);
-      const long long lo = n - d.d_max > 0 ? n - d.d_max : 0;
-      const int nvb = gather_blocks(d, lo, n);
-      if (d.alpha_r > 0.0f) hipLaunchKernelGGL((k_bwd_win<true>), dim3((unsigned)nvb), dim3(kRingThreads), 0, st, d, n, lo, n, T, 0, nvb);
-      else hipLaunchKernelGGL((k_bwd_win<false>), dim3((unsigned)nvb), dim3(kRingThreads), 0, st, d, n, lo, n, T, 0, nvb);
+      const int nvb = gather_blocks(d, lo, hi);
+      if (d.alpha_r > 0.0f) hipLaunchKernelGGL((k_bwd_win<true>), dim3((unsigned)nvb), dim3(kRingThreads), 0, st, d, k0, lo, hi, T, 0, nvb);
+      else hipLaunchKernelGGL((k_bwd_win<false>), dim3((unsigned)nvb), dim3(kRingThreads), 0, st, d, k0, lo, hi, T, 0, nvb);
       mark(h, st, 2);
     }
   }
@@ -1108,6 +1161,9 @@ int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, 
   d.tape_bits = (unsigned long long*)(ws + L.tape_bits);
   d.spk_count = (int*)(ws + L.spk_count);
   d.gwin = (float*)(ws + L.gwin); d.Gacc = (float*)(ws + L.Gacc); d.gsum = (float*)(ws + L.gsum);
+  d.wspk = (unsigned long long*)(ws + L.wspk); d.near_nspk = (int*)(ws + L.near_cnt); d.near_nev = d.near_nspk + 64;
+  d.near_ev = (uint4*)(ws + L.near_ev); d.near_spk = (int*)(ws + L.near_spk); d.near_counts = (int*)(ws + L.near_counts);
+  d.near_ev_cap = L.near_ev_cap;
   d.slot = (uint2*)(ws + L.slot); d.vmask = (unsigned*)(ws + L.vmask);
   d.fkey = (unsigned short*)(ws + L.fkey); d.famp = (int*)(ws + L.famp);
   d.nw = (cfg->capacity + 31) / 32; d.cpad = (cfg->capacity + 7) / 8 * 8;
@@ -1326,13 +1382,28 @@ int adseq_backward(adseq_t* h, const float* dL_dcount, const float* dL_dU, float
   flush_admit(h, st);
   close_group(h, st, 1);
   unsigned err = 0;
+  const long long T = h->next_step;
+  // RING, delta synapse: the reverse sweep goes window by window where a window's spikes and near
+  // events fit the staging arrays; their counts per step come back with the error word
+  std::vector<int> near_counts;
+  // (measured, backward ms per run with / without: cfg0, 100 state cells, 1.6 / 3.6; cfg1, 16,000,
+  // 9.1 / 7.9; cfg2, 10,000 over 10,000 steps, 71 / 47; cfg3, 100,000, 21.6 / 7.1 -- the one
+  // workgroup that carries the near corrections from step to step pays a chain of trips to memory
+  // per step unless the whole window sits in the caches -- so by default only up to 1,024 state
+  // cells; ADSEQ_RING_REVERSE_WINDOWS = 1: always, 0: never)
+  const int rw = env_pow2("ADSEQ_RING_REVERSE_WINDOWS", 2, 0, 2);
+  const bool by_windows = d.kind == ADSEQ_RING && d.near_ev_cap > 0 && T > 0 && (rw == 1 || (rw == 2 && d.BN <= 1024));
+  if (by_windows) {
+    near_counts.resize(2 * (size_t)T);
+    hipLaunchKernelGGL(k_bwd_near_counts, dim3((unsigned)(T < 4096 ? T : 4096)), dim3(kBlock), 0, st, d, T, d.near_counts);
+    HIP_TRY(h, hipMemcpyAsync(near_counts.data(), d.near_counts, sizeof(int) * 2 * (size_t)T, hipMemcpyDeviceToHost, st));
+  }
   HIP_TRY(h, hipMemcpyAsync(&err, &d.ctr->err, sizeof(err), hipMemcpyDeviceToHost, st));
   HIP_TRY(h, hipStreamSynchronize(st));
   if (err & ERR_BARRIER)
     return fail(h, ADSEQ_E_HIP, "adseq_backward: a wait inside a resident kernel ran out (the blocks of a launch were not running together); the run is void, reset and run again");
   if (err & (ERR_TAPE_SPIKES | ERR_TAPE_EVENTS | ERR_POOL))
     return fail(h, ADSEQ_E_CAPACITY, "adseq_backward: tape or contender pool overflowed (bits %u)", err);
-  const long long T = h->next_step;
   // gradient per unit the delay was given in: 1/tau per ms, dt/tau per step
   // (double-exponential synapse: the 1/tau factors are in the gathered adjoint, one per state)
   const float dscale = d.alpha_r > 0.0f ? d.dt
@@ -1341,7 +1412,7 @@ int adseq_backward(adseq_t* h, const float* dL_dcount, const float* dL_dU, float
   const bool bounded = d.kind != ADSEQ_RING;
   const size_t nst = d.alpha_r > 0.0f ? 2 : 1;
   if (!bounded) {
-    ring_backward_launch(h, st, T, dscale, dL_dcount, dL_dU, grad_w, grad_d);
+    ring_backward_launch(h, st, T, dscale, dL_dcount, dL_dU, grad_w, grad_d, by_windows ? near_counts.data() : nullptr);
     HIP_TRY(h, hipGetLastError());
     return ADSEQ_OK;
   }

@@ -437,7 +437,8 @@ __device__ __forceinline__ void walk_advance(WalkPos& p, long long dq, int dr, i
 
 // Walks the spike words of steps [n_lo, n_hi) as virtual block vb of nvb (16 wavefronts each)
 // and, for every spike, looks up the piece of its sorted row with arrival offsets
-// [k0 - n, k0 - n + W) (cut at arrival T when T >= 0) and appends it to the block's LDS queue;
+// [k0 - n, k0 - n + W) (cut at arrival T when T >= 0; from offset 1 for a spike at a step n >= k0,
+// whose piece is the front of its row) and appends it to the block's LDS queue;
 // handle(seg) is called instead when the queue is full.  Spikes of steps >= count_from are
 // counted into cnt[3] (spikes, their events, Q8.24 sum of those).  Ends with a block barrier.
 template <class Direct>
@@ -474,7 +475,7 @@ __device__ __forceinline__ void walk_segments(const Dev& d, ExpandLds& L, const 
         nn[j] = n_lo + pos.si;
         ww[j] = pos.rem * 8 + (lane & 7);
         int slot = slot_lo + (int)pos.si;
-        if (slot >= d.R) slot -= d.R;
+        while (slot >= d.R) slot -= d.R;   // (a walk may span up to d_max + W steps)
         sl[j] = slot;
         if (ww[j] < d.words) bw[j] = words[(size_t)(circular ? (long long)slot : nn[j]) * d.words + ww[j]];
       }
@@ -485,7 +486,7 @@ __device__ __forceinline__ void walk_segments(const Dev& d, ExpandLds& L, const 
       unsigned long long bits = bw[j];
       const long long n = nn[j];
       const int word = ww[j];
-      const int dlo = (int)(k0 - n);                      // 1 .. d_max
+      const int dlo = (int)(k0 - n);                      // 1 .. d_max; <= 0 for a spike inside the window itself
       int dhi = dlo + d.W < nb - 1 ? dlo + d.W : nb - 1;
       if (T >= 0) {
         if ((long long)dhi > T - n) dhi = (int)(T - n);   // arrivals n + D >= T are never delivered
@@ -503,7 +504,7 @@ __device__ __forceinline__ void walk_segments(const Dev& d, ExpandLds& L, const 
             const int b = trial_of(d, (int)g), i = (int)g - b * d.N;
             const unsigned* ds = d.dstart + (size_t)i * nb;
             // all loads of the spike are requested before the first is used
-            const unsigned q0 = ds[dlo], q1 = ds[dhi];
+            const unsigned q0 = ds[dlo > 0 ? dlo : 0], q1 = ds[dhi];
             const long long r0 = d.row_ptr[i];
             // (the row's length and sum are loaded for every spike, counted or not: under a branch
             // of their own they would be a second round trip to memory)
@@ -1090,8 +1091,9 @@ __global__ __launch_bounds__(kBlock) void k_bwd_step_win(long long n, long long 
 }
 
 // Gather role: far part of the queue terms for window [k0, k0 + W), whose adjoint rows are
-// complete, for the recorded spikes of steps [n_lo, n_hi) (k0 - d_max <= n_lo, n_hi <= k0), as
-// virtual block vb of nvb.  The piece of each spike's sorted row that arrives in the window
+// complete, for the recorded spikes of steps [n_lo, n_hi) (k0 - d_max <= n_lo; n_hi <= k0, or up to
+// the end of the window when the window was swept as a whole (ring_reverse.h): then the window's own
+// spikes take part for the per-synapse sums of their near events), as virtual block vb of nvb.  The piece of each spike's sorted row that arrives in the window
 // gathers its adjoints from the window (6.4 MB: the L2 holds it), adds them to gsum, and the
 // wavefront's sum of amplitude * adjoint is added to Gacc[n mod R][g] (one wavefront per piece,
 // one piece per spike and window).
@@ -1115,6 +1117,7 @@ __device__ __forceinline__ void role_gather(const Dev& d, ExpandLds& L, long lon
     return __uint_as_float(ab) * x;
   };
   auto finish = [&](const Seg& o, float G) {
+    if (o.dlo < 1) return;   // a spike inside the window: its near queue term has been taken already; only the per-synapse sums were wanted
     G = wave_sum_f(G);
     if (lane == 0) {
       // one wavefront per piece, one piece per spike and window: the add has no competitor; an

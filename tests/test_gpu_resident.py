@@ -115,3 +115,36 @@ def test_ring_popped_sum_is_counted(resident, monkeypatch):
     _, _, counted, _ = _run_pieces(wl, 160, 2, [70, "s", 89])
     assert counted["sum_delivered"] == ref.counters()["sum_delivered"] == derived["sum_delivered"]
     assert counted["sum_delivered"] != 0 and counted["delivered"] == ref.counters()["delivered"]
+
+
+@pytest.mark.parametrize("surrogate", [adseq.SURR_SUPERSPIKE, adseq.GRAD_SPIKE_TIME])
+@pytest.mark.parametrize("n,b,T", [(700, 3, 150), (6000, 2, 100)])
+def test_reverse_sweep_by_windows(surrogate, n, b, T, monkeypatch):
+    """The ring's reverse sweep one window at a time (a dense pass per neuron, the near
+    corrections of the window's spikes step by step inside one workgroup, then the far gather;
+    by default only for up to 1,024 state cells, here forced on): both gradients against the
+    oracle, with a cotangent on the membrane values as well, in both gradient modes, a run length
+    that is not a multiple of the window, and agreement with the sweep of one launch per step."""
+    wl = synth.ragged_network(n, 200, 40, seed=n, rate_hz=400.0, t=T, b=b, w_mean=0.004, w_std=0.004)
+    ref = oracle.Run(wl, oracle.RING, 0, n_steps=T, batch=b, surrogate=surrogate, n_threads=4)
+    assert ref.spikes.sum() > 300
+    rng = np.random.default_rng(n)
+    dc = rng.normal(0, 1e-3, (b, n)).astype(np.float32)
+    dU = rng.normal(0, 1e-4, (T, b, n)).astype(np.float32)
+    gw, gd = ref.backward(dc, dU)
+    got = {}
+    for mode in ("1", "0"):
+        monkeypatch.setenv("ADSEQ_RING_REVERSE_WINDOWS", mode)
+        sim = adseq.Adseq(wl, adseq.RING, 0, batch=b, record_tape=True, max_steps=T, surrogate=surrogate)
+        sim.run(0, T)
+        g_w = torch.empty(wl.n_synapses, device=sim.dev)
+        g_d = torch.empty(wl.n_synapses, device=sim.dev)
+        sim.backward(torch.from_numpy(dc).to(sim.dev), torch.from_numpy(dU).to(sim.dev), g_w, g_d)
+        torch.cuda.synchronize()
+        assert sim.counters()["error_bits"] == 0
+        got[mode] = (g_w.cpu().numpy(), g_d.cpu().numpy())
+        H.grad_close(got[mode][0], gw)
+        H.grad_close(got[mode][1], gd)
+        sim.close()
+    H.grad_close(got["1"][0], got["0"][0])
+    H.grad_close(got["1"][1], got["0"][1])
