@@ -84,10 +84,6 @@ struct Dev {
   // what the ring's step kernels read, side by side: a launch fetches a few lines of its argument
   // block instead of a dozen
   int W, wshift;        // window length in steps (power of two) and its log2
-  int count_pop;        // RING: the step kernels add up the Q8.24 sums they pop (checking aid, off by default)
-#if defined(ADSEQ_PHASE_CLOCK) || defined(ADSEQ_ABLATE)
-  int dbg;              // debugging builds: parts of the resident step to leave out (timing only)
-#endif
   int nblk;      // neuron blocks of a step launch: ceil(BN / 256)
   int words;     // 64-neuron words per step in spike_bits (RING) = 4 * nblk
   int* win;             // [W][BN]
@@ -99,7 +95,6 @@ struct Dev {
   unsigned long long* spike_bits;  // RING: [R][words] spikes of the last R steps
   unsigned long long* tape_bits;  // [T][words]
   uint2* synf;          // [S] sorted rows: {col << dbits | D, Q8.24 amplitude}
-  unsigned long long* drive_words;  // RING, resident kernels: drive bits of a stretch of steps, 16 per (step, block, thread)
   float* J;             // [BN] synaptic current state (alpha_s > 0); [2][BN] with the fast state behind it (alpha_r > 0)
   unsigned long long p_thresh, seed;
   float* gwin;          // [W][BN]
@@ -108,14 +103,6 @@ struct Dev {
   float* Gacc;          // [R][BN]
   uint2* synb;          // [S] sorted rows: {col << dbits | D, fp32 amplitude bits}
   float* gsum;          // [S]
-  // RING, reverse sweep by windows (ring_reverse.h)
-  unsigned long long* wspk;   // [BN] spikes of the window being swept, one bit per step
-  int* near_nspk;       // [64] numbered spikes per step of the window
-  int* near_nev;        // [64] staged near events per step of the window
-  uint4* near_ev;       // [W][near_ev_cap] staged near events
-  int* near_spk;        // [W][kNearSpikeCap] neuron of every numbered spike
-  int* near_counts;     // [2][max_steps] spikes and near events of every recorded step
-  int near_ev_cap;
   // the rest
   long long S, spike_cap, event_cap;
   const int* col;
@@ -173,6 +160,20 @@ struct Dev {
   float* bwd_G;         // FIFO/SORTED: [fsplit][BN] partial queue terms of the spikes of the step being swept
   Counters* ctr;
   BlkCtr* blk;   // FIFO / SORTED: [nblk + kFanoutBlocks]
+  // (what was added later stays behind what the per-step kernels read, whose place in the argument block is tuned)
+  int count_pop;        // RING: the step kernels add up the Q8.24 sums they pop (checking aid, off by default)
+#if defined(ADSEQ_PHASE_CLOCK) || defined(ADSEQ_ABLATE)
+  int dbg;              // debugging builds: parts of the resident step to leave out (timing only)
+#endif
+  unsigned long long* drive_words;  // RING, resident kernels: drive bits of a stretch of steps, 16 per (step, block, thread)
+  // RING, reverse sweep by windows (ring_reverse.h)
+  unsigned long long* wspk;   // [BN] spikes of the window being swept, one bit per step
+  int* near_nspk;       // [64] numbered spikes per step of the window
+  int* near_nev;        // [64] staged near events per step of the window
+  uint4* near_ev;       // [W][near_ev_cap] staged near events
+  int* near_spk;        // [W][kNearSpikeCap] neuron of every numbered spike
+  int* near_counts;     // [2][max_steps] spikes and near events of every recorded step
+  int near_ev_cap;
 };
 
 // Trial b = g / N of the state index g = b * N + i (0 <= g < 2^31) without an integer division:
@@ -832,7 +833,7 @@ void ring_open_window(adseq* h, hipStream_t st, long long k0) {
   static const int sort_stage = env_pow2("ADSEQ_RING_SORTSTAGE", 1, 0, 1);
   const int stage = d.cap > 0 ? ((sort_stage && d.P <= kSortParts) ? 2 : 1) : 0;
   hipLaunchKernelGGL(k_win_bin, dim3((unsigned)d.NB), dim3(kRingThreads), 0, st, d, k0, n_lo, k0, 0, d.NB,
-                     stage, h->fold_upto);
+                     stage, h->fold_upto, h->res_P > 0 ? 1 : 0);
   if (d.cap > 0) {
     const int parts = d.P < kMaxParts ? d.P : kMaxParts;
     hipLaunchKernelGGL(k_win_acc, dim3((unsigned)parts), dim3(kRingThreads), 0, st, d, k0, 0);
@@ -880,12 +881,21 @@ int step_impl(adseq* h, long long step, const float* i_ext, unsigned char* spike
     open_group(h, st);
     const dim3 grid((unsigned)d.nblk), block(kBlock);
     const int syn = d.alpha_r > 0.0f ? 2 : (d.alpha_s > 0.0f ? 1 : 0);   // synaptic current states
-    if (record && syn == 0) hipLaunchKernelGGL((k_step_win<true, 0>), grid, block, 0, st, step, i_ext, spikes_out, d);
-    else if (record && syn == 1) hipLaunchKernelGGL((k_step_win<true, 1>), grid, block, 0, st, step, i_ext, spikes_out, d);
-    else if (record) hipLaunchKernelGGL((k_step_win<true, 2>), grid, block, 0, st, step, i_ext, spikes_out, d);
-    else if (syn == 0) hipLaunchKernelGGL((k_step_win<false, 0>), grid, block, 0, st, step, i_ext, spikes_out, d);
-    else if (syn == 1) hipLaunchKernelGGL((k_step_win<false, 1>), grid, block, 0, st, step, i_ext, spikes_out, d);
-    else hipLaunchKernelGGL((k_step_win<false, 2>), grid, block, 0, st, step, i_ext, spikes_out, d);
+    if (d.count_pop) {
+      if (record && syn == 0) hipLaunchKernelGGL((k_step_win<true, 0, true>), grid, block, 0, st, step, i_ext, spikes_out, d);
+      else if (record && syn == 1) hipLaunchKernelGGL((k_step_win<true, 1, true>), grid, block, 0, st, step, i_ext, spikes_out, d);
+      else if (record) hipLaunchKernelGGL((k_step_win<true, 2, true>), grid, block, 0, st, step, i_ext, spikes_out, d);
+      else if (syn == 0) hipLaunchKernelGGL((k_step_win<false, 0, true>), grid, block, 0, st, step, i_ext, spikes_out, d);
+      else if (syn == 1) hipLaunchKernelGGL((k_step_win<false, 1, true>), grid, block, 0, st, step, i_ext, spikes_out, d);
+      else hipLaunchKernelGGL((k_step_win<false, 2, true>), grid, block, 0, st, step, i_ext, spikes_out, d);
+    } else {
+      if (record && syn == 0) hipLaunchKernelGGL((k_step_win<true, 0, false>), grid, block, 0, st, step, i_ext, spikes_out, d);
+      else if (record && syn == 1) hipLaunchKernelGGL((k_step_win<true, 1, false>), grid, block, 0, st, step, i_ext, spikes_out, d);
+      else if (record) hipLaunchKernelGGL((k_step_win<true, 2, false>), grid, block, 0, st, step, i_ext, spikes_out, d);
+      else if (syn == 0) hipLaunchKernelGGL((k_step_win<false, 0, false>), grid, block, 0, st, step, i_ext, spikes_out, d);
+      else if (syn == 1) hipLaunchKernelGGL((k_step_win<false, 1, false>), grid, block, 0, st, step, i_ext, spikes_out, d);
+      else hipLaunchKernelGGL((k_step_win<false, 2, false>), grid, block, 0, st, step, i_ext, spikes_out, d);
+    }
     h->grp_count += 1;
   } else {
     mark(h, st, -1);

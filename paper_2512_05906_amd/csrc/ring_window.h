@@ -202,7 +202,9 @@ __device__ __forceinline__ void count_popped(const Dev& d, long long v) {
 // counter: spikes and offered events are counted from the spike bits when a window closes.
 // SYN: synaptic current states (0: the jumps go into the membrane, 1: first-order synapse, 2: double-
 // exponential synapse, the slow and the fast state both take the jump and the current is their difference)
-template <bool RECORD, int SYN>
+// COUNT: the checking aid count_popped (a template parameter, so that the kernel that is timed reads
+// nothing more of its argument block than it did)
+template <bool RECORD, int SYN, bool COUNT>
 __global__ __launch_bounds__(kBlock) void k_step_win(long long n, const float* __restrict__ i_ext,
                                                      unsigned char* __restrict__ spikes_out, Dev d) {
   pin_args(d.win, d.V, d.row_ptr, d.nearcnt, d.tapeU, d.spk_count, d.spike_bits, d.tape_bits, d.synf, d.J,
@@ -267,7 +269,7 @@ __global__ __launch_bounds__(kBlock) void k_step_win(long long n, const float* _
     d.spike_bits[(size_t)(n % d.R) * d.words + word] = bits;
     if (RECORD) d.tape_bits[(size_t)n * d.words + word] = bits;
   }
-  if (d.count_pop) count_popped(d, popped);
+  if (COUNT) count_popped(d, popped);
   // in-window events of the wavefront's spikes, up to four spikes at a time: the row loads of all
   // four are in flight before the first atomic, so that a wavefront with several spikes does not
   // pay one memory round trip per spike
@@ -817,15 +819,15 @@ __device__ __forceinline__ void role_acc(const Dev& d, int* tile, long long k0, 
 // The two passes of the expansion as kernels.
 // The same roles as launches of their own (window boundaries, catching up, open loop).
 __global__ __launch_bounds__(kRingThreads) void k_win_bin(Dev d, long long k0, long long n_lo, long long n_hi,
-                                                          int vb0, int nvb, int stage, long long count_from) {
+                                                          int vb0, int nvb, int stage, long long count_from, int clear_other) {
   __shared__ ExpandLds L;
   __shared__ SortLds S;
   role_bin(d, L, S, k0, n_lo, n_hi, vb0 + (int)blockIdx.x, nvb, stage, count_from);
   // The other window buffer -- the one the steps before k0 have just used up -- is zeroed here, a
   // slice per block, for the expansion that fills it next: the resident step kernels do not clear
   // the cells they pop (their one XCD would spend a fifth of a step on those stores), and the
-  // per-step kernels, which do, lose nothing.
-  {
+  // per-step kernels, which do, lose nothing (clear_other is set when the handle runs resident kernels).
+  if (clear_other) {
     int* other = d.win + (size_t)((((k0 >> d.wshift) & 1) ^ 1)) * d.W * d.BN;
     const size_t cells = (size_t)d.W * d.BN;
     const size_t per = ((cells + nvb - 1) / nvb + 3) & ~(size_t)3;
