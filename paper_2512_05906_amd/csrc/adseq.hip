@@ -607,7 +607,7 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->J = take(c->tau_syn_ms > 0.0f ? nstates * BN * 4 : 0);
   L->win = take(bounded ? 0 : 2 * (size_t)L->W * BN * 4);
   L->spike_bits = take(bounded ? 0 : (size_t)L->R * L->words * 8);
-  L->drive_words = take(bounded ? 0 : (size_t)256 * 32 * 512 * 2);   // [kDriveSteps][kResBlocks][kResThreads] u16
+  L->drive_words = take(bounded ? 0 : (size_t)256 * 128 * 512 * 2);   // [kDriveSteps][taking-part blocks, at most 128][kResThreads] u16
   const bool fifo = c->kind == ADSEQ_FIFO;
   L->slot = take(c->kind == ADSEQ_SORTED ? (size_t)c->capacity * BN * 8 : 0);
   L->fkey = take(fifo ? (size_t)((c->capacity + 7) / 8 * 8) * BN * 2 : 0);
@@ -914,7 +914,9 @@ int step_impl(adseq* h, long long step, const float* i_ext, unsigned char* spike
 template <bool RECORD, int NG>
 void launch_run_xcd(const Dev& d, hipStream_t st, int syn, long long n0, int cnt, unsigned bar_base, int P, int chunk) {
   // block b runs on XCD b mod 8: with stride 8 the taking-part blocks share one XCD
-  static const int stride = env_pow2("ADSEQ_RING_RESIDENT_STRIDE", kResStride, 1, 8);
+  // (at most 32 taking-part blocks per XCD, one per compute unit: what the barrier measurements cover)
+  int stride = env_pow2("ADSEQ_RING_RESIDENT_STRIDE", kResStride, 1, 8);
+  while (stride > 1 && (long long)P * stride > 32 * 8) stride >>= 1;
   const dim3 grid((unsigned)(P * stride)), block(kResLaunch);
   if (syn == 0) hipLaunchKernelGGL((k_run_xcd<RECORD, 0, NG>), grid, block, 0, st, n0, cnt, bar_base, P, chunk, stride, d);
   else if (syn == 1) hipLaunchKernelGGL((k_run_xcd<RECORD, 1, NG>), grid, block, 0, st, n0, cnt, bar_base, P, chunk, stride, d);
@@ -1215,7 +1217,8 @@ int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, 
     // default they run up to 32,768 state cells.  ADSEQ_RING_RESIDENT = 0: never, 1: whenever
     // the layout allows (up to 131,072 state cells).
     const int resident = env_pow2("ADSEQ_RING_RESIDENT", 2, 0, 2);
-    long long chunk = ((long long)d.BN + kResBlocks - 1) / kResBlocks;
+    const int res_blocks = env_pow2("ADSEQ_RING_RESIDENT_BLOCKS", kResBlocks, 8, 128);   // taking-part blocks at most (more than 32 spread over several XCDs)
+    long long chunk = ((long long)d.BN + res_blocks - 1) / res_blocks;
     chunk = (chunk + 255) / 256 * 256;
     if (resident && chunk <= 8 * kResThreads && d.BN % 4 == 0 && (resident == 1 || d.BN <= 32768)) {
       h->res_chunk = (int)chunk;

@@ -23,7 +23,7 @@ constexpr int kResThreads = 512;      // two wavefronts per SIMD: a step is boun
                                       // and by how many row loads of the step's spikes are in flight at once
 constexpr int kResBlocks = 32;        // taking-part blocks at most: the compute units of one XCD
 constexpr int kResStride = 8;         // XCDs: block b runs on XCD b mod 8
-constexpr int kResMaxSpins = 1 << 22;
+constexpr int kResMaxSpins = 1 << 16;  // polls of one wait before it gives up (tens of ms; a step takes microseconds)
 constexpr int kResLaunch = kResThreads + 64;   // one more wavefront per block that only synchronises: it
                                                // polls the barrier counter and adds the block's arrival, so that
                                                // a poll never waits behind the stores of a wavefront that has neurons
@@ -125,7 +125,8 @@ __global__ __launch_bounds__(kResLaunch) void k_run_xcd(long long n0, int nsteps
   if (blockIdx.x % stride) return;
   const int rank = blockIdx.x / stride;
   if (rank >= P) return;
-  if (threadIdx.x == 0) { s_dead = 0; s_nspk = 0; }
+  // (a wait that ran out in an earlier launch stays on record: then nobody waits any more, the run is void anyway)
+  if (threadIdx.x == 0) { s_dead = (ld_agent(&d.ctr->err) & ERR_BARRIER) ? 1 : 0; s_nspk = 0; }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const bool worker = threadIdx.x < kResThreads;   // uniform per wavefront; the last wavefront only synchronises
   const int lo = rank * chunk;
