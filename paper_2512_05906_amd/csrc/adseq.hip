@@ -475,6 +475,10 @@ struct adseq {
   long long drive_from = 0, drive_upto = 0;   // RING, resident kernels: steps whose drive words are in place
   unsigned bar_base = 0;      // RING, resident kernels: value of the barrier counter after the launches so far
   int res_P = 0, res_chunk = 0, res_npt = 0;   // RING: taking-part blocks, neurons per block, per thread (0: one launch per step)
+  // RING, experimental (ADSEQ_RING_OVERLAP = 1): the far part of the next window expanded ahead on a stream of the library's own
+  hipStream_t aux = nullptr;
+  hipEvent_t ev_boundary = nullptr, ev_ahead = nullptr;
+  long long ahead_for = -1;   // window start whose far part (spikes before the previous boundary) is being expanded ahead, or -1
   bool in_static = false;     // the handle is the device's static one (adseq_create_static): never deleted
 };
 
@@ -712,9 +716,13 @@ void fill_u32(hipStream_t st, void* p, unsigned v, size_t count) {
   hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)g), dim3(kBlock), 0, st, (unsigned*)p, v, count);
 }
 
+void join_ahead(adseq* h, hipStream_t st);
+
 // Clears the dynamic state (not the prepared synapses).
 void launch_reset(adseq* h, hipStream_t st) {
   const Dev& d = h->dev;
+  join_ahead(h, st);
+  h->ahead_for = -1;
   h->fold_upto = 0;
   h->bar_base = 0;   // (the counter itself is cleared with the other counters)
   h->drive_from = h->drive_upto = 0;
@@ -823,22 +831,58 @@ void close_group(adseq* h, hipStream_t st, int kind);
 // per-part accumulation; without staging room the first pass scatters with atomics and the
 // second is skipped).  The staging pass also counts the spikes not counted yet, and their
 // events, into the device counters.
+// Expansion of the events of the spikes of steps [n_lo, n_hi) that arrive in window [k0, k0 + W) on `st`.
+void launch_expansion(adseq* h, hipStream_t st, long long k0, long long n_lo, long long n_hi, long long count_from) {
+  const Dev& d = h->dev;
+  // staging mode: 0 none (atomics), 1 one store per event, 2 ordered by part in LDS first
+  static const int sort_stage = env_pow2("ADSEQ_RING_SORTSTAGE", 1, 0, 1);
+  const int stage = d.cap > 0 ? ((sort_stage && d.P <= kSortParts) ? 2 : 1) : 0;
+  hipLaunchKernelGGL(k_win_bin, dim3((unsigned)d.NB), dim3(kRingThreads), 0, st, d, k0, n_lo, n_hi, 0, d.NB,
+                     stage, count_from, h->res_P > 0 ? 1 : 0);
+  if (d.cap > 0) {
+    const int parts = d.P < kMaxParts ? d.P : kMaxParts;
+    hipLaunchKernelGGL(k_win_acc, dim3((unsigned)parts), dim3(kRingThreads), 0, st, d, k0, 0);
+  }
+}
+
+// The main stream waits for what was expanded ahead on the library's own stream (experimental overlap).
+void join_ahead(adseq* h, hipStream_t st) {
+  if (h->ahead_for >= 0 && h->ev_ahead) (void)hipStreamWaitEvent(st, h->ev_ahead, 0);
+}
+
 void ring_open_window(adseq* h, hipStream_t st, long long k0) {
   const Dev& d = h->dev;
   if ((k0 & (long long)(d.W - 1)) != 0 || k0 <= 0) return;
   close_group(h, st, 1);
   mark(h, st, -1);
-  const long long n_lo = k0 - d.d_max > 0 ? k0 - d.d_max : 0;
-  // staging mode: 0 none (atomics), 1 one store per event, 2 ordered by part in LDS first
-  static const int sort_stage = env_pow2("ADSEQ_RING_SORTSTAGE", 1, 0, 1);
-  const int stage = d.cap > 0 ? ((sort_stage && d.P <= kSortParts) ? 2 : 1) : 0;
-  hipLaunchKernelGGL(k_win_bin, dim3((unsigned)d.NB), dim3(kRingThreads), 0, st, d, k0, n_lo, k0, 0, d.NB,
-                     stage, h->fold_upto, h->res_P > 0 ? 1 : 0);
-  if (d.cap > 0) {
-    const int parts = d.P < kMaxParts ? d.P : kMaxParts;
-    hipLaunchKernelGGL(k_win_acc, dim3((unsigned)parts), dim3(kRingThreads), 0, st, d, k0, 0);
+  long long n_lo = k0 - d.d_max > 0 ? k0 - d.d_max : 0;
+  static const int overlap = env_pow2("ADSEQ_RING_OVERLAP", 0, 0, 1);
+  const bool ahead = overlap && h->res_P == 0;
+  if (ahead) {
+    if (!h->aux) {
+      (void)hipStreamCreateWithFlags(&h->aux, hipStreamNonBlocking);
+      (void)hipEventCreateWithFlags(&h->ev_boundary, hipEventDisableTiming);
+      (void)hipEventCreateWithFlags(&h->ev_ahead, hipEventDisableTiming);
+    }
+    // what was expanded ahead covers the spikes before the previous boundary: only the last window's are left
+    if (h->ahead_for == k0) { join_ahead(h, st); n_lo = k0 - d.W; }
+    else join_ahead(h, st);
+    h->ahead_for = -1;
   }
+  launch_expansion(h, st, k0, n_lo, k0, h->fold_upto);
   h->fold_upto = k0;
+  if (ahead && h->aux) {
+    // the next window's events from the spikes before this boundary: on the other stream, beside the steps of this window
+    const long long k1 = k0 + d.W;
+    const long long lo2 = k1 - d.d_max > 0 ? k1 - d.d_max : 0;
+    if (lo2 < k0) {
+      (void)hipEventRecord(h->ev_boundary, st);
+      (void)hipStreamWaitEvent(h->aux, h->ev_boundary, 0);
+      launch_expansion(h, h->aux, k1, lo2, k0, k0 /* nothing is counted here */);
+      (void)hipEventRecord(h->ev_ahead, h->aux);
+      h->ahead_for = k1;
+    }
+  }
   mark(h, st, 0);
 }
 
@@ -1273,6 +1317,11 @@ extern "C" {
 
 int adseq_destroy(adseq_t* h) {
   if (!h) return ADSEQ_E_INVALID_ARG;
+  if (h->aux) {
+    (void)hipStreamSynchronize(h->aux);
+    (void)hipStreamDestroy(h->aux); (void)hipEventDestroy(h->ev_boundary); (void)hipEventDestroy(h->ev_ahead);
+    h->aux = nullptr;
+  }
   for (hipEvent_t e : h->evs) (void)hipEventDestroy(e);
   if (h->in_static) {
     h->evs.clear();
@@ -1393,6 +1442,7 @@ int adseq_backward(adseq_t* h, const float* dL_dcount, const float* dL_dU, float
     return fail(h, ADSEQ_E_NO_TAPE, "adseq_backward: no complete recorded forward run");
   hipStream_t st = (hipStream_t)stream;
   flush_admit(h, st);
+  join_ahead(h, st);
   close_group(h, st, 1);
   unsigned err = 0;
   const long long T = h->next_step;
@@ -1458,6 +1508,7 @@ int adseq_counters(adseq_t* h, int64_t* out8, void* stream) {
   hipStream_t st = (hipStream_t)stream;
   const Dev& d = h->dev;
   flush_admit(h, st);
+  join_ahead(h, st);
   if (d.kind == ADSEQ_RING) {
     // The ring keeps no per-event counters.  Spikes and the events they emit are counted from
     // the spike words: up to the last window boundary by the boundary pass (device counters),
