@@ -254,8 +254,12 @@ int adseq_drop_count(adseq_t *h, uint64_t *dropped, uint64_t *enqueued, uint64_t
                      void *stream);
 
 /* Further counters (host pointer to 8 int64): [0] offered, [1] dropped, [2] delivered events;
- * [3..5] the same as sums of Q8.24 amplitudes; [6] spikes recorded on the tape; [7] device error
- * bits.  Synchronises `stream`. */
+ * [3..5] the same as sums of Q8.24 amplitudes; [6] spikes recorded on the tape; [7] error bits:
+ * 4, 8, 16 tape or contender-pool overflow (ADSEQ_E_CAPACITY), 32 a bounded wait inside a resident
+ * kernel ran out (ADSEQ_E_HIP; the run is void), 64 a warning from adseq_create: for some target the
+ * |amplitudes| of its incoming synapses add up to 128 or more, so that a step in which enough of them
+ * deliver together would wrap its 32-bit fixed-point sum (range +-128) without further notice.
+ * Synchronises `stream`. */
 int adseq_counters(adseq_t *h, int64_t *out8, void *stream);
 
 /* Where the tape lives inside the workspace (device pointers; valid for the handle's life).

@@ -41,7 +41,8 @@ constexpr int kFanoutBlocks = 1024;
 
 enum : unsigned {
   ERR_DELAY = 1u, ERR_GRAPH = 2u, ERR_TAPE_SPIKES = 4u, ERR_TAPE_EVENTS = 8u, ERR_POOL = 16u,
-  ERR_BARRIER = 32u   // a bounded wait of a resident kernel ran out
+  ERR_BARRIER = 32u,  // a bounded wait of a resident kernel ran out
+  ERR_RANGE = 64u     // some target's incoming amplitudes add up to 128 or more in magnitude: a Q8.24 sum could wrap
 };
 
 struct Counters {
@@ -161,6 +162,7 @@ struct Dev {
   Counters* ctr;
   BlkCtr* blk;   // FIFO / SORTED: [nblk + kFanoutBlocks]
   // (what was added later stays behind what the per-step kernels read, whose place in the argument block is tuned)
+  long long* insum;     // [N] create only: sum of |Q8.24 amplitude| over every target's incoming synapses
   int count_pop;        // RING: the step kernels add up the Q8.24 sums they pop (checking aid, off by default)
 #if defined(ADSEQ_PHASE_CLOCK) || defined(ADSEQ_ABLATE)
   int dbg;              // debugging builds: parts of the resident step to leave out (timing only)
@@ -347,6 +349,26 @@ __global__ __launch_bounds__(kBlock) void k_copy_i32(const int* __restrict__ src
   for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) dst[i] = src[i];
 }
 
+// Create: worst case of every target's Q8.24 sum.  The delivered amplitudes of one step are summed
+// as wrapping 32-bit integers (range +-128); if all synapses onto one target delivered at once the
+// magnitude could reach the sum of their |amplitude|.  Where that sum is 2^31 or more, ERR_RANGE is
+// set: a warning, reported with the counters (the oracle wraps the same way, so the two still agree).
+__global__ __launch_bounds__(kBlock) void k_in_sums(Dev d) {
+  for (long long p = (long long)blockIdx.x * kBlock + threadIdx.x; p < d.S; p += (long long)gridDim.x * kBlock) {
+    unsigned pk; int a;
+    if (d.kind == ADSEQ_RING) { const uint2 e = d.synf[p]; pk = e.x; a = (int)e.y; }
+    else { pk = d.packed[p]; a = d.a_q[p]; }
+    const long long mag = a < 0 ? -(long long)a : (long long)a;
+    if (mag) atomicAdd((unsigned long long*)&d.insum[pk >> d.dbits], (unsigned long long)mag);
+  }
+}
+__global__ __launch_bounds__(kBlock) void k_in_check(Dev d) {
+  bool bad = false;
+  for (long long j = (long long)blockIdx.x * kBlock + threadIdx.x; j < d.N; j += (long long)gridDim.x * kBlock)
+    bad = bad || d.insum[j] > 0x7fffffffLL;
+  if (__ballot(bad) && (threadIdx.x & 63) == 0) atomicOr(&d.ctr->err, ERR_RANGE);
+}
+
 // ---------------------------------------------------------------- ring queue (windowed delay line)
 
 #include "ring_window.h"
@@ -479,6 +501,7 @@ struct adseq {
   hipStream_t aux = nullptr;
   hipEvent_t ev_boundary = nullptr, ev_ahead = nullptr;
   long long ahead_for = -1;   // window start whose far part (spikes before the previous boundary) is being expanded ahead, or -1
+  bool range_warn = false;    // some target's incoming |amplitudes| add up to 128 or more (ERR_RANGE, reported with the counters)
   bool in_static = false;     // the handle is the device's static one (adseq_create_static): never deleted
 };
 
@@ -487,7 +510,7 @@ namespace {
 struct Layout {
   size_t V, J, bwd_carryJ, win, spike_bits, drive_words, sq_next, sq_hs, sq_key, sq_flag, I_acc, last_evb, slot, fkey, famp, vmask, occ, head, min_k, cnt, cont, c_head, pool_p, pool_t, pool_next,
       pool_k, pool_a, spk_words, stepcnt, packed, a_q, synf, synb, dstart, nearcnt, perm, rowsum, rowlen, ebuf, ecnt, amp, fdec, tapeU,
-      tape_bits, spk_count, step_off, step_evoff, tape_spk, tape_evb, tape_row, tape_adm, bwd_ring, bwd_carry, bwd_G, gwin, Gacc, gsum, wspk, near_cnt, near_ev, near_spk, near_counts, ctr, blk,
+      tape_bits, spk_count, step_off, step_evoff, tape_spk, tape_evb, tape_row, tape_adm, bwd_ring, bwd_carry, bwd_G, gwin, Gacc, gsum, insum, wspk, near_cnt, near_ev, near_spk, near_counts, ctr, blk,
       total;
   long long spike_cap, event_cap, pool_cap;
   int R, dbits, nblk, words;
@@ -506,6 +529,28 @@ int env_pow2(const char* name, int dflt, int lo, int hi) {
 }
 // Window length of the ring in steps.
 int ring_window_steps() { return env_pow2("ADSEQ_RING_WINDOW", 16, 2, 64); }
+
+// Resident step kernels (ring_resident.h): up to 32 blocks of 512 threads (up to 128 over several
+// XCDs by ADSEQ_RING_RESIDENT_BLOCKS), one or two groups of four neurons per thread, B N a
+// multiple of 4 (16-byte aligned rows).  Measured on the configs: 2.1 against 4.7 us per step at
+// 100 state cells, 3.6 against 4.7 at 16,000, 4.9 against 5.3 at 10,000 with a long history, 4.4
+// against 4.1 at 100,000 -- a launch per step uses all 256 compute units for the spikes' row
+// loads and atomic adds, the resident kernel 32 -- so by default they run up to 32,768 state
+// cells.  ADSEQ_RING_RESIDENT = 0: never, 1: whenever the layout allows (up to 131,072 cells).
+struct ResidentPlan { int P = 0, chunk = 0, npt = 0; };   // taking-part blocks (0: a launch per step), cells per block, groups per thread
+ResidentPlan resident_plan(long long BN) {
+  ResidentPlan r;
+  const int resident = env_pow2("ADSEQ_RING_RESIDENT", 2, 0, 2);
+  const int res_blocks = env_pow2("ADSEQ_RING_RESIDENT_BLOCKS", kResBlocks, 8, 128);
+  long long chunk = (BN + res_blocks - 1) / res_blocks;
+  chunk = (chunk + 255) / 256 * 256;
+  if (resident && chunk <= 8 * kResThreads && BN % 4 == 0 && (resident == 1 || BN <= 32768)) {
+    r.chunk = (int)chunk;
+    r.P = (int)((BN + chunk - 1) / chunk);
+    r.npt = chunk <= 4 * kResThreads ? 1 : 2;
+  }
+  return r;
+}
 // Cells (target, step) of the LDS tile of one target part.
 int ring_tile_cells() { return env_pow2("ADSEQ_RING_TILE", 4096, 1024, kMaxTileCells); }
 
@@ -611,7 +656,7 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->J = take(c->tau_syn_ms > 0.0f ? nstates * BN * 4 : 0);
   L->win = take(bounded ? 0 : 2 * (size_t)L->W * BN * 4);
   L->spike_bits = take(bounded ? 0 : (size_t)L->R * L->words * 8);
-  L->drive_words = take(bounded ? 0 : (size_t)256 * 128 * 512 * 2);   // [kDriveSteps][taking-part blocks, at most 128][kResThreads] u16
+  L->drive_words = take(bounded ? 0 : (size_t)kDriveSteps * resident_plan((long long)BN).P * kResThreads * 2);   // [kDriveSteps][taking-part blocks][kResThreads] u16
   const bool fifo = c->kind == ADSEQ_FIFO;
   L->slot = take(c->kind == ADSEQ_SORTED ? (size_t)c->capacity * BN * 8 : 0);
   L->fkey = take(fifo ? (size_t)((c->capacity + 7) / 8 * 8) * BN * 2 : 0);
@@ -648,6 +693,7 @@ bool make_layout(const adseq_config* c, Layout* L) {
   L->nearcnt = take(bounded ? 0 : (size_t)(L->W + 1) * c->n_neurons * 4);
   L->perm = take(bounded ? 0 : S * 4);
   L->rowsum = take((size_t)c->n_neurons * 8);
+  L->insum = take((size_t)c->n_neurons * 8);
   L->rowlen = take(bounded ? (size_t)c->n_neurons * 4 : 0);
   L->ebuf = take(bounded ? 0 : stage_parts * L->NB * (size_t)L->cap * 8);
   L->ecnt = take(bounded ? 0 : stage_parts * L->NB * 4);
@@ -1213,6 +1259,7 @@ int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, 
   d.win = (int*)(ws + L.win);
   d.dstart = (unsigned*)(ws + L.dstart); d.nearcnt = (unsigned*)(ws + L.nearcnt);
   d.perm = (unsigned*)(ws + L.perm); d.rowsum = (long long*)(ws + L.rowsum); d.rowlen = (int*)(ws + L.rowlen);
+  d.insum = (long long*)(ws + L.insum);
   d.ebuf = (uint2*)(ws + L.ebuf); d.ecnt = (int*)(ws + L.ecnt);
   d.tape_bits = (unsigned long long*)(ws + L.tape_bits);
   d.spk_count = (int*)(ws + L.spk_count);
@@ -1253,22 +1300,8 @@ int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, 
   d.bwd_G = (float*)(ws + L.bwd_G);
 
   if (d.kind == ADSEQ_RING) {
-    // resident step kernels (ring_resident.h): up to 32 blocks of 512 threads, one or two groups
-    // of four neurons per thread, B N a multiple of 4 (16-byte aligned rows).  Measured on the
-    // configs: 2.1 against 4.7 us per step at 100 state cells, 3.6 against 4.7 at 16,000, 4.9 against
-    // 5.3 at 10,000 with a long history, 4.4 against 4.1 at 100,000 -- a launch per step uses all 256
-    // compute units for the spikes' row loads and atomic adds, the resident kernel 32 -- so by
-    // default they run up to 32,768 state cells.  ADSEQ_RING_RESIDENT = 0: never, 1: whenever
-    // the layout allows (up to 131,072 state cells).
-    const int resident = env_pow2("ADSEQ_RING_RESIDENT", 2, 0, 2);
-    const int res_blocks = env_pow2("ADSEQ_RING_RESIDENT_BLOCKS", kResBlocks, 8, 128);   // taking-part blocks at most (more than 32 spread over several XCDs)
-    long long chunk = ((long long)d.BN + res_blocks - 1) / res_blocks;
-    chunk = (chunk + 255) / 256 * 256;
-    if (resident && chunk <= 8 * kResThreads && d.BN % 4 == 0 && (resident == 1 || d.BN <= 32768)) {
-      h->res_chunk = (int)chunk;
-      h->res_P = (int)(((long long)d.BN + chunk - 1) / chunk);
-      h->res_npt = chunk <= 4 * kResThreads ? 1 : 2;   // groups of four neurons per thread
-    }
+    const ResidentPlan rp = resident_plan((long long)d.BN);
+    h->res_chunk = rp.chunk; h->res_P = rp.P; h->res_npt = rp.npt;
   }
   hipStream_t st = (hipStream_t)cfg->stream;
   launch_reset(h, st);
@@ -1304,9 +1337,22 @@ int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, 
       hipLaunchKernelGGL(k_row_sums, dim3(gr), dim3(kBlock), 0, st, d);
     }
   }
+  if (e == hipSuccess && !(err & (ERR_GRAPH | ERR_DELAY)) && d.S > 0) {
+    fill_u32(st, d.insum, 0u, (size_t)d.N * 2);
+    size_t g = ((size_t)d.S + kBlock - 1) / kBlock;
+    hipLaunchKernelGGL(k_in_sums, dim3((unsigned)(g > 16384 ? 16384 : g)), dim3(kBlock), 0, st, d);
+    hipLaunchKernelGGL(k_in_check, dim3((unsigned)grid_for((size_t)d.N)), dim3(kBlock), 0, st, d);
+    e = read_err();
+  }
   if (e != hipSuccess) { drop(); return ADSEQ_E_HIP; }
   if (err & ERR_GRAPH) { drop(); return ADSEQ_E_GRAPH; }
   if (err & ERR_DELAY) { drop(); return ADSEQ_E_DELAY_RANGE; }
+  h->range_warn = (err & ERR_RANGE) != 0;
+  if (h->range_warn) {   // the warning is kept on the host (a reset clears the device word)
+    unsigned zero = 0;
+    (void)hipMemcpyAsync(&d.ctr->err, &zero, sizeof(zero), hipMemcpyHostToDevice, st);
+    (void)hipStreamSynchronize(st);
+  }
   *out = h;
   return ADSEQ_OK;
 }
@@ -1528,7 +1574,7 @@ int adseq_counters(adseq_t* h, int64_t* out8, void* stream) {
   HIP_TRY(h, hipStreamSynchronize(st));
   out8[0] = (int64_t)c.offered; out8[1] = (int64_t)c.dropped; out8[2] = (int64_t)c.delivered;
   out8[3] = c.sum_offered; out8[4] = c.sum_dropped; out8[5] = c.sum_delivered;
-  out8[6] = c.tape_spikes; out8[7] = (int64_t)c.err;
+  out8[6] = c.tape_spikes; out8[7] = (int64_t)c.err | (h->range_warn ? (int64_t)ERR_RANGE : 0);
   if (d.kind != ADSEQ_RING) {
     // the kernels keep private counters per block: add them up here
     const size_t nb = (size_t)d.nblk + fan_slots(d.nblk) + (per_synapse_kind(d.kind) ? kSynqBlocks : 0);

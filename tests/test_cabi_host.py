@@ -37,6 +37,9 @@ def test_workspace_size_grows_with_the_queue():
     # per slot a 16-bit arrival key and a 32-bit amplitude, one more mask word per target, padding
     assert 56 * 200 * 6 <= fifo64 - fifo8 <= 56 * 200 * 6 + 200 * 4 + 3 * 256
     assert ring % 256 == 0
+    # a small ring fits the static workspace of adseq_create_static (its staging for the resident
+    # step kernels is sized by the blocks that take part, not by the largest launch)
+    assert ring < adseq.STATIC_WORKSPACE_BYTES // 4
     no_tape = lib.adseq_workspace_bytes(C.byref(_cfg(record_tape=0, max_steps=0)))
     assert no_tape < ring
     # one queue per synapse and trial: a 16-bit arrival key per slot

@@ -148,3 +148,20 @@ def test_reverse_sweep_by_windows(surrogate, n, b, T, monkeypatch):
         sim.close()
     H.grad_close(got["1"][0], got["0"][0])
     H.grad_close(got["1"][1], got["0"][1])
+
+
+def test_range_warning_for_sums_that_could_wrap():
+    """adseq_create adds up |amplitude| over every target's incoming synapses; where that reaches
+    128 (the range of the Q8.24 sums) the counters carry the warning bit 64, also after a reset."""
+    wl = synth.ragged_network(50, 40, 10, seed=2, rate_hz=100.0, t=20, b=1, w_mean=0.05, w_std=0.01)
+    sim = adseq.Adseq(wl, adseq.RING, 0)
+    assert sim.counters()["error_bits"] == 0
+    sim.close()
+    big = synth.ragged_network(50, 40, 10, seed=2, rate_hz=100.0, t=20, b=1, w_mean=9.0, w_std=0.5)
+    for kind, cap in ((adseq.RING, 0), (adseq.FIFO, 4)):
+        sim = adseq.Adseq(big, kind, cap)
+        assert sim.counters()["error_bits"] == 64
+        sim.reset()
+        sim.run(0, 5)
+        assert sim.counters()["error_bits"] & 64
+        sim.close()
