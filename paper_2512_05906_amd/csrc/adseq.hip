@@ -163,6 +163,7 @@ struct Dev {
   BlkCtr* blk;   // FIFO / SORTED: [nblk + kFanoutBlocks]
   // (what was added later stays behind what the per-step kernels read, whose place in the argument block is tuned)
   long long* insum;     // [N] create only: sum of |Q8.24 amplitude| over every target's incoming synapses
+  int lazy_rows;        // RING: the step kernels fetch row start, in-window count and far queue term for spiking lanes only (experiment)
   int count_pop;        // RING: the step kernels add up the Q8.24 sums they pop (checking aid, off by default)
 #if defined(ADSEQ_PHASE_CLOCK) || defined(ADSEQ_ABLATE)
   int dbg;              // debugging builds: parts of the resident step to leave out (timing only)
@@ -971,21 +972,19 @@ int step_impl(adseq* h, long long step, const float* i_ext, unsigned char* spike
     open_group(h, st);
     const dim3 grid((unsigned)d.nblk), block(kBlock);
     const int syn = d.alpha_r > 0.0f ? 2 : (d.alpha_s > 0.0f ? 1 : 0);   // synaptic current states
-    if (d.count_pop) {
-      if (record && syn == 0) hipLaunchKernelGGL((k_step_win<true, 0, true>), grid, block, 0, st, step, i_ext, spikes_out, d);
-      else if (record && syn == 1) hipLaunchKernelGGL((k_step_win<true, 1, true>), grid, block, 0, st, step, i_ext, spikes_out, d);
-      else if (record) hipLaunchKernelGGL((k_step_win<true, 2, true>), grid, block, 0, st, step, i_ext, spikes_out, d);
-      else if (syn == 0) hipLaunchKernelGGL((k_step_win<false, 0, true>), grid, block, 0, st, step, i_ext, spikes_out, d);
-      else if (syn == 1) hipLaunchKernelGGL((k_step_win<false, 1, true>), grid, block, 0, st, step, i_ext, spikes_out, d);
-      else hipLaunchKernelGGL((k_step_win<false, 2, true>), grid, block, 0, st, step, i_ext, spikes_out, d);
-    } else {
-      if (record && syn == 0) hipLaunchKernelGGL((k_step_win<true, 0, false>), grid, block, 0, st, step, i_ext, spikes_out, d);
-      else if (record && syn == 1) hipLaunchKernelGGL((k_step_win<true, 1, false>), grid, block, 0, st, step, i_ext, spikes_out, d);
-      else if (record) hipLaunchKernelGGL((k_step_win<true, 2, false>), grid, block, 0, st, step, i_ext, spikes_out, d);
-      else if (syn == 0) hipLaunchKernelGGL((k_step_win<false, 0, false>), grid, block, 0, st, step, i_ext, spikes_out, d);
-      else if (syn == 1) hipLaunchKernelGGL((k_step_win<false, 1, false>), grid, block, 0, st, step, i_ext, spikes_out, d);
-      else hipLaunchKernelGGL((k_step_win<false, 2, false>), grid, block, 0, st, step, i_ext, spikes_out, d);
-    }
+#define ADSEQ_STEP_WIN(MODE)                                                                                   \
+  do {                                                                                                         \
+    if (record && syn == 0) hipLaunchKernelGGL((k_step_win<true, 0, MODE>), grid, block, 0, st, step, i_ext, spikes_out, d);       \
+    else if (record && syn == 1) hipLaunchKernelGGL((k_step_win<true, 1, MODE>), grid, block, 0, st, step, i_ext, spikes_out, d);  \
+    else if (record) hipLaunchKernelGGL((k_step_win<true, 2, MODE>), grid, block, 0, st, step, i_ext, spikes_out, d);              \
+    else if (syn == 0) hipLaunchKernelGGL((k_step_win<false, 0, MODE>), grid, block, 0, st, step, i_ext, spikes_out, d);           \
+    else if (syn == 1) hipLaunchKernelGGL((k_step_win<false, 1, MODE>), grid, block, 0, st, step, i_ext, spikes_out, d);           \
+    else hipLaunchKernelGGL((k_step_win<false, 2, MODE>), grid, block, 0, st, step, i_ext, spikes_out, d);                         \
+  } while (0)
+    if (d.count_pop) ADSEQ_STEP_WIN(1);
+    else if (d.lazy_rows) ADSEQ_STEP_WIN(2);
+    else ADSEQ_STEP_WIN(0);
+#undef ADSEQ_STEP_WIN
     h->grp_count += 1;
   } else {
     mark(h, st, -1);
@@ -1098,9 +1097,10 @@ void ring_backward_launch(adseq* h, hipStream_t st, long long T, float dscale, c
       }
     } else {
       for (long long n = k1 - 1; n >= k0; --n) {
-        if (d.alpha_r > 0.0f) hipLaunchKernelGGL((k_bwd_step_win<2>), gn, block, 0, st, n, T, dL_dcount, dL_dU, d);
-        else if (d.alpha_s > 0.0f) hipLaunchKernelGGL((k_bwd_step_win<1>), gn, block, 0, st, n, T, dL_dcount, dL_dU, d);
-        else hipLaunchKernelGGL((k_bwd_step_win<0>), gn, block, 0, st, n, T, dL_dcount, dL_dU, d);
+        if (d.alpha_r > 0.0f) hipLaunchKernelGGL((k_bwd_step_win<2, false>), gn, block, 0, st, n, T, dL_dcount, dL_dU, d);
+        else if (d.alpha_s > 0.0f) hipLaunchKernelGGL((k_bwd_step_win<1, false>), gn, block, 0, st, n, T, dL_dcount, dL_dU, d);
+        else if (d.lazy_rows) hipLaunchKernelGGL((k_bwd_step_win<0, true>), gn, block, 0, st, n, T, dL_dcount, dL_dU, d);
+        else hipLaunchKernelGGL((k_bwd_step_win<0, false>), gn, block, 0, st, n, T, dL_dcount, dL_dU, d);
       }
     }
     h->grp_count += nsteps;
@@ -1254,6 +1254,7 @@ int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, 
   d.dbg = getenv("ADSEQ_DBG") ? atoi(getenv("ADSEQ_DBG")) : 0;
 #endif
   d.count_pop = env_pow2("ADSEQ_RING_COUNT_POPPED", 0, 0, 1);
+  d.lazy_rows = env_pow2("ADSEQ_RING_LAZY_ROWS", 0, 0, 1);
   d.W = L.W; d.wshift = L.wshift; d.tp_shift = L.tp_shift; d.P = L.P; d.NB = L.NB; d.cap = L.cap;
   d.wgroups = L.wgroups;
   d.win = (int*)(ws + L.win);

@@ -202,9 +202,11 @@ __device__ __forceinline__ void count_popped(const Dev& d, long long v) {
 // counter: spikes and offered events are counted from the spike bits when a window closes.
 // SYN: synaptic current states (0: the jumps go into the membrane, 1: first-order synapse, 2: double-
 // exponential synapse, the slow and the fast state both take the jump and the current is their difference)
-// COUNT: the checking aid count_popped (a template parameter, so that the kernel that is timed reads
-// nothing more of its argument block than it did)
-template <bool RECORD, int SYN, bool COUNT>
+// MODE 1: the checking aid count_popped (a template parameter, so that the kernel that is timed reads
+// nothing more of its argument block than it did).  MODE 2: row start and in-window count are
+// fetched by the spiking lanes only (12 bytes per neuron less HBM traffic, one more memory round
+// trip between the spike and its fan-out).
+template <bool RECORD, int SYN, int MODE>
 __global__ __launch_bounds__(kBlock) void k_step_win(long long n, const float* __restrict__ i_ext,
                                                      unsigned char* __restrict__ spikes_out, Dev d) {
   pin_args(d.win, d.V, d.row_ptr, d.nearcnt, d.tapeU, d.spk_count, d.spike_bits, d.tape_bits, d.synf, d.J,
@@ -229,8 +231,10 @@ __global__ __launch_bounds__(kBlock) void k_step_win(long long n, const float* _
     popped = acc;
     // row start and in-window entry count of every neuron, loaded beside the pop so that a
     // spiking neuron's fan-out does not wait for them (both arrays stay in the L2)
-    r0 = d.row_ptr[i];
-    if (near_h >= 1) ncnt = d.nearcnt[(size_t)near_h * d.N + i];
+    if (MODE != 2) {
+      r0 = d.row_ptr[i];
+      if (near_h >= 1) ncnt = d.nearcnt[(size_t)near_h * d.N + i];
+    }
     const float v = d.V[g];
     const float jsyn = SYN ? d.J[g] : 0.0f;
     const float jfast = SYN == 2 ? d.J[(size_t)d.BN + g] : 0.0f;
@@ -254,6 +258,10 @@ __global__ __launch_bounds__(kBlock) void k_step_win(long long n, const float* _
     if (i_ext) I = I + i_ext[g];
     const float U = __fmaf_rn(d.alpha, v, I);
     s = U >= d.theta;
+    if (MODE == 2 && s) {
+      r0 = d.row_ptr[i];
+      if (near_h >= 1) ncnt = d.nearcnt[(size_t)near_h * d.N + i];
+    }
     // state and tape are written once per launch and not read again by it: non-temporal stores
     // leave no dirty lines behind for the end of the kernel to write back (2^20 cells: 8.8 -> 7.6 us)
     __builtin_nontemporal_store(s ? d.v_reset : U, &d.V[g]);
@@ -269,7 +277,7 @@ __global__ __launch_bounds__(kBlock) void k_step_win(long long n, const float* _
     d.spike_bits[(size_t)(n % d.R) * d.words + word] = bits;
     if (RECORD) d.tape_bits[(size_t)n * d.words + word] = bits;
   }
-  if (COUNT) count_popped(d, popped);
+  if (MODE == 1) count_popped(d, popped);
   // in-window events of the wavefront's spikes, up to four spikes at a time: the row loads of all
   // four are in flight before the first atomic, so that a wavefront with several spikes does not
   // pay one memory round trip per spike
@@ -998,7 +1006,9 @@ __device__ __forceinline__ float near_gather(const Dev& d, const float* __restri
 // (see bwd_update)
 // SYN: synaptic current states, as in k_step_win; 2 = double-exponential synapse: every gather
 // takes two adjoints, X for the weight and Y for the delay (see bwd_receiver)
-template <int SYN>
+// LAZY: row start, in-window count and far queue term are fetched by the spiking lanes only (16
+// bytes per neuron less HBM traffic, one more memory round trip before the gathers)
+template <int SYN, bool LAZY>
 __global__ __launch_bounds__(kBlock) void k_bwd_step_win(long long n, long long T,
                                                          const float* __restrict__ dL_dcount,
                                                          const float* __restrict__ dL_dU, Dev d) {
@@ -1024,15 +1034,22 @@ __global__ __launch_bounds__(kBlock) void k_bwd_step_win(long long n, long long 
     U = d.tapeU[(size_t)n * d.BN + g];
     if (d.surrogate == ADSEQ_GRAD_SPIKE_TIME && n > 0) Uprev = d.tapeU[(size_t)(n - 1) * d.BN + g];
     carry = d.bwd_carry[g];
-    r0 = d.row_ptr[i];
-    if (near_h >= 1) ncnt = d.nearcnt[(size_t)near_h * d.N + i];
     if (dL_dcount) inner = dL_dcount[g];
     if (dL_dU) dU = dL_dU[(size_t)n * d.BN + g];
-    // far queue term: only spiking neurons have one, but it is loaded for all so that it does
-    // not wait for the membrane value
+    // far queue term: only spiking neurons have one, but (unless LAZY) it is loaded for all so
+    // that it does not wait for the membrane value; the same for the row start and count
     float* ga = &d.Gacc[(size_t)(n % d.R) * d.BN + g];
-    G = *ga;
+    if (!LAZY) {
+      r0 = d.row_ptr[i];
+      if (near_h >= 1) ncnt = d.nearcnt[(size_t)near_h * d.N + i];
+      G = *ga;
+    }
     s = U >= d.theta;
+    if (LAZY && s) {
+      r0 = d.row_ptr[i];
+      if (near_h >= 1) ncnt = d.nearcnt[(size_t)near_h * d.N + i];
+      G = *ga;
+    }
     if (G != 0.0f) *ga = 0.0f;
   }
   // in-window part of the queue term of the wavefront's spikes, up to four spikes at a time (row

@@ -114,6 +114,17 @@ def test_ring_window_length_and_staging_capacity(window, stage, monkeypatch):
     assert ref.spikes.sum() > 300
 
 
+def test_ring_row_data_fetched_by_spiking_lanes_only(monkeypatch):
+    """ADSEQ_RING_LAZY_ROWS = 1: the step kernels load row start, in-window count and far queue
+    term for spiking lanes only (less traffic, one more round trip): same trace, counters, event
+    sets and gradients."""
+    monkeypatch.setenv("ADSEQ_RING_LAZY_ROWS", "1")
+    wl = synth.ragged_network(900, 300, 37, seed=15, rate_hz=300.0, t=150, b=3, w_mean=0.004, w_std=0.003)
+    ref, _ = _compare_forward(wl, oracle.RING, 0)
+    assert ref.spikes.sum() > 300
+    _compare_backward(wl, oracle.RING, 0, 150, 3)
+
+
 @pytest.mark.parametrize("rate_hz", [40.0, 80.0, 160.0])
 def test_ring_sparse_windows_take_atomics_block_by_block(rate_hz):
     """48,000 state cells (188 target parts) and a firing rate that climbs from zero: a block of
