@@ -236,6 +236,10 @@ __global__ __launch_bounds__(kResThreads) void k_xcd_stream(Sync* s, int* __rest
   if (rank == 0 && threadIdx.x == 0) s->ticks[0] = wall_clock64() - t0;
 }
 
+// MODE 0: every block adds to random cells of the whole array.  MODE 1: the blocks of XCD x add to
+// random cells of the x-th eighth only (no cell is touched by two XCDs).  (An atomic add of
+// workgroup scope compiles to the same instruction as one of agent scope: there is no third case.)
+template <int MODE>
 __global__ __launch_bounds__(kResThreads) void k_xcd_atomics(Sync* s, int* cells, unsigned M, int per, int only_xcc, int P) {
   __shared__ int s_rank;
   if (only_xcc >= 0 && (int)xcc_id() != only_xcc) return;
@@ -243,14 +247,22 @@ __global__ __launch_bounds__(kResThreads) void k_xcd_atomics(Sync* s, int* cells
   __syncthreads();
   const int rank = s_rank;
   if (rank >= P) return;
+  const unsigned slice = M / 8u, base = MODE ? (xcc_id() & 7u) * slice : 0u, span = MODE ? slice : M;
   const unsigned long long t0 = wall_clock64();
   for (int r = 0; r < per; ++r) {
     const unsigned e = ((unsigned)r * P + rank) * kResThreads + threadIdx.x;
-    atomicAdd(&cells[hash32(e * 2654435761u + 12345u) % M], 1);
+    int* cell = &cells[base + hash32(e * 2654435761u + 12345u) % span];
+    atomicAdd(cell, 1);
   }
   wait_vm();
   __syncthreads();
-  if (rank == 0 && threadIdx.x == 0) s->ticks[0] = wall_clock64() - t0;
+  if (threadIdx.x == 0) atomicMax((unsigned long long*)&s->ticks[0], (unsigned long long)(wall_clock64() - t0));
+}
+
+__global__ void k_sum_cells(const int* cells, unsigned M, unsigned long long* out) {
+  unsigned long long t = 0;
+  for (unsigned i = blockIdx.x * blockDim.x + threadIdx.x; i < M; i += gridDim.x * blockDim.x) t += (unsigned)cells[i];
+  atomicAdd(out, t);
 }
 
 // ---------------------------------------------------------------- host
@@ -459,24 +471,36 @@ static int resident_main() {
     CK(hipFree(src)); CK(hipFree(dst));
   }
 
-  printf("random atomic adds by the blocks of ONE XCD and of all (64 per thread):\n");
+  printf("random atomic adds by the blocks of ONE XCD and of all (64 per thread; time of the slowest block):\n");
   {
     const unsigned Ms[] = {200000u, 1600000u};
+    unsigned long long* total = nullptr;
+    CK(hipMalloc(&total, 8));
     for (unsigned M : Ms) {
       int* cells = nullptr;
-      CK(hipMalloc(&cells, (size_t)M * 4)); CK(hipMemset(cells, 0, (size_t)M * 4));
-      const int cfgs[][3] = {{256, 0, 32}, {256, -1, 256}};
+      CK(hipMalloc(&cells, (size_t)M * 4));
+      const int cfgs[][4] = {{256, 0, 32, 0}, {256, 0, 32, 1}, {256, -1, 256, 0}, {256, -1, 256, 1}};
+      const char* what[] = {"anywhere", "own eighth per XCD"};
       for (auto& g : cfgs) {
         if (res_reset(c)) return 1;
-        k_xcd_atomics<<<g[0], kResThreads>>>(c.s, cells, M, 64, g[1], g[2]);
+        CK(hipMemset(cells, 0, (size_t)M * 4)); CK(hipMemset(total, 0, 8));
+        if (g[3] == 0) k_xcd_atomics<0><<<g[0], kResThreads>>>(c.s, cells, M, 64, g[1], g[2]);
+        else k_xcd_atomics<1><<<g[0], kResThreads>>>(c.s, cells, M, 64, g[1], g[2]);
+        CK(hipDeviceSynchronize());
+        k_sum_cells<<<256, 256>>>(cells, M, total);
         CK(hipDeviceSynchronize());
         if (res_read(c)) return 1;
+        unsigned long long got = 0;
+        CK(hipMemcpy(&got, total, 8, hipMemcpyDeviceToHost));
+        const unsigned long long want = 64ull * g[2] * kResThreads;
         const double us = (double)c.h.ticks[0] * 0.01;
-        printf("  %.1f MB of cells, %3d blocks %-12s: %8.1f us, %6.2f G adds/s\n", M * 4 / 1e6, g[2],
-               g[1] >= 0 ? "of one XCD" : "(all XCDs)", us, 64.0 * g[2] * kResThreads / us / 1e3);
+        printf("  %.1f MB of cells, %3d blocks %-12s %-19s: %8.1f us, %6.2f G adds/s, sum of the cells %s\n", M * 4 / 1e6, g[2],
+               g[1] >= 0 ? "of one XCD," : "(all XCDs),", what[g[3]], us, 64.0 * g[2] * kResThreads / us / 1e3,
+               got == want ? "right" : "WRONG");
       }
       CK(hipFree(cells));
     }
+    CK(hipFree(total));
   }
   CK(hipFree(c.s));
   return 0;
