@@ -351,6 +351,9 @@ void run_trial(oracle_run& r, int b) {
     }
   }
   if (progress) fclose(progress);
+  if (b > 0)   // the other trials of a batch say when they are done
+    if (const char* path = getenv("ORACLE_PROGRESS_FILE"))
+      if (FILE* f = fopen(path, "a")) { fprintf(f, "oracle run: kind %d, N %d, trial %d of %d done\n", c.kind, N, b, B); fclose(f); }
   tr.in_flight = 0;
   while (!pq.empty()) {
     if (!latest || tr.admitted[pq.top().idx]) { tr.in_flight += 1; tr.sum_flight += r.a_q[pq.top().syn]; }
@@ -563,7 +566,12 @@ int oracle_backward(const oracle_run* r, const float* dL_dcount, const float* dL
   if (r->status != 0) return r->status;
   const int64_t S = r->cfg.n_synapses;
   std::vector<double> gw(S, 0.0), gd(S, 0.0);
-  for (int b = 0; b < r->cfg.batch; ++b) backward_trial(*r, b, dL_dcount, dL_dU, gw, gd, gU_out);
+  const char* path = r->cfg.batch > 1 ? getenv("ORACLE_PROGRESS_FILE") : nullptr;
+  for (int b = 0; b < r->cfg.batch; ++b) {
+    backward_trial(*r, b, dL_dcount, dL_dU, gw, gd, gU_out);
+    if (path)
+      if (FILE* f = fopen(path, "a")) { fprintf(f, "oracle reverse sweep: trial %d of %d done\n", b, r->cfg.batch); fclose(f); }
+  }
   std::memcpy(grad_w, gw.data(), sizeof(double) * S);
   std::memcpy(grad_d, gd.data(), sizeof(double) * S);
   return 0;

@@ -8,12 +8,16 @@ configuration bench.py times (same grids, same window length, same staging regio
   a stronger drive: 2.5e7 events, longer than the largest delay, so the spike history wraps);
 * config 2 (10,000 neurons x 1,000) over its 10,000 steps with the drive tuned for 5 Hz: ring,
   FIFO[8], FIFO[32]: membrane trace, counters, drop rate;
-* config 4 at its full batch (256 trials of 4,096 neurons: 2^20 state cells, the largest grids of
-  the step kernels) for 200 steps.
+* config 4 as it is written (256 trials of 4,096 neurons: 2^20 state cells, continuous delays,
+  5,000 steps, 10 Hz drive), sorted[128] and FIFO[32]: membrane trace (21 GB) bit for bit,
+  counters, spike counts, both gradients; and for 200 steps with stronger drives (the dense
+  routes of the kernels at this size).
 
-The oracle runs of the first three groups are started in background threads when the session
+The oracle runs of the first four groups are started in background threads when the session
 begins (tests/whole_refs.py); each test runs the GPU side first and then takes its reference.
 """
+import resource
+
 import numpy as np
 import pytest
 import torch
@@ -97,6 +101,45 @@ def test_cfg2_whole(name):
         assert (0.65 < drop < 0.80) if cap == 8 else (0.18 < drop < 0.32)
         assert sim.drop_count()["dropped"] == rc["dropped"]
     sim.close()
+
+
+@pytest.mark.parametrize("name", ["cfg4_sorted128_T5000", "cfg4_fifo32_T5000"])
+def test_cfg4_whole(name):
+    """Config 4 at its own size and length.  The trace is compared in slices of 250 steps (1 GB)."""
+    key, kind, cap, T, _ = whole_refs.JOBS[name]
+    wl = whole_refs.workload(key)
+    B, N = wl.batch, wl.n_neurons
+    print(f"{name}: GPU forward", flush=True)
+    spike_cap = 1 << 20     # (about 1.4e5 spikes and 3.5e7 events in the whole run)
+    sim = adseq.Adseq(wl, kind, cap, record_tape=True, max_steps=T, tape_spike_capacity=spike_cap,
+                      tape_event_capacity=spike_cap * wl.fan_out)
+    sim.run(0, T)
+    torch.cuda.synchronize()
+    print("waiting for the oracle run", flush=True)
+    ref = whole_refs.get(name)
+    U = sim.tape()["U"]
+    for n0 in range(0, T, 250):
+        got = U[n0:n0 + 250].cpu().numpy().view(np.uint32).reshape(-1)
+        want = ref["U"][n0:n0 + 250].view(np.uint32).reshape(-1)
+        assert np.array_equal(got, want), f"membrane trace differs in steps {n0}..{n0 + 249}"
+    c, rc = sim.counters(), ref["counters"]
+    for k in ("enqueued", "dropped", "delivered", "sum_enqueued", "sum_dropped", "sum_delivered"):
+        assert c[k] == rc[k], k
+    assert c["error_bits"] == 0 and rc["enqueued"] > 2e7
+    cnt = torch.empty(B * N, dtype=torch.int32, device=sim.dev)
+    sim.spike_counts(cnt)
+    np.testing.assert_array_equal(cnt.cpu().numpy(), ref["counts"].reshape(-1))
+    g_w = torch.full((wl.n_synapses,), 7.0, dtype=torch.float32, device=sim.dev)
+    g_d = torch.full((wl.n_synapses,), 7.0, dtype=torch.float32, device=sim.dev)
+    sim.backward(torch.from_numpy(ref["dL_dc"].reshape(-1)).to(sim.dev), None, g_w, g_d)
+    torch.cuda.synchronize()
+    H.grad_close(g_w.cpu().numpy(), ref["gw"])
+    H.grad_close(g_d.cpu().numpy(), ref["gd"])
+    assert np.abs(ref["gw"]).max() > 0 and np.abs(ref["gd"]).max() > 0
+    sim.close()
+    del ref
+    whole_refs.drop(name)
+    print(f"{name}: done, peak host memory of the test process {resource.getrusage(resource.RUSAGE_SELF).ru_maxrss / 2**20:.1f} GiB", flush=True)
 
 
 @pytest.mark.parametrize("kind,cap,drive_hz", [("ring", 0, 10.0), ("ring", 0, 100.0), ("fifo", 32, 250.0), ("sorted", 128, 10.0)])

@@ -4,8 +4,10 @@ One oracle run of the headline network over its 1,000 steps takes minutes on one
 through one priority queue), so all the long runs are started in background threads when the test
 session has collected that module (tests/conftest.py) and overlap with each other and with the
 GPU tests that come before; a test takes its reference with get(name), which waits for the run.
-Every run appends a line per 50 time steps to gpurun_out/oracle_progress.log (the oracle's own
-progress hook), so that a long wait is not mistaken for a hang."""
+Every run appends a line per 50 time steps of its first trial, and one per further trial, to
+gpurun_out/oracle_progress.log (the oracle's own progress hook), so that a long wait is not
+mistaken for a hang.  The two runs of config 4 (256 trials over 5,000 steps: 47 GB inside the
+oracle each) take turns in one worker of their own, with 16 threads over the trials."""
 import os
 import threading
 from concurrent.futures import ThreadPoolExecutor
@@ -20,6 +22,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 _lock = threading.Lock()
 _workloads = {}
 _pool = None
+_pool_batched = None
 _futures = {}
 
 # name -> (workload key, oracle kind, capacity, steps, gradients wanted)
@@ -31,6 +34,8 @@ JOBS = {
     "cfg2_ring_T10000": ("cfg2_5hz", oracle.RING, 0, 10000, False),
     "cfg2_fifo8_T10000": ("cfg2_5hz", oracle.FIFO, 8, 10000, False),
     "cfg2_fifo32_T10000": ("cfg2_5hz", oracle.FIFO, 32, 10000, False),
+    "cfg4_sorted128_T5000": ("cfg4", oracle.SORTED, 128, 5000, True),
+    "cfg4_fifo32_T5000": ("cfg4", oracle.FIFO, 32, 5000, True),
 }
 
 
@@ -43,6 +48,8 @@ def workload(key):
                 _workloads[key] = synth.cfg3(rate_hz=55.0, n_steps=300)
             elif key == "cfg2_5hz":      # config 2 with the drive tuned for 5 Hz
                 _workloads[key] = synth.cfg2(rate_hz=synth.CFG2_DRIVE_HZ[5])
+            elif key == "cfg4":          # config 4 as it is written: 256 trials, 5,000 steps, 10 Hz drive
+                _workloads[key] = synth.cfg4()
             else:
                 raise KeyError(key)
         return _workloads[key]
@@ -57,9 +64,13 @@ def dL_dcount(wl, counts):
 def _job(name):
     key, kind, cap, T, grads = JOBS[name]
     wl = workload(key)
-    ref = oracle.Run(wl, kind, cap, n_steps=T)
+    ref = oracle.Run(wl, kind, cap, n_steps=T, n_threads=16 if wl.batch > 1 else 1)
     out = dict(U=ref.U, counters=ref.counters())
-    counts = ref.spikes.sum(axis=0)
+    counts = np.zeros((wl.batch, wl.n_neurons), dtype=np.int64)
+    spikes = ref.spikes
+    for n0 in range(0, T, 256):     # (in slices: the sum of a 5 GB raster would widen it to 8 bytes per entry)
+        counts += spikes[n0:n0 + 256].sum(axis=0, dtype=np.int64)
+    del spikes
     out["counts"] = counts.astype(np.int32)
     if grads:
         out["dL_dc"] = dL_dcount(wl, counts)
@@ -70,15 +81,21 @@ def _job(name):
 
 def start(names=None):
     """Starts the oracle runs in background threads (once)."""
-    global _pool
+    global _pool, _pool_batched
     with _lock:
         if _pool is not None:
             return
         os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
         os.environ.setdefault("ORACLE_PROGRESS_FILE", os.path.join(ROOT, "gpurun_out", "oracle_progress.log"))
         _pool = ThreadPoolExecutor(max_workers=len(JOBS))
+        _pool_batched = ThreadPoolExecutor(max_workers=1)
     for name in (names or JOBS):
-        _futures[name] = _pool.submit(_job, name)
+        pool = _pool_batched if workload_batch(name) > 1 else _pool
+        _futures[name] = pool.submit(_job, name)
+
+
+def workload_batch(name):
+    return 256 if JOBS[name][0] == "cfg4" else 1
 
 
 def get(name):
@@ -86,3 +103,8 @@ def get(name):
     if name not in _futures:
         start([name])
     return _futures[name].result()
+
+
+def drop(name):
+    """Lets go of a reference that has been used (the large ones are tens of GB)."""
+    _futures.pop(name, None)
