@@ -233,23 +233,165 @@ int prepare_synapses(oracle_run& r) {
   return 0;
 }
 
+using EventQueue = std::priority_queue<Event, std::vector<Event>, Later>;
+
+// Queue discipline of kinds 0-2: one queue per TARGET neuron.  Kind 0 (ring) is unbounded; kinds 1
+// (FIFO) and 2 (sorted) hold at most `capacity` events per target and refuse a newcomer while
+// full (Section 4.3, "FIFORing": incoming spikes are dropped when the queue is full).  Both deliver
+// at the arrival step, so the exact priority queue serves them; only the occupancy count differs
+// from the ring.
+struct TargetQueues {
+  const oracle_run& r; const bool bounded; const int b;
+  std::vector<int32_t> occ;   // events held per target
+  TargetQueues(const oracle_run& run, int trial)
+      : r(run), bounded(run.cfg.kind != 0), b(trial), occ((size_t)run.cfg.n_neurons, 0) {}
+  // an event comes up at its arrival step: true = it is delivered
+  bool arrive(Trial&, const Event& e) { occ[r.cfg.col[e.syn]] -= 1; return true; }
+  // synapse p offers an event emitted at step n that arrives at step k
+  void offer(Trial& tr, EventQueue& pq, int64_t p, int32_t n, int32_t k) {
+    const oracle_config& c = r.cfg;
+    const size_t j = (size_t)c.col[p];
+    if (bounded && occ[j] >= c.capacity) {
+      tr.admitted.push_back(0);
+      tr.n_dropped += 1; tr.sum_drop += r.a_q[p];
+      if (c.log_events) tr.dropped.add(p, n, k, b);
+      return;
+    }
+    tr.admitted.push_back(1);
+    occ[j] += 1;
+    tr.max_occ = std::max(tr.max_occ, occ[j]);
+    pq.push(Event{k, p, n, (int64_t)tr.admitted.size() - 1});
+  }
+  bool counts_at_end(const Trial&, const Event&) const { return true; }
+};
+
+// Queue disciplines of kinds 3-5: one queue per SYNAPSE (Section 4.3, the per-synapse variants).
+// Kind 3: a FIFO of `capacity` events per synapse, a full one refuses the newcomer.
+// Kinds 4 and 5: the newest event replaces the one held in its slot, and the replaced one is
+// lost: kind 4 has one slot per synapse, kind 5 `capacity` bins chosen by arrival step mod capacity.
+// A replaced event stays in the priority queue with its admission flag cleared and is skipped
+// when it comes up.
+struct SynapseQueues {
+  const oracle_run& r; const int b;
+  const bool latest; const int nbins;
+  std::vector<int32_t> occ;      // kind 3: events held per synapse
+  std::vector<int64_t> held;     // kinds 4, 5: admission flag of the event held per (synapse, bin), -1 = none
+  std::vector<int32_t> held_n;   // its emission step
+  SynapseQueues(const oracle_run& run, int trial)
+      : r(run), b(trial), latest(run.cfg.kind == 4 || run.cfg.kind == 5),
+        nbins(run.cfg.kind == 5 ? run.cfg.capacity : 1),
+        occ(latest ? (size_t)0 : (size_t)run.cfg.n_synapses, 0),
+        held(latest ? (size_t)run.cfg.n_synapses * nbins : 0, -1),
+        held_n(latest ? (size_t)run.cfg.n_synapses * nbins : 0, 0) {}
+  bool arrive(Trial& tr, const Event& e) {
+    if (latest) {
+      if (!tr.admitted[e.idx]) return false;     // it was replaced while in transit
+      held[(size_t)e.syn * nbins + e.k % nbins] = -1;
+    } else {
+      occ[(size_t)e.syn] -= 1;
+    }
+    return true;
+  }
+  void offer(Trial& tr, EventQueue& pq, int64_t p, int32_t n, int32_t k) {
+    const oracle_config& c = r.cfg;
+    if (latest) {
+      const size_t hb = (size_t)p * nbins + k % nbins;
+      if (held[hb] >= 0) {                 // the event held there so far is lost
+        tr.admitted[held[hb]] = 0;
+        tr.n_dropped += 1; tr.sum_drop += r.a_q[p];
+        if (c.log_events) tr.dropped.add(p, held_n[hb], held_n[hb] + r.D[p], b);
+      }
+      held[hb] = (int64_t)tr.admitted.size(); held_n[hb] = n;
+      tr.admitted.push_back(1);
+      tr.max_occ = std::max(tr.max_occ, 1);
+      pq.push(Event{k, p, n, held[hb]});
+      return;
+    }
+    if (occ[(size_t)p] >= c.capacity) {
+      tr.admitted.push_back(0);
+      tr.n_dropped += 1; tr.sum_drop += r.a_q[p];
+      if (c.log_events) tr.dropped.add(p, n, k, b);
+      return;
+    }
+    tr.admitted.push_back(1);
+    occ[(size_t)p] += 1;
+    tr.max_occ = std::max(tr.max_occ, occ[(size_t)p]);
+    pq.push(Event{k, p, n, (int64_t)tr.admitted.size() - 1});
+  }
+  bool counts_at_end(const Trial& tr, const Event& e) const { return !latest || tr.admitted[e.idx]; }
+};
+
+// State of one trial's neurons between steps: membrane value and the synaptic current state(s),
+// in fp32 (the arithmetic the method is compared in) and in fp64 (exact_f64 runs).
+struct NeuronState {
+  std::vector<float> V, J, J2;
+  std::vector<double> V64, J64, J264;
+  explicit NeuronState(int N) : V(N, 0.0f), J(N, 0.0f), J2(N, 0.0f), V64(N, 0.0), J64(N, 0.0), J264(N, 0.0) {}
+};
+
+// Steps (2) and (3) of a time step for every neuron of trial b: drive, synapse model, leaky
+// integration, threshold and reset (Section 2.1 eqs. 1-3 on the grid of Section 3.2 eqs. 10-11).
+// acc / acc64: what step (1) popped for each neuron (Q8.24 sum / exact sum).  Records the tape
+// row and appends the neurons that spiked to `fired` in ascending order.
+void step_neurons(oracle_run& r, int b, int n, const std::vector<int32_t>& acc, const std::vector<double>& acc64,
+                  NeuronState& st, std::vector<int32_t>& fired) {
+  const oracle_config& c = r.cfg;
+  const int N = c.n_neurons, B = c.batch;
+  const bool exact = c.exact_f64 != 0;
+  const bool dexp = c.tau_rise_ms > 0.0f;          // two states A = J, B = J2; isyn = A - B
+  const bool syn_state = c.tau_syn_ms > 0.0f;
+  const size_t base = ((size_t)n * B + b) * N;
+  std::vector<float>& V = st.V; std::vector<float>& J = st.J; std::vector<float>& J2 = st.J2;
+  std::vector<double>& V64 = st.V64; std::vector<double>& J64 = st.J64; std::vector<double>& J264 = st.J264;
+  fired.clear();
+  for (int j = 0; j < N; ++j) {
+    const bool xi = (uint64_t)drive_bits(c.seed, (uint64_t)b * N + j, (uint64_t)n) < r.p_thresh;
+    bool s;
+    if (!exact) {
+      float I = (float)acc[j] * 0x1p-24f;
+      if (dexp) {
+        const float jump = I;
+        J[j] = std::fmaf(r.alpha_s_f, J[j], jump); J2[j] = std::fmaf(r.alpha_r_f, J2[j], jump);
+        I = J[j] - J2[j];
+      } else if (syn_state) { I = std::fmaf(r.alpha_s_f, J[j], I); J[j] = I; }   // isyn = alpha_s isyn + jumps
+      I = I + (xi ? c.ext_weight : 0.0f);
+      if (c.i_ext) I = I + c.i_ext[base + j];
+      const float u = std::fmaf(r.alpha_f, V[j], I);
+      s = c.forced_spikes ? (c.forced_spikes[base + j] != 0) : (u >= c.v_thresh);
+      V[j] = s ? c.v_reset : u;
+      r.U[base + j] = u; r.I[base + j] = I;
+    } else {
+      double I = acc64[j];
+      if (dexp) {
+        const double jump = I;
+        J64[j] = r.alpha_s_d * J64[j] + jump; J264[j] = r.alpha_r_d * J264[j] + jump;
+        I = J64[j] - J264[j];
+      } else if (syn_state) { I = r.alpha_s_d * J64[j] + I; J64[j] = I; }
+      I += xi ? (double)c.ext_weight : 0.0;
+      if (c.i_ext) I += (double)c.i_ext[base + j];
+      const double u = r.alpha_d * V64[j] + I;
+      s = c.forced_spikes ? (c.forced_spikes[base + j] != 0) : (u >= (double)c.v_thresh);
+      V64[j] = s ? (double)c.v_reset : u;
+      r.U64[base + j] = u; r.U[base + j] = (float)u; r.I[base + j] = (float)I;
+    }
+    r.S[base + j] = s ? 1 : 0;
+    if (c.keep_currents) r.Iq[base + j] = acc[j];
+    if (s) fired.push_back(j);
+  }
+}
+
+// One trial, forward: the event-driven simulation with one exact priority queue keyed by
+// (arrival step, synapse).  Per time step: (1) pop every event whose arrival step is n, (2) drive
+// and (3) LIF for every neuron, (4) fan the step's spikes out in ascending (source, row position)
+// order, each synapse offering its event to the queue discipline Q.
+template <class Q>
 void run_trial(oracle_run& r, int b) {
   const oracle_config& c = r.cfg;
   const int N = c.n_neurons, T = c.n_steps, B = c.batch;
-  const bool bounded = c.kind != 0;
-  const bool exact = c.exact_f64 != 0;
   Trial& tr = r.trials[b];
-  std::priority_queue<Event, std::vector<Event>, Later> pq;
-  const bool per_syn = c.kind == 3;   // occupancy counted per synapse instead of per target
-  const bool latest = c.kind == 4 || c.kind == 5;   // the newest event replaces the one held in its slot / bin
-  const int nbins = c.kind == 5 ? c.capacity : 1;    // kind 4: one slot; kind 5: bin = arrival step mod capacity
-  std::vector<int64_t> held(latest ? (size_t)c.n_synapses * nbins : 0, -1);   // admission flag of the held event
-  std::vector<int32_t> held_n(latest ? (size_t)c.n_synapses * nbins : 0, 0);
-  std::vector<int32_t> occ(per_syn ? (size_t)c.n_synapses : (latest ? (size_t)0 : (size_t)N), 0);
-  std::vector<float> V(N, 0.0f), J(N, 0.0f), J2(N, 0.0f);   // membrane state, synaptic current state(s)
-  std::vector<double> V64(N, 0.0), J64(N, 0.0), J264(N, 0.0);
-  const bool dexp = c.tau_rise_ms > 0.0f;          // two states A = J, B = J2; isyn = A - B
-  const bool syn_state = c.tau_syn_ms > 0.0f;
+  EventQueue pq;
+  Q queues(r, b);
+  NeuronState state(N);
   std::vector<int32_t> acc(N);
   std::vector<double> acc64(N);
   std::vector<int32_t> fired;
@@ -262,91 +404,27 @@ void run_trial(oracle_run& r, int b) {
 
   for (int n = 0; n < T; ++n) {
     if (progress && n % 50 == 0) { fprintf(progress, "oracle run: kind %d, N %d, step %d of %d\n", c.kind, N, n, T); fflush(progress); }
-    const size_t base = ((size_t)n * B + b) * N;
     // (1) pop every event whose arrival step is n
     std::fill(acc.begin(), acc.end(), 0);
     std::fill(acc64.begin(), acc64.end(), 0.0);
     while (!pq.empty() && pq.top().k == n) {
       const Event e = pq.top(); pq.pop();
-      if (latest) {
-        if (!tr.admitted[e.idx]) continue;     // it was replaced while in transit
-        held[(size_t)e.syn * nbins + e.k % nbins] = -1;
-      }
+      if (!queues.arrive(tr, e)) continue;
       const int j = c.col[e.syn];
       acc[j] = (int32_t)((uint32_t)acc[j] + (uint32_t)r.a_q[e.syn]);  // wrapping add
       acc64[j] += r.a_d[e.syn];
-      if (!latest) occ[per_syn ? (size_t)e.syn : (size_t)j] -= 1;
       tr.n_delivered += 1; tr.sum_deliv += r.a_q[e.syn];
       if (c.log_events) tr.delivered.add(e.syn, e.n_emit, e.k, b);
     }
     // (2) drive and (3) LIF
-    fired.clear();
-    for (int j = 0; j < N; ++j) {
-      const bool xi = (uint64_t)drive_bits(c.seed, (uint64_t)b * N + j, (uint64_t)n) < r.p_thresh;
-      bool s;
-      if (!exact) {
-        float I = (float)acc[j] * 0x1p-24f;
-        if (dexp) {
-          const float jump = I;
-          J[j] = std::fmaf(r.alpha_s_f, J[j], jump); J2[j] = std::fmaf(r.alpha_r_f, J2[j], jump);
-          I = J[j] - J2[j];
-        } else if (syn_state) { I = std::fmaf(r.alpha_s_f, J[j], I); J[j] = I; }   // isyn = alpha_s isyn + jumps
-        I = I + (xi ? c.ext_weight : 0.0f);
-        if (c.i_ext) I = I + c.i_ext[base + j];
-        const float u = std::fmaf(r.alpha_f, V[j], I);
-        s = c.forced_spikes ? (c.forced_spikes[base + j] != 0) : (u >= c.v_thresh);
-        V[j] = s ? c.v_reset : u;
-        r.U[base + j] = u; r.I[base + j] = I;
-      } else {
-        double I = acc64[j];
-        if (dexp) {
-          const double jump = I;
-          J64[j] = r.alpha_s_d * J64[j] + jump; J264[j] = r.alpha_r_d * J264[j] + jump;
-          I = J64[j] - J264[j];
-        } else if (syn_state) { I = r.alpha_s_d * J64[j] + I; J64[j] = I; }
-        I += xi ? (double)c.ext_weight : 0.0;
-        if (c.i_ext) I += (double)c.i_ext[base + j];
-        const double u = r.alpha_d * V64[j] + I;
-        s = c.forced_spikes ? (c.forced_spikes[base + j] != 0) : (u >= (double)c.v_thresh);
-        V64[j] = s ? (double)c.v_reset : u;
-        r.U64[base + j] = u; r.U[base + j] = (float)u; r.I[base + j] = (float)I;
-      }
-      r.S[base + j] = s ? 1 : 0;
-      if (c.keep_currents) r.Iq[base + j] = acc[j];
-      if (s) fired.push_back(j);
-    }
+    step_neurons(r, b, n, acc, acc64, state, fired);
     // (4) fan out the spikes of this step in ascending (source, row position) order
     for (int i : fired) {
       SpikeRec rec{n, i, (int64_t)tr.admitted.size()};
       tr.spikes.push_back(rec);
       for (int64_t p = c.row_ptr[i]; p < c.row_ptr[i + 1]; ++p) {
-        const int j = c.col[p];
-        const int32_t k = n + r.D[p];
         tr.enqueued += 1; tr.sum_enq += r.a_q[p];
-        if (latest) {
-          const size_t hb = (size_t)p * nbins + k % nbins;
-          if (held[hb] >= 0) {                 // the event held there so far is lost
-            tr.admitted[held[hb]] = 0;
-            tr.n_dropped += 1; tr.sum_drop += r.a_q[p];
-            if (c.log_events) tr.dropped.add(p, held_n[hb], held_n[hb] + r.D[p], b);
-          }
-          held[hb] = (int64_t)tr.admitted.size(); held_n[hb] = n;
-          tr.admitted.push_back(1);
-          tr.max_occ = std::max(tr.max_occ, 1);
-          pq.push(Event{k, p, n, held[hb]});
-          continue;
-        }
-        const size_t oi = per_syn ? (size_t)p : (size_t)j;
-        if (bounded && occ[oi] >= c.capacity) {
-          tr.admitted.push_back(0);
-          tr.n_dropped += 1; tr.sum_drop += r.a_q[p];
-          if (c.log_events) tr.dropped.add(p, n, k, b);
-          continue;
-        }
-        tr.admitted.push_back(1);
-        occ[oi] += 1;
-        tr.max_occ = std::max(tr.max_occ, occ[oi]);
-        pq.push(Event{k, p, n, (int64_t)tr.admitted.size() - 1});
+        queues.offer(tr, pq, p, n, n + r.D[p]);
       }
     }
   }
@@ -356,9 +434,14 @@ void run_trial(oracle_run& r, int b) {
       if (FILE* f = fopen(path, "a")) { fprintf(f, "oracle run: kind %d, N %d, trial %d of %d done\n", c.kind, N, b, B); fclose(f); }
   tr.in_flight = 0;
   while (!pq.empty()) {
-    if (!latest || tr.admitted[pq.top().idx]) { tr.in_flight += 1; tr.sum_flight += r.a_q[pq.top().syn]; }
+    if (queues.counts_at_end(tr, pq.top())) { tr.in_flight += 1; tr.sum_flight += r.a_q[pq.top().syn]; }
     pq.pop();
   }
+}
+
+void run_trial(oracle_run& r, int b) {
+  if (r.cfg.kind <= 2) run_trial<TargetQueues>(r, b);
+  else run_trial<SynapseQueues>(r, b);
 }
 
 // Reverse-time sweep for one trial; adds this trial's contribution to gw, gd.
