@@ -50,6 +50,9 @@ def main():
     ap.add_argument("--no-fifo-leg", action="store_true", help="skip the FIFO[32] comparison leg of the default workload")
     ap.add_argument("--graph-forward", action="store_true",
                     help="also time the forward run replayed from a captured HIP graph (reported as graph_forward_ms)")
+    ap.add_argument("--phase-clocks", action="store_true",
+                    help="run on the library built with phase clocks (python -m paper_2512_05906_amd.build --phase-clocks) "
+                         "and add the phases of the ring's window expansion to the line; a diagnostic, not a bench line")
     ap.add_argument("--cpu-sample-events", type=float, default=4e7)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -59,7 +62,13 @@ def main():
 
     import numpy as np
     import torch
-    from paper_2512_05906_amd import adseq, build, synth
+    from paper_2512_05906_amd import build
+
+    if args.phase_clocks:
+        if not os.path.exists(build.LIB_PHASE):
+            build.build_library(phase_clocks=True)
+        os.environ["ADSEQ_LIB"] = build.LIB_PHASE
+    from paper_2512_05906_amd import adseq, synth
 
     if not os.path.exists(build.LIB):   # load what is built; build only if nothing is
         build.build_library()
@@ -110,6 +119,18 @@ def main():
     wall = time.perf_counter() - t0
     fwd_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
     bwd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+    phase_clocks = None
+    if args.phase_clocks and kind == adseq.RING:
+        import ctypes
+        ticks = (ctypes.c_uint64 * 24)()
+        rc = sim.lib.adseq_debug_phase_clocks(sim.h, ticks, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+        assert rc == 0, rc
+        names = ["staging: walk over the spike words", "staging: counters", "staging: piece offsets", "staging: row loads + counting in LDS",
+                 "staging: scan", "staging: ordering in LDS", "staging: run stores", "staging: cursors", "accumulation: counters + clearing the tile",
+                 "accumulation: run loads + adds in LDS", "accumulation: tile to window"]
+        nwin = max(1, int(ticks[15]))
+        # (the counters are cleared by adseq_reset: these are the expansions of the last forward run, block 0 of each launch)
+        phase_clocks = {"windows": nwin, "us_per_window": {nm: round(ticks[i] * 0.01 / nwin, 3) for i, nm in enumerate(names)}}
     c = sim.counters()
     assert c["error_bits"] == 0, c
     delivered, offered, dropped = c["delivered"], c["enqueued"], c["dropped"]
@@ -228,6 +249,8 @@ def main():
                      "frac_of_measured_copy": kernels[dom]["achieved_GBs"] / copy_gbs if copy_gbs else None},
         "kernels": kernels,
     }
+    if phase_clocks:
+        out["phase_clocks"] = phase_clocks
 
     if args.graph_forward:
         # The forward run (reset + T steps) captured once into a HIP graph and replayed: what graph

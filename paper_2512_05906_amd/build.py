@@ -18,8 +18,19 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_library(verbose: bool = False) -> str:
+LIB_PHASE = os.path.join(HERE, "libadseq_phase.so")
+
+
+def build_library(verbose: bool = False, phase_clocks: bool = False) -> str:
+    """phase_clocks: a second library, libadseq_phase.so, whose window expansion and resident step
+    kernels clock their phases (bench.py --phase-clocks reads them); the product library has none."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    if phase_clocks:
+        cmd = [hipcc] + HIPCC_FLAGS + ["-DADSEQ_PHASE_CLOCK", "-o", LIB_PHASE, SRC]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.check_call(cmd)
+        return LIB_PHASE
     cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB, SRC]
     if verbose:
         print(" ".join(cmd), flush=True)
@@ -46,6 +57,10 @@ def build_chip_rates() -> str:
 
 
 if __name__ == "__main__":
+    import sys
+    if "--phase-clocks" in sys.argv[1:]:
+        print(build_library(verbose=True, phase_clocks=True))
+        sys.exit(0)
     print(build_library(verbose=True))
     print(build_copy_reference())
     print(build_chip_rates())

@@ -55,7 +55,8 @@ struct Counters {
   unsigned long long fold[3];       // scratch of k_count_spikes: spikes, events, Q8.24 sum
   alignas(128) unsigned bar[32];    // bar[0]: arrivals at the barriers of the resident step kernels (a line of its own)
 #ifdef ADSEQ_PHASE_CLOCK
-  unsigned long long phase[8];      // debugging builds: 10 ns ticks block 0 spent in each phase of the resident steps
+  unsigned long long phase[24];     // builds with phase clocks: 10 ns ticks block 0 spent in each phase; [0, 8) resident steps or
+                                    // staging pass of the window expansion, [8, 11) accumulation pass, [15] expansions counted
 #endif
 };
 
@@ -648,6 +649,7 @@ bool make_layout(const adseq_config* c, Layout* L) {
     if (!c->step_event_capacity) ev = ev < 65536.0 ? 65536.0 : (ev > 67108864.0 ? 67108864.0 : ev);
     const double per = ev / ((double)stage_parts * (double)L->NB);
     L->cap = (int)(per > 65536.0 ? 65536.0 : per);
+    if (L->cap >= 16) L->cap &= ~15;   // regions begin on 128-byte lines: a run's first 16 events are one line
   }
   L->ctr = take(sizeof(Counters));
   L->blk = take(bounded ? ((size_t)L->nblk + fan_slots(L->nblk) + (synq ? kSynqBlocks : 0)) * sizeof(BlkCtr)
@@ -1680,5 +1682,16 @@ int adseq_profile_read(adseq_t* h, double* ms4, int64_t* launches4, void* stream
 }
 
 const char* adseq_last_error(const adseq_t* h) { return h ? h->err : "null handle"; }
+
+#ifdef ADSEQ_PHASE_CLOCK
+// Builds with phase clocks only (python -m paper_2512_05906_amd.build --phase-clocks; not part of
+// the C ABI): the 24 tick counters (10 ns each) of the phases, see Counters.
+int adseq_debug_phase_clocks(adseq_t* h, uint64_t* out24, void* stream) {
+  if (!h || !out24) return ADSEQ_E_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  if (hipMemcpyAsync(out24, h->dev.ctr->phase, sizeof(unsigned long long) * 24, hipMemcpyDeviceToHost, st) != hipSuccess) return ADSEQ_E_HIP;
+  return hipStreamSynchronize(st) == hipSuccess ? ADSEQ_OK : ADSEQ_E_HIP;
+}
+#endif
 
 }  // extern "C"

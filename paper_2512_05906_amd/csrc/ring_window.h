@@ -390,6 +390,22 @@ __global__ __launch_bounds__(kBlock) void k_open_step_win(Dev d, long long n, co
 
 // ---------------------------------------------------------------- forward: window expansion
 
+// Phase clocks of the expansion (builds with ADSEQ_PHASE_CLOCK only): thread 0 of block 0 adds the
+// 10 ns ticks since the last mark to Counters::phase[i].
+#ifdef ADSEQ_PHASE_CLOCK
+#define XPH_BEGIN unsigned long long xpt = wall_clock64();
+#define XPH_ARG , unsigned long long& xpt
+#define XPH_PASS , xpt
+#define XPH(i) { if (blockIdx.x == 0 && threadIdx.x == 0) { const unsigned long long t_ = wall_clock64(); d.ctr->phase[i] += t_ - xpt; xpt = t_; } }
+#define XPH_COUNT(i) { if (blockIdx.x == 0 && threadIdx.x == 0) d.ctr->phase[i] += 1; }
+#else
+#define XPH_BEGIN
+#define XPH_ARG
+#define XPH_PASS
+#define XPH(i)
+#define XPH_COUNT(i)
+#endif
+
 // Streaming loads of the expansion and gather passes (row pieces and staged events are read
 // once per pass): non-temporal, so that they do not push the window out of the L2.  (The staging
 // stores stay ordinary: as non-temporal 8-byte stores they reach memory one by one, 2.6x slower.)
@@ -602,7 +618,7 @@ __device__ __forceinline__ int block_scan_excl(int v, int* s_w, int* total) {
 // Ordered staging of the pieces L.q[0, qn): see SortLds.  L.cur[part] stays the cursor of the
 // part's staging region (the pieces that overflowed the queue during the walk used it too).
 __device__ __forceinline__ void stage_sorted(const Dev& d, ExpandLds& L, SortLds& S, int* __restrict__ win,
-                                             int nparts, int vb, int qn) {
+                                             int nparts, int vb, int qn XPH_ARG) {
   const int t = threadIdx.x;
   int total = 0;
   {
@@ -613,6 +629,7 @@ __device__ __forceinline__ void stage_sorted(const Dev& d, ExpandLds& L, SortLds
     if (t < kSortParts) S.cnt[t] = 0;
   }
   __syncthreads();
+  XPH(2)
   const unsigned lmask = (1u << d.tp_shift) - 1u;
   constexpr int kPer = kSortChunk / kRingThreads;
   for (int c0 = 0; c0 < total; c0 += kSortChunk) {
@@ -624,6 +641,7 @@ __device__ __forceinline__ void stage_sorted(const Dev& d, ExpandLds& L, SortLds
       for (; (b << 6) < p_hi; ++b) S.map[b - (c0 >> 6)] = t;
     }
     __syncthreads();
+    XPH(2)
     // A: this thread's events of the chunk (all row entries requested before the first is used):
     // piece, row entry, part, rank within (chunk, part)
     uint2 e[kPer]; int dlo[kPer], tb[kPer];
@@ -656,6 +674,7 @@ __device__ __forceinline__ void stage_sorted(const Dev& d, ExpandLds& L, SortLds
       }
     }
     __syncthreads();
+    XPH(3)
     // B: positions of the parts in the chunk and in their staging regions
     {
       const int c = t < nparts ? S.cnt[t] : 0;
@@ -670,11 +689,13 @@ __device__ __forceinline__ void stage_sorted(const Dev& d, ExpandLds& L, SortLds
       if (t == 0) S.base[nparts] = tot;
     }
     __syncthreads();
+    XPH(4)
     // C: order the chunk by part
 #pragma unroll
     for (int m = 0; m < kPer; ++m)
       if (pr[m] >= 0) S.ev[S.base[w0[m] >> 16] + pr[m]] = make_uint2(w0[m], e[m].y);
     __syncthreads();
+    XPH(5)
     // D: write the runs
     const int staged = S.base[nparts];
     for (int x = t; x < staged; x += kRingThreads) {
@@ -691,6 +712,7 @@ __device__ __forceinline__ void stage_sorted(const Dev& d, ExpandLds& L, SortLds
       }
     }
     __syncthreads();
+    XPH(6)
   }
 }
 
@@ -707,6 +729,7 @@ __device__ __forceinline__ void role_bin(const Dev& d, ExpandLds& L, SortLds& S,
   for (int x = threadIdx.x; x < nparts; x += kRingThreads) L.cur[x] = 0;
   if (threadIdx.x == 0) { L.qn = 0; L.qhead = 0; L.qlen = 0; }
   __syncthreads();
+  XPH_BEGIN
   const int lane = threadIdx.x & 63;
   auto one = [&](const Seg& o) {
     for (int q = lane; q < o.len; q += 64) {
@@ -716,6 +739,7 @@ __device__ __forceinline__ void role_bin(const Dev& d, ExpandLds& L, SortLds& S,
   };
   long long cnt[3] = {0, 0, 0};
   walk_segments(d, L, d.spike_bits, true, k0, n_lo, n_hi, -1, vb, nvb, count_from, cnt, one);
+  XPH(0)
   // counters first: their atomics complete while the events are staged
   if (count_from < n_hi) fold_counts(d, L, cnt, vb);
   const int qn = L.qn < kSegQueue ? L.qn : kSegQueue;
@@ -733,9 +757,10 @@ __device__ __forceinline__ void role_bin(const Dev& d, ExpandLds& L, SortLds& S,
     __syncthreads();
     if (L.qn <= kSegQueue && L.qlen < nparts) nparts = 0;   // uniform over the block
   }
+  XPH(1)
   const bool staged = nparts > 0;
   if (stage == 2 && nparts > 0 && nparts <= kSortParts) {
-    stage_sorted(d, L, S, win, nparts, vb, qn);
+    stage_sorted(d, L, S, win, nparts, vb, qn XPH_PASS);
   } else {
     for (;;) {
       int t = 0;
@@ -768,6 +793,8 @@ __device__ __forceinline__ void role_bin(const Dev& d, ExpandLds& L, SortLds& S,
     }
   }
   __syncthreads();
+  XPH(7)
+  XPH_COUNT(15)
   // (the counters are zero when the pass begins: the accumulation pass clears what it has read)
   if (staged)
     for (int x = threadIdx.x; x < nparts; x += kRingThreads) {
@@ -784,12 +811,14 @@ __device__ __forceinline__ void role_acc(const Dev& d, int* tile, long long k0, 
   const int cells = d.W << d.tp_shift;
   const int nb_runs = d.NB;
   int* __restrict__ cnts = d.ecnt + (size_t)part * nb_runs;
+  XPH_BEGIN
   // nothing staged for this part (its blocks of pass 1 chose atomics, or had no event for it):
   // leave before the tile is touched
   int any = 0;
   for (int x = threadIdx.x; x < nb_runs; x += kRingThreads) any |= cnts[x];
   for (int x = threadIdx.x; x < cells; x += kRingThreads) tile[x] = 0;
   if (!__syncthreads_or(any)) return;
+  XPH(8)
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int sub = lane & 15, grp = lane >> 4;
   for (int r0 = (wv * 4 + grp) * 4; r0 < nb_runs; r0 += kRingWaves * 16) {
@@ -812,6 +841,7 @@ __device__ __forceinline__ void role_acc(const Dev& d, int* tile, long long k0, 
     }
   }
   __syncthreads();
+  XPH(9)
   const int tp = 1 << d.tp_shift;
   int* __restrict__ win = win_of(d, k0);
   for (int x = threadIdx.x; x < cells; x += kRingThreads) {
@@ -822,6 +852,10 @@ __device__ __forceinline__ void role_acc(const Dev& d, int* tile, long long k0, 
     // that nobody waits for a load
     if (v != 0 && t < d.BN) atomicAdd(&win[(size_t)r * d.BN + t], v);
   }
+#ifdef ADSEQ_PHASE_CLOCK
+  __syncthreads();
+  XPH(10)
+#endif
 }
 
 // The two passes of the expansion as kernels.
