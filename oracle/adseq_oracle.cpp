@@ -72,6 +72,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <queue>
+#include <string>
 #include <thread>
 #include <vector>
 
@@ -102,6 +103,7 @@ struct oracle_config {
   float tau_rise_ms;           // > 0 (needs tau_syn_ms > tau_rise_ms and integer delays): double-exponential
                                // synapse built from two such states (Section 3.2, closing remark): A with
                                // tau_syn_ms, B with tau_rise_ms, both take every jump, isyn = A - B
+  const char* progress_file;   // NULL, or a file that long runs append progress lines to (copied at the call)
 };
 
 }  // extern "C"
@@ -198,6 +200,7 @@ struct oracle_run {
   std::vector<int32_t> Iq; std::vector<float> I;
   std::vector<Trial> trials;
   EventLog delivered, dropped;  // all trials concatenated
+  std::string progress_file;    // empty: no progress lines
 };
 
 namespace {
@@ -396,11 +399,12 @@ void run_trial(oracle_run& r, int b) {
   std::vector<double> acc64(N);
   std::vector<int32_t> fired;
 
-  // Long runs say how far they are: a line per 50 steps of trial 0 appended to the file named by
-  // ORACLE_PROGRESS_FILE, if set (a run of the largest configuration takes minutes).
+  // Long runs say how far they are: a line per 50 steps of trial 0 appended to the progress file
+  // of the call, if it names one (a run of the largest configuration takes minutes).  (The path
+  // comes with the call and not from the environment: reading the environment here, in a thread,
+  // while another thread of the process changes it is a crash waiting to happen.)
   FILE* progress = nullptr;
-  if (b == 0)
-    if (const char* path = getenv("ORACLE_PROGRESS_FILE")) progress = fopen(path, "a");
+  if (b == 0 && !r.progress_file.empty()) progress = fopen(r.progress_file.c_str(), "a");
 
   for (int n = 0; n < T; ++n) {
     if (progress && n % 50 == 0) { fprintf(progress, "oracle run: kind %d, N %d, step %d of %d\n", c.kind, N, n, T); fflush(progress); }
@@ -429,9 +433,8 @@ void run_trial(oracle_run& r, int b) {
     }
   }
   if (progress) fclose(progress);
-  if (b > 0)   // the other trials of a batch say when they are done
-    if (const char* path = getenv("ORACLE_PROGRESS_FILE"))
-      if (FILE* f = fopen(path, "a")) { fprintf(f, "oracle run: kind %d, N %d, trial %d of %d done\n", c.kind, N, b, B); fclose(f); }
+  if (b > 0 && !r.progress_file.empty())   // the other trials of a batch say when they are done
+    if (FILE* f = fopen(r.progress_file.c_str(), "a")) { fprintf(f, "oracle run: kind %d, N %d, trial %d of %d done\n", c.kind, N, b, B); fclose(f); }
   tr.in_flight = 0;
   while (!pq.empty()) {
     if (queues.counts_at_end(tr, pq.top())) { tr.in_flight += 1; tr.sum_flight += r.a_q[pq.top().syn]; }
@@ -555,6 +558,8 @@ extern "C" {
 oracle_run* oracle_forward(const oracle_config* cfg) {
   oracle_run* r = new oracle_run();
   r->cfg = *cfg;
+  if (cfg->progress_file) r->progress_file = cfg->progress_file;
+  r->cfg.progress_file = nullptr;   // (the caller's string need not outlive the call)
   const oracle_config& c = r->cfg;
   if (c.n_neurons < 1 || c.batch < 1 || c.n_steps < 0 || c.d_max_steps < 1 ||
       (c.kind != 0 && c.capacity < 1) || c.kind < 0 || c.kind > 5 ||
@@ -649,11 +654,11 @@ int oracle_backward(const oracle_run* r, const float* dL_dcount, const float* dL
   if (r->status != 0) return r->status;
   const int64_t S = r->cfg.n_synapses;
   std::vector<double> gw(S, 0.0), gd(S, 0.0);
-  const char* path = r->cfg.batch > 1 ? getenv("ORACLE_PROGRESS_FILE") : nullptr;
+  const bool say = r->cfg.batch > 1 && !r->progress_file.empty();
   for (int b = 0; b < r->cfg.batch; ++b) {
     backward_trial(*r, b, dL_dcount, dL_dU, gw, gd, gU_out);
-    if (path)
-      if (FILE* f = fopen(path, "a")) { fprintf(f, "oracle reverse sweep: trial %d of %d done\n", b, r->cfg.batch); fclose(f); }
+    if (say)
+      if (FILE* f = fopen(r->progress_file.c_str(), "a")) { fprintf(f, "oracle reverse sweep: trial %d of %d done\n", b, r->cfg.batch); fclose(f); }
   }
   std::memcpy(grad_w, gw.data(), sizeof(double) * S);
   std::memcpy(grad_d, gd.data(), sizeof(double) * S);

@@ -41,6 +41,7 @@ class _Cfg(C.Structure):
         ("i_ext", C.c_void_p), ("forced_spikes", C.c_void_p),
         ("log_events", C.c_int32), ("keep_currents", C.c_int32), ("n_threads", C.c_int32),
         ("tau_syn_ms", C.c_float), ("tau_rise_ms", C.c_float),
+        ("progress_file", C.c_char_p),
     ]
 
 
@@ -126,7 +127,9 @@ class Run:
                    forced_spikes=_ptr(k["forced"]), log_events=int(log_events),
                    keep_currents=int(keep_currents), n_threads=n_threads,
                    tau_syn_ms=float(getattr(wl, "tau_syn_ms", 0.0)),
-                   tau_rise_ms=float(getattr(wl, "tau_rise_ms", 0.0)))
+                   tau_rise_ms=float(getattr(wl, "tau_rise_ms", 0.0)),
+                   # (read from Python's own copy of the environment: the C side never calls getenv)
+                   progress_file=(os.environ.get("ORACLE_PROGRESS_FILE") or "").encode() or None)
         self._exact = bool(exact_f64)
         self._keep_currents = keep_currents
         self._h = L.oracle_forward(C.byref(cfg))

@@ -34,6 +34,9 @@ JOBS = {
     "cfg2_ring_T10000": ("cfg2_5hz", oracle.RING, 0, 10000, False),
     "cfg2_fifo8_T10000": ("cfg2_5hz", oracle.FIFO, 8, 10000, False),
     "cfg2_fifo32_T10000": ("cfg2_5hz", oracle.FIFO, 32, 10000, False),
+    "cfg2_20hz_ring_T10000": ("cfg2_20hz", oracle.RING, 0, 10000, False),
+    "cfg2_20hz_fifo8_T10000": ("cfg2_20hz", oracle.FIFO, 8, 10000, False),
+    "cfg2_20hz_fifo32_T10000": ("cfg2_20hz", oracle.FIFO, 32, 10000, False),
     "cfg4_sorted128_T5000": ("cfg4", oracle.SORTED, 128, 5000, True),
     "cfg4_fifo32_T5000": ("cfg4", oracle.FIFO, 32, 5000, True),
 }
@@ -48,6 +51,8 @@ def workload(key):
                 _workloads[key] = synth.cfg3(rate_hz=55.0, n_steps=300)
             elif key == "cfg2_5hz":      # config 2 with the drive tuned for 5 Hz
                 _workloads[key] = synth.cfg2(rate_hz=synth.CFG2_DRIVE_HZ[5])
+            elif key == "cfg2_20hz":     # ... and for 20 Hz
+                _workloads[key] = synth.cfg2(rate_hz=synth.CFG2_DRIVE_HZ[20])
             elif key == "cfg4":          # config 4 as it is written: 256 trials, 5,000 steps, 10 Hz drive
                 _workloads[key] = synth.cfg4()
             else:
