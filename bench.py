@@ -129,8 +129,19 @@ def main():
                  "staging: scan", "staging: ordering in LDS", "staging: run stores", "staging: cursors", "accumulation: counters + clearing the tile",
                  "accumulation: run loads + adds in LDS", "accumulation: tile to window"]
         nwin = max(1, int(ticks[15]))
-        # (the counters are cleared by adseq_reset: these are the expansions of the last forward run, block 0 of each launch)
+        # (block 0 of each launch; the expansions of the last forward run from step 512 on, where the spike history is full)
         phase_clocks = {"windows": nwin, "us_per_window": {nm: round(ticks[i] * 0.01 / nwin, 3) for i, nm in enumerate(names)}}
+        spans = (ctypes.c_uint64 * 2048)()
+        assert sim.lib.adseq_debug_block_spans(sim.h, spans, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)) == 0
+        sp = np.array(spans[:], dtype=np.float64).reshape(2, 512, 2)
+        for k, nm in enumerate(("staging", "accumulation")):   # blocks of the last launch of each pass: when they began and ended
+            on = sp[k][:, 1] > 0
+            if on.any():
+                t0 = sp[k][on, 0].min()
+                phase_clocks[nm + "_blocks_last_launch_us"] = {
+                    "blocks": int(on.sum()), "last_begin": round((sp[k][on, 0].max() - t0) * 0.01, 2),
+                    "first_end": round((sp[k][on, 1].min() - t0) * 0.01, 2), "median_end": round((np.median(sp[k][on, 1]) - t0) * 0.01, 2),
+                    "last_end": round((sp[k][on, 1].max() - t0) * 0.01, 2)}
     c = sim.counters()
     assert c["error_bits"] == 0, c
     delivered, offered, dropped = c["delivered"], c["enqueued"], c["dropped"]

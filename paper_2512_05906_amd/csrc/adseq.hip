@@ -57,6 +57,7 @@ struct Counters {
 #ifdef ADSEQ_PHASE_CLOCK
   unsigned long long phase[24];     // builds with phase clocks: 10 ns ticks block 0 spent in each phase; [0, 8) resident steps or
                                     // staging pass of the window expansion, [8, 11) accumulation pass, [15] expansions counted
+  unsigned long long span[2][512][2]; // the same builds: wall clock at begin and end of every block of the last staging [0] and accumulation [1] launch
 #endif
 };
 
@@ -904,6 +905,10 @@ void ring_open_window(adseq* h, hipStream_t st, long long k0) {
   if ((k0 & (long long)(d.W - 1)) != 0 || k0 <= 0) return;
   close_group(h, st, 1);
   mark(h, st, -1);
+#ifdef ADSEQ_PHASE_CLOCK
+  // the phase clocks cover the windows from step 512 on (the spike history is full by then)
+  if (k0 == 512) fill_u32(st, reinterpret_cast<unsigned*>(d.ctr->phase), 0u, 48);
+#endif
   long long n_lo = k0 - d.d_max > 0 ? k0 - d.d_max : 0;
   static const int overlap = env_pow2("ADSEQ_RING_OVERLAP", 0, 0, 1);
   const bool ahead = overlap && h->res_P == 0;
@@ -1690,6 +1695,13 @@ int adseq_debug_phase_clocks(adseq_t* h, uint64_t* out24, void* stream) {
   if (!h || !out24) return ADSEQ_E_INVALID_ARG;
   hipStream_t st = (hipStream_t)stream;
   if (hipMemcpyAsync(out24, h->dev.ctr->phase, sizeof(unsigned long long) * 24, hipMemcpyDeviceToHost, st) != hipSuccess) return ADSEQ_E_HIP;
+  return hipStreamSynchronize(st) == hipSuccess ? ADSEQ_OK : ADSEQ_E_HIP;
+}
+// The block spans of the last staging and accumulation launch: out[2][512][2] ticks.
+int adseq_debug_block_spans(adseq_t* h, uint64_t* out, void* stream) {
+  if (!h || !out) return ADSEQ_E_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  if (hipMemcpyAsync(out, h->dev.ctr->span, sizeof(unsigned long long) * 2 * 512 * 2, hipMemcpyDeviceToHost, st) != hipSuccess) return ADSEQ_E_HIP;
   return hipStreamSynchronize(st) == hipSuccess ? ADSEQ_OK : ADSEQ_E_HIP;
 }
 #endif

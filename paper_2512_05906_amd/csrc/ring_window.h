@@ -398,12 +398,14 @@ __global__ __launch_bounds__(kBlock) void k_open_step_win(Dev d, long long n, co
 #define XPH_PASS , xpt
 #define XPH(i) { if (blockIdx.x == 0 && threadIdx.x == 0) { const unsigned long long t_ = wall_clock64(); d.ctr->phase[i] += t_ - xpt; xpt = t_; } }
 #define XPH_COUNT(i) { if (blockIdx.x == 0 && threadIdx.x == 0) d.ctr->phase[i] += 1; }
+#define XPH_SPAN(k, e) { if (threadIdx.x == 0 && blockIdx.x < 512) d.ctr->span[k][blockIdx.x][e] = wall_clock64(); }
 #else
 #define XPH_BEGIN
 #define XPH_ARG
 #define XPH_PASS
 #define XPH(i)
 #define XPH_COUNT(i)
+#define XPH_SPAN(k, e)
 #endif
 
 // Streaming loads of the expansion and gather passes (row pieces and staged events are read
@@ -864,7 +866,9 @@ __global__ __launch_bounds__(kRingThreads) void k_win_bin(Dev d, long long k0, l
                                                           int vb0, int nvb, int stage, long long count_from, int clear_other) {
   __shared__ ExpandLds L;
   __shared__ SortLds S;
+  XPH_SPAN(0, 0)
   role_bin(d, L, S, k0, n_lo, n_hi, vb0 + (int)blockIdx.x, nvb, stage, count_from);
+  XPH_SPAN(0, 1)
   // The other window buffer -- the one the steps before k0 have just used up -- is zeroed here, a
   // slice per block, for the expansion that fills it next: the resident step kernels do not clear
   // the cells they pop (their one XCD would spend a fifth of a step on those stores), and the
@@ -885,7 +889,9 @@ __global__ __launch_bounds__(kRingThreads) void k_win_bin(Dev d, long long k0, l
 }
 __global__ __launch_bounds__(kRingThreads) void k_win_acc(Dev d, long long k0, int p0) {
   __shared__ int tile[kMaxTileCells];
+  XPH_SPAN(1, 0)
   role_acc(d, tile, k0, p0 + (int)blockIdx.x);
+  XPH_SPAN(1, 1)
 }
 
 // Spikes of steps [n_lo, n_hi) (still in the circular spike words), their events and the Q8.24
