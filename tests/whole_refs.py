@@ -5,7 +5,7 @@ through one priority queue), so all the long runs are started in background thre
 session has collected that module (tests/conftest.py) and overlap with each other and with the
 GPU tests that come before; a test takes its reference with get(name), which waits for the run.
 Every run appends a line per 50 time steps of its first trial, and one per further trial, to
-gpurun_out/oracle_progress.log (the oracle's own progress hook), so that a long wait is not
+the progress log in the run's output folder (the oracle's own progress hook), so that a long wait is not
 mistaken for a hang.  The two runs of config 4 (256 trials over 5,000 steps: 47 GB inside the
 oracle each) take turns in one worker of their own, with 16 threads over the trials."""
 import os
