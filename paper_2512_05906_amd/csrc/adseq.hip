@@ -165,6 +165,7 @@ struct Dev {
   BlkCtr* blk;   // FIFO / SORTED: [nblk + kFanoutBlocks]
   // (what was added later stays behind what the per-step kernels read, whose place in the argument block is tuned)
   long long* insum;     // [N] create only: sum of |Q8.24 amplitude| over every target's incoming synapses
+  int res_spins;        // RING, resident kernels: polls of one wait before it gives up (kResMaxSpins; ADSEQ_RING_RESIDENT_SPINS lowers it to test the failure path)
   int lazy_rows;        // RING: the step kernels fetch row start, in-window count and far queue term for spiking lanes only (experiment)
   int count_pop;        // RING: the step kernels add up the Q8.24 sums they pop (checking aid, off by default)
 #if defined(ADSEQ_PHASE_CLOCK) || defined(ADSEQ_ABLATE)
@@ -1262,6 +1263,7 @@ int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, 
 #endif
   d.count_pop = env_pow2("ADSEQ_RING_COUNT_POPPED", 0, 0, 1);
   d.lazy_rows = env_pow2("ADSEQ_RING_LAZY_ROWS", 0, 0, 1);
+  d.res_spins = env_pow2("ADSEQ_RING_RESIDENT_SPINS", kResMaxSpins, 1, kResMaxSpins);
   d.W = L.W; d.wshift = L.wshift; d.tp_shift = L.tp_shift; d.P = L.P; d.NB = L.NB; d.cap = L.cap;
   d.wgroups = L.wgroups;
   d.win = (int*)(ws + L.win);

@@ -23,7 +23,7 @@ constexpr int kResThreads = 512;      // two wavefronts per SIMD: a step is boun
                                       // and by how many row loads of the step's spikes are in flight at once
 constexpr int kResBlocks = 32;        // taking-part blocks at most: the compute units of one XCD
 constexpr int kResStride = 8;         // XCDs: block b runs on XCD b mod 8
-constexpr int kResMaxSpins = 1 << 16;  // polls of one wait before it gives up (tens of ms; a step takes microseconds)
+constexpr int kResMaxSpins = 1 << 16;  // polls of one wait before it gives up (tens of ms; a step takes microseconds); Dev::res_spins, lowered only by tests of the failure path
 constexpr int kResLaunch = kResThreads + 64;   // one more wavefront per block that only synchronises: it
                                                // polls the barrier counter and adds the block's arrival, so that
                                                // a poll never waits behind the stores of a wavefront that has neurons
@@ -54,7 +54,7 @@ __device__ __forceinline__ void res_wait(const Dev& d, unsigned target, int* dea
   if (threadIdx.x == kResThreads && !*dead) {
     int spins = 0;
     while ((int)(ld_agent(&d.ctr->bar[0]) - target) < 0) {
-      if (++spins > kResMaxSpins) { atomicOr(&d.ctr->err, ERR_BARRIER); *dead = 1; break; }
+      if (++spins > d.res_spins) { atomicOr(&d.ctr->err, ERR_BARRIER); *dead = 1; break; }
     }
   }
   __syncthreads();

@@ -165,3 +165,28 @@ def test_range_warning_for_sums_that_could_wrap():
         sim.run(0, 5)
         assert sim.counters()["error_bits"] & 64
         sim.close()
+
+
+def test_resident_wait_that_runs_out_is_reported(monkeypatch):
+    """Failure path of the resident kernels' bounded waits, forced from the host: with a limit of
+    one poll per wait (ADSEQ_RING_RESIDENT_SPINS=1) the 32 blocks do not wait for one another, every
+    kernel still runs to its end, the error word carries bit 32, and adseq_drop_count and
+    adseq_backward refuse the run; a reset clears the state, and a handle with the ordinary limit
+    gives the oracle's result on the same network."""
+    wl = synth.ragged_network(5000, 30, 20, seed=21, rate_hz=700.0, t=60, b=20, w_mean=0.02, w_std=0.01)
+    monkeypatch.setenv("ADSEQ_RING_RESIDENT_SPINS", "1")
+    sim = adseq.Adseq(wl, adseq.RING, 0, record_tape=True, max_steps=60)
+    sim.run(0, 60)
+    torch.cuda.synchronize()
+    assert sim.counters()["error_bits"] & 32
+    with pytest.raises(adseq.AdseqError):
+        sim.drop_count()
+    g = torch.empty(wl.n_synapses, device=sim.dev)
+    with pytest.raises(adseq.AdseqError):
+        sim.backward(torch.zeros(20 * 5000, device=sim.dev), None, g, g.clone())
+    sim.reset()
+    assert sim.counters()["error_bits"] == 0
+    sim.close()
+    monkeypatch.delenv("ADSEQ_RING_RESIDENT_SPINS")
+    ref = _check(wl, 60, 20, [60])
+    assert ref.spikes.sum() > 100
