@@ -10,6 +10,8 @@
 // Every wait is a bounded spin.  A wait that runs out sets Sync::err and the block stops
 // waiting for the rest of the kernel, so every block reaches the end whatever happens.
 
+#include <hip/hip_ext.h>
+
 constexpr int kResThreads = 1024;
 constexpr int kMaxSpins = 1 << 16;
 
@@ -265,6 +267,28 @@ __global__ void k_sum_cells(const int* cells, unsigned M, unsigned long long* ou
   atomicAdd(out, t);
 }
 
+// ---------------------------------------------------------------- a chain of launches without the queue's barrier
+// Kernel k of a chain: one thread per block waits (bounded, and not at all once a wait has run
+// out) until all nblk blocks of kernel k - 1 have arrived on the per-XCD counters, then the block
+// arrives itself.  Launched in stream order these waits are over at once; launched with
+// hipExtAnyOrderLaunch the queue may start kernel k while k - 1 still runs, so that the launch
+// overhead would hide behind the kernel before -- where the flag is honoured.
+__global__ __launch_bounds__(256) void k_chain(Sync* s, unsigned k, unsigned nblk) {
+  if (threadIdx.x == 0 && k > 0 && !__hip_atomic_load(&s->err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
+    const unsigned target = k * nblk;
+    int spins = 0;
+    for (;;) {
+      unsigned sum = 0;
+#pragma unroll
+      for (int x = 0; x < 8; ++x) sum += __hip_atomic_load(&s->xc[x][0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if ((int)(sum - target) >= 0) break;
+      if (++spins > kMaxSpins) { atomicOr(&s->err, 1u); break; }
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) atomicAdd(&s->xc[xcc_id() & 7u][0], 1u);
+}
+
 // ---------------------------------------------------------------- host
 static const char* kBits[] = {"none", "sc0", "sc1", "sc0 sc1", "nt"};
 
@@ -501,6 +525,28 @@ static int resident_main() {
       CK(hipFree(cells));
     }
     CK(hipFree(total));
+  }
+  printf("chain of 1000 dependent kernels, 391 x 256 threads, each waiting in its first thread for the arrivals of the one before:\n");
+  for (int any = 0; any < 2; ++any) {
+    if (res_reset(c)) return 1;
+    const unsigned nblk = 391;
+    for (int rep = 0; rep < 2; ++rep) {
+      if (res_reset(c)) return 1;
+      CK(hipEventRecord(c.e0));
+      for (unsigned k = 0; k < 1000; ++k) {
+        if (any) hipExtLaunchKernelGGL(k_chain, dim3(nblk), dim3(256), 0, 0, nullptr, nullptr, hipExtAnyOrderLaunch, c.s, k, nblk);
+        else k_chain<<<nblk, 256>>>(c.s, k, nblk);
+      }
+      CK(hipEventRecord(c.e1));
+      CK(hipDeviceSynchronize());
+    }
+    float ms = 0;
+    CK(hipEventElapsedTime(&ms, c.e0, c.e1));
+    if (res_read(c)) return 1;
+    unsigned total = 0;
+    for (int x = 0; x < 8; ++x) total += c.h.xc[x][0];
+    printf("  %-44s: %6.2f us per kernel%s, arrivals %s\n", any ? "launched with hipExtAnyOrderLaunch" : "launched in stream order",
+           ms, c.h.err ? " (A WAIT RAN OUT)" : "", total == 1000u * nblk ? "complete" : "INCOMPLETE");
   }
   CK(hipFree(c.s));
   return 0;
