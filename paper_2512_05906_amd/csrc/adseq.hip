@@ -54,6 +54,7 @@ struct Counters {
   unsigned long long in_flight[2];  // scratch of k_ring_in_flight: events, Q8.24 sum
   unsigned long long fold[3];       // scratch of k_count_spikes: spikes, events, Q8.24 sum
   alignas(128) unsigned bar[32];    // bar[0]: arrivals at the barriers of the resident step kernels (a line of its own)
+  alignas(128) unsigned arrive[8][32];  // arrive[x][0]: blocks with index x mod 8 of the chained step launches that have arrived (ring_chain.h)
 #ifdef ADSEQ_PHASE_CLOCK
   unsigned long long phase[24];     // builds with phase clocks: 10 ns ticks block 0 spent in each phase; [0, 8) resident steps or
                                     // staging pass of the window expansion, [8, 11) accumulation pass, [15] expansions counted
@@ -168,6 +169,7 @@ struct Dev {
   int res_spins;        // RING, resident kernels: polls of one wait before it gives up (kResMaxSpins; ADSEQ_RING_RESIDENT_SPINS lowers it to test the failure path)
   int lazy_rows;        // RING: the step kernels fetch row start, in-window count and far queue term for spiking lanes only (experiment)
   int count_pop;        // RING: the step kernels add up the Q8.24 sums they pop (checking aid, off by default)
+  int chain_sleep;      // RING, chained step launches: pauses of 128 cycles between two polls of a wait
 #if defined(ADSEQ_PHASE_CLOCK) || defined(ADSEQ_ABLATE)
   int dbg;              // debugging builds: parts of the resident step to leave out (timing only)
 #endif
@@ -378,6 +380,7 @@ __global__ __launch_bounds__(kBlock) void k_in_check(Dev d) {
 #include "ring_window.h"
 #include "ring_resident.h"
 #include "ring_reverse.h"
+#include "ring_chain.h"
 
 // ---------------------------------------------------------------- backward (FIFO / SORTED)
 
@@ -505,6 +508,13 @@ struct adseq {
   hipStream_t aux = nullptr;
   hipEvent_t ev_boundary = nullptr, ev_ahead = nullptr;
   long long ahead_for = -1;   // window start whose far part (spikes before the previous boundary) is being expanded ahead, or -1
+  // RING, chained step launches (ring_chain.h): dealt out over the caller's stream and one of the library's own
+  bool chain = false;         // the handle's runs and reverse sweeps use them
+  hipStream_t chain_st = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  unsigned chain_arrivals = 0;   // arrivals of all chained launches so far (what the next one waits for)
+  unsigned chain_turn = 0;       // chained launches so far: the parity picks the stream
+  int chain_tpb = 256;           // threads per block of the chained launches (256 or 1024)
   bool range_warn = false;    // some target's incoming |amplitudes| add up to 128 or more (ERR_RANGE, reported with the counters)
   bool in_static = false;     // the handle is the device's static one (adseq_create_static): never deleted
 };
@@ -776,6 +786,7 @@ void launch_reset(adseq* h, hipStream_t st) {
   h->ahead_for = -1;
   h->fold_upto = 0;
   h->bar_base = 0;   // (the counter itself is cleared with the other counters)
+  h->chain_arrivals = 0;   // (likewise)
   h->drive_from = h->drive_upto = 0;
   const size_t BN = (size_t)d.BN;
   fill_u32(st, d.ctr, 0u, sizeof(Counters) / 4);
@@ -1057,6 +1068,59 @@ void ring_run_resident(adseq* h, hipStream_t st, long long step0, long long n_st
   }
 }
 
+// RING, chained step launches (ring_chain.h): the step launches go to the caller's stream and to a
+// stream of the library's own in turn and wait for one another themselves.  The stream and the two
+// events are made at the first use.
+bool chain_ready(adseq* h) {
+  if (h->chain_st) return true;
+  hipStream_t s = nullptr;
+  hipEvent_t a = nullptr, b = nullptr;
+  if (hipStreamCreateWithFlags(&s, hipStreamNonBlocking) != hipSuccess) return false;
+  if (hipEventCreateWithFlags(&a, hipEventDisableTiming) != hipSuccess) { (void)hipStreamDestroy(s); return false; }
+  if (hipEventCreateWithFlags(&b, hipEventDisableTiming) != hipSuccess) { (void)hipEventDestroy(a); (void)hipStreamDestroy(s); return false; }
+  h->chain_st = s; h->ev_fork = a; h->ev_join = b;
+  return true;
+}
+// The library's stream goes on from where `st` is now / `st` goes on when the library's stream is done.
+void chain_fork(adseq* h, hipStream_t st) {
+  (void)hipEventRecord(h->ev_fork, st);
+  (void)hipStreamWaitEvent(h->chain_st, h->ev_fork, 0);
+}
+void chain_join(adseq* h, hipStream_t st) {
+  (void)hipEventRecord(h->ev_join, h->chain_st);
+  (void)hipStreamWaitEvent(st, h->ev_join, 0);
+}
+hipStream_t chain_next_stream(adseq* h, hipStream_t st) { return (h->chain_turn++ & 1u) ? h->chain_st : st; }
+
+// RING: steps step0 .. step0 + n_steps - 1 as chained launches.  At a window boundary both streams
+// meet: the expansion runs on `st` after everything before it and before everything after it.
+void ring_run_chain(adseq* h, hipStream_t st, long long step0, long long n_steps) {
+  const Dev& d = h->dev;
+  const dim3 grid((unsigned)d.nblk), block(kBlock);
+  bool forked = false;
+  for (long long n = step0; n < step0 + n_steps; ++n) {
+    if ((n & (long long)(d.W - 1)) == 0 && n > 0 && forked) { chain_join(h, st); forked = false; }
+    ring_open_window(h, st, n);
+    open_group(h, st);
+    if (!forked) { chain_fork(h, st); forked = true; }
+    const bool record = d.record && h->tape_ok && n < d.max_steps;
+    if (d.record && n >= d.max_steps) h->tape_ok = false;
+    hipStream_t s = chain_next_stream(h, st);
+    if (h->chain_tpb == 1024) {
+      const dim3 g4((unsigned)((d.BN + 1023) / 1024)), b4(1024);
+      if (record) hipLaunchKernelGGL((k_step_chain<true, 1024>), g4, b4, 0, s, n, h->chain_arrivals, d);
+      else hipLaunchKernelGGL((k_step_chain<false, 1024>), g4, b4, 0, s, n, h->chain_arrivals, d);
+      h->chain_arrivals += g4.x - (unsigned)d.nblk;
+    } else if (record) hipLaunchKernelGGL((k_step_chain<true, 256>), grid, block, 0, s, n, h->chain_arrivals, d);
+    else hipLaunchKernelGGL((k_step_chain<false, 256>), grid, block, 0, s, n, h->chain_arrivals, d);
+    h->chain_arrivals += (unsigned)d.nblk;
+    h->grp_count += 1;
+    h->enq_calls += 1;
+    h->next_step = n + 1;
+  }
+  if (forked) chain_join(h, st);
+}
+
 // RING: virtual blocks of one far gather over the spikes of steps [n_lo, n_hi): about four
 // 8-word lines per wavefront.
 int gather_blocks(const Dev& d, long long n_lo, long long n_hi) {
@@ -1104,6 +1168,20 @@ void ring_backward_launch(adseq* h, hipStream_t st, long long T, float dscale, c
         }
       }
     } else {
+      if (h->chain && chain_ready(h)) {
+        chain_fork(h, st);
+        for (long long n = k1 - 1; n >= k0; --n) {
+          if (h->chain_tpb == 1024) {
+            const dim3 g4((unsigned)((d.BN + 1023) / 1024));
+            hipLaunchKernelGGL((k_bwd_step_chain<1024>), g4, dim3(1024), 0, chain_next_stream(h, st), n, T, h->chain_arrivals, dL_dcount, dL_dU, d);
+            h->chain_arrivals += g4.x;
+          } else {
+            hipLaunchKernelGGL((k_bwd_step_chain<256>), gn, block, 0, chain_next_stream(h, st), n, T, h->chain_arrivals, dL_dcount, dL_dU, d);
+            h->chain_arrivals += (unsigned)d.nblk;
+          }
+        }
+        chain_join(h, st);
+      } else
       for (long long n = k1 - 1; n >= k0; --n) {
         if (d.alpha_r > 0.0f) hipLaunchKernelGGL((k_bwd_step_win<2, false>), gn, block, 0, st, n, T, dL_dcount, dL_dU, d);
         else if (d.alpha_s > 0.0f) hipLaunchKernelGGL((k_bwd_step_win<1, false>), gn, block, 0, st, n, T, dL_dcount, dL_dU, d);
@@ -1312,6 +1390,15 @@ int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, 
   if (d.kind == ADSEQ_RING) {
     const ResidentPlan rp = resident_plan((long long)d.BN);
     h->res_chunk = rp.chunk; h->res_P = rp.P; h->res_npt = rp.npt;
+    // chained step launches (ring_chain.h; experimental, off by default: measured slower than a launch per step on
+    // one stream): delta synapse, and two launches' blocks must fit the chip side by side (512 blocks each at
+    // most).  ADSEQ_RING_CHAIN = 1: wherever that holds (instead of the resident kernels too).  The static handle
+    // makes no stream of its own.
+    const int chain = env_pow2("ADSEQ_RING_CHAIN", 0, 0, 1);
+    h->chain = chain && !h->in_static && !(d.alpha_s > 0.0f) && !d.count_pop && !d.lazy_rows && d.nblk <= 512;
+    if (h->chain) h->res_P = 0;
+    h->chain_tpb = env_pow2("ADSEQ_RING_CHAIN_THREADS", 256, 256, 1024) == 1024 ? 1024 : 256;
+    d.chain_sleep = env_pow2("ADSEQ_RING_CHAIN_SLEEP", 1, 0, 64);
   }
   hipStream_t st = (hipStream_t)cfg->stream;
   launch_reset(h, st);
@@ -1373,6 +1460,11 @@ extern "C" {
 
 int adseq_destroy(adseq_t* h) {
   if (!h) return ADSEQ_E_INVALID_ARG;
+  if (h->chain_st) {
+    (void)hipStreamSynchronize(h->chain_st);
+    (void)hipStreamDestroy(h->chain_st); (void)hipEventDestroy(h->ev_fork); (void)hipEventDestroy(h->ev_join);
+    h->chain_st = nullptr;
+  }
   if (h->aux) {
     (void)hipStreamSynchronize(h->aux);
     (void)hipStreamDestroy(h->aux); (void)hipEventDestroy(h->ev_boundary); (void)hipEventDestroy(h->ev_ahead);
@@ -1478,6 +1570,8 @@ int adseq_run(adseq_t* h, int64_t step0, int64_t n_steps, void* stream) {
     return fail(h, ADSEQ_E_ORDER, "adseq_run: got step %lld, expected %lld", (long long)step0, h->next_step);
   if (h->dev.kind == ADSEQ_RING && h->res_P > 0) {
     ring_run_resident(h, (hipStream_t)stream, step0, n_steps);
+  } else if (h->dev.kind == ADSEQ_RING && h->chain && n_steps >= 2 && chain_ready(h)) {
+    ring_run_chain(h, (hipStream_t)stream, step0, n_steps);
   } else {
     for (int64_t n = 0; n < n_steps; ++n) {
       const int rc = step_impl(h, step0 + n, nullptr, nullptr, (hipStream_t)stream);

@@ -11,6 +11,7 @@
 // dependent-access latencies, and what one XCD alone streams and scatters.  Every wait is a
 // bounded spin: a wait that runs out sets an error word, and the blocks go on to the end.
 #include <hip/hip_runtime.h>
+#include <chrono>
 
 #include <cstdio>
 #include <cstdlib>
@@ -47,6 +48,11 @@ __global__ void k_random(int* arr, unsigned M, size_t n_ops, int per) {
   if ((MODE == 1 || MODE == 3) && acc == 0x7fffffff) arr[0] = acc;
 }
 
+// Holds the stream for `ticks` of the 100 MHz wall clock (a bounded wait by construction).
+__global__ void k_hold(unsigned long long ticks) {
+  const unsigned long long t0 = wall_clock64();
+  while (wall_clock64() - t0 < ticks) __builtin_amdgcn_s_sleep(32);
+}
 __global__ void k_empty(int* p) { if (p && threadIdx.x == 9999) p[0] = 1; }
 
 // Dense neuron step as a stream: per neuron one cell (int) and one state (float) read, the state
@@ -128,9 +134,11 @@ static int run(const char* name, int* arr, unsigned M, size_t n_ops, unsigned gr
 }
 
 #include "resident_rates.h"
+#include "exchange_rates.h"
 
 int main(int argc, char** argv) {
   if (argc > 1 && strcmp(argv[1], "resident") == 0) return resident_main();
+  if (argc > 1 && strcmp(argv[1], "exchange") == 0) return exchange_main();
   hipEvent_t e0, e1;
   CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
   float ms = 0;
@@ -140,6 +148,21 @@ int main(int argc, char** argv) {
     CK(hipEventRecord(e1)); CK(hipEventSynchronize(e1)); CK(hipEventElapsedTime(&ms, e0, e1));
   }
   printf("1000 empty launches of 391 x 256 threads on one stream: %.2f us each\n", ms);
+  // The same with the queue filled beforehand: a kernel that holds the stream for 6 ms goes first, the host
+  // enqueues the 1000 launches behind it (2.4 ms of host time), and the events bracket what the GPU then
+  // needs by itself -- so that the figure above can be told apart from the host's own rate of enqueueing.
+  {
+    double host_us = 0;
+    for (int rep = 0; rep < 2; ++rep) {
+      k_hold<<<1, 64>>>(600000ull);   // 6 ms in 10 ns ticks
+      CK(hipEventRecord(e0));
+      const auto t0 = std::chrono::steady_clock::now();
+      for (int i = 0; i < 1000; ++i) k_empty<<<391, 256>>>(nullptr);
+      host_us = std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count() / 1000.0;
+      CK(hipEventRecord(e1)); CK(hipEventSynchronize(e1)); CK(hipEventElapsedTime(&ms, e0, e1));
+    }
+    printf("1000 empty launches of 391 x 256 threads enqueued behind a kernel that holds the stream: %.2f us each on the GPU (the host enqueues one in %.2f us)\n", ms, host_us);
+  }
   const int shapes[][2] = {{4096, 256}, {2048, 512}, {1024, 1024}, {16384, 64}};
   for (auto& sh : shapes) {
     for (int rep = 0; rep < 2; ++rep) {

@@ -11,6 +11,7 @@
 // waiting for the rest of the kernel, so every block reaches the end whatever happens.
 
 #include <hip/hip_ext.h>
+#include <chrono>
 
 constexpr int kResThreads = 1024;
 constexpr int kMaxSpins = 1 << 16;
@@ -547,6 +548,62 @@ static int resident_main() {
     for (int x = 0; x < 8; ++x) total += c.h.xc[x][0];
     printf("  %-44s: %6.2f us per kernel%s, arrivals %s\n", any ? "launched with hipExtAnyOrderLaunch" : "launched in stream order",
            ms, c.h.err ? " (A WAIT RAN OUT)" : "", total == 1000u * nblk ? "complete" : "INCOMPLETE");
+  }
+  printf("the same chain dealt out over two streams in turn (no barrier between the queues; the kernels' own waits order them):\n");
+  {
+    hipStream_t two[2];
+    CK(hipStreamCreateWithFlags(&two[0], hipStreamNonBlocking));
+    CK(hipStreamCreateWithFlags(&two[1], hipStreamNonBlocking));
+    const unsigned nblk = 391;
+    double us = 0, host_us = 0;
+    for (int rep = 0; rep < 3; ++rep) {
+      if (res_reset(c)) return 1;
+      CK(hipDeviceSynchronize());
+      const auto t0 = std::chrono::steady_clock::now();
+      for (unsigned k = 0; k < 1000; ++k) k_chain<<<nblk, 256, 0, two[k & 1]>>>(c.s, k, nblk);
+      const auto t1 = std::chrono::steady_clock::now();
+      CK(hipStreamSynchronize(two[0])); CK(hipStreamSynchronize(two[1]));
+      const auto t2 = std::chrono::steady_clock::now();
+      host_us = std::chrono::duration<double, std::micro>(t1 - t0).count() / 1000.0;
+      us = std::chrono::duration<double, std::micro>(t2 - t0).count() / 1000.0;
+    }
+    if (res_read(c)) return 1;
+    unsigned total = 0;
+    for (int x = 0; x < 8; ++x) total += c.h.xc[x][0];
+    printf("  two streams in turn                         : %6.2f us per kernel by the host's clock (the host needs %.2f us to enqueue one)%s, arrivals %s\n",
+           us, host_us, c.h.err ? " (A WAIT RAN OUT)" : "", total == 1000u * nblk ? "complete" : "INCOMPLETE");
+    // the same with both queues filled beforehand: a kernel holds each stream for 8 ms in front of the chain, the host enqueues
+    // everything meanwhile, and the events bracket what the GPU then needs by itself
+    float ms = 0;
+    for (int rep = 0; rep < 2; ++rep) {
+      if (res_reset(c)) return 1;
+      CK(hipDeviceSynchronize());
+      k_hold<<<1, 64, 0, two[0]>>>(800000ull);
+      k_hold<<<1, 64, 0, two[1]>>>(800000ull);
+      CK(hipEventRecord(c.e0, two[1]));
+      for (unsigned k = 0; k < 1000; ++k) k_chain<<<nblk, 256, 0, two[k & 1]>>>(c.s, k, nblk);
+      CK(hipEventRecord(c.e1, two[1]));
+      CK(hipStreamSynchronize(two[0])); CK(hipStreamSynchronize(two[1]));
+      CK(hipEventElapsedTime(&ms, c.e0, c.e1));
+    }
+    if (res_read(c)) return 1;
+    total = 0;
+    for (int x = 0; x < 8; ++x) total += c.h.xc[x][0];
+    printf("  two streams in turn, queues filled beforehand: %6.2f us per kernel on the GPU%s, arrivals %s\n", ms,
+           c.h.err ? " (A WAIT RAN OUT)" : "", total == 1000u * nblk ? "complete" : "INCOMPLETE");
+    // and one stream, in order, filled beforehand, for comparison
+    for (int rep = 0; rep < 2; ++rep) {
+      if (res_reset(c)) return 1;
+      CK(hipDeviceSynchronize());
+      k_hold<<<1, 64, 0, two[0]>>>(800000ull);
+      CK(hipEventRecord(c.e0, two[0]));
+      for (unsigned k = 0; k < 1000; ++k) k_chain<<<nblk, 256, 0, two[0]>>>(c.s, k, nblk);
+      CK(hipEventRecord(c.e1, two[0]));
+      CK(hipStreamSynchronize(two[0]));
+      CK(hipEventElapsedTime(&ms, c.e0, c.e1));
+    }
+    printf("  one stream, queue filled beforehand          : %6.2f us per kernel on the GPU\n", ms);
+    CK(hipStreamDestroy(two[0])); CK(hipStreamDestroy(two[1]));
   }
   CK(hipFree(c.s));
   return 0;
