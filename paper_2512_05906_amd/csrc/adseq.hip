@@ -380,6 +380,7 @@ __global__ __launch_bounds__(kBlock) void k_in_check(Dev d) {
 #include "ring_window.h"
 #include "ring_resident.h"
 #include "ring_reverse.h"
+#include "ring_resident_reverse.h"
 #include "ring_chain.h"
 
 // ---------------------------------------------------------------- backward (FIFO / SORTED)
@@ -504,6 +505,7 @@ struct adseq {
   long long drive_from = 0, drive_upto = 0;   // RING, resident kernels: steps whose drive words are in place
   unsigned bar_base = 0;      // RING, resident kernels: value of the barrier counter after the launches so far
   int res_P = 0, res_chunk = 0, res_npt = 0;   // RING: taking-part blocks, neurons per block, per thread (0: one launch per step)
+  int rev_P = 0, rev_chunk = 0, rev_npt = 0;   // RING, reverse sweep: the same for the resident reverse kernel (0: one launch per step)
   // RING, experimental (ADSEQ_RING_OVERLAP = 1): the far part of the next window expanded ahead on a stream of the library's own
   hipStream_t aux = nullptr;
   hipEvent_t ev_boundary = nullptr, ev_ahead = nullptr;
@@ -562,6 +564,23 @@ ResidentPlan resident_plan(long long BN) {
     r.chunk = (int)chunk;
     r.P = (int)((BN + chunk - 1) / chunk);
     r.npt = chunk <= 4 * kResThreads ? 1 : 2;
+  }
+  return r;
+}
+// Resident reverse kernel (ring_resident_reverse.h): up to 256 blocks of 512 threads with four consecutive
+// neurons each (at most 2,048 neurons per block), B N a multiple of 4; delta synapse only.
+// ADSEQ_RING_RESIDENT_REVERSE = 0: never, 1 (default): whenever the layout allows; ADSEQ_RING_REVERSE_BLOCKS:
+// taking-part blocks (8 .. 256, default 256).
+ResidentPlan reverse_plan(long long BN) {
+  ResidentPlan r;
+  const int on = env_pow2("ADSEQ_RING_RESIDENT_REVERSE", 1, 0, 1);
+  const int blocks = env_pow2("ADSEQ_RING_REVERSE_BLOCKS", 256, 8, 256);
+  long long chunk = (BN + blocks - 1) / blocks;
+  chunk = (chunk + 255) / 256 * 256;
+  if (on && chunk <= 4 * kResThreads && BN % 4 == 0) {
+    r.chunk = (int)chunk;
+    r.P = (int)((BN + chunk - 1) / chunk);
+    r.npt = 1;
   }
   return r;
 }
@@ -1168,7 +1187,15 @@ void ring_backward_launch(adseq* h, hipStream_t st, long long T, float dscale, c
         }
       }
     } else {
-      if (h->chain && chain_ready(h)) {
+      if (h->rev_P > 0) {
+        // the steps of the window in one launch on the blocks of one XCD (ring_resident_reverse.h)
+        int stride = env_pow2("ADSEQ_RING_RESIDENT_STRIDE", kResStride, 1, 8);
+        while (stride > 1 && (long long)h->rev_P * stride > 32 * 8) stride >>= 1;
+        const dim3 rg((unsigned)(h->rev_P * stride)), rb(kResLaunch);
+        if (dL_dU) hipLaunchKernelGGL((k_bwd_xcd<true>), rg, rb, 0, st, k1, nsteps, T, h->bar_base, h->rev_P, h->rev_chunk, stride, dL_dcount, dL_dU, d);
+        else hipLaunchKernelGGL((k_bwd_xcd<false>), rg, rb, 0, st, k1, nsteps, T, h->bar_base, h->rev_P, h->rev_chunk, stride, dL_dcount, dL_dU, d);
+        h->bar_base += (unsigned)(nsteps - 1) * (unsigned)h->rev_P;
+      } else if (h->chain && chain_ready(h)) {
         chain_fork(h, st);
         for (long long n = k1 - 1; n >= k0; --n) {
           if (h->chain_tpb == 1024) {
@@ -1390,6 +1417,10 @@ int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, 
   if (d.kind == ADSEQ_RING) {
     const ResidentPlan rp = resident_plan((long long)d.BN);
     h->res_chunk = rp.chunk; h->res_P = rp.P; h->res_npt = rp.npt;
+    if (!(d.alpha_s > 0.0f)) {
+      const ResidentPlan vp = reverse_plan((long long)d.BN);
+      h->rev_chunk = vp.chunk; h->rev_P = vp.P; h->rev_npt = vp.npt;
+    }
     // chained step launches (ring_chain.h; experimental, off by default: measured slower than a launch per step on
     // one stream): delta synapse, and two launches' blocks must fit the chip side by side (512 blocks each at
     // most).  ADSEQ_RING_CHAIN = 1: wherever that holds (instead of the resident kernels too).  The static handle

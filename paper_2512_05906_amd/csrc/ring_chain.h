@@ -209,55 +209,10 @@ __global__ __launch_bounds__(TPB) void k_bwd_step_chain(long long n, long long T
   }
   unsigned long long m = __ballot(s && ncnt > 0);
   const int lane = threadIdx.x & 63;
-  // first batch: rows and the gathers two and more steps away go out before the wait
+  // Up to four of the wavefront's spikes at a time: row bounds, the first 64 entries of each row, and the gathers two and
+  // more steps away (rows of the adjoint window that the stream orders before this launch).
   ChainBatch cb;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    cb.pr[j] = 0; cb.cn[j] = 0; cb.bs[j] = 0; cb.Ls[j] = -1;
-    if (m) {
-      const int L = __ffsll((long long)m) - 1;
-      m &= m - 1;
-      cb.Ls[j] = L;
-      cb.pr[j] = lane_get(r0, L); cb.cn[j] = lane_get(ncnt, L); cb.bs[j] = lane_get(b, L) * d.N;
-    }
-  }
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    cb.e[j] = make_uint2(0u, 0u);
-    if ((unsigned)lane < cb.cn[j]) cb.e[j] = d.synb[cb.pr[j] + lane];
-  }
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    cb.gv[j] = 0.0f;
-    const int D = (int)(cb.e[j].x & d.dmask);
-    if ((unsigned)lane < cb.cn[j] && D >= 2 && n + D < T)
-      cb.gv[j] = gwin[(size_t)(phi + D) * d.BN + (size_t)cb.bs[j] + (cb.e[j].x >> d.dbits)];
-  }
-  chain_wait(d, target);
-  float carry = 0.0f;
-  if (act) carry = ld_agent(&d.bwd_carry[g]);
-  for (;;) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int D = (int)(cb.e[j].x & d.dmask);
-      if ((unsigned)lane < cb.cn[j] && D == 1 && n + D < T)
-        cb.gv[j] = ld_agent(&gwin[(size_t)(phi + D) * d.BN + (size_t)cb.bs[j] + (cb.e[j].x >> d.dbits)]);
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      if (cb.Ls[j] < 0) continue;    // uniform
-      const int D = (int)(cb.e[j].x & d.dmask);
-      float part = 0.0f;
-      if ((unsigned)lane < cb.cn[j] && n + D < T) {
-        part = __uint_as_float(cb.e[j].y) * cb.gv[j];
-        unsafeAtomicAdd(&d.gsum[cb.pr[j] + lane], cb.gv[j]);
-      }
-      part = wave_sum_f(part);
-      if (cb.cn[j] > 64u) part += near_gather_agent(d, gwin, n, T, phi, cb.pr[j] + 64, cb.cn[j] - 64u, cb.bs[j]);
-      if (lane == cb.Ls[j]) G += part;
-    }
-    if (!m) break;
-    // further batches (more than four spikes among the wavefront's 64 neurons): after the wait as a whole
+  auto next_batch = [&]() {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       cb.pr[j] = 0; cb.cn[j] = 0; cb.bs[j] = 0; cb.Ls[j] = -1;
@@ -280,6 +235,34 @@ __global__ __launch_bounds__(TPB) void k_bwd_step_chain(long long n, long long T
       if ((unsigned)lane < cb.cn[j] && D >= 2 && n + D < T)
         cb.gv[j] = gwin[(size_t)(phi + D) * d.BN + (size_t)cb.bs[j] + (cb.e[j].x >> d.dbits)];
     }
+  };
+  next_batch();   // the first batch is in flight before the wait
+  chain_wait(d, target);
+  float carry = 0.0f;
+  if (act) carry = ld_agent(&d.bwd_carry[g]);
+  for (;;) {
+    // the gathers one step away: row n + 1, written by the launch this one has waited for
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int D = (int)(cb.e[j].x & d.dmask);
+      if ((unsigned)lane < cb.cn[j] && D == 1 && n + D < T)
+        cb.gv[j] = ld_agent(&gwin[(size_t)(phi + D) * d.BN + (size_t)cb.bs[j] + (cb.e[j].x >> d.dbits)]);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (cb.Ls[j] < 0) continue;    // uniform
+      const int D = (int)(cb.e[j].x & d.dmask);
+      float part = 0.0f;
+      if ((unsigned)lane < cb.cn[j] && n + D < T) {
+        part = __uint_as_float(cb.e[j].y) * cb.gv[j];
+        unsafeAtomicAdd(&d.gsum[cb.pr[j] + lane], cb.gv[j]);
+      }
+      part = wave_sum_f(part);
+      if (cb.cn[j] > 64u) part += near_gather_agent(d, gwin, n, T, phi, cb.pr[j] + 64, cb.cn[j] - 64u, cb.bs[j]);
+      if (lane == cb.Ls[j]) G += part;
+    }
+    if (!m) break;
+    next_batch();   // (more than four spikes among the wavefront's 64 neurons)
   }
   if (act) {
     float gu;

@@ -150,6 +150,50 @@ def test_reverse_sweep_by_windows(surrogate, n, b, T, monkeypatch):
     H.grad_close(got["1"][1], got["0"][1])
 
 
+@pytest.mark.parametrize("surrogate", [adseq.SURR_SUPERSPIKE, adseq.GRAD_SPIKE_TIME])
+@pytest.mark.parametrize("n,b,T,d_max,rate,continuous", [(700, 3, 150, 40, 400.0, False), (6000, 2, 100, 40, 2500.0, False),
+                                                        (20000, 4, 70, 40, 400.0, False), (900, 4, 70, 2, 400.0, False),
+                                                        (1500, 2, 90, 30, 400.0, True)])
+def test_resident_reverse_sweep(surrogate, n, b, T, d_max, rate, continuous, monkeypatch):
+    """The reverse steps of a window in one launch on the blocks of one XCD (ring_resident_reverse.h):
+    both gradients against the oracle, with a cotangent on the membrane values as well, in both
+    gradient modes; four and eight neurons per thread; a run length that is not a multiple of the
+    window; a drive under which a block has more than 32 spikes in a step (the spikes beyond a
+    wavefront's first batch); delays of one and two steps only (rows of up to 200 entries: more than
+    64 inside the window, the gathers beyond a wavefront's first load); continuous delays; and
+    agreement with the sweep of one launch per step."""
+    wl = synth.ragged_network(n, 200, d_max, seed=n, rate_hz=rate, t=T, b=b, w_mean=0.004, w_std=0.004,
+                              continuous=continuous)
+    ref = oracle.Run(wl, oracle.RING, 0, n_steps=T, batch=b, surrogate=surrogate, n_threads=4)
+    assert ref.spikes.sum() > 300
+    rng = np.random.default_rng(n)
+    dc = rng.normal(0, 1e-3, (b, n)).astype(np.float32)
+    dU = rng.normal(0, 1e-4, (T, b, n)).astype(np.float32)
+    gw, gd = ref.backward(dc, dU)
+    got = {}
+    monkeypatch.setenv("ADSEQ_RING_REVERSE_WINDOWS", "0")
+    for mode in ("1", "0"):
+        monkeypatch.setenv("ADSEQ_RING_RESIDENT_REVERSE", mode)
+        sim = adseq.Adseq(wl, adseq.RING, 0, batch=b, record_tape=True, max_steps=T, surrogate=surrogate)
+        sim.run(0, T)
+        g_w = torch.empty(wl.n_synapses, device=sim.dev)
+        g_d = torch.empty(wl.n_synapses, device=sim.dev)
+        sim.backward(torch.from_numpy(dc).to(sim.dev), torch.from_numpy(dU).to(sim.dev), g_w, g_d)
+        torch.cuda.synchronize()
+        assert sim.counters()["error_bits"] == 0
+        got[mode] = (g_w.cpu().numpy(), g_d.cpu().numpy())
+        H.grad_close(got[mode][0], gw)
+        H.grad_close(got[mode][1], gd)
+        # a second sweep over the same tape gives the same gradients (carry, window and far terms start from zero again)
+        if mode == "1":
+            sim.backward(torch.from_numpy(dc).to(sim.dev), torch.from_numpy(dU).to(sim.dev), g_w, g_d)
+            torch.cuda.synchronize()
+            H.grad_close(g_w.cpu().numpy(), gw)
+        sim.close()
+    H.grad_close(got["1"][0], got["0"][0])
+    H.grad_close(got["1"][1], got["0"][1])
+
+
 def test_range_warning_for_sums_that_could_wrap():
     """adseq_create adds up |amplitude| over every target's incoming synapses; where that reaches
     128 (the range of the Q8.24 sums) the counters carry the warning bit 64, also after a reset."""
