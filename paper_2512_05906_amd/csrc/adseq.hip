@@ -55,6 +55,7 @@ struct Counters {
   unsigned long long fold[3];       // scratch of k_count_spikes: spikes, events, Q8.24 sum
   alignas(128) unsigned bar[32];    // bar[0]: arrivals at the barriers of the resident step kernels (a line of its own)
   alignas(128) unsigned arrive[8][32];  // arrive[x][0]: blocks with index x mod 8 of the chained step launches that have arrived (ring_chain.h)
+  alignas(128) unsigned rev_arrivals[8][32];  // rev_arrivals[x][0]: arrivals of the blocks with rank x mod 8 at the barriers of the resident reverse kernel
 #ifdef ADSEQ_PHASE_CLOCK
   unsigned long long phase[24];     // builds with phase clocks: 10 ns ticks block 0 spent in each phase; [0, 8) resident steps or
                                     // staging pass of the window expansion, [8, 11) accumulation pass, [15] expansions counted
@@ -170,6 +171,8 @@ struct Dev {
   int lazy_rows;        // RING: the step kernels fetch row start, in-window count and far queue term for spiking lanes only (experiment)
   int count_pop;        // RING: the step kernels add up the Q8.24 sums they pop (checking aid, off by default)
   int chain_sleep;      // RING, chained step launches: pauses of 128 cycles between two polls of a wait
+  int rev_delay;        // RING, resident reverse kernel: pauses of 1,024 cycles before the first poll of a barrier
+  int res_wide;         // RING, resident forward kernel: arrivals on eight counters instead of one (experiment)
 #if defined(ADSEQ_PHASE_CLOCK) || defined(ADSEQ_ABLATE)
   int dbg;              // debugging builds: parts of the resident step to leave out (timing only)
 #endif
@@ -504,6 +507,7 @@ struct adseq {
   size_t ev_used = 0;
   long long drive_from = 0, drive_upto = 0;   // RING, resident kernels: steps whose drive words are in place
   unsigned bar_base = 0;      // RING, resident kernels: value of the barrier counter after the launches so far
+  unsigned rev_base = 0;      // RING, resident reverse kernel: sum of its arrival counters after the launches so far
   int res_P = 0, res_chunk = 0, res_npt = 0;   // RING: taking-part blocks, neurons per block, per thread (0: one launch per step)
   int rev_P = 0, rev_chunk = 0, rev_npt = 0;   // RING, reverse sweep: the same for the resident reverse kernel (0: one launch per step)
   // RING, experimental (ADSEQ_RING_OVERLAP = 1): the far part of the next window expanded ahead on a stream of the library's own
@@ -570,11 +574,11 @@ ResidentPlan resident_plan(long long BN) {
 // Resident reverse kernel (ring_resident_reverse.h): up to 256 blocks of 512 threads with four consecutive
 // neurons each (at most 2,048 neurons per block), B N a multiple of 4; delta synapse only.
 // ADSEQ_RING_RESIDENT_REVERSE = 0: never, 1 (default): whenever the layout allows; ADSEQ_RING_REVERSE_BLOCKS:
-// taking-part blocks (8 .. 256, default 256).
+// taking-part blocks (8 .. 256, default 128).
 ResidentPlan reverse_plan(long long BN) {
   ResidentPlan r;
   const int on = env_pow2("ADSEQ_RING_RESIDENT_REVERSE", 1, 0, 1);
-  const int blocks = env_pow2("ADSEQ_RING_REVERSE_BLOCKS", 256, 8, 256);
+  const int blocks = env_pow2("ADSEQ_RING_REVERSE_BLOCKS", 128, 8, 256);
   long long chunk = (BN + blocks - 1) / blocks;
   chunk = (chunk + 255) / 256 * 256;
   if (on && chunk <= 4 * kResThreads && BN % 4 == 0) {
@@ -805,6 +809,7 @@ void launch_reset(adseq* h, hipStream_t st) {
   h->ahead_for = -1;
   h->fold_upto = 0;
   h->bar_base = 0;   // (the counter itself is cleared with the other counters)
+  h->rev_base = 0;   // (likewise)
   h->chain_arrivals = 0;   // (likewise)
   h->drive_from = h->drive_upto = 0;
   const size_t BN = (size_t)d.BN;
@@ -1072,14 +1077,15 @@ void ring_run_resident(adseq* h, hipStream_t st, long long step0, long long n_st
                          h->res_P, h->res_chunk, h->res_npt);
       h->drive_from = n; h->drive_upto = upto;
     }
+    const unsigned base = d.res_wide ? h->rev_base : h->bar_base;
     if (record) {
-      if (h->res_npt == 1) launch_run_xcd<true, 1>(d, st, syn, n, cnt, h->bar_base, h->res_P, h->res_chunk);
-      else launch_run_xcd<true, 2>(d, st, syn, n, cnt, h->bar_base, h->res_P, h->res_chunk);
+      if (h->res_npt == 1) launch_run_xcd<true, 1>(d, st, syn, n, cnt, base, h->res_P, h->res_chunk);
+      else launch_run_xcd<true, 2>(d, st, syn, n, cnt, base, h->res_P, h->res_chunk);
     } else {
-      if (h->res_npt == 1) launch_run_xcd<false, 1>(d, st, syn, n, cnt, h->bar_base, h->res_P, h->res_chunk);
-      else launch_run_xcd<false, 2>(d, st, syn, n, cnt, h->bar_base, h->res_P, h->res_chunk);
+      if (h->res_npt == 1) launch_run_xcd<false, 1>(d, st, syn, n, cnt, base, h->res_P, h->res_chunk);
+      else launch_run_xcd<false, 2>(d, st, syn, n, cnt, base, h->res_P, h->res_chunk);
     }
-    h->bar_base += (unsigned)(cnt - 1) * (unsigned)h->res_P;
+    (d.res_wide ? h->rev_base : h->bar_base) += (unsigned)(cnt - 1) * (unsigned)h->res_P;
     h->grp_count += cnt;
     h->enq_calls += cnt;
     n += cnt;
@@ -1192,9 +1198,9 @@ void ring_backward_launch(adseq* h, hipStream_t st, long long T, float dscale, c
         int stride = env_pow2("ADSEQ_RING_RESIDENT_STRIDE", kResStride, 1, 8);
         while (stride > 1 && (long long)h->rev_P * stride > 32 * 8) stride >>= 1;
         const dim3 rg((unsigned)(h->rev_P * stride)), rb(kResLaunch);
-        if (dL_dU) hipLaunchKernelGGL((k_bwd_xcd<true>), rg, rb, 0, st, k1, nsteps, T, h->bar_base, h->rev_P, h->rev_chunk, stride, dL_dcount, dL_dU, d);
-        else hipLaunchKernelGGL((k_bwd_xcd<false>), rg, rb, 0, st, k1, nsteps, T, h->bar_base, h->rev_P, h->rev_chunk, stride, dL_dcount, dL_dU, d);
-        h->bar_base += (unsigned)(nsteps - 1) * (unsigned)h->rev_P;
+        if (dL_dU) hipLaunchKernelGGL((k_bwd_xcd<true>), rg, rb, 0, st, k1, nsteps, T, h->rev_base, h->rev_P, h->rev_chunk, stride, dL_dcount, dL_dU, d);
+        else hipLaunchKernelGGL((k_bwd_xcd<false>), rg, rb, 0, st, k1, nsteps, T, h->rev_base, h->rev_P, h->rev_chunk, stride, dL_dcount, dL_dU, d);
+        h->rev_base += (unsigned)(nsteps - 1) * (unsigned)h->rev_P;
       } else if (h->chain && chain_ready(h)) {
         chain_fork(h, st);
         for (long long n = k1 - 1; n >= k0; --n) {
@@ -1430,6 +1436,8 @@ int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, 
     if (h->chain) h->res_P = 0;
     h->chain_tpb = env_pow2("ADSEQ_RING_CHAIN_THREADS", 256, 256, 1024) == 1024 ? 1024 : 256;
     d.chain_sleep = env_pow2("ADSEQ_RING_CHAIN_SLEEP", 1, 0, 64);
+    d.rev_delay = env_pow2("ADSEQ_RING_REVERSE_DELAY", 1, 0, 16);
+    d.res_wide = env_pow2("ADSEQ_RING_RESIDENT_WIDE", 0, 0, 1);
   }
   hipStream_t st = (hipStream_t)cfg->stream;
   launch_reset(h, st);

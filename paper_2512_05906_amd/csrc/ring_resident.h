@@ -60,6 +60,33 @@ __device__ __forceinline__ void res_wait(const Dev& d, unsigned target, int* dea
   __syncthreads();
 }
 
+// The same barrier for many blocks on several XCDs (Dev::res_wide): arrivals at ONE counter queue up behind one another
+// (11 ns each), so the blocks arrive on eight counters, a line each, and the synchronising wavefront polls all eight side
+// by side (one per lane) until their sum reaches the target; the first poll waits a little, because polls are loads of
+// the very lines the arrivals add to.
+__device__ __forceinline__ void wide_arrive(const Dev& d, int rank) {
+  wait_all_memory();
+  __syncthreads();
+  if (threadIdx.x == kResThreads) atomicAdd(&d.ctr->rev_arrivals[rank & 7][0], 1u);
+}
+__device__ __forceinline__ void wide_wait(const Dev& d, unsigned target, int* dead) {
+  if (threadIdx.x >= kResThreads && !*dead) {   // the synchronising wavefront, all lanes (the same way through for each)
+    const int lane = threadIdx.x & 63;
+    const unsigned* p = &d.ctr->rev_arrivals[lane & 7][0];
+    for (int k = 0; k < d.rev_delay; ++k) __builtin_amdgcn_s_sleep(16);
+    int spins = 0;
+    for (;;) {
+      const unsigned v = lane < 8 ? ld_agent(p) : 0u;
+      unsigned sum = 0;
+#pragma unroll
+      for (int x = 0; x < 8; ++x) sum += (unsigned)__builtin_amdgcn_readlane((int)v, x);
+      if ((int)(sum - target) >= 0) break;
+      if (++spins > d.res_spins) { if (lane == 0) { atomicOr(&d.ctr->err, ERR_BARRIER); *dead = 1; } break; }
+    }
+  }
+  __syncthreads();
+}
+
 // Layout of a taking-part block's neurons (ResMap): block `rank` owns neurons [rank * chunk,
 // rank * chunk + chunk), chunk a multiple of 256 and at most NG * 1024; thread t of the block owns,
 // in group q < NG, the four consecutive neurons rank * chunk + q * 1024 + 4 t + c, c < 4.  A
@@ -201,7 +228,10 @@ __global__ __launch_bounds__(kResLaunch) void k_run_xcd(long long n0, int nsteps
     const __amdgpu_buffer_rsrc_t cells = res_rows(win, hi * 4);
     PHASE(5)
     // the adds of step n - 1 are in place once every block has arrived
-    if (k > 0) res_wait(d, bar_base + (unsigned)k * (unsigned)P, &s_dead);
+    if (k > 0) {
+      if (d.res_wide) wide_wait(d, bar_base + (unsigned)k * (unsigned)P, &s_dead);
+      else res_wait(d, bar_base + (unsigned)k * (unsigned)P, &s_dead);
+    }
     PHASE(0)
 #pragma unroll
     for (int q = 0; q < NG; ++q) asm volatile("" ::"v"(touch[q]));   // (the touching loads of the step before stay alive until here)
@@ -308,7 +338,10 @@ __global__ __launch_bounds__(kResLaunch) void k_run_xcd(long long n0, int nsteps
     wait_all_memory();
 #endif
     PHASE(3)
-    if (k + 1 < nsteps) res_arrive(d);
+    if (k + 1 < nsteps) {
+      if (d.res_wide) wide_arrive(d, rank);
+      else res_arrive(d);
+    }
     if (threadIdx.x == 0) s_nspk = 0;   // (every wavefront has read the list: block barrier in res_arrive; the last step needs none)
     // touch the cells of the row two steps on (values that may still change are not used: the
     // loads only bring the lines into the L2, two steps before they are popped; issued after the
