@@ -155,9 +155,9 @@ def test_reverse_sweep_by_windows(surrogate, n, b, T, monkeypatch):
                                                         (20000, 4, 70, 40, 400.0, False), (900, 4, 70, 2, 400.0, False),
                                                         (1500, 2, 90, 30, 400.0, True)])
 def test_resident_reverse_sweep(surrogate, n, b, T, d_max, rate, continuous, monkeypatch):
-    """The reverse steps of a window in one launch on the blocks of one XCD (ring_resident_reverse.h):
+    """The reverse steps of a window in one launch with a grid barrier per step (ring_resident_reverse.h):
     both gradients against the oracle, with a cotangent on the membrane values as well, in both
-    gradient modes; four and eight neurons per thread; a run length that is not a multiple of the
+    gradient modes; a few blocks and 128; a run length that is not a multiple of the
     window; a drive under which a block has more than 32 spikes in a step (the spikes beyond a
     wavefront's first batch); delays of one and two steps only (rows of up to 200 entries: more than
     64 inside the window, the gathers beyond a wavefront's first load); continuous delays; and
@@ -192,6 +192,84 @@ def test_resident_reverse_sweep(surrogate, n, b, T, d_max, rate, continuous, mon
         sim.close()
     H.grad_close(got["1"][0], got["0"][0])
     H.grad_close(got["1"][1], got["0"][1])
+
+
+def _reverse_against_oracle(wl, T, b, surrogate=adseq.SURR_SUPERSPIKE):
+    ref = oracle.Run(wl, oracle.RING, 0, n_steps=T, batch=b, surrogate=surrogate, n_threads=4)
+    rng = np.random.default_rng(wl.n_neurons)
+    dc = rng.normal(0, 1e-3, (b, wl.n_neurons)).astype(np.float32)
+    gw, gd = ref.backward(dc, None)
+    sim = adseq.Adseq(wl, adseq.RING, 0, batch=b, record_tape=True, max_steps=T, surrogate=surrogate)
+    sim.run(0, T)
+    g_w = torch.empty(wl.n_synapses, device=sim.dev)
+    g_d = torch.empty(wl.n_synapses, device=sim.dev)
+    sim.backward(torch.from_numpy(dc).to(sim.dev), None, g_w, g_d)
+    torch.cuda.synchronize()
+    assert sim.counters()["error_bits"] == 0
+    H.grad_close(g_w.cpu().numpy(), gw)
+    H.grad_close(g_d.cpu().numpy(), gd)
+    sim.close()
+    return ref
+
+
+@pytest.mark.parametrize("blocks,stride", [("8", "8"), ("32", "1"), ("256", "2"), ("128", "4")])
+def test_resident_reverse_block_counts_and_spread(blocks, stride, monkeypatch):
+    """The resident reverse kernel with few and many taking-part blocks, on one XCD and spread over
+    all of them (every stride-th block of the grid takes part): nothing in its results depends on
+    where the blocks run.  A trial boundary inside a thread's four neurons (N = 301, four trials), no
+    cotangent on the membrane values, windows of 8 steps."""
+    monkeypatch.setenv("ADSEQ_RING_REVERSE_WINDOWS", "0")
+    monkeypatch.setenv("ADSEQ_RING_RESIDENT_REVERSE", "1")
+    monkeypatch.setenv("ADSEQ_RING_REVERSE_BLOCKS", blocks)
+    monkeypatch.setenv("ADSEQ_RING_RESIDENT_STRIDE", stride)
+    monkeypatch.setenv("ADSEQ_RING_WINDOW", "8")
+    wl = synth.ragged_network(301, 150, 30, seed=41, rate_hz=500.0, t=90, b=4, w_mean=0.006, w_std=0.004)
+    ref = _reverse_against_oracle(wl, 90, 4)
+    assert ref.spikes.sum() > 300
+    wl = synth.ragged_network(30000, 40, 30, seed=42, rate_hz=500.0, t=50, b=2, w_mean=0.02, w_std=0.01)
+    ref = _reverse_against_oracle(wl, 50, 2, adseq.GRAD_SPIKE_TIME)
+    assert ref.spikes.sum() > 300
+
+
+def test_resident_reverse_falls_back_where_the_layout_does_not_fit(monkeypatch):
+    """B N not a multiple of 4 (rows of the window not 16-byte aligned) and more state cells than 256 blocks of
+    2,048 hold: the reverse sweep goes by one launch per step, same gradients."""
+    monkeypatch.setenv("ADSEQ_RING_REVERSE_WINDOWS", "0")
+    wl = synth.ragged_network(1201, 100, 30, seed=43, rate_hz=500.0, t=60, b=3, w_mean=0.008, w_std=0.005)
+    _reverse_against_oracle(wl, 60, 3)
+    monkeypatch.setenv("ADSEQ_RING_REVERSE_BLOCKS", "8")
+    wl = synth.ragged_network(20000, 40, 30, seed=44, rate_hz=500.0, t=40, b=1, w_mean=0.02, w_std=0.01)   # 8 blocks of 2,048 < 20,000
+    _reverse_against_oracle(wl, 40, 1)
+
+
+def test_resident_reverse_wait_that_runs_out_is_reported(monkeypatch):
+    """Failure path of the reverse kernel's bounded waits, forced from the host (one poll per wait): every kernel
+    runs to its end, the error word carries bit 32 after the sweep, a reset clears it, and a handle with the
+    ordinary limit gives the oracle's gradients."""
+    monkeypatch.setenv("ADSEQ_RING_REVERSE_WINDOWS", "0")
+    monkeypatch.setenv("ADSEQ_RING_RESIDENT", "0")
+    monkeypatch.setenv("ADSEQ_RING_REVERSE_DELAY", "0")
+    wl = synth.ragged_network(40000, 30, 20, seed=45, rate_hz=700.0, t=60, b=2, w_mean=0.02, w_std=0.01)
+    sim = adseq.Adseq(wl, adseq.RING, 0, record_tape=True, max_steps=60)
+    sim.run(0, 60)
+    torch.cuda.synchronize()
+    assert sim.counters()["error_bits"] == 0
+    sim.close()
+    monkeypatch.setenv("ADSEQ_RING_RESIDENT_SPINS", "1")
+    sim = adseq.Adseq(wl, adseq.RING, 0, record_tape=True, max_steps=60)
+    sim.run(0, 60)
+    g = torch.empty(wl.n_synapses, device=sim.dev)
+    sim.backward(torch.zeros(2 * 40000, device=sim.dev) + 1e-3, None, g, g.clone())
+    torch.cuda.synchronize()
+    assert sim.counters()["error_bits"] & 32
+    with pytest.raises(adseq.AdseqError):
+        sim.drop_count()
+    sim.reset()
+    assert sim.counters()["error_bits"] == 0
+    sim.close()
+    monkeypatch.delenv("ADSEQ_RING_RESIDENT_SPINS")
+    monkeypatch.delenv("ADSEQ_RING_REVERSE_DELAY")
+    _reverse_against_oracle(wl, 60, 2)
 
 
 def test_range_warning_for_sums_that_could_wrap():
