@@ -197,6 +197,9 @@ def main():
                          if args.queue in ("syn", "latest", "bins") else "k_neurons (admission + pop + drive + LIF + spike words)"),
                  "bwd_gather": "k_bwd_rows (adjoint gathers and gradient sums of the step's recorded spikes)",
                  "bwd_neurons": "k_bwd_neurons (adjoint update)"}
+    if args.queue == "ring" and prof.get("bwd_neurons", {}).get("launches", T) < T:
+        # fewer launches than steps: the reverse steps of a window ran in one launch each (resident reverse kernel)
+        label["bwd_neurons"] = "k_bwd_xcd (the reverse steps of one window in one launch: adjoint update + in-window gather, a grid barrier per step)"
     kernels = {}
     for k, v in prof.items():
         if v["launches"]:

@@ -1222,7 +1222,7 @@ void ring_backward_launch(adseq* h, hipStream_t st, long long T, float dscale, c
         else hipLaunchKernelGGL((k_bwd_step_win<0, false>), gn, block, 0, st, n, T, dL_dcount, dL_dU, d);
       }
     }
-    h->grp_count += nsteps;
+    h->grp_count += (!whole && h->rev_P > 0) ? 1 : nsteps;   // launches of the group: the resident reverse kernel takes the window in one
     // far gather into the window (and, after a sweep of the whole window, the per-synapse sums of
     // its own near events): spikes of steps [lo, hi)
     const long long lo = k0 - d.d_max > 0 ? k0 - d.d_max : 0;
