@@ -237,7 +237,12 @@ int adseq_run(adseq_t *h, int64_t step0, int64_t n_steps, void *stream);
  * G_i of the surrogate modes, and gJ / tau_syn + gB / tau_rise that of gU / tau_m in grad_d and in
  * the spike-time mode's E), summed over
  * trials.  dL_dcount: fp32 [B*N] or NULL; dL_dU: fp32 [T][B*N] or NULL; grad_w, grad_d: fp32 [S],
- * overwritten.  Synchronises the stream once at the start to read the device error word. */
+ * overwritten.  Synchronises the stream once at the start to read the device error word.
+ * ADSEQ_RING runs the reverse steps of a window in one kernel whose blocks wait for one another
+ * at a barrier per step (every wait bounded); should such a wait run out -- the blocks of a launch
+ * were not running together -- the kernels still run to their end, the gradients are void, and
+ * the error word carries bit 32 afterwards: read it with adseq_counters once the stream is done
+ * (adseq_drop_count and the next adseq_backward refuse the run with ADSEQ_E_HIP). */
 int adseq_backward(adseq_t *h, const float *dL_dcount, const float *dL_dU, float *grad_w,
                    float *grad_d, void *stream);
 
@@ -297,7 +302,7 @@ int adseq_spike_counts(adseq_t *h, int32_t *counts, void *stream);
  * [2] backward queue term + gradients, [3] backward neuron update.  Classes for RING: [0] the
  * expansion of one window (staging pass + accumulation pass, timed as a pair and counted as one
  * launch), [1] forward step kernel, [2] backward far gather of one window, [3] backward step
- * kernel; the step kernels are timed in groups (all the step launches between two window
+ * kernel (where the reverse steps of a window run in one launch, that launch); the step kernels are timed in groups (all the step launches between two window
  * boundaries between one pair of events), because an event after every 5 us launch would add
  * half as much again. */
 int adseq_profile(adseq_t *h, int enable);
