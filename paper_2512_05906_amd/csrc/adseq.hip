@@ -384,6 +384,7 @@ __global__ __launch_bounds__(kBlock) void k_in_check(Dev d) {
 #include "ring_resident.h"
 #include "ring_reverse.h"
 #include "ring_resident_reverse.h"
+#include "ring_resident_forward.h"
 #include "ring_chain.h"
 
 // ---------------------------------------------------------------- backward (FIFO / SORTED)
@@ -510,6 +511,8 @@ struct adseq {
   unsigned rev_base = 0;      // RING, resident reverse kernel: sum of its arrival counters after the launches so far
   int res_P = 0, res_chunk = 0, res_npt = 0;   // RING: taking-part blocks, neurons per block, per thread (0: one launch per step)
   int rev_P = 0, rev_chunk = 0, rev_npt = 0;   // RING, reverse sweep: the same for the resident reverse kernel (0: one launch per step)
+  int fwd_P = 0, fwd_chunk = 0;                // RING: the same for the forward kernel over the whole chip (ring_resident_forward.h; 0: not used)
+  float fwd_margin = 0.005f;                   // how far below the threshold the early value of a candidate may lie
   // RING, experimental (ADSEQ_RING_OVERLAP = 1): the far part of the next window expanded ahead on a stream of the library's own
   hipStream_t aux = nullptr;
   hipEvent_t ev_boundary = nullptr, ev_ahead = nullptr;
@@ -575,10 +578,13 @@ ResidentPlan resident_plan(long long BN) {
 // neurons each (at most 2,048 neurons per block), B N a multiple of 4; delta synapse only.
 // ADSEQ_RING_RESIDENT_REVERSE = 0: never, 1 (default): whenever the layout allows; ADSEQ_RING_REVERSE_BLOCKS:
 // taking-part blocks (8 .. 256, default 128).
-ResidentPlan reverse_plan(long long BN) {
+ResidentPlan reverse_plan(long long BN, bool forward = false) {
   ResidentPlan r;
-  const int on = env_pow2("ADSEQ_RING_RESIDENT_REVERSE", 1, 0, 1);
-  const int blocks = env_pow2("ADSEQ_RING_REVERSE_BLOCKS", 128, 8, 256);
+  // (forward: 0 never, 1 wherever the layout fits, default from 2,048 state cells on: below that one XCD's blocks, whose
+  // barrier is shorter, are faster -- 100 cells 2.4 against 2.9 us per step)
+  const int fwd = env_pow2("ADSEQ_RING_FORWARD_CHIP", 2, 0, 2);
+  const int on = forward ? ((fwd == 1 || (fwd == 2 && BN >= 2048)) ? 1 : 0) : env_pow2("ADSEQ_RING_RESIDENT_REVERSE", 1, 0, 1);
+  const int blocks = forward ? env_pow2("ADSEQ_RING_FORWARD_BLOCKS", 256, 8, 256) : env_pow2("ADSEQ_RING_REVERSE_BLOCKS", 128, 8, 256);
   long long chunk = (BN + blocks - 1) / blocks;
   chunk = (chunk + 255) / 256 * 256;
   if (on && chunk <= 4 * kResThreads && BN % 4 == 0) {
@@ -924,7 +930,7 @@ void launch_expansion(adseq* h, hipStream_t st, long long k0, long long n_lo, lo
   static const int sort_stage = env_pow2("ADSEQ_RING_SORTSTAGE", 1, 0, 1);
   const int stage = d.cap > 0 ? ((sort_stage && d.P <= kSortParts) ? 2 : 1) : 0;
   hipLaunchKernelGGL(k_win_bin, dim3((unsigned)d.NB), dim3(kRingThreads), 0, st, d, k0, n_lo, n_hi, 0, d.NB,
-                     stage, count_from, h->res_P > 0 ? 1 : 0);
+                     stage, count_from, (h->res_P > 0 || h->fwd_P > 0) ? 1 : 0);
   if (d.cap > 0) {
     const int parts = d.P < kMaxParts ? d.P : kMaxParts;
     hipLaunchKernelGGL(k_win_acc, dim3((unsigned)parts), dim3(kRingThreads), 0, st, d, k0, 0);
@@ -1086,6 +1092,33 @@ void ring_run_resident(adseq* h, hipStream_t st, long long step0, long long n_st
       else launch_run_xcd<false, 2>(d, st, syn, n, cnt, base, h->res_P, h->res_chunk);
     }
     (d.res_wide ? h->rev_base : h->bar_base) += (unsigned)(cnt - 1) * (unsigned)h->res_P;
+    h->grp_count += cnt;
+    h->enq_calls += cnt;
+    n += cnt;
+    h->next_step = n;
+  }
+}
+
+// RING: steps step0 .. step0 + n_steps - 1 with one launch per window over the whole chip (ring_resident_forward.h).
+void ring_run_chip(adseq* h, hipStream_t st, long long step0, long long n_steps) {
+  const Dev& d = h->dev;
+  long long n = step0;
+  const long long end = step0 + n_steps;
+  int stride = env_pow2("ADSEQ_RING_RESIDENT_STRIDE", kResStride, 1, 8);
+  while (stride > 1 && (long long)h->fwd_P * stride > 32 * 8) stride >>= 1;
+  const dim3 grid((unsigned)(h->fwd_P * stride)), block(kResLaunch);
+  while (n < end) {
+    ring_open_window(h, st, n);
+    open_group(h, st);
+    const long long in_win = (long long)d.W - (n & (long long)(d.W - 1));
+    int cnt = (int)(end - n < in_win ? end - n : in_win);
+    // a launch either records all its steps or none: it ends where the tape ends
+    const bool record = d.record && h->tape_ok && n < d.max_steps;
+    if (record && n + cnt > d.max_steps) cnt = (int)(d.max_steps - n);
+    if (d.record && n >= d.max_steps) h->tape_ok = false;
+    if (record) hipLaunchKernelGGL((k_fwd_chip<true>), grid, block, 0, st, n, cnt, h->rev_base, h->fwd_P, h->fwd_chunk, stride, h->fwd_margin, d);
+    else hipLaunchKernelGGL((k_fwd_chip<false>), grid, block, 0, st, n, cnt, h->rev_base, h->fwd_P, h->fwd_chunk, stride, h->fwd_margin, d);
+    h->rev_base += (unsigned)(cnt - 1) * (unsigned)h->fwd_P;
     h->grp_count += cnt;
     h->enq_calls += cnt;
     n += cnt;
@@ -1426,6 +1459,14 @@ int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, 
     if (!(d.alpha_s > 0.0f)) {
       const ResidentPlan vp = reverse_plan((long long)d.BN);
       h->rev_chunk = vp.chunk; h->rev_P = vp.P; h->rev_npt = vp.npt;
+      // forward kernel over the whole chip with the candidates' rows requested ahead (ring_resident_forward.h): the
+      // reverse kernel's layout (ADSEQ_RING_FORWARD_BLOCKS taking-part blocks, default 256).  ADSEQ_RING_FORWARD_CHIP:
+      // see reverse_plan; ADSEQ_RING_FORWARD_MARGIN: candidate margin in thousandths of the membrane unit (default 5).
+      const ResidentPlan fp = reverse_plan((long long)d.BN, true);
+      if (fp.P > 0 && !d.count_pop) {
+        h->fwd_P = fp.P; h->fwd_chunk = fp.chunk; h->res_P = 0;
+        if (const char* e = getenv("ADSEQ_RING_FORWARD_MARGIN")) { const int v = atoi(e); if (v >= 0 && v <= 100000) h->fwd_margin = (float)v * 1e-3f; }
+      }
     }
     // chained step launches (ring_chain.h; experimental, off by default: measured slower than a launch per step on
     // one stream): delta synapse, and two launches' blocks must fit the chip side by side (512 blocks each at
@@ -1607,7 +1648,9 @@ int adseq_run(adseq_t* h, int64_t step0, int64_t n_steps, void* stream) {
   if (n_steps < 0) return fail(h, ADSEQ_E_INVALID_ARG, "adseq_run: negative step count");
   if (step0 != h->next_step)
     return fail(h, ADSEQ_E_ORDER, "adseq_run: got step %lld, expected %lld", (long long)step0, h->next_step);
-  if (h->dev.kind == ADSEQ_RING && h->res_P > 0) {
+  if (h->dev.kind == ADSEQ_RING && h->fwd_P > 0) {
+    ring_run_chip(h, (hipStream_t)stream, step0, n_steps);
+  } else if (h->dev.kind == ADSEQ_RING && h->res_P > 0) {
     ring_run_resident(h, (hipStream_t)stream, step0, n_steps);
   } else if (h->dev.kind == ADSEQ_RING && h->chain && n_steps >= 2 && chain_ready(h)) {
     ring_run_chain(h, (hipStream_t)stream, step0, n_steps);

@@ -117,6 +117,33 @@ def test_ring_popped_sum_is_counted(resident, monkeypatch):
     assert counted["sum_delivered"] != 0 and counted["delivered"] == ref.counters()["delivered"]
 
 
+@pytest.mark.parametrize("margin", ["20", "0", "100000"])
+@pytest.mark.parametrize("n,fan,b", [(100, 30, 1), (301, 200, 4), (2500, 60, 16), (40000, 20, 1), (131072, 6, 1)])
+def test_forward_chip_sizes_and_margins(n, fan, b, margin, monkeypatch):
+    """The forward kernel over the whole chip that requests the rows of the neurons about to spike ahead of the
+    barrier (ring_resident_forward.h; ADSEQ_RING_FORWARD_CHIP=1): membrane trace bit for bit, counters, spike counts.
+    One block to 128; a trial boundary inside a thread's neurons; the default margin, margin 0 (a neuron lifted over the
+    threshold by the last step's events was no candidate: the slow way) and a margin that makes every neuron a
+    candidate (only the first 32 of a block are requested ahead, the others go the slow way)."""
+    monkeypatch.setenv("ADSEQ_RING_FORWARD_CHIP", "1")
+    monkeypatch.setenv("ADSEQ_RING_FORWARD_MARGIN", margin)
+    wl = synth.ragged_network(n, fan, 40, seed=n + b, rate_hz=700.0, t=120, b=b, w_mean=0.6 / fan, w_std=0.4 / fan)
+    ref = _check(wl, 120, b, [120])
+    assert ref.spikes.sum() > 100
+
+
+@pytest.mark.parametrize("window", [2, 8, 64])
+def test_forward_chip_window_lengths_and_pieces(window, monkeypatch):
+    monkeypatch.setenv("ADSEQ_RING_FORWARD_CHIP", "1")
+    monkeypatch.setenv("ADSEQ_RING_WINDOW", str(window))
+    wl = synth.ragged_network(700, 300, 37, seed=5, rate_hz=300.0, t=150, b=2, w_mean=0.004, w_std=0.003)
+    ref = _check(wl, 150, 2, [1, 30, "s", "s", 7, 64, "s", 45])
+    assert ref.spikes.sum() > 300
+    # delays of one and two steps only: rows with more than 64 entries inside the window
+    wl = synth.ragged_network(900, 200, 2, seed=6, rate_hz=400.0, t=70, b=2, w_mean=0.004, w_std=0.004)
+    _check(wl, 70, 2, [70])
+
+
 @pytest.mark.parametrize("surrogate", [adseq.SURR_SUPERSPIKE, adseq.GRAD_SPIKE_TIME])
 @pytest.mark.parametrize("n,b,T", [(700, 3, 150), (6000, 2, 100)])
 def test_reverse_sweep_by_windows(surrogate, n, b, T, monkeypatch):
