@@ -37,6 +37,7 @@
 namespace {
 
 constexpr int kBlock = 256;
+constexpr int kArriveLines = 16;   // arrival counters of a grid barrier, a 128-byte line each (ring_resident_reverse.h)
 constexpr int kFanoutBlocks = 1024;
 
 enum : unsigned {
@@ -55,7 +56,7 @@ struct Counters {
   unsigned long long fold[3];       // scratch of k_count_spikes: spikes, events, Q8.24 sum
   alignas(128) unsigned bar[32];    // bar[0]: arrivals at the barriers of the resident step kernels (a line of its own)
   alignas(128) unsigned arrive[8][32];  // arrive[x][0]: blocks with index x mod 8 of the chained step launches that have arrived (ring_chain.h)
-  alignas(128) unsigned rev_arrivals[8][32];  // rev_arrivals[x][0]: arrivals of the blocks with rank x mod 8 at the barriers of the resident reverse kernel
+  alignas(128) unsigned rev_arrivals[kArriveLines][32];  // rev_arrivals[x][0]: arrivals of the blocks with rank x mod kArriveLines at the grid barriers of the resident reverse kernel and of the forward kernel over the whole chip
 #ifdef ADSEQ_PHASE_CLOCK
   unsigned long long phase[24];     // builds with phase clocks: 10 ns ticks block 0 spent in each phase; [0, 8) resident steps or
                                     // staging pass of the window expansion, [8, 11) accumulation pass, [15] expansions counted
@@ -1477,7 +1478,7 @@ int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, 
     if (h->chain) h->res_P = 0;
     h->chain_tpb = env_pow2("ADSEQ_RING_CHAIN_THREADS", 256, 256, 1024) == 1024 ? 1024 : 256;
     d.chain_sleep = env_pow2("ADSEQ_RING_CHAIN_SLEEP", 1, 0, 64);
-    d.rev_delay = env_pow2("ADSEQ_RING_REVERSE_DELAY", 1, 0, 16);
+    d.rev_delay = env_pow2("ADSEQ_RING_REVERSE_DELAY", 0, 0, 16);
     d.res_wide = env_pow2("ADSEQ_RING_RESIDENT_WIDE", 0, 0, 1);
   }
   hipStream_t st = (hipStream_t)cfg->stream;

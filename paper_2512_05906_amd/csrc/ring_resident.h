@@ -67,19 +67,19 @@ __device__ __forceinline__ void res_wait(const Dev& d, unsigned target, int* dea
 __device__ __forceinline__ void wide_arrive(const Dev& d, int rank) {
   wait_all_memory();
   __syncthreads();
-  if (threadIdx.x == kResThreads) atomicAdd(&d.ctr->rev_arrivals[rank & 7][0], 1u);
+  if (threadIdx.x == kResThreads) atomicAdd(&d.ctr->rev_arrivals[rank & (kArriveLines - 1)][0], 1u);
 }
 __device__ __forceinline__ void wide_wait(const Dev& d, unsigned target, int* dead) {
   if (threadIdx.x >= kResThreads && !*dead) {   // the synchronising wavefront, all lanes (the same way through for each)
     const int lane = threadIdx.x & 63;
-    const unsigned* p = &d.ctr->rev_arrivals[lane & 7][0];
+    const unsigned* p = &d.ctr->rev_arrivals[lane & (kArriveLines - 1)][0];
     for (int k = 0; k < d.rev_delay; ++k) __builtin_amdgcn_s_sleep(16);
     int spins = 0;
     for (;;) {
-      const unsigned v = lane < 8 ? ld_agent(p) : 0u;
+      const unsigned v = lane < kArriveLines ? ld_agent(p) : 0u;
       unsigned sum = 0;
 #pragma unroll
-      for (int x = 0; x < 8; ++x) sum += (unsigned)__builtin_amdgcn_readlane((int)v, x);
+      for (int x = 0; x < kArriveLines; ++x) sum += (unsigned)__builtin_amdgcn_readlane((int)v, x);
       if ((int)(sum - target) >= 0) break;
       if (++spins > d.res_spins) { if (lane == 0) { atomicOr(&d.ctr->err, ERR_BARRIER); *dead = 1; } break; }
     }

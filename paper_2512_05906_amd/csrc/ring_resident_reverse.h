@@ -63,7 +63,7 @@ struct RevBatch {
 __device__ __forceinline__ void rev_arrive(const Dev& d, bool arrive, int rank) {
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0); the other counters at their maximum
   __syncthreads();
-  if (arrive && threadIdx.x == kResThreads) atomicAdd(&d.ctr->rev_arrivals[rank & 7][0], 1u);
+  if (arrive && threadIdx.x == kResThreads) atomicAdd(&d.ctr->rev_arrivals[rank & (kArriveLines - 1)][0], 1u);
 }
 
 // The grid barrier's wait.  Arrivals at ONE counter queue up behind one another (11 ns each: 256 blocks, 2.8 us), so the
@@ -73,14 +73,14 @@ __device__ __forceinline__ void rev_arrive(const Dev& d, bool arrive, int rank) 
 __device__ __forceinline__ void rev_wait(const Dev& d, unsigned target, int* dead) {
   if (threadIdx.x >= kResThreads && !*dead) {   // the synchronising wavefront, all lanes (the same way through for each)
     const int lane = threadIdx.x & 63;
-    const unsigned* p = &d.ctr->rev_arrivals[lane & 7][0];
+    const unsigned* p = &d.ctr->rev_arrivals[lane & (kArriveLines - 1)][0];
     for (int k = 0; k < d.rev_delay; ++k) __builtin_amdgcn_s_sleep(16);
     int spins = 0;
     for (;;) {
-      const unsigned v = lane < 8 ? ld_agent(p) : 0u;
+      const unsigned v = lane < kArriveLines ? ld_agent(p) : 0u;
       unsigned sum = 0;
 #pragma unroll
-      for (int x = 0; x < 8; ++x) sum += (unsigned)__builtin_amdgcn_readlane((int)v, x);
+      for (int x = 0; x < kArriveLines; ++x) sum += (unsigned)__builtin_amdgcn_readlane((int)v, x);
       if ((int)(sum - target) >= 0) break;
       if (++spins > d.res_spins) { if (lane == 0) { atomicOr(&d.ctr->err, ERR_BARRIER); *dead = 1; } break; }
     }

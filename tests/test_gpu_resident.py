@@ -275,6 +275,7 @@ def test_resident_reverse_wait_that_runs_out_is_reported(monkeypatch):
     ordinary limit gives the oracle's gradients."""
     monkeypatch.setenv("ADSEQ_RING_REVERSE_WINDOWS", "0")
     monkeypatch.setenv("ADSEQ_RING_RESIDENT", "0")
+    monkeypatch.setenv("ADSEQ_RING_FORWARD_CHIP", "0")   # (the forward run by one launch per step: no wait of its own to run out)
     monkeypatch.setenv("ADSEQ_RING_REVERSE_DELAY", "0")
     wl = synth.ragged_network(40000, 30, 20, seed=45, rate_hz=700.0, t=60, b=2, w_mean=0.02, w_std=0.01)
     sim = adseq.Adseq(wl, adseq.RING, 0, record_tape=True, max_steps=60)
@@ -297,6 +298,31 @@ def test_resident_reverse_wait_that_runs_out_is_reported(monkeypatch):
     monkeypatch.delenv("ADSEQ_RING_RESIDENT_SPINS")
     monkeypatch.delenv("ADSEQ_RING_REVERSE_DELAY")
     _reverse_against_oracle(wl, 60, 2)
+
+
+def test_forward_chip_wait_that_runs_out_is_reported(monkeypatch):
+    """The same for the forward kernel over the whole chip: one poll per wait, no delay before it; the kernels run
+    to their end, the error word carries bit 32, adseq_drop_count and adseq_backward refuse the run, a reset clears it."""
+    monkeypatch.setenv("ADSEQ_RING_FORWARD_CHIP", "1")
+    monkeypatch.setenv("ADSEQ_RING_REVERSE_DELAY", "0")
+    monkeypatch.setenv("ADSEQ_RING_RESIDENT_SPINS", "1")
+    wl = synth.ragged_network(40000, 30, 20, seed=46, rate_hz=700.0, t=60, b=2, w_mean=0.02, w_std=0.01)
+    sim = adseq.Adseq(wl, adseq.RING, 0, record_tape=True, max_steps=60)
+    sim.run(0, 60)
+    torch.cuda.synchronize()
+    assert sim.counters()["error_bits"] & 32
+    with pytest.raises(adseq.AdseqError):
+        sim.drop_count()
+    g = torch.empty(wl.n_synapses, device=sim.dev)
+    with pytest.raises(adseq.AdseqError):
+        sim.backward(torch.zeros(2 * 40000, device=sim.dev), None, g, g.clone())
+    sim.reset()
+    assert sim.counters()["error_bits"] == 0
+    sim.close()
+    monkeypatch.delenv("ADSEQ_RING_RESIDENT_SPINS")
+    monkeypatch.delenv("ADSEQ_RING_REVERSE_DELAY")
+    ref = _check(wl, 60, 2, [60])
+    assert ref.spikes.sum() > 100
 
 
 def test_range_warning_for_sums_that_could_wrap():
