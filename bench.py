@@ -200,6 +200,9 @@ def main():
     if args.queue == "ring" and prof.get("bwd_neurons", {}).get("launches", T) < T:
         # fewer launches than steps: the reverse steps of a window ran in one launch each (resident reverse kernel)
         label["bwd_neurons"] = "k_bwd_xcd (the reverse steps of one window in one launch: adjoint update + in-window gather, a grid barrier per step)"
+    if args.queue == "ring" and prof.get("lif", {}).get("launches", T) < T:
+        # likewise forward: the steps of a window in one launch over the whole chip
+        label["lif"] = "k_fwd_chip (the steps of one window in one launch: pop + drive + LIF + spike bits + in-window scatter, a grid barrier per step)"
     kernels = {}
     for k, v in prof.items():
         if v["launches"]:

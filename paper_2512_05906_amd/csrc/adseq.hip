@@ -1120,7 +1120,7 @@ void ring_run_chip(adseq* h, hipStream_t st, long long step0, long long n_steps)
     if (record) hipLaunchKernelGGL((k_fwd_chip<true>), grid, block, 0, st, n, cnt, h->rev_base, h->fwd_P, h->fwd_chunk, stride, h->fwd_margin, d);
     else hipLaunchKernelGGL((k_fwd_chip<false>), grid, block, 0, st, n, cnt, h->rev_base, h->fwd_P, h->fwd_chunk, stride, h->fwd_margin, d);
     h->rev_base += (unsigned)(cnt - 1) * (unsigned)h->fwd_P;
-    h->grp_count += cnt;
+    h->grp_count += 1;   // (launches of the group)
     h->enq_calls += cnt;
     n += cnt;
     h->next_step = n;
