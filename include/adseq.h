@@ -217,8 +217,13 @@ int adseq_run_open(adseq_t *h, int64_t step0, int64_t n_steps, const int32_t *sp
  * [B*N] or NULL. */
 int adseq_step(adseq_t *h, int64_t step, const float *i_ext, uint8_t *spikes_out, void *stream);
 
-/* n_steps closed-loop steps starting at `step0` (same as calling adseq_step in a loop with
- * i_ext = spikes_out = NULL). */
+/* n_steps closed-loop steps starting at `step0` (same results as calling adseq_step in a loop with
+ * i_ext = spikes_out = NULL).  ADSEQ_RING runs the steps between two window boundaries in ONE kernel
+ * whose blocks (at most one per compute unit) wait for one another at a barrier per step; such a
+ * launch needs the device free enough for all its blocks to run at the same time.  Every wait is
+ * bounded: if one runs out, the kernels still run to their end, the run is void, and the error
+ * word carries bit 32 (adseq_counters; adseq_drop_count and adseq_backward then return
+ * ADSEQ_E_HIP until adseq_reset). */
 int adseq_run(adseq_t *h, int64_t step0, int64_t n_steps, void *stream);
 
 /* Reverse-time sweep over the T steps recorded since the last reset (Section 3.2: the event
