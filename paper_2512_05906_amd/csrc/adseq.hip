@@ -931,7 +931,7 @@ void launch_expansion(adseq* h, hipStream_t st, long long k0, long long n_lo, lo
   static const int sort_stage = env_pow2("ADSEQ_RING_SORTSTAGE", 1, 0, 1);
   const int stage = d.cap > 0 ? ((sort_stage && d.P <= kSortParts) ? 2 : 1) : 0;
   hipLaunchKernelGGL(k_win_bin, dim3((unsigned)d.NB), dim3(kRingThreads), 0, st, d, k0, n_lo, n_hi, 0, d.NB,
-                     stage, count_from, (h->res_P > 0 || h->fwd_P > 0) ? 1 : 0);
+                     stage, count_from, h->res_P > 0 ? 1 : 0);
   if (d.cap > 0) {
     const int parts = d.P < kMaxParts ? d.P : kMaxParts;
     hipLaunchKernelGGL(k_win_acc, dim3((unsigned)parts), dim3(kRingThreads), 0, st, d, k0, 0);

@@ -17,8 +17,8 @@
 // same order, as k_step_win.
 //
 // Membrane state, row bounds and the step-independent half of the drive's hash stay in registers
-// for the launch; tape, spike words and spike counts are stored after the arrival.  The popped
-// cells are not cleared here (the expansion at the next window boundary zeroes the used buffer).
+// for the launch; the popped cells are cleared, and tape, spike words and spike counts stored, after
+// the arrival.
 
 constexpr int kFwdCand = 32;   // candidates per block and step whose rows are requested ahead (four per worker wavefront)
 
@@ -241,7 +241,12 @@ __global__ __launch_bounds__(kResLaunch) void k_fwd_chip(long long n0, int nstep
     }
     rev_arrive(d, k + 1 < nsteps, rank);   // (adds acknowledged; every wavefront has read the lists)
     if (threadIdx.x == 0) s_nslow = 0;   // (the next step's slow spikes are counted behind its first block barrier)
-    // ---- after the arrival, off the chain: tape, spike words and counts of this step
+    // ---- after the arrival, off the chain: the popped cells cleared (nothing adds to them before the window after next
+    // is expanded, launches later), tape, spike words and counts of this step
+    {
+      const res_v4i z = {0, 0, 0, 0};
+      __builtin_amdgcn_raw_buffer_store_b128(z, cells, g0 * 4, 0, 0);
+    }
     if (RECORD) {
       const __amdgpu_buffer_rsrc_t tape = res_rows(d.tapeU + (size_t)n * d.BN, hi * 4);
       const res_v4f u4 = {U[0], U[1], U[2], U[3]};
