@@ -220,7 +220,9 @@ int adseq_step(adseq_t *h, int64_t step, const float *i_ext, uint8_t *spikes_out
 /* n_steps closed-loop steps starting at `step0` (same results as calling adseq_step in a loop with
  * i_ext = spikes_out = NULL).  ADSEQ_RING runs the steps between two window boundaries in ONE kernel
  * whose blocks (at most one per compute unit) wait for one another at a barrier per step; such a
- * launch needs the device free enough for all its blocks to run at the same time.  Every wait is
+ * launch needs the device free enough for all its blocks to run at the same time.  adseq_create
+ * asks the runtime how many such blocks the device holds at once and, below 256, keeps to one
+ * launch per step (same results).  Every wait is
  * bounded: if one runs out, the kernels still run to their end, the run is void, and the error
  * word carries bit 32 (adseq_counters; adseq_drop_count and adseq_backward then return
  * ADSEQ_E_HIP until adseq_reset). */

@@ -595,6 +595,27 @@ ResidentPlan reverse_plan(long long BN, bool forward = false) {
   }
   return r;
 }
+// The grid barrier of the resident kernels ends only when every block of the launch (kResLaunch threads each, 256
+// blocks at most: one per compute unit of the MI355X) is on the chip at the same time.  True when the device can hold
+// 256 blocks of kernel f at once; where it cannot (fewer compute units, or a kernel too large for one), the time steps
+// go by one launch each.  ADSEQ_RING_ASSUME_CUS replaces the device's compute-unit count in this check (tests of the
+// decision; it changes nothing else).
+bool resident_fits(const void* f) {
+  int dev = 0, cus = 0, per = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return false;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return false;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per, f, kResLaunch, 0) != hipSuccess) { (void)hipGetLastError(); return false; }
+  if (const char* e = getenv("ADSEQ_RING_ASSUME_CUS")) { const int v = atoi(e); if (v >= 1 && v <= 4096) cus = v; }
+  return (long long)cus * per >= 256;
+}
+template <bool RECORD>
+const void* run_xcd_kernel_of(int syn, int npt) {
+  if (npt == 1) return syn == 0 ? (const void*)k_run_xcd<RECORD, 0, 1> : (syn == 1 ? (const void*)k_run_xcd<RECORD, 1, 1> : (const void*)k_run_xcd<RECORD, 2, 1>);
+  return syn == 0 ? (const void*)k_run_xcd<RECORD, 0, 2> : (syn == 1 ? (const void*)k_run_xcd<RECORD, 1, 2> : (const void*)k_run_xcd<RECORD, 2, 2>);
+}
+const void* run_xcd_kernel(bool record, int syn, int npt) {
+  return record ? run_xcd_kernel_of<true>(syn, npt) : run_xcd_kernel_of<false>(syn, npt);
+}
 // Cells (target, step) of the LDS tile of one target part.
 int ring_tile_cells() { return env_pow2("ADSEQ_RING_TILE", 4096, 1024, kMaxTileCells); }
 
@@ -1455,15 +1476,19 @@ int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, 
   d.bwd_G = (float*)(ws + L.bwd_G);
 
   if (d.kind == ADSEQ_RING) {
-    const ResidentPlan rp = resident_plan((long long)d.BN);
+    const int syn = d.alpha_r > 0.0f ? 2 : (d.alpha_s > 0.0f ? 1 : 0);
+    ResidentPlan rp = resident_plan((long long)d.BN);
+    if (rp.P > 0 && !(resident_fits(run_xcd_kernel(true, syn, rp.npt)) && resident_fits(run_xcd_kernel(false, syn, rp.npt)))) rp = ResidentPlan();
     h->res_chunk = rp.chunk; h->res_P = rp.P; h->res_npt = rp.npt;
     if (!(d.alpha_s > 0.0f)) {
-      const ResidentPlan vp = reverse_plan((long long)d.BN);
+      ResidentPlan vp = reverse_plan((long long)d.BN);
+      if (vp.P > 0 && !(resident_fits((const void*)k_bwd_xcd<true>) && resident_fits((const void*)k_bwd_xcd<false>))) vp = ResidentPlan();
       h->rev_chunk = vp.chunk; h->rev_P = vp.P; h->rev_npt = vp.npt;
       // forward kernel over the whole chip with the candidates' rows requested ahead (ring_resident_forward.h): the
       // reverse kernel's layout (ADSEQ_RING_FORWARD_BLOCKS taking-part blocks, default 256).  ADSEQ_RING_FORWARD_CHIP:
       // see reverse_plan; ADSEQ_RING_FORWARD_MARGIN: candidate margin in thousandths of the membrane unit (default 5).
-      const ResidentPlan fp = reverse_plan((long long)d.BN, true);
+      ResidentPlan fp = reverse_plan((long long)d.BN, true);
+      if (fp.P > 0 && !(resident_fits((const void*)k_fwd_chip<true>) && resident_fits((const void*)k_fwd_chip<false>))) fp = ResidentPlan();
       if (fp.P > 0 && !d.count_pop) {
         h->fwd_P = fp.P; h->fwd_chunk = fp.chunk; h->res_P = 0;
         if (const char* e = getenv("ADSEQ_RING_FORWARD_MARGIN")) { const int v = atoi(e); if (v >= 0 && v <= 100000) h->fwd_margin = (float)v * 1e-3f; }

@@ -269,6 +269,33 @@ def test_resident_reverse_falls_back_where_the_layout_does_not_fit(monkeypatch):
     _reverse_against_oracle(wl, 40, 1)
 
 
+def test_resident_kernels_need_their_blocks_on_the_chip_together(monkeypatch):
+    """The grid barrier needs all blocks of a launch resident at once.  A device that cannot hold them (here: the
+    host check is told of 64 compute units) gets one launch per time step, forward and in reverse, and the same
+    results; with the real count the windows go by one launch each."""
+    wl = synth.ragged_network(6000, 40, 30, seed=47, rate_hz=600.0, t=64, b=2, w_mean=0.02, w_std=0.01)
+
+    def launches():
+        sim = adseq.Adseq(wl, adseq.RING, 0, batch=2, record_tape=True, max_steps=64)
+        sim.profile(True)
+        sim.run(0, 64)
+        g = torch.empty(wl.n_synapses, device=sim.dev)
+        sim.backward(torch.zeros(2 * 6000, device=sim.dev) + 1e-3, None, g, g.clone())
+        torch.cuda.synchronize()
+        p = sim.profile_read()
+        assert sim.counters()["error_bits"] == 0
+        sim.close()
+        return p["lif"]["launches"], p["bwd_neurons"]["launches"]
+
+    fwd, rev = launches()
+    assert fwd < 64 and rev < 64
+    monkeypatch.setenv("ADSEQ_RING_ASSUME_CUS", "64")
+    fwd, rev = launches()
+    assert fwd == 64 and rev == 64
+    _check(wl, 64, 2, [64])
+    _reverse_against_oracle(wl, 64, 2)
+
+
 def test_resident_reverse_wait_that_runs_out_is_reported(monkeypatch):
     """Failure path of the reverse kernel's bounded waits, forced from the host (one poll per wait): every kernel
     runs to its end, the error word carries bit 32 after the sweep, a reset clears it, and a handle with the
