@@ -131,10 +131,14 @@ def main():
         nwin = max(1, int(ticks[15]))
         # (block 0 of each launch; the expansions of the last forward run from step 512 on, where the spike history is full)
         phase_clocks = {"windows": nwin, "us_per_window": {nm: round(ticks[i] * 0.01 / nwin, 3) for i, nm in enumerate(names)}}
-        spans = (ctypes.c_uint64 * 2048)()
+        ngat = max(1, int(ticks[19]))
+        phase_clocks["gathers"] = ngat   # (far gathers of the last reverse sweep, block 0 of each launch)
+        phase_clocks["us_per_gather"] = {nm: round(ticks[16 + i] * 0.01 / ngat, 3) for i, nm in enumerate(
+            ["gather: walk over the spike words", "gather: row pieces, adjoints, sums", "gather: the block's other wavefronts"])}
+        spans = (ctypes.c_uint64 * 3072)()
         assert sim.lib.adseq_debug_block_spans(sim.h, spans, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)) == 0
-        sp = np.array(spans[:], dtype=np.float64).reshape(2, 512, 2)
-        for k, nm in enumerate(("staging", "accumulation")):   # blocks of the last launch of each pass: when they began and ended
+        sp = np.array(spans[:], dtype=np.float64).reshape(3, 512, 2)
+        for k, nm in enumerate(("staging", "accumulation", "gather")):   # blocks of the last launch of each pass: when they began and ended
             on = sp[k][:, 1] > 0
             if on.any():
                 t0 = sp[k][on, 0].min()

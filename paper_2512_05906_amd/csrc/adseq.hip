@@ -59,8 +59,8 @@ struct Counters {
   alignas(128) unsigned rev_arrivals[kArriveLines][32];  // rev_arrivals[x][0]: arrivals of the blocks with rank x mod kArriveLines at the grid barriers of the resident reverse kernel and of the forward kernel over the whole chip
 #ifdef ADSEQ_PHASE_CLOCK
   unsigned long long phase[24];     // builds with phase clocks: 10 ns ticks block 0 spent in each phase; [0, 8) resident steps or
-                                    // staging pass of the window expansion, [8, 11) accumulation pass, [15] expansions counted
-  unsigned long long span[2][512][2]; // the same builds: wall clock at begin and end of every block of the last staging [0] and accumulation [1] launch
+                                    // staging pass of the window expansion, [8, 11) accumulation pass, [15] expansions counted, [16, 19) far gather of the reverse sweep (walk, pieces, waiting for the block's other wavefronts), [19] gathers counted
+  unsigned long long span[3][512][2]; // the same builds: wall clock at begin and end of every block of the last staging [0], accumulation [1] and far gather [2] launch
 #endif
 };
 
@@ -1901,11 +1901,11 @@ int adseq_debug_phase_clocks(adseq_t* h, uint64_t* out24, void* stream) {
   if (hipMemcpyAsync(out24, h->dev.ctr->phase, sizeof(unsigned long long) * 24, hipMemcpyDeviceToHost, st) != hipSuccess) return ADSEQ_E_HIP;
   return hipStreamSynchronize(st) == hipSuccess ? ADSEQ_OK : ADSEQ_E_HIP;
 }
-// The block spans of the last staging and accumulation launch: out[2][512][2] ticks.
+// The block spans of the last staging, accumulation and far gather launch: out[3][512][2] ticks.
 int adseq_debug_block_spans(adseq_t* h, uint64_t* out, void* stream) {
   if (!h || !out) return ADSEQ_E_INVALID_ARG;
   hipStream_t st = (hipStream_t)stream;
-  if (hipMemcpyAsync(out, h->dev.ctr->span, sizeof(unsigned long long) * 2 * 512 * 2, hipMemcpyDeviceToHost, st) != hipSuccess) return ADSEQ_E_HIP;
+  if (hipMemcpyAsync(out, h->dev.ctr->span, sizeof(unsigned long long) * 3 * 512 * 2, hipMemcpyDeviceToHost, st) != hipSuccess) return ADSEQ_E_HIP;
   return hipStreamSynchronize(st) == hipSuccess ? ADSEQ_OK : ADSEQ_E_HIP;
 }
 #endif

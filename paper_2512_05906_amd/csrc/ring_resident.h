@@ -203,7 +203,7 @@ __global__ __launch_bounds__(kResLaunch) void k_run_xcd(long long n0, int nsteps
   unsigned long long pc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, pt = wall_clock64();
 #define PHASE(i) { const unsigned long long t_ = wall_clock64(); pc[i] += t_ - pt; pt = t_; }
 #else
-#define PHASE(i)
+#define PHASE(i) {}
 #endif
 #ifdef ADSEQ_ABLATE
 #define DBG_SKIP(bit) (d.dbg & (bit))

@@ -403,9 +403,9 @@ __global__ __launch_bounds__(kBlock) void k_open_step_win(Dev d, long long n, co
 #define XPH_BEGIN
 #define XPH_ARG
 #define XPH_PASS
-#define XPH(i)
-#define XPH_COUNT(i)
-#define XPH_SPAN(k, e)
+#define XPH(i) {}          // (empty blocks, so that a mark after an `if` never leaves the next statement under it)
+#define XPH_COUNT(i) {}
+#define XPH_SPAN(k, e) {}
 #endif
 
 // Streaming loads of the expansion and gather passes (row pieces and staged events are read
@@ -1160,6 +1160,10 @@ __global__ __launch_bounds__(kBlock) void k_bwd_step_win(long long n, long long 
 template <bool DEXP>
 __device__ __forceinline__ void role_gather(const Dev& d, ExpandLds& L, long long k0, long long n_lo, long long n_hi,
                                             long long T, int vb, int nvb) {
+  XPH_BEGIN
+#ifdef ADSEQ_PHASE_CLOCK
+  if (k0 == 512) XPH_SPAN(2, 0)   // (one window from the middle of the run)
+#endif
   if (threadIdx.x == 0) { L.qn = 0; L.qhead = 0; }
   __syncthreads();
   const int lane = threadIdx.x & 63;
@@ -1195,6 +1199,7 @@ __device__ __forceinline__ void role_gather(const Dev& d, ExpandLds& L, long lon
   };
   long long cnt[3] = {0, 0, 0};
   walk_segments(d, L, d.tape_bits, false, k0, n_lo, n_hi, T, vb, nvb, n_hi, cnt, one);
+  XPH(16)
   const int qn = L.qn < kSegQueue ? L.qn : kSegQueue;
   for (;;) {
     int t = 0;
@@ -1238,6 +1243,14 @@ __device__ __forceinline__ void role_gather(const Dev& d, ExpandLds& L, long lon
       finish(o[j], G);
     }
   }
+#ifdef ADSEQ_PHASE_CLOCK
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // (the clock reads after the wavefront's own loads and adds)
+  XPH(17)
+  __syncthreads();
+  XPH(18)
+  XPH_COUNT(19)
+  if (k0 == 512) XPH_SPAN(2, 1)
+#endif
 }
 
 template <bool DEXP>
