@@ -694,15 +694,21 @@ bool make_layout(const adseq_config* c, Layout* L) {
     L->W = ring_window_steps();
     while (L->W > c->d_max_steps) L->W >>= 1;
     L->wshift = bit_width((unsigned)L->W) - 1;
+    // LDS tile of the accumulation pass: by default 4,096 cells, fewer (down to 1,024) where the state array would
+    // otherwise give fewer than 256 target parts, one workgroup each (cfg2, 10,000 targets: 40 parts of 256 targets
+    // left five compute units in six idle; expansion 30.8 -> 22.2 us per window with 157 parts of 64)
     int cells = ring_tile_cells();
+    if (!getenv("ADSEQ_RING_TILE"))
+      while (cells > 1024 && cells > 2 * L->W && (long long)BN * L->W / cells < 256) cells >>= 1;
     if (cells < L->W) cells = L->W;
     L->tp_shift = bit_width((unsigned)cells) - 1 - L->wshift;
     L->P = (int)((BN + ((size_t)1 << L->tp_shift) - 1) >> L->tp_shift);
     L->wgroups = (L->words + 7) / 8;
-    // blocks of the staging pass: about four 8-word lines per wavefront when the history is
-    // full, but no more than one block per compute unit (measured best on cfg3: 256 of 128..512)
+    // blocks of the staging pass: one 8-word line per wavefront when the history is full, but no
+    // more than one block per compute unit (measured best on cfg3: 256 of 128..512; cfg2, 4,000 lines:
+    // 22.2 us per window with 63 blocks, 19.6 with 128 or 256; cfg1, 1,600 lines: 14.6 with 25, 12.0 with 128)
     const long long lines = (long long)c->d_max_steps * L->wgroups;
-    long long nb = (lines + 4 * kRingWaves - 1) / (4 * kRingWaves);
+    long long nb = (lines + kRingWaves - 1) / kRingWaves;
     L->NB = env_pow2("ADSEQ_RING_BINBLOCKS", (int)(nb < 1 ? 1 : (nb > 256 ? 256 : nb)), 1, kMaxBinBlocks);
     stage_parts = (size_t)(L->P < kMaxParts ? L->P : kMaxParts);
     // staging capacity in events: by default what a window holds when every neuron fires at
@@ -1201,11 +1207,12 @@ void ring_run_chain(adseq* h, hipStream_t st, long long step0, long long n_steps
   if (forked) chain_join(h, st);
 }
 
-// RING: virtual blocks of one far gather over the spikes of steps [n_lo, n_hi): about four
-// 8-word lines per wavefront.
+// RING: virtual blocks of one far gather over the spikes of steps [n_lo, n_hi): one 8-word line per
+// wavefront, one block per compute unit at most (cfg2, 4,000 lines: 19.0 us per window with 63 blocks, 14.0 with 128,
+// 12.2 with 256, 14.0 with 512; cfg3: 256 of 128..1,024).
 int gather_blocks(const Dev& d, long long n_lo, long long n_hi) {
   const long long lines = (n_hi - n_lo) * d.wgroups;
-  long long g = (lines + 4 * kRingWaves - 1) / (4 * kRingWaves);
+  long long g = (lines + kRingWaves - 1) / kRingWaves;
   return env_pow2("ADSEQ_RING_GATHERBLOCKS", (int)(g < 1 ? 1 : (g > 256 ? 256 : g)), 1, 2048);
 }
 
