@@ -6,7 +6,7 @@ session has collected that module (tests/conftest.py) and overlap with each othe
 GPU tests that come before; a test takes its reference with get(name), which waits for the run.
 Every run appends a line per 50 time steps of its first trial, and one per further trial, to
 the progress log in the run's output folder (the oracle's own progress hook), so that a long wait is not
-mistaken for a hang.  The two runs of config 4 (256 trials over 5,000 steps: 47 GB inside the
+mistaken for a hang.  The four runs of config 4 (256 trials over 5,000 steps: 47 GB inside the
 oracle each) take turns in one worker of their own, with 16 threads over the trials."""
 import os
 import threading
@@ -29,6 +29,7 @@ _futures = {}
 JOBS = {
     "cfg3_ring_T1000": ("cfg3", oracle.RING, 0, 1000, True),
     "cfg3_fifo32_T1000": ("cfg3", oracle.FIFO, 32, 1000, True),
+    "cfg3_synfifo4_T1000": ("cfg3", oracle.SYN_FIFO, 4, 1000, True),
     "cfg3_sorted32_T300": ("cfg3_55hz", oracle.SORTED, 32, 300, True),
     "cfg3_latest_T300": ("cfg3_55hz", oracle.SYN_LATEST, 1, 300, True),
     "cfg2_ring_T10000": ("cfg2_5hz", oracle.RING, 0, 10000, False),
@@ -37,8 +38,11 @@ JOBS = {
     "cfg2_20hz_ring_T10000": ("cfg2_20hz", oracle.RING, 0, 10000, False),
     "cfg2_20hz_fifo8_T10000": ("cfg2_20hz", oracle.FIFO, 8, 10000, False),
     "cfg2_20hz_fifo32_T10000": ("cfg2_20hz", oracle.FIFO, 32, 10000, False),
+    "cfg2_20hz_synfifo4_T10000": ("cfg2_20hz", oracle.SYN_FIFO, 4, 10000, False),
     "cfg4_sorted128_T5000": ("cfg4", oracle.SORTED, 128, 5000, True),
     "cfg4_fifo32_T5000": ("cfg4", oracle.FIFO, 32, 5000, True),
+    "cfg4_ring_T5000": ("cfg4", oracle.RING, 0, 5000, True),
+    "cfg4_synfifo4_T5000": ("cfg4", oracle.SYN_FIFO, 4, 5000, True),
 }
 
 
