@@ -2,8 +2,9 @@
 configuration bench.py times (same grids, same window length, same staging regions):
 
 * the headline network (100,000 neurons x fan-out 1,000 = 1e8 synapses, delays 1..250 steps) over
-  the 1,000 steps and with the drive of the run bench.py times, ring, FIFO[32] and one FIFO[4] per
-  synapse: membrane trace bit for bit, all counters, spike counts, and every entry of both gradients;
+  the 1,000 steps and with the drive of the run bench.py times, every queue kind (ring, FIFO[32],
+  sorted[32], per synapse FIFO[4], latest-spike slot, 4 time bins): membrane trace bit for bit, all
+  counters, spike counts, and every entry of both gradients;
 * the same network with the sorted queue and with the latest-spike slot per synapse (300 steps at
   a stronger drive: 2.5e7 events, longer than the largest delay, so the spike history wraps);
 * config 2 (10,000 neurons x 1,000) over its 10,000 steps with the drives tuned for 5 and for 20 Hz:
@@ -52,8 +53,8 @@ def _check_forward(sim, ref, T):
     return rc
 
 
-@pytest.mark.parametrize("name", ["cfg3_sorted32_T300", "cfg3_latest_T300", "cfg3_fifo32_T1000", "cfg3_ring_T1000",
-                                  "cfg3_synfifo4_T1000"])
+@pytest.mark.parametrize("name", ["cfg3_sorted32_T300", "cfg3_latest_T300", "cfg3_fifo32_T1000", "cfg3_sorted32_T1000",
+                                  "cfg3_ring_T1000", "cfg3_synfifo4_T1000", "cfg3_latest_T1000", "cfg3_bins4_T1000"])
 def test_cfg3_whole(name):
     key, kind, cap, T, _ = whole_refs.JOBS[name]
     wl = whole_refs.workload(key)
@@ -63,12 +64,14 @@ def test_cfg3_whole(name):
     ref = whole_refs.get(name)
     rc = _check_forward(sim, ref, T)
     if name.endswith("T1000"):   # the run bench.py times: 2e8 events offered to the ring
-        assert rc["enqueued"] > (1.5e8 if kind in (oracle.RING, oracle.SYN_FIFO) else 5e7)
+        assert rc["enqueued"] > (1.5e8 if kind in (oracle.RING, oracle.SYN_FIFO) else 5e7)   # (the lossy kinds fire less)
         if kind == oracle.RING:
             rate = ref["counts"].sum() / (wl.n_neurons * T * wl.dt_ms * 1e-3)
             assert 19.0 < rate < 21.0 and rc["dropped"] == 0
         elif kind == oracle.SYN_FIFO:   # a synapse would have to carry more than four spikes of its one source at once
             assert 0 < rc["dropped"] < 1e-5 * rc["enqueued"]
+        elif kind in (oracle.SYN_LATEST, oracle.SYN_BINS):   # one slot loses 9 %, four time bins 2.5 %
+            assert 0.01 < rc["dropped"] / rc["enqueued"] < 0.12
         else:
             assert 0.6 < rc["dropped"] / rc["enqueued"] < 0.8
     else:

@@ -30,6 +30,9 @@ JOBS = {
     "cfg3_ring_T1000": ("cfg3", oracle.RING, 0, 1000, True),
     "cfg3_fifo32_T1000": ("cfg3", oracle.FIFO, 32, 1000, True),
     "cfg3_synfifo4_T1000": ("cfg3", oracle.SYN_FIFO, 4, 1000, True),
+    "cfg3_sorted32_T1000": ("cfg3", oracle.SORTED, 32, 1000, True),
+    "cfg3_latest_T1000": ("cfg3", oracle.SYN_LATEST, 1, 1000, True),
+    "cfg3_bins4_T1000": ("cfg3", oracle.SYN_BINS, 4, 1000, True),
     "cfg3_sorted32_T300": ("cfg3_55hz", oracle.SORTED, 32, 300, True),
     "cfg3_latest_T300": ("cfg3_55hz", oracle.SYN_LATEST, 1, 300, True),
     "cfg2_ring_T10000": ("cfg2_5hz", oracle.RING, 0, 10000, False),
