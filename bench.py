@@ -135,6 +135,10 @@ def main():
         phase_clocks["gathers"] = ngat   # (far gathers of the last reverse sweep, block 0 of each launch)
         phase_clocks["us_per_gather"] = {nm: round(ticks[16 + i] * 0.01 / ngat, 3) for i, nm in enumerate(
             ["gather: walk over the spike words", "gather: row pieces, adjoints, sums", "gather: the block's other wavefronts"])}
+        if ticks[21]:   # reverse steps of the resident reverse kernel without a grid barrier (wavefront 0 of block 0)
+            phase_clocks["us_per_reverse_step"] = {nm: round(ticks[i] * 0.01 / int(ticks[21]), 3) for i, nm in (
+                (22, "requests"), (23, "row computed and stored"), (11, "gathers issued"), (12, "next step's spikes listed, their rows requested"),
+                (13, "gathers complete, per-spike sums"), (14, "spiking neurons stored, block barrier"), (20, "requests of the step complete"))}
         spans = (ctypes.c_uint64 * 3072)()
         assert sim.lib.adseq_debug_block_spans(sim.h, spans, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)) == 0
         sp = np.array(spans[:], dtype=np.float64).reshape(3, 512, 2)

@@ -168,6 +168,7 @@ struct Dev {
   BlkCtr* blk;   // FIFO / SORTED: [nblk + kFanoutBlocks]
   // (what was added later stays behind what the per-step kernels read, whose place in the argument block is tuned)
   long long* insum;     // [N] create only: sum of |Q8.24 amplitude| over every target's incoming synapses
+  int flow_hold;        // RING, reverse kernel without a grid barrier: 1 = spiking neurons never store their final adjoints (ADSEQ_RING_FLOW_WITHHOLD: drives the waits' failure path from the host)
   int res_spins;        // RING, resident kernels: polls of one wait before it gives up (kResMaxSpins; ADSEQ_RING_RESIDENT_SPINS lowers it to test the failure path)
   int lazy_rows;        // RING: the step kernels fetch row start, in-window count and far queue term for spiking lanes only (experiment)
   int count_pop;        // RING: the step kernels add up the Q8.24 sums they pop (checking aid, off by default)
@@ -385,6 +386,7 @@ __global__ __launch_bounds__(kBlock) void k_in_check(Dev d) {
 #include "ring_resident.h"
 #include "ring_reverse.h"
 #include "ring_resident_reverse.h"
+#include "ring_flow_reverse.h"
 #include "ring_resident_forward.h"
 #include "ring_chain.h"
 
@@ -512,6 +514,7 @@ struct adseq {
   unsigned rev_base = 0;      // RING, resident reverse kernel: sum of its arrival counters after the launches so far
   int res_P = 0, res_chunk = 0, res_npt = 0;   // RING: taking-part blocks, neurons per block, per thread (0: one launch per step)
   int rev_P = 0, rev_chunk = 0, rev_npt = 0;   // RING, reverse sweep: the same for the resident reverse kernel (0: one launch per step)
+  bool rev_flow = false;                      // RING: the resident reverse kernel without a grid barrier (ring_flow_reverse.h)
   int fwd_P = 0, fwd_chunk = 0;                // RING: the same for the forward kernel over the whole chip (ring_resident_forward.h; 0: not used)
   float fwd_margin = 0.005f;                   // how far below the threshold the early value of a candidate may lie
   // RING, experimental (ADSEQ_RING_OVERLAP = 1): the far part of the next window expanded ahead on a stream of the library's own
@@ -585,7 +588,9 @@ ResidentPlan reverse_plan(long long BN, bool forward = false) {
   // barrier is shorter, are faster -- 100 cells 2.4 against 2.9 us per step)
   const int fwd = env_pow2("ADSEQ_RING_FORWARD_CHIP", 2, 0, 2);
   const int on = forward ? ((fwd == 1 || (fwd == 2 && BN >= 2048)) ? 1 : 0) : env_pow2("ADSEQ_RING_RESIDENT_REVERSE", 1, 0, 1);
-  const int blocks = forward ? env_pow2("ADSEQ_RING_FORWARD_BLOCKS", 256, 8, 256) : env_pow2("ADSEQ_RING_REVERSE_BLOCKS", 128, 8, 256);
+  // (reverse: 256 blocks for the kernel without a grid barrier, 128 for the one with: its barrier costs more with more blocks)
+  const int blocks = forward ? env_pow2("ADSEQ_RING_FORWARD_BLOCKS", 256, 8, 256)
+                             : env_pow2("ADSEQ_RING_REVERSE_BLOCKS", env_pow2("ADSEQ_RING_REVERSE_FLOW", 1, 0, 1) ? 256 : 128, 8, 256);
   long long chunk = (BN + blocks - 1) / blocks;
   chunk = (chunk + 255) / 256 * 256;
   if (on && chunk <= 4 * kResThreads && BN % 4 == 0) {
@@ -600,11 +605,11 @@ ResidentPlan reverse_plan(long long BN, bool forward = false) {
 // 256 blocks of kernel f at once; where it cannot (fewer compute units, or a kernel too large for one), the time steps
 // go by one launch each.  ADSEQ_RING_ASSUME_CUS replaces the device's compute-unit count in this check (tests of the
 // decision; it changes nothing else).
-bool resident_fits(const void* f) {
+bool resident_fits(const void* f, int threads = kResLaunch) {
   int dev = 0, cus = 0, per = 0;
   if (hipGetDevice(&dev) != hipSuccess) return false;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return false;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per, f, kResLaunch, 0) != hipSuccess) { (void)hipGetLastError(); return false; }
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per, f, threads, 0) != hipSuccess) { (void)hipGetLastError(); return false; }
   if (const char* e = getenv("ADSEQ_RING_ASSUME_CUS")) { const int v = atoi(e); if (v >= 1 && v <= 4096) cus = v; }
   return (long long)cus * per >= 256;
 }
@@ -1233,6 +1238,7 @@ void ring_backward_launch(adseq* h, hipStream_t st, long long T, float dscale, c
   fill_u32(st, d.gwin, 0u, nst * 2 * (size_t)d.W * d.BN);
   fill_u32(st, d.Gacc, 0u, (size_t)d.R * d.BN);
   if (counts) fill_u32(st, d.near_nspk, 0u, 128);
+  int flow_filled = -1;   // window buffer that the resident reverse kernel before has filled with its sentinel (-1: none)
   for (long long k0 = (T - 1) & ~(long long)(d.W - 1); k0 >= 0; k0 -= d.W) {
     const long long k1 = k0 + d.W < T ? k0 + d.W : T;
     const int nsteps = (int)(k1 - k0);
@@ -1260,9 +1266,21 @@ void ring_backward_launch(adseq* h, hipStream_t st, long long T, float dscale, c
         int stride = env_pow2("ADSEQ_RING_RESIDENT_STRIDE", kResStride, 1, 8);
         while (stride > 1 && (long long)h->rev_P * stride > 32 * 8) stride >>= 1;
         const dim3 rg((unsigned)(h->rev_P * stride)), rb(kResLaunch);
+        if (h->rev_flow) {
+          // no grid barrier: every cell of the window's buffer says "not written yet" until its owner stores it.
+          // The launch before this one has filled the buffer in passing, unless this is the sweep's first launch or
+          // the window after this one was swept another way
+          const int buf = (int)((k0 >> d.wshift) & 1);
+          if (flow_filled != buf) fill_u32(st, d.gwin + (size_t)buf * d.W * d.BN, kFlowSentinel, (size_t)d.W * d.BN);
+          const int fill_other = (counts == nullptr && k0 > 0) ? 1 : 0;
+          if (dL_dU) hipLaunchKernelGGL((k_bwd_flow<true>), rg, dim3(kResThreads), 0, st, k1, nsteps, T, h->rev_P, h->rev_chunk, stride, fill_other, dL_dcount, dL_dU, d);
+          else hipLaunchKernelGGL((k_bwd_flow<false>), rg, dim3(kResThreads), 0, st, k1, nsteps, T, h->rev_P, h->rev_chunk, stride, fill_other, dL_dcount, dL_dU, d);
+          flow_filled = fill_other ? 1 - buf : -1;
+        } else {
         if (dL_dU) hipLaunchKernelGGL((k_bwd_xcd<true>), rg, rb, 0, st, k1, nsteps, T, h->rev_base, h->rev_P, h->rev_chunk, stride, dL_dcount, dL_dU, d);
         else hipLaunchKernelGGL((k_bwd_xcd<false>), rg, rb, 0, st, k1, nsteps, T, h->rev_base, h->rev_P, h->rev_chunk, stride, dL_dcount, dL_dU, d);
         h->rev_base += (unsigned)(nsteps - 1) * (unsigned)h->rev_P;
+        }
       } else if (h->chain && chain_ready(h)) {
         chain_fork(h, st);
         for (long long n = k1 - 1; n >= k0; --n) {
@@ -1437,6 +1455,7 @@ int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, 
   d.count_pop = env_pow2("ADSEQ_RING_COUNT_POPPED", 0, 0, 1);
   d.lazy_rows = env_pow2("ADSEQ_RING_LAZY_ROWS", 0, 0, 1);
   d.res_spins = env_pow2("ADSEQ_RING_RESIDENT_SPINS", kResMaxSpins, 1, kResMaxSpins);
+  d.flow_hold = env_pow2("ADSEQ_RING_FLOW_WITHHOLD", 0, 0, 1);
   d.W = L.W; d.wshift = L.wshift; d.tp_shift = L.tp_shift; d.P = L.P; d.NB = L.NB; d.cap = L.cap;
   d.wgroups = L.wgroups;
   d.win = (int*)(ws + L.win);
@@ -1491,6 +1510,10 @@ int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, 
       ResidentPlan vp = reverse_plan((long long)d.BN);
       if (vp.P > 0 && !(resident_fits((const void*)k_bwd_xcd<true>) && resident_fits((const void*)k_bwd_xcd<false>))) vp = ResidentPlan();
       h->rev_chunk = vp.chunk; h->rev_P = vp.P; h->rev_npt = vp.npt;
+      // the same layout without a grid barrier: the blocks wait for the cells they gather (ring_flow_reverse.h);
+      // ADSEQ_RING_REVERSE_FLOW = 0: the kernel with a barrier per step
+      h->rev_flow = vp.P > 0 && env_pow2("ADSEQ_RING_REVERSE_FLOW", 1, 0, 1) &&
+                    resident_fits((const void*)k_bwd_flow<true>, kResThreads) && resident_fits((const void*)k_bwd_flow<false>, kResThreads);
       // forward kernel over the whole chip with the candidates' rows requested ahead (ring_resident_forward.h): the
       // reverse kernel's layout (ADSEQ_RING_FORWARD_BLOCKS taking-part blocks, default 256).  ADSEQ_RING_FORWARD_CHIP:
       // see reverse_plan; ADSEQ_RING_FORWARD_MARGIN: candidate margin in thousandths of the membrane unit (default 5).

@@ -150,7 +150,7 @@ __device__ __forceinline__ float bwd_near_correction(const Dev& d, long long n, 
   float sg = 0.0f;
   if (d.surrogate == ADSEQ_SURR_SUPERSPIKE) {
     const float x = fabsf(U - d.theta) + 1.0f;
-    sg = 1.0f / (x * x);
+    sg = __builtin_amdgcn_rcpf(x * x);   // (as bwd_update)
   }
   *dgu = sg * Gn;
   float e = 0.0f;

@@ -965,7 +965,7 @@ __device__ __forceinline__ float bwd_update(const Dev& d, long long n, float U, 
   float sg = 0.0f;
   if (d.surrogate == ADSEQ_SURR_SUPERSPIKE) {
     const float x = fabsf(U - d.theta) + 1.0f;
-    sg = 1.0f / (x * x);
+    sg = __builtin_amdgcn_rcpf(x * x);   // (one instruction, 1 ulp: the division's dozen were a third of a dense reverse step)
   }
   float inner = dcount;
   if (s) inner += G;

@@ -20,6 +20,14 @@ def _resident_on(monkeypatch):
     monkeypatch.setenv("ADSEQ_RING_RESIDENT", "1")
 
 
+@pytest.fixture(params=["flow", "barrier"])
+def rev_kernel(request, monkeypatch):
+    """The two resident reverse kernels: blocks that wait for the cells they gather (the default) and a grid
+    barrier per step."""
+    monkeypatch.setenv("ADSEQ_RING_REVERSE_FLOW", "1" if request.param == "flow" else "0")
+    return request.param
+
+
 def _run_pieces(wl, T, B, pieces, **kw):
     """Forward run through adseq_run / adseq_step in the given pieces (int = that many steps in one
     adseq_run call, 's' = one adseq_step call); returns (sim, U, counters, counts)."""
@@ -181,7 +189,7 @@ def test_reverse_sweep_by_windows(surrogate, n, b, T, monkeypatch):
 @pytest.mark.parametrize("n,b,T,d_max,rate,continuous", [(700, 3, 150, 40, 400.0, False), (6000, 2, 100, 40, 2500.0, False),
                                                         (20000, 4, 70, 40, 400.0, False), (900, 4, 70, 2, 400.0, False),
                                                         (1500, 2, 90, 30, 400.0, True)])
-def test_resident_reverse_sweep(surrogate, n, b, T, d_max, rate, continuous, monkeypatch):
+def test_resident_reverse_sweep(surrogate, n, b, T, d_max, rate, continuous, rev_kernel, monkeypatch):
     """The reverse steps of a window in one launch with a grid barrier per step (ring_resident_reverse.h):
     both gradients against the oracle, with a cotangent on the membrane values as well, in both
     gradient modes; a few blocks and 128; a run length that is not a multiple of the
@@ -240,7 +248,7 @@ def _reverse_against_oracle(wl, T, b, surrogate=adseq.SURR_SUPERSPIKE):
 
 
 @pytest.mark.parametrize("blocks,stride", [("8", "8"), ("32", "1"), ("256", "2"), ("128", "4")])
-def test_resident_reverse_block_counts_and_spread(blocks, stride, monkeypatch):
+def test_resident_reverse_block_counts_and_spread(blocks, stride, rev_kernel, monkeypatch):
     """The resident reverse kernel with few and many taking-part blocks, on one XCD and spread over
     all of them (every stride-th block of the grid takes part): nothing in its results depends on
     where the blocks run.  A trial boundary inside a thread's four neurons (N = 301, four trials), no
@@ -258,7 +266,7 @@ def test_resident_reverse_block_counts_and_spread(blocks, stride, monkeypatch):
     assert ref.spikes.sum() > 300
 
 
-def test_resident_reverse_falls_back_where_the_layout_does_not_fit(monkeypatch):
+def test_resident_reverse_falls_back_where_the_layout_does_not_fit(rev_kernel, monkeypatch):
     """B N not a multiple of 4 (rows of the window not 16-byte aligned) and more state cells than 256 blocks of
     2,048 hold: the reverse sweep goes by one launch per step, same gradients."""
     monkeypatch.setenv("ADSEQ_RING_REVERSE_WINDOWS", "0")
@@ -296,8 +304,9 @@ def test_resident_kernels_need_their_blocks_on_the_chip_together(monkeypatch):
     _reverse_against_oracle(wl, 64, 2)
 
 
-def test_resident_reverse_wait_that_runs_out_is_reported(monkeypatch):
-    """Failure path of the reverse kernel's bounded waits, forced from the host (one poll per wait): every kernel
+def test_resident_reverse_wait_that_runs_out_is_reported(rev_kernel, monkeypatch):
+    """Failure path of the reverse kernels' bounded waits, forced from the host (one poll per wait at the grid barrier;
+    without a barrier, spiking neurons that withhold their final adjoints and 16 polls per wait): every kernel
     runs to its end, the error word carries bit 32 after the sweep, a reset clears it, and a handle with the
     ordinary limit gives the oracle's gradients."""
     monkeypatch.setenv("ADSEQ_RING_REVERSE_WINDOWS", "0")
@@ -310,7 +319,9 @@ def test_resident_reverse_wait_that_runs_out_is_reported(monkeypatch):
     torch.cuda.synchronize()
     assert sim.counters()["error_bits"] == 0
     sim.close()
-    monkeypatch.setenv("ADSEQ_RING_RESIDENT_SPINS", "1")
+    monkeypatch.setenv("ADSEQ_RING_RESIDENT_SPINS", "16" if rev_kernel == "flow" else "1")
+    if rev_kernel == "flow":
+        monkeypatch.setenv("ADSEQ_RING_FLOW_WITHHOLD", "1")
     sim = adseq.Adseq(wl, adseq.RING, 0, record_tape=True, max_steps=60)
     sim.run(0, 60)
     g = torch.empty(wl.n_synapses, device=sim.dev)
@@ -324,6 +335,7 @@ def test_resident_reverse_wait_that_runs_out_is_reported(monkeypatch):
     sim.close()
     monkeypatch.delenv("ADSEQ_RING_RESIDENT_SPINS")
     monkeypatch.delenv("ADSEQ_RING_REVERSE_DELAY")
+    monkeypatch.delenv("ADSEQ_RING_FLOW_WITHHOLD", raising=False)
     _reverse_against_oracle(wl, 60, 2)
 
 
