@@ -90,7 +90,7 @@ __device__ __forceinline__ float flow_row_tail(const Dev& d, const float* __rest
 #define FPH(i) {}
 #endif
 
-template <bool HAS_DU>
+template <bool HAS_DU, int SURR>
 __device__ __forceinline__ void flow_step(const Dev& d, RevState& S, const int PAR, RevBatch& cur, RevBatch& nxt, bool last,
                                           int* s_dead, int* s_nspk, RevSpike (*s_spk)[kRevList], float (*s_G2)[4 * kResThreads],
                                           float* fill_row, int& cnt_base0, int& cnt_base1 FPH_ARG) {
@@ -135,7 +135,7 @@ __device__ __forceinline__ void flow_step(const Dev& d, RevState& S, const int P
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       float gu;
-      S.carry[c] = bwd_update(d, n, U[c], 0.0f, (smask >> c) & 1u, S.carry[c], S.dLc[c], Gf[c], dU[c], &gu);
+      S.carry[c] = bwd_update_as<SURR>(d, n, U[c], 0.0f, (smask >> c) & 1u, S.carry[c], S.dLc[c], Gf[c], dU[c], &gu);
       gu4[c] = ((smask >> c) & 1u) ? __uint_as_float(kFlowSentinel) : gu;
     }
     const __amdgpu_buffer_rsrc_t row = res_rows(gwin, hi * 4), far = res_rows(d.Gacc + (size_t)S.slot * d.BN, hi * 4);
@@ -282,7 +282,7 @@ __device__ __forceinline__ void flow_step(const Dev& d, RevState& S, const int P
       float G = Gf[c] + Gx[c];
       if (near_h >= 1 && S.rlen[c] > 0 && !((S.ovf_cur >> c) & 1u)) G += s_G[4 * (int)threadIdx.x + c];
       float gu;
-      S.carry[c] = bwd_update(d, n, U[c], S.Ub[c], true, 0.0f, S.dLc[c], G, dU[c], &gu);
+      S.carry[c] = bwd_update_as<SURR>(d, n, U[c], S.Ub[c], true, 0.0f, S.dLc[c], G, dU[c], &gu);
       if (!d.flow_hold) st_agent(&gwin[g0 + c], gu);   // (withheld only by the test of the waits' failure path)
     }
   }
@@ -308,10 +308,10 @@ __device__ __forceinline__ void flow_step(const Dev& d, RevState& S, const int P
 // Reverse steps n_hi - 1, n_hi - 2, ..., n_hi - nsteps, all inside one window whose buffer the host
 // has filled with the sentinel.  P taking-part blocks (every stride-th block of the grid), each
 // owning `chunk` <= 2,048 neurons, four consecutive ones per thread (16-byte accesses); B N a
-// multiple of 4.  HAS_DU: a cotangent on the membrane values comes with the call.
+// multiple of 4.  HAS_DU: a cotangent on the membrane values comes with the call; SURR: the gradient mode.
 // fill_other: the launch also fills the OTHER window buffer (the one the next launch sweeps) with the sentinel, every
 // block the cells of its own neurons, a row per step and what is left when the steps are done.
-template <bool HAS_DU>
+template <bool HAS_DU, int SURR>
 __global__ __launch_bounds__(kResThreads) void k_bwd_flow(long long n_hi, int nsteps, long long T, int P, int chunk, int stride,
                                                           int fill_other, const float* __restrict__ dL_dcount,
                                                           const float* __restrict__ dL_dU, Dev d) {
@@ -372,7 +372,7 @@ __global__ __launch_bounds__(kResThreads) void k_bwd_flow(long long n_hi, int ns
   float* const other = gwin_of(d, n_hi - 1 + d.W);   // (the buffers take turns window by window)
   int cnt_base0 = 0, cnt_base1 = 0;   // what the counters of list 0 and list 1 held when their last list was complete
   for (int k = 0; k < nsteps; ++k) {
-    flow_step<HAS_DU>(d, S, k & 1, A, B, k + 1 == nsteps, &s_dead, s_nspk, s_spk, s_G,
+    flow_step<HAS_DU, SURR>(d, S, k & 1, A, B, k + 1 == nsteps, &s_dead, s_nspk, s_spk, s_G,
                       fill_other ? other + (size_t)(phi0 - k) * d.BN : nullptr, cnt_base0, cnt_base1 FPH_PASS);
     A = B;
   }

@@ -960,10 +960,13 @@ __global__ __launch_bounds__(kBlock) void k_ring_in_flight(Dev d, long long n_en
 // emission time depends on the membrane value v the step started from, dt_spk/dv = -1 / vdot with
 // vdot = (U - v) / dt (1 where that is 0), and hands (1 / tau) G to its receivers (eq. 17), so
 // E = -(1 / vdot)(1 / tau) G goes back to the state before the step.
-__device__ __forceinline__ float bwd_update(const Dev& d, long long n, float U, float Uprev, bool s, float carry,
-                                            float dcount, float G, float dU, float* gu_out) {
+// (SURR: the gradient mode, d.surrogate, as a constant of the caller where it has one: a reverse step of a resident
+// kernel is bound by the instructions it issues)
+template <int SURR>
+__device__ __forceinline__ float bwd_update_as(const Dev& d, long long n, float U, float Uprev, bool s, float carry,
+                                               float dcount, float G, float dU, float* gu_out) {
   float sg = 0.0f;
-  if (d.surrogate == ADSEQ_SURR_SUPERSPIKE) {
+  if (SURR == ADSEQ_SURR_SUPERSPIKE) {
     const float x = fabsf(U - d.theta) + 1.0f;
     sg = __builtin_amdgcn_rcpf(x * x);   // (one instruction, 1 ulp: the division's dozen were a third of a dense reverse step)
   }
@@ -974,7 +977,7 @@ __device__ __forceinline__ float bwd_update(const Dev& d, long long n, float U, 
   gu += dU;
   *gu_out = gu;
   float e = 0.0f;
-  if (d.surrogate == ADSEQ_GRAD_SPIKE_TIME && s) {
+  if (SURR == ADSEQ_GRAD_SPIKE_TIME && s) {
     const float vprev = n > 0 ? (Uprev >= d.theta ? d.v_reset : Uprev) : 0.0f;
     float vdot = (U - vprev) / d.dt;
     if (vdot == 0.0f) vdot = 1.0f;
@@ -982,6 +985,12 @@ __device__ __forceinline__ float bwd_update(const Dev& d, long long n, float U, 
     e = d.alpha_r > 0.0f ? -(1.0f / vdot) * G : -(1.0f / vdot) * (1.0f / d.tau) * G;
   }
   return __fmaf_rn(d.alpha, gu, e);
+}
+__device__ __forceinline__ float bwd_update(const Dev& d, long long n, float U, float Uprev, bool s, float carry,
+                                            float dcount, float G, float dU, float* gu_out) {
+  if (d.surrogate == ADSEQ_SURR_SUPERSPIKE) return bwd_update_as<ADSEQ_SURR_SUPERSPIKE>(d, n, U, Uprev, s, carry, dcount, G, dU, gu_out);
+  if (d.surrogate == ADSEQ_GRAD_SPIKE_TIME) return bwd_update_as<ADSEQ_GRAD_SPIKE_TIME>(d, n, U, Uprev, s, carry, dcount, G, dU, gu_out);
+  return bwd_update_as<ADSEQ_SURR_OFF>(d, n, U, Uprev, s, carry, dcount, G, dU, gu_out);
 }
 
 // What an event delivered to neuron g at this step gathers: the adjoint of the state that took its
