@@ -618,13 +618,16 @@ const void* run_xcd_kernel_of(int syn, int npt) {
   if (npt == 1) return syn == 0 ? (const void*)k_run_xcd<RECORD, 0, 1> : (syn == 1 ? (const void*)k_run_xcd<RECORD, 1, 1> : (const void*)k_run_xcd<RECORD, 2, 1>);
   return syn == 0 ? (const void*)k_run_xcd<RECORD, 0, 2> : (syn == 1 ? (const void*)k_run_xcd<RECORD, 1, 2> : (const void*)k_run_xcd<RECORD, 2, 2>);
 }
-template <bool DU>
+template <bool DU, int NPT>
 const void* flow_kernel_of(int surrogate) {
-  if (surrogate == ADSEQ_SURR_SUPERSPIKE) return (const void*)k_bwd_flow<DU, ADSEQ_SURR_SUPERSPIKE>;
-  if (surrogate == ADSEQ_GRAD_SPIKE_TIME) return (const void*)k_bwd_flow<DU, ADSEQ_GRAD_SPIKE_TIME>;
-  return (const void*)k_bwd_flow<DU, ADSEQ_SURR_OFF>;
+  if (surrogate == ADSEQ_SURR_SUPERSPIKE) return (const void*)k_bwd_flow<DU, ADSEQ_SURR_SUPERSPIKE, NPT>;
+  if (surrogate == ADSEQ_GRAD_SPIKE_TIME) return (const void*)k_bwd_flow<DU, ADSEQ_GRAD_SPIKE_TIME, NPT>;
+  return (const void*)k_bwd_flow<DU, ADSEQ_SURR_OFF, NPT>;
 }
-const void* flow_kernel(bool du, int surrogate) { return du ? flow_kernel_of<true>(surrogate) : flow_kernel_of<false>(surrogate); }
+const void* flow_kernel(bool du, int surrogate, int chunk) {
+  if (chunk <= kResThreads) return du ? flow_kernel_of<true, 1>(surrogate) : flow_kernel_of<false, 1>(surrogate);
+  return du ? flow_kernel_of<true, 4>(surrogate) : flow_kernel_of<false, 4>(surrogate);
+}
 const void* run_xcd_kernel(bool record, int syn, int npt) {
   return record ? run_xcd_kernel_of<true>(syn, npt) : run_xcd_kernel_of<false>(syn, npt);
 }
@@ -1280,11 +1283,14 @@ void ring_backward_launch(adseq* h, hipStream_t st, long long T, float dscale, c
           const int buf = (int)((k0 >> d.wshift) & 1);
           if (flow_filled != buf) fill_u32(st, d.gwin + (size_t)buf * d.W * d.BN, kFlowSentinel, (size_t)d.W * d.BN);
           const int fill_other = (counts == nullptr && k0 > 0) ? 1 : 0;
-#define ADSEQ_FLOW(DU, SURR) hipLaunchKernelGGL((k_bwd_flow<DU, SURR>), rg, dim3(kResThreads), 0, st, k1, nsteps, T, h->rev_P, h->rev_chunk, stride, fill_other, dL_dcount, dL_dU, d)
+          // (one neuron per thread where a block owns no more than it has threads, else four)
+#define ADSEQ_FLOW3(DU, SURR, NPT) hipLaunchKernelGGL((k_bwd_flow<DU, SURR, NPT>), rg, dim3(kResThreads), 0, st, k1, nsteps, T, h->rev_P, h->rev_chunk, stride, fill_other, dL_dcount, dL_dU, d)
+#define ADSEQ_FLOW(DU, SURR) do { if (h->rev_chunk <= kResThreads) ADSEQ_FLOW3(DU, SURR, 1); else ADSEQ_FLOW3(DU, SURR, 4); } while (0)
           if (d.surrogate == ADSEQ_SURR_SUPERSPIKE) { if (dL_dU) ADSEQ_FLOW(true, ADSEQ_SURR_SUPERSPIKE); else ADSEQ_FLOW(false, ADSEQ_SURR_SUPERSPIKE); }
           else if (d.surrogate == ADSEQ_GRAD_SPIKE_TIME) { if (dL_dU) ADSEQ_FLOW(true, ADSEQ_GRAD_SPIKE_TIME); else ADSEQ_FLOW(false, ADSEQ_GRAD_SPIKE_TIME); }
           else { if (dL_dU) ADSEQ_FLOW(true, ADSEQ_SURR_OFF); else ADSEQ_FLOW(false, ADSEQ_SURR_OFF); }
 #undef ADSEQ_FLOW
+#undef ADSEQ_FLOW3
           flow_filled = fill_other ? 1 - buf : -1;
         } else {
         if (dL_dU) hipLaunchKernelGGL((k_bwd_xcd<true>), rg, rb, 0, st, k1, nsteps, T, h->rev_base, h->rev_P, h->rev_chunk, stride, dL_dcount, dL_dU, d);
@@ -1523,7 +1529,7 @@ int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, 
       // the same layout without a grid barrier: the blocks wait for the cells they gather (ring_flow_reverse.h);
       // ADSEQ_RING_REVERSE_FLOW = 0: the kernel with a barrier per step
       h->rev_flow = vp.P > 0 && env_pow2("ADSEQ_RING_REVERSE_FLOW", 1, 0, 1) &&
-                    resident_fits(flow_kernel(true, d.surrogate), kResThreads) && resident_fits(flow_kernel(false, d.surrogate), kResThreads);
+                    resident_fits(flow_kernel(true, d.surrogate, vp.chunk), kResThreads) && resident_fits(flow_kernel(false, d.surrogate, vp.chunk), kResThreads);
       // forward kernel over the whole chip with the candidates' rows requested ahead (ring_resident_forward.h): the
       // reverse kernel's layout (ADSEQ_RING_FORWARD_BLOCKS taking-part blocks, default 256).  ADSEQ_RING_FORWARD_CHIP:
       // see reverse_plan; ADSEQ_RING_FORWARD_MARGIN: candidate margin in thousandths of the membrane unit (default 5).

@@ -79,6 +79,56 @@ __device__ __forceinline__ float flow_row_tail(const Dev& d, const float* __rest
 // One reverse step of a wavefront.  PAR: list buffer of the step being run (the other one takes the
 // list of the step after it); cur: the batch of the step being run (rows requested a step ago),
 // nxt: filled here for the next one.
+// NPT consecutive neurons of a thread, loaded and stored with one access of 4 NPT bytes.
+template <int NPT> struct FlowVec { float v[NPT]; };
+template <int NPT, int AUX>
+__device__ __forceinline__ FlowVec<NPT> flow_load(__amdgpu_buffer_rsrc_t rs, int off) {
+  FlowVec<NPT> r;
+  if constexpr (NPT == 4) {
+    const res_v4f x = __builtin_bit_cast(res_v4f, __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, AUX));
+    r.v[0] = x[0]; r.v[1] = x[1]; r.v[2] = x[2]; r.v[3] = x[3];
+  } else {
+    static_assert(NPT == 1, "one or four neurons per thread");
+    r.v[0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, off, 0, AUX));
+  }
+  return r;
+}
+template <int NPT, int AUX>
+__device__ __forceinline__ void flow_store(const FlowVec<NPT>& x, __amdgpu_buffer_rsrc_t rs, int off) {
+  if constexpr (NPT == 4) {
+    const res_v4f y = {x.v[0], x.v[1], x.v[2], x.v[3]};
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(res_v4i, y), rs, off, 0, AUX);
+  } else {
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, x.v[0]), rs, off, 0, AUX);
+  }
+}
+template <int NPT>
+__device__ __forceinline__ FlowVec<NPT> flow_splat(float a) {
+  FlowVec<NPT> r;
+#pragma unroll
+  for (int c = 0; c < NPT; ++c) r.v[c] = a;
+  return r;
+}
+
+// What a thread carries through the launch (as RevState, for NPT neurons per thread).
+template <int NPT>
+struct FlowState {
+  float carry[NPT], dLc[NPT];        // its neurons: carry of the adjoint, dL/dcount
+  long long r0[NPT]; int rlen[NPT];  // bounds of their sorted rows
+  unsigned actmask;                  // bit c: neuron c exists
+  FlowVec<NPT> Ua, Ub, Uc;           // tape values of the step being run, of the one after it, of the one after that
+  FlowVec<NPT> Ga, Gb, dUa, dUb;     // far queue terms and dL/dU of the step being run and of the next
+  unsigned ovf_cur;                  // bit c: neuron c spiked in the step being run and did not fit the list
+  int nspk_cur;                      // listed spikes of the step being run
+  // the same in every lane
+  long long n;                       // step being run
+  int phi, tail, slot;               // n mod W, T - 1 - n, n mod R
+  float* gwin;                       // row n of the adjoint window
+  const float* tape2;                // tape row of step n - 2 (of step 0 below that)
+  const float* du1;                  // dL/dU row of step n - 1 (of step 0 below that)
+  int g0, hi;
+};
+
 // (builds with phase clocks: where a step's time goes, wavefront 0 of block 0)
 #ifdef ADSEQ_PHASE_CLOCK
 #define FPH_ARG , unsigned long long* fpc, unsigned long long& fpt
@@ -90,8 +140,8 @@ __device__ __forceinline__ float flow_row_tail(const Dev& d, const float* __rest
 #define FPH(i) {}
 #endif
 
-template <bool HAS_DU, int SURR>
-__device__ __forceinline__ void flow_step(const Dev& d, RevState& S, const int PAR, RevBatch& cur, RevBatch& nxt, bool last,
+template <bool HAS_DU, int SURR, int NPT>
+__device__ __forceinline__ void flow_step(const Dev& d, FlowState<NPT>& S, const int PAR, RevBatch& cur, RevBatch& nxt, bool last,
                                           int* s_dead, int* s_nspk, RevSpike (*s_spk)[kRevList], float (*s_G2)[4 * kResThreads],
                                           float* fill_row, int& cnt_base0, int& cnt_base1 FPH_ARG) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -102,13 +152,13 @@ __device__ __forceinline__ void flow_step(const Dev& d, RevState& S, const int P
   float* __restrict__ gwin = S.gwin;
   float* s_G = s_G2[PAR];
   const int g0 = S.g0, hi = S.hi;
-  float U[4], Gf[4], dU[4];
+  float U[NPT], Gf[NPT], dU[NPT];
   unsigned smask = 0, s1 = 0;
 #pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    U[c] = S.Ua[c]; Gf[c] = S.Ga[c]; dU[c] = HAS_DU ? S.dUa[c] : 0.0f;
+  for (int c = 0; c < NPT; ++c) {
+    U[c] = S.Ua.v[c]; Gf[c] = S.Ga.v[c]; dU[c] = HAS_DU ? S.dUa.v[c] : 0.0f;
     smask |= U[c] >= d.theta ? 1u << c : 0u;
-    s1 |= S.Ub[c] >= d.theta ? 1u << c : 0u;
+    s1 |= S.Ub.v[c] >= d.theta ? 1u << c : 0u;
   }
   smask &= S.actmask; s1 &= S.actmask;
   // ---- requested first, so that they are there when the step ends (the values move up a place then, and a move of a
@@ -120,38 +170,31 @@ __device__ __forceinline__ void flow_step(const Dev& d, RevState& S, const int P
 #endif
   {
     const __amdgpu_buffer_rsrc_t t2 = res_rows(S.tape2, hi * 4), f1 = res_rows(d.Gacc + (size_t)slot1 * d.BN, hi * 4);
-    S.Uc = __builtin_bit_cast(res_v4f, __builtin_amdgcn_raw_buffer_load_b128(t2, g0 * 4, 0, kBufNonTemporal));
-    S.Gb = __builtin_bit_cast(res_v4f, __builtin_amdgcn_raw_buffer_load_b128(f1, g0 * 4, 0, kBufNonTemporal));
-    if (HAS_DU) {
-      const __amdgpu_buffer_rsrc_t u1 = res_rows(S.du1, hi * 4);
-      S.dUb = __builtin_bit_cast(res_v4f, __builtin_amdgcn_raw_buffer_load_b128(u1, g0 * 4, 0, kBufNonTemporal));
-    }
+    S.Uc = flow_load<NPT, kBufNonTemporal>(t2, g0 * 4);
+    S.Gb = flow_load<NPT, kBufNonTemporal>(f1, g0 * 4);
+    if (HAS_DU) S.dUb = flow_load<NPT, kBufNonTemporal>(res_rows(S.du1, hi * 4), g0 * 4);
   }
   FPH(5)
   // ---- the row of this step, as early as can be (others may be waiting for it): final for every neuron that does not
   // spike; a spiking neuron's cell says "not yet" until its queue term is gathered below
   if (__ballot(S.actmask != 0u) != 0ull) {   // (wavefronts without neurons skip the arithmetic)
-    res_v4f gu4;
+    FlowVec<NPT> gu4;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
+    for (int c = 0; c < NPT; ++c) {
       float gu;
       S.carry[c] = bwd_update_as<SURR>(d, n, U[c], 0.0f, (smask >> c) & 1u, S.carry[c], S.dLc[c], Gf[c], dU[c], &gu);
-      gu4[c] = ((smask >> c) & 1u) ? __uint_as_float(kFlowSentinel) : gu;
+      gu4.v[c] = ((smask >> c) & 1u) ? __uint_as_float(kFlowSentinel) : gu;
     }
     const __amdgpu_buffer_rsrc_t row = res_rows(gwin, hi * 4), far = res_rows(d.Gacc + (size_t)S.slot * d.BN, hi * 4);
 #ifdef ADSEQ_PHASE_CLOCK
     if (!(d.dbg & 8))
 #endif
     {
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(res_v4i, gu4), row, g0 * 4, 0, kBufAgent);
+    flow_store<NPT, kBufAgent>(gu4, row, g0 * 4);
     // the far queue terms are used up: the slot is another step's R steps on (stored by every lane, set or not)
-    const res_v4i z = {0, 0, 0, 0};
-    __builtin_amdgcn_raw_buffer_store_b128(z, far, g0 * 4, 0, 0);
-    if (fill_row) {
-      // the same row of the OTHER window buffer, which the next launch sweeps: "not written yet"
-      const res_v4i nv = {(int)kFlowSentinel, (int)kFlowSentinel, (int)kFlowSentinel, (int)kFlowSentinel};
-      __builtin_amdgcn_raw_buffer_store_b128(nv, res_rows(fill_row, hi * 4), g0 * 4, 0, 0);
-    }
+    flow_store<NPT, 0>(flow_splat<NPT>(0.0f), far, g0 * 4);
+    // the same row of the OTHER window buffer, which the next launch sweeps: "not written yet"
+    if (fill_row) flow_store<NPT, 0>(flow_splat<NPT>(__uint_as_float(kFlowSentinel)), res_rows(fill_row, hi * 4), g0 * 4);
     }
   }
   FPH(6)
@@ -180,24 +223,24 @@ __device__ __forceinline__ void flow_step(const Dev& d, RevState& S, const int P
   for (int u = 0; u < 4; ++u) { nxt.e[u] = make_uint2(0u, 0u); nxt.r0[u] = 0; nxt.len[u] = 0; nxt.base[u] = 0; nxt.loc[u] = 0; }
   if (near1 >= 1) {
     if (__ballot(s1 != 0u) != 0ull) {
-      unsigned long long m[4];
+      unsigned long long m[NPT];
       int total = 0;
 #pragma unroll
-      for (int c = 0; c < 4; ++c) { m[c] = __ballot(((s1 >> c) & 1u) && S.rlen[c] > 0); total += __popcll(m[c]); }   // (a spike with an empty row is not listed)
+      for (int c = 0; c < NPT; ++c) { m[c] = __ballot(((s1 >> c) & 1u) && S.rlen[c] > 0); total += __popcll(m[c]); }   // (a spike with an empty row is not listed)
       // (the counters of the two lists only ever grow -- no reset to order against the other wavefronts: a list's
       // places count from what its counter held when the list before it was complete, cnt_base)
       int at = 0;
       if (lane == 0) at = atomicAdd(&s_nspk[PAR ^ 1], total);
       at = __builtin_amdgcn_readfirstlane(at) - (PAR ? cnt_base0 : cnt_base1);
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
+      for (int c = 0; c < NPT; ++c) {
         if (m[c] == 0ull) continue;   // uniform
         if ((m[c] >> lane) & 1ull) {
           const int idx = at + __popcll(m[c] & ((1ull << lane) - 1ull));
           if (idx < kRevList) {
             RevSpike r;
             r.r0 = S.r0[c]; r.len = S.rlen[c];
-            r.pk = (4 * (int)threadIdx.x + c) | (trial_of(d, g0 + c) << kRevLocBits);
+            r.pk = (NPT * (int)threadIdx.x + c) | (trial_of(d, g0 + c) << kRevLocBits);
             s_spk[PAR ^ 1][idx] = r;
           } else {
             ovf_nxt |= 1u << c;
@@ -232,7 +275,9 @@ __device__ __forceinline__ void flow_step(const Dev& d, RevState& S, const int P
   }
   FPH(1)
   // ---- the gathered adjoints, once they are all there; per-spike sums; the spiking neurons' final values
-  float Gx[4] = {0.0f, 0.0f, 0.0f, 0.0f};   // near parts that come back to the owner directly (spikes that did not fit the list)
+  float Gx[NPT];   // near parts that come back to the owner directly (spikes that did not fit the list)
+#pragma unroll
+  for (int c = 0; c < NPT; ++c) Gx[c] = 0.0f;
   if (near_h >= 1) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -254,7 +299,7 @@ __device__ __forceinline__ void flow_step(const Dev& d, RevState& S, const int P
     // more spikes than the list holds: the owner's wavefront takes them one by one
     if (__ballot(S.ovf_cur != 0u) != 0ull) {
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
+      for (int c = 0; c < NPT; ++c) {
         unsigned long long m = __ballot((S.ovf_cur >> c) & 1u);
         while (m) {
           const int L = __ffsll((long long)m) - 1;
@@ -277,12 +322,12 @@ __device__ __forceinline__ void flow_step(const Dev& d, RevState& S, const int P
   // neuron's update does not use the carry: the reset cuts it)
   if (smask) {
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
+    for (int c = 0; c < NPT; ++c) {
       if (!((smask >> c) & 1u)) continue;
       float G = Gf[c] + Gx[c];
-      if (near_h >= 1 && S.rlen[c] > 0 && !((S.ovf_cur >> c) & 1u)) G += s_G[4 * (int)threadIdx.x + c];
+      if (near_h >= 1 && S.rlen[c] > 0 && !((S.ovf_cur >> c) & 1u)) G += s_G[NPT * (int)threadIdx.x + c];
       float gu;
-      S.carry[c] = bwd_update_as<SURR>(d, n, U[c], S.Ub[c], true, 0.0f, S.dLc[c], G, dU[c], &gu);
+      S.carry[c] = bwd_update_as<SURR>(d, n, U[c], S.Ub.v[c], true, 0.0f, S.dLc[c], G, dU[c], &gu);
       if (!d.flow_hold) st_agent(&gwin[g0 + c], gu);   // (withheld only by the test of the waits' failure path)
     }
   }
@@ -307,11 +352,12 @@ __device__ __forceinline__ void flow_step(const Dev& d, RevState& S, const int P
 
 // Reverse steps n_hi - 1, n_hi - 2, ..., n_hi - nsteps, all inside one window whose buffer the host
 // has filled with the sentinel.  P taking-part blocks (every stride-th block of the grid), each
-// owning `chunk` <= 2,048 neurons, four consecutive ones per thread (16-byte accesses); B N a
-// multiple of 4.  HAS_DU: a cotangent on the membrane values comes with the call; SURR: the gradient mode.
+// owning `chunk` <= NPT * 512 neurons, NPT consecutive ones per thread (NPT = 4: 16-byte accesses, B N a
+// multiple of 4; NPT = 1 where the blocks own 512 neurons at most: the dense part of a step then spreads over all
+// the block's wavefronts).  HAS_DU: a cotangent on the membrane values comes with the call; SURR: the gradient mode.
 // fill_other: the launch also fills the OTHER window buffer (the one the next launch sweeps) with the sentinel, every
 // block the cells of its own neurons, a row per step and what is left when the steps are done.
-template <bool HAS_DU, int SURR>
+template <bool HAS_DU, int SURR, int NPT>
 __global__ __launch_bounds__(kResThreads) void k_bwd_flow(long long n_hi, int nsteps, long long T, int P, int chunk, int stride,
                                                           int fill_other, const float* __restrict__ dL_dcount,
                                                           const float* __restrict__ dL_dU, Dev d) {
@@ -325,12 +371,12 @@ __global__ __launch_bounds__(kResThreads) void k_bwd_flow(long long n_hi, int ns
   const int phi0 = (int)((n_hi - 1) & (long long)(d.W - 1));
   const long long tail0 = T - n_hi < 0x3fffffffLL ? T - n_hi : 0x3fffffffLL;
   const int lo = rank * chunk;
-  RevState S;
+  FlowState<NPT> S;
   S.hi = lo + chunk < d.BN ? lo + chunk : d.BN;
-  S.g0 = lo + 4 * (int)threadIdx.x;
+  S.g0 = lo + NPT * (int)threadIdx.x;
   S.actmask = 0;
 #pragma unroll
-  for (int c = 0; c < 4; ++c) {
+  for (int c = 0; c < NPT; ++c) {
     const int g = S.g0 + c;
     S.rlen[c] = 0; S.r0[c] = 0; S.carry[c] = 0.0f; S.dLc[c] = 0.0f;
     if (g < S.hi) {
@@ -342,11 +388,8 @@ __global__ __launch_bounds__(kResThreads) void k_bwd_flow(long long n_hi, int ns
       if (dL_dcount) S.dLc[c] = dL_dcount[g];
     }
   }
-  auto load_row = [&](const float* p) {
-    const __amdgpu_buffer_rsrc_t rs = res_rows(p, S.hi * 4);
-    return __builtin_bit_cast(res_v4f, __builtin_amdgcn_raw_buffer_load_b128(rs, S.g0 * 4, 0, kBufNonTemporal));
-  };
-  const res_v4f zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+  auto load_row = [&](const float* p) { return flow_load<NPT, kBufNonTemporal>(res_rows(p, S.hi * 4), S.g0 * 4); };
+  const FlowVec<NPT> zero4 = flow_splat<NPT>(0.0f);
   S.n = n_hi - 1; S.phi = phi0; S.tail = (int)tail0;
   S.slot = (int)((n_hi - 1) % d.R);   // (one division per launch)
   S.gwin = gwin_of(d, n_hi - 1) + (size_t)phi0 * d.BN;
@@ -372,16 +415,15 @@ __global__ __launch_bounds__(kResThreads) void k_bwd_flow(long long n_hi, int ns
   float* const other = gwin_of(d, n_hi - 1 + d.W);   // (the buffers take turns window by window)
   int cnt_base0 = 0, cnt_base1 = 0;   // what the counters of list 0 and list 1 held when their last list was complete
   for (int k = 0; k < nsteps; ++k) {
-    flow_step<HAS_DU, SURR>(d, S, k & 1, A, B, k + 1 == nsteps, &s_dead, s_nspk, s_spk, s_G,
+    flow_step<HAS_DU, SURR, NPT>(d, S, k & 1, A, B, k + 1 == nsteps, &s_dead, s_nspk, s_spk, s_G,
                       fill_other ? other + (size_t)(phi0 - k) * d.BN : nullptr, cnt_base0, cnt_base1 FPH_PASS);
     A = B;
   }
   if (fill_other && (S.actmask != 0u)) {
     // rows of the other buffer that no step of this launch stood for (a window cut short by the end of the run)
-    const res_v4i nv = {(int)kFlowSentinel, (int)kFlowSentinel, (int)kFlowSentinel, (int)kFlowSentinel};
     for (int r = 0; r < d.W; ++r)
       if (r > phi0 || r <= phi0 - nsteps)
-        __builtin_amdgcn_raw_buffer_store_b128(nv, res_rows(other + (size_t)r * d.BN, S.hi * 4), S.g0 * 4, 0, 0);
+        flow_store<NPT, 0>(flow_splat<NPT>(__uint_as_float(kFlowSentinel)), res_rows(other + (size_t)r * d.BN, S.hi * 4), S.g0 * 4);
   }
 #ifdef ADSEQ_PHASE_CLOCK
   if (blockIdx.x == 0 && threadIdx.x == 0) {
@@ -391,6 +433,6 @@ __global__ __launch_bounds__(kResThreads) void k_bwd_flow(long long n_hi, int ns
   }
 #endif
 #pragma unroll
-  for (int c = 0; c < 4; ++c)
+  for (int c = 0; c < NPT; ++c)
     if ((S.actmask >> c) & 1u) d.bwd_carry[S.g0 + c] = S.carry[c];
 }
