@@ -135,10 +135,6 @@ def main():
         phase_clocks["gathers"] = ngat   # (far gathers of the last reverse sweep, block 0 of each launch)
         phase_clocks["us_per_gather"] = {nm: round(ticks[16 + i] * 0.01 / ngat, 3) for i, nm in enumerate(
             ["gather: walk over the spike words", "gather: row pieces, adjoints, sums", "gather: the block's other wavefronts"])}
-        if ticks[21]:   # reverse steps of the resident reverse kernel without a grid barrier (wavefront 0 of block 0)
-            phase_clocks["us_per_reverse_step"] = {nm: round(ticks[i] * 0.01 / int(ticks[21]), 3) for i, nm in (
-                (22, "requests"), (23, "row computed and stored"), (11, "gathers issued"), (12, "next step's spikes listed, their rows requested"),
-                (13, "gathers complete, per-spike sums"), (14, "spiking neurons stored, block barrier"), (20, "requests of the step complete"))}
         spans = (ctypes.c_uint64 * 3072)()
         assert sim.lib.adseq_debug_block_spans(sim.h, spans, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)) == 0
         sp = np.array(spans[:], dtype=np.float64).reshape(3, 512, 2)
@@ -207,7 +203,9 @@ def main():
                  "bwd_neurons": "k_bwd_neurons (adjoint update)"}
     if args.queue == "ring" and prof.get("bwd_neurons", {}).get("launches", T) < T:
         # fewer launches than steps: the reverse steps of a window ran in one launch each (resident reverse kernel)
-        label["bwd_neurons"] = "k_bwd_xcd (the reverse steps of one window in one launch: adjoint update + in-window gather, a grid barrier per step)"
+        label["bwd_neurons"] = ("k_bwd_xcd (the reverse steps of one window in one launch: adjoint update + in-window gather, a grid barrier per step)"
+                                if os.environ.get("ADSEQ_RING_REVERSE_FLOW", "1") == "0" else
+                                "k_bwd_flow (the reverse steps of one window in one launch: adjoint update + in-window gather, no grid barrier: a gather waits for the cell it reads)")
     if args.queue == "ring" and prof.get("lif", {}).get("launches", T) < T:
         # likewise forward: the steps of a window in one launch over the whole chip
         label["lif"] = "k_fwd_chip (the steps of one window in one launch: pop + drive + LIF + spike bits + in-window scatter, a grid barrier per step)"

@@ -129,21 +129,10 @@ struct FlowState {
   int g0, hi;
 };
 
-// (builds with phase clocks: where a step's time goes, wavefront 0 of block 0)
-#ifdef ADSEQ_PHASE_CLOCK
-#define FPH_ARG , unsigned long long* fpc, unsigned long long& fpt
-#define FPH_PASS , fpc, fpt
-#define FPH(i) { const unsigned long long t_ = wall_clock64(); fpc[i] += t_ - fpt; fpt = t_; }
-#else
-#define FPH_ARG
-#define FPH_PASS
-#define FPH(i) {}
-#endif
-
 template <bool HAS_DU, int SURR, int NPT>
 __device__ __forceinline__ void flow_step(const Dev& d, FlowState<NPT>& S, const int PAR, RevBatch& cur, RevBatch& nxt, bool last,
                                           int* s_dead, int* s_nspk, RevSpike (*s_spk)[kRevList], float (*s_G2)[4 * kResThreads],
-                                          float* fill_row, int& cnt_base0, int& cnt_base1 FPH_ARG) {
+                                          float* fill_row, int& cnt_base0, int& cnt_base1) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   constexpr int kWaves = kResThreads / 64;
   const long long n = S.n;
@@ -165,16 +154,12 @@ __device__ __forceinline__ void flow_step(const Dev& d, FlowState<NPT>& S, const
   // register that a load has not filled yet waits for the load): tape values of step n - 2, far queue terms and dL/dU
   // of step n - 1 (below step 0 the rows are step 0's again and are never used)
   const int slot1 = n >= 1 ? (S.slot == 0 ? d.R - 1 : S.slot - 1) : 0;   // (n - 1) mod R
-#ifdef ADSEQ_PHASE_CLOCK
-  if (!(d.dbg & 4))
-#endif
   {
     const __amdgpu_buffer_rsrc_t t2 = res_rows(S.tape2, hi * 4), f1 = res_rows(d.Gacc + (size_t)slot1 * d.BN, hi * 4);
     S.Uc = flow_load<NPT, kBufNonTemporal>(t2, g0 * 4);
     S.Gb = flow_load<NPT, kBufNonTemporal>(f1, g0 * 4);
     if (HAS_DU) S.dUb = flow_load<NPT, kBufNonTemporal>(res_rows(S.du1, hi * 4), g0 * 4);
   }
-  FPH(5)
   // ---- the row of this step, as early as can be (others may be waiting for it): final for every neuron that does not
   // spike; a spiking neuron's cell says "not yet" until its queue term is gathered below
   if (__ballot(S.actmask != 0u) != 0ull) {   // (wavefronts without neurons skip the arithmetic)
@@ -186,18 +171,12 @@ __device__ __forceinline__ void flow_step(const Dev& d, FlowState<NPT>& S, const
       gu4.v[c] = ((smask >> c) & 1u) ? __uint_as_float(kFlowSentinel) : gu;
     }
     const __amdgpu_buffer_rsrc_t row = res_rows(gwin, hi * 4), far = res_rows(d.Gacc + (size_t)S.slot * d.BN, hi * 4);
-#ifdef ADSEQ_PHASE_CLOCK
-    if (!(d.dbg & 8))
-#endif
-    {
     flow_store<NPT, kBufAgent>(gu4, row, g0 * 4);
     // the far queue terms are used up: the slot is another step's R steps on (stored by every lane, set or not)
     flow_store<NPT, 0>(flow_splat<NPT>(0.0f), far, g0 * 4);
     // the same row of the OTHER window buffer, which the next launch sweeps: "not written yet"
     if (fill_row) flow_store<NPT, 0>(flow_splat<NPT>(__uint_as_float(kFlowSentinel)), res_rows(fill_row, hi * 4), g0 * 4);
-    }
   }
-  FPH(6)
   // ---- this step's gathers (rows requested a step ago): every entry of the leading 64 that arrives inside the window
   float gv[4];
   const float* gp[4];
@@ -215,7 +194,6 @@ __device__ __forceinline__ void flow_step(const Dev& d, FlowState<NPT>& S, const
       }
     }
   }
-  FPH(0)
   // ---- the step after this one: list of the block's spikes, the leading 64 entries of their rows requested
   int nspk_nxt = 0;
   unsigned ovf_nxt = 0;
@@ -273,7 +251,6 @@ __device__ __forceinline__ void flow_step(const Dev& d, FlowState<NPT>& S, const
       }
     }
   }
-  FPH(1)
   // ---- the gathered adjoints, once they are all there; per-spike sums; the spiking neurons' final values
   float Gx[NPT];   // near parts that come back to the owner directly (spikes that did not fit the list)
 #pragma unroll
@@ -317,7 +294,6 @@ __device__ __forceinline__ void flow_step(const Dev& d, FlowState<NPT>& S, const
 #pragma unroll
     for (int u = 0; u < 4; ++u) cur.gv[u] = 0.0f;
   }
-  FPH(2)
   // the spiking neurons, with their whole queue term and the membrane value the step started from (a spiking
   // neuron's update does not use the carry: the reset cuts it)
   if (smask) {
@@ -335,7 +311,6 @@ __device__ __forceinline__ void flow_step(const Dev& d, FlowState<NPT>& S, const
 #pragma unroll
   for (int u = 0; u < 4; ++u)
     if (cur.len[u] > 0 && ((cur.ok >> u) & 1u)) unsafeAtomicAdd(&d.gsum[cur.r0[u] + lane], cur.gv[u]);
-  FPH(3)
   // on to the next step
   S.nspk_cur = nspk_nxt; S.ovf_cur = ovf_nxt;
   S.Ua = S.Ub; S.Ub = S.Uc; S.Ga = S.Gb; S.dUa = S.dUb;
@@ -344,10 +319,6 @@ __device__ __forceinline__ void flow_step(const Dev& d, FlowState<NPT>& S, const
   if (HAS_DU && n >= 2) S.du1 -= d.BN;
   S.gwin -= d.BN;
   S.n = n - 1; S.phi -= 1; S.tail += 1;
-#ifdef ADSEQ_PHASE_CLOCK
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // (what the moves above wait for, made visible)
-#endif
-  FPH(4)
 }
 
 // Reverse steps n_hi - 1, n_hi - 2, ..., n_hi - nsteps, all inside one window whose buffer the host
@@ -409,14 +380,11 @@ __global__ __launch_bounds__(kResThreads) void k_bwd_flow(long long n_hi, int ns
   }
   A.ok = 0u; B.ok = 0u;
   __syncthreads();
-#ifdef ADSEQ_PHASE_CLOCK
-  unsigned long long fpc[7] = {0, 0, 0, 0, 0, 0, 0}, fpt = wall_clock64();
-#endif
   float* const other = gwin_of(d, n_hi - 1 + d.W);   // (the buffers take turns window by window)
   int cnt_base0 = 0, cnt_base1 = 0;   // what the counters of list 0 and list 1 held when their last list was complete
   for (int k = 0; k < nsteps; ++k) {
     flow_step<HAS_DU, SURR, NPT>(d, S, k & 1, A, B, k + 1 == nsteps, &s_dead, s_nspk, s_spk, s_G,
-                      fill_other ? other + (size_t)(phi0 - k) * d.BN : nullptr, cnt_base0, cnt_base1 FPH_PASS);
+                      fill_other ? other + (size_t)(phi0 - k) * d.BN : nullptr, cnt_base0, cnt_base1);
     A = B;
   }
   if (fill_other && (S.actmask != 0u)) {
@@ -425,13 +393,6 @@ __global__ __launch_bounds__(kResThreads) void k_bwd_flow(long long n_hi, int ns
       if (r > phi0 || r <= phi0 - nsteps)
         flow_store<NPT, 0>(flow_splat<NPT>(__uint_as_float(kFlowSentinel)), res_rows(other + (size_t)r * d.BN, S.hi * 4), S.g0 * 4);
   }
-#ifdef ADSEQ_PHASE_CLOCK
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
-    const int at[7] = {11, 12, 13, 14, 20, 22, 23};
-    for (int i = 0; i < 7; ++i) atomicAdd(&d.ctr->phase[at[i]], fpc[i]);
-    atomicAdd(&d.ctr->phase[21], (unsigned long long)nsteps);
-  }
-#endif
 #pragma unroll
   for (int c = 0; c < NPT; ++c)
     if ((S.actmask >> c) & 1u) d.bwd_carry[S.g0 + c] = S.carry[c];
