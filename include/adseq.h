@@ -245,9 +245,10 @@ int adseq_run(adseq_t *h, int64_t step0, int64_t n_steps, void *stream);
  * the spike-time mode's E), summed over
  * trials.  dL_dcount: fp32 [B*N] or NULL; dL_dU: fp32 [T][B*N] or NULL; grad_w, grad_d: fp32 [S],
  * overwritten.  Synchronises the stream once at the start to read the device error word.
- * ADSEQ_RING runs the reverse steps of a window in one kernel whose blocks wait for one another
- * at a barrier per step (every wait bounded); should such a wait run out -- the blocks of a launch
- * were not running together -- the kernels still run to their end, the gradients are void, and
+ * ADSEQ_RING runs the reverse steps of a window in one kernel whose blocks wait for one another's
+ * results (for the adjoint cells they gather; every wait bounded); should such a wait run out --
+ * the blocks of a launch were not running together, or a cotangent held the NaN that marks a cell
+ * as not written yet (bits 0x7fa5c3e1) -- the kernels still run to their end, the gradients are void, and
  * the error word carries bit 32 afterwards: read it with adseq_counters once the stream is done
  * (adseq_drop_count and the next adseq_backward refuse the run with ADSEQ_E_HIP). */
 int adseq_backward(adseq_t *h, const float *dL_dcount, const float *dL_dU, float *grad_w,
