@@ -158,11 +158,15 @@ __global__ __launch_bounds__(kResLaunch) void k_fwd_chip(long long n0, int nstep
     __syncthreads();
     const int ncand = s_ncand < kFwdCand ? s_ncand : kFwdCand;
     // this wavefront's candidates: wave, wave + 8, wave + 16, wave + 24 of the list
-    uint2 ce[4]; long long cr0[4]; int clen[4], cbase[4], cloc[4];
+    // (the entries 64 .. 127 as well where a row may hold more than 64 inside the window: late in a window a spike
+    // of the headline network has 60 of them on average, and a row's entries beyond those in registers are a trip to
+    // memory between the threshold and the arrival)
+    uint2 ce[4], ce2[4]; long long cr0[4]; int clen[4], cbase[4], cloc[4];
+    const bool two = near_h >= 8;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int x = wave + u * kWaves;
-      ce[u] = make_uint2(0u, 0u); cr0[u] = 0; clen[u] = 0; cbase[u] = 0; cloc[u] = 0;
+      ce[u] = make_uint2(0u, 0u); ce2[u] = make_uint2(0u, 0u); cr0[u] = 0; clen[u] = 0; cbase[u] = 0; cloc[u] = 0;
       if (x < ncand) {   // (the same in every lane)
         const RevSpike r = s_cand[x];
         cr0[u] = uniform_of(r.r0);
@@ -174,6 +178,12 @@ __global__ __launch_bounds__(kResLaunch) void k_fwd_chip(long long n0, int nstep
         const __amdgpu_buffer_rsrc_t rs = res_rows(d.synf + cr0[u], shown * 8);
         const unsigned long long ev = __builtin_bit_cast(unsigned long long, __builtin_amdgcn_raw_buffer_load_b64(rs, lane * 8, 0, 0));
         ce[u] = make_uint2((unsigned)ev, (unsigned)(ev >> 32));
+        if (two && clen[u] > 64) {   // (uniform)
+          const int shown2 = clen[u] < 128 ? clen[u] : 128;
+          const __amdgpu_buffer_rsrc_t rs2 = res_rows(d.synf + cr0[u], shown2 * 8);
+          const unsigned long long ev2 = __builtin_bit_cast(unsigned long long, __builtin_amdgcn_raw_buffer_load_b64(rs2, 512 + lane * 8, 0, 0));
+          ce2[u] = make_uint2((unsigned)ev2, (unsigned)(ev2 >> 32));
+        }
       }
     }
     // ---- the adds of step n - 1 are in place once every block has arrived
@@ -230,7 +240,14 @@ __global__ __launch_bounds__(kResLaunch) void k_fwd_chip(long long n0, int nstep
       const int D = (int)(ce[u].x & d.dmask);
       const bool ok = lane < clen[u] && D <= near_h;
       if (ok) atomicAdd(&win[(size_t)D * d.BN + (size_t)cbase[u] + (ce[u].x >> d.dbits)], (int)ce[u].y);
-      fwd_row_tail(d, win, near_h, cr0[u], clen[u], cbase[u], 64, ok);
+      if (two && clen[u] > 64) {   // (uniform)
+        const int D2 = (int)(ce2[u].x & d.dmask);
+        const bool ok2 = (__ballot(ok) >> 63) != 0ull && 64 + lane < clen[u] && D2 <= near_h;   // (the rows ascend: nothing behind an entry that arrives too late)
+        if (ok2) atomicAdd(&win[(size_t)D2 * d.BN + (size_t)cbase[u] + (ce2[u].x >> d.dbits)], (int)ce2[u].y);
+        fwd_row_tail(d, win, near_h, cr0[u], clen[u], cbase[u], 128, ok2);
+      } else {
+        fwd_row_tail(d, win, near_h, cr0[u], clen[u], cbase[u], 64, ok);
+      }
     }
     // the others: row entries loaded now
     const int nslow = s_nslow;
