@@ -1,6 +1,6 @@
 // Ring queue, forward: the steps of one window in ONE launch over the whole chip, with the rows of
 // the neurons that are ABOUT to spike requested ahead (delta synapse).  Included by adseq.hip after
-// ring_resident_reverse.h, whose barrier (rev_wait / rev_arrive: eight arrival counters, a
+// ring_resident_reverse.h, whose barrier (rev_wait / rev_arrive: kArriveLines arrival counters, a
 // wavefront per block that only synchronises, bounded waits) and list entries it shares.
 //
 // The chain a forward step cannot avoid is: cells of the row (final once every block has arrived

@@ -27,11 +27,14 @@
 // no request stands behind a branch that depends on loaded data.
 //
 // The barrier: 128 blocks by default, spread over the chip's XCDs.  Arrivals at one counter
-// queue up behind one another (11 ns each), so the blocks arrive on eight counters, a line each;
-// the last wavefront of a block owns no neurons, only passes the block's barriers, polls the eight
-// counters side by side and adds the block's arrival; its first poll waits half a microsecond,
-// because polls are loads of the very lines the arrivals add to (measured on 100,000 neurons: one
-// counter, polls at once 4.5-6.8 us per step; eight counters, first poll delayed 3.55 us).
+// queue up behind one another (11 ns each), so the blocks arrive on kArriveLines (16) counters, a
+// line each; the last wavefront of a block owns no neurons, only passes the block's barriers,
+// polls the counters side by side and adds the block's arrival.  Polls are loads of the very lines
+// the arrivals add to (measured on 100,000 neurons: one counter, polls at once 4.5-6.8 us per
+// step; eight counters, first poll delayed by half a microsecond 3.55 us; sixteen, no delay 3.5 us).
+//
+// The default reverse kernel is k_bwd_flow (ring_flow_reverse.h), which has no grid barrier; this
+// one runs with ADSEQ_RING_REVERSE_FLOW = 0 and lends the other its lists, batches and helpers.
 //
 // Same arithmetic as k_bwd_step_win; the order in which a spike's terms are added differs (fp32
 // rounding only).  Results do not depend on where the blocks run: what crosses blocks goes
@@ -67,7 +70,7 @@ __device__ __forceinline__ void rev_arrive(const Dev& d, bool arrive, int rank) 
 }
 
 // The grid barrier's wait.  Arrivals at ONE counter queue up behind one another (11 ns each: 256 blocks, 2.8 us), so the
-// blocks arrive on eight counters, a line each, and the synchronising wavefront polls all eight side by side (one per
+// blocks arrive on kArriveLines counters, a line each, and the synchronising wavefront polls them all side by side (one per
 // lane) until their sum reaches the target.  The polls are loads of the very lines the arrivals add to, so the first
 // poll waits for as long as the workers need at least for what they do in front of the barrier.
 __device__ __forceinline__ void rev_wait(const Dev& d, unsigned target, int* dead) {
