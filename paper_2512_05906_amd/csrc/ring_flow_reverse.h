@@ -54,7 +54,7 @@ __device__ __forceinline__ float flow_row_tail(const Dev& d, const float* __rest
     const float* p = gwin;
     unsigned amp = 0u;
     if (q0 + lane < len) {
-      const uint2 e = d.synb[r0 + q0 + lane];
+      const uint2 e = load_stream(&d.synb[r0 + q0 + lane]);
       const int D = (int)(e.x & d.dmask);
       if (D <= near_h) {
         want = true;

@@ -38,7 +38,7 @@ __device__ __forceinline__ void fwd_row_tail(const Dev& d, int* __restrict__ win
   for (; (__ballot(more) >> 63) && q0 < len; q0 += 64) {
     more = false;
     if (q0 + lane < len) {
-      const uint2 e = d.synf[r0 + q0 + lane];
+      const uint2 e = load_stream(&d.synf[r0 + q0 + lane]);
       const int D = (int)(e.x & d.dmask);
       if (D <= near_h) {
         atomicAdd(&win[(size_t)D * d.BN + (size_t)base + (e.x >> d.dbits)], (int)e.y);

@@ -108,7 +108,7 @@ __device__ __forceinline__ float rev_row_tail(const Dev& d, const float* __restr
     more = false;
     float t = 0.0f;
     if (q0 + lane < len) {
-      const uint2 e = d.synb[r0 + q0 + lane];
+      const uint2 e = load_stream(&d.synb[r0 + q0 + lane]);
       const int D = (int)(e.x & d.dmask);
       if (D <= near_h) {
         const float gv = ld_agent(&gwin[(size_t)D * d.BN + (size_t)base + (e.x >> d.dbits)]);

@@ -411,6 +411,9 @@ __global__ __launch_bounds__(kBlock) void k_open_step_win(Dev d, long long n, co
 // Streaming loads of the expansion and gather passes (row pieces and staged events are read
 // once per pass): non-temporal, so that they do not push the window out of the L2.  (The staging
 // stores stay ordinary: as non-temporal 8-byte stores they reach memory one by one, 2.6x slower.)
+// Also what the resident kernels read a row's later entries with: ONE 8-byte load (written as
+// `const uint2 e = row[i]` with e.y used only under a test of e.x, the compiler loads the two halves
+// one after the other, the second behind the test: two trips to memory for one).
 __device__ __forceinline__ uint2 load_stream(const uint2* p) {
   const unsigned long long v = __builtin_nontemporal_load(reinterpret_cast<const unsigned long long*>(p));
   return make_uint2((unsigned)v, (unsigned)(v >> 32));
