@@ -593,7 +593,9 @@ ResidentPlan reverse_plan(long long BN, bool forward = false) {
                              : env_pow2("ADSEQ_RING_REVERSE_BLOCKS", env_pow2("ADSEQ_RING_REVERSE_FLOW", 1, 0, 1) ? 256 : 128, 8, 256);
   long long chunk = (BN + blocks - 1) / blocks;
   chunk = (chunk + 255) / 256 * 256;
-  if (on && chunk <= 4 * kResThreads && BN % 4 == 0) {
+  // (the reverse kernel without a grid barrier also takes eight neurons per thread: a million state cells)
+  const int per_thread = (!forward && env_pow2("ADSEQ_RING_REVERSE_FLOW", 1, 0, 1)) ? 8 : 4;
+  if (on && chunk <= per_thread * kResThreads && BN % 4 == 0) {
     r.chunk = (int)chunk;
     r.P = (int)((BN + chunk - 1) / chunk);
     r.npt = 1;
@@ -626,7 +628,8 @@ const void* flow_kernel_of(int surrogate) {
 }
 const void* flow_kernel(bool du, int surrogate, int chunk) {
   if (chunk <= kResThreads) return du ? flow_kernel_of<true, 1>(surrogate) : flow_kernel_of<false, 1>(surrogate);
-  return du ? flow_kernel_of<true, 4>(surrogate) : flow_kernel_of<false, 4>(surrogate);
+  if (chunk <= 4 * kResThreads) return du ? flow_kernel_of<true, 4>(surrogate) : flow_kernel_of<false, 4>(surrogate);
+  return du ? flow_kernel_of<true, 8>(surrogate) : flow_kernel_of<false, 8>(surrogate);
 }
 const void* run_xcd_kernel(bool record, int syn, int npt) {
   return record ? run_xcd_kernel_of<true>(syn, npt) : run_xcd_kernel_of<false>(syn, npt);
@@ -1285,7 +1288,7 @@ void ring_backward_launch(adseq* h, hipStream_t st, long long T, float dscale, c
           const int fill_other = (counts == nullptr && k0 > 0) ? 1 : 0;
           // (one neuron per thread where a block owns no more than it has threads, else four)
 #define ADSEQ_FLOW3(DU, SURR, NPT) hipLaunchKernelGGL((k_bwd_flow<DU, SURR, NPT>), rg, dim3(kResThreads), 0, st, k1, nsteps, T, h->rev_P, h->rev_chunk, stride, fill_other, dL_dcount, dL_dU, d)
-#define ADSEQ_FLOW(DU, SURR) do { if (h->rev_chunk <= kResThreads) ADSEQ_FLOW3(DU, SURR, 1); else ADSEQ_FLOW3(DU, SURR, 4); } while (0)
+#define ADSEQ_FLOW(DU, SURR) do { if (h->rev_chunk <= kResThreads) ADSEQ_FLOW3(DU, SURR, 1); else if (h->rev_chunk <= 4 * kResThreads) ADSEQ_FLOW3(DU, SURR, 4); else ADSEQ_FLOW3(DU, SURR, 8); } while (0)
           if (d.surrogate == ADSEQ_SURR_SUPERSPIKE) { if (dL_dU) ADSEQ_FLOW(true, ADSEQ_SURR_SUPERSPIKE); else ADSEQ_FLOW(false, ADSEQ_SURR_SUPERSPIKE); }
           else if (d.surrogate == ADSEQ_GRAD_SPIKE_TIME) { if (dL_dU) ADSEQ_FLOW(true, ADSEQ_GRAD_SPIKE_TIME); else ADSEQ_FLOW(false, ADSEQ_GRAD_SPIKE_TIME); }
           else { if (dL_dU) ADSEQ_FLOW(true, ADSEQ_SURR_OFF); else ADSEQ_FLOW(false, ADSEQ_SURR_OFF); }
@@ -1524,12 +1527,13 @@ int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, 
     h->res_chunk = rp.chunk; h->res_P = rp.P; h->res_npt = rp.npt;
     if (!(d.alpha_s > 0.0f)) {
       ResidentPlan vp = reverse_plan((long long)d.BN);
-      if (vp.P > 0 && !(resident_fits((const void*)k_bwd_xcd<true>) && resident_fits((const void*)k_bwd_xcd<false>))) vp = ResidentPlan();
+      if (vp.P > 0 && vp.chunk <= 4 * kResThreads && !(resident_fits((const void*)k_bwd_xcd<true>) && resident_fits((const void*)k_bwd_xcd<false>))) vp = ResidentPlan();
       h->rev_chunk = vp.chunk; h->rev_P = vp.P; h->rev_npt = vp.npt;
       // the same layout without a grid barrier: the blocks wait for the cells they gather (ring_flow_reverse.h);
       // ADSEQ_RING_REVERSE_FLOW = 0: the kernel with a barrier per step
       h->rev_flow = vp.P > 0 && env_pow2("ADSEQ_RING_REVERSE_FLOW", 1, 0, 1) &&
                     resident_fits(flow_kernel(true, d.surrogate, vp.chunk), kResThreads) && resident_fits(flow_kernel(false, d.surrogate, vp.chunk), kResThreads);
+      if (!h->rev_flow && vp.chunk > 4 * kResThreads) { h->rev_chunk = 0; h->rev_P = 0; h->rev_npt = 0; }   // (the kernel with a barrier holds four neurons per thread)
       // forward kernel over the whole chip with the candidates' rows requested ahead (ring_resident_forward.h): the
       // reverse kernel's layout (ADSEQ_RING_FORWARD_BLOCKS taking-part blocks, default 256).  ADSEQ_RING_FORWARD_CHIP:
       // see reverse_plan; ADSEQ_RING_FORWARD_MARGIN: candidate margin in thousandths of the membrane unit (default 5).

@@ -84,18 +84,27 @@ template <int NPT> struct FlowVec { float v[NPT]; };
 template <int NPT, int AUX>
 __device__ __forceinline__ FlowVec<NPT> flow_load(__amdgpu_buffer_rsrc_t rs, int off) {
   FlowVec<NPT> r;
-  if constexpr (NPT == 4) {
+  if constexpr (NPT == 8) {
+    const res_v4f x = __builtin_bit_cast(res_v4f, __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, AUX));
+    const res_v4f y = __builtin_bit_cast(res_v4f, __builtin_amdgcn_raw_buffer_load_b128(rs, off + 16, 0, AUX));
+    r.v[0] = x[0]; r.v[1] = x[1]; r.v[2] = x[2]; r.v[3] = x[3];
+    r.v[4] = y[0]; r.v[5] = y[1]; r.v[6] = y[2]; r.v[7] = y[3];
+  } else if constexpr (NPT == 4) {
     const res_v4f x = __builtin_bit_cast(res_v4f, __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, AUX));
     r.v[0] = x[0]; r.v[1] = x[1]; r.v[2] = x[2]; r.v[3] = x[3];
   } else {
-    static_assert(NPT == 1, "one or four neurons per thread");
+    static_assert(NPT == 1, "one, four or eight neurons per thread");
     r.v[0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, off, 0, AUX));
   }
   return r;
 }
 template <int NPT, int AUX>
 __device__ __forceinline__ void flow_store(const FlowVec<NPT>& x, __amdgpu_buffer_rsrc_t rs, int off) {
-  if constexpr (NPT == 4) {
+  if constexpr (NPT == 8) {
+    const res_v4f y = {x.v[0], x.v[1], x.v[2], x.v[3]}, z = {x.v[4], x.v[5], x.v[6], x.v[7]};
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(res_v4i, y), rs, off, 0, AUX);
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(res_v4i, z), rs, off + 16, 0, AUX);
+  } else if constexpr (NPT == 4) {
     const res_v4f y = {x.v[0], x.v[1], x.v[2], x.v[3]};
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(res_v4i, y), rs, off, 0, AUX);
   } else {
@@ -131,7 +140,7 @@ struct FlowState {
 
 template <bool HAS_DU, int SURR, int NPT>
 __device__ __forceinline__ void flow_step(const Dev& d, FlowState<NPT>& S, const int PAR, RevBatch& cur, RevBatch& nxt, bool last,
-                                          int* s_dead, int* s_nspk, RevSpike (*s_spk)[kRevList], float (*s_G2)[4 * kResThreads],
+                                          int* s_dead, int* s_nspk, RevSpike (*s_spk)[kRevList], float (*s_G2)[(NPT < 4 ? 4 : NPT) * kResThreads],
                                           float* fill_row, int& cnt_base0, int& cnt_base1) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   constexpr int kWaves = kResThreads / 64;
@@ -323,9 +332,9 @@ __device__ __forceinline__ void flow_step(const Dev& d, FlowState<NPT>& S, const
 
 // Reverse steps n_hi - 1, n_hi - 2, ..., n_hi - nsteps, all inside one window whose buffer the host
 // has filled with the sentinel.  P taking-part blocks (every stride-th block of the grid), each
-// owning `chunk` <= NPT * 512 neurons, NPT consecutive ones per thread (NPT = 4: 16-byte accesses, B N a
-// multiple of 4; NPT = 1 where the blocks own 512 neurons at most: the dense part of a step then spreads over all
-// the block's wavefronts).  HAS_DU: a cotangent on the membrane values comes with the call; SURR: the gradient mode.
+// owning `chunk` <= NPT * 512 neurons, NPT consecutive ones per thread (NPT = 4 or, for state arrays beyond
+// 256 x 2,048 cells, 8: 16-byte accesses, B N a multiple of 4; NPT = 1 where the blocks own 512 neurons at most: the
+// dense part of a step then spreads over all the block's wavefronts).  HAS_DU: a cotangent on the membrane values comes with the call; SURR: the gradient mode.
 // fill_other: the launch also fills the OTHER window buffer (the one the next launch sweeps) with the sentinel, every
 // block the cells of its own neurons, a row per step and what is left when the steps are done.
 template <bool HAS_DU, int SURR, int NPT>
@@ -334,7 +343,7 @@ __global__ __launch_bounds__(kResThreads) void k_bwd_flow(long long n_hi, int ns
                                                           const float* __restrict__ dL_dU, Dev d) {
   __shared__ int s_dead, s_nspk[2];
   __shared__ RevSpike s_spk[2][kRevList];     // the block's spikes of the step being run and of the step being prepared
-  __shared__ float s_G[2][4 * kResThreads];   // near part of the queue term of every listed spike, by its neuron's place (two steps' worth in turn)
+  __shared__ float s_G[2][(NPT < 4 ? 4 : NPT) * kResThreads];   // near part of the queue term of every listed spike, by its neuron's place (two steps' worth in turn)
   if (blockIdx.x % stride) return;
   const int rank = blockIdx.x / stride;
   if (rank >= P) return;

@@ -267,8 +267,9 @@ def test_resident_reverse_block_counts_and_spread(blocks, stride, rev_kernel, mo
 
 
 def test_resident_reverse_falls_back_where_the_layout_does_not_fit(rev_kernel, monkeypatch):
-    """B N not a multiple of 4 (rows of the window not 16-byte aligned) and more state cells than 256 blocks of
-    2,048 hold: the reverse sweep goes by one launch per step, same gradients."""
+    """B N not a multiple of 4 (rows of the window not 16-byte aligned): the reverse sweep goes by one launch per step,
+    same gradients.  More state cells than the blocks hold at four neurons per thread (8 blocks of 2,048 < 20,000): the
+    kernel with a grid barrier falls back likewise, the one without takes eight neurons per thread."""
     monkeypatch.setenv("ADSEQ_RING_REVERSE_WINDOWS", "0")
     wl = synth.ragged_network(1201, 100, 30, seed=43, rate_hz=500.0, t=60, b=3, w_mean=0.008, w_std=0.005)
     _reverse_against_oracle(wl, 60, 3)
