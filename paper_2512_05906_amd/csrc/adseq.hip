@@ -1162,8 +1162,11 @@ void ring_run_chip(adseq* h, hipStream_t st, long long step0, long long n_steps)
     const bool record = d.record && h->tape_ok && n < d.max_steps;
     if (record && n + cnt > d.max_steps) cnt = (int)(d.max_steps - n);
     if (d.record && n >= d.max_steps) h->tape_ok = false;
-    if (record) hipLaunchKernelGGL((k_fwd_chip<true>), grid, block, 0, st, n, cnt, h->rev_base, h->fwd_P, h->fwd_chunk, stride, h->fwd_margin, d);
-    else hipLaunchKernelGGL((k_fwd_chip<false>), grid, block, 0, st, n, cnt, h->rev_base, h->fwd_P, h->fwd_chunk, stride, h->fwd_margin, d);
+    // (one neuron per thread where a block owns no more neurons than it has worker threads, else four)
+#define ADSEQ_FWD(REC, NPT) hipLaunchKernelGGL((k_fwd_chip<REC, NPT>), grid, block, 0, st, n, cnt, h->rev_base, h->fwd_P, h->fwd_chunk, stride, h->fwd_margin, d)
+    if (h->fwd_chunk <= kResThreads) { if (record) ADSEQ_FWD(true, 1); else ADSEQ_FWD(false, 1); }
+    else { if (record) ADSEQ_FWD(true, 4); else ADSEQ_FWD(false, 4); }
+#undef ADSEQ_FWD
     h->rev_base += (unsigned)(cnt - 1) * (unsigned)h->fwd_P;
     h->grp_count += 1;   // (launches of the group)
     h->enq_calls += cnt;
@@ -1538,7 +1541,10 @@ int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, 
       // reverse kernel's layout (ADSEQ_RING_FORWARD_BLOCKS taking-part blocks, default 256).  ADSEQ_RING_FORWARD_CHIP:
       // see reverse_plan; ADSEQ_RING_FORWARD_MARGIN: candidate margin in thousandths of the membrane unit (default 5).
       ResidentPlan fp = reverse_plan((long long)d.BN, true);
-      if (fp.P > 0 && !(resident_fits((const void*)k_fwd_chip<true>) && resident_fits((const void*)k_fwd_chip<false>))) fp = ResidentPlan();
+      if (fp.P > 0 && !(fp.chunk <= kResThreads
+                            ? resident_fits((const void*)k_fwd_chip<true, 1>) && resident_fits((const void*)k_fwd_chip<false, 1>)
+                            : resident_fits((const void*)k_fwd_chip<true, 4>) && resident_fits((const void*)k_fwd_chip<false, 4>)))
+        fp = ResidentPlan();
       if (fp.P > 0 && !d.count_pop) {
         h->fwd_P = fp.P; h->fwd_chunk = fp.chunk; h->res_P = 0;
         if (const char* e = getenv("ADSEQ_RING_FORWARD_MARGIN")) { const int v = atoi(e); if (v >= 0 && v <= 100000) h->fwd_margin = (float)v * 1e-3f; }

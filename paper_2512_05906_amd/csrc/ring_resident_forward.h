@@ -22,10 +22,11 @@
 
 constexpr int kFwdCand = 32;   // candidates per block and step whose rows are requested ahead (four per worker wavefront)
 
+template <int NPT>
 struct FwdState {
-  float V[4];
-  long long r0[4]; int rlen[4];
-  unsigned long long zg[4];      // mix64(seed + G (g + 1)): the neuron's half of the drive's hash
+  float V[NPT];
+  long long r0[NPT]; int rlen[NPT];
+  unsigned long long zg[NPT];    // mix64(seed + G (g + 1)): the neuron's half of the drive's hash
   unsigned actmask;
   int g0, hi;
 };
@@ -49,10 +50,11 @@ __device__ __forceinline__ void fwd_row_tail(const Dev& d, int* __restrict__ win
 }
 
 // Steps n0 .. n0 + nsteps - 1, all inside one window.  P taking-part blocks (every stride-th block of
-// the grid), each owning `chunk` <= 2,048 neurons, four consecutive ones per thread; B N a multiple
-// of 4.  bar_base: sum of the arrival counters when the launch begins.  margin: how far below the
+// the grid), each owning `chunk` <= NPT * 512 neurons, NPT consecutive ones per thread (four, or one where a block
+// owns no more neurons than it has threads: a step's instructions then spread over all its wavefronts); B N a
+// multiple of 4.  bar_base: sum of the arrival counters when the launch begins.  margin: how far below the
 // threshold the early value of a candidate may lie.
-template <bool RECORD>
+template <bool RECORD, int NPT>
 __global__ __launch_bounds__(kResLaunch) void k_fwd_chip(long long n0, int nsteps, unsigned bar_base, int P, int chunk,
                                                           int stride, float margin, Dev d) {
   __shared__ int s_dead, s_ncand, s_nslow;
@@ -78,13 +80,13 @@ __global__ __launch_bounds__(kResLaunch) void k_fwd_chip(long long n0, int nstep
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   constexpr int kWaves = kResThreads / 64;
   const int lo = rank * chunk;
-  FwdState S;
+  FwdState<NPT> S;
   S.hi = lo + chunk < d.BN ? lo + chunk : d.BN;
-  S.g0 = lo + 4 * (int)threadIdx.x;
+  S.g0 = lo + NPT * (int)threadIdx.x;
   S.actmask = 0;
   const unsigned long long G64 = 0x9E3779B97F4A7C15ull;
 #pragma unroll
-  for (int c = 0; c < 4; ++c) {
+  for (int c = 0; c < NPT; ++c) {
     const int g = S.g0 + c;
     S.V[c] = 0.0f; S.r0[c] = 0; S.rlen[c] = 0; S.zg[c] = 0ull;
     if (g < S.hi) {
@@ -97,9 +99,9 @@ __global__ __launch_bounds__(kResLaunch) void k_fwd_chip(long long n0, int nstep
     }
   }
   const int g0 = S.g0, hi = S.hi;
-  // the wavefront's four spike words: lane w < 4 stores word (first neuron of the wavefront) / 64 + w
+  // the wavefront's NPT spike words: lane w < NPT stores word (first neuron of the wavefront) / 64 + w
   const int gw = __builtin_amdgcn_readfirstlane(g0);
-  const int my_word = (lane < 4 && gw < lo + chunk && (gw >> 6) + lane < d.words) ? (gw >> 6) + lane : -1;
+  const int my_word = (lane < NPT && gw < lo + chunk && (gw >> 6) + lane < d.words) ? (gw >> 6) + lane : -1;
   int slot = (int)(n0 % d.R);   // row of the circular spike words that holds step n0 (one division per launch)
   int phi = (int)(n0 & (long long)(d.W - 1));
   int* __restrict__ win = win_of(d, n0) + (size_t)phi * d.BN;   // row of the step being run
@@ -115,15 +117,15 @@ __global__ __launch_bounds__(kResLaunch) void k_fwd_chip(long long n0, int nstep
     unsigned xi = 0;
     if (d.p_thresh) {
 #pragma unroll
-      for (int c = 0; c < 4; ++c)
+      for (int c = 0; c < NPT; ++c)
         xi |= (mix64(S.zg[c] + G64 * ((unsigned long long)n + 1ull)) >> 32) < d.p_thresh ? 1u << c : 0u;
     }
     unsigned cmask = 0;   // bit c: neuron c is a candidate
     {
-      const res_v4i early = __builtin_amdgcn_raw_buffer_load_b128(cells, g0 * 4, 0, kBufAgent);
+      const FlowVec<NPT> early = flow_load<NPT, kBufAgent>(cells, g0 * 4);
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        float I = (float)early[c] * 0x1p-24f;
+      for (int c = 0; c < NPT; ++c) {
+        float I = (float)__float_as_int(early.v[c]) * 0x1p-24f;
         if (d.p_thresh) I = I + (((xi >> c) & 1u) ? d.ext_w : 0.0f);
         cmask |= __fmaf_rn(d.alpha, S.V[c], I) >= cand_theta ? 1u << c : 0u;
       }
@@ -132,22 +134,22 @@ __global__ __launch_bounds__(kResLaunch) void k_fwd_chip(long long n0, int nstep
     }
     unsigned listed = 0;   // bit c: neuron c is among the block's first kFwdCand candidates
     if (__ballot(cmask != 0u) != 0ull) {
-      unsigned long long m[4];
+      unsigned long long m[NPT];
       int total = 0;
 #pragma unroll
-      for (int c = 0; c < 4; ++c) { m[c] = __ballot(((cmask >> c) & 1u) && S.rlen[c] > 0); total += __popcll(m[c]); }
+      for (int c = 0; c < NPT; ++c) { m[c] = __ballot(((cmask >> c) & 1u) && S.rlen[c] > 0); total += __popcll(m[c]); }
       int at = 0;
       if (lane == 0 && total) at = atomicAdd(&s_ncand, total);
       at = __builtin_amdgcn_readfirstlane(at);
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
+      for (int c = 0; c < NPT; ++c) {
         if (m[c] == 0ull) continue;   // uniform
         if ((m[c] >> lane) & 1ull) {
           const int idx = at + __popcll(m[c] & ((1ull << lane) - 1ull));
           if (idx < kFwdCand) {
             RevSpike r;
             r.r0 = S.r0[c]; r.len = S.rlen[c];
-            r.pk = (4 * (int)threadIdx.x + c) | (trial_of(d, g0 + c) << kRevLocBits);
+            r.pk = (NPT * (int)threadIdx.x + c) | (trial_of(d, g0 + c) << kRevLocBits);
             s_cand[idx] = r;
             listed |= 1u << c;
           }
@@ -188,13 +190,13 @@ __global__ __launch_bounds__(kResLaunch) void k_fwd_chip(long long n0, int nstep
     }
     // ---- the adds of step n - 1 are in place once every block has arrived
     if (k > 0) rev_wait(d, bar_base + (unsigned)k * (unsigned)P, &s_dead);
-    float U[4];
+    float U[NPT];
     unsigned smask = 0;
     {
-      const res_v4i acc = __builtin_amdgcn_raw_buffer_load_b128(cells, g0 * 4, 0, kBufAgent);
+      const FlowVec<NPT> acc = flow_load<NPT, kBufAgent>(cells, g0 * 4);
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        float I = (float)acc[c] * 0x1p-24f;
+      for (int c = 0; c < NPT; ++c) {
+        float I = (float)__float_as_int(acc.v[c]) * 0x1p-24f;
         if (d.p_thresh) I = I + (((xi >> c) & 1u) ? d.ext_w : 0.0f);
         U[c] = __fmaf_rn(d.alpha, S.V[c], I);
         const bool s = U[c] >= d.theta;
@@ -206,25 +208,25 @@ __global__ __launch_bounds__(kResLaunch) void k_fwd_chip(long long n0, int nstep
     // which candidates spiked; the spikes that were no (listed) candidates go to the slow list
     if (__ballot(listed != 0u) != 0ull) {
 #pragma unroll
-      for (int c = 0; c < 4; ++c)
-        if ((listed >> c) & 1u) s_fired[4 * (int)threadIdx.x + c] = (unsigned char)((smask >> c) & 1u);
+      for (int c = 0; c < NPT; ++c)
+        if ((listed >> c) & 1u) s_fired[NPT * (int)threadIdx.x + c] = (unsigned char)((smask >> c) & 1u);
     }
     const unsigned slowmask = near_h >= 1 ? (smask & ~listed) : 0u;
     if (__ballot(slowmask != 0u) != 0ull) {
-      unsigned long long m[4];
+      unsigned long long m[NPT];
       int total = 0;
 #pragma unroll
-      for (int c = 0; c < 4; ++c) { m[c] = __ballot(((slowmask >> c) & 1u) && S.rlen[c] > 0); total += __popcll(m[c]); }
+      for (int c = 0; c < NPT; ++c) { m[c] = __ballot(((slowmask >> c) & 1u) && S.rlen[c] > 0); total += __popcll(m[c]); }
       int at = 0;
       if (lane == 0 && total) at = atomicAdd(&s_nslow, total);
       at = __builtin_amdgcn_readfirstlane(at);
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
+      for (int c = 0; c < NPT; ++c) {
         if (m[c] == 0ull) continue;   // uniform
         if ((m[c] >> lane) & 1ull) {
           RevSpike r;
           r.r0 = S.r0[c]; r.len = S.rlen[c];
-          r.pk = (4 * (int)threadIdx.x + c) | (trial_of(d, g0 + c) << kRevLocBits);
+          r.pk = (NPT * (int)threadIdx.x + c) | (trial_of(d, g0 + c) << kRevLocBits);
           s_slow[at + __popcll(m[c] & ((1ull << lane) - 1ull))] = r;
         }
         at += __popcll(m[c]);
@@ -260,28 +262,31 @@ __global__ __launch_bounds__(kResLaunch) void k_fwd_chip(long long n0, int nstep
     if (threadIdx.x == 0) s_nslow = 0;   // (the next step's slow spikes are counted behind its first block barrier)
     // ---- after the arrival, off the chain: the popped cells cleared (nothing adds to them before the window after next
     // is expanded, launches later), tape, spike words and counts of this step
-    {
-      const res_v4i z = {0, 0, 0, 0};
-      __builtin_amdgcn_raw_buffer_store_b128(z, cells, g0 * 4, 0, 0);
-    }
+    flow_store<NPT, 0>(flow_splat<NPT>(0.0f), cells, g0 * 4);   // (the bits of 0.0f are those of the integer 0)
     if (RECORD) {
       const __amdgpu_buffer_rsrc_t tape = res_rows(d.tapeU + (size_t)n * d.BN, hi * 4);
-      const res_v4f u4 = {U[0], U[1], U[2], U[3]};
-      __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(res_v4i, u4), tape, g0 * 4, 0, kBufNonTemporal);
+      FlowVec<NPT> u4;
+#pragma unroll
+      for (int c = 0; c < NPT; ++c) u4.v[c] = U[c];
+      flow_store<NPT, kBufNonTemporal>(u4, tape, g0 * 4);
     }
     unsigned long long wbits = 0ull;
     if (__ballot(smask != 0u) != 0ull) {
       if (RECORD) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
+        for (int c = 0; c < NPT; ++c)
           if ((smask >> c) & 1u) atomicAdd(&d.spk_count[g0 + c], 1);
       }
-      // lane 16 w + x holds neurons 4 x .. 4 x + 3 of word w; lane l of a ballot must stand for neuron l of the word
+      if constexpr (NPT == 4) {
+        // lane 16 w + x holds neurons 4 x .. 4 x + 3 of word w; lane l of a ballot must stand for neuron l of the word
 #pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        const int v = __shfl((int)smask, 16 * w + (lane >> 2), 64);
-        const unsigned long long b = __ballot((v >> (lane & 3)) & 1);
-        if (lane == w) wbits = b;
+        for (int w = 0; w < 4; ++w) {
+          const int v = __shfl((int)smask, 16 * w + (lane >> 2), 64);
+          const unsigned long long b = __ballot((v >> (lane & 3)) & 1);
+          if (lane == w) wbits = b;
+        }
+      } else {
+        wbits = __ballot(smask & 1u);   // lane l holds neuron l of the wavefront's one word
       }
     }
     if (my_word >= 0) {
@@ -293,6 +298,6 @@ __global__ __launch_bounds__(kResLaunch) void k_fwd_chip(long long n0, int nstep
     win += d.BN;
   }
 #pragma unroll
-  for (int c = 0; c < 4; ++c)
+  for (int c = 0; c < NPT; ++c)
     if ((S.actmask >> c) & 1u) d.V[g0 + c] = S.V[c];
 }
