@@ -578,8 +578,9 @@ ResidentPlan resident_plan(long long BN) {
   }
   return r;
 }
-// Resident reverse kernel (ring_resident_reverse.h): up to 256 blocks of 512 threads with four consecutive
-// neurons each (at most 2,048 neurons per block), B N a multiple of 4; delta synapse only.
+// Resident reverse and forward kernels (ring_flow_reverse.h, ring_resident_reverse.h, ring_resident_forward.h): up
+// to 256 blocks of 512 worker threads with one, four or -- not the reverse kernel with a grid barrier -- eight
+// consecutive neurons each (at most 4,096 neurons per block), B N a multiple of 4; delta synapse only.
 // ADSEQ_RING_RESIDENT_REVERSE = 0: never, 1 (default): whenever the layout allows; ADSEQ_RING_REVERSE_BLOCKS:
 // taking-part blocks (8 .. 256, default 128).
 ResidentPlan reverse_plan(long long BN, bool forward = false) {
@@ -593,8 +594,8 @@ ResidentPlan reverse_plan(long long BN, bool forward = false) {
                              : env_pow2("ADSEQ_RING_REVERSE_BLOCKS", env_pow2("ADSEQ_RING_REVERSE_FLOW", 1, 0, 1) ? 256 : 128, 8, 256);
   long long chunk = (BN + blocks - 1) / blocks;
   chunk = (chunk + 255) / 256 * 256;
-  // (the reverse kernel without a grid barrier also takes eight neurons per thread: a million state cells)
-  const int per_thread = (!forward && env_pow2("ADSEQ_RING_REVERSE_FLOW", 1, 0, 1)) ? 8 : 4;
+  // (the forward kernel and the reverse kernel without a grid barrier also take eight neurons per thread: a million state cells)
+  const int per_thread = (forward || env_pow2("ADSEQ_RING_REVERSE_FLOW", 1, 0, 1)) ? 8 : 4;
   if (on && chunk <= per_thread * kResThreads && BN % 4 == 0) {
     r.chunk = (int)chunk;
     r.P = (int)((BN + chunk - 1) / chunk);
@@ -1165,7 +1166,8 @@ void ring_run_chip(adseq* h, hipStream_t st, long long step0, long long n_steps)
     // (one neuron per thread where a block owns no more neurons than it has worker threads, else four)
 #define ADSEQ_FWD(REC, NPT) hipLaunchKernelGGL((k_fwd_chip<REC, NPT>), grid, block, 0, st, n, cnt, h->rev_base, h->fwd_P, h->fwd_chunk, stride, h->fwd_margin, d)
     if (h->fwd_chunk <= kResThreads) { if (record) ADSEQ_FWD(true, 1); else ADSEQ_FWD(false, 1); }
-    else { if (record) ADSEQ_FWD(true, 4); else ADSEQ_FWD(false, 4); }
+    else if (h->fwd_chunk <= 4 * kResThreads) { if (record) ADSEQ_FWD(true, 4); else ADSEQ_FWD(false, 4); }
+    else { if (record) ADSEQ_FWD(true, 8); else ADSEQ_FWD(false, 8); }
 #undef ADSEQ_FWD
     h->rev_base += (unsigned)(cnt - 1) * (unsigned)h->fwd_P;
     h->grp_count += 1;   // (launches of the group)
@@ -1543,7 +1545,9 @@ int create_in(const adseq_config* cfg, void* workspace, size_t workspace_bytes, 
       ResidentPlan fp = reverse_plan((long long)d.BN, true);
       if (fp.P > 0 && !(fp.chunk <= kResThreads
                             ? resident_fits((const void*)k_fwd_chip<true, 1>) && resident_fits((const void*)k_fwd_chip<false, 1>)
-                            : resident_fits((const void*)k_fwd_chip<true, 4>) && resident_fits((const void*)k_fwd_chip<false, 4>)))
+                            : fp.chunk <= 4 * kResThreads
+                            ? resident_fits((const void*)k_fwd_chip<true, 4>) && resident_fits((const void*)k_fwd_chip<false, 4>)
+                            : resident_fits((const void*)k_fwd_chip<true, 8>) && resident_fits((const void*)k_fwd_chip<false, 8>)))
         fp = ResidentPlan();
       if (fp.P > 0 && !d.count_pop) {
         h->fwd_P = fp.P; h->fwd_chunk = fp.chunk; h->res_P = 0;

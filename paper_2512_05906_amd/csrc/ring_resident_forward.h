@@ -50,17 +50,17 @@ __device__ __forceinline__ void fwd_row_tail(const Dev& d, int* __restrict__ win
 }
 
 // Steps n0 .. n0 + nsteps - 1, all inside one window.  P taking-part blocks (every stride-th block of
-// the grid), each owning `chunk` <= NPT * 512 neurons, NPT consecutive ones per thread (four, or one where a block
-// owns no more neurons than it has threads: a step's instructions then spread over all its wavefronts); B N a
-// multiple of 4.  bar_base: sum of the arrival counters when the launch begins.  margin: how far below the
+// the grid), each owning `chunk` <= NPT * 512 neurons, NPT consecutive ones per thread (four; eight for state arrays
+// beyond 256 x 2,048 cells; one where a block owns no more neurons than it has threads: a step's instructions then
+// spread over all its wavefronts); B N a multiple of 4.  bar_base: sum of the arrival counters when the launch begins.  margin: how far below the
 // threshold the early value of a candidate may lie.
 template <bool RECORD, int NPT>
 __global__ __launch_bounds__(kResLaunch) void k_fwd_chip(long long n0, int nsteps, unsigned bar_base, int P, int chunk,
                                                           int stride, float margin, Dev d) {
   __shared__ int s_dead, s_ncand, s_nslow;
   __shared__ RevSpike s_cand[kFwdCand];            // candidates of the step: row bounds, place | trial << kRevLocBits
-  __shared__ RevSpike s_slow[4 * kResThreads];     // spikes that were no candidates (one entry per neuron at most)
-  __shared__ unsigned char s_fired[4 * kResThreads];   // by the neuron's place in the block: it spiked in this step
+  __shared__ RevSpike s_slow[(NPT < 4 ? 4 : NPT) * kResThreads];     // spikes that were no candidates (one entry per neuron at most)
+  __shared__ unsigned char s_fired[(NPT < 4 ? 4 : NPT) * kResThreads];   // by the neuron's place in the block: it spiked in this step
   if (blockIdx.x % stride) return;
   const int rank = blockIdx.x / stride;
   if (rank >= P) return;
@@ -277,7 +277,15 @@ __global__ __launch_bounds__(kResLaunch) void k_fwd_chip(long long n0, int nstep
         for (int c = 0; c < NPT; ++c)
           if ((smask >> c) & 1u) atomicAdd(&d.spk_count[g0 + c], 1);
       }
-      if constexpr (NPT == 4) {
+      if constexpr (NPT == 8) {
+        // lane 8 w + x holds neurons 8 x .. 8 x + 7 of word w
+#pragma unroll
+        for (int w = 0; w < 8; ++w) {
+          const int v = __shfl((int)smask, 8 * w + (lane >> 3), 64);
+          const unsigned long long b = __ballot((v >> (lane & 7)) & 1);
+          if (lane == w) wbits = b;
+        }
+      } else if constexpr (NPT == 4) {
         // lane 16 w + x holds neurons 4 x .. 4 x + 3 of word w; lane l of a ballot must stand for neuron l of the word
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
