@@ -2,7 +2,10 @@
 blocks of one XCD, ring_resident.h) against the CPU oracle, through the C ABI: membrane trace bit
 for bit, counters, spike counts; every register layout (1, 4, 8 neurons per thread), several
 window lengths, batches, the synaptic current states, runs cut into pieces and mixed with single
-steps, resets, and agreement with the one-launch-per-step path."""
+steps, resets, and agreement with the one-launch-per-step path; likewise the forward kernel over the
+whole chip (ring_resident_forward.h) and the two resident reverse kernels -- without a grid barrier
+(ring_flow_reverse.h, the default) and with one (ring_resident_reverse.h) -- with their layouts of
+one, four and eight neurons per thread, block counts, spreads over the XCDs and failure paths."""
 import numpy as np
 import pytest
 import torch
