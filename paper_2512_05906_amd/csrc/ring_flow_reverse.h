@@ -1,7 +1,8 @@
 // Ring queue, reverse sweep: the steps of one window in ONE launch with NO grid barrier -- the blocks
 // wait for the very cells they gather (delta synapse).  Included by adseq.hip after
-// ring_resident_reverse.h, whose layout (P taking-part blocks, four consecutive neurons per thread,
-// spikes listed a step ahead, the leading 64 entries of their rows requested ahead) it shares.
+// ring_resident_reverse.h, whose layout (P taking-part blocks, consecutive neurons per thread -- here
+// one, four or eight --, spikes listed a step ahead, the leading 64 entries of their rows requested
+// ahead) it shares.
 //
 // What a reverse step n needs from other blocks is only the adjoints its spikes' in-window entries
 // gather: cells of the rows n + 1 .. of the adjoint window (Section 3.2 eqs. 13 and 17 carried back
@@ -22,7 +23,9 @@
 // Against the barrier per step of k_bwd_xcd (same arithmetic, same order of a spike's terms):
 // there a step was gathers behind the barrier, the stores of the spiking neurons, their
 // acknowledgement, the arrival, the poll -- three and a half trips over the fabric; here it is the
-// gathers, and a second round of them where the first came too early.
+// gathers, and a second round of them where the first came too early.  What a step costs then is
+// mostly the instructions a wavefront issues: hence the kernel per gradient mode, the one neuron per
+// thread where the blocks are small enough, the two block barriers per step instead of three.
 
 constexpr unsigned kFlowSentinel = 0x7fa5c3e1u;   // "not written yet" (a NaN with this payload)
 
